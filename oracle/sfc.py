@@ -1,0 +1,582 @@
+"""Plain numpy oracle for quantized 3x3 convolution by Symbolic Fourier Convolution.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, obviously-correct CPU
+statement of the method (arXiv 2407.02913).  It is imported by ``tests/``, by
+``__graft_entry__.smoke()`` and by the ``cpu_baseline`` leg of ``bench.py`` and
+by nothing else; it never imports the HIP library, and the HIP library never
+calls it.  All integer stages are computed exactly (int64, or float64 matmuls
+whose every partial sum is an integer below 2**53, which is asserted); all
+floating-point stages are float64.
+
+What is the definition and what is the algorithm
+------------------------------------------------
+* ``direct_conv``            -- the *definition* of the result (cross-correlation,
+                               stride 1, zero padding 1).  In exact-integer mode
+                               SFC reaches exactly this result.
+* ``sfc6_1d`` ...            -- the 1-D matrices of SFC-6(6,3) as printed in
+                               Appendix A (one erratum, see ``BT_PRINTED_ROW7``).
+* ``nested_2d``              -- the 2-D form of Eq. (1): Kronecker products,
+                               10*10 = 100 multiplications per 6x6 tile.
+* ``hermitian_2d``           -- the 88-multiplication form.  Appendix A only
+                               states the count; the construction used here is
+                               written out in the docstring.
+* ``conv_exact``             -- Eq. (1) with exact integers.
+* ``conv_requant``           -- Eq. (1) with the frequency-wise / channel-wise
+                               transform-domain quantizer of Sec. 5.
+
+Pins (see tests/test_oracle_*.py): printed matrices (tests/golden), the
+bilinear identity sum_p A[p,o] B[p,i] G[p,r] = 6 [i = o + r], numpy's FFT for the
+symbolic DFT-6, complex multiplication for the 3-multiplication product rule,
+brute-force correlation on tiny inputs, torch's conv2d for ``direct_conv``, the
+multiplication counts 100/88 and the ratios 3.68x / 2.25x, and bit-exact
+equality of ``conv_exact`` with ``direct_conv``.  ``conv_requant`` is an
+approximation with no printed values: it is pinned by reduction to
+``conv_exact`` (unit scales, power-of-two scales), by hand-computed values of
+the quantizer, and by its error against ``direct_conv`` shrinking by about 2x
+per extra bit.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# ---------------------------------------------------------------------------
+# Sec. 4.1, "1) DFT-6": symbolic DFT with s = exp(j*pi/3), s^2 = s - 1.
+# ---------------------------------------------------------------------------
+
+#: F_6 of Eq. (DFT6): rows are [X0, X1.a0, X1.a1, X2.a0, X2.a1, X3] where a
+#: complex point is the first-order polynomial a0 + a1*s.
+F6 = np.array(
+    [
+        [1, 1, 1, 1, 1, 1],
+        [1, 1, 0, -1, -1, 0],
+        [0, -1, -1, 0, 1, 1],
+        [1, 0, -1, 1, 0, -1],
+        [0, -1, 1, 0, -1, 1],
+        [1, -1, 1, -1, 1, -1],
+    ],
+    dtype=np.int64,
+)
+
+#: iF_6 (numerators; the common factor is 1/6), as printed after Eq. (DFT6).
+#: Row c gives the weight of symbol component c in each of the six samples.
+#: Read this way, IF6.T @ F6 == 6 * (cyclic advance by one sample): the printed
+#: matrix carries the one-sample alignment that the integrated A matrix needs.
+IF6 = np.array(
+    [
+        [1, 1, 1, 1, 1, 1],
+        [1, -1, -2, -1, 1, 2],
+        [-1, -2, -1, 1, 2, 1],
+        [-1, -1, 2, -1, -1, 2],
+        [-2, 1, 1, -2, 1, 1],
+        [-1, 1, -1, 1, -1, 1],
+    ],
+    dtype=np.int64,
+)
+
+S_ROOT = np.exp(1j * np.pi / 3.0)  # the symbol s, only ever used by checks
+
+
+def s6_to_complex(sym: np.ndarray) -> np.ndarray:
+    """S_6 of Eq. (DFT6): symbolic components -> the six complex DFT values.
+
+    ``sym`` has the six F_6 components on axis 0.  Returns X_0..X_5 with
+    X_5 = conj(X_1) and X_4 = conj(X_2) (written in the paper as a0 - a1*s^2,
+    since conj(s) = -s^2 = 1 - s).
+    """
+    sym = np.asarray(sym, dtype=np.float64)
+    x0, a10, a11, a20, a21, x3 = sym
+    x1 = a10 + a11 * S_ROOT
+    x2 = a20 + a21 * S_ROOT
+    x5 = a10 + a11 * (-(S_ROOT**2))
+    x4 = a20 + a21 * (-(S_ROOT**2))
+    return np.stack([x0 + 0j, x1, x2, x3 + 0j, x4, x5])
+
+
+def poly_mul_s6(a: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """Eq. (DFT6M): (a0 + a1 s)(w0 + w1 s) = o0 + o1 s with three multiplications."""
+    a0, a1 = a
+    w0, w1 = w
+    m0 = a0 * w0
+    m1 = a1 * w1
+    m2 = (a0 + a1) * (w0 + w1)
+    return np.stack([m0 - m1, m2 - m0])
+
+
+def sft6_butterfly(z):
+    """F_6 z through the DFT-2 x DFT-3 decomposition of Sec. 4.1.
+
+    Returns (the six components in F_6's row order, number of additions).  A
+    subtraction, or an addition of a negated operand, counts as one addition,
+    as the paper counts them.
+    """
+    z = [np.asarray(v, dtype=np.int64) for v in z]
+    e = [z[i] + z[i + 3] for i in range(3)]
+    d = [z[i] - z[i + 3] for i in range(3)]
+    adds = 6
+    x0 = e[0] + e[1] + e[2]
+    a20, a21 = e[0] - e[2], e[2] - e[1]
+    x3 = d[0] - d[1] + d[2]
+    a10, a11 = d[0] + d[1], -d[1] - d[2]
+    adds += 2 + 2 + 2 + 2
+    return np.stack([x0, a10, a11, a20, a21, x3]), adds
+
+
+# ---------------------------------------------------------------------------
+# Appendix A: SFC-6(6x6, 3x3), polynomial multiplication integrated.
+# Row roles (0-based): 0 -> k=0 (real); 1,2,3 -> k=1 as (a0, a1, a0+a1);
+# 4,5,6 -> k=2 likewise; 7 -> k=3 (real); 8, 9 -> the two correction terms of
+# Sec. 4.2 (x0 - x6 paired with f0 -> output 0, x7 - x1 paired with f2 -> output 5).
+# ---------------------------------------------------------------------------
+
+#: Row 7 of B^T exactly as printed.  It breaks the bilinear identity; the k=3
+#: row of F_6 (alternating signs, as also printed for SFC-6(7x7,3x3)) is used.
+BT_PRINTED_ROW7 = np.array([0, 1, -1, 1, 1, -1, 1, 0], dtype=np.int64)
+
+BT_1D = np.array(
+    [
+        [0, 1, 1, 1, 1, 1, 1, 0],
+        [0, 1, 1, 0, -1, -1, 0, 0],
+        [0, 0, -1, -1, 0, 1, 1, 0],
+        [0, 1, 0, -1, -1, 0, 1, 0],
+        [0, 1, 0, -1, 1, 0, -1, 0],
+        [0, 0, -1, 1, 0, -1, 1, 0],
+        [0, 1, -1, 0, 1, -1, 0, 0],
+        [0, 1, -1, 1, -1, 1, -1, 0],  # erratum: printed as BT_PRINTED_ROW7
+        [1, 0, 0, 0, 0, 0, -1, 0],
+        [0, -1, 0, 0, 0, 0, 0, 1],
+    ],
+    dtype=np.int64,
+)
+
+G_1D = np.array(
+    [
+        [1, 1, 1],
+        [0, 1, 1],
+        [-1, -1, 0],
+        [-1, 0, 1],
+        [-1, 0, 1],
+        [1, -1, 0],
+        [0, -1, 1],
+        [1, -1, 1],
+        [1, 0, 0],
+        [0, 0, 1],
+    ],
+    dtype=np.int64,
+)
+
+#: Numerators of A; the printed matrix carries the factor 1/6.
+A_1D = np.array(
+    [
+        [1, 1, 1, 1, 1, 1],
+        [2, 1, -1, -2, -1, 1],
+        [-1, 1, 2, 1, -1, -2],
+        [-1, -2, -1, 1, 2, 1],
+        [1, -2, 1, 1, -2, 1],
+        [1, 1, -2, 1, 1, -2],
+        [-2, 1, 1, -2, 1, 1],
+        [-1, 1, -1, 1, -1, 1],
+        [6, 0, 0, 0, 0, 0],
+        [0, 0, 0, 0, 0, 6],
+    ],
+    dtype=np.int64,
+)
+A_1D_DEN = 6
+
+TILE_OUT = 6  # M: outputs per tile edge
+TILE_IN = 8  # M + R - 1
+KERNEL = 3  # R
+REAL_ROWS = (0, 7, 8, 9)
+COMPLEX_GROUPS = ((1, 2, 3), (4, 5, 6))  # (a0 row, a1 row, a0+a1 row)
+
+
+def sfc6_1d():
+    """The three 1-D matrices of SFC-6(6,3): (B^T 10x8, G 10x3, A numerators 10x6, 6)."""
+    return BT_1D.copy(), G_1D.copy(), A_1D.copy(), A_1D_DEN
+
+
+def integrate_1d():
+    """Re-derive B^T, G, A of SFC-6(6,3) from Sec. 4.1-4.2 instead of reading them.
+
+    Steps, in the paper's order:
+      1. forward SFT-6 (F_6) of the six inner samples x1..x6        (Eq. DFT6)
+      2. the same symbolic DFT of the filter, aligned so that the cyclic
+         result lands on the tile's outputs: G_k = sum_r f_r s^{k(r-2)}
+      3. the 3-multiplication product rule folded into both matrices as an
+         extra a0+a1 row per complex point                           (Eq. DFT6M)
+      4. inverse transform iF_6, with the product rule's post-additions
+         (o0 = m0 - m1, o1 = m2 - m0) folded into A's rows
+      5. two correction terms that turn the wrapped outputs 0 and 5 of the
+         cyclic convolution into linear-convolution outputs          (Sec. 4.2)
+    Returns (B^T, G, A numerators, 6) in the same row order as Appendix A.
+    """
+    bt = np.zeros((10, 8), dtype=np.int64)
+    g = np.zeros((10, 3), dtype=np.int64)
+    a = np.zeros((10, 6), dtype=np.int64)
+
+    # powers of s as (c0, c1) with s^n = c0 + c1 s, using s^2 = s - 1
+    def s_pow(n):
+        c = np.array([1, 0], dtype=np.int64)
+        n %= 6
+        for _ in range(n):
+            c = np.array([-c[1], c[0] + c[1]])  # (c0 + c1 s) s = -c1 + (c0 + c1) s
+        return c
+
+    # 1. rows of F_6 act on the inner samples (columns 1..6)
+    comp_rows = {0: 0, 1: 1, 2: 2, 4: 3, 5: 4, 7: 5}  # B^T row -> F_6 row
+    for brow, frow in comp_rows.items():
+        bt[brow, 1:7] = F6[frow]
+    # 2. filter DFT: G_k = sum_r f_r s^{k (r - 2)}
+    for k, (r0, r1) in ((1, (1, 2)), (2, (4, 5))):
+        for r in range(3):
+            c = s_pow(k * (r - 2))
+            g[r0, r] = c[0]
+            g[r1, r] = c[1]
+    g[0] = 1  # k = 0
+    for r in range(3):  # k = 3: s^{3(r-2)} = (-1)^{r-2}
+        g[7, r] = 1 if (r - 2) % 2 == 0 else -1
+    # 3. Karatsuba-style sum rows
+    for r0, r1, rs in COMPLEX_GROUPS:
+        bt[rs] = bt[r0] + bt[r1]
+        g[rs] = g[r0] + g[r1]
+    # 4. inverse: y = sum_c IF6[c] * component_c, o0 = m0 - m1, o1 = m2 - m0
+    a[0] = IF6[0]
+    a[7] = IF6[5]
+    for (r0, r1, rs), (c0, c1) in zip(COMPLEX_GROUPS, ((1, 2), (3, 4))):
+        a[r0] = IF6[c0] - IF6[c1]
+        a[r1] = -IF6[c0]
+        a[rs] = IF6[c1]
+    # 5. corrections: output 0 wraps x6 where x0 is wanted (times f0); output 5
+    # wraps x1 where x7 is wanted (times f2).  One multiplication each, and the
+    # products are not divided by 6.
+    bt[8, 0], bt[8, 6] = 1, -1
+    g[8, 0] = 1
+    a[8, 0] = 6
+    bt[9, 7], bt[9, 1] = 1, -1
+    g[9, 2] = 1
+    a[9, 5] = 6
+    return bt, g, a, 6
+
+
+# ---------------------------------------------------------------------------
+# 2-D forms (Eq. 1: y = A^T [ (G f G^T) . (B^T x B) ] A )
+# ---------------------------------------------------------------------------
+
+
+def nested_2d():
+    """Nested (Kronecker) 2-D form: 100 points per tile.
+
+    Returns (B2 [100,64], G2 [100,9], A2 numerators [100,36], 36); point
+    p = 10*p1 + p2 with p1 along the vertical (row) axis of the tile.
+    """
+    bt, g, a, den = sfc6_1d()
+    return np.kron(bt, bt), np.kron(g, g), np.kron(a, a), den * den
+
+
+def hermitian_2d():
+    """88-point 2-D form ("when Hermitian symmetry is fully considered", Appendix A).
+
+    The paper states the count only.  Construction used here:
+
+    * Every nested point in which at most one axis is a complex frequency is
+      kept unchanged, in nested order (64 of the 100 points).
+    * For each pair of complex frequencies (k1, k2) in {1,2}^2 the nested form
+      spends 3*3 = 9 multiplications on the product of two elements of
+      Z[s]/(s^2-s+1) (x) Z[t]/(t^2-t+1), a = a00 + a10 s + a01 t + a11 s t.
+      Because t^2 - t + 1 = (t - s)(t - (1 - s)), that ring maps into
+      Z[s] x Z[s] by t -> s and t -> 1 - s.  These images are the true 2-D DFT
+      values Z[k1, k2] and Z[k1, -k2]; the remaining two conjugates are
+      redundant for real data, which is the Hermitian symmetry being used:
+          U = (a00 - a11)       + (a10 + a01 + a11) s        (t -> s)
+          V = (a00 + a01 + a11) + (a10 - a01) s              (t -> 1 - s)
+      Each image is multiplied by the 3-multiplication rule of Eq. (DFT6M),
+      i.e. points U0, U1, U0+U1, V0, V1, V0+V1: 6 multiplications.
+    * Inverse of the ring map (exact over the integers because the result is
+      the integer nested product):
+          o01 = (2 (Uo1 - Vo1) - (Vo0 - Uo0)) / 3
+          o11 = (2 (Vo0 - Uo0) - (Uo1 - Vo1)) / 3
+          o00 = Uo0 + o11,   o10 = Vo1 + o01
+      and the tile output is sum_ij (c_i (x) c_j) o_ij with c_0 = -A[a1 row],
+      c_1 = A[sum row] (the iF_6 rows recovered from the folded A).
+    Count: 64 + 4*6 = 88.  Order: the 64 kept points in nested order, then the
+    blocks (k1,k2) = (1,1), (1,2), (2,1), (2,2), six points each in the order
+    U0, U1, U0+U1, V0, V1, V0+V1.
+
+    Returns (B2 [88,64], G2 [88,9], A2 numerators [88,36], 36).
+    """
+    bt, g, a, den = sfc6_1d()
+    complex_rows = {r for grp in COMPLEX_GROUPS for r in grp}
+    b_rows, g_rows, a_rows = [], [], []
+    for p1 in range(10):
+        for p2 in range(10):
+            if p1 in complex_rows and p2 in complex_rows:
+                continue
+            b_rows.append(np.kron(bt[p1], bt[p2]))
+            g_rows.append(np.kron(g[p1], g[p2]))
+            a_rows.append(np.kron(a[p1], a[p2]))
+
+    def six_points(m, grp1, grp2):
+        """U0, U1, U0+U1, V0, V1, V0+V1 for a 1-D matrix m (B^T or G)."""
+        c = [[np.kron(m[grp1[i]], m[grp2[j]]) for j in range(2)] for i in range(2)]
+        u0 = c[0][0] - c[1][1]
+        u1 = c[1][0] + c[0][1] + c[1][1]
+        v0 = c[0][0] + c[0][1] + c[1][1]
+        v1 = c[1][0] - c[0][1]
+        return [u0, u1, u0 + u1, v0, v1, v0 + v1]
+
+    # 3 * o_ij as integer combinations of the six products (mU0,mU1,mU2,mV0,mV1,mV2)
+    uo0 = np.array([1, -1, 0, 0, 0, 0])
+    uo1 = np.array([-1, 0, 1, 0, 0, 0])
+    vo0 = np.array([0, 0, 0, 1, -1, 0])
+    vo1 = np.array([0, 0, 0, -1, 0, 1])
+    o01_x3 = 2 * (uo1 - vo1) - (vo0 - uo0)
+    o11_x3 = 2 * (vo0 - uo0) - (uo1 - vo1)
+    o00_x3 = 3 * uo0 + o11_x3
+    o10_x3 = 3 * vo1 + o01_x3
+    o_x3 = {(0, 0): o00_x3, (1, 0): o10_x3, (0, 1): o01_x3, (1, 1): o11_x3}
+
+    for grp1 in COMPLEX_GROUPS:
+        for grp2 in COMPLEX_GROUPS:
+            b_rows += six_points(bt, grp1, grp2)
+            g_rows += six_points(g, grp1, grp2)
+            c1 = (-a[grp1[1]], a[grp1[2]])
+            c2 = (-a[grp2[1]], a[grp2[2]])
+            block = np.zeros((6, 36), dtype=np.int64)
+            for (i, j), comb in o_x3.items():
+                block += np.outer(comb, np.kron(c1[i], c2[j]))
+            assert np.all(block % 3 == 0), "thirds must cancel"
+            a_rows += list(block // 3)
+    return (
+        np.array(b_rows, dtype=np.int64),
+        np.array(g_rows, dtype=np.int64),
+        np.array(a_rows, dtype=np.int64),
+        den * den,
+    )
+
+
+_ALGORITHMS = {"6x6_p88": hermitian_2d, "6x6_p100": nested_2d}
+
+
+def algorithm(name: str):
+    """(B2, G2, A2 numerators, denominator) for "6x6_p88" or "6x6_p100"."""
+    return _ALGORITHMS[name]()
+
+
+def multiplications_per_tile(name: str) -> int:
+    """Real multiplications per 6x6 output tile and (Cin, Cout) pair: one per point."""
+    return algorithm(name)[0].shape[0]
+
+
+def direct_multiplications_per_tile() -> int:
+    return TILE_OUT * TILE_OUT * KERNEL * KERNEL
+
+
+# ---------------------------------------------------------------------------
+# The definition: direct 3x3 cross-correlation, stride 1, zero padding 1.
+# ---------------------------------------------------------------------------
+
+
+def _exact_f64(*max_abs_and_len):
+    """Assert that a float64 contraction of integers is exact (below 2**53)."""
+    bound = 1.0
+    for v in max_abs_and_len:
+        bound *= float(v)
+    assert bound < 2.0**53, "integer contraction would not be exact in float64"
+
+
+def direct_conv(x: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """acc[n,k,h,w] = sum_{c,r,s} x[n,c,h+r-1,w+s-1] * w[k,c,r,s], zeros outside.
+
+    int8 inputs, exact int64 result.  (No kernel flip: the paper's matrices
+    compute y_o = sum_r x_{o+r} f_r.)
+    """
+    x = np.asarray(x)
+    w = np.asarray(w)
+    n, c, h, wd = x.shape
+    k = w.shape[0]
+    assert w.shape == (k, c, 3, 3)
+    _exact_f64(np.abs(x).max(initial=1), np.abs(w).max(initial=1), 9 * c)
+    xp = np.zeros((n, c, h + 2, wd + 2), dtype=np.float64)
+    xp[:, :, 1 : 1 + h, 1 : 1 + wd] = x
+    wf = w.astype(np.float64)
+    acc = np.zeros((k, n, h, wd), dtype=np.float64)
+    for r in range(3):
+        for s in range(3):
+            acc += np.tensordot(wf[:, :, r, s], xp[:, :, r : r + h, s : s + wd], axes=([1], [1]))
+    return np.rint(acc).astype(np.int64).transpose(1, 0, 2, 3)
+
+
+def dequantize(acc: np.ndarray, x_scale, w_scale) -> np.ndarray:
+    """y = acc * (s_x * s_w[k]) in float64; ``w_scale`` is a scalar or has Cout entries."""
+    ws = np.broadcast_to(np.asarray(w_scale, dtype=np.float64).reshape(-1), (acc.shape[1],))
+    return acc.astype(np.float64) * (float(x_scale) * ws)[None, :, None, None]
+
+
+# ---------------------------------------------------------------------------
+# Tiling (paper silent on padding; reading: zero pad 1, ragged tiles read zeros
+# beyond the image and their surplus outputs are dropped -- exact by linearity)
+# ---------------------------------------------------------------------------
+
+
+def tile_grid(h: int, w: int):
+    return -(-h // TILE_OUT), -(-w // TILE_OUT)
+
+
+def gather_tiles(x: np.ndarray) -> np.ndarray:
+    """[N,C,H,W] -> tiles [T, C, 8, 8], T = N*th*tw, t = (n*th + ti)*tw + tj.
+
+    Tile (ti,tj) covers input rows 6*ti-1 .. 6*ti+6 and columns 6*tj-1 .. 6*tj+6.
+    """
+    n, c, h, w = x.shape
+    th, tw = tile_grid(h, w)
+    xp = np.zeros((n, c, TILE_OUT * th + 2, TILE_OUT * tw + 2), dtype=np.int64)
+    xp[:, :, 1 : 1 + h, 1 : 1 + w] = x
+    tiles = np.empty((n, th, tw, c, TILE_IN, TILE_IN), dtype=np.int64)
+    for ti in range(th):
+        for tj in range(tw):
+            tiles[:, ti, tj] = xp[:, :, 6 * ti : 6 * ti + 8, 6 * tj : 6 * tj + 8]
+    return tiles.reshape(n * th * tw, c, TILE_IN, TILE_IN)
+
+
+def scatter_tiles(o: np.ndarray, n: int, h: int, w: int) -> np.ndarray:
+    """Tile outputs [T, K, 6, 6] -> [N, K, H, W], dropping the ragged surplus."""
+    th, tw = tile_grid(h, w)
+    k = o.shape[1]
+    o = o.reshape(n, th, tw, k, TILE_OUT, TILE_OUT)
+    full = np.empty((n, k, TILE_OUT * th, TILE_OUT * tw), dtype=o.dtype)
+    for ti in range(th):
+        for tj in range(tw):
+            full[:, :, 6 * ti : 6 * ti + 6, 6 * tj : 6 * tj + 6] = o[:, ti, tj]
+    return np.ascontiguousarray(full[:, :, :h, :w])
+
+
+# ---------------------------------------------------------------------------
+# The three stages of Eq. (1)
+# ---------------------------------------------------------------------------
+
+
+def input_transform(x: np.ndarray, b2: np.ndarray) -> np.ndarray:
+    """V[p,t,c] = sum_ij B2[p,(i,j)] * tile[t,c,i,j]  (B^T x B, additions only)."""
+    tiles = gather_tiles(x)
+    t, c = tiles.shape[:2]
+    v = b2 @ tiles.reshape(t * c, 64).T  # int64, exact
+    return v.reshape(b2.shape[0], t, c)
+
+
+def filter_transform(w: np.ndarray, g2: np.ndarray) -> np.ndarray:
+    """U[p,k,c] = sum_rs G2[p,(r,s)] * w[k,c,r,s]  (G f G^T, additions only)."""
+    k, c = w.shape[:2]
+    u = g2 @ np.asarray(w, dtype=np.int64).reshape(k * c, 9).T
+    return u.reshape(g2.shape[0], k, c)
+
+
+def pointwise_product(v: np.ndarray, u: np.ndarray) -> np.ndarray:
+    """M[p,t,k] = sum_c V[p,t,c] * U[p,k,c]: the element-wise product of Eq. (1)
+    summed over input channels, i.e. one [T x Cin] . [Cin x Cout] product per point."""
+    _exact_f64(np.abs(v).max(initial=1), np.abs(u).max(initial=1), v.shape[2])
+    m = np.matmul(v.astype(np.float64), u.astype(np.float64).transpose(0, 2, 1))
+    return np.rint(m).astype(np.int64)
+
+
+def output_transform_exact(m: np.ndarray, a2: np.ndarray, den: int, n: int, h: int, w: int):
+    """acc = (A2^T M) / den, which must divide exactly; returns int64 [N,K,H,W]."""
+    p, t, k = m.shape
+    o = (a2.T @ m.reshape(p, t * k)).reshape(36, t, k)
+    assert np.all(o % den == 0), "exact SFC output must be divisible by the denominator"
+    o = (o // den).transpose(1, 2, 0).reshape(t, k, TILE_OUT, TILE_OUT)
+    return scatter_tiles(o, n, h, w)
+
+
+def conv_exact(x, w, alg="6x6_p88", return_taps=False):
+    """Eq. (1) over the integers, no transform-domain rounding: equals ``direct_conv``."""
+    b2, g2, a2, den = algorithm(alg)
+    n, _, h, wd = x.shape
+    v = input_transform(x, b2)
+    u = filter_transform(w, g2)
+    m = pointwise_product(v, u)
+    acc = output_transform_exact(m, a2, den, n, h, wd)
+    if return_taps:
+        return acc, {"V": v, "U": u, "M": m}
+    return acc
+
+
+# ---------------------------------------------------------------------------
+# Sec. 5: frequency-wise (activations) and channel+frequency-wise (filters)
+# quantization in the transform domain.
+# ---------------------------------------------------------------------------
+
+QMAX = 127  # symmetric int8
+
+
+def reciprocal_f32(scale) -> np.ndarray:
+    """1/scale as one correctly rounded float32 division (what the quantizer multiplies by)."""
+    return (np.float32(1.0) / np.asarray(scale, dtype=np.float32)).astype(np.float32)
+
+
+def quantize(values: np.ndarray, inv_scale: np.ndarray, qmax: int = QMAX) -> np.ndarray:
+    """round-half-even(values * inv_scale), clamped to [-qmax, qmax].
+
+    The product of a transform-domain integer (below 2**14) with a float32
+    reciprocal scale has at most 38 significant bits, so the float64 product
+    is exact and ``rint`` rounds the true product once, ties to even.
+    """
+    prod = np.asarray(values, dtype=np.float64) * np.asarray(inv_scale, dtype=np.float64)
+    return np.clip(np.rint(prod), -qmax, qmax).astype(np.int64)
+
+
+def calibrate_act_scales(x_calib: np.ndarray, alg="6x6_p88", qmax: int = QMAX) -> np.ndarray:
+    """s_Tx[p] = max |V[p,.,.]| / qmax over a calibration tensor (float32; 0 -> 1).
+
+    The paper learns its scales with AdaQuant on ImageNet images; abs-max
+    calibration stands in for that.  One scale per multiplication point.
+    """
+    v = input_transform(x_calib, algorithm(alg)[0])
+    mx = np.abs(v).max(axis=(1, 2)).astype(np.float32)
+    s = mx / np.float32(qmax)
+    return np.where(mx == 0, np.float32(1.0), s).astype(np.float32)
+
+
+def calibrate_filter_scales(w: np.ndarray, alg="6x6_p88", qmax: int = QMAX) -> np.ndarray:
+    """s_Tf[p,k] = max_c |U[p,k,c]| / qmax (float32; 0 -> 1): channel + frequency wise."""
+    u = filter_transform(w, algorithm(alg)[1])
+    mx = np.abs(u).max(axis=2).astype(np.float32)
+    s = mx / np.float32(qmax)
+    return np.where(mx == 0, np.float32(1.0), s).astype(np.float32)
+
+
+def output_transform_dequant(m, a2, den, sx_pt, sw_pt, x_scale, w_scale, n, h, w):
+    """y[o] = (s_x s_w[k] / den) * sum_p A2[p,o] * (M[p] * s_Tx[p] * s_Tf[p,k]), float64."""
+    p, t, k = m.shape
+    scale = np.asarray(sx_pt, dtype=np.float64)[:, None] * np.asarray(sw_pt, dtype=np.float64)
+    md = m.astype(np.float64) * scale[:, None, :]
+    o = (a2.T.astype(np.float64) @ md.reshape(p, t * k)).reshape(36, t, k)
+    o = o.transpose(1, 2, 0).reshape(t, k, TILE_OUT, TILE_OUT)
+    y = scatter_tiles(o, n, h, w)
+    ws = np.broadcast_to(np.asarray(w_scale, dtype=np.float64).reshape(-1), (k,))
+    return y * (float(x_scale) * ws / den)[None, :, None, None]
+
+
+def conv_requant(x, w, sx_pt, sw_pt, x_scale, w_scale, alg="6x6_p88", qmax=QMAX, return_taps=False):
+    """The quantized fast convolution of Sec. 5 (unnumbered equation):
+
+        y = sum_Cin ( s_Tx round(B^T x B / s_Tx) . s_Tf round(G f G^T / s_Tf) )
+
+    followed by the output transform and the spatial-domain scales.
+    ``sx_pt`` [P] and ``sw_pt`` [P, Cout] are float32 scales.
+    """
+    b2, g2, a2, den = algorithm(alg)
+    n, _, h, wd = x.shape
+    v = input_transform(x, b2)
+    u = filter_transform(w, g2)
+    vq = quantize(v, reciprocal_f32(sx_pt)[:, None, None], qmax)
+    uq = quantize(u, reciprocal_f32(sw_pt)[:, :, None], qmax)
+    m = pointwise_product(vq, uq)
+    y = output_transform_dequant(m, a2, den, sx_pt, sw_pt, x_scale, w_scale, n, h, wd)
+    if return_taps:
+        return y, {"V": vq, "U": uq, "M": m}
+    return y
+
+
+def requantize_activation(y: np.ndarray, y_scale: float) -> np.ndarray:
+    """Next layer's int8 input: clamp(round-half-even(max(y, 0) / s_act), 0, 127)."""
+    inv = float(reciprocal_f32(y_scale))
+    return np.clip(np.rint(np.maximum(y, 0.0) * inv), 0, QMAX).astype(np.int8)

@@ -1,0 +1,374 @@
+"""Pins for the CPU oracle: the paper's printed values, closed forms, library
+routines and brute force.  Nothing here touches the HIP library."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import sfc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "sfc6_6x6_3x3_printed.txt")
+
+
+def load_golden(path=GOLDEN):
+    blocks, name = {}, None
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        if line.startswith("["):
+            name = line.strip("[]")
+            blocks[name] = []
+        else:
+            blocks[name].append(line.split())
+    out = {}
+    for k, rows in blocks.items():
+        if k == "counts":
+            out[k] = {r[0]: int(r[1]) for r in rows}
+        else:
+            out[k] = np.array(rows, dtype=np.int64)
+    return out
+
+
+def bilinear_1d(a, bt, g):
+    return np.einsum("po,pi,pr->oir", a, bt, g)
+
+
+def expected_1d(den=6):
+    ref = np.zeros((6, 8, 3), dtype=np.int64)
+    for o in range(6):
+        for r in range(3):
+            ref[o, o + r, r] = den
+    return ref
+
+
+def expected_2d(den=36):
+    ref = np.zeros((6, 6, 8, 8, 3, 3), dtype=np.int64)
+    for o1, o2, r1, r2 in itertools.product(range(6), range(6), range(3), range(3)):
+        ref[o1, o2, o1 + r1, o2 + r2, r1, r2] = den
+    return ref
+
+
+# ---- printed values ---------------------------------------------------------
+
+
+def test_printed_matrices_match_oracle_tables():
+    gold = load_golden()
+    bt, g, a, den = sfc.sfc6_1d()
+    assert den == 6
+    assert np.array_equal(gold["F6"], sfc.F6)
+    assert np.array_equal(gold["IF6_times_6"], sfc.IF6)
+    assert np.array_equal(gold["G"], g)
+    assert np.array_equal(gold["A_times_6"], a)
+    # B^T equals the print except for the one erratum row
+    diff_rows = np.nonzero((gold["BT"] != bt).any(axis=1))[0]
+    assert list(diff_rows) == [7]
+    assert np.array_equal(gold["BT"][7], sfc.BT_PRINTED_ROW7)
+    assert np.array_equal(gold["BT_row8_corrected"][0], bt[7])
+
+
+def test_erratum_row_as_printed_breaks_the_identity_and_the_fix_restores_it():
+    gold = load_golden()
+    as_printed = bilinear_1d(gold["A_times_6"], gold["BT"], gold["G"])
+    assert np.count_nonzero(as_printed != expected_1d()) > 0
+    bt, g, a, _ = sfc.sfc6_1d()
+    assert np.array_equal(bilinear_1d(a, bt, g), expected_1d())
+
+
+def test_matrices_rederived_from_sections_4_1_and_4_2_equal_the_print():
+    bt, g, a, den = sfc.sfc6_1d()
+    bt2, g2, a2, den2 = sfc.integrate_1d()
+    assert den == den2
+    assert np.array_equal(bt, bt2) and np.array_equal(g, g2) and np.array_equal(a, a2)
+
+
+def test_folded_post_additions_sum_to_zero():
+    # o0 = m0 - m1, o1 = m2 - m0 folded into A means the three rows of a complex group cancel
+    _, _, a, _ = sfc.sfc6_1d()
+    for r0, r1, rs in sfc.COMPLEX_GROUPS:
+        assert np.all(a[r0] + a[r1] + a[rs] == 0)
+
+
+# ---- symbolic DFT-6 against the numeric DFT ---------------------------------
+
+
+def test_sft6_equals_numpy_fft():
+    rng = np.random.default_rng(1)
+    x = rng.integers(-128, 128, size=(6, 50))
+    num = sfc.s6_to_complex(sfc.F6 @ x)
+    assert np.allclose(num, np.fft.fft(x, axis=0), atol=1e-9)
+
+
+def test_printed_inverse_returns_the_sequence_advanced_by_one():
+    rng = np.random.default_rng(2)
+    x = rng.integers(-128, 128, size=(6, 20))
+    back = sfc.IF6.T @ (sfc.F6 @ x)
+    assert np.array_equal(back, 6 * np.roll(x, -1, axis=0))
+
+
+def test_three_multiplication_rule_is_complex_multiplication_at_s():
+    rng = np.random.default_rng(3)
+    a = rng.integers(-1000, 1000, size=(2, 100))
+    w = rng.integers(-1000, 1000, size=(2, 100))
+    o = sfc.poly_mul_s6(a, w)
+    lhs = (a[0] + a[1] * sfc.S_ROOT) * (w[0] + w[1] * sfc.S_ROOT)
+    assert np.allclose(o[0] + o[1] * sfc.S_ROOT, lhs, atol=1e-6)
+    assert abs(sfc.S_ROOT**2 - (sfc.S_ROOT - 1)) < 1e-12
+
+
+def test_sft6_butterfly_costs_14_additions():
+    gold = load_golden()
+    rng = np.random.default_rng(4)
+    z = rng.integers(-128, 128, size=(6, 33))
+    vals, adds = sfc.sft6_butterfly(list(z))
+    assert np.array_equal(vals, sfc.F6 @ z)
+    assert adds == gold["counts"]["sft6_additions"] == 14
+
+
+# ---- 1-D algorithm against brute force --------------------------------------
+
+
+def test_1d_sfc_equals_linear_correlation_brute_force():
+    bt, g, a, den = sfc.sfc6_1d()
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        x = rng.integers(-128, 128, size=8)
+        f = rng.integers(-128, 128, size=3)
+        y6 = a.T @ ((g @ f) * (bt @ x))
+        brute = [sum(int(x[o + r]) * int(f[r]) for r in range(3)) for o in range(6)]
+        assert np.array_equal(y6, den * np.array(brute))
+        assert np.array_equal(np.correlate(x, f, mode="valid"), brute)
+
+
+def test_correction_terms_turn_cyclic_outputs_into_linear_ones():
+    # Sec. 4.2 (Fig. 2): the cyclic result of the six inner samples, computed here
+    # with numpy's numeric FFT, is wrong only at its two wrapped outputs, and one
+    # extra multiply-accumulate each repairs them.
+    rng = np.random.default_rng(6)
+    for _ in range(20):
+        x = rng.integers(-128, 128, size=8).astype(np.float64)
+        f = rng.integers(-128, 128, size=3).astype(np.float64)
+        z = x[1:7]
+        kern = np.zeros(6)
+        kern[[5, 0, 1]] = f  # y_o = z_{o-1} f0 + z_o f1 + z_{o+1} f2, cyclic
+        cyc = np.real(np.fft.ifft(np.fft.fft(z) * np.conj(np.fft.fft(kern))))
+        lin = np.correlate(x, f, mode="valid")
+        assert np.allclose(cyc[1:5], lin[1:5])
+        assert not np.allclose(cyc[[0, 5]], lin[[0, 5]])
+        fixed = cyc.copy()
+        fixed[0] += (x[0] - x[6]) * f[0]
+        fixed[5] += (x[7] - x[1]) * f[2]
+        assert np.allclose(fixed, lin)
+
+
+# ---- 2-D forms ---------------------------------------------------------------
+
+
+@pytest.mark.parametrize("alg,points", [("6x6_p100", 100), ("6x6_p88", 88)])
+def test_2d_bilinear_identity(alg, points):
+    b2, g2, a2, den = sfc.algorithm(alg)
+    assert b2.shape == (points, 64) and g2.shape == (points, 9) and a2.shape == (points, 36)
+    t = np.einsum("po,pi,pr->oir", a2, b2, g2).reshape(6, 6, 8, 8, 3, 3)
+    assert np.array_equal(t, expected_2d(den))
+    # transforms stay addition-only; bit growth as derived from the row sums
+    assert set(np.unique(b2)) <= {-1, 0, 1} and set(np.unique(g2)) <= {-1, 0, 1}
+    assert np.abs(b2).sum(axis=1).max() == 36 and np.abs(g2).sum(axis=1).max() == 9
+    assert np.abs(a2).max() <= 36
+
+
+def test_hermitian_form_shares_its_first_64_points_with_the_nested_form():
+    b100, g100, a100, _ = sfc.nested_2d()
+    b88, g88, a88, _ = sfc.hermitian_2d()
+    cplx = {1, 2, 3, 4, 5, 6}
+    keep = [10 * i + j for i in range(10) for j in range(10) if not (i in cplx and j in cplx)]
+    assert len(keep) == 64
+    assert np.array_equal(b88[:64], b100[keep])
+    assert np.array_equal(g88[:64], g100[keep])
+    assert np.array_equal(a88[:64], a100[keep])
+
+
+def test_multiplication_counts_and_reductions():
+    c = load_golden()["counts"]
+    nested = sfc.multiplications_per_tile("6x6_p100")
+    herm = sfc.multiplications_per_tile("6x6_p88")
+    direct = sfc.direct_multiplications_per_tile()
+    assert (nested, herm, direct) == (
+        c["nested_multiplications"],
+        c["hermitian_multiplications"],
+        c["direct_multiplications"],
+    )
+    assert round(100 * direct / herm) == c["reduction_x100"]  # 3.68x
+    assert round(10000 * herm / direct) == c["complexity_percent_x100"]  # 27.16 %
+    # Winograd F(2x2,3x3): (2+3-1)^2 multiplications for 2x2 outputs of a 3x3 filter
+    wino, wino_direct = (2 + 3 - 1) ** 2, 2 * 2 * 9
+    assert round(100 * wino_direct / wino) == c["winograd_f2x2_3x3_reduction_x100"]
+    assert round(1000 * wino / wino_direct) == c["winograd_f2x2_3x3_complexity_percent_x10"]
+
+
+# ---- the definition ----------------------------------------------------------
+
+
+def naive_conv(x, w):
+    n, c, h, wd = x.shape
+    k = w.shape[0]
+    out = np.zeros((n, k, h, wd), dtype=np.int64)
+    for ni, ki, hi, wi in itertools.product(range(n), range(k), range(h), range(wd)):
+        acc = 0
+        for ci, r, s in itertools.product(range(c), range(3), range(3)):
+            hh, ww = hi + r - 1, wi + s - 1
+            if 0 <= hh < h and 0 <= ww < wd:
+                acc += int(x[ni, ci, hh, ww]) * int(w[ki, ci, r, s])
+        out[ni, ki, hi, wi] = acc
+    return out
+
+
+def test_direct_conv_brute_force_tiny():
+    rng = np.random.default_rng(7)
+    x = rng.integers(-128, 128, size=(2, 3, 5, 7)).astype(np.int8)
+    w = rng.integers(-128, 128, size=(4, 3, 3, 3)).astype(np.int8)
+    assert np.array_equal(sfc.direct_conv(x, w), naive_conv(x, w))
+
+
+def test_direct_conv_equals_torch_conv2d():
+    import torch
+
+    rng = np.random.default_rng(8)
+    x = rng.integers(-128, 128, size=(2, 16, 14, 9)).astype(np.int8)
+    w = rng.integers(-128, 128, size=(8, 16, 3, 3)).astype(np.int8)
+    ref = torch.nn.functional.conv2d(
+        torch.from_numpy(x.astype(np.float64)), torch.from_numpy(w.astype(np.float64)), padding=1
+    ).numpy()
+    assert np.array_equal(sfc.direct_conv(x, w), np.rint(ref).astype(np.int64))
+
+
+# ---- exact mode: SFC == direct convolution over the integers -----------------
+
+SHAPES = [
+    (1, 16, 16, 32, 32),  # the small workload: ragged (32 = 5*6 + 2)
+    (2, 3, 5, 14, 14),
+    (1, 4, 4, 7, 7),
+    (2, 2, 3, 13, 9),
+    (1, 1, 1, 6, 6),
+    (1, 2, 2, 1, 1),
+    (1, 1, 2, 5, 12),
+]
+
+
+@pytest.mark.parametrize("alg", ["6x6_p100", "6x6_p88"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_exact_sfc_equals_direct_conv(alg, shape):
+    n, c, k, h, w = shape
+    rng = np.random.default_rng(hash(shape) % 2**32)
+    x = rng.integers(-128, 128, size=(n, c, h, w)).astype(np.int8)
+    wt = rng.integers(-128, 128, size=(k, c, 3, 3)).astype(np.int8)
+    acc, taps = sfc.conv_exact(x, wt, alg, return_taps=True)  # asserts remainder 0 inside
+    assert np.array_equal(acc, sfc.direct_conv(x, wt))
+    assert np.abs(taps["V"]).max() <= 36 * 128 and np.abs(taps["U"]).max() <= 9 * 128
+
+
+def test_exact_sfc_extreme_values():
+    x = np.full((1, 2, 8, 8), -128, dtype=np.int8)
+    w = np.full((2, 2, 3, 3), -128, dtype=np.int8)
+    w[1] = 127
+    for alg in ("6x6_p100", "6x6_p88"):
+        assert np.array_equal(sfc.conv_exact(x, w, alg), sfc.direct_conv(x, w))
+
+
+def test_tiling_round_trip():
+    rng = np.random.default_rng(9)
+    x = rng.integers(-128, 128, size=(2, 3, 13, 9)).astype(np.int8)
+    tiles = sfc.gather_tiles(x)
+    th, tw = sfc.tile_grid(13, 9)
+    assert tiles.shape == (2 * th * tw, 3, 8, 8)
+    inner = tiles[:, :, 1:7, 1:7].transpose(0, 1, 2, 3)
+    assert np.array_equal(sfc.scatter_tiles(inner, 2, 13, 9), x)
+    # halo of the first tile is the zero padding
+    assert np.all(tiles[0, :, 0, :] == 0) and np.all(tiles[0, :, :, 0] == 0)
+
+
+# ---- Sec. 5 quantizer ----------------------------------------------------------
+
+
+def test_quantizer_hand_values():
+    # ties go to even, negative values mirror, clamp is symmetric
+    v = np.array([1, 3, 5, -1, -3, 7, 1000, -1000, 0])
+    q = sfc.quantize(v, np.float32(0.5))
+    assert list(q) == [0, 2, 2, 0, -2, 4, 127, -127, 0]
+    # 1/3 in float32 is 0x3EAAAAAB > 1/3: 3 * that is slightly above 1 -> rounds to 1; 381*inv -> 127
+    inv = sfc.reciprocal_f32(np.float32(3.0))
+    assert inv.dtype == np.float32 and float(inv) == float(np.float32(1.0) / np.float32(3.0))
+    assert list(sfc.quantize(np.array([3, 4, 5, 381, 383]), inv)) == [1, 1, 2, 127, 127]
+    assert list(sfc.quantize(np.array([9, -9]), np.float32(0.5), qmax=7)) == [4, -4]
+
+
+def test_requant_reduces_to_exact_when_nothing_rounds_or_clamps():
+    # small-valued data: every transform-domain value is already within +-127
+    rng = np.random.default_rng(10)
+    x = rng.integers(-1, 2, size=(1, 3, 9, 8)).astype(np.int8)
+    w = rng.integers(-2, 3, size=(4, 3, 3, 3)).astype(np.int8)
+    for alg in ("6x6_p100", "6x6_p88"):
+        p = sfc.multiplications_per_tile(alg)
+        ones_x = np.ones(p, dtype=np.float32)
+        ones_w = np.ones((p, 4), dtype=np.float32)
+        ws = np.array([0.5, 0.25, 2.0, 1.0], dtype=np.float32)
+        y, taps = sfc.conv_requant(x, w, ones_x, ones_w, 0.125, ws, alg, return_taps=True)
+        acc, taps_e = sfc.conv_exact(x, w, alg, return_taps=True)
+        assert np.array_equal(taps["V"], taps_e["V"]) and np.array_equal(taps["U"], taps_e["U"])
+        ref = sfc.dequantize(sfc.direct_conv(x, w), 0.125, ws)
+        assert np.allclose(y, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
+        assert np.array_equal(acc, sfc.direct_conv(x, w))
+
+
+def test_requant_with_power_of_two_point_scales_is_still_exact():
+    # s_Tx[p] = 2^-e_p, s_Tf[p,k] = 2^-f_pk: dividing by them never rounds, so the
+    # result must still be the direct convolution.  A scale applied to the wrong
+    # point, or a missing factor, changes the answer.
+    rng = np.random.default_rng(11)
+    x = rng.integers(-1, 2, size=(2, 2, 7, 11)).astype(np.int8)
+    w = rng.integers(-1, 2, size=(3, 2, 3, 3)).astype(np.int8)
+    for alg in ("6x6_p100", "6x6_p88"):
+        p = sfc.multiplications_per_tile(alg)
+        sx = (2.0 ** -rng.integers(0, 2, size=p)).astype(np.float32)  # |V| <= 36 -> <= 72
+        sw = (2.0 ** -rng.integers(0, 4, size=(p, 3))).astype(np.float32)  # |U| <= 9 -> <= 72
+        y = sfc.conv_requant(x, w, sx, sw, 0.02, np.array([0.01], np.float32), alg)
+        ref = sfc.dequantize(sfc.direct_conv(x, w), 0.02, np.float32(0.01))
+        assert np.allclose(y, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
+
+
+def test_requant_error_is_small_and_halves_per_extra_bit():
+    from paper_2407_02913_amd import synth
+
+    shape = synth.LayerShape("t", 2, 16, 16, 14, 14, "relu", True, 2)
+    d = synth.make_layer(shape)
+    ref = sfc.dequantize(sfc.direct_conv(d["x"], d["w"]), d["x_scale"], d["w_scale"])
+    errs = []
+    for bits in (8, 7, 6, 5):
+        qmax = 2 ** (bits - 1) - 1
+        sx = sfc.calibrate_act_scales(d["x"], qmax=qmax)
+        sw = sfc.calibrate_filter_scales(d["w"], qmax=qmax)
+        y = sfc.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"], qmax=qmax)
+        errs.append(np.sqrt(np.mean((y - ref) ** 2)) / np.sqrt(np.mean(ref**2)))
+    assert errs[0] < 0.03
+    for a, b in zip(errs, errs[1:]):
+        assert 1.5 < b / a < 2.7
+
+
+def test_calibrated_scales():
+    rng = np.random.default_rng(12)
+    x = rng.integers(-128, 128, size=(1, 3, 8, 8)).astype(np.int8)
+    w = rng.integers(-128, 128, size=(2, 3, 3, 3)).astype(np.int8)
+    w[1] = 0
+    sx = sfc.calibrate_act_scales(x)
+    sw = sfc.calibrate_filter_scales(w)
+    assert sx.dtype == np.float32 and sx.shape == (88,) and sw.shape == (88, 2)
+    assert np.all(sw[:, 1] == 1.0)  # an all-zero channel gets scale 1
+    b2, g2, _, _ = sfc.algorithm("6x6_p88")
+    v = sfc.input_transform(x, b2)
+    q = sfc.quantize(v, sfc.reciprocal_f32(sx)[:, None, None])
+    assert np.abs(q).max() == 127  # abs-max calibration uses the full range
+
+
+def test_requantize_activation():
+    y = np.array([-1.0, 0.0, 0.25, 0.75, 1.25, 1.3, 100.0])
+    assert list(sfc.requantize_activation(y, 0.5)) == [0, 0, 0, 2, 2, 3, 127]
