@@ -1,0 +1,151 @@
+/*
+ * sfc.h -- C ABI of the MI355X (gfx950) library for quantized 3x3 convolution by
+ * Symbolic Fourier Convolution, SFC-6(6x6,3x3) (arXiv 2407.02913).
+ *
+ * The library computes, for int8 activations x[N,Cin,H,W] and int8 filters
+ * w[Cout,Cin,3,3] (stride 1, zero padding 1, cross-correlation),
+ *
+ *      y = A^T [ (G f G^T) . (B^T x B) ] A        summed over Cin      (Eq. 1)
+ *
+ * with the addition-only symbolic DFT-6 transforms of Sec. 4.1, the correction
+ * terms of Sec. 4.2 and the integrated matrices of Appendix A, on 6x6 output
+ * tiles (8x8 input tiles).  Per tile and (Cin,Cout) pair it spends P = 88
+ * multiplications (Hermitian form) or P = 100 (nested form), Appendix A.
+ *
+ * Conventions
+ *  - "dev" pointers are device (HBM) addresses on the current HIP device, "host"
+ *    pointers are ordinary host memory.  Device pointers must be 16-byte aligned.
+ *  - The library never allocates or frees device memory and never synchronizes
+ *    the stream, except where a call says it blocks.  The caller owns every
+ *    device buffer and keeps it alive until the work queued on `stream` is done.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *  - Every call returns an sfc_status; argument errors are detected before any
+ *    launch; nothing is printed and nothing aborts.
+ *  - A plan is host memory owned by the library.  After sfc_transform_filter it
+ *    is read-only and may serve concurrent sfc_conv2d_nchw calls on different
+ *    streams provided each call has its own workspace.
+ */
+#ifndef SFC_H_
+#define SFC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sfc_plan_s sfc_plan_t;
+
+typedef enum {
+  SFC_OK = 0,
+  SFC_EINVAL = 1,       /* null pointer, non-positive size, misaligned pointer, bad enum */
+  SFC_EUNSUPPORTED = 2, /* valid request this build does not implement */
+  SFC_ENOMEM = 3,       /* host allocation failed */
+  SFC_ENOTREADY = 4,    /* scales or filter not set yet */
+  SFC_EHIP = 5          /* a HIP runtime call or kernel launch failed */
+} sfc_status;
+
+/* Which 2-D point set realizes the element-wise product of Eq. (1), Appendix A. */
+typedef enum {
+  SFC_ALG_6X6_P88 = 0, /* Hermitian symmetry fully used: 88 multiplications per tile */
+  SFC_ALG_6X6_P100 = 1 /* nested (Kronecker) form: 100 multiplications per tile */
+} sfc_alg;
+
+typedef enum {
+  /* Transform domain kept in exact integers (int16 operands, int32 sums): the
+   * result equals direct convolution bit for bit (Sec. 5.1 assumes the
+   * transforms accurate).  int32 sums are guaranteed for Cin <= 404. */
+  SFC_MODE_EXACT = 0,
+  /* Transform-domain operands rounded to int8 with one scale per point for the
+   * activations and one per (point, Cout) for the filters (Sec. 5, the
+   * frequency-wise / channel-wise quantization equation). */
+  SFC_MODE_REQUANT_I8 = 1
+} sfc_mode;
+
+typedef enum {
+  SFC_OUT_F32 = 0, /* y float32 [N,Cout,H,W], dequantized */
+  SFC_OUT_I32 = 1  /* exact mode only: the raw integer sums, int32 [N,Cout,H,W] */
+} sfc_out;
+
+typedef enum {
+  SFC_PATH_STAGED = 0, /* V and M pass through the workspace; taps available */
+  SFC_PATH_FUSED = 1   /* product and output transform in one kernel; M never leaves the chip */
+} sfc_path;
+
+typedef struct {
+  int32_t N, Cin, Cout, H, W; /* 3x3 filter, stride 1, zero padding 1 are fixed */
+  int32_t alg;                /* sfc_alg */
+  int32_t mode;               /* sfc_mode */
+  int32_t out;                /* sfc_out */
+  int32_t path;               /* sfc_path */
+  int32_t per_channel_wscale; /* 0: one filter scale, 1: Cout filter scales */
+} sfc_conv_desc;
+
+/* Host only.  Validates the description and derives the tile grid
+ * (ceil(H/6) x ceil(W/6) tiles per image) and all buffer sizes.  No device work.
+ * *out receives a plan to be released with sfc_plan_destroy. */
+sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out);
+void sfc_plan_destroy(sfc_plan_t* plan);
+
+/* Sizes the caller must allocate (device bytes) and the derived counts:
+ * P = multiplications per tile (88 or 100), tiles = N*ceil(H/6)*ceil(W/6).
+ * Any output pointer may be NULL. */
+sfc_status sfc_plan_sizes(const sfc_plan_t* plan, size_t* filter_bytes, size_t* workspace_bytes,
+                          int32_t* P, int64_t* tiles);
+
+/* Requantized mode: the transform-domain scales of Sec. 5, copied into the plan.
+ * sx_host[P]: one activation scale per point (s_Tx).  sw_host[P*Cout], laid out
+ * [P][Cout]: one filter scale per point and output channel (s_Tf).  All > 0.
+ * Point order: for P = 100, p = 10*p1 + p2 over the rows of the printed 1-D
+ * matrices (p1 vertical); for P = 88, first the 64 nested points that are not
+ * complex x complex, in that same order, then for (k1,k2) = (1,1),(1,2),(2,1),(2,2)
+ * the six points U0,U1,U0+U1,V0,V1,V0+V1 of the two independent 2-D frequencies.
+ * Must precede sfc_transform_filter. */
+sfc_status sfc_set_point_scales(sfc_plan_t* plan, const float* sx_host, const float* sw_host);
+
+/* Abs-max calibration helpers (the paper tunes scales with AdaQuant on real
+ * data; abs-max over a calibration tensor stands in): scale = max|value|/127,
+ * 1 where the maximum is 0.  Both block until the result is in host memory.
+ * workspace_dev must hold workspace_bytes of a plan whose N >= n_images. */
+sfc_status sfc_calibrate_act_scales(const sfc_plan_t* plan, const int8_t* x_dev, int32_t n_images,
+                                    void* workspace_dev, void* stream, float* sx_host_out /*[P]*/);
+sfc_status sfc_calibrate_filter_scales(const sfc_plan_t* plan, const int8_t* w_dev,
+                                       void* workspace_dev, void* stream,
+                                       float* sw_host_out /*[P*Cout]*/);
+
+/* Filter transform U = G f G^T (Appendix A's G, additions only), once per layer.
+ * w_dev: int8 [Cout,Cin,3,3].  wscale_host: [1] or [Cout] spatial-domain filter
+ * scales.  filter_dev: >= filter_bytes, receives U (int16 in exact mode, rounded
+ * to int8 in requantized mode) and the per-point dequantization table; the plan
+ * remembers the pointer.  Asynchronous on `stream` apart from a small pageable
+ * host-to-device copy.  Requantized mode needs sfc_set_point_scales first
+ * (SFC_ENOTREADY otherwise). */
+sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const float* wscale_host,
+                                void* filter_dev, void* stream);
+
+/* The hot path: input-tile transform V = B^T x B, P products
+ * M_p[tiles x Cout] = V_p[tiles x Cin] . U_p[Cin x Cout], output transform with
+ * the correction terms, dequantization and the NCHW store.
+ * x_dev: int8 [N,Cin,H,W]; x_scale: spatial-domain activation scale.
+ * y_dev: float32 (SFC_OUT_F32) or int32 (SFC_OUT_I32) [N,Cout,H,W].
+ * workspace_dev: >= workspace_bytes, private to this call until it completes.
+ * SFC_ENOTREADY before sfc_transform_filter. */
+sfc_status sfc_conv2d_nchw(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale, void* y_dev,
+                           void* workspace_dev, void* stream);
+
+/* Where the intermediate tensors of the last staged call live, for parity checks.
+ * which: 0 = V [P][tiles][Cin], 1 = U [P][Cout][Cin], 2 = M [P][tiles][Cout] (int32).
+ * ptr receives a device address inside workspace_dev (V, M) or the filter buffer
+ * (U); elem_bytes is 1 or 2 for V and U (int8 / int16) and 4 for M; dims and
+ * strides (in elements) describe the three axes.  V is valid on both paths, M
+ * only on SFC_PATH_STAGED (SFC_EUNSUPPORTED otherwise). */
+sfc_status sfc_tap_info(const sfc_plan_t* plan, const void* workspace_dev, int32_t which,
+                        const void** ptr, int32_t* elem_bytes, int64_t dims[3], int64_t strides[3]);
+
+const char* sfc_status_string(sfc_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SFC_H_ */

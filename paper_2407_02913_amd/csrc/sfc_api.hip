@@ -1,0 +1,310 @@
+// C ABI of the SFC library: plans, argument checks, buffer layout, stage sequencing.
+// Every numeric step runs in the kernels of sfc_kernels.hip; this file only
+// validates, lays out buffers and launches.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/sfc.h"
+#include "sfc_internal.hpp"
+
+using sfc::FilterViews;
+using sfc::Geometry;
+
+struct sfc_plan_s {
+  sfc_conv_desc d;
+  Geometry g;
+  int esz;  // bytes per transform-domain operand: 2 exact, 1 requantized
+  // filter buffer layout (byte offsets)
+  size_t off_U, off_dequant, off_inv_sw, off_inv_sx, off_wscale, filter_bytes;
+  // workspace layout
+  size_t off_V, off_M, workspace_bytes;
+  std::vector<float> sx, sw;  // [P], [P][Cout]
+  bool scales_set;
+  std::vector<float> staging;  // host image of the float tables of the filter buffer
+  void* filter_dev;
+  bool filter_ready;
+};
+
+namespace {
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+FilterViews views(const sfc_plan_s* p, void* filter_dev) {
+  char* b = static_cast<char*>(filter_dev);
+  FilterViews f;
+  f.U = b + p->off_U;
+  f.dequant = reinterpret_cast<float*>(b + p->off_dequant);
+  f.inv_sw = reinterpret_cast<float*>(b + p->off_inv_sw);
+  f.inv_sx = reinterpret_cast<float*>(b + p->off_inv_sx);
+  f.wscale = reinterpret_cast<float*>(b + p->off_wscale);
+  return f;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sfc_status_string(sfc_status s) {
+  switch (s) {
+    case SFC_OK: return "ok";
+    case SFC_EINVAL: return "invalid argument";
+    case SFC_EUNSUPPORTED: return "unsupported configuration";
+    case SFC_ENOMEM: return "host allocation failed";
+    case SFC_ENOTREADY: return "scales or filter not set";
+    case SFC_EHIP: return "HIP runtime or launch failure";
+  }
+  return "unknown status";
+}
+
+sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
+  if (!desc || !out) return SFC_EINVAL;
+  *out = nullptr;
+  const sfc_conv_desc& d = *desc;
+  if (d.N <= 0 || d.Cin <= 0 || d.Cout <= 0 || d.H <= 0 || d.W <= 0) return SFC_EINVAL;
+  if (d.alg != SFC_ALG_6X6_P88 && d.alg != SFC_ALG_6X6_P100) return SFC_EINVAL;
+  if (d.mode != SFC_MODE_EXACT && d.mode != SFC_MODE_REQUANT_I8) return SFC_EINVAL;
+  if (d.out != SFC_OUT_F32 && d.out != SFC_OUT_I32) return SFC_EINVAL;
+  if (d.path != SFC_PATH_STAGED && d.path != SFC_PATH_FUSED) return SFC_EINVAL;
+  if (d.per_channel_wscale != 0 && d.per_channel_wscale != 1) return SFC_EINVAL;
+  if (d.out == SFC_OUT_I32 && d.mode != SFC_MODE_EXACT) return SFC_EUNSUPPORTED;
+  if (d.path == SFC_PATH_FUSED && d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
+  if (d.W > 1024 || d.H > (1 << 20) || d.Cin > (1 << 16) || d.Cout > 65535 * 16)
+    return SFC_EUNSUPPORTED;
+
+  Geometry g;
+  g.N = d.N; g.Cin = d.Cin; g.Cout = d.Cout; g.H = d.H; g.W = d.W;
+  g.th = (d.H + 5) / 6;
+  g.tw = (d.W + 5) / 6;
+  const int64_t strips = (int64_t)d.N * g.th;
+  const int64_t T = strips * g.tw;
+  if (T > (1ll << 30)) return SFC_EUNSUPPORTED;
+  g.strips = (int)strips;
+  g.T = (int)T;
+  g.Tp = (int)((T + 15) / 16 * 16);
+  g.Cp = (d.Cin + 63) / 64 * 64;
+  g.Kp = (d.Cout + 15) / 16 * 16;
+  g.P = d.alg == SFC_ALG_6X6_P88 ? 88 : 100;
+
+  sfc_plan_s* p = new (std::nothrow) sfc_plan_s();
+  if (!p) return SFC_ENOMEM;
+  p->d = d;
+  p->g = g;
+  p->esz = d.mode == SFC_MODE_EXACT ? 2 : 1;
+  const size_t PK = (size_t)g.P * g.Kp;
+  size_t off = 0;
+  p->off_U = off;        off = align_up(off + PK * g.Cp * p->esz, 256);
+  p->off_dequant = off;  off = align_up(off + PK * sizeof(float), 256);
+  p->off_inv_sw = off;   off = align_up(off + PK * sizeof(float), 256);
+  p->off_inv_sx = off;   off = align_up(off + g.P * sizeof(float), 256);
+  p->off_wscale = off;   off = align_up(off + g.Kp * sizeof(float), 256);
+  p->filter_bytes = off;
+  off = 0;
+  p->off_V = off;        off = align_up(off + (size_t)g.P * g.Tp * g.Cp * p->esz, 256);
+  p->off_M = off;
+  if (d.path == SFC_PATH_STAGED) off = align_up(off + (size_t)g.P * g.Tp * g.Kp * 4, 256);
+  // calibration scratch (abs-max tables) must fit as well
+  const size_t calib = align_up((size_t)g.P * (size_t)(g.Cout > 1 ? g.Cout : 1) * 4, 256);
+  p->workspace_bytes = off > calib ? off : calib;
+  p->scales_set = false;
+  p->filter_dev = nullptr;
+  p->filter_ready = false;
+  *out = p;
+  return SFC_OK;
+}
+
+void sfc_plan_destroy(sfc_plan_t* plan) { delete plan; }
+
+sfc_status sfc_plan_sizes(const sfc_plan_t* plan, size_t* filter_bytes, size_t* workspace_bytes,
+                          int32_t* P, int64_t* tiles) {
+  if (!plan) return SFC_EINVAL;
+  if (filter_bytes) *filter_bytes = plan->filter_bytes;
+  if (workspace_bytes) *workspace_bytes = plan->workspace_bytes;
+  if (P) *P = plan->g.P;
+  if (tiles) *tiles = plan->g.T;
+  return SFC_OK;
+}
+
+sfc_status sfc_set_point_scales(sfc_plan_t* plan, const float* sx_host, const float* sw_host) {
+  if (!plan || !sx_host || !sw_host) return SFC_EINVAL;
+  if (plan->d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
+  const int P = plan->g.P, K = plan->g.Cout;
+  auto ok = [](float s) {
+    if (!(s > 0.0f) || !std::isfinite(s)) return false;
+    const float inv = 1.0f / s;
+    return std::isfinite(inv) && inv > 0.0f;
+  };
+  for (int p = 0; p < P; ++p)
+    if (!ok(sx_host[p])) return SFC_EINVAL;
+  for (size_t i = 0; i < (size_t)P * K; ++i)
+    if (!ok(sw_host[i])) return SFC_EINVAL;
+  try {
+    plan->sx.assign(sx_host, sx_host + P);
+    plan->sw.assign(sw_host, sw_host + (size_t)P * K);
+  } catch (...) {
+    return SFC_ENOMEM;
+  }
+  plan->scales_set = true;
+  plan->filter_ready = false;
+  return SFC_OK;
+}
+
+sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const float* wscale_host,
+                                void* filter_dev, void* stream) {
+  if (!plan || !w_dev || !wscale_host || !filter_dev) return SFC_EINVAL;
+  if (!aligned16(w_dev) || !aligned16(filter_dev)) return SFC_EINVAL;
+  const Geometry& g = plan->g;
+  const bool requant = plan->d.mode == SFC_MODE_REQUANT_I8;
+  if (requant && !plan->scales_set) return SFC_ENOTREADY;
+  for (int k = 0; k < (plan->d.per_channel_wscale ? g.Cout : 1); ++k)
+    if (!(wscale_host[k] > 0.0f) || !std::isfinite(wscale_host[k])) return SFC_EINVAL;
+
+  // host image of the float tables: [dequant | inv_sw | inv_sx | wscale], contiguous
+  // from off_dequant to filter_bytes
+  const size_t table_bytes = plan->filter_bytes - plan->off_dequant;
+  try {
+    plan->staging.assign(table_bytes / sizeof(float), 0.0f);
+  } catch (...) {
+    return SFC_ENOMEM;
+  }
+  char* base = reinterpret_cast<char*>(plan->staging.data()) - plan->off_dequant;
+  float* dequant = reinterpret_cast<float*>(base + plan->off_dequant);
+  float* inv_sw = reinterpret_cast<float*>(base + plan->off_inv_sw);
+  float* inv_sx = reinterpret_cast<float*>(base + plan->off_inv_sx);
+  float* wscale = reinterpret_cast<float*>(base + plan->off_wscale);
+  for (int k = 0; k < g.Kp; ++k)
+    wscale[k] = k < g.Cout ? wscale_host[plan->d.per_channel_wscale ? k : 0] : 0.0f;
+  for (int p = 0; p < g.P; ++p) {
+    inv_sx[p] = requant ? 1.0f / plan->sx[p] : 1.0f;
+    for (int k = 0; k < g.Kp; ++k) {
+      float dq = 0.0f, inv = 1.0f;
+      if (requant && k < g.Cout) {
+        const float sw = plan->sw[(size_t)p * g.Cout + k];
+        inv = 1.0f / sw;
+        dq = (float)((double)plan->sx[p] * (double)sw * (double)wscale[k] / 36.0);
+      }
+      dequant[(size_t)p * g.Kp + k] = dq;
+      inv_sw[(size_t)p * g.Kp + k] = inv;
+    }
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(static_cast<char*>(filter_dev) + plan->off_dequant, plan->staging.data(),
+                     table_bytes, hipMemcpyHostToDevice, s) != hipSuccess)
+    return SFC_EHIP;
+  const FilterViews f = views(plan, filter_dev);
+  if (sfc::launch_filter_transform(plan->d.alg, plan->d.mode, g, w_dev, f, s) != hipSuccess)
+    return SFC_EHIP;
+  plan->filter_dev = filter_dev;
+  plan->filter_ready = true;
+  return SFC_OK;
+}
+
+sfc_status sfc_conv2d_nchw(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale, void* y_dev,
+                           void* workspace_dev, void* stream) {
+  if (!plan || !x_dev || !y_dev || !workspace_dev) return SFC_EINVAL;
+  if (!aligned16(x_dev) || !aligned16(y_dev) || !aligned16(workspace_dev)) return SFC_EINVAL;
+  if (!(x_scale > 0.0f) || !std::isfinite(x_scale)) return SFC_EINVAL;
+  if (!plan->filter_ready) return SFC_ENOTREADY;
+  const Geometry& g = plan->g;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const FilterViews f = views(plan, plan->filter_dev);
+  char* ws = static_cast<char*>(workspace_dev);
+  void* V = ws + plan->off_V;
+  if (sfc::launch_input_transform(plan->d.alg, plan->d.mode, g, x_dev, V, f.inv_sx, s) !=
+      hipSuccess)
+    return SFC_EHIP;
+  if (plan->d.path == SFC_PATH_FUSED) {
+    if (sfc::launch_fused_product_output(plan->d.alg, g, V, f, x_scale,
+                                         static_cast<float*>(y_dev), s) != hipSuccess)
+      return SFC_EHIP;
+    return SFC_OK;
+  }
+  int32_t* M = reinterpret_cast<int32_t*>(ws + plan->off_M);
+  if (sfc::launch_product(plan->d.mode, g, V, f.U, M, s) != hipSuccess) return SFC_EHIP;
+  if (sfc::launch_output_transform(plan->d.alg, plan->d.mode, plan->d.out, g, M, f, x_scale, y_dev,
+                                   s) != hipSuccess)
+    return SFC_EHIP;
+  return SFC_OK;
+}
+
+sfc_status sfc_tap_info(const sfc_plan_t* plan, const void* workspace_dev, int32_t which,
+                        const void** ptr, int32_t* elem_bytes, int64_t dims[3],
+                        int64_t strides[3]) {
+  if (!plan || !ptr || !elem_bytes || !dims || !strides) return SFC_EINVAL;
+  const Geometry& g = plan->g;
+  const char* ws = static_cast<const char*>(workspace_dev);
+  switch (which) {
+    case 0:
+      if (!workspace_dev) return SFC_EINVAL;
+      *ptr = ws + plan->off_V;
+      *elem_bytes = plan->esz;
+      dims[0] = g.P; dims[1] = g.T; dims[2] = g.Cin;
+      strides[0] = (int64_t)g.Tp * g.Cp; strides[1] = g.Cp; strides[2] = 1;
+      return SFC_OK;
+    case 1:
+      if (!plan->filter_ready) return SFC_ENOTREADY;
+      *ptr = static_cast<const char*>(plan->filter_dev) + plan->off_U;
+      *elem_bytes = plan->esz;
+      dims[0] = g.P; dims[1] = g.Cout; dims[2] = g.Cin;
+      strides[0] = (int64_t)g.Kp * g.Cp; strides[1] = g.Cp; strides[2] = 1;
+      return SFC_OK;
+    case 2:
+      if (!workspace_dev) return SFC_EINVAL;
+      if (plan->d.path != SFC_PATH_STAGED) return SFC_EUNSUPPORTED;
+      *ptr = ws + plan->off_M;
+      *elem_bytes = 4;
+      dims[0] = g.P; dims[1] = g.T; dims[2] = g.Cout;
+      strides[0] = (int64_t)g.Tp * g.Kp; strides[1] = g.Kp; strides[2] = 1;
+      return SFC_OK;
+    default:
+      return SFC_EINVAL;
+  }
+}
+
+static sfc_status maxima_to_scales(const int32_t* dev, size_t count, hipStream_t s, float* out) {
+  std::vector<int32_t> host;
+  try {
+    host.resize(count);
+  } catch (...) {
+    return SFC_ENOMEM;
+  }
+  if (hipMemcpyAsync(host.data(), dev, count * sizeof(int32_t), hipMemcpyDeviceToHost, s) !=
+      hipSuccess)
+    return SFC_EHIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return SFC_EHIP;
+  for (size_t i = 0; i < count; ++i)
+    out[i] = host[i] == 0 ? 1.0f : (float)host[i] / 127.0f;
+  return SFC_OK;
+}
+
+sfc_status sfc_calibrate_act_scales(const sfc_plan_t* plan, const int8_t* x_dev, int32_t n_images,
+                                    void* workspace_dev, void* stream, float* sx_host_out) {
+  if (!plan || !x_dev || !workspace_dev || !sx_host_out) return SFC_EINVAL;
+  if (!aligned16(x_dev) || !aligned16(workspace_dev)) return SFC_EINVAL;
+  if (n_images <= 0 || n_images > plan->g.N) return SFC_EINVAL;
+  Geometry g = plan->g;
+  g.N = n_images;
+  g.strips = n_images * g.th;
+  g.T = g.strips * g.tw;
+  g.Tp = (g.T + 15) / 16 * 16;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t* maxima = static_cast<int32_t*>(workspace_dev);
+  if (sfc::launch_act_absmax(plan->d.alg, g, x_dev, maxima, s) != hipSuccess) return SFC_EHIP;
+  return maxima_to_scales(maxima, g.P, s, sx_host_out);
+}
+
+sfc_status sfc_calibrate_filter_scales(const sfc_plan_t* plan, const int8_t* w_dev,
+                                       void* workspace_dev, void* stream, float* sw_host_out) {
+  if (!plan || !w_dev || !workspace_dev || !sw_host_out) return SFC_EINVAL;
+  if (!aligned16(w_dev) || !aligned16(workspace_dev)) return SFC_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t* maxima = static_cast<int32_t*>(workspace_dev);
+  if (sfc::launch_filter_absmax(plan->d.alg, plan->g, w_dev, maxima, s) != hipSuccess)
+    return SFC_EHIP;
+  return maxima_to_scales(maxima, (size_t)plan->g.P * plan->g.Cout, s, sw_host_out);
+}
+
+}  // extern "C"

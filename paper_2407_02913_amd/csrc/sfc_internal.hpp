@@ -1,0 +1,47 @@
+// Internal interface between the C ABI (sfc_api.hip) and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace sfc {
+
+// Everything a kernel needs to know about one convolution, by value.
+struct Geometry {
+  int N, Cin, Cout, H, W;
+  int th, tw;     // tile grid per image: ceil(H/6), ceil(W/6)
+  int strips;     // N * th: one strip = one row of tiles of one image
+  int T;          // tiles = strips * tw
+  int Tp;         // T rounded up to 16 (row padding of V and M)
+  int Cp;         // Cin rounded up to 64 (the K extent of one int8 MFMA)
+  int Kp;         // Cout rounded up to 16
+  int P;          // multiplication points per tile
+};
+
+// Device-side views of the filter buffer (all inside the caller's filter_dev).
+struct FilterViews {
+  void* U;              // [P][Kp][Cp] int8 (requantized) or int16 (exact)
+  float* dequant;       // requantized: [P][Kp] s_Tx[p]*s_Tf[p,k]*s_w[k]/36; exact: unused
+  float* inv_sw;        // [P][Kp] 1/s_Tf
+  float* inv_sx;        // [P]     1/s_Tx
+  float* wscale;        // [Kp]    s_w[k]
+};
+
+hipError_t launch_filter_transform(int alg, int mode, const Geometry& g, const int8_t* w,
+                                   const FilterViews& f, hipStream_t s);
+hipError_t launch_input_transform(int alg, int mode, const Geometry& g, const int8_t* x, void* V,
+                                  const float* inv_sx, hipStream_t s);
+hipError_t launch_product(int mode, const Geometry& g, const void* V, const void* U, int32_t* M,
+                          hipStream_t s);
+hipError_t launch_output_transform(int alg, int mode, int out, const Geometry& g, const int32_t* M,
+                                   const FilterViews& f, float x_scale, void* y, hipStream_t s);
+hipError_t launch_fused_product_output(int alg, const Geometry& g, const void* V,
+                                       const FilterViews& f, float x_scale, float* y,
+                                       hipStream_t s);
+// abs-max calibration: maxima are int32, zeroed by the launcher
+hipError_t launch_act_absmax(int alg, const Geometry& g, const int8_t* x, int32_t* maxima /*[P]*/,
+                             hipStream_t s);
+hipError_t launch_filter_absmax(int alg, const Geometry& g, const int8_t* w,
+                                int32_t* maxima /*[P][Cout]*/, hipStream_t s);
+
+}  // namespace sfc

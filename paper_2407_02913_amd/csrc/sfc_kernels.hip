@@ -1,0 +1,459 @@
+// HIP kernels for SFC-6(6x6,3x3) on gfx950 (wave64, int8 MFMA).
+//
+//   filter_transform_kernel   U = G f G^T               (once per layer)
+//   input_transform_kernel    V = B^T x B               (NCHW int8 -> [P][Tp][Cp])
+//   product_i8_kernel         M_p = V_p . U_p^T         (int8 MFMA, int32 sums)
+//   product_i16_kernel        the same for exact mode   (int16 operands, vector ALU)
+//   output_transform_kernel   y = A^T M A, corrections, dequantization, NCHW store
+//
+// Layouts (element strides): V[p][t][c] = (p*Tp + t)*Cp + c, U[p][k][c] =
+// (p*Kp + k)*Cp + c, M[p][t][k] = (p*Tp + t)*Kp + k.  Channels c >= Cin and
+// filters k >= Cout are zero in U, so padding never contributes to a sum.
+#include "sfc_internal.hpp"
+#include "sfc_points.hpp"
+
+namespace sfc {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// round-half-even(v * inv) clamped to [-127, 127].  Adding 1.5 * 2^23 inside one
+// fused multiply-add rounds the exact product once, to an integer, ties to even;
+// the integer then sits in the low mantissa bits.
+__device__ __forceinline__ int quantize_i8(int v, float inv) {
+  constexpr float kMagic = 12582912.0f;  // 0x4B400000
+  float t = __fmaf_rn((float)v, inv, kMagic);
+  t = fminf(fmaxf(t, kMagic - 127.0f), kMagic + 127.0f);
+  return __float_as_int(t) - 0x4B400000;
+}
+
+// ---------------------------------------------------------------------------
+// filter transform: one thread per (k, c) of the padded [Kp][Cp] domain
+// ---------------------------------------------------------------------------
+template <int ALG, int MODE>
+__global__ __launch_bounds__(256) void filter_transform_kernel(const int8_t* __restrict__ w,
+                                                               void* __restrict__ U,
+                                                               const float* __restrict__ inv_sw,
+                                                               Geometry g) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  const int k = blockIdx.y;
+  if (c >= g.Cp) return;
+  int f[3][3];
+  const bool valid = (k < g.Cout) && (c < g.Cin);
+#pragma unroll
+  for (int r = 0; r < 3; ++r)
+#pragma unroll
+    for (int s = 0; s < 3; ++s)
+      f[r][s] = valid ? (int)w[((size_t)k * g.Cin + c) * 9 + r * 3 + s] : 0;
+  int half[3][8];
+#pragma unroll
+  for (int r = 0; r < 3; ++r) fwd3(f[r], half[r]);
+  int comp[8][8];
+#pragma unroll
+  for (int b = 0; b < 8; ++b) {
+    const int col[3] = {half[0][b], half[1][b], half[2][b]};
+    int cc[8];
+    fwd3(col, cc);
+#pragma unroll
+    for (int a = 0; a < 8; ++a) comp[a][b] = cc[a];
+  }
+  for_each_point<ALG>(comp, [&](int p, int v) {
+    const size_t idx = ((size_t)p * g.Kp + k) * g.Cp + c;
+    if constexpr (MODE == 1) {
+      ((int8_t*)U)[idx] = (int8_t)quantize_i8(v, inv_sw[p * g.Kp + k]);
+    } else {
+      ((int16_t*)U)[idx] = (int16_t)v;
+    }
+  });
+}
+
+// abs-max over Cin of every transformed filter value: one block per k
+template <int ALG>
+__global__ __launch_bounds__(256) void filter_absmax_kernel(const int8_t* __restrict__ w,
+                                                            int32_t* __restrict__ maxima,
+                                                            Geometry g) {
+  __shared__ int smax[AlgTraits<ALG>::P];
+  const int k = blockIdx.x;
+  for (int i = threadIdx.x; i < AlgTraits<ALG>::P; i += blockDim.x) smax[i] = 0;
+  __syncthreads();
+  for (int c = threadIdx.x; c < g.Cin; c += blockDim.x) {
+    int f[3][3];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+      for (int s = 0; s < 3; ++s) f[r][s] = (int)w[((size_t)k * g.Cin + c) * 9 + r * 3 + s];
+    int half[3][8];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) fwd3(f[r], half[r]);
+    int comp[8][8];
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      const int col[3] = {half[0][b], half[1][b], half[2][b]};
+      int cc[8];
+      fwd3(col, cc);
+#pragma unroll
+      for (int a = 0; a < 8; ++a) comp[a][b] = cc[a];
+    }
+    for_each_point<ALG>(comp, [&](int p, int v) { atomicMax(&smax[p], v < 0 ? -v : v); });
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < AlgTraits<ALG>::P; i += blockDim.x)
+    maxima[(size_t)i * g.Cout + k] = smax[i];
+}
+
+// ---------------------------------------------------------------------------
+// input transform
+//
+// One workgroup owns S consecutive strips (a strip = one row of tiles of one
+// image, i.e. input rows 6*ti-1 .. 6*ti+6) for 64 channels.  The eight input
+// rows of a (strip, channel) are one contiguous run of 8*W bytes in NCHW, so the
+// workgroup copies them to LDS with coalesced loads, then each thread transforms
+// one (tile, channel) patch with lanes running along channels, which makes the
+// V stores contiguous.  MODE: 0 int16 out, 1 int8 requantized out, 2 abs-max.
+// ---------------------------------------------------------------------------
+struct StripParams {
+  int S;         // strips per workgroup
+  int cs;        // LDS bytes per (strip, channel): 8*W padded to 4*(odd)
+  int vec4;      // 1: W % 4 == 0, rows are dword aligned
+};
+
+template <int ALG, int MODE>
+__global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __restrict__ x,
+                                                              void* __restrict__ V,
+                                                              const float* __restrict__ inv_sx,
+                                                              int32_t* __restrict__ maxima,
+                                                              Geometry g, StripParams sp) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  constexpr int P = AlgTraits<ALG>::P;
+  __shared__ int smax[MODE == 2 ? P : 1];
+  if constexpr (MODE == 2) {
+    for (int i = threadIdx.x; i < P; i += blockDim.x) smax[i] = 0;
+  }
+  const int strip0 = blockIdx.x * sp.S;
+  const int c0 = blockIdx.y * 64;
+  const int W = g.W, H = g.H;
+  const int seg = 8 * W;  // bytes per (strip, channel)
+
+  // ---- stage the raw rows -------------------------------------------------
+  if (sp.vec4) {
+    const int segw = seg >> 2;
+    const int total = sp.S * 64 * segw;
+    for (int i = threadIdx.x; i < total; i += blockDim.x) {
+      const int e = i % segw;
+      const int sc = i / segw;
+      const int c = sc & 63, s = sc >> 6;
+      const int strip = strip0 + s;
+      unsigned val = 0;
+      if (strip < g.strips && c0 + c < g.Cin) {
+        const int n = strip / g.th, ti = strip - n * g.th;
+        const int row = (4 * e) / W;
+        const int h = 6 * ti - 1 + row;
+        if (h >= 0 && h < H) {
+          const size_t base = (((size_t)n * g.Cin + c0 + c) * H + h) * W + (4 * e - row * W);
+          val = *(const unsigned*)(x + base);
+        }
+      }
+      *(unsigned*)(lds + (size_t)sc * sp.cs + 4 * e) = val;
+    }
+  } else {
+    const int total = sp.S * 64 * seg;
+    for (int i = threadIdx.x; i < total; i += blockDim.x) {
+      const int e = i % seg;
+      const int sc = i / seg;
+      const int c = sc & 63, s = sc >> 6;
+      const int strip = strip0 + s;
+      unsigned char val = 0;
+      if (strip < g.strips && c0 + c < g.Cin) {
+        const int n = strip / g.th, ti = strip - n * g.th;
+        const int row = e / W;
+        const int h = 6 * ti - 1 + row;
+        if (h >= 0 && h < H) {
+          const size_t base = (((size_t)n * g.Cin + c0 + c) * H + h) * W + (e - row * W);
+          val = (unsigned char)x[base];
+        }
+      }
+      lds[(size_t)sc * sp.cs + e] = val;
+    }
+  }
+  __syncthreads();
+
+  // ---- transform: item = (strip s, tile column tj, channel c), c fastest ----
+  const int items = sp.S * g.tw * 64;
+  for (int item = threadIdx.x; item < items; item += blockDim.x) {
+    const int c = item & 63;
+    const int rest = item >> 6;
+    const int tj = rest % g.tw;
+    const int s = rest / g.tw;
+    const int strip = strip0 + s;
+    if (strip >= g.strips) continue;
+    const signed char* src = (const signed char*)lds + (size_t)(s * 64 + c) * sp.cs;
+    int half[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int row[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int col = 6 * tj - 1 + j;
+        row[j] = (col >= 0 && col < W) ? (int)src[i * W + col] : 0;
+      }
+      fwd8(row, half[i]);  // horizontal axis: half[i][b]
+    }
+    int comp[8][8];
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      int col[8], cc[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) col[i] = half[i][b];
+      fwd8(col, cc);
+#pragma unroll
+      for (int a = 0; a < 8; ++a) comp[a][b] = cc[a];
+    }
+    const size_t t = (size_t)strip * g.tw + tj;
+    const size_t row_off = t * g.Cp + c0 + c;
+    const size_t pstride = (size_t)g.Tp * g.Cp;
+    for_each_point<ALG>(comp, [&](int p, int v) {
+      if constexpr (MODE == 1) {
+        ((int8_t*)V)[p * pstride + row_off] = (int8_t)quantize_i8(v, inv_sx[p]);
+      } else if constexpr (MODE == 0) {
+        ((int16_t*)V)[p * pstride + row_off] = (int16_t)v;
+      } else {
+        atomicMax(&smax[p], v < 0 ? -v : v);
+      }
+    });
+  }
+  if constexpr (MODE == 2) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < P; i += blockDim.x)
+      if (smax[i] > 0) atomicMax(&maxima[i], smax[i]);
+  }
+}
+
+__global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// ---------------------------------------------------------------------------
+// transform-domain product, requantized mode: int8 MFMA 16x16x64.
+// One wave computes a 16-tile x 16-filter block of one point.  A-operand lane l
+// holds tile row l%16, channels 16*(l/16)..+15 of the 64-channel slice; the
+// B-operand holds filter row l%16 with the same channel slots; the result lane l
+// holds filter column l%16 of tile rows 4*(l/16)..+3.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void product_i8_kernel(const int8_t* __restrict__ V,
+                                                         const int8_t* __restrict__ U,
+                                                         int32_t* __restrict__ M, Geometry g) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int kblocks = g.Kp >> 4;
+  const int tblocks = g.Tp >> 4;
+  const int blk = blockIdx.x * 4 + wave;
+  if (blk >= kblocks * tblocks) return;
+  const int kb = blk % kblocks, tb = blk / kblocks;
+  const int p = blockIdx.y;
+  const int8_t* a_ptr = V + ((size_t)p * g.Tp + tb * 16 + (lane & 15)) * g.Cp + (lane >> 4) * 16;
+  const int8_t* b_ptr = U + ((size_t)p * g.Kp + kb * 16 + (lane & 15)) * g.Cp + (lane >> 4) * 16;
+  v4i acc = {0, 0, 0, 0};
+  for (int kc = 0; kc < g.Cp; kc += 64) {
+    const v4i a = *(const v4i*)(a_ptr + kc);
+    const v4i b = *(const v4i*)(b_ptr + kc);
+    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc, 0, 0, 0);
+  }
+  int32_t* out = M + ((size_t)p * g.Tp + tb * 16 + (lane >> 4) * 4) * g.Kp + kb * 16 + (lane & 15);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) out[(size_t)j * g.Kp] = acc[j];
+}
+
+// exact mode: int16 operands, int32 sums on the vector ALU, 16x16 block per workgroup
+__global__ __launch_bounds__(256) void product_i16_kernel(const int16_t* __restrict__ V,
+                                                          const int16_t* __restrict__ U,
+                                                          int32_t* __restrict__ M, Geometry g) {
+  __shared__ int16_t sv[16][66];
+  __shared__ int16_t su[16][66];
+  const int kblocks = g.Kp >> 4;
+  const int kb = blockIdx.x % kblocks, tb = blockIdx.x / kblocks;
+  const int p = blockIdx.y;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  int acc = 0;
+  for (int kc = 0; kc < g.Cp; kc += 64) {
+    for (int i = threadIdx.x; i < 16 * 64; i += 256) {
+      const int r = i >> 6, c = i & 63;
+      sv[r][c] = V[((size_t)p * g.Tp + tb * 16 + r) * g.Cp + kc + c];
+      su[r][c] = U[((size_t)p * g.Kp + kb * 16 + r) * g.Cp + kc + c];
+    }
+    __syncthreads();
+#pragma unroll 16
+    for (int c = 0; c < 64; ++c) acc += (int)sv[ty][c] * (int)su[tx][c];
+    __syncthreads();
+  }
+  M[((size_t)p * g.Tp + tb * 16 + ty) * g.Kp + kb * 16 + tx] = acc;
+}
+
+// ---------------------------------------------------------------------------
+// output transform, staged: one thread per (tile, filter), lanes along filters
+// ---------------------------------------------------------------------------
+template <int ALG, int MODE, int OUT>
+__global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __restrict__ M,
+                                                               const float* __restrict__ dequant,
+                                                               const float* __restrict__ wscale,
+                                                               float x_scale, void* __restrict__ y,
+                                                               Geometry g, int kx) {
+  const int k = blockIdx.y * kx + (threadIdx.x % kx);
+  const int t = blockIdx.x * (256 / kx) + (threadIdx.x / kx);
+  if (k >= g.Cout || t >= g.T) return;
+  const size_t pstride = (size_t)g.Tp * g.Kp;
+  const int32_t* m = M + (size_t)t * g.Kp + k;
+  const int tiles_per_image = g.th * g.tw;
+  const int n = t / tiles_per_image;
+  const int rem = t - n * tiles_per_image;
+  const int ti = rem / g.tw, tj = rem - ti * g.tw;
+  const size_t ybase = ((size_t)n * g.Cout + k) * g.H * g.W;
+
+  if constexpr (MODE == 1) {
+    float out[6][6];
+    output_transform<ALG, float>(
+        [&](int p) { return (float)m[p * pstride] * dequant[p * g.Kp + k]; }, out);
+#pragma unroll
+    for (int o1 = 0; o1 < 6; ++o1) {
+      const int h = 6 * ti + o1;
+      if (h >= g.H) continue;
+#pragma unroll
+      for (int o2 = 0; o2 < 6; ++o2) {
+        const int w = 6 * tj + o2;
+        if (w < g.W) ((float*)y)[ybase + (size_t)h * g.W + w] = out[o1][o2] * x_scale;
+      }
+    }
+  } else {
+    int out[6][6];
+    output_transform<ALG, int>([&](int p) { return m[p * pstride]; }, out);
+    const float scale = x_scale * wscale[k];
+#pragma unroll
+    for (int o1 = 0; o1 < 6; ++o1) {
+      const int h = 6 * ti + o1;
+      if (h >= g.H) continue;
+#pragma unroll
+      for (int o2 = 0; o2 < 6; ++o2) {
+        const int w = 6 * tj + o2;
+        if (w >= g.W) continue;
+        const int acc = out[o1][o2] / 36;  // exact: the sum is a multiple of 36
+        if constexpr (OUT == 1)
+          ((int32_t*)y)[ybase + (size_t)h * g.W + w] = acc;
+        else
+          ((float*)y)[ybase + (size_t)h * g.W + w] = (float)acc * scale;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+
+static StripParams strip_params(const Geometry& g) {
+  StripParams sp;
+  int seg4 = (8 * g.W + 3) / 4;
+  if ((seg4 & 1) == 0) seg4 += 1;  // odd dword stride: lanes along channels hit distinct banks
+  sp.cs = 4 * seg4;
+  sp.vec4 = (g.W % 4 == 0) ? 1 : 0;
+  // aim at >= 256 (tile, channel) items and <= 32 KB of LDS per workgroup
+  int S = 1;
+  while (S < 16 && S * 2 * 64 * sp.cs <= 32 * 1024 && S * g.tw * 64 < 512) S *= 2;
+  sp.S = S;
+  return sp;
+}
+
+template <int ALG, int MODE>
+static hipError_t launch_input_impl(const Geometry& g, const int8_t* x, void* V,
+                                    const float* inv_sx, int32_t* maxima, hipStream_t s) {
+  const StripParams sp = strip_params(g);
+  const size_t lds = (size_t)sp.S * 64 * sp.cs;
+  if (lds > 64 * 1024) return hipErrorInvalidValue;
+  dim3 grid((g.strips + sp.S - 1) / sp.S, g.Cp / 64);
+  hipLaunchKernelGGL((input_transform_kernel<ALG, MODE>), grid, dim3(256), lds, s, x, V, inv_sx,
+                     maxima, g, sp);
+  return hipGetLastError();
+}
+
+hipError_t launch_input_transform(int alg, int mode, const Geometry& g, const int8_t* x, void* V,
+                                  const float* inv_sx, hipStream_t s) {
+  if (alg == 0) {
+    return mode == 1 ? launch_input_impl<0, 1>(g, x, V, inv_sx, nullptr, s)
+                     : launch_input_impl<0, 0>(g, x, V, inv_sx, nullptr, s);
+  }
+  return mode == 1 ? launch_input_impl<1, 1>(g, x, V, inv_sx, nullptr, s)
+                   : launch_input_impl<1, 0>(g, x, V, inv_sx, nullptr, s);
+}
+
+hipError_t launch_act_absmax(int alg, const Geometry& g, const int8_t* x, int32_t* maxima,
+                             hipStream_t s) {
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((g.P + 255) / 256), dim3(256), 0, s, maxima, g.P, 0);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return alg == 0 ? launch_input_impl<0, 2>(g, x, nullptr, nullptr, maxima, s)
+                  : launch_input_impl<1, 2>(g, x, nullptr, nullptr, maxima, s);
+}
+
+hipError_t launch_filter_absmax(int alg, const Geometry& g, const int8_t* w, int32_t* maxima,
+                                hipStream_t s) {
+  if (alg == 0)
+    hipLaunchKernelGGL(filter_absmax_kernel<0>, dim3(g.Cout), dim3(256), 0, s, w, maxima, g);
+  else
+    hipLaunchKernelGGL(filter_absmax_kernel<1>, dim3(g.Cout), dim3(256), 0, s, w, maxima, g);
+  return hipGetLastError();
+}
+
+hipError_t launch_filter_transform(int alg, int mode, const Geometry& g, const int8_t* w,
+                                   const FilterViews& f, hipStream_t s) {
+  dim3 grid((g.Cp + 255) / 256, g.Kp);
+  dim3 block(256);
+  if (alg == 0 && mode == 1)
+    hipLaunchKernelGGL((filter_transform_kernel<0, 1>), grid, block, 0, s, w, f.U, f.inv_sw, g);
+  else if (alg == 0)
+    hipLaunchKernelGGL((filter_transform_kernel<0, 0>), grid, block, 0, s, w, f.U, f.inv_sw, g);
+  else if (mode == 1)
+    hipLaunchKernelGGL((filter_transform_kernel<1, 1>), grid, block, 0, s, w, f.U, f.inv_sw, g);
+  else
+    hipLaunchKernelGGL((filter_transform_kernel<1, 0>), grid, block, 0, s, w, f.U, f.inv_sw, g);
+  return hipGetLastError();
+}
+
+hipError_t launch_product(int mode, const Geometry& g, const void* V, const void* U, int32_t* M,
+                          hipStream_t s) {
+  const int blocks = (g.Tp / 16) * (g.Kp / 16);
+  if (mode == 1) {
+    hipLaunchKernelGGL(product_i8_kernel, dim3((blocks + 3) / 4, g.P), dim3(256), 0, s,
+                       (const int8_t*)V, (const int8_t*)U, M, g);
+  } else {
+    hipLaunchKernelGGL(product_i16_kernel, dim3(blocks, g.P), dim3(256), 0, s, (const int16_t*)V,
+                       (const int16_t*)U, M, g);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_output_transform(int alg, int mode, int out, const Geometry& g, const int32_t* M,
+                                   const FilterViews& f, float x_scale, void* y, hipStream_t s) {
+  int kx = 64;
+  while (kx > g.Kp) kx >>= 1;  // Kp is a multiple of 16
+  dim3 grid((g.T + (256 / kx) - 1) / (256 / kx), (g.Cout + kx - 1) / kx);
+  dim3 block(256);
+#define SFC_LAUNCH_OUT(A, MD, O)                                                              \
+  hipLaunchKernelGGL((output_transform_kernel<A, MD, O>), grid, block, 0, s, M, f.dequant,     \
+                     f.wscale, x_scale, y, g, kx)
+  if (alg == 0) {
+    if (mode == 1) SFC_LAUNCH_OUT(0, 1, 0);
+    else if (out == 1) SFC_LAUNCH_OUT(0, 0, 1);
+    else SFC_LAUNCH_OUT(0, 0, 0);
+  } else {
+    if (mode == 1) SFC_LAUNCH_OUT(1, 1, 0);
+    else if (out == 1) SFC_LAUNCH_OUT(1, 0, 1);
+    else SFC_LAUNCH_OUT(1, 0, 0);
+  }
+#undef SFC_LAUNCH_OUT
+  return hipGetLastError();
+}
+
+hipError_t launch_fused_product_output(int, const Geometry&, const void*, const FilterViews&, float,
+                                       float*, hipStream_t) {
+  return hipErrorNotSupported;
+}
+
+}  // namespace sfc

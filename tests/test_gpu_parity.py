@@ -1,0 +1,139 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Integer stages (V, U, M taps, exact-mode sums) must be bit-exact; the dequantized
+float32 output must be within 1e-5 of max|y_ref| of the oracle's float64 value."""
+import numpy as np
+import pytest
+
+from oracle import sfc as oracle
+from paper_2407_02913_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+F32_TOL = 1e-5
+
+SMALL_SHAPES = [  # (N, Cin, Cout, H, W)
+    (1, 16, 16, 32, 32),  # the small workload: 36 tiles, ragged (32 = 5*6 + 2)
+    (2, 3, 5, 14, 14),
+    (1, 4, 4, 7, 7),
+    (2, 2, 3, 13, 9),
+    (1, 1, 1, 1, 1),  # degenerate: one pixel, one channel
+    (1, 1, 2, 6, 6),  # exactly one full tile
+    (3, 70, 40, 9, 20),  # Cin spans two 64-channel slices, Cout not a multiple of 16
+    (5, 64, 64, 12, 18),  # 30 tiles: a ragged last 16-row block
+]
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2407_02913_amd import binding as b
+
+    b.load()
+    return b
+
+
+def uniform_case(shape, seed):
+    n, c, k, h, w = shape
+    rng = np.random.default_rng(seed)
+    x = rng.integers(-128, 128, size=(n, c, h, w)).astype(np.int8)
+    wt = rng.integers(-128, 128, size=(k, c, 3, 3)).astype(np.int8)
+    ws = rng.uniform(0.005, 0.02, size=k).astype(np.float32)
+    return x, wt, 0.02, ws
+
+
+def rel_err(y, ref):
+    return float(np.abs(y.astype(np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+@pytest.mark.parametrize("alg", ["6x6_p88", "6x6_p100"])
+@pytest.mark.parametrize("shape", SMALL_SHAPES)
+def test_exact_mode_taps_and_sums_bit_exact(binding, shape, alg):
+    x, w, xs, ws = uniform_case(shape, 100 + len(alg) + sum(shape))
+    print("case exact", shape, alg, flush=True)
+    acc_ref, taps_ref = oracle.conv_exact(x, w, alg, return_taps=True)
+    assert np.array_equal(acc_ref, oracle.direct_conv(x, w))
+    acc, taps = binding.conv2d(x, w, xs, ws, mode="exact", alg=alg, out="i32", return_taps=True)
+    for name in ("V", "U", "M"):
+        assert np.array_equal(taps[name].astype(np.int64), taps_ref[name]), name
+    assert np.array_equal(acc.astype(np.int64), acc_ref)
+    y = binding.conv2d(x, w, xs, ws, mode="exact", alg=alg, out="f32")
+    assert rel_err(y, oracle.dequantize(acc_ref, xs, ws)) <= F32_TOL
+
+
+@pytest.mark.parametrize("alg", ["6x6_p88", "6x6_p100"])
+@pytest.mark.parametrize("shape", SMALL_SHAPES)
+def test_requant_mode_taps_bit_exact_and_output_close(binding, shape, alg):
+    x, w, xs, ws = uniform_case(shape, 200 + len(alg) + sum(shape))
+    print("case requant", shape, alg, flush=True)
+    # calibrate on different data so that some values clamp
+    xc, _, _, _ = uniform_case(shape, 300 + sum(shape))
+    sx = oracle.calibrate_act_scales(xc // 2, alg)
+    sw = oracle.calibrate_filter_scales(w, alg)
+    y_ref, taps_ref = oracle.conv_requant(x, w, sx, sw, xs, ws, alg, return_taps=True)
+    y, taps = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, sx=sx, sw=sw, return_taps=True)
+    for name in ("V", "U", "M"):
+        assert np.array_equal(taps[name].astype(np.int64), taps_ref[name]), name
+    assert np.abs(taps["V"]).max() == 127  # the clamp was exercised
+    assert rel_err(y, y_ref) <= F32_TOL
+
+
+def test_single_filter_scale(binding):
+    x, w, xs, _ = uniform_case((1, 16, 16, 32, 32), 7)
+    ws = np.array([0.01], dtype=np.float32)
+    acc = binding.conv2d(x, w, xs, ws, mode="exact", out="i32")
+    assert np.array_equal(acc.astype(np.int64), oracle.direct_conv(x, w))
+    y = binding.conv2d(x, w, xs, ws, mode="exact", out="f32")
+    assert rel_err(y, oracle.dequantize(oracle.direct_conv(x, w), xs, ws)) <= F32_TOL
+
+
+@pytest.mark.parametrize("alg", ["6x6_p88", "6x6_p100"])
+def test_gpu_calibration_matches_oracle(binding, alg):
+    import torch
+
+    d = synth.make_layer(synth.LayerShape("cal", 4, 24, 20, 14, 10, "relu", True, 2))
+    plan = binding.Plan(4, 24, 20, 14, 10, alg=alg, mode="requant")
+    wbuf = binding.device_buffer(plan.workspace_bytes)
+    xd = torch.from_numpy(d["x"]).cuda()
+    wd = torch.from_numpy(d["w"]).cuda()
+    sx = plan.calibrate_act_scales(xd, wbuf)
+    sw = plan.calibrate_filter_scales(wd, wbuf)
+    assert np.array_equal(sx, oracle.calibrate_act_scales(d["x"], alg))
+    assert np.array_equal(sw, oracle.calibrate_filter_scales(d["w"], alg))
+    # fewer calibration images than the plan's batch
+    sx2 = plan.calibrate_act_scales(xd[:2].contiguous(), wbuf)
+    assert np.array_equal(sx2, oracle.calibrate_act_scales(d["x"][:2], alg))
+    plan.close()
+
+
+FULL = ["resnet56", "resnet28", "resnet14", "resnet7"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_requant_against_oracle(binding, name):
+    """The ResNet-shaped workloads at full size, staged path, every element."""
+    shape = synth.LAYERS[name]
+    print("case full", name, flush=True)
+    d = synth.make_layer(shape)
+    sx = oracle.calibrate_act_scales(d["x_calib"])
+    sw = oracle.calibrate_filter_scales(d["w"])
+    y_ref, taps_ref = oracle.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"], return_taps=True)
+    y, taps = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", sx=sx, sw=sw,
+                             return_taps=True)
+    for tap in ("V", "U", "M"):
+        assert np.array_equal(taps[tap].astype(np.int64), taps_ref[tap]), tap
+    assert rel_err(y, y_ref) <= F32_TOL
+    # the approximation itself stays close to the direct convolution
+    direct = oracle.dequantize(oracle.direct_conv(d["x"], d["w"]), d["x_scale"], d["w_scale"])
+    rms = np.sqrt(np.mean((y - direct) ** 2)) / np.sqrt(np.mean(direct**2))
+    assert rms < 0.05
+
+
+@pytest.mark.parametrize("name", ["resnet56", "resnet7"])
+def test_full_size_exact_against_direct_conv(binding, name):
+    shape = synth.LAYERS[name]
+    print("case full exact", name, flush=True)
+    d = synth.make_layer(shape)
+    ref = oracle.direct_conv(d["x"], d["w"])
+    assert np.abs(ref).max() * 36 < 2**31  # int32 sums hold for this data (Cin = 512 included)
+    acc = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="exact", out="i32")
+    assert np.array_equal(acc.astype(np.int64), ref)

@@ -1,0 +1,161 @@
+"""CPU-only tests of the HIP library's host side: it loads, exports what
+include/sfc.h declares, validates arguments without touching a GPU, and its add
+networks (compiled for the host) realize the oracle's matrices."""
+import ctypes as C
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import sfc as oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sfc.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2407_02913_amd import binding
+
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__ as entry
+
+        entry.build()
+    return binding.load()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sfc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_three_named_entry_points():
+    names = declared_functions()
+    for must in ("sfc_plan", "sfc_transform_filter", "sfc_conv2d_nchw"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    from paper_2407_02913_amd import binding
+
+    names = declared_functions()
+    assert sorted(binding.EXPORTS) == names
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    from paper_2407_02913_amd import binding
+
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    monkeypatch.setattr(binding, "_lib", None)
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        binding.load()
+
+
+def make_desc(**kw):
+    from paper_2407_02913_amd import binding
+
+    base = dict(N=2, Cin=16, Cout=24, H=14, W=9, alg=0, mode=1, out=0, path=0, per_channel_wscale=1)
+    base.update(kw)
+    return binding.ConvDesc(**base)
+
+
+def plan_status(lib, desc):
+    h = C.c_void_p()
+    st = lib.sfc_plan(C.byref(desc), C.byref(h))
+    return st, h
+
+
+def test_plan_sizes_and_counts(lib):
+    st, h = plan_status(lib, make_desc())
+    assert st == 0
+    fb, wb, p, t = C.c_size_t(), C.c_size_t(), C.c_int32(), C.c_int64()
+    assert lib.sfc_plan_sizes(h, C.byref(fb), C.byref(wb), C.byref(p), C.byref(t)) == 0
+    th, tw = oracle.tile_grid(14, 9)
+    assert p.value == oracle.multiplications_per_tile("6x6_p88") == 88
+    assert t.value == 2 * th * tw
+    tp, cp, kp = -(-t.value // 16) * 16, 64, 32
+    assert fb.value >= 88 * kp * cp + 2 * 88 * kp * 4
+    assert wb.value >= 88 * tp * cp + 88 * tp * kp * 4
+    assert lib.sfc_plan_sizes(h, None, None, None, None) == 0
+    lib.sfc_plan_destroy(h)
+    st, h = plan_status(lib, make_desc(alg=1, mode=0))
+    assert st == 0
+    assert lib.sfc_plan_sizes(h, C.byref(fb), C.byref(wb), C.byref(p), C.byref(t)) == 0
+    assert p.value == 100 and fb.value >= 100 * kp * cp * 2
+    lib.sfc_plan_destroy(h)
+
+
+@pytest.mark.parametrize(
+    "kw,code",
+    [
+        (dict(N=0), 1), (dict(Cin=-1), 1), (dict(H=0), 1), (dict(alg=7), 1), (dict(mode=2), 1),
+        (dict(out=5), 1), (dict(path=3), 1), (dict(per_channel_wscale=2), 1),
+        (dict(out=1, mode=1), 2),  # raw integer output only in exact mode
+        (dict(path=1, mode=0), 2),  # fused path is the requantized one
+        (dict(W=5000), 2),
+    ],
+)
+def test_plan_rejects_bad_descriptions(lib, kw, code):
+    st, h = plan_status(lib, make_desc(**kw))
+    assert st == code and not h.value
+
+
+def test_null_and_order_errors_without_gpu(lib):
+    assert lib.sfc_plan(None, None) == 1
+    st, h = plan_status(lib, make_desc())
+    assert st == 0
+    p = 88
+    sx = (C.c_float * p)(*([0.5] * p))
+    sw = (C.c_float * (p * 24))(*([0.25] * (p * 24)))
+    assert lib.sfc_set_point_scales(h, None, sw) == 1
+    bad = (C.c_float * p)(*([0.5] * (p - 1) + [0.0]))
+    assert lib.sfc_set_point_scales(h, bad, sw) == 1
+    nan = (C.c_float * p)(*([0.5] * (p - 1) + [float("nan")]))
+    assert lib.sfc_set_point_scales(h, nan, sw) == 1
+    assert lib.sfc_set_point_scales(h, sx, sw) == 0
+    # conv before the filter transform, and misaligned / null pointers: rejected before any launch
+    assert lib.sfc_conv2d_nchw(h, C.c_void_p(256), C.c_float(1.0), C.c_void_p(512), C.c_void_p(1024), None) == 4
+    assert lib.sfc_conv2d_nchw(h, None, C.c_float(1.0), C.c_void_p(512), C.c_void_p(1024), None) == 1
+    assert lib.sfc_conv2d_nchw(h, C.c_void_p(257), C.c_float(1.0), C.c_void_p(512), C.c_void_p(1024), None) == 1
+    assert lib.sfc_conv2d_nchw(h, C.c_void_p(256), C.c_float(-1.0), C.c_void_p(512), C.c_void_p(1024), None) == 1
+    ws = (C.c_float * 24)(*([0.01] * 24))
+    assert lib.sfc_transform_filter(h, C.c_void_p(3), ws, C.c_void_p(512), None) == 1
+    lib.sfc_plan_destroy(h)
+    # requantized mode needs its scales before the filter transform
+    st, h = plan_status(lib, make_desc())
+    assert lib.sfc_transform_filter(h, C.c_void_p(256), ws, C.c_void_p(512), None) == 4
+    lib.sfc_plan_destroy(h)
+    # exact-mode plans take no point scales
+    st, h = plan_status(lib, make_desc(mode=0))
+    assert lib.sfc_set_point_scales(h, sx, sw) == 2
+    lib.sfc_plan_destroy(h)
+    assert lib.sfc_status_string(0) == b"ok" and lib.sfc_status_string(4) == b"scales or filter not set"
+
+
+@pytest.fixture(scope="module")
+def kernel_maps(tmp_path_factory):
+    """The linear maps realized by the kernels' add networks, compiled for the host."""
+    exe = tmp_path_factory.mktemp("host") / "points_check"
+    src = os.path.join(ROOT, "tests", "host", "points_check.cpp")
+    subprocess.run(["/opt/rocm/bin/hipcc", "--cuda-host-only", "-O1", "-std=c++17", src, "-o", str(exe)],
+                   check=True, capture_output=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    maps = {}
+    for line in out.splitlines():
+        kind, alg, p, *vals = line.split()
+        maps.setdefault((kind, int(alg)), {})[int(p)] = [int(v) for v in vals]
+    return {k: np.array([v[i] for i in range(len(v))]) for k, v in maps.items()}
+
+
+@pytest.mark.parametrize("alg_id,alg", [(0, "6x6_p88"), (1, "6x6_p100")])
+def test_kernel_add_networks_realize_the_oracle_matrices(kernel_maps, alg_id, alg):
+    b2, g2, a2, den = oracle.algorithm(alg)
+    assert den == 36
+    assert np.array_equal(kernel_maps[("B", alg_id)], b2)
+    assert np.array_equal(kernel_maps[("G", alg_id)], g2)
+    assert np.array_equal(kernel_maps[("A", alg_id)], a2)
