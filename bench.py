@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Throughput of the SFC 3x3 int8 convolution hot path on one MI355X.
+
+A step is one pass of the whole hot path (input-tile transform, transform-domain
+products, output transform with dequantization and NCHW store) over one batch of
+synthetic ResNet-shaped input already resident in HBM.  The filter transform is
+done once, outside the timed region, as the paper amortizes it (Sec. 3).
+Buffers rotate over several sets so that consecutive steps do not re-hit the
+memory-side cache.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
+MFMA_I8_PEAK_TOPS = 5000.0  # dense int8
+ROTATE_BYTES = 640 << 20  # footprint of the rotating buffer sets (> 256 MB memory-side cache)
+
+
+def stage_bytes(shape, P, tiles, path):
+    """Algorithmic bytes per launch of each kernel (requantized mode)."""
+    x = shape.N * shape.Cin * shape.H * shape.W
+    v = P * tiles * shape.Cin
+    u = P * shape.Cout * shape.Cin
+    m = 4 * P * tiles * shape.Cout
+    y = 4 * shape.N * shape.Cout * shape.H * shape.W
+    if path == "fused":
+        return {"input_transform": x + v, "fused_product_output": v + u + y}
+    return {"input_transform": x + v, "product": v + u + m, "output_transform": m + y}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet56")
+    ap.add_argument("--path", default=None, choices=[None, "staged", "fused"])
+    ap.add_argument("--alg", default="6x6_p88")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the layer shards over "
+              "the batch with no exchange step); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2407_02913_amd import binding, synth
+
+    binding.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    shape = synth.LAYERS[args.workload]
+    data = synth.make_layer(shape)
+    path = args.path or binding.DEFAULT_PATH
+
+    plan = binding.Plan(shape.N, shape.Cin, shape.Cout, shape.H, shape.W, alg=args.alg,
+                        mode="requant", path=path, per_channel_wscale=shape.per_channel_wscale)
+    x_host = torch.from_numpy(data["x"])
+    w_dev = torch.from_numpy(data["w"]).cuda()
+    xc_dev = torch.from_numpy(data["x_calib"]).cuda()
+    fbuf = binding.device_buffer(plan.filter_bytes)
+    # scales from the library's own abs-max calibration (no oracle on the product path)
+    scratch = binding.device_buffer(plan.workspace_bytes)
+    sx = plan.calibrate_act_scales(xc_dev, scratch)
+    sw = plan.calibrate_filter_scales(w_dev, scratch)
+    plan.set_point_scales(sx, sw)
+    plan.transform_filter(w_dev, data["w_scale"], fbuf)
+    del scratch
+
+    ybytes = 4 * shape.N * shape.Cout * shape.H * shape.W
+    per_set = x_host.numel() + plan.workspace_bytes + ybytes
+    nsets = max(2, min(24, -(-ROTATE_BYTES // per_set)))
+    sets = []
+    for _ in range(nsets):
+        sets.append((x_host.cuda(), binding.device_buffer(plan.workspace_bytes),
+                     torch.empty((shape.N, shape.Cout, shape.H, shape.W), dtype=torch.float32,
+                                 device="cuda")))
+    xs = float(data["x_scale"])
+
+    def step(i, mask=binding.STAGE_ALL):
+        xd, ws, y = sets[i % nsets]
+        plan.conv2d_stages(xd, xs, y, ws, mask)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+
+    # per-kernel durations: each stage alone, back to back, over the rotating sets
+    # (every set already holds valid V / M from the full passes above)
+    if path == "fused":
+        stages = {"input_transform": binding.STAGE_INPUT,
+                  "fused_product_output": binding.STAGE_PRODUCT | binding.STAGE_OUTPUT}
+    else:
+        stages = {"input_transform": binding.STAGE_INPUT, "product": binding.STAGE_PRODUCT,
+                  "output_transform": binding.STAGE_OUTPUT}
+    launches = max(50, min(args.steps, 400))
+    stage_us = {}
+    for name, mask in stages.items():
+        for i in range(10):
+            step(i, mask)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(launches):
+            step(i, mask)
+        e1.record()
+        torch.cuda.synchronize()
+        stage_us[name] = e0.elapsed_time(e1) * 1e3 / launches
+    bytes_per = stage_bytes(shape, plan.P, plan.tiles, path)
+    dominant = max(stage_us, key=stage_us.get)
+    achieved = bytes_per[dominant] / (stage_us[dominant] * 1e-6) / 1e9
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"traffic_{dominant}_{args.workload}.txt")
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("hbm_bytes_per_launch"):
+                traffic = float(line.split()[1])
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": traffic, "algorithmic_bytes": bytes_per[dominant],
+                "avg_us": round(stage_us[dominant], 2),
+                "stages_us": {k: round(v, 2) for k, v in stage_us.items()},
+                "stages_gbs": {k: round(bytes_per[k] / (stage_us[k] * 1e-6) / 1e9, 1) for k in stage_us}}
+    sfc_ops = 2 * plan.P * plan.tiles * shape.Cin * shape.Cout
+    prod_key = "fused_product_output" if path == "fused" else "product"
+    roofline["product_mfma_frac"] = round(sfc_ops / (stage_us[prod_key] * 1e-6) / 1e12 / MFMA_I8_PEAK_TOPS, 4)
+
+    tops = shape.direct_ops / (ms_per_step * 1e-3) / 1e12
+    out = {
+        "metric": "direct-conv-equivalent int8 TOPS per 3x3 layer",
+        "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: N={shape.N} Cin=Cout={shape.Cin} H=W={shape.H} 3x3 s1 p1",
+                   "algorithm": f"SFC-6(6x6,3x3) P={plan.P}", "mode": "requant-int8 transform domain",
+                   "path": path, "buffer_sets": nsets, "host_ms_per_step": round(wall_ms, 5)},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import sfc as oracle  # the cpu_baseline leg is the only user of the oracle here
+
+        try:
+            from threadpoolctl import threadpool_info
+
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        # bounded sample: whole passes over the same batch until about 10 s have gone by
+        passes, t0 = 0, time.perf_counter()
+        while True:
+            oracle.conv_requant(data["x"], data["w"], sx, sw, data["x_scale"], data["w_scale"], args.alg)
+            passes += 1
+            dt = time.perf_counter() - t0
+            if dt >= 10.0 or passes >= 50:
+                break
+        out["cpu_baseline"] = {"value": round(passes * shape.direct_ops / dt / 1e12, 5), "unit": "TOPS",
+                               "cores": int(cores), "kind": "oracle",
+                               "sample": f"oracle.conv_requant on the full {args.workload} batch "
+                                         f"(N={shape.N}), {passes} passes in {dt:.1f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

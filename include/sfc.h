@@ -134,6 +134,15 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
 sfc_status sfc_conv2d_nchw(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale, void* y_dev,
                            void* workspace_dev, void* stream);
 
+/* Profiling aid: the same work as sfc_conv2d_nchw restricted to the stages in
+ * stage_mask, so that one stage can be timed alone on buffers a full call has
+ * filled.  SFC_STAGE_INPUT: V = B^T x B.  SFC_STAGE_PRODUCT: M = V.U (staged path).
+ * SFC_STAGE_OUTPUT: y from M (staged path); on the fused path SFC_STAGE_PRODUCT |
+ * SFC_STAGE_OUTPUT must be given together and run the one fused kernel. */
+enum { SFC_STAGE_INPUT = 1, SFC_STAGE_PRODUCT = 2, SFC_STAGE_OUTPUT = 4, SFC_STAGE_ALL = 7 };
+sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale,
+                             void* y_dev, void* workspace_dev, void* stream, int32_t stage_mask);
+
 /* Where the intermediate tensors of the last staged call live, for parity checks.
  * which: 0 = V [P][tiles][Cin], 1 = U [P][Cout][Cin], 2 = M [P][tiles][Cout] (int32).
  * ptr receives a device address inside workspace_dev (V, M) or the filter buffer

@@ -21,12 +21,15 @@ ALG = {"6x6_p88": 0, "6x6_p100": 1}
 MODE = {"exact": 0, "requant": 1}
 OUT = {"f32": 0, "i32": 1}
 PATH = {"staged": 0, "fused": 1}
+STAGE_INPUT, STAGE_PRODUCT, STAGE_OUTPUT, STAGE_ALL = 1, 2, 4, 7
+#: the path bench.py and callers get when they do not ask for one
+DEFAULT_PATH = "staged"
 
 #: every symbol include/sfc.h declares
 EXPORTS = (
     "sfc_plan", "sfc_plan_destroy", "sfc_plan_sizes", "sfc_set_point_scales",
     "sfc_calibrate_act_scales", "sfc_calibrate_filter_scales", "sfc_transform_filter",
-    "sfc_conv2d_nchw", "sfc_tap_info", "sfc_status_string",
+    "sfc_conv2d_nchw", "sfc_conv2d_stages", "sfc_tap_info", "sfc_status_string",
 )
 
 
@@ -73,6 +76,8 @@ def load(force: bool = False):
     lib.sfc_transform_filter.restype = i32
     lib.sfc_conv2d_nchw.argtypes = [vp, vp, f32, vp, vp, vp]
     lib.sfc_conv2d_nchw.restype = i32
+    lib.sfc_conv2d_stages.argtypes = [vp, vp, f32, vp, vp, vp, i32]
+    lib.sfc_conv2d_stages.restype = i32
     lib.sfc_tap_info.argtypes = [vp, vp, i32, C.POINTER(vp), C.POINTER(i32),
                                  C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.sfc_tap_info.restype = i32
@@ -165,6 +170,12 @@ class Plan:
                                       C.c_void_p(y_dev.data_ptr()),
                                       C.c_void_p(workspace.data_ptr()), _stream_ptr(stream)),
                "sfc_conv2d_nchw")
+
+    def conv2d_stages(self, x_dev, x_scale: float, y_dev, workspace, mask: int, stream=None):
+        _check(load().sfc_conv2d_stages(self._h, C.c_void_p(x_dev.data_ptr()), C.c_float(x_scale),
+                                        C.c_void_p(y_dev.data_ptr()),
+                                        C.c_void_p(workspace.data_ptr()), _stream_ptr(stream),
+                                        int(mask)), "sfc_conv2d_stages")
 
     def tap(self, which: str, workspace) -> np.ndarray:
         """Copy of V, U or M in canonical [P][tiles|Cout][Cin|Cout] order (synchronizes)."""

@@ -170,11 +170,11 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
   } catch (...) {
     return SFC_ENOMEM;
   }
-  char* base = reinterpret_cast<char*>(plan->staging.data()) - plan->off_dequant;
-  float* dequant = reinterpret_cast<float*>(base + plan->off_dequant);
-  float* inv_sw = reinterpret_cast<float*>(base + plan->off_inv_sw);
-  float* inv_sx = reinterpret_cast<float*>(base + plan->off_inv_sx);
-  float* wscale = reinterpret_cast<float*>(base + plan->off_wscale);
+  auto table = [&](size_t off) { return plan->staging.data() + (off - plan->off_dequant) / sizeof(float); };
+  float* dequant = table(plan->off_dequant);
+  float* inv_sw = table(plan->off_inv_sw);
+  float* inv_sx = table(plan->off_inv_sx);
+  float* wscale = table(plan->off_wscale);
   for (int k = 0; k < g.Kp; ++k)
     wscale[k] = k < g.Cout ? wscale_host[plan->d.per_channel_wscale ? k : 0] : 0.0f;
   for (int p = 0; p < g.P; ++p) {
@@ -202,32 +202,47 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
   return SFC_OK;
 }
 
-sfc_status sfc_conv2d_nchw(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale, void* y_dev,
-                           void* workspace_dev, void* stream) {
+sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale,
+                             void* y_dev, void* workspace_dev, void* stream, int32_t stage_mask) {
   if (!plan || !x_dev || !y_dev || !workspace_dev) return SFC_EINVAL;
   if (!aligned16(x_dev) || !aligned16(y_dev) || !aligned16(workspace_dev)) return SFC_EINVAL;
   if (!(x_scale > 0.0f) || !std::isfinite(x_scale)) return SFC_EINVAL;
+  if (stage_mask <= 0 || stage_mask > SFC_STAGE_ALL) return SFC_EINVAL;
   if (!plan->filter_ready) return SFC_ENOTREADY;
+  const bool fused = plan->d.path == SFC_PATH_FUSED;
+  const int tail = stage_mask & (SFC_STAGE_PRODUCT | SFC_STAGE_OUTPUT);
+  if (fused && tail != 0 && tail != (SFC_STAGE_PRODUCT | SFC_STAGE_OUTPUT)) return SFC_EINVAL;
   const Geometry& g = plan->g;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const FilterViews f = views(plan, plan->filter_dev);
   char* ws = static_cast<char*>(workspace_dev);
   void* V = ws + plan->off_V;
-  if (sfc::launch_input_transform(plan->d.alg, plan->d.mode, g, x_dev, V, f.inv_sx, s) !=
-      hipSuccess)
-    return SFC_EHIP;
-  if (plan->d.path == SFC_PATH_FUSED) {
-    if (sfc::launch_fused_product_output(plan->d.alg, g, V, f, x_scale,
-                                         static_cast<float*>(y_dev), s) != hipSuccess)
+  if (stage_mask & SFC_STAGE_INPUT) {
+    if (sfc::launch_input_transform(plan->d.alg, plan->d.mode, g, x_dev, V, f.inv_sx, s) !=
+        hipSuccess)
+      return SFC_EHIP;
+  }
+  if (fused) {
+    if (tail && sfc::launch_fused_product_output(plan->d.alg, g, V, f, x_scale,
+                                                 static_cast<float*>(y_dev), s) != hipSuccess)
       return SFC_EHIP;
     return SFC_OK;
   }
   int32_t* M = reinterpret_cast<int32_t*>(ws + plan->off_M);
-  if (sfc::launch_product(plan->d.mode, g, V, f.U, M, s) != hipSuccess) return SFC_EHIP;
-  if (sfc::launch_output_transform(plan->d.alg, plan->d.mode, plan->d.out, g, M, f, x_scale, y_dev,
-                                   s) != hipSuccess)
-    return SFC_EHIP;
+  if (stage_mask & SFC_STAGE_PRODUCT) {
+    if (sfc::launch_product(plan->d.mode, g, V, f.U, M, s) != hipSuccess) return SFC_EHIP;
+  }
+  if (stage_mask & SFC_STAGE_OUTPUT) {
+    if (sfc::launch_output_transform(plan->d.alg, plan->d.mode, plan->d.out, g, M, f, x_scale,
+                                     y_dev, s) != hipSuccess)
+      return SFC_EHIP;
+  }
   return SFC_OK;
+}
+
+sfc_status sfc_conv2d_nchw(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale, void* y_dev,
+                           void* workspace_dev, void* stream) {
+  return sfc_conv2d_stages(plan, x_dev, x_scale, y_dev, workspace_dev, stream, SFC_STAGE_ALL);
 }
 
 sfc_status sfc_tap_info(const sfc_plan_t* plan, const void* workspace_dev, int32_t which,
