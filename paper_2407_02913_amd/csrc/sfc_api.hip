@@ -89,6 +89,8 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   g.Kp = (d.Cout + 15) / 16 * 16;
   g.P = d.alg == SFC_ALG_6X6_P88 ? 88 : 100;
 
+  if (d.path == SFC_PATH_FUSED && !sfc::fused_supported(g)) return SFC_EUNSUPPORTED;
+
   sfc_plan_s* p = new (std::nothrow) sfc_plan_s();
   if (!p) return SFC_ENOMEM;
   p->d = d;

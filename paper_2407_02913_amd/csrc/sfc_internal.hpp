@@ -38,6 +38,8 @@ hipError_t launch_output_transform(int alg, int mode, int out, const Geometry& g
 hipError_t launch_fused_product_output(int alg, const Geometry& g, const void* V,
                                        const FilterViews& f, float x_scale, float* y,
                                        hipStream_t s);
+// whether the fused kernel covers this geometry (Cin padded to 64, 128, 256 or 512)
+bool fused_supported(const Geometry& g);
 // abs-max calibration: maxima are int32, zeroed by the launcher
 hipError_t launch_act_absmax(int alg, const Geometry& g, const int8_t* x, int32_t* maxima /*[P]*/,
                              hipStream_t s);

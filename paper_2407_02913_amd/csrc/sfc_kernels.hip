@@ -451,9 +451,4 @@ hipError_t launch_output_transform(int alg, int mode, int out, const Geometry& g
   return hipGetLastError();
 }
 
-hipError_t launch_fused_product_output(int, const Geometry&, const void*, const FilterViews&, float,
-                                       float*, hipStream_t) {
-  return hipErrorNotSupported;
-}
-
 }  // namespace sfc

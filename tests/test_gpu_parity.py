@@ -137,3 +137,56 @@ def test_full_size_exact_against_direct_conv(binding, name):
     assert np.abs(ref).max() * 36 < 2**31  # int32 sums hold for this data (Cin = 512 included)
     acc = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="exact", out="i32")
     assert np.array_equal(acc.astype(np.int64), ref)
+
+
+# ---- fused path: products never leave the chip, so only V, U and y can be compared ----
+
+FUSED_SHAPES = [
+    (1, 16, 16, 32, 32),
+    (2, 3, 5, 14, 14),
+    (1, 4, 4, 7, 7),  # odd W: scalar stores
+    (2, 2, 3, 13, 9),
+    (1, 1, 1, 1, 1),
+    (3, 70, 40, 9, 20),  # two 64-channel chunks, Cout 40: a partly idle wave
+    (5, 64, 64, 12, 18),  # 30 tiles: padding rows in the last block
+    (2, 200, 72, 11, 7),  # four chunks (Cin padded to 256), two workgroups along Cout
+    (1, 500, 24, 8, 8),  # eight chunks
+]
+
+
+@pytest.mark.parametrize("alg", ["6x6_p88", "6x6_p100"])
+@pytest.mark.parametrize("shape", FUSED_SHAPES)
+def test_fused_path_matches_oracle(binding, shape, alg):
+    x, w, xs, ws = uniform_case(shape, 400 + len(alg) + sum(shape))
+    print("case fused", shape, alg, flush=True)
+    xc, _, _, _ = uniform_case(shape, 500 + sum(shape))
+    sx = oracle.calibrate_act_scales(xc // 2, alg)
+    sw = oracle.calibrate_filter_scales(w, alg)
+    y_ref, taps_ref = oracle.conv_requant(x, w, sx, sw, xs, ws, alg, return_taps=True)
+    y, taps = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path="fused", sx=sx, sw=sw,
+                             return_taps=True)
+    for name in ("V", "U"):
+        assert np.array_equal(taps[name].astype(np.int64), taps_ref[name]), name
+    assert rel_err(y, y_ref) <= F32_TOL
+    # and it agrees with the staged path of the same library to float32 rounding
+    y_staged = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path="staged", sx=sx, sw=sw)
+    assert rel_err(y, y_staged.astype(np.float64)) <= F32_TOL
+
+
+def test_fused_path_rejects_unsupported_channel_counts(binding):
+    with pytest.raises(binding.SfcError) as e:
+        binding.Plan(1, 3 * 64, 16, 8, 8, path="fused")  # three chunks
+    assert e.value.code == 2
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_fused_against_oracle(binding, name):
+    """The launch configuration bench.py times, every output element."""
+    shape = synth.LAYERS[name]
+    print("case full fused", name, flush=True)
+    d = synth.make_layer(shape)
+    sx = oracle.calibrate_act_scales(d["x_calib"])
+    sw = oracle.calibrate_filter_scales(d["w"])
+    y_ref = oracle.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"])
+    y = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", path="fused", sx=sx, sw=sw)
+    assert rel_err(y, y_ref) <= F32_TOL
