@@ -69,10 +69,11 @@ struct Order {
   }
 };
 
-constexpr int kRing = 8;        // operand slots in flight (64-channel chunks)
+constexpr int kRing = 8;          // operand slots in flight (64-channel chunks)
+constexpr int kBufferFlags = 0x00020000;  // raw buffer descriptor word 3: 32-bit data format
 constexpr int kStageStride = 98;  // floats per filter row of the staging block (16 tiles x 6 + 2)
 
-template <int ALG, int KC>
+template <int ALG, int KC, bool VEC2>
 __global__ __launch_bounds__(256) void fused_product_output_kernel(
     const int8_t* __restrict__ V, const int8_t* __restrict__ U, const float* __restrict__ dequant,
     float x_scale, float* __restrict__ y, Geometry g) {
@@ -81,19 +82,20 @@ __global__ __launch_bounds__(256) void fused_product_output_kernel(
   constexpr int NS = P * KC;  // chunk steps
 
   __shared__ __align__(16) float stage[4][16 * kStageStride];
-  __shared__ int tile_off[16];   // y offset of the tile's first output, -1: padding row
-  __shared__ int tile_ext[16];   // valid rows | valid cols << 8
+  __shared__ float dq_lds[P][64];  // dequantization factors of this workgroup's 64 filters
+  __shared__ int tile_off[16];     // y offset of the tile's first output
+  __shared__ int tile_ext[16];     // valid rows | valid cols << 8 (0: padding row)
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int t0 = blockIdx.x * 16;
   const int kb = blockIdx.y * 4 + wave;
   const bool active = kb * 16 < g.Kp;
-  const int k = kb * 16 + (lane & 15);
+  const int k = active ? kb * 16 + (lane & 15) : 0;
 
   if (threadIdx.x < 16) {
     const int t = t0 + threadIdx.x;
-    int off = -1, ext = 0;
+    int off = 0, ext = 0;
     if (t < g.T) {
       const int per = g.th * g.tw;
       const int n = t / per, rem = t - n * per;
@@ -105,22 +107,36 @@ __global__ __launch_bounds__(256) void fused_product_output_kernel(
     tile_off[threadIdx.x] = off;
     tile_ext[threadIdx.x] = ext;
   }
+  {
+    // all loads in flight at once: P is a multiple of 4
+    const int kk = blockIdx.y * 64 + (threadIdx.x & 63);
+    float tmp[P / 4];
+#pragma unroll
+    for (int i = 0; i < P / 4; ++i)
+      tmp[i] = kk < g.Kp ? dequant[(size_t)(4 * i + wave) * g.Kp + kk] : 0.0f;
+#pragma unroll
+    for (int i = 0; i < P / 4; ++i) dq_lds[4 * i + wave][threadIdx.x & 63] = tmp[i];
+  }
   __syncthreads();
 
-  const size_t vstride = (size_t)g.Tp * g.Cp;  // per point
-  const size_t ustride = (size_t)g.Kp * g.Cp;
-  const int8_t* a_base = V + (size_t)(t0 + (lane & 15)) * g.Cp + (lane >> 4) * 16;
-  const int8_t* b_base = U + (size_t)(active ? k : 0) * g.Cp + (lane >> 4) * 16;
-  const float* d_base = dequant + (active ? k : 0);
+  // buffer addressing: one 32-bit lane offset per operand, the point's plane and
+  // the channel chunk go into the scalar offset, so a load costs no vector ALU work
+  const unsigned vstride = (unsigned)g.Tp * g.Cp;
+  const unsigned ustride = (unsigned)g.Kp * g.Cp;
+  const unsigned aoff = (unsigned)(t0 + (lane & 15)) * g.Cp + (lane >> 4) * 16;
+  const unsigned boff = (unsigned)k * g.Cp + (lane >> 4) * 16;
+  const float* dq_lane = &dq_lds[0][wave * 16 + (lane & 15)];
+  const __amdgpu_buffer_rsrc_t vres =
+      __builtin_amdgcn_make_buffer_rsrc((void*)V, 0, (int)(vstride * (unsigned)P), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t ures =
+      __builtin_amdgcn_make_buffer_rsrc((void*)U, 0, (int)(ustride * (unsigned)P), kBufferFlags);
 
   v4i a[kRing], b[kRing];
-  float dq[kRing];
   auto load_chunk = [&](int s) {  // s is a compile-time constant at every call site
     const int q = s / KC, kc = s % KC;
     const int p = order.pt[q];
-    a[s % kRing] = *(const v4i*)(a_base + p * vstride + kc * 64);
-    b[s % kRing] = *(const v4i*)(b_base + p * ustride + kc * 64);
-    if (kc == 0) dq[q % kRing] = d_base[(size_t)p * g.Kp];
+    a[s % kRing] = __builtin_amdgcn_raw_buffer_load_b128(vres, aoff, p * vstride + kc * 64, 0);
+    b[s % kRing] = __builtin_amdgcn_raw_buffer_load_b128(ures, boff, p * ustride + kc * 64, 0);
   };
 #pragma unroll
   for (int s = 0; s < kRing && s < NS; ++s) load_chunk(s);
@@ -129,7 +145,7 @@ __global__ __launch_bounds__(256) void fused_product_output_kernel(
   v4i pending = {0, 0, 0, 0};
   float pending_d = 0.0f;
   auto issue = [&](int qq) {  // MFMA chain of point qq, refilling the ring behind it
-    pending_d = dq[qq % kRing];  // read before the slot is refilled below
+    pending_d = dq_lane[order.pt[qq] * 64];
     v4i acc = {0, 0, 0, 0};
 #pragma unroll
     for (int kc = 0; kc < KC; ++kc) {
@@ -194,7 +210,30 @@ __global__ __launch_bounds__(256) void fused_product_output_kernel(
     inv8(c1, z[2 + 2 * g2]);
   }
 
+  // ---- store plan: which staged values this lane writes, fixed over the six rows ----
+  // VEC2: 16 filters x 48 float pairs per row phase, lanes contiguous along (tile, o2);
+  // otherwise 16 x 96 single floats.
+  constexpr int SLOTS = VEC2 ? 12 : 24;
+  unsigned yo[SLOTS];  // byte offset into y of output row 0
+  int rows[SLOTS];     // valid output rows for this slot (0: nothing to store)
+  int rd[SLOTS];       // staging index
+#pragma unroll
+  for (int i = 0; i < SLOTS; ++i) {
+    const int e = i * 64 + lane;
+    constexpr int per_k = VEC2 ? 48 : 96, per_t = VEC2 ? 3 : 6, step = VEC2 ? 2 : 1;
+    const int kk = e / per_k, r = e - kk * per_k;
+    const int tl = r / per_t, o2 = step * (r - tl * per_t);
+    const int kcol = kb * 16 + kk;
+    const int ext = tile_ext[tl];
+    const bool ok = active && kcol < g.Cout && o2 < (ext >> 8);
+    rows[i] = ok ? (ext & 0xff) : 0;
+    yo[i] = 4u * ((unsigned)tile_off[tl] + (unsigned)(kcol * g.H) * g.W + o2);
+    rd[i] = kk * kStageStride + tl * 6 + o2;
+  }
+
   // ---- inverse along the horizontal axis, one output row per phase ----------
+  const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)y, 0, (int)(4u * (unsigned)(g.N * g.Cout) * (unsigned)(g.H * g.W)), kBufferFlags);
   float* st = stage[wave];
   const int wr_base = (lane & 15) * kStageStride + (lane >> 4) * 24;  // + j*6 + o2
 #pragma unroll
@@ -203,86 +242,294 @@ __global__ __launch_bounds__(256) void fused_product_output_kernel(
 #pragma unroll
     for (int bb = 0; bb < 8; ++bb) zc[bb] = z[bb][o1];
     inv8(zc, out);
-    if (active) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int o2 = 0; o2 < 6; o2 += 2) {
-          v2f pr = {out[o2][j] * x_scale, out[o2 + 1][j] * x_scale};
-          *(v2f*)(st + wr_base + j * 6 + o2) = pr;
-        }
-    }
+      for (int o2 = 0; o2 < 6; o2 += 2) {
+        v2f pr = {out[o2][j] * x_scale, out[o2 + 1][j] * x_scale};
+        *(v2f*)(st + wr_base + j * 6 + o2) = pr;
+      }
     __syncthreads();
-    if (active) {
-      // 16 filters x 48 float pairs, lanes contiguous along (tile, o2)
+    const unsigned yrow = 4u * (unsigned)(o1 * g.W);
 #pragma unroll
-      for (int i = 0; i < 12; ++i) {
-        const int e = i * 64 + lane;
-        const int kk = e / 48, r = e - kk * 48;
-        const int tl = r / 3, o2 = 2 * (r - tl * 3);
-        const int kcol = kb * 16 + kk;
-        const int off = tile_off[tl], ext = tile_ext[tl];
-        const v2f val = *(const v2f*)(st + kk * kStageStride + tl * 6 + o2);
-        if (off >= 0 && kcol < g.Cout && o1 < (ext & 0xff)) {
-          const int cols = ext >> 8;
-          float* dst = y + (size_t)off + ((size_t)kcol * g.H + o1) * g.W + o2;
-          if (o2 + 1 < cols) {
-            if ((g.W & 1) == 0) {
-              *(v2f*)dst = val;
-            } else {
-              dst[0] = val.x;
-              dst[1] = val.y;
-            }
-          } else if (o2 < cols) {
-            dst[0] = val.x;
-          }
-        }
+    for (int i = 0; i < SLOTS; ++i) {
+      if constexpr (VEC2) {
+        const v2f val = *(const v2f*)(st + rd[i]);
+        if (o1 < rows[i]) __builtin_amdgcn_raw_buffer_store_b64(val, yres, yo[i], yrow, 0);
+      } else {
+        const float val = st[rd[i]];
+        if (o1 < rows[i])
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), yres, yo[i], yrow, 0);
       }
     }
     __syncthreads();
   }
 }
 
-template <int ALG>
+// ---------------------------------------------------------------------------
+// Variant B: the same block of 16 tiles x 16 filters is owned by a whole workgroup
+// of four waves.  In round r wave w runs the MFMA chain of point 4r + w, scales
+// the sums and leaves them in LDS in the MFMA's own layout; after one barrier
+// every thread reads the four values of its single (tile, filter) pair and
+// feeds the output transform.  One pair per thread keeps the register count low
+// enough for several waves per SIMD, which hides the operand-load latency and
+// staggers the final stores of different workgroups.
+// ---------------------------------------------------------------------------
+template <int ALG, int KC, bool VEC2>
+__global__ __launch_bounds__(256, 4) void fused_product_output_kernel_b(
+    const int8_t* __restrict__ V, const int8_t* __restrict__ U, const float* __restrict__ dequant,
+    float x_scale, float* __restrict__ y, Geometry g) {
+  constexpr int P = AlgTraits<ALG>::P;
+  constexpr Order<ALG> order{};
+  constexpr int ROUNDS = P / 4;
+  constexpr int NS = ROUNDS * KC;  // chunk steps of one wave
+
+  __shared__ __align__(16) float mx[2][4][256];  // [buffer][point of the round][MFMA layout]
+  __shared__ __align__(16) float stage[16 * kStageStride];
+  __shared__ float dq_lds[P][16];
+  __shared__ int tile_off[16];
+  __shared__ int tile_ext[16];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int t0 = blockIdx.x * 16;
+  const int kb = blockIdx.y;
+  const int kcol = kb * 16 + (lane & 15);  // < Kp
+
+  if (threadIdx.x < 16) {
+    const int t = t0 + threadIdx.x;
+    int off = 0, ext = 0;
+    if (t < g.T) {
+      const int per = g.th * g.tw;
+      const int n = t / per, rem = t - n * per;
+      const int ti = rem / g.tw, tj = rem - ti * g.tw;
+      off = ((n * g.Cout) * g.H + 6 * ti) * g.W + 6 * tj;
+      const int rows = min(6, g.H - 6 * ti), cols = min(6, g.W - 6 * tj);
+      ext = rows | (cols << 8);
+    }
+    tile_off[threadIdx.x] = off;
+    tile_ext[threadIdx.x] = ext;
+  }
+  {
+    constexpr int PER = (P * 16 + 255) / 256;
+    float tmp[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int e = i * 256 + threadIdx.x;
+      tmp[i] = e < P * 16 ? dequant[(size_t)(e >> 4) * g.Kp + kb * 16 + (e & 15)] : 0.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int e = i * 256 + threadIdx.x;
+      if (e < P * 16) dq_lds[e >> 4][e & 15] = tmp[i];
+    }
+  }
+
+  const unsigned vstride = (unsigned)g.Tp * g.Cp;
+  const unsigned ustride = (unsigned)g.Kp * g.Cp;
+  const unsigned aoff = (unsigned)(t0 + (lane & 15)) * g.Cp + (lane >> 4) * 16;
+  const unsigned boff = (unsigned)kcol * g.Cp + (lane >> 4) * 16;
+  const __amdgpu_buffer_rsrc_t vres =
+      __builtin_amdgcn_make_buffer_rsrc((void*)V, 0, (int)(vstride * (unsigned)P), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t ures =
+      __builtin_amdgcn_make_buffer_rsrc((void*)U, 0, (int)(ustride * (unsigned)P), kBufferFlags);
+
+  // operand ring of this wave: chunk step s = r*KC + kc of its own point 4r + wave.
+  // The point index depends on the wave, so the plane offset is a table lookup
+  // made uniform with readfirstlane.
+  __shared__ int pt_lds[P];
+  if (threadIdx.x < P) {
+    int v = 0;
+#pragma unroll
+    for (int i = 0; i < P; ++i)
+      if (i == (int)threadIdx.x) v = order.pt[i];
+    pt_lds[threadIdx.x] = v;
+  }
+  __syncthreads();
+
+  v4i a[kRing], b[kRing];
+  auto point_of = [&](int r) { return __builtin_amdgcn_readfirstlane(pt_lds[4 * r + wave]); };
+  auto load_chunk = [&](int s) {
+    const int r = s / KC, kc = s % KC;
+    const int p = point_of(r);
+    a[s % kRing] = __builtin_amdgcn_raw_buffer_load_b128(vres, aoff, p * vstride + kc * 64, 0);
+    b[s % kRing] = __builtin_amdgcn_raw_buffer_load_b128(ures, boff, p * ustride + kc * 64, 0);
+  };
+#pragma unroll
+  for (int s = 0; s < kRing && s < NS; ++s) load_chunk(s);
+
+  auto mfma_round = [&](int r) {
+    v4i acc = {0, 0, 0, 0};
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+      const int s = r * KC + kc;
+      acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[s % kRing], b[s % kRing], acc, 0, 0, 0);
+      if (s + kRing < NS) load_chunk(s + kRing);
+    }
+    return acc;
+  };
+  auto publish = [&](int r, v4i acc) {
+    const float d = dq_lds[point_of(r)][lane & 15];
+    const v4f m = {(float)acc.x * d, (float)acc.y * d, (float)acc.z * d, (float)acc.w * d};
+    *(v4f*)(&mx[r & 1][wave][lane * 4]) = m;
+  };
+
+  publish(0, mfma_round(0));
+  __syncthreads();
+
+  // consumer side: this thread's pair is tile row 4*wave + lane/16, filter lane%16
+  const int rd_idx = (wave * 16 + (lane & 15)) * 4 + (lane >> 4);
+  int q = 0;  // folds to a constant
+  float cur[4];
+  v4i acc_next = {0, 0, 0, 0};
+  auto next = [&]() -> float {
+    const int r = q >> 2, i = q & 3;
+    if (i == 0) {
+      if (r + 1 < ROUNDS) acc_next = mfma_round(r + 1);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) cur[j] = mx[r & 1][j][rd_idx];
+    }
+    const float v = cur[i];
+    if (i == 3) {
+      if (r + 1 < ROUNDS) publish(r + 1, acc_next);
+      __syncthreads();
+    }
+    ++q;
+    return v;
+  };
+
+  float z[8][6];
+  constexpr int real_comp[4] = {0, 5, 6, 7};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float col[10], cc[8];
+#pragma unroll
+    for (int r1 = 0; r1 < 10; ++r1) col[r1] = next();
+    collapse10(col, cc);
+    inv8(cc, z[real_comp[j]]);
+  }
+#pragma unroll
+  for (int g2 = 0; g2 < 2; ++g2) {
+    float c0[8], c1[8];
+    if constexpr (ALG == 1) {
+      float h0[10], h1[10];
+#pragma unroll
+      for (int r1 = 0; r1 < 10; ++r1) {
+        const float m0 = next(), m1 = next(), m2 = next();
+        h0[r1] = m0 - m1;
+        h1[r1] = m2 - m0;
+      }
+      collapse10(h0, c0);
+      collapse10(h1, c1);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float m0 = next(), m1 = next(), m2 = next();
+        c0[real_comp[j]] = m0 - m1;
+        c1[real_comp[j]] = m2 - m0;
+      }
+#pragma unroll
+      for (int g1 = 0; g1 < 2; ++g1) {
+        float m[6];
+#pragma unroll
+        for (int i = 0; i < 6; ++i) m[i] = next();
+        hermitian_collapse(m, c0[1 + 2 * g1], c0[2 + 2 * g1], c1[1 + 2 * g1], c1[2 + 2 * g1]);
+      }
+    }
+    inv8(c0, z[1 + 2 * g2]);
+    inv8(c1, z[2 + 2 * g2]);
+  }
+
+  // ---- store plan: 16 filters x 48 float pairs (or 96 floats) over 256 threads ----
+  constexpr int SLOTS = VEC2 ? 3 : 6;
+  unsigned yo[SLOTS];
+  int rows[SLOTS];
+  int rd[SLOTS];
+#pragma unroll
+  for (int i = 0; i < SLOTS; ++i) {
+    const int e = i * 256 + threadIdx.x;
+    constexpr int per_k = VEC2 ? 48 : 96, per_t = VEC2 ? 3 : 6, step = VEC2 ? 2 : 1;
+    const int kk = e / per_k, r = e - kk * per_k;
+    const int tl = r / per_t, o2 = step * (r - tl * per_t);
+    const int kc2 = kb * 16 + kk;
+    const int ext = tile_ext[tl];
+    const bool ok = kc2 < g.Cout && o2 < (ext >> 8);
+    rows[i] = ok ? (ext & 0xff) : 0;
+    yo[i] = 4u * ((unsigned)tile_off[tl] + (unsigned)(kc2 * g.H) * g.W + o2);
+    rd[i] = kk * kStageStride + tl * 6 + o2;
+  }
+  const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)y, 0, (int)(4u * (unsigned)(g.N * g.Cout) * (unsigned)(g.H * g.W)), kBufferFlags);
+  const int wr_base = (lane & 15) * kStageStride + (4 * wave + (lane >> 4)) * 6;
+#pragma unroll
+  for (int o1 = 0; o1 < 6; ++o1) {
+    float zc[8], out[6];
+#pragma unroll
+    for (int bb = 0; bb < 8; ++bb) zc[bb] = z[bb][o1];
+    inv8(zc, out);
+#pragma unroll
+    for (int o2 = 0; o2 < 6; o2 += 2) {
+      v2f pr = {out[o2] * x_scale, out[o2 + 1] * x_scale};
+      *(v2f*)(stage + wr_base + o2) = pr;
+    }
+    __syncthreads();
+    const unsigned yrow = 4u * (unsigned)(o1 * g.W);
+#pragma unroll
+    for (int i = 0; i < SLOTS; ++i) {
+      if constexpr (VEC2) {
+        const v2f val = *(const v2f*)(stage + rd[i]);
+        if (o1 < rows[i]) __builtin_amdgcn_raw_buffer_store_b64(val, yres, yo[i], yrow, 0);
+      } else {
+        const float val = stage[rd[i]];
+        if (o1 < rows[i])
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), yres, yo[i], yrow, 0);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+template <int ALG, bool VEC2>
 static hipError_t launch_fused_alg(const Geometry& g, const void* V, const FilterViews& f,
                                    float x_scale, float* y, hipStream_t s) {
   const int kblocks = g.Kp / 16;
-  dim3 grid(g.Tp / 16, (kblocks + 3) / 4);
+  dim3 grid(g.Tp / 16, kblocks);
   dim3 block(256);
   const int8_t* v = (const int8_t*)V;
   const int8_t* u = (const int8_t*)f.U;
+#define SFC_LAUNCH_FUSED(KC)                                                                   \
+  hipLaunchKernelGGL((fused_product_output_kernel_b<ALG, KC, VEC2>), grid, block, 0, s, v, u,  \
+                     f.dequant, x_scale, y, g)
   switch (g.Cp / 64) {
-    case 1:
-      hipLaunchKernelGGL((fused_product_output_kernel<ALG, 1>), grid, block, 0, s, v, u, f.dequant, x_scale, y, g);
-      break;
-    case 2:
-      hipLaunchKernelGGL((fused_product_output_kernel<ALG, 2>), grid, block, 0, s, v, u, f.dequant, x_scale, y, g);
-      break;
-    case 4:
-      hipLaunchKernelGGL((fused_product_output_kernel<ALG, 4>), grid, block, 0, s, v, u, f.dequant, x_scale, y, g);
-      break;
-    case 8:
-      hipLaunchKernelGGL((fused_product_output_kernel<ALG, 8>), grid, block, 0, s, v, u, f.dequant, x_scale, y, g);
-      break;
-    default:
-      return hipErrorNotSupported;
+    case 1: SFC_LAUNCH_FUSED(1); break;
+    case 2: SFC_LAUNCH_FUSED(2); break;
+    case 4: SFC_LAUNCH_FUSED(4); break;
+    case 8: SFC_LAUNCH_FUSED(8); break;
+    default: return hipErrorNotSupported;
   }
+#undef SFC_LAUNCH_FUSED
   return hipGetLastError();
 }
 
 bool fused_supported(const Geometry& g) {
   const int kc = g.Cp / 64;
-  // y offsets are kept in 32 bits inside the kernel
-  const long long ysize = (long long)g.N * g.Cout * g.H * g.W;
-  return (kc == 1 || kc == 2 || kc == 4 || kc == 8) && ysize < (1ll << 31);
+  // V, U and y are addressed through buffer descriptors with 32-bit byte offsets
+  const long long ybytes = 4ll * g.N * g.Cout * g.H * g.W;
+  const long long vbytes = (long long)g.P * g.Tp * g.Cp, ubytes = (long long)g.P * g.Kp * g.Cp;
+  const long long lim = 1ll << 31;
+  return (kc == 1 || kc == 2 || kc == 4 || kc == 8) && ybytes < lim && vbytes < lim && ubytes < lim;
 }
 
 hipError_t launch_fused_product_output(int alg, const Geometry& g, const void* V,
                                        const FilterViews& f, float x_scale, float* y,
                                        hipStream_t s) {
   if (!fused_supported(g)) return hipErrorNotSupported;
-  return alg == 0 ? launch_fused_alg<0>(g, V, f, x_scale, y, s)
-                  : launch_fused_alg<1>(g, V, f, x_scale, y, s);
+  const bool vec2 = (g.W % 2) == 0;  // float pairs stay 8-byte aligned in y
+  if (alg == 0)
+    return vec2 ? launch_fused_alg<0, true>(g, V, f, x_scale, y, s)
+                : launch_fused_alg<0, false>(g, V, f, x_scale, y, s);
+  return vec2 ? launch_fused_alg<1, true>(g, V, f, x_scale, y, s)
+              : launch_fused_alg<1, false>(g, V, f, x_scale, y, s);
 }
 
 }  // namespace sfc
