@@ -31,6 +31,9 @@ hipError_t launch_filter_transform(int alg, int mode, const Geometry& g, const i
                                    const FilterViews& f, hipStream_t s);
 hipError_t launch_input_transform(int alg, int mode, const Geometry& g, const int8_t* x, void* V,
                                   const float* inv_sx, hipStream_t s);
+// requantized-mode kernel; hipErrorNotSupported when the geometry is outside its limits
+hipError_t launch_input_transform_i8(int alg, const Geometry& g, const int8_t* x, void* V,
+                                     const float* inv_sx, hipStream_t s);
 hipError_t launch_product(int mode, const Geometry& g, const void* V, const void* U, int32_t* M,
                           hipStream_t s);
 hipError_t launch_output_transform(int alg, int mode, int out, const Geometry& g, const int32_t* M,

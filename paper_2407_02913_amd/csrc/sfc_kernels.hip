@@ -375,6 +375,10 @@ static hipError_t launch_input_impl(const Geometry& g, const int8_t* x, void* V,
 
 hipError_t launch_input_transform(int alg, int mode, const Geometry& g, const int8_t* x, void* V,
                                   const float* inv_sx, hipStream_t s) {
+  if (mode == 1) {
+    const hipError_t e = launch_input_transform_i8(alg, g, x, V, inv_sx, s);
+    if (e != hipErrorNotSupported) return e;
+  }
   if (alg == 0) {
     return mode == 1 ? launch_input_impl<0, 1>(g, x, V, inv_sx, nullptr, s)
                      : launch_input_impl<0, 0>(g, x, V, inv_sx, nullptr, s);
