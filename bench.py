@@ -123,6 +123,21 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         stage_us[name] = e0.elapsed_time(e1) * 1e3 / launches
+    # calibration: the library's plain copy kernel over rotating 128 MiB buffers gives
+    # the streaming bandwidth this device reaches in this run (read + write bytes)
+    cal_bytes = 128 << 20
+    cal = [(torch.empty(cal_bytes, dtype=torch.uint8, device="cuda"),
+            torch.empty(cal_bytes, dtype=torch.uint8, device="cuda")) for _ in range(3)]
+    for i in range(3):
+        binding.stream_copy(cal[i][1], cal[i][0])
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(12):
+        binding.stream_copy(cal[i % 3][1], cal[i % 3][0])
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * cal_bytes * 12 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del cal
     bytes_per = stage_bytes(shape, plan.P, plan.tiles, path)
     dominant = max(stage_us, key=stage_us.get)
     achieved = bytes_per[dominant] / (stage_us[dominant] * 1e-6) / 1e9
@@ -137,7 +152,8 @@ def main():
                 "traffic": traffic, "algorithmic_bytes": bytes_per[dominant],
                 "avg_us": round(stage_us[dominant], 2),
                 "stages_us": {k: round(v, 2) for k, v in stage_us.items()},
-                "stages_gbs": {k: round(bytes_per[k] / (stage_us[k] * 1e-6) / 1e9, 1) for k in stage_us}}
+                "stages_gbs": {k: round(bytes_per[k] / (stage_us[k] * 1e-6) / 1e9, 1) for k in stage_us},
+                "stream_copy_gbs": round(copy_gbs, 1)}
     sfc_ops = 2 * plan.P * plan.tiles * shape.Cin * shape.Cout
     prod_key = "fused_product_output" if path == "fused" else "product"
     roofline["product_mfma_frac"] = round(sfc_ops / (stage_us[prod_key] * 1e-6) / 1e12 / MFMA_I8_PEAK_TOPS, 4)

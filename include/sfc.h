@@ -152,6 +152,13 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
 sfc_status sfc_tap_info(const sfc_plan_t* plan, const void* workspace_dev, int32_t which,
                         const void** ptr, int32_t* elem_bytes, int64_t dims[3], int64_t strides[3]);
 
+/* Measurement aid: a plain streaming copy of `bytes` (a multiple of 16, both
+ * pointers 16-byte aligned) from src_dev to dst_dev on `stream`.  It reads and
+ * writes every byte exactly once, so hardware byte counters and achieved-bandwidth
+ * figures of the convolution kernels can be calibrated against a kernel of known
+ * traffic on the same device. */
+sfc_status sfc_stream_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
+
 const char* sfc_status_string(sfc_status s);
 
 #ifdef __cplusplus

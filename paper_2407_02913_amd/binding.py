@@ -23,13 +23,13 @@ OUT = {"f32": 0, "i32": 1}
 PATH = {"staged": 0, "fused": 1}
 STAGE_INPUT, STAGE_PRODUCT, STAGE_OUTPUT, STAGE_ALL = 1, 2, 4, 7
 #: the path bench.py and callers get when they do not ask for one
-DEFAULT_PATH = "staged"
+DEFAULT_PATH = "fused"
 
 #: every symbol include/sfc.h declares
 EXPORTS = (
     "sfc_plan", "sfc_plan_destroy", "sfc_plan_sizes", "sfc_set_point_scales",
     "sfc_calibrate_act_scales", "sfc_calibrate_filter_scales", "sfc_transform_filter",
-    "sfc_conv2d_nchw", "sfc_conv2d_stages", "sfc_tap_info", "sfc_status_string",
+    "sfc_conv2d_nchw", "sfc_conv2d_stages", "sfc_tap_info", "sfc_stream_copy", "sfc_status_string",
 )
 
 
@@ -81,6 +81,8 @@ def load(force: bool = False):
     lib.sfc_tap_info.argtypes = [vp, vp, i32, C.POINTER(vp), C.POINTER(i32),
                                  C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.sfc_tap_info.restype = i32
+    lib.sfc_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
+    lib.sfc_stream_copy.restype = i32
     lib.sfc_status_string.argtypes = [i32]
     lib.sfc_status_string.restype = C.c_char_p
     _lib = lib
@@ -195,6 +197,14 @@ class Plan:
         flat = base.view(torch.uint8)[off:].view(dtype)
         view = torch.as_strided(flat, tuple(dims), tuple(strides))
         return view.cpu().numpy().copy()
+
+
+def stream_copy(dst, src, stream=None):
+    """Plain streaming copy kernel of the library (bandwidth / counter calibration)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() >= nbytes and nbytes % 16 == 0
+    _check(load().sfc_stream_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nbytes,
+                                  _stream_ptr(stream)), "sfc_stream_copy")
 
 
 def device_buffer(nbytes: int):

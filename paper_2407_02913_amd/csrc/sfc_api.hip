@@ -281,6 +281,15 @@ sfc_status sfc_tap_info(const sfc_plan_t* plan, const void* workspace_dev, int32
   }
 }
 
+sfc_status sfc_stream_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream) {
+  if (!dst_dev || !src_dev) return SFC_EINVAL;
+  if (!aligned16(dst_dev) || !aligned16(src_dev) || (bytes & 15u) != 0) return SFC_EINVAL;
+  if (sfc::launch_stream_copy(dst_dev, src_dev, bytes, static_cast<hipStream_t>(stream)) !=
+      hipSuccess)
+    return SFC_EHIP;
+  return SFC_OK;
+}
+
 static sfc_status maxima_to_scales(const int32_t* dev, size_t count, hipStream_t s, float* out) {
   std::vector<int32_t> host;
   try {

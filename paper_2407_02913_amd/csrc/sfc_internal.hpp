@@ -49,4 +49,6 @@ hipError_t launch_act_absmax(int alg, const Geometry& g, const int8_t* x, int32_
 hipError_t launch_filter_absmax(int alg, const Geometry& g, const int8_t* w,
                                 int32_t* maxima /*[P][Cout]*/, hipStream_t s);
 
+hipError_t launch_stream_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+
 }  // namespace sfc

@@ -227,6 +227,24 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
   }
 }
 
+// plain streaming copy, 16 bytes per lane, grid-stride
+__global__ __launch_bounds__(256) void stream_copy_kernel(const v4i* __restrict__ src,
+                                                          v4i* __restrict__ dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_stream_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  const size_t n = bytes / 16;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const v4i*)src,
+                     (v4i*)dst, n);
+  return hipGetLastError();
+}
+
 __global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
