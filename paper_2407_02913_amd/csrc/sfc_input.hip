@@ -53,51 +53,63 @@ __global__ __launch_bounds__(384, 2) void input_transform_i8_kernel(
       (void*)x, 0, (int)((unsigned)(g.N * g.Cin) * (unsigned)(H * W)), kBufFlags);
 
   // ---- 1. stage ---------------------------------------------------------------
-  // One instruction covers four rows x 16 dwords of a (strip, channel); a batch of
-  // four (strip, channel) pairs per wave keeps eight loads in flight before the
-  // first LDS write.  Global dwords need not be aligned (W may be odd); a dword that
+  // One instruction covers four rows x 16 dwords of a (strip, channel): lane =
+  // (row within the half, dword).  Everything that depends on the lane or the
+  // strip is hoisted; per channel only a scalar plane offset changes.  A batch
+  // of four channels per wave keeps eight loads in flight before the first LDS
+  // write.  Global dwords need not be aligned (W may be odd); a dword that
   // straddles the end of an image row is assembled from its valid bytes.
   {
-    const int nsc = ip.S * 64;
     const int dpr = ip.wp >> 2;  // dwords per staged row, <= 16
     const int rsub = lane >> 4, dcol = lane & 15;
     const int col = colbase + 4 * dcol - 4;  // image column of this lane's dword
     const int nvalid = col < 0 ? 0 : min(4, max(0, W - col));
+    const unsigned plane_stride = (unsigned)(H * W);
     constexpr int BATCH = 4;
-    for (int sc0 = wave; sc0 < nsc; sc0 += BATCH * nwaves) {
-      unsigned vals[BATCH][2];
+    for (int s = 0; s < ip.S; ++s) {
+      const int strip = strip0 + s;
+      const bool strip_live = strip < g.strips;
+      const int n = strip / g.th, ti = strip - n * g.th;
+      bool ok[2];
+      unsigned voff[2], loff[2];
 #pragma unroll
-      for (int bi = 0; bi < BATCH; ++bi) {
-        const int sc = sc0 + bi * nwaves;
-        const int s = min(sc, nsc - 1) >> 6, c = sc & 63;
-        const int strip = strip0 + s;
-        const bool live = sc < nsc && strip < g.strips && c0 + c < g.Cin;
-        const int n = strip / g.th, ti = strip - n * g.th;
-        const unsigned plane = (unsigned)((n * g.Cin + c0 + c) * H) * (unsigned)W;
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const int h = 6 * ti - 1 + half * 4 + rsub;
-          const unsigned off = (unsigned)(h * W + col);
-          unsigned val = 0;
-          if (live && dcol < dpr && h >= 0 && h < H) {
-            if (nvalid == 4) {
-              val = __builtin_amdgcn_raw_buffer_load_b32(xres, off, plane, 0);
-            } else {
-              for (int bb = 0; bb < nvalid; ++bb)
-                val |= (unsigned)__builtin_amdgcn_raw_buffer_load_b8(xres, off + bb, plane, 0)
-                       << (8 * bb);
-            }
-          }
-          vals[bi][half] = val;
-        }
+      for (int half = 0; half < 2; ++half) {
+        const int h = 6 * ti - 1 + half * 4 + rsub;
+        ok[half] = strip_live && dcol < dpr && h >= 0 && h < H && nvalid > 0;
+        voff[half] = (unsigned)(h * W + col);
+        loff[half] = (unsigned)(s * 64 * ip.cs + (half * 4 + rsub) * ip.wp + 4 * dcol);
       }
+      const unsigned plane0 = (unsigned)(n * g.Cin + c0) * plane_stride;
+      for (int cb = wave; cb < 64; cb += BATCH * nwaves) {
+        unsigned vals[BATCH][2];
 #pragma unroll
-      for (int bi = 0; bi < BATCH; ++bi) {
-        const int sc = sc0 + bi * nwaves;
-        if (sc < nsc && dcol < dpr) {
+        for (int bi = 0; bi < BATCH; ++bi) {
+          const int c = cb + bi * nwaves;
+          const bool live = c < 64 && c0 + c < g.Cin;
+          const unsigned plane = plane0 + (unsigned)c * plane_stride;
 #pragma unroll
-          for (int half = 0; half < 2; ++half)
-            *(unsigned*)(lds + sc * ip.cs + (half * 4 + rsub) * ip.wp + 4 * dcol) = vals[bi][half];
+          for (int half = 0; half < 2; ++half) {
+            unsigned val = 0;
+            if (live && ok[half]) {
+              if (nvalid == 4) {
+                val = __builtin_amdgcn_raw_buffer_load_b32(xres, voff[half], plane, 0);
+              } else {
+                for (int bb = 0; bb < nvalid; ++bb)
+                  val |= (unsigned)__builtin_amdgcn_raw_buffer_load_b8(xres, voff[half] + bb, plane, 0)
+                         << (8 * bb);
+              }
+            }
+            vals[bi][half] = val;
+          }
+        }
+#pragma unroll
+        for (int bi = 0; bi < BATCH; ++bi) {
+          const int c = cb + bi * nwaves;
+          if (c < 64 && dcol < dpr) {
+#pragma unroll
+            for (int half = 0; half < 2; ++half)
+              *(unsigned*)(lds + loff[half] + c * ip.cs) = vals[bi][half];
+          }
         }
       }
     }
