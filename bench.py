@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--path", default=None, choices=[None, "staged", "fused"])
     ap.add_argument("--alg", default="6x6_p88")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--buffer-sets", type=int, default=0,
+                    help="rotating input/workspace/output sets (0: enough to exceed the memory-side cache)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the layer shards over "
@@ -78,7 +80,7 @@ def main():
 
     ybytes = 4 * shape.N * shape.Cout * shape.H * shape.W
     per_set = x_host.numel() + plan.workspace_bytes + ybytes
-    nsets = max(2, min(24, -(-ROTATE_BYTES // per_set)))
+    nsets = args.buffer_sets if args.buffer_sets > 0 else max(2, min(24, -(-ROTATE_BYTES // per_set)))
     sets = []
     for _ in range(nsets):
         sets.append((x_host.cuda(), binding.device_buffer(plan.workspace_bytes),

@@ -69,7 +69,8 @@ struct Order {
   }
 };
 
-constexpr int kRing = 8;          // operand slots in flight (64-channel chunks)
+constexpr int kRing = 4;          // operand slots in flight (64-channel chunks)
+constexpr int kStreamStore = 2;    // buffer cache policy "nt": y is written once and not re-read here
 constexpr int kBufferFlags = 0x00020000;  // raw buffer descriptor word 3: 32-bit data format
 constexpr int kStageStride = 98;  // floats per filter row of the staging block (16 tiles x 6 + 2)
 
@@ -268,12 +269,13 @@ __global__ __launch_bounds__(256) void fused_product_output_kernel(
 
 // ---------------------------------------------------------------------------
 // Variant B: the same block of 16 tiles x 16 filters is owned by a whole workgroup
-// of four waves.  In round r wave w runs the MFMA chain of point 4r + w, scales
-// the sums and leaves them in LDS in the MFMA's own layout; after one barrier
-// every thread reads the four values of its single (tile, filter) pair and
-// feeds the output transform.  One pair per thread keeps the register count low
-// enough for several waves per SIMD, which hides the operand-load latency and
-// staggers the final stores of different workgroups.
+// of four waves.  Points are handled in rounds of PPR; in a round every wave runs
+// the MFMA chains of PPR/4 points, scales the sums and leaves them in LDS in the
+// MFMA's own layout; after one barrier every thread reads the PPR values of its
+// single (tile, filter) pair and feeds the output transform.  One pair per thread
+// keeps the register count low enough for four waves per SIMD.  Nothing in the
+// prologue waits on global memory: operands and dequantization factors stream
+// through a register ring that is filled before the first barrier.
 // ---------------------------------------------------------------------------
 template <int ALG, int KC, bool VEC2>
 __global__ __launch_bounds__(256, 4) void fused_product_output_kernel_b(
@@ -281,17 +283,20 @@ __global__ __launch_bounds__(256, 4) void fused_product_output_kernel_b(
     float x_scale, float* __restrict__ y, Geometry g) {
   constexpr int P = AlgTraits<ALG>::P;
   constexpr Order<ALG> order{};
-  constexpr int ROUNDS = P / 4;
-  constexpr int NS = ROUNDS * KC;  // chunk steps of one wave
+  constexpr int PPR = (P % 8 == 0) ? 8 : 4;  // points per round
+  constexpr int PW = PPR / 4;                // points per wave and round
+  constexpr int ROUNDS = P / PPR;
+  constexpr int NJ = P / 4;                  // points of one wave
+  constexpr int NS = NJ * KC;                // chunk steps of one wave
 
-  __shared__ __align__(16) float mx[2][4][256];  // [buffer][point of the round][MFMA layout]
-  __shared__ __align__(16) float stage[16 * kStageStride];
-  __shared__ float dq_lds[P][16];
+  __shared__ __align__(16) float mx[2][PPR][256];  // [buffer][point of the round][MFMA layout]
+  __shared__ __align__(16) float stage[2][16 * kStageStride];
   __shared__ int tile_off[16];
   __shared__ int tile_ext[16];
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const int t0 = blockIdx.x * 16;
   const int kb = blockIdx.y;
   const int kcol = kb * 16 + (lane & 15);  // < Kp
@@ -310,20 +315,6 @@ __global__ __launch_bounds__(256, 4) void fused_product_output_kernel_b(
     tile_off[threadIdx.x] = off;
     tile_ext[threadIdx.x] = ext;
   }
-  {
-    constexpr int PER = (P * 16 + 255) / 256;
-    float tmp[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int e = i * 256 + threadIdx.x;
-      tmp[i] = e < P * 16 ? dequant[(size_t)(e >> 4) * g.Kp + kb * 16 + (e & 15)] : 0.0f;
-    }
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int e = i * 256 + threadIdx.x;
-      if (e < P * 16) dq_lds[e >> 4][e & 15] = tmp[i];
-    }
-  }
 
   const unsigned vstride = (unsigned)g.Tp * g.Cp;
   const unsigned ustride = (unsigned)g.Kp * g.Cp;
@@ -333,67 +324,67 @@ __global__ __launch_bounds__(256, 4) void fused_product_output_kernel_b(
       __builtin_amdgcn_make_buffer_rsrc((void*)V, 0, (int)(vstride * (unsigned)P), kBufferFlags);
   const __amdgpu_buffer_rsrc_t ures =
       __builtin_amdgcn_make_buffer_rsrc((void*)U, 0, (int)(ustride * (unsigned)P), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t dres = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)dequant, 0, (int)(4u * (unsigned)P * (unsigned)g.Kp), kBufferFlags);
 
-  // operand ring of this wave: chunk step s = r*KC + kc of its own point 4r + wave.
-  // The point index depends on the wave, so the plane offset is a table lookup
-  // made uniform with readfirstlane.
-  __shared__ int pt_lds[P];
-  if (threadIdx.x < P) {
-    int v = 0;
-#pragma unroll
-    for (int i = 0; i < P; ++i)
-      if (i == (int)threadIdx.x) v = order.pt[i];
-    pt_lds[threadIdx.x] = v;
-  }
-  __syncthreads();
-
+  // This wave's j-th point is the (4j + wave)-th of the processing order: one of
+  // four compile-time constants chosen by the uniform wave index, so the plane
+  // offsets stay scalar.  Chunk step s = j*KC + kc.
+  auto point_of = [&](int j) {
+    const int p0 = order.pt[4 * j], p1 = order.pt[4 * j + 1], p2 = order.pt[4 * j + 2],
+              p3 = order.pt[4 * j + 3];
+    return wave_u == 0 ? p0 : wave_u == 1 ? p1 : wave_u == 2 ? p2 : p3;
+  };
   v4i a[kRing], b[kRing];
-  auto point_of = [&](int r) { return __builtin_amdgcn_readfirstlane(pt_lds[4 * r + wave]); };
+  float dq[kRing];
   auto load_chunk = [&](int s) {
-    const int r = s / KC, kc = s % KC;
-    const int p = point_of(r);
+    const int j = s / KC, kc = s % KC;
+    const int p = point_of(j);
     a[s % kRing] = __builtin_amdgcn_raw_buffer_load_b128(vres, aoff, p * vstride + kc * 64, 0);
     b[s % kRing] = __builtin_amdgcn_raw_buffer_load_b128(ures, boff, p * ustride + kc * 64, 0);
+    if (kc == 0)
+      dq[j % kRing] = __builtin_bit_cast(
+          float, __builtin_amdgcn_raw_buffer_load_b32(dres, 4u * (unsigned)kcol, 4u * (unsigned)(p * g.Kp), 0));
   };
 #pragma unroll
   for (int s = 0; s < kRing && s < NS; ++s) load_chunk(s);
 
-  auto mfma_round = [&](int r) {
+  // MFMA chain of this wave's point j, already scaled (the factor is read before
+  // its ring slot is refilled)
+  auto product = [&](int j) -> v4f {
+    const float d = dq[j % kRing];
     v4i acc = {0, 0, 0, 0};
 #pragma unroll
     for (int kc = 0; kc < KC; ++kc) {
-      const int s = r * KC + kc;
+      const int s = j * KC + kc;
       acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[s % kRing], b[s % kRing], acc, 0, 0, 0);
       if (s + kRing < NS) load_chunk(s + kRing);
     }
-    return acc;
+    return v4f{(float)acc.x * d, (float)acc.y * d, (float)acc.z * d, (float)acc.w * d};
   };
-  auto publish = [&](int r, v4i acc) {
-    const float d = dq_lds[point_of(r)][lane & 15];
-    const v4f m = {(float)acc.x * d, (float)acc.y * d, (float)acc.z * d, (float)acc.w * d};
-    *(v4f*)(&mx[r & 1][wave][lane * 4]) = m;
+  // round r: this wave's points j = r*PW .. r*PW + PW-1 land in slots 4*(j % PW) + wave
+  auto publish_round = [&](int r) {
+#pragma unroll
+    for (int i = 0; i < PW; ++i)
+      *(v4f*)(&mx[r & 1][4 * i + wave][lane * 4]) = product(r * PW + i);
   };
 
-  publish(0, mfma_round(0));
+  publish_round(0);
   __syncthreads();
 
   // consumer side: this thread's pair is tile row 4*wave + lane/16, filter lane%16
   const int rd_idx = (wave * 16 + (lane & 15)) * 4 + (lane >> 4);
   int q = 0;  // folds to a constant
-  float cur[4];
-  v4i acc_next = {0, 0, 0, 0};
+  float cur[PPR];
   auto next = [&]() -> float {
-    const int r = q >> 2, i = q & 3;
+    const int r = q / PPR, i = q % PPR;
     if (i == 0) {
-      if (r + 1 < ROUNDS) acc_next = mfma_round(r + 1);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) cur[j] = mx[r & 1][j][rd_idx];
+      for (int j = 0; j < PPR; ++j) cur[j] = mx[r & 1][j][rd_idx];
+      if (r + 1 < ROUNDS) publish_round(r + 1);
     }
     const float v = cur[i];
-    if (i == 3) {
-      if (r + 1 < ROUNDS) publish(r + 1, acc_next);
-      __syncthreads();
-    }
+    if (i == PPR - 1) __syncthreads();
     ++q;
     return v;
   };
@@ -461,31 +452,32 @@ __global__ __launch_bounds__(256, 4) void fused_product_output_kernel_b(
   const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
       (void*)y, 0, (int)(4u * (unsigned)(g.N * g.Cout) * (unsigned)(g.H * g.W)), kBufferFlags);
   const int wr_base = (lane & 15) * kStageStride + (4 * wave + (lane >> 4)) * 6;
+  // one barrier per output row: the staging block is double buffered
 #pragma unroll
   for (int o1 = 0; o1 < 6; ++o1) {
     float zc[8], out[6];
 #pragma unroll
     for (int bb = 0; bb < 8; ++bb) zc[bb] = z[bb][o1];
     inv8(zc, out);
+    float* st = stage[o1 & 1];
 #pragma unroll
     for (int o2 = 0; o2 < 6; o2 += 2) {
       v2f pr = {out[o2] * x_scale, out[o2 + 1] * x_scale};
-      *(v2f*)(stage + wr_base + o2) = pr;
+      *(v2f*)(st + wr_base + o2) = pr;
     }
     __syncthreads();
     const unsigned yrow = 4u * (unsigned)(o1 * g.W);
 #pragma unroll
     for (int i = 0; i < SLOTS; ++i) {
       if constexpr (VEC2) {
-        const v2f val = *(const v2f*)(stage + rd[i]);
-        if (o1 < rows[i]) __builtin_amdgcn_raw_buffer_store_b64(val, yres, yo[i], yrow, 0);
+        const v2f val = *(const v2f*)(st + rd[i]);
+        if (o1 < rows[i]) __builtin_amdgcn_raw_buffer_store_b64(val, yres, yo[i], yrow, kStreamStore);
       } else {
-        const float val = stage[rd[i]];
+        const float val = st[rd[i]];
         if (o1 < rows[i])
-          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), yres, yo[i], yrow, 0);
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), yres, yo[i], yrow, kStreamStore);
       }
     }
-    __syncthreads();
   }
 }
 

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(384, 2) void input_transform_i8_kernel(
   // One instruction covers four rows x 16 dwords of a (strip, channel): lane =
   // (row within the half, dword).  Everything that depends on the lane or the
   // strip is hoisted; per channel only a scalar plane offset changes.  A batch
-  // of four channels per wave keeps eight loads in flight before the first LDS
+  // of up to 16 channels per wave keeps up to 32 loads in flight before the first LDS
   // write.  Global dwords need not be aligned (W may be odd); a dword that
   // straddles the end of an image row is assembled from its valid bytes.
   {
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(384, 2) void input_transform_i8_kernel(
     const int col = colbase + 4 * dcol - 4;  // image column of this lane's dword
     const int nvalid = col < 0 ? 0 : min(4, max(0, W - col));
     const unsigned plane_stride = (unsigned)(H * W);
-    constexpr int BATCH = 4;
+    constexpr int BATCH = 16;
     for (int s = 0; s < ip.S; ++s) {
       const int strip = strip0 + s;
       const bool strip_live = strip < g.strips;
