@@ -23,6 +23,13 @@ namespace sfc {
 typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int kBufFlags = 0x00020000;  // raw buffer descriptor word 3: 32-bit data format
 
+// id -> position such that ids congruent modulo 8 (same XCD) map to one contiguous range
+__device__ __forceinline__ int xcd_contiguous(int id, int n) {
+  const int q = n >> 3, r = n & 7;
+  const int xcd = id & 7, idx = id >> 3;
+  return xcd * q + min(xcd, r) + idx;
+}
+
 struct InputPlan {
   int S;        // strips per workgroup
   int chunks;   // tile-column chunks per strip
@@ -41,8 +48,12 @@ __global__ __launch_bounds__(384, 2) void input_transform_i8_kernel(
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int nwaves = blockDim.x >> 6;  // = S * tlw
-  const int chunk = blockIdx.x % ip.chunks;
-  const int strip0 = (blockIdx.x / ip.chunks) * ip.S;
+  // Workgroups are dealt to the 8 XCDs round-robin by id; remap so that each XCD
+  // (each L2) gets a contiguous range of (strip, chunk) items: neighbours share
+  // halo rows and overlapping columns.
+  const int bx = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int chunk = bx % ip.chunks;
+  const int strip0 = (bx / ip.chunks) * ip.S;
   const int c0 = blockIdx.y * 64;
   const int tj0 = chunk * ip.tlw;
   const int colbase = (6 * tj0) & ~3;       // image column held at LDS byte 4 of a row
