@@ -65,7 +65,12 @@ typedef enum {
 
 typedef enum {
   SFC_OUT_F32 = 0, /* y float32 [N,Cout,H,W], dequantized */
-  SFC_OUT_I32 = 1  /* exact mode only: the raw integer sums, int32 [N,Cout,H,W] */
+  SFC_OUT_I32 = 1, /* exact mode only: the raw integer sums, int32 [N,Cout,H,W] */
+  /* requantized mode only: the next layer's int8 activations,
+   * clamp(round-half-even(max(y, 0) / y_scale), 0, 127), int8 [N,Cout,H,W]; the
+   * scale is set with sfc_set_output_scale.  This is the epilogue that chains
+   * stride-1 layers of a stack without a float32 round trip. */
+  SFC_OUT_I8_RELU = 2
 } sfc_out;
 
 typedef enum {
@@ -104,6 +109,10 @@ sfc_status sfc_plan_sizes(const sfc_plan_t* plan, size_t* filter_bytes, size_t* 
  * Must precede sfc_transform_filter. */
 sfc_status sfc_set_point_scales(sfc_plan_t* plan, const float* sx_host, const float* sw_host);
 
+/* SFC_OUT_I8_RELU plans: the activation scale of the output tensor (> 0), host only.
+ * Must precede sfc_conv2d_nchw (SFC_ENOTREADY otherwise). */
+sfc_status sfc_set_output_scale(sfc_plan_t* plan, float y_scale);
+
 /* Abs-max calibration helpers (the paper tunes scales with AdaQuant on real
  * data; abs-max over a calibration tensor stands in): scale = max|value|/127,
  * 1 where the maximum is 0.  Both block until the result is in host memory.
@@ -128,7 +137,7 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
  * M_p[tiles x Cout] = V_p[tiles x Cin] . U_p[Cin x Cout], output transform with
  * the correction terms, dequantization and the NCHW store.
  * x_dev: int8 [N,Cin,H,W]; x_scale: spatial-domain activation scale.
- * y_dev: float32 (SFC_OUT_F32) or int32 (SFC_OUT_I32) [N,Cout,H,W].
+ * y_dev: float32 (SFC_OUT_F32), int32 (SFC_OUT_I32) or int8 (SFC_OUT_I8_RELU) [N,Cout,H,W].
  * workspace_dev: >= workspace_bytes, private to this call until it completes.
  * SFC_ENOTREADY before sfc_transform_filter. */
 sfc_status sfc_conv2d_nchw(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale, void* y_dev,

@@ -19,7 +19,7 @@ STATUS_NAMES = {0: "SFC_OK", 1: "SFC_EINVAL", 2: "SFC_EUNSUPPORTED", 3: "SFC_ENO
                 4: "SFC_ENOTREADY", 5: "SFC_EHIP"}
 ALG = {"6x6_p88": 0, "6x6_p100": 1}
 MODE = {"exact": 0, "requant": 1}
-OUT = {"f32": 0, "i32": 1}
+OUT = {"f32": 0, "i32": 1, "i8": 2}
 PATH = {"staged": 0, "fused": 1}
 STAGE_INPUT, STAGE_PRODUCT, STAGE_OUTPUT, STAGE_ALL = 1, 2, 4, 7
 #: the path bench.py and callers get when they do not ask for one
@@ -27,7 +27,7 @@ DEFAULT_PATH = "fused"
 
 #: every symbol include/sfc.h declares
 EXPORTS = (
-    "sfc_plan", "sfc_plan_destroy", "sfc_plan_sizes", "sfc_set_point_scales",
+    "sfc_plan", "sfc_plan_destroy", "sfc_plan_sizes", "sfc_set_point_scales", "sfc_set_output_scale",
     "sfc_calibrate_act_scales", "sfc_calibrate_filter_scales", "sfc_transform_filter",
     "sfc_conv2d_nchw", "sfc_conv2d_stages", "sfc_tap_info", "sfc_stream_copy", "sfc_status_string",
 )
@@ -68,6 +68,8 @@ def load(force: bool = False):
     lib.sfc_plan_sizes.restype = i32
     lib.sfc_set_point_scales.argtypes = [vp, C.POINTER(f32), C.POINTER(f32)]
     lib.sfc_set_point_scales.restype = i32
+    lib.sfc_set_output_scale.argtypes = [vp, f32]
+    lib.sfc_set_output_scale.restype = i32
     lib.sfc_calibrate_act_scales.argtypes = [vp, vp, i32, vp, vp, C.POINTER(f32)]
     lib.sfc_calibrate_act_scales.restype = i32
     lib.sfc_calibrate_filter_scales.argtypes = [vp, vp, vp, vp, C.POINTER(f32)]
@@ -139,6 +141,9 @@ class Plan:
         assert sx.shape == (self.P,) and sw.shape == (self.P, self.desc.Cout), (sx.shape, sw.shape)
         _check(load().sfc_set_point_scales(self._h, _f32_ptr(sx), _f32_ptr(sw)),
                "sfc_set_point_scales")
+
+    def set_output_scale(self, y_scale: float):
+        _check(load().sfc_set_output_scale(self._h, C.c_float(y_scale)), "sfc_set_output_scale")
 
     def calibrate_act_scales(self, x_dev, workspace, stream=None) -> np.ndarray:
         out = np.empty(self.P, dtype=np.float32)
@@ -215,7 +220,7 @@ def device_buffer(nbytes: int):
 
 
 def conv2d(x: np.ndarray, w: np.ndarray, x_scale: float, w_scale, mode="requant", alg="6x6_p88",
-           out="f32", path="staged", sx=None, sw=None, return_taps=False):
+           out="f32", path="staged", sx=None, sw=None, return_taps=False, y_scale=None):
     """Convenience wrapper: numpy in, numpy out, one layer through the C ABI."""
     import torch
 
@@ -230,9 +235,11 @@ def conv2d(x: np.ndarray, w: np.ndarray, x_scale: float, w_scale, mode="requant"
     wbuf = device_buffer(plan.workspace_bytes)
     if mode == "requant":
         plan.set_point_scales(sx, sw)
+    if out == "i8":
+        plan.set_output_scale(float(y_scale))
     plan.transform_filter(wdv, ws_arr, fbuf)
-    y = torch.empty((n, cout, h, wd), dtype=torch.int32 if out == "i32" else torch.float32,
-                    device="cuda")
+    ydt = {"i32": torch.int32, "f32": torch.float32, "i8": torch.int8}[out]
+    y = torch.empty((n, cout, h, wd), dtype=ydt, device="cuda")
     plan.conv2d(xd, float(x_scale), y, wbuf)
     torch.cuda.synchronize()
     res = y.cpu().numpy()

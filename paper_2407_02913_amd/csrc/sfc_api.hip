@@ -26,6 +26,7 @@ struct sfc_plan_s {
   std::vector<float> staging;  // host image of the float tables of the filter buffer
   void* filter_dev;
   bool filter_ready;
+  float inv_y;  // 1 / output scale (SFC_OUT_I8_RELU), 0: not set
 };
 
 namespace {
@@ -67,10 +68,11 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   if (d.N <= 0 || d.Cin <= 0 || d.Cout <= 0 || d.H <= 0 || d.W <= 0) return SFC_EINVAL;
   if (d.alg != SFC_ALG_6X6_P88 && d.alg != SFC_ALG_6X6_P100) return SFC_EINVAL;
   if (d.mode != SFC_MODE_EXACT && d.mode != SFC_MODE_REQUANT_I8) return SFC_EINVAL;
-  if (d.out != SFC_OUT_F32 && d.out != SFC_OUT_I32) return SFC_EINVAL;
+  if (d.out != SFC_OUT_F32 && d.out != SFC_OUT_I32 && d.out != SFC_OUT_I8_RELU) return SFC_EINVAL;
   if (d.path != SFC_PATH_STAGED && d.path != SFC_PATH_FUSED) return SFC_EINVAL;
   if (d.per_channel_wscale != 0 && d.per_channel_wscale != 1) return SFC_EINVAL;
   if (d.out == SFC_OUT_I32 && d.mode != SFC_MODE_EXACT) return SFC_EUNSUPPORTED;
+  if (d.out == SFC_OUT_I8_RELU && d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
   if (d.path == SFC_PATH_FUSED && d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
   if (d.W > 1024 || d.H > (1 << 20) || d.Cin > (1 << 16) || d.Cout > 65535 * 16)
     return SFC_EUNSUPPORTED;
@@ -114,6 +116,7 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   p->scales_set = false;
   p->filter_dev = nullptr;
   p->filter_ready = false;
+  p->inv_y = 0.0f;
   *out = p;
   return SFC_OK;
 }
@@ -151,6 +154,16 @@ sfc_status sfc_set_point_scales(sfc_plan_t* plan, const float* sx_host, const fl
   }
   plan->scales_set = true;
   plan->filter_ready = false;
+  return SFC_OK;
+}
+
+sfc_status sfc_set_output_scale(sfc_plan_t* plan, float y_scale) {
+  if (!plan) return SFC_EINVAL;
+  if (plan->d.out != SFC_OUT_I8_RELU) return SFC_EUNSUPPORTED;
+  if (!(y_scale > 0.0f) || !std::isfinite(y_scale)) return SFC_EINVAL;
+  const float inv = 1.0f / y_scale;
+  if (!std::isfinite(inv) || !(inv > 0.0f)) return SFC_EINVAL;
+  plan->inv_y = inv;
   return SFC_OK;
 }
 
@@ -211,6 +224,7 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
   if (!(x_scale > 0.0f) || !std::isfinite(x_scale)) return SFC_EINVAL;
   if (stage_mask <= 0 || stage_mask > SFC_STAGE_ALL) return SFC_EINVAL;
   if (!plan->filter_ready) return SFC_ENOTREADY;
+  if (plan->d.out == SFC_OUT_I8_RELU && plan->inv_y == 0.0f) return SFC_ENOTREADY;
   const bool fused = plan->d.path == SFC_PATH_FUSED;
   const int tail = stage_mask & (SFC_STAGE_PRODUCT | SFC_STAGE_OUTPUT);
   if (fused && tail != 0 && tail != (SFC_STAGE_PRODUCT | SFC_STAGE_OUTPUT)) return SFC_EINVAL;
@@ -225,8 +239,8 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
       return SFC_EHIP;
   }
   if (fused) {
-    if (tail && sfc::launch_fused_product_output(plan->d.alg, g, V, f, x_scale,
-                                                 static_cast<float*>(y_dev), s) != hipSuccess)
+    if (tail && sfc::launch_fused_product_output(plan->d.alg, plan->d.out, g, V, f, x_scale,
+                                                 plan->inv_y, y_dev, s) != hipSuccess)
       return SFC_EHIP;
     return SFC_OK;
   }
@@ -236,7 +250,7 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
   }
   if (stage_mask & SFC_STAGE_OUTPUT) {
     if (sfc::launch_output_transform(plan->d.alg, plan->d.mode, plan->d.out, g, M, f, x_scale,
-                                     y_dev, s) != hipSuccess)
+                                     plan->inv_y, y_dev, s) != hipSuccess)
       return SFC_EHIP;
   }
   return SFC_OK;

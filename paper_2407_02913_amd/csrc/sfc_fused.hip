@@ -1,21 +1,21 @@
 // Fused transform-domain product + output transform for SFC-6(6x6,3x3), gfx950.
 //
-// One wave owns a block of 16 tiles x 16 filters.  For every multiplication
-// point it runs the int8 MFMA 16x16x64 over the input channels, scales the
-// int32 sums by the point's dequantization factor and feeds them straight into
-// the output transform, so the products M never leave the registers.
+// A workgroup of four waves owns a block of 16 tiles x 16 filters.  For every
+// multiplication point one of its waves runs the int8 MFMA 16x16x64 over the input
+// channels and scales the int32 sums by the point's dequantization factor; the
+// products M go through LDS to the thread that owns the (tile, filter) pair and
+// straight into the output transform, so M never reaches HBM.
 //
 // Result layout of the 16x16 MFMA: lane l holds filter column l%16 of tile rows
-// 4*(l/16)..+3.  A lane therefore owns four (tile, filter) pairs and the output
-// transform is lane-local; the four pairs ride in a 4-vector so that the add
-// networks of sfc_points.hpp are reused unchanged.
+// 4*(l/16)..+3; written as one 16-byte LDS store per lane, pair (t, k) sits at
+// float ((t/4)*16 + k)*4 + t%4.
 //
 // Points are consumed grouped by their horizontal row class so that each group
 // collapses at once (product rule post-additions, Hermitian recombination,
 // inverse symbolic DFT along the vertical axis) into z[b][o1]; only z (8x6 values
 // per pair) stays live.  The last step runs the inverse along the horizontal axis
 // one output row at a time, stages the row block in LDS and stores it with
-// contiguous lanes.
+// contiguous lanes (consecutive tiles of a strip form full image rows).
 #include "sfc_internal.hpp"
 #include "sfc_points.hpp"
 
@@ -24,11 +24,6 @@ namespace sfc {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v2f __attribute__((ext_vector_type(2)));
-
-template <>
-struct Third<v4f> {
-  static __device__ __forceinline__ v4f apply(v4f v) { return v * (1.0f / 3.0f); }
-};
 
 // canonical index of the kept nested point (r1, r2) in the 88-point order
 __host__ __device__ constexpr int kept_index(int r1, int r2) {
@@ -74,202 +69,8 @@ constexpr int kStreamStore = 2;    // buffer cache policy "nt": y is written onc
 constexpr int kBufferFlags = 0x00020000;  // raw buffer descriptor word 3: 32-bit data format
 constexpr int kStageStride = 98;  // floats per filter row of the staging block (16 tiles x 6 + 2)
 
-template <int ALG, int KC, bool VEC2>
-__global__ __launch_bounds__(256) void fused_product_output_kernel(
-    const int8_t* __restrict__ V, const int8_t* __restrict__ U, const float* __restrict__ dequant,
-    float x_scale, float* __restrict__ y, Geometry g) {
-  constexpr int P = AlgTraits<ALG>::P;
-  constexpr Order<ALG> order{};
-  constexpr int NS = P * KC;  // chunk steps
-
-  __shared__ __align__(16) float stage[4][16 * kStageStride];
-  __shared__ float dq_lds[P][64];  // dequantization factors of this workgroup's 64 filters
-  __shared__ int tile_off[16];     // y offset of the tile's first output
-  __shared__ int tile_ext[16];     // valid rows | valid cols << 8 (0: padding row)
-
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  const int t0 = blockIdx.x * 16;
-  const int kb = blockIdx.y * 4 + wave;
-  const bool active = kb * 16 < g.Kp;
-  const int k = active ? kb * 16 + (lane & 15) : 0;
-
-  if (threadIdx.x < 16) {
-    const int t = t0 + threadIdx.x;
-    int off = 0, ext = 0;
-    if (t < g.T) {
-      const int per = g.th * g.tw;
-      const int n = t / per, rem = t - n * per;
-      const int ti = rem / g.tw, tj = rem - ti * g.tw;
-      off = ((n * g.Cout) * g.H + 6 * ti) * g.W + 6 * tj;
-      const int rows = min(6, g.H - 6 * ti), cols = min(6, g.W - 6 * tj);
-      ext = rows | (cols << 8);
-    }
-    tile_off[threadIdx.x] = off;
-    tile_ext[threadIdx.x] = ext;
-  }
-  {
-    // all loads in flight at once: P is a multiple of 4
-    const int kk = blockIdx.y * 64 + (threadIdx.x & 63);
-    float tmp[P / 4];
-#pragma unroll
-    for (int i = 0; i < P / 4; ++i)
-      tmp[i] = kk < g.Kp ? dequant[(size_t)(4 * i + wave) * g.Kp + kk] : 0.0f;
-#pragma unroll
-    for (int i = 0; i < P / 4; ++i) dq_lds[4 * i + wave][threadIdx.x & 63] = tmp[i];
-  }
-  __syncthreads();
-
-  // buffer addressing: one 32-bit lane offset per operand, the point's plane and
-  // the channel chunk go into the scalar offset, so a load costs no vector ALU work
-  const unsigned vstride = (unsigned)g.Tp * g.Cp;
-  const unsigned ustride = (unsigned)g.Kp * g.Cp;
-  const unsigned aoff = (unsigned)(t0 + (lane & 15)) * g.Cp + (lane >> 4) * 16;
-  const unsigned boff = (unsigned)k * g.Cp + (lane >> 4) * 16;
-  const float* dq_lane = &dq_lds[0][wave * 16 + (lane & 15)];
-  const __amdgpu_buffer_rsrc_t vres =
-      __builtin_amdgcn_make_buffer_rsrc((void*)V, 0, (int)(vstride * (unsigned)P), kBufferFlags);
-  const __amdgpu_buffer_rsrc_t ures =
-      __builtin_amdgcn_make_buffer_rsrc((void*)U, 0, (int)(ustride * (unsigned)P), kBufferFlags);
-
-  v4i a[kRing], b[kRing];
-  auto load_chunk = [&](int s) {  // s is a compile-time constant at every call site
-    const int q = s / KC, kc = s % KC;
-    const int p = order.pt[q];
-    a[s % kRing] = __builtin_amdgcn_raw_buffer_load_b128(vres, aoff, p * vstride + kc * 64, 0);
-    b[s % kRing] = __builtin_amdgcn_raw_buffer_load_b128(ures, boff, p * ustride + kc * 64, 0);
-  };
-#pragma unroll
-  for (int s = 0; s < kRing && s < NS; ++s) load_chunk(s);
-
-  int q = 0;  // folds to a constant: the code below is straight-line after unrolling
-  v4i pending = {0, 0, 0, 0};
-  float pending_d = 0.0f;
-  auto issue = [&](int qq) {  // MFMA chain of point qq, refilling the ring behind it
-    pending_d = dq_lane[order.pt[qq] * 64];
-    v4i acc = {0, 0, 0, 0};
-#pragma unroll
-    for (int kc = 0; kc < KC; ++kc) {
-      const int s = qq * KC + kc;
-      acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[s % kRing], b[s % kRing], acc, 0, 0, 0);
-      if (s + kRing < NS) load_chunk(s + kRing);
-    }
-    pending = acc;
-  };
-  issue(0);
-  // product of the next point in processing order, dequantized; overlaps the
-  // following point's MFMA chain with the caller's additions
-  auto next = [&]() -> v4f {
-    const v4i acc = pending;
-    const float d = pending_d;
-    if (q + 1 < P) issue(q + 1);
-    ++q;
-    return v4f{(float)acc.x * d, (float)acc.y * d, (float)acc.z * d, (float)acc.w * d};
-  };
-
-  // z[b][o1]: horizontal component b, vertical output o1 (times 6)
-  v4f z[8][6];
-  constexpr int real_comp[4] = {0, 5, 6, 7};
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    v4f col[10], cc[8];
-#pragma unroll
-    for (int r1 = 0; r1 < 10; ++r1) col[r1] = next();
-    collapse10(col, cc);
-    inv8(cc, z[real_comp[j]]);
-  }
-#pragma unroll
-  for (int g2 = 0; g2 < 2; ++g2) {
-    v4f c0[8], c1[8];  // components along the vertical axis for horizontal a0 / a1
-    if constexpr (ALG == 1) {
-      v4f h0[10], h1[10];
-#pragma unroll
-      for (int r1 = 0; r1 < 10; ++r1) {
-        const v4f m0 = next(), m1 = next(), m2 = next();
-        h0[r1] = m0 - m1;
-        h1[r1] = m2 - m0;
-      }
-      collapse10(h0, c0);
-      collapse10(h1, c1);
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const v4f m0 = next(), m1 = next(), m2 = next();
-        c0[real_comp[j]] = m0 - m1;
-        c1[real_comp[j]] = m2 - m0;
-      }
-#pragma unroll
-      for (int g1 = 0; g1 < 2; ++g1) {
-        v4f m[6];
-#pragma unroll
-        for (int i = 0; i < 6; ++i) m[i] = next();
-        // o[i][j]: i along the vertical axis (component a), j along the horizontal one
-        hermitian_collapse(m, c0[1 + 2 * g1], c0[2 + 2 * g1], c1[1 + 2 * g1], c1[2 + 2 * g1]);
-      }
-    }
-    inv8(c0, z[1 + 2 * g2]);
-    inv8(c1, z[2 + 2 * g2]);
-  }
-
-  // ---- store plan: which staged values this lane writes, fixed over the six rows ----
-  // VEC2: 16 filters x 48 float pairs per row phase, lanes contiguous along (tile, o2);
-  // otherwise 16 x 96 single floats.
-  constexpr int SLOTS = VEC2 ? 12 : 24;
-  unsigned yo[SLOTS];  // byte offset into y of output row 0
-  int rows[SLOTS];     // valid output rows for this slot (0: nothing to store)
-  int rd[SLOTS];       // staging index
-#pragma unroll
-  for (int i = 0; i < SLOTS; ++i) {
-    const int e = i * 64 + lane;
-    constexpr int per_k = VEC2 ? 48 : 96, per_t = VEC2 ? 3 : 6, step = VEC2 ? 2 : 1;
-    const int kk = e / per_k, r = e - kk * per_k;
-    const int tl = r / per_t, o2 = step * (r - tl * per_t);
-    const int kcol = kb * 16 + kk;
-    const int ext = tile_ext[tl];
-    const bool ok = active && kcol < g.Cout && o2 < (ext >> 8);
-    rows[i] = ok ? (ext & 0xff) : 0;
-    yo[i] = 4u * ((unsigned)tile_off[tl] + (unsigned)(kcol * g.H) * g.W + o2);
-    rd[i] = kk * kStageStride + tl * 6 + o2;
-  }
-
-  // ---- inverse along the horizontal axis, one output row per phase ----------
-  const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)y, 0, (int)(4u * (unsigned)(g.N * g.Cout) * (unsigned)(g.H * g.W)), kBufferFlags);
-  float* st = stage[wave];
-  const int wr_base = (lane & 15) * kStageStride + (lane >> 4) * 24;  // + j*6 + o2
-#pragma unroll
-  for (int o1 = 0; o1 < 6; ++o1) {
-    v4f zc[8], out[6];
-#pragma unroll
-    for (int bb = 0; bb < 8; ++bb) zc[bb] = z[bb][o1];
-    inv8(zc, out);
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int o2 = 0; o2 < 6; o2 += 2) {
-        v2f pr = {out[o2][j] * x_scale, out[o2 + 1][j] * x_scale};
-        *(v2f*)(st + wr_base + j * 6 + o2) = pr;
-      }
-    __syncthreads();
-    const unsigned yrow = 4u * (unsigned)(o1 * g.W);
-#pragma unroll
-    for (int i = 0; i < SLOTS; ++i) {
-      if constexpr (VEC2) {
-        const v2f val = *(const v2f*)(st + rd[i]);
-        if (o1 < rows[i]) __builtin_amdgcn_raw_buffer_store_b64(val, yres, yo[i], yrow, 0);
-      } else {
-        const float val = st[rd[i]];
-        if (o1 < rows[i])
-          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), yres, yo[i], yrow, 0);
-      }
-    }
-    __syncthreads();
-  }
-}
-
 // ---------------------------------------------------------------------------
-// Variant B: the same block of 16 tiles x 16 filters is owned by a whole workgroup
-// of four waves.  Points are handled in rounds of PPR; in a round every wave runs
+// Points are handled in rounds of PPR; in a round every wave runs
 // the MFMA chains of PPR/4 points, scales the sums and leaves them in LDS in the
 // MFMA's own layout; after one barrier every thread reads the PPR values of its
 // single (tile, filter) pair and feeds the output transform.  One pair per thread
@@ -277,10 +78,12 @@ __global__ __launch_bounds__(256) void fused_product_output_kernel(
 // prologue waits on global memory: operands and dequantization factors stream
 // through a register ring that is filled before the first barrier.
 // ---------------------------------------------------------------------------
-template <int ALG, int KC, bool VEC2>
-__global__ __launch_bounds__(256, 4) void fused_product_output_kernel_b(
+// VEC2: W is even, so float pairs (or byte pairs) of an output row stay aligned.
+// OUT8: write the next layer's int8 activations (ReLU, round, clamp) instead of float32.
+template <int ALG, int KC, bool VEC2, bool OUT8>
+__global__ __launch_bounds__(256, 4) void fused_product_output_kernel(
     const int8_t* __restrict__ V, const int8_t* __restrict__ U, const float* __restrict__ dequant,
-    float x_scale, float* __restrict__ y, Geometry g) {
+    float x_scale, float inv_y, void* __restrict__ y, Geometry g) {
   constexpr int P = AlgTraits<ALG>::P;
   constexpr Order<ALG> order{};
   constexpr int PPR = (P % 8 == 0) ? 8 : 4;  // points per round
@@ -431,26 +234,32 @@ __global__ __launch_bounds__(256, 4) void fused_product_output_kernel_b(
     inv8(c1, z[2 + 2 * g2]);
   }
 
-  // ---- store plan: 16 filters x 48 float pairs (or 96 floats) over 256 threads ----
-  constexpr int SLOTS = VEC2 ? 3 : 6;
+  // ---- store plan, fixed over the six output rows --------------------------------
+  // float32: 16 filters x 48 float pairs (or 96 floats) over 256 threads, lanes
+  // contiguous along (tile, o2).  int8: one (filter, tile) row of six bytes per thread.
+  constexpr int SLOTS = OUT8 ? 1 : (VEC2 ? 3 : 6);
   unsigned yo[SLOTS];
   int rows[SLOTS];
   int rd[SLOTS];
+  int cols8 = 0;
+  const unsigned esz = OUT8 ? 1u : 4u;
 #pragma unroll
   for (int i = 0; i < SLOTS; ++i) {
     const int e = i * 256 + threadIdx.x;
-    constexpr int per_k = VEC2 ? 48 : 96, per_t = VEC2 ? 3 : 6, step = VEC2 ? 2 : 1;
+    constexpr int per_k = OUT8 ? 16 : (VEC2 ? 48 : 96), per_t = OUT8 ? 1 : (VEC2 ? 3 : 6),
+                  step = VEC2 ? 2 : 1;
     const int kk = e / per_k, r = e - kk * per_k;
-    const int tl = r / per_t, o2 = step * (r - tl * per_t);
+    const int tl = r / per_t, o2 = OUT8 ? 0 : step * (r - tl * per_t);
     const int kc2 = kb * 16 + kk;
     const int ext = tile_ext[tl];
     const bool ok = kc2 < g.Cout && o2 < (ext >> 8);
     rows[i] = ok ? (ext & 0xff) : 0;
-    yo[i] = 4u * ((unsigned)tile_off[tl] + (unsigned)(kc2 * g.H) * g.W + o2);
+    yo[i] = esz * ((unsigned)tile_off[tl] + (unsigned)(kc2 * g.H) * g.W + o2);
     rd[i] = kk * kStageStride + tl * 6 + o2;
+    if constexpr (OUT8) cols8 = ext >> 8;
   }
   const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)y, 0, (int)(4u * (unsigned)(g.N * g.Cout) * (unsigned)(g.H * g.W)), kBufferFlags);
+      y, 0, (int)(esz * (unsigned)(g.N * g.Cout) * (unsigned)(g.H * g.W)), kBufferFlags);
   const int wr_base = (lane & 15) * kStageStride + (4 * wave + (lane >> 4)) * 6;
   // one barrier per output row: the staging block is double buffered
 #pragma unroll
@@ -466,32 +275,62 @@ __global__ __launch_bounds__(256, 4) void fused_product_output_kernel_b(
       *(v2f*)(st + wr_base + o2) = pr;
     }
     __syncthreads();
-    const unsigned yrow = 4u * (unsigned)(o1 * g.W);
+    const unsigned yrow = esz * (unsigned)(o1 * g.W);
+    if constexpr (OUT8) {
+      // ReLU + round-half-even + clamp to [0, 127]: adding 1.5 * 2^23 in one fused
+      // multiply-add leaves the integer in the low mantissa bits
+      constexpr float kMagic = 12582912.0f;
+      unsigned q[6];
 #pragma unroll
-    for (int i = 0; i < SLOTS; ++i) {
-      if constexpr (VEC2) {
-        const v2f val = *(const v2f*)(st + rd[i]);
-        if (o1 < rows[i]) __builtin_amdgcn_raw_buffer_store_b64(val, yres, yo[i], yrow, kStreamStore);
-      } else {
-        const float val = st[rd[i]];
-        if (o1 < rows[i])
-          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), yres, yo[i], yrow, kStreamStore);
+      for (int o2 = 0; o2 < 6; ++o2) {
+        float t = __fmaf_rn(st[rd[0] + o2], inv_y, kMagic);
+        t = __builtin_amdgcn_fmed3f(t, kMagic, kMagic + 127.0f);
+        q[o2] = __float_as_uint(t) & 0xffu;
+      }
+      if (o1 < rows[0]) {
+#pragma unroll
+        for (int o2 = 0; o2 < 6; o2 += 2) {
+          if constexpr (VEC2) {
+            if (o2 < cols8)
+              __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(q[o2] | (q[o2 + 1] << 8)), yres,
+                                                    yo[0] + o2, yrow, kStreamStore);
+          } else {
+            if (o2 < cols8)
+              __builtin_amdgcn_raw_buffer_store_b8((unsigned char)q[o2], yres, yo[0] + o2, yrow,
+                                                   kStreamStore);
+            if (o2 + 1 < cols8)
+              __builtin_amdgcn_raw_buffer_store_b8((unsigned char)q[o2 + 1], yres, yo[0] + o2 + 1,
+                                                   yrow, kStreamStore);
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < SLOTS; ++i) {
+        if constexpr (VEC2) {
+          const v2f val = *(const v2f*)(st + rd[i]);
+          if (o1 < rows[i]) __builtin_amdgcn_raw_buffer_store_b64(val, yres, yo[i], yrow, kStreamStore);
+        } else {
+          const float val = st[rd[i]];
+          if (o1 < rows[i])
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), yres, yo[i], yrow, kStreamStore);
+        }
       }
     }
   }
 }
 
-template <int ALG, bool VEC2>
+template <int ALG, bool VEC2, bool OUT8>
 static hipError_t launch_fused_alg(const Geometry& g, const void* V, const FilterViews& f,
-                                   float x_scale, float* y, hipStream_t s) {
+                                   float x_scale, float inv_y, void* y, hipStream_t s) {
   const int kblocks = g.Kp / 16;
   dim3 grid(g.Tp / 16, kblocks);
   dim3 block(256);
   const int8_t* v = (const int8_t*)V;
   const int8_t* u = (const int8_t*)f.U;
-#define SFC_LAUNCH_FUSED(KC)                                                                   \
-  hipLaunchKernelGGL((fused_product_output_kernel_b<ALG, KC, VEC2>), grid, block, 0, s, v, u,  \
-                     f.dequant, x_scale, y, g)
+#define SFC_LAUNCH_FUSED(KC)                                                                  \
+  hipLaunchKernelGGL((fused_product_output_kernel<ALG, KC, VEC2, OUT8>), grid, block, 0, s, v, \
+                     u, f.dequant, x_scale, inv_y, y, g)
   switch (g.Cp / 64) {
     case 1: SFC_LAUNCH_FUSED(1); break;
     case 2: SFC_LAUNCH_FUSED(2); break;
@@ -512,16 +351,23 @@ bool fused_supported(const Geometry& g) {
   return (kc == 1 || kc == 2 || kc == 4 || kc == 8) && ybytes < lim && vbytes < lim && ubytes < lim;
 }
 
-hipError_t launch_fused_product_output(int alg, const Geometry& g, const void* V,
-                                       const FilterViews& f, float x_scale, float* y,
+template <int ALG>
+static hipError_t launch_fused_out(int out, const Geometry& g, const void* V, const FilterViews& f,
+                                   float x_scale, float inv_y, void* y, hipStream_t s) {
+  const bool vec2 = (g.W % 2) == 0;  // pairs of an output row stay aligned in y
+  if (out == 2)
+    return vec2 ? launch_fused_alg<ALG, true, true>(g, V, f, x_scale, inv_y, y, s)
+                : launch_fused_alg<ALG, false, true>(g, V, f, x_scale, inv_y, y, s);
+  return vec2 ? launch_fused_alg<ALG, true, false>(g, V, f, x_scale, inv_y, y, s)
+              : launch_fused_alg<ALG, false, false>(g, V, f, x_scale, inv_y, y, s);
+}
+
+hipError_t launch_fused_product_output(int alg, int out, const Geometry& g, const void* V,
+                                       const FilterViews& f, float x_scale, float inv_y, void* y,
                                        hipStream_t s) {
-  if (!fused_supported(g)) return hipErrorNotSupported;
-  const bool vec2 = (g.W % 2) == 0;  // float pairs stay 8-byte aligned in y
-  if (alg == 0)
-    return vec2 ? launch_fused_alg<0, true>(g, V, f, x_scale, y, s)
-                : launch_fused_alg<0, false>(g, V, f, x_scale, y, s);
-  return vec2 ? launch_fused_alg<1, true>(g, V, f, x_scale, y, s)
-              : launch_fused_alg<1, false>(g, V, f, x_scale, y, s);
+  if (!fused_supported(g) || out == 1) return hipErrorNotSupported;
+  return alg == 0 ? launch_fused_out<0>(out, g, V, f, x_scale, inv_y, y, s)
+                  : launch_fused_out<1>(out, g, V, f, x_scale, inv_y, y, s);
 }
 
 }  // namespace sfc

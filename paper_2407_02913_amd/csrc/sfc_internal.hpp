@@ -36,10 +36,12 @@ hipError_t launch_input_transform_i8(int alg, const Geometry& g, const int8_t* x
                                      const float* inv_sx, hipStream_t s);
 hipError_t launch_product(int mode, const Geometry& g, const void* V, const void* U, int32_t* M,
                           hipStream_t s);
+// out: 0 float32, 1 int32 sums (exact mode), 2 int8 with ReLU (inv_y = 1 / output scale)
 hipError_t launch_output_transform(int alg, int mode, int out, const Geometry& g, const int32_t* M,
-                                   const FilterViews& f, float x_scale, void* y, hipStream_t s);
-hipError_t launch_fused_product_output(int alg, const Geometry& g, const void* V,
-                                       const FilterViews& f, float x_scale, float* y,
+                                   const FilterViews& f, float x_scale, float inv_y, void* y,
+                                   hipStream_t s);
+hipError_t launch_fused_product_output(int alg, int out, const Geometry& g, const void* V,
+                                       const FilterViews& f, float x_scale, float inv_y, void* y,
                                        hipStream_t s);
 // whether the fused kernel covers this geometry (Cin padded to 64, 128, 256 or 512)
 bool fused_supported(const Geometry& g);

@@ -313,8 +313,9 @@ template <int ALG, int MODE, int OUT>
 __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __restrict__ M,
                                                                const float* __restrict__ dequant,
                                                                const float* __restrict__ wscale,
-                                                               float x_scale, void* __restrict__ y,
-                                                               Geometry g, int kx) {
+                                                               float x_scale, float inv_y,
+                                                               void* __restrict__ y, Geometry g,
+                                                               int kx) {
   const int k = blockIdx.y * kx + (threadIdx.x % kx);
   const int t = blockIdx.x * (256 / kx) + (threadIdx.x / kx);
   if (k >= g.Cout || t >= g.T) return;
@@ -337,7 +338,18 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __
 #pragma unroll
       for (int o2 = 0; o2 < 6; ++o2) {
         const int w = 6 * tj + o2;
-        if (w < g.W) ((float*)y)[ybase + (size_t)h * g.W + w] = out[o1][o2] * x_scale;
+        if (w >= g.W) continue;
+        const float v = out[o1][o2] * x_scale;
+        if constexpr (OUT == 2) {
+          // next layer's activation: ReLU, one fused multiply-add that rounds to an
+          // integer (ties to even), clamp to [0, 127]
+          constexpr float kMagic = 12582912.0f;
+          float t = __fmaf_rn(v, inv_y, kMagic);
+          t = fminf(fmaxf(t, kMagic), kMagic + 127.0f);
+          ((int8_t*)y)[ybase + (size_t)h * g.W + w] = (int8_t)(__float_as_int(t) - 0x4B400000);
+        } else {
+          ((float*)y)[ybase + (size_t)h * g.W + w] = v;
+        }
       }
     }
   } else {
@@ -452,20 +464,23 @@ hipError_t launch_product(int mode, const Geometry& g, const void* V, const void
 }
 
 hipError_t launch_output_transform(int alg, int mode, int out, const Geometry& g, const int32_t* M,
-                                   const FilterViews& f, float x_scale, void* y, hipStream_t s) {
+                                   const FilterViews& f, float x_scale, float inv_y, void* y,
+                                   hipStream_t s) {
   int kx = 64;
   while (kx > g.Kp) kx >>= 1;  // Kp is a multiple of 16
   dim3 grid((g.T + (256 / kx) - 1) / (256 / kx), (g.Cout + kx - 1) / kx);
   dim3 block(256);
 #define SFC_LAUNCH_OUT(A, MD, O)                                                              \
   hipLaunchKernelGGL((output_transform_kernel<A, MD, O>), grid, block, 0, s, M, f.dequant,     \
-                     f.wscale, x_scale, y, g, kx)
+                     f.wscale, x_scale, inv_y, y, g, kx)
   if (alg == 0) {
-    if (mode == 1) SFC_LAUNCH_OUT(0, 1, 0);
+    if (mode == 1 && out == 2) SFC_LAUNCH_OUT(0, 1, 2);
+    else if (mode == 1) SFC_LAUNCH_OUT(0, 1, 0);
     else if (out == 1) SFC_LAUNCH_OUT(0, 0, 1);
     else SFC_LAUNCH_OUT(0, 0, 0);
   } else {
-    if (mode == 1) SFC_LAUNCH_OUT(1, 1, 0);
+    if (mode == 1 && out == 2) SFC_LAUNCH_OUT(1, 1, 2);
+    else if (mode == 1) SFC_LAUNCH_OUT(1, 1, 0);
     else if (out == 1) SFC_LAUNCH_OUT(1, 0, 1);
     else SFC_LAUNCH_OUT(1, 0, 0);
   }

@@ -190,3 +190,87 @@ def test_full_size_fused_against_oracle(binding, name):
     y_ref = oracle.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"])
     y = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", path="fused", sx=sx, sw=sw)
     assert rel_err(y, y_ref) <= F32_TOL
+
+
+# ---- int8 + ReLU epilogue (chaining stride-1 layers of a stack) ----------------------
+
+
+def check_i8_against_oracle(y8, y_ref, y_scale):
+    """Exact wherever the oracle's value is not within float32 reach of a rounding boundary."""
+    inv = float(oracle.reciprocal_f32(y_scale))
+    t = np.maximum(y_ref, 0.0) * inv
+    q_ref = np.clip(np.rint(t), 0, 127)
+    assert np.array_equal(q_ref.astype(np.int8), oracle.requantize_activation(y_ref, y_scale))
+    diff = y8.astype(np.int64) - q_ref.astype(np.int64)
+    slack = F32_TOL * np.abs(y_ref).max() * inv + 1e-6
+    near_boundary = np.abs(t - np.floor(t) - 0.5) <= slack
+    assert np.abs(diff).max() <= 1
+    assert np.all(diff[~near_boundary] == 0)
+    return float(np.count_nonzero(diff)) / diff.size
+
+
+@pytest.mark.parametrize("path", ["staged", "fused"])
+@pytest.mark.parametrize("shape", [(1, 16, 16, 32, 32), (2, 3, 5, 14, 14), (1, 4, 4, 7, 7), (3, 70, 40, 9, 20)])
+def test_int8_relu_output(binding, shape, path):
+    x, w, xs, ws = uniform_case(shape, 600 + sum(shape))
+    print("case i8", shape, path, flush=True)
+    sx = oracle.calibrate_act_scales(x)
+    sw = oracle.calibrate_filter_scales(w)
+    y_ref = oracle.conv_requant(x, w, sx, sw, xs, ws)
+    y_scale = float(np.float32(max(y_ref.max(), 1e-6) / 127.0 * 0.8))  # 0.8: some values clamp at 127
+    y8 = binding.conv2d(x, w, xs, ws, mode="requant", path=path, out="i8", sx=sx, sw=sw, y_scale=y_scale)
+    assert y8.dtype == np.int8 and y8.min() == 0 and y8.max() == 127
+    frac = check_i8_against_oracle(y8, y_ref, y_scale)
+    assert frac < 1e-3
+
+
+def test_int8_output_needs_its_scale(binding):
+    import torch
+
+    plan = binding.Plan(1, 16, 16, 8, 8, out="i8", path="fused")
+    with pytest.raises(binding.SfcError) as e:
+        binding.Plan(1, 16, 16, 8, 8, out="i8", mode="exact")
+    assert e.value.code == 2
+    p = plan.P
+    plan.set_point_scales(np.ones(p, np.float32), np.ones((p, 16), np.float32))
+    w = torch.zeros((16, 16, 3, 3), dtype=torch.int8, device="cuda")
+    fbuf = binding.device_buffer(plan.filter_bytes)
+    plan.transform_filter(w, np.ones(16, np.float32), fbuf)
+    x = torch.zeros((1, 16, 8, 8), dtype=torch.int8, device="cuda")
+    y = torch.zeros((1, 16, 8, 8), dtype=torch.int8, device="cuda")
+    ws = binding.device_buffer(plan.workspace_bytes)
+    with pytest.raises(binding.SfcError) as e:
+        plan.conv2d(x, 0.02, y, ws)
+    assert e.value.code == 4
+    plan.set_output_scale(0.5)
+    plan.conv2d(x, 0.02, y, ws)
+    torch.cuda.synchronize()
+    plan.close()
+
+
+def test_resnet18_shaped_stack_chained_with_int8_activations(binding):
+    """The 13 stride-1 3x3 layers, chained inside each resolution stage (reduced batch).
+
+    Every layer is checked against the oracle on the oracle's own input of that layer;
+    the library's self-chained run must then stay close to the oracle's chain."""
+    layers = synth.stack_layers(batch=8)
+    x_ref = x_gpu = None
+    prev = None
+    for idx, shape in enumerate(layers):
+        print("case stack layer", idx, shape.name, flush=True)
+        d = synth.make_layer(shape)
+        if prev is None or (shape.Cin, shape.H) != (prev.Cin, prev.H):
+            x_ref = x_gpu = d["x"]  # a new stage starts from fresh synthetic activations
+        sx = oracle.calibrate_act_scales(x_ref)
+        sw = oracle.calibrate_filter_scales(d["w"])
+        y_ref = oracle.conv_requant(x_ref, d["w"], sx, sw, d["x_scale"], d["w_scale"])
+        y_scale = float(np.float32(max(y_ref.max(), 1e-6) / 127.0))
+        kw = dict(mode="requant", path="fused", out="i8", sx=sx, sw=sw, y_scale=y_scale)
+        y8 = binding.conv2d(x_ref, d["w"], d["x_scale"], d["w_scale"], **kw)
+        check_i8_against_oracle(y8, y_ref, y_scale)
+        # self-chained: the library's own previous output is this layer's input
+        y8_chain = binding.conv2d(x_gpu, d["w"], d["x_scale"], d["w_scale"], **kw)
+        x_next_ref = oracle.requantize_activation(y_ref, y_scale)
+        delta = np.abs(y8_chain.astype(np.int64) - x_next_ref.astype(np.int64))
+        assert delta.max() <= 2 and np.mean(delta != 0) < 0.01
+        x_ref, x_gpu, prev = x_next_ref, y8_chain, shape
