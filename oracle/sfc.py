@@ -182,20 +182,89 @@ A_1D = np.array(
 )
 A_1D_DEN = 6
 
-TILE_OUT = 6  # M: outputs per tile edge
+# ---------------------------------------------------------------------------
+# Appendix A: SFC-6(7x7, 3x3) (also Sec. 4.2, whose printed A has two garbled
+# entries; the appendix print satisfies the bilinear identity and is used).
+# Rows 0..7 as above, acting on x1..x6 of nine samples; four correction rows:
+#   8: (x0 - x6) f0 -> output 0        9: (x7 - x1) f2 -> output 5
+#  10: (x7 - x1) f1 -> output 6       11: (x8 - x2) f2 -> output 6
+# Output 6 is the cyclic output 0 (same column of A) plus its two corrections:
+# the tile is stretched from 6 to 7 outputs with two more multiplications.
+# ---------------------------------------------------------------------------
+BT7_1D = np.array(
+    [
+        [0, 1, 1, 1, 1, 1, 1, 0, 0],
+        [0, 1, 1, 0, -1, -1, 0, 0, 0],
+        [0, 0, -1, -1, 0, 1, 1, 0, 0],
+        [0, 1, 0, -1, -1, 0, 1, 0, 0],
+        [0, 1, 0, -1, 1, 0, -1, 0, 0],
+        [0, 0, -1, 1, 0, -1, 1, 0, 0],
+        [0, 1, -1, 0, 1, -1, 0, 0, 0],
+        [0, 1, -1, 1, -1, 1, -1, 0, 0],
+        [1, 0, 0, 0, 0, 0, -1, 0, 0],
+        [0, -1, 0, 0, 0, 0, 0, 1, 0],
+        [0, -1, 0, 0, 0, 0, 0, 1, 0],
+        [0, 0, -1, 0, 0, 0, 0, 0, 1],
+    ],
+    dtype=np.int64,
+)
+
+G7_1D = np.array(
+    [
+        [1, 1, 1],
+        [0, 1, 1],
+        [-1, -1, 0],
+        [-1, 0, 1],
+        [-1, 0, 1],
+        [1, -1, 0],
+        [0, -1, 1],
+        [1, -1, 1],
+        [1, 0, 0],
+        [0, 0, 1],
+        [0, 1, 0],
+        [0, 0, 1],
+    ],
+    dtype=np.int64,
+)
+
+A7_1D = np.array(
+    [
+        [1, 1, 1, 1, 1, 1, 1],
+        [2, 1, -1, -2, -1, 1, 2],
+        [-1, 1, 2, 1, -1, -2, -1],
+        [-1, -2, -1, 1, 2, 1, -1],
+        [1, -2, 1, 1, -2, 1, 1],
+        [1, 1, -2, 1, 1, -2, 1],
+        [-2, 1, 1, -2, 1, 1, -2],
+        [-1, 1, -1, 1, -1, 1, -1],
+        [6, 0, 0, 0, 0, 0, 0],
+        [0, 0, 0, 0, 0, 6, 0],
+        [0, 0, 0, 0, 0, 0, 6],
+        [0, 0, 0, 0, 0, 0, 6],
+    ],
+    dtype=np.int64,
+)
+
+TILE_OUT = 6  # M of the primary variant SFC-6(6x6,3x3)
 TILE_IN = 8  # M + R - 1
 KERNEL = 3  # R
-REAL_ROWS = (0, 7, 8, 9)
-COMPLEX_GROUPS = ((1, 2, 3), (4, 5, 6))  # (a0 row, a1 row, a0+a1 row)
+COMPLEX_GROUPS = ((1, 2, 3), (4, 5, 6))  # (a0 row, a1 row, a0+a1 row), both variants
 
 
-def sfc6_1d():
-    """The three 1-D matrices of SFC-6(6,3): (B^T 10x8, G 10x3, A numerators 10x6, 6)."""
-    return BT_1D.copy(), G_1D.copy(), A_1D.copy(), A_1D_DEN
+def sfc6_1d(m: int = 6):
+    """The three 1-D matrices of SFC-6(m,3), m = 6 or 7: (B^T, G, A numerators, 6).
+
+    m = 6: B^T 10x8, G 10x3, A 10x6.  m = 7: B^T 12x9, G 12x3, A 12x7.
+    """
+    if m == 6:
+        return BT_1D.copy(), G_1D.copy(), A_1D.copy(), A_1D_DEN
+    if m == 7:
+        return BT7_1D.copy(), G7_1D.copy(), A7_1D.copy(), A_1D_DEN
+    raise ValueError(m)
 
 
-def integrate_1d():
-    """Re-derive B^T, G, A of SFC-6(6,3) from Sec. 4.1-4.2 instead of reading them.
+def integrate_1d(m: int = 6):
+    """Re-derive B^T, G, A of SFC-6(m,3), m = 6 or 7, from Sec. 4.1-4.2 instead of reading them.
 
     Steps, in the paper's order:
       1. forward SFT-6 (F_6) of the six inner samples x1..x6        (Eq. DFT6)
@@ -209,9 +278,10 @@ def integrate_1d():
          cyclic convolution into linear-convolution outputs          (Sec. 4.2)
     Returns (B^T, G, A numerators, 6) in the same row order as Appendix A.
     """
-    bt = np.zeros((10, 8), dtype=np.int64)
-    g = np.zeros((10, 3), dtype=np.int64)
-    a = np.zeros((10, 6), dtype=np.int64)
+    rows = 10 if m == 6 else 12
+    bt = np.zeros((rows, m + 2), dtype=np.int64)
+    g = np.zeros((rows, 3), dtype=np.int64)
+    a = np.zeros((rows, m), dtype=np.int64)
 
     # powers of s as (c0, c1) with s^n = c0 + c1 s, using s^2 = s - 1
     def s_pow(n):
@@ -239,12 +309,12 @@ def integrate_1d():
         bt[rs] = bt[r0] + bt[r1]
         g[rs] = g[r0] + g[r1]
     # 4. inverse: y = sum_c IF6[c] * component_c, o0 = m0 - m1, o1 = m2 - m0
-    a[0] = IF6[0]
-    a[7] = IF6[5]
+    a[0, :6] = IF6[0]
+    a[7, :6] = IF6[5]
     for (r0, r1, rs), (c0, c1) in zip(COMPLEX_GROUPS, ((1, 2), (3, 4))):
-        a[r0] = IF6[c0] - IF6[c1]
-        a[r1] = -IF6[c0]
-        a[rs] = IF6[c1]
+        a[r0, :6] = IF6[c0] - IF6[c1]
+        a[r1, :6] = -IF6[c0]
+        a[rs, :6] = IF6[c1]
     # 5. corrections: output 0 wraps x6 where x0 is wanted (times f0); output 5
     # wraps x1 where x7 is wanted (times f2).  One multiplication each, and the
     # products are not divided by 6.
@@ -254,6 +324,16 @@ def integrate_1d():
     bt[9, 7], bt[9, 1] = 1, -1
     g[9, 2] = 1
     a[9, 5] = 6
+    if m == 7:
+        # a seventh output: the cyclic result wraps output 6 onto output 0
+        # (x6 f0 + x1 f1 + x2 f2), where x7 f1 and x8 f2 are wanted
+        a[:8, 6] = a[:8, 0]
+        bt[10, 7], bt[10, 1] = 1, -1
+        g[10, 1] = 1
+        a[10, 6] = 6
+        bt[11, 8], bt[11, 2] = 1, -1
+        g[11, 2] = 1
+        a[11, 6] = 6
     return bt, g, a, 6
 
 
@@ -262,18 +342,18 @@ def integrate_1d():
 # ---------------------------------------------------------------------------
 
 
-def nested_2d():
-    """Nested (Kronecker) 2-D form: 100 points per tile.
+def nested_2d(m: int = 6):
+    """Nested (Kronecker) 2-D form: 100 points per 6x6 tile, 144 per 7x7 tile.
 
-    Returns (B2 [100,64], G2 [100,9], A2 numerators [100,36], 36); point
-    p = 10*p1 + p2 with p1 along the vertical (row) axis of the tile.
+    Returns (B2 [P,(m+2)^2], G2 [P,9], A2 numerators [P,m^2], 36); point
+    p = rows*p1 + p2 with p1 along the vertical (row) axis of the tile.
     """
-    bt, g, a, den = sfc6_1d()
+    bt, g, a, den = sfc6_1d(m)
     return np.kron(bt, bt), np.kron(g, g), np.kron(a, a), den * den
 
 
-def hermitian_2d():
-    """88-point 2-D form ("when Hermitian symmetry is fully considered", Appendix A).
+def hermitian_2d(m: int = 6):
+    """88-point (6x6) / 132-point (7x7) 2-D form ("when Hermitian symmetry is fully considered", Appendix A).
 
     The paper states the count only.  Construction used here:
 
@@ -297,17 +377,19 @@ def hermitian_2d():
           o00 = Uo0 + o11,   o10 = Vo1 + o01
       and the tile output is sum_ij (c_i (x) c_j) o_ij with c_0 = -A[a1 row],
       c_1 = A[sum row] (the iF_6 rows recovered from the folded A).
-    Count: 64 + 4*6 = 88.  Order: the 64 kept points in nested order, then the
-    blocks (k1,k2) = (1,1), (1,2), (2,1), (2,2), six points each in the order
-    U0, U1, U0+U1, V0, V1, V0+V1.
+    Count: 64 + 4*6 = 88 for the 6x6 tile; 108 + 24 = 132 for the 7x7 tile (the
+    same construction: only the number of correction rows differs).  Order: the
+    kept points in nested order, then the blocks (k1,k2) = (1,1), (1,2), (2,1),
+    (2,2), six points each in the order U0, U1, U0+U1, V0, V1, V0+V1.
 
-    Returns (B2 [88,64], G2 [88,9], A2 numerators [88,36], 36).
+    Returns (B2 [P,(m+2)^2], G2 [P,9], A2 numerators [P,m^2], 36).
     """
-    bt, g, a, den = sfc6_1d()
+    bt, g, a, den = sfc6_1d(m)
+    nrows = bt.shape[0]
     complex_rows = {r for grp in COMPLEX_GROUPS for r in grp}
     b_rows, g_rows, a_rows = [], [], []
-    for p1 in range(10):
-        for p2 in range(10):
+    for p1 in range(nrows):
+        for p2 in range(nrows):
             if p1 in complex_rows and p2 in complex_rows:
                 continue
             b_rows.append(np.kron(bt[p1], bt[p2]))
@@ -340,7 +422,7 @@ def hermitian_2d():
             g_rows += six_points(g, grp1, grp2)
             c1 = (-a[grp1[1]], a[grp1[2]])
             c2 = (-a[grp2[1]], a[grp2[2]])
-            block = np.zeros((6, 36), dtype=np.int64)
+            block = np.zeros((6, m * m), dtype=np.int64)
             for (i, j), comb in o_x3.items():
                 block += np.outer(comb, np.kron(c1[i], c2[j]))
             assert np.all(block % 3 == 0), "thirds must cancel"
@@ -353,21 +435,32 @@ def hermitian_2d():
     )
 
 
-_ALGORITHMS = {"6x6_p88": hermitian_2d, "6x6_p100": nested_2d}
+_ALGORITHMS = {
+    "6x6_p88": (hermitian_2d, 6),
+    "6x6_p100": (nested_2d, 6),
+    "7x7_p132": (hermitian_2d, 7),
+    "7x7_p144": (nested_2d, 7),
+}
 
 
 def algorithm(name: str):
-    """(B2, G2, A2 numerators, denominator) for "6x6_p88" or "6x6_p100"."""
-    return _ALGORITHMS[name]()
+    """(B2, G2, A2 numerators, denominator) for "6x6_p88", "6x6_p100", "7x7_p132", "7x7_p144"."""
+    build, m = _ALGORITHMS[name]
+    return build(m)
+
+
+def tile_out(name: str) -> int:
+    """Outputs per tile edge (M of SFC-6(MxM,3x3))."""
+    return _ALGORITHMS[name][1]
 
 
 def multiplications_per_tile(name: str) -> int:
-    """Real multiplications per 6x6 output tile and (Cin, Cout) pair: one per point."""
+    """Real multiplications per output tile and (Cin, Cout) pair: one per point."""
     return algorithm(name)[0].shape[0]
 
 
-def direct_multiplications_per_tile() -> int:
-    return TILE_OUT * TILE_OUT * KERNEL * KERNEL
+def direct_multiplications_per_tile(m: int = TILE_OUT) -> int:
+    return m * m * KERNEL * KERNEL
 
 
 # ---------------------------------------------------------------------------
@@ -417,36 +510,43 @@ def dequantize(acc: np.ndarray, x_scale, w_scale) -> np.ndarray:
 # ---------------------------------------------------------------------------
 
 
-def tile_grid(h: int, w: int):
-    return -(-h // TILE_OUT), -(-w // TILE_OUT)
+def tile_grid(h: int, w: int, m: int = TILE_OUT):
+    return -(-h // m), -(-w // m)
 
 
-def gather_tiles(x: np.ndarray) -> np.ndarray:
-    """[N,C,H,W] -> tiles [T, C, 8, 8], T = N*th*tw, t = (n*th + ti)*tw + tj.
+def gather_tiles(x: np.ndarray, m: int = TILE_OUT) -> np.ndarray:
+    """[N,C,H,W] -> tiles [T, C, m+2, m+2], T = N*th*tw, t = (n*th + ti)*tw + tj.
 
-    Tile (ti,tj) covers input rows 6*ti-1 .. 6*ti+6 and columns 6*tj-1 .. 6*tj+6.
+    Tile (ti,tj) covers input rows m*ti-1 .. m*ti+m and columns m*tj-1 .. m*tj+m.
     """
     n, c, h, w = x.shape
-    th, tw = tile_grid(h, w)
-    xp = np.zeros((n, c, TILE_OUT * th + 2, TILE_OUT * tw + 2), dtype=np.int64)
+    th, tw = tile_grid(h, w, m)
+    xp = np.zeros((n, c, m * th + 2, m * tw + 2), dtype=np.int64)
     xp[:, :, 1 : 1 + h, 1 : 1 + w] = x
-    tiles = np.empty((n, th, tw, c, TILE_IN, TILE_IN), dtype=np.int64)
+    tiles = np.empty((n, th, tw, c, m + 2, m + 2), dtype=np.int64)
     for ti in range(th):
         for tj in range(tw):
-            tiles[:, ti, tj] = xp[:, :, 6 * ti : 6 * ti + 8, 6 * tj : 6 * tj + 8]
-    return tiles.reshape(n * th * tw, c, TILE_IN, TILE_IN)
+            tiles[:, ti, tj] = xp[:, :, m * ti : m * ti + m + 2, m * tj : m * tj + m + 2]
+    return tiles.reshape(n * th * tw, c, m + 2, m + 2)
 
 
 def scatter_tiles(o: np.ndarray, n: int, h: int, w: int) -> np.ndarray:
-    """Tile outputs [T, K, 6, 6] -> [N, K, H, W], dropping the ragged surplus."""
-    th, tw = tile_grid(h, w)
+    """Tile outputs [T, K, m, m] -> [N, K, H, W], dropping the ragged surplus."""
+    m = o.shape[-1]
+    th, tw = tile_grid(h, w, m)
     k = o.shape[1]
-    o = o.reshape(n, th, tw, k, TILE_OUT, TILE_OUT)
-    full = np.empty((n, k, TILE_OUT * th, TILE_OUT * tw), dtype=o.dtype)
+    o = o.reshape(n, th, tw, k, m, m)
+    full = np.empty((n, k, m * th, m * tw), dtype=o.dtype)
     for ti in range(th):
         for tj in range(tw):
-            full[:, :, 6 * ti : 6 * ti + 6, 6 * tj : 6 * tj + 6] = o[:, ti, tj]
+            full[:, :, m * ti : m * ti + m, m * tj : m * tj + m] = o[:, ti, tj]
     return np.ascontiguousarray(full[:, :, :h, :w])
+
+
+def _isqrt(n: int) -> int:
+    r = int(round(n**0.5))
+    assert r * r == n
+    return r
 
 
 # ---------------------------------------------------------------------------
@@ -456,9 +556,10 @@ def scatter_tiles(o: np.ndarray, n: int, h: int, w: int) -> np.ndarray:
 
 def input_transform(x: np.ndarray, b2: np.ndarray) -> np.ndarray:
     """V[p,t,c] = sum_ij B2[p,(i,j)] * tile[t,c,i,j]  (B^T x B, additions only)."""
-    tiles = gather_tiles(x)
+    n_in = _isqrt(b2.shape[1])
+    tiles = gather_tiles(x, n_in - 2)
     t, c = tiles.shape[:2]
-    v = b2 @ tiles.reshape(t * c, 64).T  # int64, exact
+    v = b2 @ tiles.reshape(t * c, n_in * n_in).T  # int64, exact
     return v.reshape(b2.shape[0], t, c)
 
 
@@ -480,9 +581,10 @@ def pointwise_product(v: np.ndarray, u: np.ndarray) -> np.ndarray:
 def output_transform_exact(m: np.ndarray, a2: np.ndarray, den: int, n: int, h: int, w: int):
     """acc = (A2^T M) / den, which must divide exactly; returns int64 [N,K,H,W]."""
     p, t, k = m.shape
-    o = (a2.T @ m.reshape(p, t * k)).reshape(36, t, k)
+    mo = _isqrt(a2.shape[1])
+    o = (a2.T @ m.reshape(p, t * k)).reshape(mo * mo, t, k)
     assert np.all(o % den == 0), "exact SFC output must be divisible by the denominator"
-    o = (o // den).transpose(1, 2, 0).reshape(t, k, TILE_OUT, TILE_OUT)
+    o = (o // den).transpose(1, 2, 0).reshape(t, k, mo, mo)
     return scatter_tiles(o, n, h, w)
 
 
@@ -548,8 +650,9 @@ def output_transform_dequant(m, a2, den, sx_pt, sw_pt, x_scale, w_scale, n, h, w
     p, t, k = m.shape
     scale = np.asarray(sx_pt, dtype=np.float64)[:, None] * np.asarray(sw_pt, dtype=np.float64)
     md = m.astype(np.float64) * scale[:, None, :]
-    o = (a2.T.astype(np.float64) @ md.reshape(p, t * k)).reshape(36, t, k)
-    o = o.transpose(1, 2, 0).reshape(t, k, TILE_OUT, TILE_OUT)
+    mo = _isqrt(a2.shape[1])
+    o = (a2.T.astype(np.float64) @ md.reshape(p, t * k)).reshape(mo * mo, t, k)
+    o = o.transpose(1, 2, 0).reshape(t, k, mo, mo)
     y = scatter_tiles(o, n, h, w)
     ws = np.broadcast_to(np.asarray(w_scale, dtype=np.float64).reshape(-1), (k,))
     return y * (float(x_scale) * ws / den)[None, :, None, None]

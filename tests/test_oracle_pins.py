@@ -372,3 +372,93 @@ def test_calibrated_scales():
 def test_requantize_activation():
     y = np.array([-1.0, 0.0, 0.25, 0.75, 1.25, 1.3, 100.0])
     assert list(sfc.requantize_activation(y, 0.5)) == [0, 0, 0, 2, 2, 3, 127]
+
+
+# ---- SFC-6(7x7,3x3): the tile stretched to seven outputs (Sec. 4.2, Appendix A) ----
+
+GOLDEN7 = os.path.join(os.path.dirname(__file__), "golden", "sfc6_7x7_3x3_printed.txt")
+
+
+def expected_1d_m(m, den=6):
+    ref = np.zeros((m, m + 2, 3), dtype=np.int64)
+    for o in range(m):
+        for r in range(3):
+            ref[o, o + r, r] = den
+    return ref
+
+
+def test_7x7_printed_matrices_and_the_garbled_main_text_print():
+    gold = load_golden(GOLDEN7)
+    bt, g, a, den = sfc.sfc6_1d(7)
+    assert den == 6
+    assert np.array_equal(gold["BT"], bt) and np.array_equal(gold["G"], g)
+    assert np.array_equal(gold["A_times_6"], a)
+    assert np.array_equal(bilinear_1d(a, bt, g), expected_1d_m(7))
+    bad = bilinear_1d(gold["A_times_6_main_text"], bt, g)
+    assert np.count_nonzero(bad != expected_1d_m(7)) > 0
+    diff = np.argwhere(gold["A_times_6_main_text"] != a)
+    assert [tuple(d) for d in diff] == [(2, 2), (6, 2)]
+
+
+def test_7x7_matrices_rederived_equal_the_print():
+    bt, g, a, _ = sfc.sfc6_1d(7)
+    bt2, g2, a2, _ = sfc.integrate_1d(7)
+    assert np.array_equal(bt, bt2) and np.array_equal(g, g2) and np.array_equal(a, a2)
+    # rows 0..7 and the first two corrections are those of the 6x6 tile, on nine samples
+    bt6, g6, a6, _ = sfc.sfc6_1d(6)
+    assert np.array_equal(bt[:10, :8], bt6) and np.array_equal(g[:10], g6)
+    assert np.array_equal(a[:10, :6], a6)
+
+
+def test_7x7_1d_brute_force():
+    bt, g, a, den = sfc.sfc6_1d(7)
+    rng = np.random.default_rng(15)
+    for _ in range(50):
+        x = rng.integers(-128, 128, size=9)
+        f = rng.integers(-128, 128, size=3)
+        y = a.T @ ((g @ f) * (bt @ x))
+        brute = [sum(int(x[o + r]) * int(f[r]) for r in range(3)) for o in range(7)]
+        assert np.array_equal(y, den * np.array(brute))
+
+
+@pytest.mark.parametrize("alg,points", [("7x7_p144", 144), ("7x7_p132", 132)])
+def test_7x7_2d_bilinear_identity_and_counts(alg, points):
+    c = load_golden(GOLDEN7)["counts"]
+    b2, g2, a2, den = sfc.algorithm(alg)
+    assert sfc.tile_out(alg) == 7
+    assert b2.shape == (points, 81) and g2.shape == (points, 9) and a2.shape == (points, 49)
+    t = np.einsum("po,pi,pr->oir", a2, b2, g2).reshape(7, 7, 9, 9, 3, 3)
+    ref = np.zeros_like(t)
+    for o1, o2, r1, r2 in itertools.product(range(7), range(7), range(3), range(3)):
+        ref[o1, o2, o1 + r1, o2 + r2, r1, r2] = den
+    assert np.array_equal(t, ref)
+    assert set(np.unique(b2)) <= {-1, 0, 1} and set(np.unique(g2)) <= {-1, 0, 1}
+    assert points == c["nested_multiplications" if alg.endswith("144") else "hermitian_multiplications"]
+    if points == 132:
+        direct = sfc.direct_multiplications_per_tile(7)
+        assert direct == c["direct_multiplications"]
+        assert round(10000 * points / direct) == c["complexity_percent_x100"]  # 29.93 %
+
+
+@pytest.mark.parametrize("alg", ["7x7_p144", "7x7_p132"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_7x7_exact_sfc_equals_direct_conv(alg, shape):
+    n, c, k, h, w = shape
+    rng = np.random.default_rng(hash(shape) % 2**32 + 1)
+    x = rng.integers(-128, 128, size=(n, c, h, w)).astype(np.int8)
+    wt = rng.integers(-128, 128, size=(k, c, 3, 3)).astype(np.int8)
+    assert np.array_equal(sfc.conv_exact(x, wt, alg), sfc.direct_conv(x, wt))
+
+
+def test_7x7_requant_reduces_to_exact_and_tiles_imagenet_shapes_without_waste():
+    rng = np.random.default_rng(16)
+    x = rng.integers(-1, 2, size=(1, 3, 14, 7)).astype(np.int8)
+    w = rng.integers(-2, 3, size=(4, 3, 3, 3)).astype(np.int8)
+    for alg in ("7x7_p144", "7x7_p132"):
+        p = sfc.multiplications_per_tile(alg)
+        y = sfc.conv_requant(x, w, np.ones(p, np.float32), np.ones((p, 4), np.float32), 0.125,
+                             np.float32(0.5), alg)
+        ref = sfc.dequantize(sfc.direct_conv(x, w), 0.125, np.float32(0.5))
+        assert np.allclose(y, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
+    for hw in (56, 28, 14, 7):  # Sec. 4.2: feature maps of 224x224 models have the factor 7
+        assert hw % 7 == 0 and sfc.tile_grid(hw, hw, 7) == (hw // 7, hw // 7)
