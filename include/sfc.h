@@ -1,6 +1,6 @@
 /*
  * sfc.h -- C ABI of the MI355X (gfx950) library for quantized 3x3 convolution by
- * Symbolic Fourier Convolution, SFC-6(6x6,3x3) (arXiv 2407.02913).
+ * Symbolic Fourier Convolution, SFC-6(6x6,3x3) and SFC-6(7x7,3x3) (arXiv 2407.02913).
  *
  * The library computes, for int8 activations x[N,Cin,H,W] and int8 filters
  * w[Cout,Cin,3,3] (stride 1, zero padding 1, cross-correlation),
@@ -8,9 +8,10 @@
  *      y = A^T [ (G f G^T) . (B^T x B) ] A        summed over Cin      (Eq. 1)
  *
  * with the addition-only symbolic DFT-6 transforms of Sec. 4.1, the correction
- * terms of Sec. 4.2 and the integrated matrices of Appendix A, on 6x6 output
- * tiles (8x8 input tiles).  Per tile and (Cin,Cout) pair it spends P = 88
- * multiplications (Hermitian form) or P = 100 (nested form), Appendix A.
+ * terms of Sec. 4.2 and the integrated matrices of Appendix A, on MxM output
+ * tiles ((M+2)x(M+2) input tiles), M = 6 or 7.  Per tile and (Cin,Cout) pair it
+ * spends P = 88 / 132 multiplications (Hermitian form, M = 6 / 7) or P = 100 / 144
+ * (nested form), Appendix A.
  *
  * Conventions
  *  - "dev" pointers are device (HBM) addresses on the current HIP device, "host"
@@ -48,8 +49,10 @@ typedef enum {
 
 /* Which 2-D point set realizes the element-wise product of Eq. (1), Appendix A. */
 typedef enum {
-  SFC_ALG_6X6_P88 = 0, /* Hermitian symmetry fully used: 88 multiplications per tile */
-  SFC_ALG_6X6_P100 = 1 /* nested (Kronecker) form: 100 multiplications per tile */
+  SFC_ALG_6X6_P88 = 0,  /* SFC-6(6x6,3x3), Hermitian symmetry fully used: 88 multiplications per tile */
+  SFC_ALG_6X6_P100 = 1, /* SFC-6(6x6,3x3), nested (Kronecker) form: 100 multiplications */
+  SFC_ALG_7X7_P132 = 2, /* SFC-6(7x7,3x3) (Sec. 4.2, Appendix A), Hermitian form: 132 multiplications */
+  SFC_ALG_7X7_P144 = 3  /* SFC-6(7x7,3x3), nested form: 144 multiplications */
 } sfc_alg;
 
 typedef enum {
@@ -88,13 +91,13 @@ typedef struct {
 } sfc_conv_desc;
 
 /* Host only.  Validates the description and derives the tile grid
- * (ceil(H/6) x ceil(W/6) tiles per image) and all buffer sizes.  No device work.
+ * (ceil(H/M) x ceil(W/M) tiles per image) and all buffer sizes.  No device work.
  * *out receives a plan to be released with sfc_plan_destroy. */
 sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out);
 void sfc_plan_destroy(sfc_plan_t* plan);
 
 /* Sizes the caller must allocate (device bytes) and the derived counts:
- * P = multiplications per tile (88 or 100), tiles = N*ceil(H/6)*ceil(W/6).
+ * P = multiplications per tile (88, 100, 132 or 144), tiles = N*ceil(H/M)*ceil(W/M).
  * Any output pointer may be NULL. */
 sfc_status sfc_plan_sizes(const sfc_plan_t* plan, size_t* filter_bytes, size_t* workspace_bytes,
                           int32_t* P, int64_t* tiles);
@@ -102,10 +105,11 @@ sfc_status sfc_plan_sizes(const sfc_plan_t* plan, size_t* filter_bytes, size_t* 
 /* Requantized mode: the transform-domain scales of Sec. 5, copied into the plan.
  * sx_host[P]: one activation scale per point (s_Tx).  sw_host[P*Cout], laid out
  * [P][Cout]: one filter scale per point and output channel (s_Tf).  All > 0.
- * Point order: for P = 100, p = 10*p1 + p2 over the rows of the printed 1-D
- * matrices (p1 vertical); for P = 88, first the 64 nested points that are not
- * complex x complex, in that same order, then for (k1,k2) = (1,1),(1,2),(2,1),(2,2)
- * the six points U0,U1,U0+U1,V0,V1,V0+V1 of the two independent 2-D frequencies.
+ * Point order, with R = 10 (M = 6) or 12 (M = 7) rows in the printed 1-D matrices:
+ * nested form, p = R*p1 + p2 (p1 vertical); Hermitian form, first the R*R - 36
+ * nested points that are not complex x complex, in that same order, then for
+ * (k1,k2) = (1,1),(1,2),(2,1),(2,2) the six points U0,U1,U0+U1,V0,V1,V0+V1 of the
+ * two independent 2-D frequencies.
  * Must precede sfc_transform_filter. */
 sfc_status sfc_set_point_scales(sfc_plan_t* plan, const float* sx_host, const float* sw_host);
 

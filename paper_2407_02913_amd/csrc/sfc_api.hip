@@ -66,7 +66,7 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   *out = nullptr;
   const sfc_conv_desc& d = *desc;
   if (d.N <= 0 || d.Cin <= 0 || d.Cout <= 0 || d.H <= 0 || d.W <= 0) return SFC_EINVAL;
-  if (d.alg != SFC_ALG_6X6_P88 && d.alg != SFC_ALG_6X6_P100) return SFC_EINVAL;
+  if (d.alg < SFC_ALG_6X6_P88 || d.alg > SFC_ALG_7X7_P144) return SFC_EINVAL;
   if (d.mode != SFC_MODE_EXACT && d.mode != SFC_MODE_REQUANT_I8) return SFC_EINVAL;
   if (d.out != SFC_OUT_F32 && d.out != SFC_OUT_I32 && d.out != SFC_OUT_I8_RELU) return SFC_EINVAL;
   if (d.path != SFC_PATH_STAGED && d.path != SFC_PATH_FUSED) return SFC_EINVAL;
@@ -79,8 +79,10 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
 
   Geometry g;
   g.N = d.N; g.Cin = d.Cin; g.Cout = d.Cout; g.H = d.H; g.W = d.W;
-  g.th = (d.H + 5) / 6;
-  g.tw = (d.W + 5) / 6;
+  g.alg = d.alg;
+  const int mt = (d.alg == SFC_ALG_7X7_P132 || d.alg == SFC_ALG_7X7_P144) ? 7 : 6;
+  g.th = (d.H + mt - 1) / mt;
+  g.tw = (d.W + mt - 1) / mt;
   const int64_t strips = (int64_t)d.N * g.th;
   const int64_t T = strips * g.tw;
   if (T > (1ll << 30)) return SFC_EUNSUPPORTED;
@@ -89,7 +91,8 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   g.Tp = (int)((T + 15) / 16 * 16);
   g.Cp = (d.Cin + 63) / 64 * 64;
   g.Kp = (d.Cout + 15) / 16 * 16;
-  g.P = d.alg == SFC_ALG_6X6_P88 ? 88 : 100;
+  static const int kPoints[4] = {88, 100, 132, 144};
+  g.P = kPoints[d.alg];
 
   if (d.path == SFC_PATH_FUSED && !sfc::fused_supported(g)) return SFC_EUNSUPPORTED;
 
@@ -210,7 +213,7 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
                      table_bytes, hipMemcpyHostToDevice, s) != hipSuccess)
     return SFC_EHIP;
   const FilterViews f = views(plan, filter_dev);
-  if (sfc::launch_filter_transform(plan->d.alg, plan->d.mode, g, w_dev, f, s) != hipSuccess)
+  if (sfc::launch_filter_transform(plan->d.mode, g, w_dev, f, s) != hipSuccess)
     return SFC_EHIP;
   plan->filter_dev = filter_dev;
   plan->filter_ready = true;
@@ -234,12 +237,12 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
   char* ws = static_cast<char*>(workspace_dev);
   void* V = ws + plan->off_V;
   if (stage_mask & SFC_STAGE_INPUT) {
-    if (sfc::launch_input_transform(plan->d.alg, plan->d.mode, g, x_dev, V, f.inv_sx, s) !=
+    if (sfc::launch_input_transform(plan->d.mode, g, x_dev, V, f.inv_sx, s) !=
         hipSuccess)
       return SFC_EHIP;
   }
   if (fused) {
-    if (tail && sfc::launch_fused_product_output(plan->d.alg, plan->d.out, g, V, f, x_scale,
+    if (tail && sfc::launch_fused_product_output(plan->d.out, g, V, f, x_scale,
                                                  plan->inv_y, y_dev, s) != hipSuccess)
       return SFC_EHIP;
     return SFC_OK;
@@ -249,7 +252,7 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
     if (sfc::launch_product(plan->d.mode, g, V, f.U, M, s) != hipSuccess) return SFC_EHIP;
   }
   if (stage_mask & SFC_STAGE_OUTPUT) {
-    if (sfc::launch_output_transform(plan->d.alg, plan->d.mode, plan->d.out, g, M, f, x_scale,
+    if (sfc::launch_output_transform(plan->d.mode, plan->d.out, g, M, f, x_scale,
                                      plan->inv_y, y_dev, s) != hipSuccess)
       return SFC_EHIP;
   }
@@ -332,7 +335,7 @@ sfc_status sfc_calibrate_act_scales(const sfc_plan_t* plan, const int8_t* x_dev,
   g.Tp = (g.T + 15) / 16 * 16;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int32_t* maxima = static_cast<int32_t*>(workspace_dev);
-  if (sfc::launch_act_absmax(plan->d.alg, g, x_dev, maxima, s) != hipSuccess) return SFC_EHIP;
+  if (sfc::launch_act_absmax(g, x_dev, maxima, s) != hipSuccess) return SFC_EHIP;
   return maxima_to_scales(maxima, g.P, s, sx_host_out);
 }
 
@@ -342,7 +345,7 @@ sfc_status sfc_calibrate_filter_scales(const sfc_plan_t* plan, const int8_t* w_d
   if (!aligned16(w_dev) || !aligned16(workspace_dev)) return SFC_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int32_t* maxima = static_cast<int32_t*>(workspace_dev);
-  if (sfc::launch_filter_absmax(plan->d.alg, plan->g, w_dev, maxima, s) != hipSuccess)
+  if (sfc::launch_filter_absmax(plan->g, w_dev, maxima, s) != hipSuccess)
     return SFC_EHIP;
   return maxima_to_scales(maxima, (size_t)plan->g.P * plan->g.Cout, s, sw_host_out);
 }

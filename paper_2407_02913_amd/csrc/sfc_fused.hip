@@ -25,40 +25,28 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v2f __attribute__((ext_vector_type(2)));
 
-// canonical index of the kept nested point (r1, r2) in the 88-point order
-__host__ __device__ constexpr int kept_index(int r1, int r2) {
-  int n = 0;
-  for (int a = 0; a < 10; ++a)
-    for (int b = 0; b < 10; ++b) {
-      if (row_is_complex(a) && row_is_complex(b)) continue;
-      if (a == r1 && b == r2) return n;
-      ++n;
-    }
-  return -1;
-}
-
 // Processing order (canonical point indices), grouped by horizontal class.
 template <int ALG>
 struct Order {
-  static constexpr int P = AlgTraits<ALG>::P;
+  using Tr = AlgTraits<ALG>;
+  static constexpr int P = Tr::P, NR = Tr::NR, NREAL = Tr::NREAL;
   int pt[P];
   constexpr Order() : pt{} {
-    constexpr int real_rows[4] = {0, 7, 8, 9};
     int n = 0;
-    // real columns: all ten vertical rows
-    for (int j = 0; j < 4; ++j)
-      for (int r1 = 0; r1 < 10; ++r1)
-        pt[n++] = ALG == 1 ? 10 * r1 + real_rows[j] : kept_index(r1, real_rows[j]);
+    // real columns: all vertical rows
+    for (int j = 0; j < NREAL; ++j)
+      for (int r1 = 0; r1 < NR; ++r1)
+        pt[n++] = Tr::kHermitian ? kept_index<NR>(r1, real_row(j)) : NR * r1 + real_row(j);
     // complex column groups
     for (int g2 = 0; g2 < 2; ++g2) {
-      if (ALG == 1) {
-        for (int r1 = 0; r1 < 10; ++r1)
-          for (int i = 0; i < 3; ++i) pt[n++] = 10 * r1 + 1 + 3 * g2 + i;
+      if (!Tr::kHermitian) {
+        for (int r1 = 0; r1 < NR; ++r1)
+          for (int i = 0; i < 3; ++i) pt[n++] = NR * r1 + 1 + 3 * g2 + i;
       } else {
-        for (int j = 0; j < 4; ++j)
-          for (int i = 0; i < 3; ++i) pt[n++] = kept_index(real_rows[j], 1 + 3 * g2 + i);
+        for (int j = 0; j < NREAL; ++j)
+          for (int i = 0; i < 3; ++i) pt[n++] = kept_index<NR>(real_row(j), 1 + 3 * g2 + i);
         for (int g1 = 0; g1 < 2; ++g1)
-          for (int i = 0; i < 6; ++i) pt[n++] = 64 + 6 * (2 * g1 + g2) + i;
+          for (int i = 0; i < 6; ++i) pt[n++] = (NR * NR - 36) + 6 * (2 * g1 + g2) + i;
       }
     }
   }
@@ -199,8 +187,8 @@ __global__ __launch_bounds__(256, 4) void fused_product_output_kernel(
     float col[10], cc[8];
 #pragma unroll
     for (int r1 = 0; r1 < 10; ++r1) col[r1] = next();
-    collapse10(col, cc);
-    inv8(cc, z[real_comp[j]]);
+    collapse_rows(col, cc);
+    inv_outputs(cc, z[real_comp[j]]);
   }
 #pragma unroll
   for (int g2 = 0; g2 < 2; ++g2) {
@@ -213,8 +201,8 @@ __global__ __launch_bounds__(256, 4) void fused_product_output_kernel(
         h0[r1] = m0 - m1;
         h1[r1] = m2 - m0;
       }
-      collapse10(h0, c0);
-      collapse10(h1, c1);
+      collapse_rows(h0, c0);
+      collapse_rows(h1, c1);
     } else {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -230,8 +218,8 @@ __global__ __launch_bounds__(256, 4) void fused_product_output_kernel(
         hermitian_collapse(m, c0[1 + 2 * g1], c0[2 + 2 * g1], c1[1 + 2 * g1], c1[2 + 2 * g1]);
       }
     }
-    inv8(c0, z[1 + 2 * g2]);
-    inv8(c1, z[2 + 2 * g2]);
+    inv_outputs(c0, z[1 + 2 * g2]);
+    inv_outputs(c1, z[2 + 2 * g2]);
   }
 
   // ---- store plan, fixed over the six output rows --------------------------------
@@ -267,7 +255,7 @@ __global__ __launch_bounds__(256, 4) void fused_product_output_kernel(
     float zc[8], out[6];
 #pragma unroll
     for (int bb = 0; bb < 8; ++bb) zc[bb] = z[bb][o1];
-    inv8(zc, out);
+    inv_outputs(zc, out);
     float* st = stage[o1 & 1];
 #pragma unroll
     for (int o2 = 0; o2 < 6; o2 += 2) {
@@ -343,6 +331,7 @@ static hipError_t launch_fused_alg(const Geometry& g, const void* V, const Filte
 }
 
 bool fused_supported(const Geometry& g) {
+  if (g.alg > 1) return false;  // 6x6 tiles only
   const int kc = g.Cp / 64;
   // V, U and y are addressed through buffer descriptors with 32-bit byte offsets
   const long long ybytes = 4ll * g.N * g.Cout * g.H * g.W;
@@ -362,11 +351,11 @@ static hipError_t launch_fused_out(int out, const Geometry& g, const void* V, co
               : launch_fused_alg<ALG, false, false>(g, V, f, x_scale, inv_y, y, s);
 }
 
-hipError_t launch_fused_product_output(int alg, int out, const Geometry& g, const void* V,
+hipError_t launch_fused_product_output(int out, const Geometry& g, const void* V,
                                        const FilterViews& f, float x_scale, float inv_y, void* y,
                                        hipStream_t s) {
   if (!fused_supported(g) || out == 1) return hipErrorNotSupported;
-  return alg == 0 ? launch_fused_out<0>(out, g, V, f, x_scale, inv_y, y, s)
+  return g.alg == 0 ? launch_fused_out<0>(out, g, V, f, x_scale, inv_y, y, s)
                   : launch_fused_out<1>(out, g, V, f, x_scale, inv_y, y, s);
 }
 

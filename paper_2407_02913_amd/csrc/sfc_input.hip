@@ -141,14 +141,14 @@ __global__ __launch_bounds__(384, 2) void input_transform_i8_kernel(
       int row[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) row[j] = (int)src[i * ip.wp + j];
-      fwd8(row, half[i]);
+      fwd_input<8, 8>(row, half[i]);
     }
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
       int col[8], cc[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) col[i] = half[i][b];
-      fwd8(col, cc);
+      fwd_input<8, 8>(col, cc);
 #pragma unroll
       for (int a = 0; a < 8; ++a) comp[a][b] = cc[a];
     }
@@ -184,6 +184,7 @@ __global__ __launch_bounds__(384, 2) void input_transform_i8_kernel(
 }
 
 static bool make_input_plan(const Geometry& g, InputPlan* ip) {
+  if (g.alg > 1) return false;  // 6x6 tiles only
   ip->chunks = (g.tw + 5) / 6;
   ip->tlw = (g.tw + ip->chunks - 1) / ip->chunks;
   ip->S = ip->chunks > 1 ? 1 : (6 / ip->tlw > 0 ? 6 / ip->tlw : 1);
@@ -204,13 +205,13 @@ static bool make_input_plan(const Geometry& g, InputPlan* ip) {
 
 // Returns hipErrorNotSupported when the geometry is outside this kernel's limits;
 // the caller then uses the generic kernel.
-hipError_t launch_input_transform_i8(int alg, const Geometry& g, const int8_t* x, void* V,
+hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V,
                                      const float* inv_sx, hipStream_t s) {
   InputPlan ip;
   if (!make_input_plan(g, &ip)) return hipErrorNotSupported;
   dim3 grid(((g.strips + ip.S - 1) / ip.S) * ip.chunks, g.Cp / 64);
   dim3 block(64 * ip.S * ip.tlw);
-  if (alg == 0)
+  if (g.alg == 0)
     hipLaunchKernelGGL(input_transform_i8_kernel<0>, grid, block, ip.lds_bytes, s, x, (int8_t*)V,
                        inv_sx, g, ip);
   else

@@ -9,7 +9,8 @@ namespace sfc {
 // Everything a kernel needs to know about one convolution, by value.
 struct Geometry {
   int N, Cin, Cout, H, W;
-  int th, tw;     // tile grid per image: ceil(H/6), ceil(W/6)
+  int alg;        // 0: 6x6 / 88 points, 1: 6x6 / 100, 2: 7x7 / 132, 3: 7x7 / 144
+  int th, tw;     // tile grid per image: ceil(H/M), ceil(W/M), M = 6 or 7 outputs per tile edge
   int strips;     // N * th: one strip = one row of tiles of one image
   int T;          // tiles = strips * tw
   int Tp;         // T rounded up to 16 (row padding of V and M)
@@ -27,28 +28,28 @@ struct FilterViews {
   float* wscale;        // [Kp]    s_w[k]
 };
 
-hipError_t launch_filter_transform(int alg, int mode, const Geometry& g, const int8_t* w,
+hipError_t launch_filter_transform(int mode, const Geometry& g, const int8_t* w,
                                    const FilterViews& f, hipStream_t s);
-hipError_t launch_input_transform(int alg, int mode, const Geometry& g, const int8_t* x, void* V,
+hipError_t launch_input_transform(int mode, const Geometry& g, const int8_t* x, void* V,
                                   const float* inv_sx, hipStream_t s);
 // requantized-mode kernel; hipErrorNotSupported when the geometry is outside its limits
-hipError_t launch_input_transform_i8(int alg, const Geometry& g, const int8_t* x, void* V,
+hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V,
                                      const float* inv_sx, hipStream_t s);
 hipError_t launch_product(int mode, const Geometry& g, const void* V, const void* U, int32_t* M,
                           hipStream_t s);
 // out: 0 float32, 1 int32 sums (exact mode), 2 int8 with ReLU (inv_y = 1 / output scale)
-hipError_t launch_output_transform(int alg, int mode, int out, const Geometry& g, const int32_t* M,
+hipError_t launch_output_transform(int mode, int out, const Geometry& g, const int32_t* M,
                                    const FilterViews& f, float x_scale, float inv_y, void* y,
                                    hipStream_t s);
-hipError_t launch_fused_product_output(int alg, int out, const Geometry& g, const void* V,
+hipError_t launch_fused_product_output(int out, const Geometry& g, const void* V,
                                        const FilterViews& f, float x_scale, float inv_y, void* y,
                                        hipStream_t s);
 // whether the fused kernel covers this geometry (Cin padded to 64, 128, 256 or 512)
 bool fused_supported(const Geometry& g);
 // abs-max calibration: maxima are int32, zeroed by the launcher
-hipError_t launch_act_absmax(int alg, const Geometry& g, const int8_t* x, int32_t* maxima /*[P]*/,
+hipError_t launch_act_absmax(const Geometry& g, const int8_t* x, int32_t* maxima /*[P]*/,
                              hipStream_t s);
-hipError_t launch_filter_absmax(int alg, const Geometry& g, const int8_t* w,
+hipError_t launch_filter_absmax(const Geometry& g, const int8_t* w,
                                 int32_t* maxima /*[P][Cout]*/, hipStream_t s);
 
 hipError_t launch_stream_copy(void* dst, const void* src, size_t bytes, hipStream_t s);

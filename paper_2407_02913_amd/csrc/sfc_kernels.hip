@@ -26,6 +26,24 @@ __device__ __forceinline__ int quantize_i8(int v, float inv) {
   return __float_as_int(t) - 0x4B400000;
 }
 
+// 3x3 filter taps of one (k, c) -> NC x NC components (rows, then columns)
+template <int ALG>
+__device__ __forceinline__ void filter_components(
+    const int (&f)[3][3], int (&comp)[AlgTraits<ALG>::NC][AlgTraits<ALG>::NC]) {
+  constexpr int NC = AlgTraits<ALG>::NC;
+  int half[3][NC];
+#pragma unroll
+  for (int r = 0; r < 3; ++r) fwd_filter<NC>(f[r], half[r]);
+#pragma unroll
+  for (int b = 0; b < NC; ++b) {
+    const int col[3] = {half[0][b], half[1][b], half[2][b]};
+    int cc[NC];
+    fwd_filter<NC>(col, cc);
+#pragma unroll
+    for (int a = 0; a < NC; ++a) comp[a][b] = cc[a];
+  }
+}
+
 // ---------------------------------------------------------------------------
 // filter transform: one thread per (k, c) of the padded [Kp][Cp] domain
 // ---------------------------------------------------------------------------
@@ -44,18 +62,8 @@ __global__ __launch_bounds__(256) void filter_transform_kernel(const int8_t* __r
 #pragma unroll
     for (int s = 0; s < 3; ++s)
       f[r][s] = valid ? (int)w[((size_t)k * g.Cin + c) * 9 + r * 3 + s] : 0;
-  int half[3][8];
-#pragma unroll
-  for (int r = 0; r < 3; ++r) fwd3(f[r], half[r]);
-  int comp[8][8];
-#pragma unroll
-  for (int b = 0; b < 8; ++b) {
-    const int col[3] = {half[0][b], half[1][b], half[2][b]};
-    int cc[8];
-    fwd3(col, cc);
-#pragma unroll
-    for (int a = 0; a < 8; ++a) comp[a][b] = cc[a];
-  }
+  int comp[AlgTraits<ALG>::NC][AlgTraits<ALG>::NC];
+  filter_components<ALG>(f, comp);
   for_each_point<ALG>(comp, [&](int p, int v) {
     const size_t idx = ((size_t)p * g.Kp + k) * g.Cp + c;
     if constexpr (MODE == 1) {
@@ -81,18 +89,8 @@ __global__ __launch_bounds__(256) void filter_absmax_kernel(const int8_t* __rest
     for (int r = 0; r < 3; ++r)
 #pragma unroll
       for (int s = 0; s < 3; ++s) f[r][s] = (int)w[((size_t)k * g.Cin + c) * 9 + r * 3 + s];
-    int half[3][8];
-#pragma unroll
-    for (int r = 0; r < 3; ++r) fwd3(f[r], half[r]);
-    int comp[8][8];
-#pragma unroll
-    for (int b = 0; b < 8; ++b) {
-      const int col[3] = {half[0][b], half[1][b], half[2][b]};
-      int cc[8];
-      fwd3(col, cc);
-#pragma unroll
-      for (int a = 0; a < 8; ++a) comp[a][b] = cc[a];
-    }
+    int comp[AlgTraits<ALG>::NC][AlgTraits<ALG>::NC];
+    filter_components<ALG>(f, comp);
     for_each_point<ALG>(comp, [&](int p, int v) { atomicMax(&smax[p], v < 0 ? -v : v); });
   }
   __syncthreads();
@@ -104,15 +102,15 @@ __global__ __launch_bounds__(256) void filter_absmax_kernel(const int8_t* __rest
 // input transform
 //
 // One workgroup owns S consecutive strips (a strip = one row of tiles of one
-// image, i.e. input rows 6*ti-1 .. 6*ti+6) for 64 channels.  The eight input
-// rows of a (strip, channel) are one contiguous run of 8*W bytes in NCHW, so the
+// image, i.e. the M+2 input rows M*ti-1 .. M*ti+M) for 64 channels.  The input
+// rows of a (strip, channel) are one contiguous run of (M+2)*W bytes in NCHW, so the
 // workgroup copies them to LDS with coalesced loads, then each thread transforms
 // one (tile, channel) patch with lanes running along channels, which makes the
 // V stores contiguous.  MODE: 0 int16 out, 1 int8 requantized out, 2 abs-max.
 // ---------------------------------------------------------------------------
 struct StripParams {
   int S;         // strips per workgroup
-  int cs;        // LDS bytes per (strip, channel): 8*W padded to 4*(odd)
+  int cs;        // LDS bytes per (strip, channel): (M+2)*W padded to 4*(odd)
   int vec4;      // 1: W % 4 == 0, rows are dword aligned
 };
 
@@ -123,7 +121,8 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
                                                               int32_t* __restrict__ maxima,
                                                               Geometry g, StripParams sp) {
   extern __shared__ __align__(16) unsigned char lds[];
-  constexpr int P = AlgTraits<ALG>::P;
+  constexpr int P = AlgTraits<ALG>::P, M = AlgTraits<ALG>::M, NI = AlgTraits<ALG>::NI,
+                NC = AlgTraits<ALG>::NC;
   __shared__ int smax[MODE == 2 ? P : 1];
   if constexpr (MODE == 2) {
     for (int i = threadIdx.x; i < P; i += blockDim.x) smax[i] = 0;
@@ -131,7 +130,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
   const int strip0 = blockIdx.x * sp.S;
   const int c0 = blockIdx.y * 64;
   const int W = g.W, H = g.H;
-  const int seg = 8 * W;  // bytes per (strip, channel)
+  const int seg = NI * W;  // bytes per (strip, channel)
 
   // ---- stage the raw rows -------------------------------------------------
   if (sp.vec4) {
@@ -146,7 +145,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
       if (strip < g.strips && c0 + c < g.Cin) {
         const int n = strip / g.th, ti = strip - n * g.th;
         const int row = (4 * e) / W;
-        const int h = 6 * ti - 1 + row;
+        const int h = M * ti - 1 + row;
         if (h >= 0 && h < H) {
           const size_t base = (((size_t)n * g.Cin + c0 + c) * H + h) * W + (4 * e - row * W);
           val = *(const unsigned*)(x + base);
@@ -165,7 +164,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
       if (strip < g.strips && c0 + c < g.Cin) {
         const int n = strip / g.th, ti = strip - n * g.th;
         const int row = e / W;
-        const int h = 6 * ti - 1 + row;
+        const int h = M * ti - 1 + row;
         if (h >= 0 && h < H) {
           const size_t base = (((size_t)n * g.Cin + c0 + c) * H + h) * W + (e - row * W);
           val = (unsigned char)x[base];
@@ -186,26 +185,26 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
     const int strip = strip0 + s;
     if (strip >= g.strips) continue;
     const signed char* src = (const signed char*)lds + (size_t)(s * 64 + c) * sp.cs;
-    int half[8][8];
+    int half[NI][NC];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      int row[8];
+    for (int i = 0; i < NI; ++i) {
+      int row[NI];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int col = 6 * tj - 1 + j;
+      for (int j = 0; j < NI; ++j) {
+        const int col = M * tj - 1 + j;
         row[j] = (col >= 0 && col < W) ? (int)src[i * W + col] : 0;
       }
-      fwd8(row, half[i]);  // horizontal axis: half[i][b]
+      fwd_input<NI, NC>(row, half[i]);  // horizontal axis: half[i][b]
     }
-    int comp[8][8];
+    int comp[NC][NC];
 #pragma unroll
-    for (int b = 0; b < 8; ++b) {
-      int col[8], cc[8];
+    for (int b = 0; b < NC; ++b) {
+      int col[NI], cc[NC];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) col[i] = half[i][b];
-      fwd8(col, cc);
+      for (int i = 0; i < NI; ++i) col[i] = half[i][b];
+      fwd_input<NI, NC>(col, cc);
 #pragma unroll
-      for (int a = 0; a < 8; ++a) comp[a][b] = cc[a];
+      for (int a = 0; a < NC; ++a) comp[a][b] = cc[a];
     }
     const size_t t = (size_t)strip * g.tw + tj;
     const size_t row_off = t * g.Cp + c0 + c;
@@ -327,17 +326,18 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __
   const int ti = rem / g.tw, tj = rem - ti * g.tw;
   const size_t ybase = ((size_t)n * g.Cout + k) * g.H * g.W;
 
+  constexpr int MT = AlgTraits<ALG>::M;
   if constexpr (MODE == 1) {
-    float out[6][6];
+    float out[MT][MT];
     output_transform<ALG, float>(
         [&](int p) { return (float)m[p * pstride] * dequant[p * g.Kp + k]; }, out);
 #pragma unroll
-    for (int o1 = 0; o1 < 6; ++o1) {
-      const int h = 6 * ti + o1;
+    for (int o1 = 0; o1 < MT; ++o1) {
+      const int h = MT * ti + o1;
       if (h >= g.H) continue;
 #pragma unroll
-      for (int o2 = 0; o2 < 6; ++o2) {
-        const int w = 6 * tj + o2;
+      for (int o2 = 0; o2 < MT; ++o2) {
+        const int w = MT * tj + o2;
         if (w >= g.W) continue;
         const float v = out[o1][o2] * x_scale;
         if constexpr (OUT == 2) {
@@ -353,16 +353,16 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __
       }
     }
   } else {
-    int out[6][6];
+    int out[MT][MT];
     output_transform<ALG, int>([&](int p) { return m[p * pstride]; }, out);
     const float scale = x_scale * wscale[k];
 #pragma unroll
-    for (int o1 = 0; o1 < 6; ++o1) {
-      const int h = 6 * ti + o1;
+    for (int o1 = 0; o1 < MT; ++o1) {
+      const int h = MT * ti + o1;
       if (h >= g.H) continue;
 #pragma unroll
-      for (int o2 = 0; o2 < 6; ++o2) {
-        const int w = 6 * tj + o2;
+      for (int o2 = 0; o2 < MT; ++o2) {
+        const int w = MT * tj + o2;
         if (w >= g.W) continue;
         const int acc = out[o1][o2] / 36;  // exact: the sum is a multiple of 36
         if constexpr (OUT == 1)
@@ -380,7 +380,7 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __
 
 static StripParams strip_params(const Geometry& g) {
   StripParams sp;
-  int seg4 = (8 * g.W + 3) / 4;
+  int seg4 = ((alg_tile(g.alg) + 2) * g.W + 3) / 4;
   if ((seg4 & 1) == 0) seg4 += 1;  // odd dword stride: lanes along channels hit distinct banks
   sp.cs = 4 * seg4;
   sp.vec4 = (g.W % 4 == 0) ? 1 : 0;
@@ -403,50 +403,69 @@ static hipError_t launch_input_impl(const Geometry& g, const int8_t* x, void* V,
   return hipGetLastError();
 }
 
-hipError_t launch_input_transform(int alg, int mode, const Geometry& g, const int8_t* x, void* V,
-                                  const float* inv_sx, hipStream_t s) {
-  if (mode == 1) {
-    const hipError_t e = launch_input_transform_i8(alg, g, x, V, inv_sx, s);
-    if (e != hipErrorNotSupported) return e;
+template <int MODE>
+static hipError_t launch_input_alg(const Geometry& g, const int8_t* x, void* V, const float* inv_sx,
+                                   int32_t* maxima, hipStream_t s) {
+  switch (g.alg) {
+    case 0: return launch_input_impl<0, MODE>(g, x, V, inv_sx, maxima, s);
+    case 1: return launch_input_impl<1, MODE>(g, x, V, inv_sx, maxima, s);
+    case 2: return launch_input_impl<2, MODE>(g, x, V, inv_sx, maxima, s);
+    case 3: return launch_input_impl<3, MODE>(g, x, V, inv_sx, maxima, s);
   }
-  if (alg == 0) {
-    return mode == 1 ? launch_input_impl<0, 1>(g, x, V, inv_sx, nullptr, s)
-                     : launch_input_impl<0, 0>(g, x, V, inv_sx, nullptr, s);
-  }
-  return mode == 1 ? launch_input_impl<1, 1>(g, x, V, inv_sx, nullptr, s)
-                   : launch_input_impl<1, 0>(g, x, V, inv_sx, nullptr, s);
+  return hipErrorInvalidValue;
 }
 
-hipError_t launch_act_absmax(int alg, const Geometry& g, const int8_t* x, int32_t* maxima,
-                             hipStream_t s) {
+hipError_t launch_input_transform(int mode, const Geometry& g, const int8_t* x, void* V,
+                                  const float* inv_sx, hipStream_t s) {
+  if (mode == 1) {
+    const hipError_t e = launch_input_transform_i8(g, x, V, inv_sx, s);
+    if (e != hipErrorNotSupported) return e;
+    return launch_input_alg<1>(g, x, V, inv_sx, nullptr, s);
+  }
+  return launch_input_alg<0>(g, x, V, inv_sx, nullptr, s);
+}
+
+hipError_t launch_act_absmax(const Geometry& g, const int8_t* x, int32_t* maxima, hipStream_t s) {
   hipLaunchKernelGGL(fill_i32_kernel, dim3((g.P + 255) / 256), dim3(256), 0, s, maxima, g.P, 0);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return alg == 0 ? launch_input_impl<0, 2>(g, x, nullptr, nullptr, maxima, s)
-                  : launch_input_impl<1, 2>(g, x, nullptr, nullptr, maxima, s);
+  return launch_input_alg<2>(g, x, nullptr, nullptr, maxima, s);
 }
 
-hipError_t launch_filter_absmax(int alg, const Geometry& g, const int8_t* w, int32_t* maxima,
+hipError_t launch_filter_absmax(const Geometry& g, const int8_t* w, int32_t* maxima,
                                 hipStream_t s) {
-  if (alg == 0)
-    hipLaunchKernelGGL(filter_absmax_kernel<0>, dim3(g.Cout), dim3(256), 0, s, w, maxima, g);
-  else
-    hipLaunchKernelGGL(filter_absmax_kernel<1>, dim3(g.Cout), dim3(256), 0, s, w, maxima, g);
+#define SFC_LAUNCH_FMAX(A) \
+  hipLaunchKernelGGL(filter_absmax_kernel<A>, dim3(g.Cout), dim3(256), 0, s, w, maxima, g)
+  switch (g.alg) {
+    case 0: SFC_LAUNCH_FMAX(0); break;
+    case 1: SFC_LAUNCH_FMAX(1); break;
+    case 2: SFC_LAUNCH_FMAX(2); break;
+    case 3: SFC_LAUNCH_FMAX(3); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef SFC_LAUNCH_FMAX
   return hipGetLastError();
 }
 
-hipError_t launch_filter_transform(int alg, int mode, const Geometry& g, const int8_t* w,
+hipError_t launch_filter_transform(int mode, const Geometry& g, const int8_t* w,
                                    const FilterViews& f, hipStream_t s) {
   dim3 grid((g.Cp + 255) / 256, g.Kp);
   dim3 block(256);
-  if (alg == 0 && mode == 1)
-    hipLaunchKernelGGL((filter_transform_kernel<0, 1>), grid, block, 0, s, w, f.U, f.inv_sw, g);
-  else if (alg == 0)
-    hipLaunchKernelGGL((filter_transform_kernel<0, 0>), grid, block, 0, s, w, f.U, f.inv_sw, g);
-  else if (mode == 1)
-    hipLaunchKernelGGL((filter_transform_kernel<1, 1>), grid, block, 0, s, w, f.U, f.inv_sw, g);
-  else
-    hipLaunchKernelGGL((filter_transform_kernel<1, 0>), grid, block, 0, s, w, f.U, f.inv_sw, g);
+#define SFC_LAUNCH_FT(A)                                                                          \
+  do {                                                                                            \
+    if (mode == 1)                                                                                \
+      hipLaunchKernelGGL((filter_transform_kernel<A, 1>), grid, block, 0, s, w, f.U, f.inv_sw, g); \
+    else                                                                                          \
+      hipLaunchKernelGGL((filter_transform_kernel<A, 0>), grid, block, 0, s, w, f.U, f.inv_sw, g); \
+  } while (0)
+  switch (g.alg) {
+    case 0: SFC_LAUNCH_FT(0); break;
+    case 1: SFC_LAUNCH_FT(1); break;
+    case 2: SFC_LAUNCH_FT(2); break;
+    case 3: SFC_LAUNCH_FT(3); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef SFC_LAUNCH_FT
   return hipGetLastError();
 }
 
@@ -463,29 +482,35 @@ hipError_t launch_product(int mode, const Geometry& g, const void* V, const void
   return hipGetLastError();
 }
 
-hipError_t launch_output_transform(int alg, int mode, int out, const Geometry& g, const int32_t* M,
-                                   const FilterViews& f, float x_scale, float inv_y, void* y,
-                                   hipStream_t s) {
+template <int ALG>
+static hipError_t launch_output_alg(int mode, int out, const Geometry& g, const int32_t* M,
+                                    const FilterViews& f, float x_scale, float inv_y, void* y,
+                                    hipStream_t s) {
   int kx = 64;
   while (kx > g.Kp) kx >>= 1;  // Kp is a multiple of 16
   dim3 grid((g.T + (256 / kx) - 1) / (256 / kx), (g.Cout + kx - 1) / kx);
   dim3 block(256);
-#define SFC_LAUNCH_OUT(A, MD, O)                                                              \
-  hipLaunchKernelGGL((output_transform_kernel<A, MD, O>), grid, block, 0, s, M, f.dequant,     \
+#define SFC_LAUNCH_OUT(MD, O)                                                                   \
+  hipLaunchKernelGGL((output_transform_kernel<ALG, MD, O>), grid, block, 0, s, M, f.dequant,     \
                      f.wscale, x_scale, inv_y, y, g, kx)
-  if (alg == 0) {
-    if (mode == 1 && out == 2) SFC_LAUNCH_OUT(0, 1, 2);
-    else if (mode == 1) SFC_LAUNCH_OUT(0, 1, 0);
-    else if (out == 1) SFC_LAUNCH_OUT(0, 0, 1);
-    else SFC_LAUNCH_OUT(0, 0, 0);
-  } else {
-    if (mode == 1 && out == 2) SFC_LAUNCH_OUT(1, 1, 2);
-    else if (mode == 1) SFC_LAUNCH_OUT(1, 1, 0);
-    else if (out == 1) SFC_LAUNCH_OUT(1, 0, 1);
-    else SFC_LAUNCH_OUT(1, 0, 0);
-  }
+  if (mode == 1 && out == 2) SFC_LAUNCH_OUT(1, 2);
+  else if (mode == 1) SFC_LAUNCH_OUT(1, 0);
+  else if (out == 1) SFC_LAUNCH_OUT(0, 1);
+  else SFC_LAUNCH_OUT(0, 0);
 #undef SFC_LAUNCH_OUT
   return hipGetLastError();
+}
+
+hipError_t launch_output_transform(int mode, int out, const Geometry& g, const int32_t* M,
+                                   const FilterViews& f, float x_scale, float inv_y, void* y,
+                                   hipStream_t s) {
+  switch (g.alg) {
+    case 0: return launch_output_alg<0>(mode, out, g, M, f, x_scale, inv_y, y, s);
+    case 1: return launch_output_alg<1>(mode, out, g, M, f, x_scale, inv_y, y, s);
+    case 2: return launch_output_alg<2>(mode, out, g, M, f, x_scale, inv_y, y, s);
+    case 3: return launch_output_alg<3>(mode, out, g, M, f, x_scale, inv_y, y, s);
+  }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace sfc

@@ -1,23 +1,26 @@
-// Add networks of SFC-6(6x6,3x3): forward transforms to the multiplication
-// points and the output transform back, as straight-line device code.
+// Add networks of SFC-6(6x6,3x3) and SFC-6(7x7,3x3): forward transforms to the
+// multiplication points and the output transform back, as straight-line code.
 //
-// A 1-D signal of 8 samples becomes 8 "components" (Sec. 4.1-4.2):
+// A 1-D signal of M+2 samples (M = 6 or 7 outputs) becomes NC "components"
+// (Sec. 4.1-4.2):
 //   c0  X0            (real, k = 0)
 //   c1  X1.a0   c2  X1.a1     X1 = a0 + a1 s,  s = exp(j pi/3), s^2 = s - 1
 //   c3  X2.a0   c4  X2.a1
 //   c5  X3            (real, k = 3)
-//   c6  x0 - x6       correction input for output 0   (Sec. 4.2)
-//   c7  x7 - x1       correction input for output 5
+//   c6  x0 - x6       correction input for output 0, paired with f0   (Sec. 4.2)
+//   c7  x7 - x1       correction input for output 5, paired with f2
+//   c8  x7 - x1       M = 7 only: correction for output 6, paired with f1
+//   c9  x8 - x2       M = 7 only: correction for output 6, paired with f2
 // The 3-multiplication product rule (Eq. DFT6M) adds a row a0 + a1 per complex
-// point, giving the 10 rows of Appendix A's B^T and G:
-//   r0=c0 r1=c1 r2=c2 r3=c1+c2 r4=c3 r5=c4 r6=c3+c4 r7=c5 r8=c6 r9=c7.
-// In 2-D the components form an 8x8 array C[a][b] (a: vertical axis).
-//   P = 100: every (r_a, r_b) pair.
-//   P = 88 : the 64 pairs that are not complex x complex, then for each pair of
-//            complex frequencies the two independent 2-D DFT values
-//              U = (a00 - a11) + (a10 + a01 + a11) s
-//              V = (a00 + a01 + a11) + (a10 - a01) s
-//            each as (x0, x1, x0 + x1).
+// point, giving the NR = NC + 2 rows of Appendix A's B^T and G:
+//   r0=c0 r1=c1 r2=c2 r3=c1+c2 r4=c3 r5=c4 r6=c3+c4 r7=c5 r8=c6 r9=c7 (r10=c8 r11=c9).
+// In 2-D the components form an NC x NC array C[a][b] (a: vertical axis).
+//   nested   : every (r_a, r_b) pair, NR^2 points (100 / 144).
+//   Hermitian: the pairs that are not complex x complex, then for each pair of
+//              complex frequencies the two independent 2-D DFT values
+//                U = (a00 - a11) + (a10 + a01 + a11) s
+//                V = (a00 + a01 + a11) + (a10 - a01) s
+//              each as (x0, x1, x0 + x1): NR^2 - 12 points (88 / 132).
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -26,26 +29,56 @@
 
 namespace sfc {
 
-constexpr int kTileOut = 6;
-constexpr int kTileIn = 8;
-
+// ALG: 0 = 6x6 Hermitian (88), 1 = 6x6 nested (100), 2 = 7x7 Hermitian (132), 3 = 7x7 nested (144)
 template <int ALG>
-struct AlgTraits;
-template <>
-struct AlgTraits<0> {
-  static constexpr int P = 88;
+struct AlgTraits {
+  static_assert(ALG >= 0 && ALG < 4, "unknown algorithm");
+  static constexpr bool kHermitian = (ALG == 0 || ALG == 2);
+  static constexpr int M = ALG < 2 ? 6 : 7;   // outputs per tile edge
+  static constexpr int NI = M + 2;            // input samples per tile edge
+  static constexpr int NC = ALG < 2 ? 8 : 10; // components per axis
+  static constexpr int NR = NC + 2;           // rows of the printed 1-D matrices
+  static constexpr int NREAL = NR - 6;        // rows that are not part of a complex point
+  static constexpr int P = kHermitian ? NR * NR - 12 : NR * NR;
 };
-template <>
-struct AlgTraits<1> {
-  static constexpr int P = 100;
-};
+
+constexpr int kNumAlgs = 4;
+__host__ __device__ constexpr int alg_points(int alg) {
+  return alg == 0 ? 88 : alg == 1 ? 100 : alg == 2 ? 132 : 144;
+}
+__host__ __device__ constexpr int alg_tile(int alg) { return alg < 2 ? 6 : 7; }
+
+// ---- row bookkeeping ----------------------------------------------------------
+
+// row -> the component(s) it adds (second = -1: none)
+SFC_HD constexpr int row_c0(int r) {
+  return r == 0 ? 0 : r == 1 ? 1 : r == 2 ? 2 : r == 3 ? 1 : r == 4 ? 3 : r == 5 ? 4 : r == 6 ? 3 : r == 7 ? 5 : r - 2;
+}
+SFC_HD constexpr int row_c1(int r) { return r == 3 ? 2 : r == 6 ? 4 : -1; }
+SFC_HD constexpr bool row_is_complex(int r) { return r >= 1 && r <= 6; }
+// i-th real row (0, 7, 8, 9, ...) and the component it carries (0, 5, 6, 7, ...)
+SFC_HD constexpr int real_row(int i) { return i == 0 ? 0 : 6 + i; }
+SFC_HD constexpr int real_comp(int i) { return i == 0 ? 0 : 4 + i; }
+
+// canonical index of the kept nested point (r1, r2) of a Hermitian point set
+template <int NR>
+SFC_HD constexpr int kept_index(int r1, int r2) {
+  int n = 0;
+  for (int a = 0; a < NR; ++a)
+    for (int b = 0; b < NR; ++b) {
+      if (row_is_complex(a) && row_is_complex(b)) continue;
+      if (a == r1 && b == r2) return n;
+      ++n;
+    }
+  return -1;
+}
 
 // ---- forward, 1-D ----------------------------------------------------------
 
-// Eight samples -> eight components (14 additions for the symbolic DFT-6 of the
-// inner six samples, 2 for the correction inputs).
-template <typename T>
-SFC_HD void fwd8(const T (&x)[8], T (&c)[8]) {
+// M+2 samples -> NC components (14 additions for the symbolic DFT-6 of the inner
+// six samples, one per correction input).
+template <int NI, int NC, typename T>
+SFC_HD void fwd_input(const T (&x)[NI], T (&c)[NC]) {
   const T e0 = x[1] + x[4], e1 = x[2] + x[5], e2 = x[3] + x[6];
   const T d0 = x[1] - x[4], d1 = x[2] - x[5], d2 = x[3] - x[6];
   c[0] = e0 + e1 + e2;
@@ -56,11 +89,15 @@ SFC_HD void fwd8(const T (&x)[8], T (&c)[8]) {
   c[5] = d0 - d1 + d2;
   c[6] = x[0] - x[6];
   c[7] = x[7] - x[1];
+  if constexpr (NC == 10) {
+    c[8] = c[7];
+    c[9] = x[8] - x[2];
+  }
 }
 
-// Three filter taps -> eight components (rows of Appendix A's G without the sum rows).
-template <typename T>
-SFC_HD void fwd3(const T (&f)[3], T (&c)[8]) {
+// Three filter taps -> NC components (rows of Appendix A's G without the sum rows).
+template <int NC, typename T>
+SFC_HD void fwd_filter(const T (&f)[3], T (&c)[NC]) {
   c[0] = f[0] + f[1] + f[2];
   c[1] = f[1] + f[2];
   c[2] = -f[0] - f[1];
@@ -69,19 +106,16 @@ SFC_HD void fwd3(const T (&f)[3], T (&c)[8]) {
   c[5] = f[0] - f[1] + f[2];
   c[6] = f[0];
   c[7] = f[2];
+  if constexpr (NC == 10) {
+    c[8] = f[1];
+    c[9] = f[2];
+  }
 }
-
-// component index -> which components a 1-D row adds (second = -1: none)
-SFC_HD constexpr int row_c0(int r) {
-  return r == 0 ? 0 : r == 1 ? 1 : r == 2 ? 2 : r == 3 ? 1 : r == 4 ? 3 : r == 5 ? 4 : r == 6 ? 3 : r == 7 ? 5 : r == 8 ? 6 : 7;
-}
-SFC_HD constexpr int row_c1(int r) { return r == 3 ? 2 : r == 6 ? 4 : -1; }
-SFC_HD constexpr bool row_is_complex(int r) { return r >= 1 && r <= 6; }
 
 // ---- forward, 2-D: components -> multiplication points ----------------------
 
-template <typename T>
-SFC_HD T nested_point(const T (&c)[8][8], int r1, int r2) {
+template <int NC, typename T>
+SFC_HD T nested_point(const T (&c)[NC][NC], int r1, int r2) {
   const int a0 = row_c0(r1), a1 = row_c1(r1), b0 = row_c0(r2), b1 = row_c1(r2);
   T v = c[a0][b0];
   if (b1 >= 0) v += c[a0][b1];
@@ -93,8 +127,8 @@ SFC_HD T nested_point(const T (&c)[8][8], int r1, int r2) {
 }
 
 // The six Hermitian points of the frequency pair (g1, g2), g in {0,1} -> k = g + 1.
-template <typename T>
-SFC_HD void hermitian_points(const T (&c)[8][8], int g1, int g2, T (&out)[6]) {
+template <int NC, typename T>
+SFC_HD void hermitian_points(const T (&c)[NC][NC], int g1, int g2, T (&out)[6]) {
   const int a = 1 + 2 * g1, b = 1 + 2 * g2;
   const T a00 = c[a][b], a10 = c[a + 1][b], a01 = c[a][b + 1], a11 = c[a + 1][b + 1];
   const T u0 = a00 - a11, u1 = a10 + a01 + a11;
@@ -110,18 +144,19 @@ SFC_HD void hermitian_points(const T (&c)[8][8], int g1, int g2, T (&out)[6]) {
 // Calls f(p, value) for every point in canonical order.  Fully unrolled: p is a
 // compile-time constant at each call site after inlining.
 template <int ALG, typename T, typename F>
-SFC_HD void for_each_point(const T (&c)[8][8], F&& f) {
-  if constexpr (ALG == 1) {
+SFC_HD void for_each_point(const T (&c)[AlgTraits<ALG>::NC][AlgTraits<ALG>::NC], F&& f) {
+  constexpr int NR = AlgTraits<ALG>::NR;
+  if constexpr (!AlgTraits<ALG>::kHermitian) {
 #pragma unroll
-    for (int r1 = 0; r1 < 10; ++r1)
+    for (int r1 = 0; r1 < NR; ++r1)
 #pragma unroll
-      for (int r2 = 0; r2 < 10; ++r2) f(10 * r1 + r2, nested_point(c, r1, r2));
+      for (int r2 = 0; r2 < NR; ++r2) f(NR * r1 + r2, nested_point(c, r1, r2));
   } else {
     int p = 0;
 #pragma unroll
-    for (int r1 = 0; r1 < 10; ++r1)
+    for (int r1 = 0; r1 < NR; ++r1)
 #pragma unroll
-      for (int r2 = 0; r2 < 10; ++r2) {
+      for (int r2 = 0; r2 < NR; ++r2) {
         if (row_is_complex(r1) && row_is_complex(r2)) continue;
         f(p++, nested_point(c, r1, r2));
       }
@@ -139,17 +174,17 @@ SFC_HD void for_each_point(const T (&c)[8][8], F&& f) {
 
 // ---- output transform --------------------------------------------------------
 
-// Ten 1-D products -> eight components: o0 = m0 - m1, o1 = m2 - m0 (Eq. DFT6M).
-template <typename T>
-SFC_HD void collapse10(const T (&r)[10], T (&c)[8]) {
+// NR 1-D products -> NC components: o0 = m0 - m1, o1 = m2 - m0 (Eq. DFT6M).
+template <int NR, typename T>
+SFC_HD void collapse_rows(const T (&r)[NR], T (&c)[NR - 2]) {
   c[0] = r[0];
   c[1] = r[1] - r[2];
   c[2] = r[3] - r[1];
   c[3] = r[4] - r[5];
   c[4] = r[6] - r[4];
   c[5] = r[7];
-  c[6] = r[8];
-  c[7] = r[9];
+#pragma unroll
+  for (int i = 8; i < NR; ++i) c[i - 2] = r[i];
 }
 
 template <typename T>
@@ -177,10 +212,11 @@ SFC_HD void hermitian_collapse(const T (&m)[6], T& o00, T& o10, T& o01, T& o11) 
   o10 = vo1 + o01;
 }
 
-// Eight components -> six outputs, times 6 (the inverse symbolic DFT-6 through its
-// DFT-2 x DFT-3 structure, plus the two correction products with weight 6).
-template <typename T>
-SFC_HD void inv8(const T (&c)[8], T (&y)[6]) {
+// NC components -> M outputs, times 6 (the inverse symbolic DFT-6 through its
+// DFT-2 x DFT-3 structure, plus the correction products with weight 6).  For
+// M = 7 the seventh output is the cyclic output 0 with its own two corrections.
+template <int NC, typename T>
+SFC_HD void inv_outputs(const T (&c)[NC], T (&y)[NC - 2 - (NC == 10 ? 1 : 0)]) {
   // even harmonics k = 0, 2 repeat with period 3; odd harmonics k = 1, 3 flip sign
   const T t = c[0] - c[3];
   const T e0 = t - c[4] - c[4];
@@ -189,46 +225,50 @@ SFC_HD void inv8(const T (&c)[8], T (&y)[6]) {
   const T d0 = c[1] - c[2] - c[5];
   const T d1 = c[5] - c[1] - c[2] - c[2];
   const T d2 = -c[1] - c[1] - c[2] - c[5];
-  y[0] = e0 + d0 + T(6) * c[6];
+  const T y0 = e0 + d0;
+  y[0] = y0 + T(6) * c[6];
   y[1] = e1 + d1;
   y[2] = e2 + d2;
   y[3] = e0 - d0;
   y[4] = e1 - d1;
   y[5] = e2 - d2 + T(6) * c[7];
+  if constexpr (NC == 10) y[6] = y0 + T(6) * (c[8] + c[9]);
 }
 
-// All P products of one (tile, Cout) pair -> 36 outputs times 36.
+// All P products of one (tile, Cout) pair -> M x M outputs times 36.
 // get(p) returns product p (already scaled in the dequantizing case).
 template <int ALG, typename T, typename G>
-SFC_HD void output_transform(G&& get, T (&out)[6][6]) {
-  T comp[8][8];
-  if constexpr (ALG == 1) {
-    T half[10][8];
+SFC_HD void output_transform(G&& get, T (&out)[AlgTraits<ALG>::M][AlgTraits<ALG>::M]) {
+  using Tr = AlgTraits<ALG>;
+  constexpr int NR = Tr::NR, NC = Tr::NC, M = Tr::M, NREAL = Tr::NREAL;
+  T comp[NC][NC];
+  if constexpr (!Tr::kHermitian) {
+    T half[NR][NC];
 #pragma unroll
-    for (int r1 = 0; r1 < 10; ++r1) {
-      T row[10];
+    for (int r1 = 0; r1 < NR; ++r1) {
+      T row[NR];
 #pragma unroll
-      for (int r2 = 0; r2 < 10; ++r2) row[r2] = get(10 * r1 + r2);
-      collapse10(row, half[r1]);
+      for (int r2 = 0; r2 < NR; ++r2) row[r2] = get(NR * r1 + r2);
+      collapse_rows(row, half[r1]);
     }
 #pragma unroll
-    for (int b = 0; b < 8; ++b) {
-      T col[10], cc[8];
+    for (int b = 0; b < NC; ++b) {
+      T col[NR], cc[NC];
 #pragma unroll
-      for (int r1 = 0; r1 < 10; ++r1) col[r1] = half[r1][b];
-      collapse10(col, cc);
+      for (int r1 = 0; r1 < NR; ++r1) col[r1] = half[r1][b];
+      collapse_rows(col, cc);
 #pragma unroll
-      for (int a = 0; a < 8; ++a) comp[a][b] = cc[a];
+      for (int a = 0; a < NC; ++a) comp[a][b] = cc[a];
     }
   } else {
-    // the 64 kept points: rows where r1 is real hold all ten r2; rows where r1
-    // is complex hold only the four real r2 (0, 7, 8, 9)
-    T kept[10][10];
+    // kept points: rows where r1 is real hold all r2; rows where r1 is complex
+    // hold only the real r2
+    T kept[NR][NR];
     int p = 0;
 #pragma unroll
-    for (int r1 = 0; r1 < 10; ++r1)
+    for (int r1 = 0; r1 < NR; ++r1)
 #pragma unroll
-      for (int r2 = 0; r2 < 10; ++r2) {
+      for (int r2 = 0; r2 < NR; ++r2) {
         if (row_is_complex(r1) && row_is_complex(r2)) {
           kept[r1][r2] = T(0);
           continue;
@@ -236,24 +276,22 @@ SFC_HD void output_transform(G&& get, T (&out)[6][6]) {
         kept[r1][r2] = get(p++);
       }
     // real r1: collapse along the horizontal axis
-    constexpr int real_rows[4] = {0, 7, 8, 9};
-    constexpr int real_comp[4] = {0, 5, 6, 7};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      T cc[8];
-      collapse10(kept[real_rows[i]], cc);
+    for (int i = 0; i < NREAL; ++i) {
+      T cc[NC];
+      collapse_rows(kept[real_row(i)], cc);
 #pragma unroll
-      for (int b = 0; b < 8; ++b) comp[real_comp[i]][b] = cc[b];
+      for (int b = 0; b < NC; ++b) comp[real_comp(i)][b] = cc[b];
     }
     // complex r1, real r2: collapse along the vertical axis
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      T col[10], cc[8];
+    for (int j = 0; j < NREAL; ++j) {
+      T col[NR], cc[NC];
 #pragma unroll
-      for (int r1 = 0; r1 < 10; ++r1) col[r1] = kept[r1][real_rows[j]];
-      collapse10(col, cc);
+      for (int r1 = 0; r1 < NR; ++r1) col[r1] = kept[r1][real_row(j)];
+      collapse_rows(col, cc);
 #pragma unroll
-      for (int a = 1; a <= 4; ++a) comp[a][real_comp[j]] = cc[a];
+      for (int a = 1; a <= 4; ++a) comp[a][real_comp(j)] = cc[a];
     }
     // complex x complex from the Hermitian blocks
 #pragma unroll
@@ -268,17 +306,17 @@ SFC_HD void output_transform(G&& get, T (&out)[6][6]) {
       }
   }
   // separable inverse: along the horizontal axis, then the vertical one
-  T z[8][6];
+  T z[NC][M];
 #pragma unroll
-  for (int a = 0; a < 8; ++a) inv8(comp[a], z[a]);
+  for (int a = 0; a < NC; ++a) inv_outputs(comp[a], z[a]);
 #pragma unroll
-  for (int o2 = 0; o2 < 6; ++o2) {
-    T col[8], y[6];
+  for (int o2 = 0; o2 < M; ++o2) {
+    T col[NC], y[M];
 #pragma unroll
-    for (int a = 0; a < 8; ++a) col[a] = z[a][o2];
-    inv8(col, y);
+    for (int a = 0; a < NC; ++a) col[a] = z[a][o2];
+    inv_outputs(col, y);
 #pragma unroll
-    for (int o1 = 0; o1 < 6; ++o1) out[o1][o2] = y[o1];
+    for (int o1 = 0; o1 < M; ++o1) out[o1][o2] = y[o1];
   }
 }
 

@@ -45,7 +45,10 @@ def rel_err(y, ref):
     return float(np.abs(y.astype(np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
 
 
-@pytest.mark.parametrize("alg", ["6x6_p88", "6x6_p100"])
+ALGS = ["6x6_p88", "6x6_p100", "7x7_p132", "7x7_p144"]
+
+
+@pytest.mark.parametrize("alg", ALGS)
 @pytest.mark.parametrize("shape", SMALL_SHAPES)
 def test_exact_mode_taps_and_sums_bit_exact(binding, shape, alg):
     x, w, xs, ws = uniform_case(shape, 100 + len(alg) + sum(shape))
@@ -60,7 +63,7 @@ def test_exact_mode_taps_and_sums_bit_exact(binding, shape, alg):
     assert rel_err(y, oracle.dequantize(acc_ref, xs, ws)) <= F32_TOL
 
 
-@pytest.mark.parametrize("alg", ["6x6_p88", "6x6_p100"])
+@pytest.mark.parametrize("alg", ALGS)
 @pytest.mark.parametrize("shape", SMALL_SHAPES)
 def test_requant_mode_taps_bit_exact_and_output_close(binding, shape, alg):
     x, w, xs, ws = uniform_case(shape, 200 + len(alg) + sum(shape))
@@ -86,7 +89,7 @@ def test_single_filter_scale(binding):
     assert rel_err(y, oracle.dequantize(oracle.direct_conv(x, w), xs, ws)) <= F32_TOL
 
 
-@pytest.mark.parametrize("alg", ["6x6_p88", "6x6_p100"])
+@pytest.mark.parametrize("alg", ALGS)
 def test_gpu_calibration_matches_oracle(binding, alg):
     import torch
 

@@ -152,7 +152,7 @@ def kernel_maps(tmp_path_factory):
     return {k: np.array([v[i] for i in range(len(v))]) for k, v in maps.items()}
 
 
-@pytest.mark.parametrize("alg_id,alg", [(0, "6x6_p88"), (1, "6x6_p100")])
+@pytest.mark.parametrize("alg_id,alg", [(0, "6x6_p88"), (1, "6x6_p100"), (2, "7x7_p132"), (3, "7x7_p144")])
 def test_kernel_add_networks_realize_the_oracle_matrices(kernel_maps, alg_id, alg):
     b2, g2, a2, den = oracle.algorithm(alg)
     assert den == 36
