@@ -30,6 +30,8 @@ def stage_bytes(shape, P, tiles, path):
     u = P * shape.Cout * shape.Cin
     m = 4 * P * tiles * shape.Cout
     y = 4 * shape.N * shape.Cout * shape.H * shape.W
+    if path == "single":
+        return {"single_conv": x + u + y}
     if path == "fused":
         return {"input_transform": x + v, "fused_product_output": v + u + y}
     return {"input_transform": x + v, "product": v + u + m, "output_transform": m + y}
@@ -41,7 +43,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet56")
-    ap.add_argument("--path", default=None, choices=[None, "staged", "fused"])
+    ap.add_argument("--path", default=None, choices=[None, "staged", "fused", "single"])
     ap.add_argument("--alg", default="6x6_p88")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=3,
@@ -64,7 +66,8 @@ def main():
     torch.cuda.set_device(0)
     shape = synth.LAYERS[args.workload]
     data = synth.make_layer(shape)
-    path = args.path or binding.DEFAULT_PATH
+    # one kernel where the layer allows it (Cin <= 64), else input transform + fused product/output
+    path = args.path or ("single" if shape.Cin <= 64 else binding.DEFAULT_PATH)
 
     plan = binding.Plan(shape.N, shape.Cin, shape.Cout, shape.H, shape.W, alg=args.alg,
                         mode="requant", path=path, per_channel_wscale=shape.per_channel_wscale)
@@ -121,7 +124,9 @@ def main():
 
     # per-kernel durations: each stage alone, back to back, over the rotating sets
     # (every set already holds valid V / M from the full passes above)
-    if path == "fused":
+    if path == "single":
+        stages = {"single_conv": binding.STAGE_ALL}
+    elif path == "fused":
         stages = {"input_transform": binding.STAGE_INPUT,
                   "fused_product_output": binding.STAGE_PRODUCT | binding.STAGE_OUTPUT}
     else:
@@ -171,7 +176,7 @@ def main():
                 "stages_gbs": {k: round(bytes_per[k] / (stage_us[k] * 1e-6) / 1e9, 1) for k in stage_us},
                 "stream_copy_gbs": round(copy_gbs, 1)}
     sfc_ops = 2 * plan.P * plan.tiles * shape.Cin * shape.Cout
-    prod_key = "fused_product_output" if path == "fused" else "product"
+    prod_key = {"single": "single_conv", "fused": "fused_product_output", "staged": "product"}[path]
     roofline["product_mfma_frac"] = round(sfc_ops / (stage_us[prod_key] * 1e-6) / 1e12 / MFMA_I8_PEAK_TOPS, 4)
 
     tops = shape.direct_ops / (ms_per_step * 1e-3) / 1e12
@@ -181,7 +186,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{args.workload}: N={shape.N} Cin=Cout={shape.Cin} H=W={shape.H} 3x3 s1 p1",
-                   "algorithm": f"SFC-6(6x6,3x3) P={plan.P}", "mode": "requant-int8 transform domain",
+                   "algorithm": f"SFC-6({args.alg[:3]},3x3) P={plan.P}", "mode": "requant-int8 transform domain",
                    "path": path, "buffer_sets": nsets, "streams": nstreams,
                    "single_stream_ms_per_step": round(single_stream_ms, 5)},
         "roofline": roofline,

@@ -78,7 +78,10 @@ typedef enum {
 
 typedef enum {
   SFC_PATH_STAGED = 0, /* V and M pass through the workspace; taps available */
-  SFC_PATH_FUSED = 1   /* product and output transform in one kernel; M never leaves the chip */
+  SFC_PATH_FUSED = 1,  /* product and output transform in one kernel; M never leaves the chip */
+  /* Cin <= 64 only: input transform, products and output transform in one kernel;
+   * neither V nor M leaves the chip, the workspace is used by calibration only. */
+  SFC_PATH_SINGLE = 2
 } sfc_path;
 
 typedef struct {
@@ -151,7 +154,8 @@ sfc_status sfc_conv2d_nchw(const sfc_plan_t* plan, const int8_t* x_dev, float x_
  * stage_mask, so that one stage can be timed alone on buffers a full call has
  * filled.  SFC_STAGE_INPUT: V = B^T x B.  SFC_STAGE_PRODUCT: M = V.U (staged path).
  * SFC_STAGE_OUTPUT: y from M (staged path); on the fused path SFC_STAGE_PRODUCT |
- * SFC_STAGE_OUTPUT must be given together and run the one fused kernel. */
+ * SFC_STAGE_OUTPUT must be given together and run the one fused kernel; on
+ * SFC_PATH_SINGLE only SFC_STAGE_ALL is accepted. */
 enum { SFC_STAGE_INPUT = 1, SFC_STAGE_PRODUCT = 2, SFC_STAGE_OUTPUT = 4, SFC_STAGE_ALL = 7 };
 sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale,
                              void* y_dev, void* workspace_dev, void* stream, int32_t stage_mask);
@@ -160,8 +164,8 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
  * which: 0 = V [P][tiles][Cin], 1 = U [P][Cout][Cin], 2 = M [P][tiles][Cout] (int32).
  * ptr receives a device address inside workspace_dev (V, M) or the filter buffer
  * (U); elem_bytes is 1 or 2 for V and U (int8 / int16) and 4 for M; dims and
- * strides (in elements) describe the three axes.  V is valid on both paths, M
- * only on SFC_PATH_STAGED (SFC_EUNSUPPORTED otherwise). */
+ * strides (in elements) describe the three axes.  V exists on SFC_PATH_STAGED and
+ * SFC_PATH_FUSED, M only on SFC_PATH_STAGED (SFC_EUNSUPPORTED otherwise). */
 sfc_status sfc_tap_info(const sfc_plan_t* plan, const void* workspace_dev, int32_t which,
                         const void** ptr, int32_t* elem_bytes, int64_t dims[3], int64_t strides[3]);
 

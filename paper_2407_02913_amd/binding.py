@@ -20,7 +20,7 @@ STATUS_NAMES = {0: "SFC_OK", 1: "SFC_EINVAL", 2: "SFC_EUNSUPPORTED", 3: "SFC_ENO
 ALG = {"6x6_p88": 0, "6x6_p100": 1, "7x7_p132": 2, "7x7_p144": 3}
 MODE = {"exact": 0, "requant": 1}
 OUT = {"f32": 0, "i32": 1, "i8": 2}
-PATH = {"staged": 0, "fused": 1}
+PATH = {"staged": 0, "fused": 1, "single": 2}
 STAGE_INPUT, STAGE_PRODUCT, STAGE_OUTPUT, STAGE_ALL = 1, 2, 4, 7
 #: the path bench.py and callers get when they do not ask for one
 DEFAULT_PATH = "fused"
@@ -244,7 +244,7 @@ def conv2d(x: np.ndarray, w: np.ndarray, x_scale: float, w_scale, mode="requant"
     torch.cuda.synchronize()
     res = y.cpu().numpy()
     if return_taps:
-        names = ("V", "U", "M") if path == "staged" else ("V", "U")
+        names = {"staged": ("V", "U", "M"), "fused": ("V", "U"), "single": ("U",)}[path]
         taps = {k: plan.tap(k, wbuf) for k in names}
         plan.close()
         return res, taps

@@ -18,7 +18,8 @@ struct sfc_plan_s {
   Geometry g;
   int esz;  // bytes per transform-domain operand: 2 exact, 1 requantized
   // filter buffer layout (byte offsets)
-  size_t off_U, off_dequant, off_inv_sw, off_inv_sx, off_wscale, filter_bytes;
+  size_t off_U, off_dequant, off_inv_sw, off_inv_sx, off_wscale, off_dq_single, off_U_single,
+      filter_bytes;
   // workspace layout
   size_t off_V, off_M, workspace_bytes;
   std::vector<float> sx, sw;  // [P], [P][Cout]
@@ -42,6 +43,8 @@ FilterViews views(const sfc_plan_s* p, void* filter_dev) {
   f.inv_sw = reinterpret_cast<float*>(b + p->off_inv_sw);
   f.inv_sx = reinterpret_cast<float*>(b + p->off_inv_sx);
   f.wscale = reinterpret_cast<float*>(b + p->off_wscale);
+  f.dequant_single = reinterpret_cast<float*>(b + p->off_dq_single);
+  f.U_single = b + p->off_U_single;
   return f;
 }
 
@@ -69,11 +72,12 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   if (d.alg < SFC_ALG_6X6_P88 || d.alg > SFC_ALG_7X7_P144) return SFC_EINVAL;
   if (d.mode != SFC_MODE_EXACT && d.mode != SFC_MODE_REQUANT_I8) return SFC_EINVAL;
   if (d.out != SFC_OUT_F32 && d.out != SFC_OUT_I32 && d.out != SFC_OUT_I8_RELU) return SFC_EINVAL;
-  if (d.path != SFC_PATH_STAGED && d.path != SFC_PATH_FUSED) return SFC_EINVAL;
+  if (d.path != SFC_PATH_STAGED && d.path != SFC_PATH_FUSED && d.path != SFC_PATH_SINGLE)
+    return SFC_EINVAL;
   if (d.per_channel_wscale != 0 && d.per_channel_wscale != 1) return SFC_EINVAL;
   if (d.out == SFC_OUT_I32 && d.mode != SFC_MODE_EXACT) return SFC_EUNSUPPORTED;
   if (d.out == SFC_OUT_I8_RELU && d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
-  if (d.path == SFC_PATH_FUSED && d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
+  if (d.path != SFC_PATH_STAGED && d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
   if (d.W > 1024 || d.H > (1 << 20) || d.Cin > (1 << 16) || d.Cout > 65535 * 16)
     return SFC_EUNSUPPORTED;
 
@@ -95,6 +99,7 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   g.P = kPoints[d.alg];
 
   if (d.path == SFC_PATH_FUSED && !sfc::fused_supported(g)) return SFC_EUNSUPPORTED;
+  if (d.path == SFC_PATH_SINGLE && !sfc::single_supported(g)) return SFC_EUNSUPPORTED;
 
   sfc_plan_s* p = new (std::nothrow) sfc_plan_s();
   if (!p) return SFC_ENOMEM;
@@ -108,9 +113,19 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   p->off_inv_sw = off;   off = align_up(off + PK * sizeof(float), 256);
   p->off_inv_sx = off;   off = align_up(off + g.P * sizeof(float), 256);
   p->off_wscale = off;   off = align_up(off + g.Kp * sizeof(float), 256);
+  p->off_dq_single = off;
+  p->off_U_single = off;
+  if (d.path == SFC_PATH_SINGLE) {
+    const size_t kq = (size_t)(g.Cout + 63) / 64 * 64;
+    off = align_up(off + kq * g.P * sizeof(float), 256);
+    p->off_U_single = off;
+    off = align_up(off + sfc::single_filter_bytes(g), 256);
+  }
   p->filter_bytes = off;
   off = 0;
-  p->off_V = off;        off = align_up(off + (size_t)g.P * g.Tp * g.Cp * p->esz, 256);
+  p->off_V = off;
+  // the single-kernel path keeps V on chip; its workspace only serves calibration
+  if (d.path != SFC_PATH_SINGLE) off = align_up(off + (size_t)g.P * g.Tp * g.Cp * p->esz, 256);
   p->off_M = off;
   if (d.path == SFC_PATH_STAGED) off = align_up(off + (size_t)g.P * g.Tp * g.Kp * 4, 256);
   // calibration scratch (abs-max tables) must fit as well
@@ -182,7 +197,8 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
 
   // host image of the float tables: [dequant | inv_sw | inv_sx | wscale], contiguous
   // from off_dequant to filter_bytes
-  const size_t table_bytes = plan->filter_bytes - plan->off_dequant;
+  const bool single = plan->d.path == SFC_PATH_SINGLE;
+  const size_t table_bytes = (single ? plan->off_U_single : plan->filter_bytes) - plan->off_dequant;
   try {
     plan->staging.assign(table_bytes / sizeof(float), 0.0f);
   } catch (...) {
@@ -208,6 +224,14 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
       inv_sw[(size_t)p * g.Kp + k] = inv;
     }
   }
+  if (single) {
+    // [filter][processing position]; filters beyond Cout stay zero
+    std::vector<int> pt(g.P);
+    sfc::single_point_order(plan->d.alg, pt.data());
+    float* dqs = table(plan->off_dq_single);
+    for (int k = 0; k < g.Cout; ++k)
+      for (int j = 0; j < g.P; ++j) dqs[(size_t)k * g.P + j] = dequant[(size_t)pt[j] * g.Kp + k];
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (hipMemcpyAsync(static_cast<char*>(filter_dev) + plan->off_dequant, plan->staging.data(),
                      table_bytes, hipMemcpyHostToDevice, s) != hipSuccess)
@@ -215,6 +239,7 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
   const FilterViews f = views(plan, filter_dev);
   if (sfc::launch_filter_transform(plan->d.mode, g, w_dev, f, s) != hipSuccess)
     return SFC_EHIP;
+  if (single && sfc::launch_repack_filter(g, f.U, f.U_single, s) != hipSuccess) return SFC_EHIP;
   plan->filter_dev = filter_dev;
   plan->filter_ready = true;
   return SFC_OK;
@@ -229,6 +254,13 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
   if (!plan->filter_ready) return SFC_ENOTREADY;
   if (plan->d.out == SFC_OUT_I8_RELU && plan->inv_y == 0.0f) return SFC_ENOTREADY;
   const bool fused = plan->d.path == SFC_PATH_FUSED;
+  if (plan->d.path == SFC_PATH_SINGLE) {
+    if (stage_mask != SFC_STAGE_ALL) return SFC_EINVAL;  // one kernel: no stage runs alone
+    if (sfc::launch_single_conv(plan->d.out, plan->g, x_dev, views(plan, plan->filter_dev), x_scale,
+                                plan->inv_y, y_dev, static_cast<hipStream_t>(stream)) != hipSuccess)
+      return SFC_EHIP;
+    return SFC_OK;
+  }
   const int tail = stage_mask & (SFC_STAGE_PRODUCT | SFC_STAGE_OUTPUT);
   if (fused && tail != 0 && tail != (SFC_STAGE_PRODUCT | SFC_STAGE_OUTPUT)) return SFC_EINVAL;
   const Geometry& g = plan->g;
@@ -273,6 +305,7 @@ sfc_status sfc_tap_info(const sfc_plan_t* plan, const void* workspace_dev, int32
   switch (which) {
     case 0:
       if (!workspace_dev) return SFC_EINVAL;
+      if (plan->d.path == SFC_PATH_SINGLE) return SFC_EUNSUPPORTED;
       *ptr = ws + plan->off_V;
       *elem_bytes = plan->esz;
       dims[0] = g.P; dims[1] = g.T; dims[2] = g.Cin;

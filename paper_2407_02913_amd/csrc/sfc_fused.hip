@@ -16,45 +16,14 @@
 // per pair) stays live.  The last step runs the inverse along the horizontal axis
 // one output row at a time, stages the row block in LDS and stores it with
 // contiguous lanes (consecutive tiles of a strip form full image rows).
+#include "sfc_device.hpp"
 #include "sfc_internal.hpp"
 #include "sfc_points.hpp"
 
 namespace sfc {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef float v2f __attribute__((ext_vector_type(2)));
-
-// Processing order (canonical point indices), grouped by horizontal class.
-template <int ALG>
-struct Order {
-  using Tr = AlgTraits<ALG>;
-  static constexpr int P = Tr::P, NR = Tr::NR, NREAL = Tr::NREAL;
-  int pt[P];
-  constexpr Order() : pt{} {
-    int n = 0;
-    // real columns: all vertical rows
-    for (int j = 0; j < NREAL; ++j)
-      for (int r1 = 0; r1 < NR; ++r1)
-        pt[n++] = Tr::kHermitian ? kept_index<NR>(r1, real_row(j)) : NR * r1 + real_row(j);
-    // complex column groups
-    for (int g2 = 0; g2 < 2; ++g2) {
-      if (!Tr::kHermitian) {
-        for (int r1 = 0; r1 < NR; ++r1)
-          for (int i = 0; i < 3; ++i) pt[n++] = NR * r1 + 1 + 3 * g2 + i;
-      } else {
-        for (int j = 0; j < NREAL; ++j)
-          for (int i = 0; i < 3; ++i) pt[n++] = kept_index<NR>(real_row(j), 1 + 3 * g2 + i);
-        for (int g1 = 0; g1 < 2; ++g1)
-          for (int i = 0; i < 6; ++i) pt[n++] = (NR * NR - 36) + 6 * (2 * g1 + g2) + i;
-      }
-    }
-  }
-};
 
 constexpr int kRing = 4;          // operand slots in flight (64-channel chunks)
-constexpr int kStreamStore = 2;    // buffer cache policy "nt": y is written once and not re-read here
-constexpr int kBufferFlags = 0x00020000;  // raw buffer descriptor word 3: 32-bit data format
 constexpr int kStageStride = 98;  // floats per filter row of the staging block (16 tiles x 6 + 2)
 
 // ---------------------------------------------------------------------------
@@ -181,46 +150,7 @@ __global__ __launch_bounds__(256, 4) void fused_product_output_kernel(
   };
 
   float z[8][6];
-  constexpr int real_comp[4] = {0, 5, 6, 7};
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    float col[10], cc[8];
-#pragma unroll
-    for (int r1 = 0; r1 < 10; ++r1) col[r1] = next();
-    collapse_rows(col, cc);
-    inv_outputs(cc, z[real_comp[j]]);
-  }
-#pragma unroll
-  for (int g2 = 0; g2 < 2; ++g2) {
-    float c0[8], c1[8];
-    if constexpr (ALG == 1) {
-      float h0[10], h1[10];
-#pragma unroll
-      for (int r1 = 0; r1 < 10; ++r1) {
-        const float m0 = next(), m1 = next(), m2 = next();
-        h0[r1] = m0 - m1;
-        h1[r1] = m2 - m0;
-      }
-      collapse_rows(h0, c0);
-      collapse_rows(h1, c1);
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float m0 = next(), m1 = next(), m2 = next();
-        c0[real_comp[j]] = m0 - m1;
-        c1[real_comp[j]] = m2 - m0;
-      }
-#pragma unroll
-      for (int g1 = 0; g1 < 2; ++g1) {
-        float m[6];
-#pragma unroll
-        for (int i = 0; i < 6; ++i) m[i] = next();
-        hermitian_collapse(m, c0[1 + 2 * g1], c0[2 + 2 * g1], c1[1 + 2 * g1], c1[2 + 2 * g1]);
-      }
-    }
-    inv_outputs(c0, z[1 + 2 * g2]);
-    inv_outputs(c1, z[2 + 2 * g2]);
-  }
+  stream_vertical<ALG, float>(next, z);
 
   // ---- store plan, fixed over the six output rows --------------------------------
   // float32: 16 filters x 48 float pairs (or 96 floats) over 256 threads, lanes
@@ -252,10 +182,8 @@ __global__ __launch_bounds__(256, 4) void fused_product_output_kernel(
   // one barrier per output row: the staging block is double buffered
 #pragma unroll
   for (int o1 = 0; o1 < 6; ++o1) {
-    float zc[8], out[6];
-#pragma unroll
-    for (int bb = 0; bb < 8; ++bb) zc[bb] = z[bb][o1];
-    inv_outputs(zc, out);
+    float out[6];
+    stream_row<ALG, float>(z, o1, out);
     float* st = stage[o1 & 1];
 #pragma unroll
     for (int o2 = 0; o2 < 6; o2 += 2) {

@@ -15,20 +15,11 @@
 //     bytes into LDS as out[tile][p][channel].
 //  3. Copy out: each wave streams its tile's P x 64 bytes to V[p][t][c0..c0+63]
 //     with 16-byte lanes.
+#include "sfc_device.hpp"
 #include "sfc_internal.hpp"
 #include "sfc_points.hpp"
 
 namespace sfc {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-constexpr int kBufFlags = 0x00020000;  // raw buffer descriptor word 3: 32-bit data format
-
-// id -> position such that ids congruent modulo 8 (same XCD) map to one contiguous range
-__device__ __forceinline__ int xcd_contiguous(int id, int n) {
-  const int q = n >> 3, r = n & 7;
-  const int xcd = id & 7, idx = id >> 3;
-  return xcd * q + min(xcd, r) + idx;
-}
 
 struct InputPlan {
   int S;        // strips per workgroup
@@ -61,7 +52,7 @@ __global__ __launch_bounds__(384, 2) void input_transform_i8_kernel(
   const int W = g.W, H = g.H;
 
   const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)x, 0, (int)((unsigned)(g.N * g.Cin) * (unsigned)(H * W)), kBufFlags);
+      (void*)x, 0, (int)((unsigned)(g.N * g.Cin) * (unsigned)(H * W)), kBufferFlags);
 
   // ---- 1. stage ---------------------------------------------------------------
   // One instruction covers four rows x 16 dwords of a (strip, channel): lane =
@@ -169,7 +160,7 @@ __global__ __launch_bounds__(384, 2) void input_transform_i8_kernel(
     const unsigned t = (unsigned)strip * g.tw + tj;
     const unsigned vplane = (unsigned)g.Tp * g.Cp;
     const __amdgpu_buffer_rsrc_t vres = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)V, 0, (int)(vplane * (unsigned)P), kBufFlags);
+        (void*)V, 0, (int)(vplane * (unsigned)P), kBufferFlags);
     const unsigned lane_off = t * g.Cp + c0 + (lane & 3) * 16;
     const unsigned char* inp = lds + (unsigned)wave * (P * 64) + lane * 16;
 #pragma unroll

@@ -26,6 +26,10 @@ struct FilterViews {
   float* inv_sw;        // [P][Kp] 1/s_Tf
   float* inv_sx;        // [P]     1/s_Tx
   float* wscale;        // [Kp]    s_w[k]
+  // single-kernel path only (Cin <= 64): U regrouped into MFMA operands of four points
+  // x four filters, and the dequantization factors as [filter][processing position]
+  void* U_single;
+  float* dequant_single;
 };
 
 hipError_t launch_filter_transform(int mode, const Geometry& g, const int8_t* w,
@@ -46,6 +50,14 @@ hipError_t launch_fused_product_output(int out, const Geometry& g, const void* V
                                        hipStream_t s);
 // whether the fused kernel covers this geometry (Cin padded to 64, 128, 256 or 512)
 bool fused_supported(const Geometry& g);
+// single-kernel path: whether it covers this geometry, the bytes of its filter operand,
+// the regrouping of the canonical U, the processing order (position -> canonical point)
+bool single_supported(const Geometry& g);
+size_t single_filter_bytes(const Geometry& g);
+hipError_t launch_repack_filter(const Geometry& g, const void* U, void* Uf, hipStream_t s);
+void single_point_order(int alg, int* pt /*[P]*/);
+hipError_t launch_single_conv(int out, const Geometry& g, const int8_t* x, const FilterViews& f,
+                              float x_scale, float inv_y, void* y, hipStream_t s);
 // abs-max calibration: maxima are int32, zeroed by the launcher
 hipError_t launch_act_absmax(const Geometry& g, const int8_t* x, int32_t* maxima /*[P]*/,
                              hipStream_t s);

@@ -9,12 +9,12 @@
 // Layouts (element strides): V[p][t][c] = (p*Tp + t)*Cp + c, U[p][k][c] =
 // (p*Kp + k)*Cp + c, M[p][t][k] = (p*Tp + t)*Kp + k.  Channels c >= Cin and
 // filters k >= Cout are zero in U, so padding never contributes to a sum.
+#include "sfc_device.hpp"
 #include "sfc_internal.hpp"
 #include "sfc_points.hpp"
 
 namespace sfc {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
 
 // round-half-even(v * inv) clamped to [-127, 127].  Adding 1.5 * 2^23 inside one
 // fused multiply-add rounds the exact product once, to an integer, ties to even;

@@ -73,6 +73,38 @@ SFC_HD constexpr int kept_index(int r1, int r2) {
   return -1;
 }
 
+// Processing order of the fused kernels: canonical point indices grouped by
+// horizontal class (first the real columns with all their vertical rows, then the
+// two complex column groups), so that each group can be collapsed as soon as its
+// products exist.  pt[j] = canonical index of the j-th point, pos = its inverse.
+template <int ALG>
+struct Order {
+  using Tr = AlgTraits<ALG>;
+  static constexpr int P = Tr::P, NR = Tr::NR, NREAL = Tr::NREAL;
+  int pt[P];
+  int pos[P];
+  constexpr Order() : pt{}, pos{} {
+    int n = 0;
+    // real columns: all vertical rows
+    for (int j = 0; j < NREAL; ++j)
+      for (int r1 = 0; r1 < NR; ++r1)
+        pt[n++] = Tr::kHermitian ? kept_index<NR>(r1, real_row(j)) : NR * r1 + real_row(j);
+    // complex column groups
+    for (int g2 = 0; g2 < 2; ++g2) {
+      if (!Tr::kHermitian) {
+        for (int r1 = 0; r1 < NR; ++r1)
+          for (int i = 0; i < 3; ++i) pt[n++] = NR * r1 + 1 + 3 * g2 + i;
+      } else {
+        for (int j = 0; j < NREAL; ++j)
+          for (int i = 0; i < 3; ++i) pt[n++] = kept_index<NR>(real_row(j), 1 + 3 * g2 + i);
+        for (int g1 = 0; g1 < 2; ++g1)
+          for (int i = 0; i < 6; ++i) pt[n++] = (NR * NR - 36) + 6 * (2 * g1 + g2) + i;
+      }
+    }
+    for (int j = 0; j < P; ++j) pos[pt[j]] = j;
+  }
+};
+
 // ---- forward, 1-D ----------------------------------------------------------
 
 // M+2 samples -> NC components (14 additions for the symbolic DFT-6 of the inner
@@ -318,6 +350,69 @@ SFC_HD void output_transform(G&& get, T (&out)[AlgTraits<ALG>::M][AlgTraits<ALG>
 #pragma unroll
     for (int o1 = 0; o1 < M; ++o1) out[o1][o2] = y[o1];
   }
+}
+
+// ---- output transform, streaming form ------------------------------------------
+
+// Consumes the P products of one (tile, filter) pair in the processing order of
+// Order<ALG> (next() returns the following product, already scaled) and leaves
+// z[b][o1]: horizontal component b, vertical output o1, times 6.  Each group
+// collapses at once: product-rule post-additions, Hermitian recombination, inverse
+// symbolic DFT-6 with the corrections along the vertical axis.
+template <int ALG, typename T, typename F>
+SFC_HD void stream_vertical(F&& next, T (&z)[AlgTraits<ALG>::NC][AlgTraits<ALG>::M]) {
+  using Tr = AlgTraits<ALG>;
+  constexpr int NR = Tr::NR, NC = Tr::NC, NREAL = Tr::NREAL;
+#pragma unroll
+  for (int j = 0; j < NREAL; ++j) {
+    T col[NR], cc[NC];
+#pragma unroll
+    for (int r1 = 0; r1 < NR; ++r1) col[r1] = next();
+    collapse_rows(col, cc);
+    inv_outputs(cc, z[real_comp(j)]);
+  }
+#pragma unroll
+  for (int g2 = 0; g2 < 2; ++g2) {
+    T c0[NC], c1[NC];
+    if constexpr (!Tr::kHermitian) {
+      T h0[NR], h1[NR];
+#pragma unroll
+      for (int r1 = 0; r1 < NR; ++r1) {
+        const T m0 = next(), m1 = next(), m2 = next();
+        h0[r1] = m0 - m1;
+        h1[r1] = m2 - m0;
+      }
+      collapse_rows(h0, c0);
+      collapse_rows(h1, c1);
+    } else {
+#pragma unroll
+      for (int j = 0; j < NREAL; ++j) {
+        const T m0 = next(), m1 = next(), m2 = next();
+        c0[real_comp(j)] = m0 - m1;
+        c1[real_comp(j)] = m2 - m0;
+      }
+#pragma unroll
+      for (int g1 = 0; g1 < 2; ++g1) {
+        T m[6];
+#pragma unroll
+        for (int i = 0; i < 6; ++i) m[i] = next();
+        hermitian_collapse(m, c0[1 + 2 * g1], c0[2 + 2 * g1], c1[1 + 2 * g1], c1[2 + 2 * g1]);
+      }
+    }
+    inv_outputs(c0, z[1 + 2 * g2]);
+    inv_outputs(c1, z[2 + 2 * g2]);
+  }
+}
+
+// Output row o1 of the pair: the inverse along the horizontal axis (times 36 overall).
+template <int ALG, typename T>
+SFC_HD void stream_row(const T (&z)[AlgTraits<ALG>::NC][AlgTraits<ALG>::M], int o1,
+                       T (&out)[AlgTraits<ALG>::M]) {
+  constexpr int NC = AlgTraits<ALG>::NC;
+  T zc[NC];
+#pragma unroll
+  for (int b = 0; b < NC; ++b) zc[b] = z[b][o1];
+  inv_outputs(zc, out);
 }
 
 }  // namespace sfc

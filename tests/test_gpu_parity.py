@@ -176,6 +176,56 @@ def test_fused_path_matches_oracle(binding, shape, alg):
     assert rel_err(y, y_staged.astype(np.float64)) <= F32_TOL
 
 
+SINGLE_SHAPES = [
+    (1, 16, 16, 32, 32),
+    (2, 3, 5, 14, 14),
+    (1, 4, 4, 7, 7),  # odd W: scalar stores
+    (2, 2, 3, 13, 9),
+    (1, 1, 1, 1, 1),
+    (3, 60, 40, 9, 20),
+    (5, 64, 64, 12, 18),
+    (2, 64, 72, 11, 7),  # two filter groups
+    (20, 7, 130, 7, 7),  # many strips per workgroup, three filter groups
+    (1, 33, 17, 56, 56),  # two tile-column chunks per strip
+    (2, 5, 9, 6, 61),  # wide and flat: chunks of nine or eight tile columns
+]
+
+
+@pytest.mark.parametrize("alg", ALGS)
+@pytest.mark.parametrize("shape", SINGLE_SHAPES)
+def test_single_kernel_path_matches_oracle(binding, shape, alg):
+    x, w, xs, ws = uniform_case(shape, 700 + len(alg) + sum(shape))
+    print("case single", shape, alg, flush=True)
+    xc, _, _, _ = uniform_case(shape, 800 + sum(shape))
+    sx = oracle.calibrate_act_scales(xc // 2, alg)
+    sw = oracle.calibrate_filter_scales(w, alg)
+    y_ref, taps_ref = oracle.conv_requant(x, w, sx, sw, xs, ws, alg, return_taps=True)
+    y, taps = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path="single", sx=sx, sw=sw,
+                             return_taps=True)
+    assert np.array_equal(taps["U"].astype(np.int64), taps_ref["U"])
+    assert rel_err(y, y_ref) <= F32_TOL
+
+
+def test_single_kernel_path_needs_at_most_64_input_channels(binding):
+    with pytest.raises(binding.SfcError) as e:
+        binding.Plan(1, 65, 16, 8, 8, path="single")
+    assert e.value.code == 2
+
+
+@pytest.mark.parametrize("alg", ["6x6_p88", "7x7_p132"])
+def test_full_size_single_kernel_against_oracle(binding, alg):
+    """resnet56 in the launch configuration bench.py times, every output element."""
+    shape = synth.LAYERS["resnet56"]
+    print("case full single", alg, flush=True)
+    d = synth.make_layer(shape)
+    sx = oracle.calibrate_act_scales(d["x_calib"], alg)
+    sw = oracle.calibrate_filter_scales(d["w"], alg)
+    y_ref = oracle.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"], alg)
+    y = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg, path="single",
+                       sx=sx, sw=sw)
+    assert rel_err(y, y_ref) <= F32_TOL
+
+
 def test_fused_path_rejects_unsupported_channel_counts(binding):
     with pytest.raises(binding.SfcError) as e:
         binding.Plan(1, 3 * 64, 16, 8, 8, path="fused")  # three chunks
@@ -212,9 +262,11 @@ def check_i8_against_oracle(y8, y_ref, y_scale):
     return float(np.count_nonzero(diff)) / diff.size
 
 
-@pytest.mark.parametrize("path", ["staged", "fused"])
+@pytest.mark.parametrize("path", ["staged", "fused", "single"])
 @pytest.mark.parametrize("shape", [(1, 16, 16, 32, 32), (2, 3, 5, 14, 14), (1, 4, 4, 7, 7), (3, 70, 40, 9, 20)])
 def test_int8_relu_output(binding, shape, path):
+    if path == "single" and shape[1] > 64:
+        shape = (shape[0], 50, *shape[2:])
     x, w, xs, ws = uniform_case(shape, 600 + sum(shape))
     print("case i8", shape, path, flush=True)
     sx = oracle.calibrate_act_scales(x)
