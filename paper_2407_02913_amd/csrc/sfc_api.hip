@@ -27,6 +27,7 @@ struct sfc_plan_s {
   std::vector<float> staging;  // host image of the float tables of the filter buffer
   void* filter_dev;
   bool filter_ready;
+  int quad_filters;  // filters covered by the regrouped filter operand (0: none)
   float inv_y;  // 1 / output scale (SFC_OUT_I8_RELU), 0: not set
 };
 
@@ -98,7 +99,7 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   static const int kPoints[4] = {88, 100, 132, 144};
   g.P = kPoints[d.alg];
 
-  if (d.path == SFC_PATH_FUSED && !sfc::fused_supported(g)) return SFC_EUNSUPPORTED;
+  if (d.path == SFC_PATH_FUSED && !sfc::fused_quad_supported(g)) return SFC_EUNSUPPORTED;
   if (d.path == SFC_PATH_SINGLE && !sfc::single_supported(g)) return SFC_EUNSUPPORTED;
 
   sfc_plan_s* p = new (std::nothrow) sfc_plan_s();
@@ -115,11 +116,13 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   p->off_wscale = off;   off = align_up(off + g.Kp * sizeof(float), 256);
   p->off_dq_single = off;
   p->off_U_single = off;
-  if (d.path == SFC_PATH_SINGLE) {
-    const size_t kq = (size_t)(g.Cout + 63) / 64 * 64;
-    off = align_up(off + kq * g.P * sizeof(float), 256);
+  p->quad_filters = 0;
+  if (d.path == SFC_PATH_SINGLE) p->quad_filters = (g.Cout + 63) / 64 * 64;
+  if (d.path == SFC_PATH_FUSED) p->quad_filters = sfc::quad_filter_count(g);
+  if (p->quad_filters > 0) {
+    off = align_up(off + (size_t)p->quad_filters * g.P * sizeof(float), 256);
     p->off_U_single = off;
-    off = align_up(off + sfc::single_filter_bytes(g), 256);
+    off = align_up(off + (size_t)p->quad_filters * g.P * g.Cp, 256);
   }
   p->filter_bytes = off;
   off = 0;
@@ -197,8 +200,8 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
 
   // host image of the float tables: [dequant | inv_sw | inv_sx | wscale], contiguous
   // from off_dequant to filter_bytes
-  const bool single = plan->d.path == SFC_PATH_SINGLE;
-  const size_t table_bytes = (single ? plan->off_U_single : plan->filter_bytes) - plan->off_dequant;
+  const bool quad = plan->quad_filters > 0;
+  const size_t table_bytes = (quad ? plan->off_U_single : plan->filter_bytes) - plan->off_dequant;
   try {
     plan->staging.assign(table_bytes / sizeof(float), 0.0f);
   } catch (...) {
@@ -224,7 +227,7 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
       inv_sw[(size_t)p * g.Kp + k] = inv;
     }
   }
-  if (single) {
+  if (quad) {
     // [filter][processing position]; filters beyond Cout stay zero
     std::vector<int> pt(g.P);
     sfc::single_point_order(plan->d.alg, pt.data());
@@ -239,7 +242,8 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
   const FilterViews f = views(plan, filter_dev);
   if (sfc::launch_filter_transform(plan->d.mode, g, w_dev, f, s) != hipSuccess)
     return SFC_EHIP;
-  if (single && sfc::launch_repack_filter(g, f.U, f.U_single, s) != hipSuccess) return SFC_EHIP;
+  if (quad && sfc::launch_repack_filter(g, plan->quad_filters, f.U, f.U_single, s) != hipSuccess)
+    return SFC_EHIP;
   plan->filter_dev = filter_dev;
   plan->filter_ready = true;
   return SFC_OK;
@@ -274,8 +278,8 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
       return SFC_EHIP;
   }
   if (fused) {
-    if (tail && sfc::launch_fused_product_output(plan->d.out, g, V, f, x_scale,
-                                                 plan->inv_y, y_dev, s) != hipSuccess)
+    if (tail &&
+        sfc::launch_fused_quad(plan->d.out, g, V, f, x_scale, plan->inv_y, y_dev, s) != hipSuccess)
       return SFC_EHIP;
     return SFC_OK;
   }

@@ -26,8 +26,8 @@ struct FilterViews {
   float* inv_sw;        // [P][Kp] 1/s_Tf
   float* inv_sx;        // [P]     1/s_Tx
   float* wscale;        // [Kp]    s_w[k]
-  // single-kernel path only (Cin <= 64): U regrouped into MFMA operands of four points
-  // x four filters, and the dequantization factors as [filter][processing position]
+  // fused and single-kernel paths: U regrouped into MFMA operands of four points x four
+  // filters, and the dequantization factors as [filter][processing position]
   void* U_single;
   float* dequant_single;
 };
@@ -45,16 +45,18 @@ hipError_t launch_product(int mode, const Geometry& g, const void* V, const void
 hipError_t launch_output_transform(int mode, int out, const Geometry& g, const int32_t* M,
                                    const FilterViews& f, float x_scale, float inv_y, void* y,
                                    hipStream_t s);
-hipError_t launch_fused_product_output(int out, const Geometry& g, const void* V,
-                                       const FilterViews& f, float x_scale, float inv_y, void* y,
-                                       hipStream_t s);
-// whether the fused kernel covers this geometry (Cin padded to 64, 128, 256 or 512)
-bool fused_supported(const Geometry& g);
+// products + output transform in one kernel (sfc_fused_quad.hip): whether it covers this
+// geometry (Cin padded to 64, 128, 256 or 512), how many filters its operand covers
+bool fused_quad_supported(const Geometry& g);
+int quad_filter_count(const Geometry& g);
+hipError_t launch_fused_quad(int out, const Geometry& g, const void* V, const FilterViews& f,
+                             float x_scale, float inv_y, void* y, hipStream_t s);
 // single-kernel path: whether it covers this geometry, the bytes of its filter operand,
 // the regrouping of the canonical U, the processing order (position -> canonical point)
 bool single_supported(const Geometry& g);
-size_t single_filter_bytes(const Geometry& g);
-hipError_t launch_repack_filter(const Geometry& g, const void* U, void* Uf, hipStream_t s);
+// filters: how many the regrouped operand covers (a multiple of 4, >= Cout, zero beyond Kp)
+hipError_t launch_repack_filter(const Geometry& g, int filters, const void* U, void* Uf,
+                                hipStream_t s);
 void single_point_order(int alg, int* pt /*[P]*/);
 hipError_t launch_single_conv(int out, const Geometry& g, const int8_t* x, const FilterViews& f,
                               float x_scale, float inv_y, void* y, hipStream_t s);

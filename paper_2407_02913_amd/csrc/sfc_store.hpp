@@ -1,0 +1,104 @@
+// Output side shared by the fused kernels (gfx950): the per-tile store table and the
+// store of one (tile, filter) pair per lane through a wave-private LDS block.
+#pragma once
+#include "sfc_device.hpp"
+#include "sfc_points.hpp"
+
+namespace sfc {
+
+// Per-tile store data, 48 ints: [tile] output offset (elements) of the tile's first
+// element for filter 0, [16 + tile] valid rows (0: no such tile), [32 + tile] valid columns.
+template <int M>
+__device__ __forceinline__ void write_tile_entry(int* tile_tab, int tl, bool live, int n, int ti,
+                                                 int tj, int Cout, int H, int W) {
+  tile_tab[tl] = ((n * Cout) * H + M * ti) * W + M * tj;
+  tile_tab[16 + tl] = live ? min(M, H - M * ti) : 0;
+  tile_tab[32 + tl] = min(M, W - M * tj);
+}
+
+// Lane l holds z (vertical outputs of every horizontal component, see stream_vertical)
+// of the pair (tile l%16, filter 4*kq + l/16).  One output row at a time: the
+// inverse along the horizontal axis, the wave's staging block [filter 0..3][tile
+// 0..15][o2] (64*M floats), then stores in which consecutive lanes hold consecutive
+// outputs of an image row (tiles of a strip are adjacent in y).
+// OUT: 0 float32, 2 int8 with ReLU (inv_y = 1 / output scale).  VEC2: M and W even,
+// pairs of outputs stay aligned.
+template <int ALG, int OUT, bool VEC2>
+__device__ __forceinline__ void store_pairs(
+    const float (&z)[AlgTraits<ALG>::NC][AlgTraits<ALG>::M], float* stage, const int* tile_tab,
+    int lane, int kq, float x_scale, float inv_y, __amdgpu_buffer_rsrc_t yres, int Cout, int H,
+    int W) {
+  constexpr int M = AlgTraits<ALG>::M;
+  constexpr unsigned esz = OUT == 2 ? 1u : 4u;
+  // Cache policy of the y stores.  7x7 tiles divide the ResNet image widths, a
+  // workgroup then writes whole image rows and the lines can stream past the L2 ("nt");
+  // 6x6 tiles leave row pieces that share cache lines with a neighbouring workgroup,
+  // which the L2 has to merge before they go to memory.
+  constexpr int kStore = M == 7 ? kStreamStore : 0;
+  constexpr int EV = VEC2 ? 2 : 1;        // elements per lane and store
+  constexpr int NST = (M + EV - 1) / EV;  // stores per lane and output row (64*M elements)
+  // store plan: the k-th store of this lane covers elements e = EV*(lane + 64*k) of the
+  // staged row block, e = (filter*16 + tile)*M + o2
+  unsigned yoff[NST];
+  int rowlim[NST];
+#pragma unroll
+  for (int k = 0; k < NST; ++k) {
+    const unsigned e = (unsigned)(EV * (lane + 64 * k));
+    const unsigned ft = e / (unsigned)M;  // filter*16 + tile
+    const int o2 = (int)(e - ft * M), f = (int)(ft >> 4), tl = (int)(ft & 15);
+    const int kc = kq * 4 + f;
+    const bool valid = e < 64u * M && kc < Cout && o2 < tile_tab[32 + tl];
+    rowlim[k] = valid ? tile_tab[16 + tl] : 0;
+    yoff[k] = esz * (unsigned)(tile_tab[tl] + kc * (H * W) + o2);
+  }
+  float* wr = stage + ((lane >> 4) * 16 + (lane & 15)) * M;
+#pragma unroll
+  for (int o1 = 0; o1 < M; ++o1) {
+    float out[M];
+    stream_row<ALG, float>(z, o1, out);
+    if constexpr (M % 2 == 0) {
+#pragma unroll
+      for (int o2 = 0; o2 < M; o2 += 2)
+        *(v2f*)(wr + o2) = v2f{out[o2] * x_scale, out[o2 + 1] * x_scale};
+    } else {
+#pragma unroll
+      for (int o2 = 0; o2 < M; ++o2) wr[o2] = out[o2] * x_scale;
+    }
+    __builtin_amdgcn_wave_barrier();  // LDS accesses of one wave complete in order
+    const unsigned yrow = esz * (unsigned)(o1 * W);
+#pragma unroll
+    for (int k = 0; k < NST; ++k) {
+      float v0, v1 = 0.0f;
+      if constexpr (VEC2) {
+        const v2f pr = *(const v2f*)(stage + 2 * (lane + 64 * k));
+        v0 = pr.x;
+        v1 = pr.y;
+      } else {
+        v0 = (64 * k + lane < 64 * M) ? stage[lane + 64 * k] : 0.0f;
+      }
+      if (o1 < rowlim[k]) {
+        if constexpr (OUT == 2) {
+          // next layer's activation: ReLU, round half to even, clamp to [0, 127]
+          constexpr float kMagic = 12582912.0f;
+          float t0 = __fmaf_rn(v0, inv_y, kMagic), t1 = __fmaf_rn(v1, inv_y, kMagic);
+          t0 = __builtin_amdgcn_fmed3f(t0, kMagic, kMagic + 127.0f);
+          t1 = __builtin_amdgcn_fmed3f(t1, kMagic, kMagic + 127.0f);
+          const unsigned q0 = __float_as_uint(t0) & 0xffu, q1 = __float_as_uint(t1) & 0xffu;
+          if constexpr (VEC2)
+            __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(q0 | (q1 << 8)), yres, yoff[k],
+                                                  yrow, kStore);
+          else
+            __builtin_amdgcn_raw_buffer_store_b8((unsigned char)q0, yres, yoff[k], yrow, kStore);
+        } else {
+          if constexpr (VEC2)
+            __builtin_amdgcn_raw_buffer_store_b64(v2f{v0, v1}, yres, yoff[k], yrow, kStore);
+          else
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v0), yres, yoff[k], yrow, kStore);
+        }
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+}  // namespace sfc

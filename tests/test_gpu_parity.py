@@ -157,7 +157,7 @@ FUSED_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("alg", ["6x6_p88", "6x6_p100"])
+@pytest.mark.parametrize("alg", ALGS)
 @pytest.mark.parametrize("shape", FUSED_SHAPES)
 def test_fused_path_matches_oracle(binding, shape, alg):
     x, w, xs, ws = uniform_case(shape, 400 + len(alg) + sum(shape))
