@@ -2,6 +2,8 @@
 // of tiles a workgroup owns, the staging of its image rows in LDS and the input-tile
 // transform V = B^T x B with rounding to int8.
 #pragma once
+#include <type_traits>
+
 #include "sfc_device.hpp"
 #include "sfc_internal.hpp"
 #include "sfc_points.hpp"
@@ -102,51 +104,62 @@ __device__ __forceinline__ void stage_tiles(const int8_t* __restrict__ x, unsign
   constexpr int CPW = 64 / NW;  // channels per wave
   constexpr int CB = 6;         // combinations per batch
   const int ncombo = tr.S * ROWG;
-  for (int k0 = 0; k0 < ncombo; k0 += CB) {
-    unsigned vals[CB][CPW];
+  // A dword can reach past the end of the tensor only if rows are not whole dwords; the
+  // buffer load then returns zero for all of it, so those bytes are fetched one by one.
+  // Rows of whole dwords take the loop without that check.
+  auto run = [&](auto tail_check) {
+    constexpr bool kTail = decltype(tail_check)::value;
+    for (int k0 = 0; k0 < ncombo; k0 += CB) {
+      unsigned vals[CB][CPW];
 #pragma unroll
-    for (int kk = 0; kk < CB; ++kk) {
-      const int k = k0 + kk;
-      const int s = k / ROWG, rg = k - s * ROWG;
-      const int strip = strip0 + s;
-      const bool live = k < ncombo && strip < g.strips;
-      const int n = strip_image(tr, strip);
-      const int ti = strip - n * g.th;
-      const int hlo = M * ti - 1 + 4 * rg;        // image row of rsub = 0
-      const int base = (n * g.Cin * H + hlo) * W;  // its offset in channel 0 of image n
-      const bool ok = live && nvalid > 0 && 4 * rg + rsub < NI &&
-                      (unsigned)(hlo + rsub) < (unsigned)H;
-      const unsigned voff = ok ? (unsigned)(base + lane_off) : kOutOfRange;
+      for (int kk = 0; kk < CB; ++kk) {
+        const int k = k0 + kk;
+        const int s = k / ROWG, rg = k - s * ROWG;
+        const int strip = strip0 + s;
+        const bool live = k < ncombo && strip < g.strips;
+        const int n = strip_image(tr, strip);
+        const int ti = strip - n * g.th;
+        const int hlo = M * ti - 1 + 4 * rg;        // image row of rsub = 0
+        const int base = (n * g.Cin * H + hlo) * W;  // its offset in channel 0 of image n
+        const bool ok = live && nvalid > 0 && 4 * rg + rsub < NI &&
+                        (unsigned)(hlo + rsub) < (unsigned)H;
+        const unsigned voff = ok ? (unsigned)(base + lane_off) : kOutOfRange;
 #pragma unroll
-      for (int ci = 0; ci < CPW; ++ci) {
-        const int c = min(c0 + wave + NW * ci, g.Cin - 1);
-        const unsigned plane = (unsigned)c * plane_stride;
-        unsigned v = __builtin_amdgcn_raw_buffer_load_b32(xres, voff, plane, 0) & bmask;
-        // the last dword of the tensor may reach past its end, where the buffer load
-        // returns zero for the whole dword: fetch those bytes one by one
-        if (n == g.N - 1 && c == g.Cin - 1) {
-          if (ok && voff + plane + 4u > xbytes) {
-            v = 0;
-            for (int bb = 0; bb < nvalid; ++bb)
-              v |= (unsigned)__builtin_amdgcn_raw_buffer_load_b8(xres, voff + bb, plane, 0)
-                   << (8 * bb);
+        for (int ci = 0; ci < CPW; ++ci) {
+          const int c = min(c0 + wave + NW * ci, g.Cin - 1);
+          const unsigned plane = (unsigned)c * plane_stride;
+          unsigned v = __builtin_amdgcn_raw_buffer_load_b32(xres, voff, plane, 0);
+          if constexpr (kTail) {
+            v &= bmask;
+            if (n == g.N - 1 && c == g.Cin - 1) {
+              if (ok && voff + plane + 4u > xbytes) {
+                v = 0;
+                for (int bb = 0; bb < nvalid; ++bb)
+                  v |= (unsigned)__builtin_amdgcn_raw_buffer_load_b8(xres, voff + bb, plane, 0)
+                       << (8 * bb);
+              }
+            }
           }
+          vals[kk][ci] = v;
         }
-        vals[kk][ci] = v;
+      }
+#pragma unroll
+      for (int kk = 0; kk < CB; ++kk) {
+        const int k = k0 + kk;
+        const int s = k / ROWG, rg = k - s * ROWG;
+        const int row = rg * 4 + rsub;
+        if (k < ncombo && row < NI) {
+          unsigned char* dst = lds + (unsigned)(s * 64 + wave) * CS + row * WP + 4 * dcol;
+#pragma unroll
+          for (int ci = 0; ci < CPW; ++ci) *(unsigned*)(dst + NW * ci * CS) = vals[kk][ci];
+        }
       }
     }
-#pragma unroll
-    for (int kk = 0; kk < CB; ++kk) {
-      const int k = k0 + kk;
-      const int s = k / ROWG, rg = k - s * ROWG;
-      const int row = rg * 4 + rsub;
-      if (k < ncombo && row < NI) {
-        unsigned char* dst = lds + (unsigned)(s * 64 + wave) * CS + row * WP + 4 * dcol;
-#pragma unroll
-        for (int ci = 0; ci < CPW; ++ci) *(unsigned*)(dst + NW * ci * CS) = vals[kk][ci];
-      }
-    }
-  }
+  };
+  if ((W & 3) == 0)
+    run(std::false_type{});  // every dword lies wholly inside or outside its row
+  else
+    run(std::true_type{});
 }
 
 // Input-tile transform of the staged rectangle: wave = tile (16/NW of them per wave),

@@ -159,3 +159,22 @@ def test_kernel_add_networks_realize_the_oracle_matrices(kernel_maps, alg_id, al
     assert np.array_equal(kernel_maps[("B", alg_id)], b2)
     assert np.array_equal(kernel_maps[("G", alg_id)], g2)
     assert np.array_equal(kernel_maps[("A", alg_id)], a2)
+
+
+def test_bench_operation_counts_match_the_add_networks(tmp_path):
+    """bench.py's vector-ALU roofline counts: recounted from sfc_points.hpp with a counting type."""
+    import bench
+
+    exe = tmp_path / "op_count"
+    src = os.path.join(ROOT, "tests", "host", "op_count.cpp")
+    subprocess.run(["/opt/rocm/bin/hipcc", "--cuda-host-only", "-O1", "-std=c++17", src, "-o", str(exe)],
+                   check=True, capture_output=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    names = ["6x6_p88", "6x6_p100", "7x7_p132", "7x7_p144"]
+    for line in out.splitlines():
+        alg, pts, in_adds, out_ops = (int(v) for v in line.split())
+        assert pts == oracle.multiplications_per_tile(names[alg])
+        assert bench.ADD_NETWORK_OPS[names[alg]] == (in_adds, out_ops)
+    # the 6x6 input network is the paper's: 14 additions per symbolic DFT-6 plus the correction
+    # inputs, 16 per 1-D pass over 8 + 8 lines, plus the sums of the product rule
+    assert bench.ADD_NETWORK_OPS["6x6_p88"][0] == 16 * 16 + 48
