@@ -53,6 +53,82 @@ def stage_bytes(shape, P, tiles, path):
     return {"input_transform": x + v, "product": v + u + m, "output_transform": m + y}
 
 
+def run_stack(args):
+    """The 13 stride-1 3x3 layers of the ResNet-18-shaped stack at batch 64, filter transforms
+    done beforehand, int8 activations handed from layer to layer inside each resolution stage
+    (the stride-2 layers between stages are not part of this path: every stage starts from its
+    own synthetic activations).  One step = the 13 layers back to back on one stream."""
+    import numpy as np
+    import torch
+
+    from paper_2407_02913_amd import binding, synth
+
+    binding.load()
+    torch.cuda.set_device(0)
+    layers = synth.stack_layers()
+    plans, bufs = [], []
+    for shape in layers:
+        d = synth.make_layer(shape, batch=4)  # weights and calibration data; activations below
+        path = args.path or ("single" if shape.Cin <= 64 else "fused")
+        plan = binding.Plan(shape.N, shape.Cin, shape.Cout, shape.H, shape.W, alg=args.alg,
+                            mode="requant", out="i8", path=path, per_channel_wscale=True)
+        w_dev = torch.from_numpy(d["w"]).cuda()
+        xc_dev = torch.from_numpy(d["x_calib"]).cuda()
+        calib = binding.Plan(4, shape.Cin, shape.Cout, shape.H, shape.W, alg=args.alg, mode="requant",
+                             path="staged", per_channel_wscale=True)
+        scratch = binding.device_buffer(calib.workspace_bytes)
+        sx = calib.calibrate_act_scales(xc_dev, scratch)
+        sw = calib.calibrate_filter_scales(w_dev, scratch)
+        calib.close()
+        plan.set_point_scales(sx, sw)
+        # output scale: spread of a sum of 9*Cin products of the synthetic distributions
+        plan.set_output_scale(float(4.0 * 0.02 * 0.0125 * 30.0 * 20.0 * np.sqrt(9.0 * shape.Cin) / 127.0))
+        fbuf = binding.device_buffer(plan.filter_bytes)
+        plan.transform_filter(w_dev, d["w_scale"], fbuf)
+        plans.append(plan)
+        bufs.append((fbuf, binding.device_buffer(plan.workspace_bytes),
+                     torch.empty((shape.N, shape.Cout, shape.H, shape.W), dtype=torch.int8, device="cuda")))
+    stage_in = {}
+    for shape in layers:
+        if shape.Cin not in stage_in:
+            rng = np.random.default_rng(synth.BASE_SEED + shape.Cin)
+            a = np.clip(np.rint(np.abs(rng.normal(0.0, 30.0, (shape.N, shape.Cin, shape.H, shape.W)))), 0, 127)
+            stage_in[shape.Cin] = torch.from_numpy(a.astype(np.int8)).cuda()
+
+    def step():
+        prev = None
+        for shape, plan, (_, ws, y) in zip(layers, plans, bufs):
+            x = stage_in[shape.Cin] if prev is None or prev[0].Cin != shape.Cin else prev[1]
+            plan.conv2d(x, 0.02, y, ws)
+            prev = (shape, y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ops = sum(sh.direct_ops for sh in layers)
+    per_layer = []
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for shape, plan, (_, ws, y) in zip(layers, plans, bufs):
+        x = stage_in[shape.Cin]
+        e0.record()
+        for _ in range(20):
+            plan.conv2d(x, 0.02, y, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        per_layer.append(round(e0.elapsed_time(e1) * 1e3 / 20, 1))
+    print(json.dumps({
+        "metric": "direct-conv-equivalent int8 TOPS, 13-layer stack", "value": round(ops / (ms * 1e-3) / 1e12, 2),
+        "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "resnet18 stack: 13 stride-1 3x3 layers, batch 64, int8 activations between layers",
+                   "algorithm": args.alg, "direct_gop": round(ops / 1e9, 1), "layer_us": per_layer}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -71,6 +147,9 @@ def main():
         print("bench.py measures one GPU: this build has no multi-GPU path (the layer shards over "
               "the batch with no exchange step); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.workload == "stack":
+        return run_stack(args)
 
     import numpy as np
     import torch
