@@ -91,6 +91,12 @@ typedef struct {
   int32_t out;                /* sfc_out */
   int32_t path;               /* sfc_path */
   int32_t per_channel_wscale; /* 0: one filter scale, 1: Cout filter scales */
+  /* Requantized mode: bit width b of the transform-domain operands, 2..8 (0 = 8).  V and U
+   * are rounded to integers in [-(2^(b-1) - 1), 2^(b-1) - 1] and still travel as int8, so
+   * the low-precision settings the paper evaluates (int8 down to int4 in the transform
+   * domain, Sec. 6) run on the same kernels; the abs-max calibration helpers divide by the
+   * same bound.  Must be 0 in exact mode. */
+  int32_t transform_bits;
 } sfc_conv_desc;
 
 /* Host only.  Validates the description and derives the tile grid
@@ -121,7 +127,8 @@ sfc_status sfc_set_point_scales(sfc_plan_t* plan, const float* sx_host, const fl
 sfc_status sfc_set_output_scale(sfc_plan_t* plan, float y_scale);
 
 /* Abs-max calibration helpers (the paper tunes scales with AdaQuant on real
- * data; abs-max over a calibration tensor stands in): scale = max|value|/127,
+ * data; abs-max over a calibration tensor stands in): scale = max|value|/qmax
+ * (qmax = 127, or 2^(transform_bits-1) - 1),
  * 1 where the maximum is 0.  Both block until the result is in host memory.
  * workspace_dev must hold workspace_bytes of a plan whose N >= n_images. */
 sfc_status sfc_calibrate_act_scales(const sfc_plan_t* plan, const int8_t* x_dev, int32_t n_images,

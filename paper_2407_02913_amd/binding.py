@@ -35,7 +35,8 @@ EXPORTS = (
 
 class ConvDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
-                ("N", "Cin", "Cout", "H", "W", "alg", "mode", "out", "path", "per_channel_wscale")]
+                ("N", "Cin", "Cout", "H", "W", "alg", "mode", "out", "path", "per_channel_wscale",
+                 "transform_bits")]
 
 
 class SfcError(RuntimeError):
@@ -111,10 +112,10 @@ class Plan:
     """Owns one sfc_plan_t.  Tensors passed in are torch CUDA tensors."""
 
     def __init__(self, N, Cin, Cout, H, W, alg="6x6_p88", mode="requant", out="f32",
-                 path="staged", per_channel_wscale=True):
+                 path="staged", per_channel_wscale=True, transform_bits=0):
         lib = load()
         self.desc = ConvDesc(N, Cin, Cout, H, W, ALG[alg], MODE[mode], OUT[out], PATH[path],
-                             1 if per_channel_wscale else 0)
+                             1 if per_channel_wscale else 0, int(transform_bits))
         self._h = C.c_void_p()
         _check(lib.sfc_plan(C.byref(self.desc), C.byref(self._h)), "sfc_plan")
         fb, wb, p, t = C.c_size_t(), C.c_size_t(), C.c_int32(), C.c_int64()
@@ -220,7 +221,8 @@ def device_buffer(nbytes: int):
 
 
 def conv2d(x: np.ndarray, w: np.ndarray, x_scale: float, w_scale, mode="requant", alg="6x6_p88",
-           out="f32", path="staged", sx=None, sw=None, return_taps=False, y_scale=None):
+           out="f32", path="staged", sx=None, sw=None, return_taps=False, y_scale=None,
+           transform_bits=0):
     """Convenience wrapper: numpy in, numpy out, one layer through the C ABI."""
     import torch
 
@@ -228,7 +230,7 @@ def conv2d(x: np.ndarray, w: np.ndarray, x_scale: float, w_scale, mode="requant"
     cout = w.shape[0]
     ws_arr = np.asarray(w_scale, dtype=np.float32).reshape(-1)
     plan = Plan(n, cin, cout, h, wd, alg=alg, mode=mode, out=out, path=path,
-                per_channel_wscale=ws_arr.size != 1)
+                per_channel_wscale=ws_arr.size != 1, transform_bits=transform_bits)
     xd = torch.from_numpy(np.ascontiguousarray(x)).cuda()
     wdv = torch.from_numpy(np.ascontiguousarray(w)).cuda()
     fbuf = device_buffer(plan.filter_bytes)

@@ -76,6 +76,8 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   if (d.path != SFC_PATH_STAGED && d.path != SFC_PATH_FUSED && d.path != SFC_PATH_SINGLE)
     return SFC_EINVAL;
   if (d.per_channel_wscale != 0 && d.per_channel_wscale != 1) return SFC_EINVAL;
+  if (d.transform_bits != 0 && (d.transform_bits < 2 || d.transform_bits > 8)) return SFC_EINVAL;
+  if (d.transform_bits != 0 && d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
   if (d.out == SFC_OUT_I32 && d.mode != SFC_MODE_EXACT) return SFC_EUNSUPPORTED;
   if (d.out == SFC_OUT_I8_RELU && d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
   if (d.path != SFC_PATH_STAGED && d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
@@ -98,6 +100,7 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   g.Kp = (d.Cout + 15) / 16 * 16;
   static const int kPoints[4] = {88, 100, 132, 144};
   g.P = kPoints[d.alg];
+  g.qmax = (float)((1 << ((d.transform_bits ? d.transform_bits : 8) - 1)) - 1);
 
   if (d.path == SFC_PATH_FUSED && !sfc::fused_quad_supported(g)) return SFC_EUNSUPPORTED;
   if (d.path == SFC_PATH_SINGLE && !sfc::single_supported(g)) return SFC_EUNSUPPORTED;
@@ -344,7 +347,8 @@ sfc_status sfc_stream_copy(void* dst_dev, const void* src_dev, size_t bytes, voi
   return SFC_OK;
 }
 
-static sfc_status maxima_to_scales(const int32_t* dev, size_t count, hipStream_t s, float* out) {
+static sfc_status maxima_to_scales(const int32_t* dev, size_t count, float qmax, hipStream_t s,
+                                   float* out) {
   std::vector<int32_t> host;
   try {
     host.resize(count);
@@ -356,7 +360,7 @@ static sfc_status maxima_to_scales(const int32_t* dev, size_t count, hipStream_t
     return SFC_EHIP;
   if (hipStreamSynchronize(s) != hipSuccess) return SFC_EHIP;
   for (size_t i = 0; i < count; ++i)
-    out[i] = host[i] == 0 ? 1.0f : (float)host[i] / 127.0f;
+    out[i] = host[i] == 0 ? 1.0f : (float)host[i] / qmax;
   return SFC_OK;
 }
 
@@ -373,7 +377,7 @@ sfc_status sfc_calibrate_act_scales(const sfc_plan_t* plan, const int8_t* x_dev,
   hipStream_t s = static_cast<hipStream_t>(stream);
   int32_t* maxima = static_cast<int32_t*>(workspace_dev);
   if (sfc::launch_act_absmax(g, x_dev, maxima, s) != hipSuccess) return SFC_EHIP;
-  return maxima_to_scales(maxima, g.P, s, sx_host_out);
+  return maxima_to_scales(maxima, g.P, g.qmax, s, sx_host_out);
 }
 
 sfc_status sfc_calibrate_filter_scales(const sfc_plan_t* plan, const int8_t* w_dev,
@@ -384,7 +388,7 @@ sfc_status sfc_calibrate_filter_scales(const sfc_plan_t* plan, const int8_t* w_d
   int32_t* maxima = static_cast<int32_t*>(workspace_dev);
   if (sfc::launch_filter_absmax(plan->g, w_dev, maxima, s) != hipSuccess)
     return SFC_EHIP;
-  return maxima_to_scales(maxima, (size_t)plan->g.P * plan->g.Cout, s, sw_host_out);
+  return maxima_to_scales(maxima, (size_t)plan->g.P * plan->g.Cout, plan->g.qmax, s, sw_host_out);
 }
 
 }  // extern "C"

@@ -19,13 +19,14 @@ __device__ __forceinline__ int xcd_contiguous(int id, int n) {
   return xcd * q + min(xcd, r) + idx;
 }
 
-// round-half-even(v * inv) clamped to [-127, 127], as the low byte of the result.
-// Adding 1.5 * 2^23 inside one fused multiply-add rounds the exact product once,
-// to an integer, ties to even; the integer then sits in the low mantissa bits.
-__device__ __forceinline__ unsigned quantize_byte(int v, float inv) {
+// round-half-even(v * inv) clamped to [-qmax, qmax] (qmax = 2^(bits-1) - 1, at most 127),
+// as the low byte of the result.  Adding 1.5 * 2^23 inside one fused multiply-add rounds
+// the exact product once, to an integer, ties to even; the integer then sits in the low
+// mantissa bits.
+__device__ __forceinline__ unsigned quantize_byte(int v, float inv, float qmax) {
   constexpr float kMagic = 12582912.0f;
   float t = __fmaf_rn((float)v, inv, kMagic);
-  t = __builtin_amdgcn_fmed3f(t, kMagic - 127.0f, kMagic + 127.0f);
+  t = __builtin_amdgcn_fmed3f(t, kMagic - qmax, kMagic + qmax);
   return __float_as_uint(t);
 }
 

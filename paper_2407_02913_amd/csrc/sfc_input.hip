@@ -49,7 +49,7 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
 
   stage_tiles<ALG, NW>(x, lds, g, tr, strip0, tj0, c0, wave, lane);
   __syncthreads();
-  transform_tiles<ALG, NW>(lds, inv_sx, tr, tj0, wave, lane);
+  transform_tiles<ALG, NW>(lds, inv_sx, g.qmax, tr, tj0, wave, lane);
   __syncthreads();
 
   // ---- copy out: wave w takes positions w, w+NW, ...; lane = (tile, 16-byte quarter) ---

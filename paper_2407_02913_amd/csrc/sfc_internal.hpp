@@ -17,6 +17,7 @@ struct Geometry {
   int Cp;         // Cin rounded up to 64 (the K extent of one int8 MFMA)
   int Kp;         // Cout rounded up to 16
   int P;          // multiplication points per tile
+  float qmax;     // largest transform-domain magnitude, 2^(bits-1) - 1 (requantized mode)
 };
 
 // Device-side views of the filter buffer (all inside the caller's filter_dev).

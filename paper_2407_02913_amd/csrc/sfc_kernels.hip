@@ -16,13 +16,13 @@
 namespace sfc {
 
 
-// round-half-even(v * inv) clamped to [-127, 127].  Adding 1.5 * 2^23 inside one
+// round-half-even(v * inv) clamped to [-qmax, qmax].  Adding 1.5 * 2^23 inside one
 // fused multiply-add rounds the exact product once, to an integer, ties to even;
 // the integer then sits in the low mantissa bits.
-__device__ __forceinline__ int quantize_i8(int v, float inv) {
+__device__ __forceinline__ int quantize_i8(int v, float inv, float qmax) {
   constexpr float kMagic = 12582912.0f;  // 0x4B400000
   float t = __fmaf_rn((float)v, inv, kMagic);
-  t = fminf(fmaxf(t, kMagic - 127.0f), kMagic + 127.0f);
+  t = fminf(fmaxf(t, kMagic - qmax), kMagic + qmax);
   return __float_as_int(t) - 0x4B400000;
 }
 
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void filter_transform_kernel(const int8_t* __r
   for_each_point<ALG>(comp, [&](int p, int v) {
     const size_t idx = ((size_t)p * g.Kp + k) * g.Cp + c;
     if constexpr (MODE == 1) {
-      ((int8_t*)U)[idx] = (int8_t)quantize_i8(v, inv_sw[p * g.Kp + k]);
+      ((int8_t*)U)[idx] = (int8_t)quantize_i8(v, inv_sw[p * g.Kp + k], g.qmax);
     } else {
       ((int16_t*)U)[idx] = (int16_t)v;
     }
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
     const size_t pstride = (size_t)g.Tp * g.Cp;
     for_each_point<ALG>(comp, [&](int p, int v) {
       if constexpr (MODE == 1) {
-        ((int8_t*)V)[p * pstride + row_off] = (int8_t)quantize_i8(v, inv_sx[p]);
+        ((int8_t*)V)[p * pstride + row_off] = (int8_t)quantize_i8(v, inv_sx[p], g.qmax);
       } else if constexpr (MODE == 0) {
         ((int16_t*)V)[p * pstride + row_off] = (int16_t)v;
       } else {

@@ -81,7 +81,7 @@ __global__ __launch_bounds__(NW * 64) void single_conv_kernel(
   // ---- 1. stage, 2. input transform -----------------------------------------------
   stage_tiles<ALG, NW>(x, lds, g, tr, strip0, tj0, 0, wave, lane);
   __syncthreads();
-  transform_tiles<ALG, NW>(lds, inv_sx, tr, tj0, wave, lane);
+  transform_tiles<ALG, NW>(lds, inv_sx, g.qmax, tr, tj0, wave, lane);
   __syncthreads();
 
   // ---- 3. products + output transform: lane = (tile l%16, filter 4*kq + l/16) ------

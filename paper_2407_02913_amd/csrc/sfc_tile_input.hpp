@@ -171,7 +171,8 @@ __device__ __forceinline__ void stage_tiles(const int8_t* __restrict__ x, unsign
 // registers by then).  Call between two workgroup barriers; contains one itself.
 template <int ALG, int NW>
 __device__ __forceinline__ void transform_tiles(unsigned char* lds, const float* __restrict__ inv_sx,
-                                                const TileRect& tr, int tj0, int wave, int lane) {
+                                                float qmax, const TileRect& tr, int tj0, int wave,
+                                                int lane) {
   using Tr = AlgTraits<ALG>;
   constexpr int M = Tr::M, NI = Tr::NI, NC = Tr::NC;
   constexpr int SPW = 16 / NW;
@@ -218,7 +219,7 @@ __device__ __forceinline__ void transform_tiles(unsigned char* lds, const float*
       }
       unsigned char* outp = lds + tile * 64 + c;
       for_each_point<ALG>(comp, [&](int p, int v) {
-        outp[order.pos[p] * 1024] = (unsigned char)quantize_byte(v, inv_sx[p]);
+        outp[order.pos[p] * 1024] = (unsigned char)quantize_byte(v, inv_sx[p], qmax);
       });
     }
   }

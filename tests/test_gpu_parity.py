@@ -80,6 +80,37 @@ def test_requant_mode_taps_bit_exact_and_output_close(binding, shape, alg):
     assert rel_err(y, y_ref) <= F32_TOL
 
 
+@pytest.mark.parametrize("bits", [4, 6])
+@pytest.mark.parametrize("path", ["staged", "fused", "single"])
+@pytest.mark.parametrize("alg", ["6x6_p88", "7x7_p144"])
+def test_sub_int8_transform_domain(binding, alg, path, bits):
+    """Transform-domain operands rounded to 4 or 6 bits (carried in int8 lanes), Sec. 6:
+    taps bit-exact, output within tolerance, and the library's own abs-max calibration
+    divides by the same bound as the oracle's."""
+    import torch
+
+    shape = (2, 24, 20, 14, 10)
+    x, w, xs, ws = uniform_case(shape, 1100 + bits + len(alg))
+    print("case bits", alg, path, bits, flush=True)
+    qmax = 2 ** (bits - 1) - 1
+    xc, _, _, _ = uniform_case(shape, 1200 + bits)
+    sx = oracle.calibrate_act_scales(xc // 2, alg, qmax=qmax)
+    sw = oracle.calibrate_filter_scales(w, alg, qmax=qmax)
+    y_ref, taps_ref = oracle.conv_requant(x, w, sx, sw, xs, ws, alg, qmax=qmax, return_taps=True)
+    y, taps = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path=path, sx=sx, sw=sw,
+                             return_taps=True, transform_bits=bits)
+    for name in taps:
+        assert np.array_equal(taps[name].astype(np.int64), taps_ref[name]), name
+        if name in ("V", "U"):
+            assert np.abs(taps[name]).max() == qmax
+    assert rel_err(y, y_ref) <= F32_TOL
+    plan = binding.Plan(*shape, alg=alg, mode="requant", transform_bits=bits)
+    wbuf = binding.device_buffer(plan.workspace_bytes)
+    assert np.array_equal(plan.calibrate_act_scales(torch.from_numpy(xc // 2).cuda(), wbuf), sx)
+    assert np.array_equal(plan.calibrate_filter_scales(torch.from_numpy(w).cuda(), wbuf), sw)
+    plan.close()
+
+
 def test_single_filter_scale(binding):
     x, w, xs, _ = uniform_case((1, 16, 16, 32, 32), 7)
     ws = np.array([0.01], dtype=np.float32)

@@ -59,7 +59,8 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
 def make_desc(**kw):
     from paper_2407_02913_amd import binding
 
-    base = dict(N=2, Cin=16, Cout=24, H=14, W=9, alg=0, mode=1, out=0, path=0, per_channel_wscale=1)
+    base = dict(N=2, Cin=16, Cout=24, H=14, W=9, alg=0, mode=1, out=0, path=0, per_channel_wscale=1,
+                transform_bits=0)
     base.update(kw)
     return binding.ConvDesc(**base)
 
@@ -95,6 +96,8 @@ def test_plan_sizes_and_counts(lib):
     [
         (dict(N=0), 1), (dict(Cin=-1), 1), (dict(H=0), 1), (dict(alg=7), 1), (dict(mode=2), 1),
         (dict(out=5), 1), (dict(path=3), 1), (dict(per_channel_wscale=2), 1),
+        (dict(transform_bits=1), 1), (dict(transform_bits=9), 1),
+        (dict(transform_bits=4, mode=0), 2),  # exact mode has no transform-domain rounding
         (dict(out=1, mode=1), 2),  # raw integer output only in exact mode
         (dict(path=1, mode=0), 2),  # fused path is the requantized one
         (dict(W=5000), 2),
