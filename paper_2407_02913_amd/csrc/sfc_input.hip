@@ -1,8 +1,8 @@
 // Input-tile transform V = B^T x B with transform-domain requantization to int8,
 // the HBM-facing first stage of the two-kernel path (gfx950).
 //
-// A workgroup owns a rectangle of up to 16 tiles (S strips x tlw tile columns) and 64
-// input channels:
+// A workgroup owns up to NW tiles (a rectangle of S strips x tlw tile columns, or whole
+// images of a small feature map), one per wave, and 64 input channels:
 //  1. stage the M+2 input rows of every (strip, channel) in LDS (coalesced dword loads),
 //  2. transform: wave = tile, lane = channel; the rounded points land in LDS as
 //     [processing position][tile][channel], over the staging area,
@@ -33,23 +33,19 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
   // Workgroups are dealt to the 8 XCDs round-robin by id; remap so that each XCD (each
   // L2) gets a contiguous range of rectangles: neighbours share halo rows and columns.
   const int bx = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int chunk = bx % tr.chunks;
-  const int strip0 = (bx / tr.chunks) * tr.S;
-  const int tj0 = chunk * tr.tlw;
   const int c0 = blockIdx.y * 64;
 
   // tile slot -> row of V (-1: no such tile)
   int* row_tab = (int*)(lds + ip.tab_off);
   if (threadIdx.x < 16) {
     const int tl = threadIdx.x;
-    const int s = tl / tr.tlw, tjl = tl - s * tr.tlw;
-    const int strip = strip0 + s, tj = tj0 + tjl;
-    row_tab[tl] = (tl < tr.ntiles && strip < g.strips && tj < g.tw) ? strip * g.tw + tj : -1;
+    const TileCoord tc = tile_coord(g, tr, bx, tl);
+    row_tab[tl] = tc.live ? (tc.n * g.th + tc.ti) * g.tw + tc.tj : -1;
   }
 
-  stage_tiles<ALG, NW>(x, lds, g, tr, strip0, tj0, c0, wave, lane);
+  stage_input<ALG, NW>(x, lds, g, tr, bx, c0, wave, lane);
   __syncthreads();
-  transform_tiles<ALG, NW>(lds, inv_sx, g.qmax, tr, tj0, wave, lane);
+  transform_tiles<ALG, NW, 1>(lds, inv_sx, g.qmax, g, tr, bx, wave, lane);
   __syncthreads();
 
   // ---- copy out: wave w takes positions w, w+NW, ...; lane = (tile, 16-byte quarter) ---
@@ -63,11 +59,15 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
   }
 }
 
+// waves per workgroup = tiles per workgroup: the 7x7 forms hold a 9x10 half-transformed
+// patch per tile and need the registers of an 8-wave workgroup
+static int input_waves(int alg) { return alg_tile(alg) == 6 ? 16 : 8; }
+
 static bool make_input_plan(const Geometry& g, InputPlan* ip) {
   const unsigned vbytes = (unsigned)g.P * 1024u;
   const unsigned lds_max = 160u * 1024u;
   if (vbytes + 16u + 64u > lds_max) return false;
-  if (!make_tile_rect(g, lds_max - 16u - 64u, &ip->tr)) return false;
+  if (!make_tile_rect(g, lds_max - 16u - 64u, &ip->tr, input_waves(g.alg), true)) return false;
   const unsigned xbytes = tile_rect_stage_bytes(g, ip->tr);
   ip->tab_off = ((xbytes > vbytes ? xbytes : vbytes) + 15u) & ~15u;
   ip->lds_bytes = ip->tab_off + 64u;
@@ -79,7 +79,6 @@ static bool make_input_plan(const Geometry& g, InputPlan* ip) {
 template <int ALG>
 static hipError_t launch_input_i8_alg(const Geometry& g, const InputPlan& ip, const int8_t* x,
                                       void* V, const float* inv_sx, hipStream_t s) {
-  // the 7x7 forms hold a 9x10 half-transformed patch per tile and need 8 waves' registers
   constexpr int NW = AlgTraits<ALG>::M == 6 ? 16 : 8;
   auto kernel = input_transform_i8_kernel<ALG, NW>;
   static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once

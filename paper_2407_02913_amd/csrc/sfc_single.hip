@@ -61,27 +61,20 @@ __global__ __launch_bounds__(NW * 64) void single_conv_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const TileRect& tr = sp.tr;
   const int bx = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int chunk = bx % tr.chunks;
-  const int strip0 = (bx / tr.chunks) * tr.S;
-  const int tj0 = chunk * tr.tlw;
   const int W = g.W, H = g.H;
 
   // per-tile store data for step 4, written by 16 lanes now and read after the barriers
   int* tile_tab = (int*)(lds + sp.stage_off + NW * 64 * M * 4);
   if (threadIdx.x < 16) {
     const int tl = threadIdx.x;
-    const int s = tl / tr.tlw, tjl = tl - s * tr.tlw;
-    const int strip = strip0 + s, tj = tj0 + tjl;
-    const int n = strip_image(tr, strip);
-    const int ti = strip - n * g.th;
-    const bool live = tl < tr.ntiles && strip < g.strips && tj < g.tw;
-    write_tile_entry<M>(tile_tab, tl, live, n, ti, tj, g.Cout, H, W);
+    const TileCoord tc = tile_coord(g, tr, bx, tl);
+    write_tile_entry<M>(tile_tab, tl, tc.live, tc.n, tc.ti, tc.tj, g.Cout, H, W);
   }
 
   // ---- 1. stage, 2. input transform -----------------------------------------------
-  stage_tiles<ALG, NW>(x, lds, g, tr, strip0, tj0, 0, wave, lane);
+  stage_input<ALG, NW>(x, lds, g, tr, bx, 0, wave, lane);
   __syncthreads();
-  transform_tiles<ALG, NW>(lds, inv_sx, g.qmax, tr, tj0, wave, lane);
+  transform_tiles<ALG, NW>(lds, inv_sx, g.qmax, g, tr, bx, wave, lane);
   __syncthreads();
 
   // ---- 3. products + output transform: lane = (tile l%16, filter 4*kq + l/16) ------

@@ -10,14 +10,19 @@
 
 namespace sfc {
 
-// A workgroup owns S strips x tlw tile columns (a strip = one row of tiles of one
-// image), at most 16 tiles, for 64 input channels.
+// A workgroup owns at most 16 tiles for 64 input channels, in one of two shapes:
+//  - a rectangle of S strips x tlw tile columns (a strip = one row of tiles of one image);
+//  - whole images (small feature maps: at most 16 tiles per image): ipw images, staged as
+//    plain copies of their 64 channel planes.
 struct TileRect {
   int S;       // strips per workgroup
   int chunks;  // tile-column chunks per strip
   int tlw;     // tile columns per chunk
-  int ntiles;  // S * tlw <= 16
+  int ntiles;  // S * tlw, or ipw * tiles per image; <= 16
   unsigned long long th_magic;  // ceil(2^32 / th): strip / th = (strip * th_magic) >> 32
+  int whole;   // 1: whole images
+  int ipw;     // images per workgroup
+  int cs;      // whole images: LDS bytes per channel plane (an odd number of dwords)
 };
 
 // Staging layout: 64 bytes per image row (byte 4 holds image column colbase, a
@@ -29,21 +34,56 @@ __host__ __device__ constexpr int stage_channel_bytes(int tile) { return (tile +
 
 // Chooses the rectangle that fills most of the 16 tile slots, given the LDS bytes
 // available for the staged rows.  False if no rectangle fits.
-inline bool make_tile_rect(const Geometry& g, unsigned stage_budget, TileRect* tr) {
+// LDS bytes per channel plane of a whole image: H*W rounded up to dwords, plus one dword
+// if that makes the stride between channels (= lanes of the transform) an odd number of
+// dwords, so that the byte reads of 64 channels hit different banks.
+__host__ __device__ constexpr int plane_stride_bytes(int hw) {
+  const int d = (hw + 3) / 4;
+  return 4 * (d % 2 == 0 ? d + 1 : d);
+}
+
+// max_tiles: tile slots of a workgroup (16, or 8 for workgroups of eight one-tile waves).
+// partial_images: take whole images even if they leave tile slots empty, when the
+// alternative is a rectangle whose rows are not whole dwords (byte-wise staging).
+inline bool make_tile_rect(const Geometry& g, unsigned stage_budget, TileRect* tr,
+                           int max_tiles = 16, bool partial_images = false) {
   const int M = alg_tile(g.alg);
-  const int tlw_max = (kStageRow - 7) / M < 16 ? (kStageRow - 7) / M : 16;  // 5 + M*tlw + 2 <= 64
+  tr->whole = 0;
+  tr->ipw = 0;
+  tr->cs = 0;
+  // Small feature maps: whole images, if the tile slots are used at least as well as a
+  // rectangle would (always the case when the tiles of an image divide 16).
+  const int tpi = g.th * g.tw;
+  if (tpi <= max_tiles && g.H * g.W <= 1024) {
+    const int cs = plane_stride_bytes(g.H * g.W);
+    int ipw = max_tiles / tpi;
+    if (ipw > g.N) ipw = g.N;
+    while (ipw > 1 && (unsigned)(ipw * 64 * cs) > stage_budget) --ipw;
+    if ((unsigned)(ipw * 64 * cs) <= stage_budget &&
+        (max_tiles % tpi == 0 || (partial_images && g.W % 4 != 0))) {
+      tr->whole = 1;
+      tr->ipw = ipw;
+      tr->cs = cs;
+      tr->S = tr->chunks = tr->tlw = 1;
+      tr->ntiles = ipw * tpi;
+      tr->th_magic = 0;
+      return true;
+    }
+  }
+  const int tlw_max =
+      (kStageRow - 7) / M < max_tiles ? (kStageRow - 7) / M : max_tiles;  // 5 + M*tlw + 2 <= 64
   const int min_chunks = (g.tw + tlw_max - 1) / tlw_max;
   const int s_fit = (int)(stage_budget / (64u * (unsigned)stage_channel_bytes(M)));
   if (s_fit < 1) return false;
   double best = -1.0;
   for (int chunks = min_chunks; chunks <= min_chunks + 4 && chunks <= g.tw; ++chunks) {
     const int tlw = (g.tw + chunks - 1) / chunks;
-    int S = 16 / tlw;
+    int S = max_tiles / tlw;
     if (S > g.strips) S = g.strips;
     if (S > s_fit) S = s_fit;
     const int groups = (g.strips + S - 1) / S;
-    // fraction of the 16 tile slots of all workgroups that hold a real tile
-    const double use = (double)g.T / ((double)groups * chunks * 16.0);
+    // fraction of the tile slots of all workgroups that hold a real tile
+    const double use = (double)g.T / ((double)groups * chunks * (double)max_tiles);
     if (use > best + 1e-9) {
       best = use;
       tr->chunks = chunks;
@@ -55,13 +95,15 @@ inline bool make_tile_rect(const Geometry& g, unsigned stage_budget, TileRect* t
   // the reciprocal is exact while strip * th < 2^32
   if ((long long)g.strips * g.th >= (1ll << 32) || g.th < 1) return false;
   tr->th_magic = ((1ull << 32) + (unsigned long long)g.th - 1) / (unsigned long long)g.th;
-  return tr->ntiles >= 1 && tr->ntiles <= 16 && 5 + M * tr->tlw + 2 <= kStageRow;
+  return tr->ntiles >= 1 && tr->ntiles <= max_tiles && 5 + M * tr->tlw + 2 <= kStageRow;
 }
 
 inline unsigned tile_rect_stage_bytes(const Geometry& g, const TileRect& tr) {
+  if (tr.whole) return (unsigned)(tr.ipw * 64 * tr.cs);
   return (unsigned)tr.S * 64u * (unsigned)stage_channel_bytes(alg_tile(g.alg));
 }
 inline unsigned tile_rect_groups(const Geometry& g, const TileRect& tr) {
+  if (tr.whole) return (unsigned)((g.N + tr.ipw - 1) / tr.ipw);
   return (unsigned)(((g.strips + tr.S - 1) / tr.S) * tr.chunks);
 }
 
@@ -69,6 +111,93 @@ inline unsigned tile_rect_groups(const Geometry& g, const TileRect& tr) {
 
 __device__ __forceinline__ int strip_image(const TileRect& tr, int strip) {
   return (int)(((unsigned long long)(unsigned)strip * tr.th_magic) >> 32);
+}
+
+// Tile slot tl of workgroup bx: image, tile row, tile column, and whether the slot holds
+// a tile at all.
+struct TileCoord {
+  int n, ti, tj;
+  bool live;
+};
+__device__ __forceinline__ TileCoord tile_coord(const Geometry& g, const TileRect& tr, int bx,
+                                                int tl) {
+  TileCoord tc;
+  if (tr.whole) {
+    const int tpi = g.th * g.tw;
+    const int img = tl / tpi, rem = tl - img * tpi;
+    tc.n = bx * tr.ipw + img;
+    tc.ti = rem / g.tw;
+    tc.tj = rem - tc.ti * g.tw;
+    tc.live = tl < tr.ntiles && tc.n < g.N;
+  } else {
+    const int chunk = bx % tr.chunks;
+    const int s = tl / tr.tlw, tjl = tl - s * tr.tlw;
+    const int strip = (bx / tr.chunks) * tr.S + s;
+    tc.tj = chunk * tr.tlw + tjl;
+    tc.n = strip_image(tr, strip);
+    tc.ti = strip - tc.n * g.th;
+    tc.live = tl < tr.ntiles && strip < g.strips && tc.tj < g.tw;
+  }
+  return tc;
+}
+
+// Whole-image staging: the 64 channel planes c0 .. c0+63 of the workgroup's ipw images,
+// each copied as it lies in memory (H*W contiguous bytes) to lds[(slot*64 + c)*cs ..].
+// One load instruction covers CPI planes with LPC lanes each (LPC = dwords of a plane
+// rounded up to a power of two), or a 64-dword piece of one plane when a plane has more
+// than 64 dwords; wave w takes instructions w, w+NW, ...  Planes need not be dword
+// aligned in memory.  A plane's last dword may carry bytes of the next plane (they land
+// in the padding of its LDS slot and are never read); only at the very end of the tensor
+// would it reach past the buffer, so there the bytes are fetched one by one.  Images
+// beyond N read nothing (zeros).  Channels beyond Cin re-read the last one (their filter
+// operand is zero).
+template <int NW>
+__device__ __forceinline__ void stage_images(const int8_t* __restrict__ x, unsigned char* lds,
+                                             const Geometry& g, const TileRect& tr, int bx, int c0,
+                                             int wave, int lane) {
+  const int HW = g.H * g.W;
+  const unsigned xbytes = (unsigned)(g.N * g.Cin) * (unsigned)HW;
+  const __amdgpu_buffer_rsrc_t xres =
+      __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, (int)xbytes, kBufferFlags);
+  const int dpc = (HW + 3) >> 2;  // dwords per plane
+  int lpc = 1;
+  while (lpc < dpc && lpc < 64) lpc <<= 1;
+  const int cpi = 64 / lpc;               // planes per instruction
+  const int ipp = (dpc + 63) >> 6;        // instructions per plane (1 unless dpc > 64)
+  const int per_image = (64 / cpi) * ipp; // instructions per image
+  const int total = tr.ipw * per_image;
+  const int sub = lane / lpc, dw_lane = lane - sub * lpc;
+  constexpr int BATCH = 8;  // loads in flight per wave before the first LDS write
+  for (int k0 = wave; k0 < total; k0 += NW * BATCH) {
+    unsigned vals[BATCH];
+    int dst[BATCH];
+#pragma unroll
+    for (int kk = 0; kk < BATCH; ++kk) {
+      const int k = k0 + NW * kk;
+      const int slot = k / per_image, rem = k - slot * per_image;
+      const int cg = rem / ipp, piece = rem - cg * ipp;
+      const int c = cg * cpi + sub;  // channel of this lane within the 64
+      const int dw = piece * 64 + dw_lane;
+      const int n = bx * tr.ipw + slot;
+      const bool ok = k < total && n < g.N && dw < dpc;
+      const int cc = min(c0 + c, g.Cin - 1);
+      const unsigned off = (unsigned)((n * g.Cin + cc) * HW + 4 * dw);
+      unsigned v = 0;
+      if (ok) {
+        if (off + 4u <= xbytes) {
+          v = __builtin_amdgcn_raw_buffer_load_b32(xres, off, 0, 0);
+        } else {
+          for (unsigned bb = 0; off + bb < xbytes; ++bb)
+            v |= (unsigned)__builtin_amdgcn_raw_buffer_load_b8(xres, off + bb, 0, 0) << (8 * bb);
+        }
+      }
+      vals[kk] = v;
+      dst[kk] = ok ? (slot * 64 + c) * tr.cs + 4 * dw : -1;
+    }
+#pragma unroll
+    for (int kk = 0; kk < BATCH; ++kk)
+      if (dst[kk] >= 0) *(unsigned*)(lds + dst[kk]) = vals[kk];
+  }
 }
 
 // Stage the M+2 input rows of every (strip, channel) of the rectangle, channels
@@ -162,22 +291,36 @@ __device__ __forceinline__ void stage_tiles(const int8_t* __restrict__ x, unsign
     run(std::true_type{});
 }
 
-// Input-tile transform of the staged rectangle: wave = tile (16/NW of them per wave),
+// Stage the input of workgroup bx in the shape its TileRect says.
+template <int ALG, int NW>
+__device__ __forceinline__ void stage_input(const int8_t* __restrict__ x, unsigned char* lds,
+                                            const Geometry& g, const TileRect& tr, int bx, int c0,
+                                            int wave, int lane) {
+  if (tr.whole) {
+    stage_images<NW>(x, lds, g, tr, bx, c0, wave, lane);
+  } else {
+    const int chunk = bx % tr.chunks;
+    stage_tiles<ALG, NW>(x, lds, g, tr, (bx / tr.chunks) * tr.S, chunk * tr.tlw, c0, wave, lane);
+  }
+}
+
+// Input-tile transform of the staged tiles: wave = tile (16/NW of them per wave),
 // lane = channel.  Lanes running along channels are an odd number of dwords apart in
-// the staging area, so the aligned dword reads of a patch row hit 64 different banks.
+// the staging area, so the reads of a patch row (aligned dwords of a rectangle, bytes
+// of a whole image) hit 64 different banks.
 // Each thread applies the symbolic DFT-6 add network along rows and columns, forms
 // the multiplication points and rounds them to int8; the bytes go to
 // lds[order.pos[p]*1024 + tile*64 + channel], over the staging area (every patch is in
 // registers by then).  Call between two workgroup barriers; contains one itself.
-template <int ALG, int NW>
+template <int ALG, int NW, int SPW = 16 / NW>
 __device__ __forceinline__ void transform_tiles(unsigned char* lds, const float* __restrict__ inv_sx,
-                                                float qmax, const TileRect& tr, int tj0, int wave,
-                                                int lane) {
+                                                float qmax, const Geometry& g, const TileRect& tr,
+                                                int bx, int wave, int lane) {
   using Tr = AlgTraits<ALG>;
   constexpr int M = Tr::M, NI = Tr::NI, NC = Tr::NC;
-  constexpr int SPW = 16 / NW;
   constexpr int WP = kStageRow, CS = stage_channel_bytes(M);
   constexpr Order<ALG> order{};
+  const int tj0 = tr.whole ? 0 : (bx % tr.chunks) * tr.tlw;
   const int colbase = (M * tj0) & ~3;
   const int halo = M * tj0 - 1 - colbase + 4;  // LDS byte of the rectangle's first patch column
   int half[SPW][NI][NC];  // rows transformed: half[.][i][b]
@@ -185,20 +328,41 @@ __device__ __forceinline__ void transform_tiles(unsigned char* lds, const float*
   for (int it = 0; it < SPW; ++it) {
     const int tile = wave + NW * it, c = lane;
     if (tile < tr.ntiles) {
-      const int s = tile / tr.tlw, tjl = tile - s * tr.tlw;
-      // the patch row starts at an odd byte: three aligned dwords, shifted into place
-      const int o = halo + M * tjl;
-      const unsigned* src = (const unsigned*)(lds + (unsigned)(s * 64 + c) * CS + (o & ~3));
-      const unsigned sh = (unsigned)(o & 3);
+      if (tr.whole) {
+        // whole images: sign-extending byte reads of the plane, zeros outside the image
+        // (tile position and with it every bound is uniform over the wave)
+        const int tpi = g.th * g.tw;
+        const int slot = tile / tpi, rem = tile - slot * tpi;
+        const int ti = rem / g.tw, tj = rem - ti * g.tw;
+        const signed char* plane = (const signed char*)lds + (slot * 64 + c) * tr.cs;
+        const int r0 = M * ti - 1, q0 = M * tj - 1;
 #pragma unroll
-      for (int i = 0; i < NI; ++i) {
-        const unsigned d0 = src[i * (WP / 4)], d1 = src[i * (WP / 4) + 1], d2 = src[i * (WP / 4) + 2];
-        const unsigned w[3] = {__builtin_amdgcn_alignbyte(d1, d0, sh),
-                               __builtin_amdgcn_alignbyte(d2, d1, sh), d2 >> (8 * sh)};
-        int row[NI];
+        for (int i = 0; i < NI; ++i) {
+          int row[NI];
+          const bool rok = (unsigned)(r0 + i) < (unsigned)g.H;
 #pragma unroll
-        for (int j = 0; j < NI; ++j) row[j] = (int)(signed char)(w[j / 4] >> (8 * (j % 4)));
-        fwd_input<NI, NC>(row, half[it][i]);
+          for (int j = 0; j < NI; ++j) {
+            row[j] = 0;
+            if (rok && (unsigned)(q0 + j) < (unsigned)g.W) row[j] = plane[(r0 + i) * g.W + q0 + j];
+          }
+          fwd_input<NI, NC>(row, half[it][i]);
+        }
+      } else {
+        const int s = tile / tr.tlw, tjl = tile - s * tr.tlw;
+        // the patch row starts at an odd byte: three aligned dwords, shifted into place
+        const int o = halo + M * tjl;
+        const unsigned* src = (const unsigned*)(lds + (unsigned)(s * 64 + c) * CS + (o & ~3));
+        const unsigned sh = (unsigned)(o & 3);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+          const unsigned d0 = src[i * (WP / 4)], d1 = src[i * (WP / 4) + 1], d2 = src[i * (WP / 4) + 2];
+          const unsigned w[3] = {__builtin_amdgcn_alignbyte(d1, d0, sh),
+                                 __builtin_amdgcn_alignbyte(d2, d1, sh), d2 >> (8 * sh)};
+          int row[NI];
+#pragma unroll
+          for (int j = 0; j < NI; ++j) row[j] = (int)(signed char)(w[j / 4] >> (8 * (j % 4)));
+          fwd_input<NI, NC>(row, half[it][i]);
+        }
       }
     }
   }

@@ -185,6 +185,12 @@ FUSED_SHAPES = [
     (5, 64, 64, 12, 18),  # 30 tiles: padding rows in the last block
     (2, 200, 72, 11, 7),  # four chunks (Cin padded to 256), two workgroups along Cout
     (1, 500, 24, 8, 8),  # eight chunks
+    # small feature maps, staged as whole images: batch not a multiple of the images per
+    # workgroup, plane sizes that are / are not whole dwords, planes above 64 dwords
+    (5, 20, 8, 7, 7),
+    (3, 9, 8, 14, 14),
+    (7, 3, 4, 12, 12),
+    (2, 70, 16, 28, 28),
 ]
 
 
@@ -219,6 +225,10 @@ SINGLE_SHAPES = [
     (20, 7, 130, 7, 7),  # many strips per workgroup, three filter groups
     (1, 33, 17, 56, 56),  # two tile-column chunks per strip
     (2, 5, 9, 6, 61),  # wide and flat: chunks of nine or eight tile columns
+    (5, 20, 8, 7, 7),  # whole-image staging, see FUSED_SHAPES
+    (3, 9, 8, 14, 14),
+    (7, 3, 4, 12, 12),
+    (2, 64, 16, 28, 28),
 ]
 
 
@@ -263,16 +273,20 @@ def test_fused_path_rejects_unsupported_channel_counts(binding):
     assert e.value.code == 2
 
 
+@pytest.mark.parametrize("alg", ["6x6_p88", "7x7_p132"])
 @pytest.mark.parametrize("name", FULL)
-def test_full_size_fused_against_oracle(binding, name):
-    """The launch configuration bench.py times, every output element."""
+def test_full_size_fused_against_oracle(binding, name, alg):
+    """The launch configuration bench.py times, every output element (V as well)."""
     shape = synth.LAYERS[name]
-    print("case full fused", name, flush=True)
+    print("case full fused", name, alg, flush=True)
     d = synth.make_layer(shape)
-    sx = oracle.calibrate_act_scales(d["x_calib"])
-    sw = oracle.calibrate_filter_scales(d["w"])
-    y_ref = oracle.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"])
-    y = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", path="fused", sx=sx, sw=sw)
+    sx = oracle.calibrate_act_scales(d["x_calib"], alg)
+    sw = oracle.calibrate_filter_scales(d["w"], alg)
+    y_ref, taps_ref = oracle.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"], alg,
+                                          return_taps=True)
+    y, taps = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg,
+                             path="fused", sx=sx, sw=sw, return_taps=True)
+    assert np.array_equal(taps["V"].astype(np.int64), taps_ref["V"])
     assert rel_err(y, y_ref) <= F32_TOL
 
 
