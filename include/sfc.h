@@ -167,14 +167,22 @@ enum { SFC_STAGE_INPUT = 1, SFC_STAGE_PRODUCT = 2, SFC_STAGE_OUTPUT = 4, SFC_STA
 sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale,
                              void* y_dev, void* workspace_dev, void* stream, int32_t stage_mask);
 
-/* Where the intermediate tensors of the last staged call live, for parity checks.
+/* Where the intermediate tensors of the last call live, for parity checks.
  * which: 0 = V [P][tiles][Cin], 1 = U [P][Cout][Cin], 2 = M [P][tiles][Cout] (int32).
  * ptr receives a device address inside workspace_dev (V, M) or the filter buffer
- * (U); elem_bytes is 1 or 2 for V and U (int8 / int16) and 4 for M; dims and
- * strides (in elements) describe the three axes.  V exists on SFC_PATH_STAGED and
- * SFC_PATH_FUSED, M only on SFC_PATH_STAGED (SFC_EUNSUPPORTED otherwise). */
+ * (U); elem_bytes is 1 or 2 for V and U (int8 / int16) and 4 for M.  The tensor is
+ * described as a five-axis strided view (strides in elements): element (p, a, b) of
+ * the logical tensor [P][A][B] sits at
+ *   p*strides[0] + (a / dims[2])*strides[1] + (a % dims[2])*strides[2]
+ *                + (b / dims[4])*strides[3] + (b % dims[4])*strides[4],
+ * dims[0] = P, dims[1]*dims[2] >= A and dims[3]*dims[4] >= B (tiles, filters and
+ * channels are padded up; entries beyond the true counts are padding).  Plain layouts
+ * have dims[2] = dims[4] = 1; in requantized mode M is kept in blocks of 16 tiles x 4
+ * filters (the 256 bytes one wave of the output transform reads per point).
+ * V exists on SFC_PATH_STAGED and SFC_PATH_FUSED, M only on SFC_PATH_STAGED
+ * (SFC_EUNSUPPORTED otherwise). */
 sfc_status sfc_tap_info(const sfc_plan_t* plan, const void* workspace_dev, int32_t which,
-                        const void** ptr, int32_t* elem_bytes, int64_t dims[3], int64_t strides[3]);
+                        const void** ptr, int32_t* elem_bytes, int64_t dims[5], int64_t strides[5]);
 
 /* Measurement aid: a plain streaming copy of `bytes` (a multiple of 16, both
  * pointers 16-byte aligned) from src_dev to dst_dev on `stream`.  It reads and

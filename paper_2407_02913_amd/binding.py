@@ -187,11 +187,12 @@ class Plan:
 
     def tap(self, which: str, workspace) -> np.ndarray:
         """Copy of V, U or M in canonical [P][tiles|Cout][Cin|Cout] order (synchronizes)."""
+        # sfc_tap_info describes the tensor as a five-axis strided view; padding is cut off
         import torch
 
         idx = {"V": 0, "U": 1, "M": 2}[which]
         ptr, esz = C.c_void_p(), C.c_int32()
-        dims, strides = (C.c_int64 * 3)(), (C.c_int64 * 3)()
+        dims, strides = (C.c_int64 * 5)(), (C.c_int64 * 5)()
         _check(load().sfc_tap_info(self._h, C.c_void_p(workspace.data_ptr()), idx, C.byref(ptr),
                                    C.byref(esz), dims, strides), "sfc_tap_info")
         base = self._keep[0] if which == "U" else workspace
@@ -202,7 +203,10 @@ class Plan:
         torch.cuda.synchronize()
         flat = base.view(torch.uint8)[off:].view(dtype)
         view = torch.as_strided(flat, tuple(dims), tuple(strides))
-        return view.cpu().numpy().copy()
+        full = view.cpu().numpy().reshape(dims[0], dims[1] * dims[2], dims[3] * dims[4])
+        d = self.desc
+        rows, cols = {"V": (self.tiles, d.Cin), "U": (d.Cout, d.Cin), "M": (self.tiles, d.Cout)}[which]
+        return full[:, :rows, :cols].copy()
 
 
 def stream_copy(dst, src, stream=None):

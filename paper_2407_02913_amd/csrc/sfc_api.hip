@@ -304,8 +304,8 @@ sfc_status sfc_conv2d_nchw(const sfc_plan_t* plan, const int8_t* x_dev, float x_
 }
 
 sfc_status sfc_tap_info(const sfc_plan_t* plan, const void* workspace_dev, int32_t which,
-                        const void** ptr, int32_t* elem_bytes, int64_t dims[3],
-                        int64_t strides[3]) {
+                        const void** ptr, int32_t* elem_bytes, int64_t dims[5],
+                        int64_t strides[5]) {
   if (!plan || !ptr || !elem_bytes || !dims || !strides) return SFC_EINVAL;
   const Geometry& g = plan->g;
   const char* ws = static_cast<const char*>(workspace_dev);
@@ -315,23 +315,33 @@ sfc_status sfc_tap_info(const sfc_plan_t* plan, const void* workspace_dev, int32
       if (plan->d.path == SFC_PATH_SINGLE) return SFC_EUNSUPPORTED;
       *ptr = ws + plan->off_V;
       *elem_bytes = plan->esz;
-      dims[0] = g.P; dims[1] = g.T; dims[2] = g.Cin;
-      strides[0] = (int64_t)g.Tp * g.Cp; strides[1] = g.Cp; strides[2] = 1;
+      dims[0] = g.P; dims[1] = g.Tp; dims[2] = 1; dims[3] = g.Cp; dims[4] = 1;
+      strides[0] = (int64_t)g.Tp * g.Cp; strides[1] = g.Cp; strides[2] = 0; strides[3] = 1;
+      strides[4] = 0;
       return SFC_OK;
     case 1:
       if (!plan->filter_ready) return SFC_ENOTREADY;
       *ptr = static_cast<const char*>(plan->filter_dev) + plan->off_U;
       *elem_bytes = plan->esz;
-      dims[0] = g.P; dims[1] = g.Cout; dims[2] = g.Cin;
-      strides[0] = (int64_t)g.Kp * g.Cp; strides[1] = g.Cp; strides[2] = 1;
+      dims[0] = g.P; dims[1] = g.Kp; dims[2] = 1; dims[3] = g.Cp; dims[4] = 1;
+      strides[0] = (int64_t)g.Kp * g.Cp; strides[1] = g.Cp; strides[2] = 0; strides[3] = 1;
+      strides[4] = 0;
       return SFC_OK;
     case 2:
       if (!workspace_dev) return SFC_EINVAL;
       if (plan->d.path != SFC_PATH_STAGED) return SFC_EUNSUPPORTED;
       *ptr = ws + plan->off_M;
       *elem_bytes = 4;
-      dims[0] = g.P; dims[1] = g.T; dims[2] = g.Cout;
-      strides[0] = (int64_t)g.Tp * g.Kp; strides[1] = g.Kp; strides[2] = 1;
+      dims[0] = g.P;
+      strides[0] = (int64_t)g.Tp * g.Kp;
+      if (plan->d.mode == SFC_MODE_REQUANT_I8) {
+        // [P][tile block][filter quad][16 tiles][4 filters]
+        dims[1] = g.Tp / 16; dims[2] = 16; dims[3] = g.Kp / 4; dims[4] = 4;
+        strides[1] = (int64_t)g.Kp * 16; strides[2] = 4; strides[3] = 64; strides[4] = 1;
+      } else {
+        dims[1] = g.Tp; dims[2] = 1; dims[3] = g.Kp; dims[4] = 1;
+        strides[1] = g.Kp; strides[2] = 0; strides[3] = 1; strides[4] = 0;
+      }
       return SFC_OK;
     default:
       return SFC_EINVAL;

@@ -1,0 +1,257 @@
+// Staged path, requantized mode (gfx950): the transform-domain products as P batched int8
+// GEMMs on the matrix cores, and the output transform that reads their int32 sums back.
+//
+//   product_gemm_i8_kernel   M_p[tiles x Cout] = V_p[tiles x Cin] . U_p[Cout x Cin]^T  for
+//                            every point p (the element-wise product of Eq. (1) summed over
+//                            Cin), int8 MFMA 16x16x64 with int32 accumulation
+//   output_sums_kernel       y = A^T M A with the correction terms, dequantization, NCHW store
+//
+// Layouts (element strides): V[p][t][c] = (p*Tp + t)*Cp + c, U[p][k][c] = (p*Kp + k)*Cp + c.
+// M is kept in blocks of 16 tiles x 4 filters, M[p][t/16][k/4][t%16][k%4]: the 64 sums
+// (256 contiguous bytes) that one wave of the output transform needs per point, and that
+// a quarter wave of the GEMM holds in one accumulator register quad.
+#include "sfc_device.hpp"
+#include "sfc_internal.hpp"
+#include "sfc_points.hpp"
+#include "sfc_store.hpp"
+
+namespace sfc {
+
+// ---------------------------------------------------------------------------------------
+// Batched GEMM.  A workgroup of four waves computes a 128-filter x 128-tile block of one
+// point; each wave a 64 x 64 quarter as 4 x 4 MFMA blocks (A operand = filters, B operand =
+// tiles, so that a lane ends up with four consecutive filters of one tile: 16 contiguous
+// bytes of M).  Per 64-channel chunk the workgroup stages 128 x 64 bytes of U and of V in
+// LDS through registers, the next chunk's loads in flight while the current one is
+// multiplied.  LDS rows are 80 bytes apart: the 16 rows a quarter wave reads as one MFMA
+// operand (16 bytes each) then fall into different banks.
+// ---------------------------------------------------------------------------------------
+constexpr int kGemmBlock = 128;  // filters and tiles per workgroup
+constexpr int kGemmPitch = 80;   // LDS bytes per operand row (64 + padding)
+
+__global__ __launch_bounds__(256) void product_gemm_i8_kernel(const int8_t* __restrict__ V,
+                                                              const int8_t* __restrict__ U,
+                                                              int32_t* __restrict__ M, Geometry g,
+                                                              int nbt, int nbf) {
+  constexpr int BL = kGemmBlock, PITCH = kGemmPitch;
+  constexpr int TILE_BYTES = BL * PITCH;  // one staged operand
+  __shared__ __align__(16) unsigned char lds[4 * TILE_BYTES];  // [buffer][U, V]
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave >> 1, wn = wave & 1;  // quarter: filters 64*wm.., tiles 64*wn..
+  // Workgroups that share an XCD (an L2) take consecutive positions, i.e. the blocks of the
+  // same few points: V_p and U_p are then fetched from memory once per XCD.
+  const int pos = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int per_point = nbt * nbf;
+  const int p = pos / per_point, rem = pos - p * per_point;
+  const int bt = rem / nbf, bf = rem - bt * nbf;
+  const int KC = g.Cp >> 6;
+
+  const __amdgpu_buffer_rsrc_t ures = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(U + (size_t)p * g.Kp * g.Cp), 0, g.Kp * g.Cp, kBufferFlags);
+  const __amdgpu_buffer_rsrc_t vres = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(V + (size_t)p * g.Tp * g.Cp), 0, g.Tp * g.Cp, kBufferFlags);
+
+  // loader: piece q = tid + 256*i is 16 bytes of operand row q/4, segment q%4; rows beyond
+  // the tensor get an offset outside the buffer (the load returns zero)
+  constexpr unsigned kOutOfRange = 0x80000000u;
+  unsigned usrc[2], vsrc[2], ldst[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int q = (int)threadIdx.x + 256 * i;
+    const int row = q >> 2, seg = q & 3;
+    const int k = bf * BL + row, t = bt * BL + row;
+    usrc[i] = k < g.Kp ? (unsigned)(k * g.Cp + seg * 16) : kOutOfRange;
+    vsrc[i] = t < g.Tp ? (unsigned)(t * g.Cp + seg * 16) : kOutOfRange;
+    ldst[i] = (unsigned)(row * PITCH + seg * 16);
+  }
+  v4i ureg[2], vreg[2];
+  auto load_regs = [&](int kc) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      ureg[i] = __builtin_amdgcn_raw_buffer_load_b128(ures, usrc[i], (unsigned)kc * 64u, 0);
+      vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(vres, vsrc[i], (unsigned)kc * 64u, 0);
+    }
+  };
+  auto store_lds = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      *(v4i*)(lds + (2 * buf) * TILE_BYTES + ldst[i]) = ureg[i];
+      *(v4i*)(lds + (2 * buf + 1) * TILE_BYTES + ldst[i]) = vreg[i];
+    }
+  };
+
+  v4i acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = v4i{0, 0, 0, 0};
+
+  const unsigned a_lane = (unsigned)((wm * 64 + (lane & 15)) * PITCH + (lane >> 4) * 16);
+  const unsigned b_lane = (unsigned)((wn * 64 + (lane & 15)) * PITCH + (lane >> 4) * 16);
+
+  load_regs(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kc = 0; kc < KC; ++kc) {
+    const int buf = kc & 1;
+    if (kc + 1 < KC) load_regs(kc + 1);
+    v4i a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      a[i] = *(const v4i*)(lds + (2 * buf) * TILE_BYTES + a_lane + i * 16 * PITCH);
+      b[i] = *(const v4i*)(lds + (2 * buf + 1) * TILE_BYTES + b_lane + i * 16 * PITCH);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+    if (kc + 1 < KC) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+
+  // lane: filter quad (k0 + 16*i)/4 + lane/16, tile block (t0 + 16*j)/16, tile lane%16 of it:
+  // the four sums of an accumulator are 16 contiguous bytes of M, a wave writes 1 KiB
+  const __amdgpu_buffer_rsrc_t mres = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(M + (size_t)p * g.Tp * g.Kp), 0, g.Tp * g.Kp * 4, kBufferFlags);
+  const int k0 = bf * BL + wm * 64, t0 = bt * BL + wn * 64;
+  const int kquads = g.Kp >> 2;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int tb = (t0 >> 4) + j;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int kq = ((k0 + 16 * i) >> 2) + (lane >> 4);
+      if (tb * 16 < g.Tp && kq < kquads)
+        __builtin_amdgcn_raw_buffer_store_b128(
+            acc[i][j], mres, (unsigned)(((tb * kquads + kq) * 64 + (lane & 15) * 4) * 4), 0, 0);
+    }
+  }
+}
+
+hipError_t launch_product_gemm_i8(const Geometry& g, const void* V, const void* U, int32_t* M,
+                                  hipStream_t s) {
+  const int nbt = (g.Tp + kGemmBlock - 1) / kGemmBlock, nbf = (g.Kp + kGemmBlock - 1) / kGemmBlock;
+  const long long total = (long long)g.P * nbt * nbf;
+  // 32-bit byte offsets inside one point's V, U and M
+  if (total > 0x7fffffffll || (long long)g.Tp * g.Cp >= (1ll << 31) ||
+      (long long)g.Kp * g.Cp >= (1ll << 31) || (long long)g.Tp * g.Kp * 4 >= (1ll << 31))
+    return hipErrorNotSupported;
+  hipLaunchKernelGGL(product_gemm_i8_kernel, dim3((unsigned)total), dim3(256), 0, s,
+                     (const int8_t*)V, (const int8_t*)U, M, g, nbt, nbf);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Output transform from M.  Wave w of a workgroup owns filters 4w..4w+3 of a 4*NW-filter
+// group and 16 consecutive tiles, lane l the pair (tile l%16, filter 4w + l/16) -- the
+// arrangement of the fused kernels, so the streaming output transform and the LDS-staged
+// NCHW store are theirs.  The int32 sums of the pair are read point by point in
+// processing order, kSumRing loads ahead; no barrier, no LDS besides the store staging.
+// ---------------------------------------------------------------------------------------
+constexpr int kSumRing = 12;
+
+template <int ALG, int OUT, bool VEC2, int NW>
+__global__ __launch_bounds__(NW * 64) void output_sums_kernel(const int32_t* __restrict__ M,
+                                                              const float* __restrict__ dequant,
+                                                              float x_scale, float inv_y,
+                                                              void* __restrict__ y, Geometry g) {
+  using Tr = AlgTraits<ALG>;
+  constexpr int P = Tr::P, Mo = Tr::M, NC = Tr::NC, D = kSumRing;
+  constexpr Order<ALG> order{};
+  __shared__ __align__(16) unsigned char lds[NW * 64 * Mo * 4 + 256];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  float* stage = (float*)lds + wave * (64 * Mo);
+  int* tile_tab = (int*)(lds + NW * 64 * Mo * 4);
+  const int t0 = blockIdx.x * 16;
+  const int kq = blockIdx.y * NW + wave;
+  const int kcol = kq * 4 + (lane >> 4);
+  if (threadIdx.x < 16) {
+    const int tl = threadIdx.x, t = t0 + tl;
+    const int per = g.th * g.tw;
+    const int n = t / per, rem = t - n * per;
+    const int ti = rem / g.tw, tj = rem - ti * g.tw;
+    write_tile_entry<Mo>(tile_tab, tl, t < g.T, n, ti, tj, g.Cout, g.H, g.W);
+  }
+  __syncthreads();
+
+  const unsigned mplane = (unsigned)g.Tp * (unsigned)g.Kp * 4u;  // bytes of one point of M
+  const __amdgpu_buffer_rsrc_t mres =
+      __builtin_amdgcn_make_buffer_rsrc((void*)M, 0, (int)(mplane * (unsigned)P), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t dres = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)dequant, 0, P * g.Kp * 4, kBufferFlags);
+  constexpr unsigned esz = OUT == 2 ? 1u : 4u;
+  const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
+      y, 0, (int)(esz * (unsigned)(g.N * g.Cout) * (unsigned)(g.H * g.W)), kBufferFlags);
+  // filters beyond the padded count read nothing (zeros) and store nothing
+  const bool kvalid = kcol < g.Kp;
+  const unsigned m_lane =
+      kvalid ? (unsigned)(((blockIdx.x * (g.Kp >> 2) + kq) * 64 + (lane & 15) * 4 + (lane >> 4)) * 4)
+             : 0x80000000u;
+  const unsigned d_lane = kvalid ? (unsigned)kcol * 4u : 0x80000000u;
+  const unsigned dplane = (unsigned)g.Kp * 4u;
+
+  int mring[D];
+  float dring[D];
+  auto load_point = [&](int j) {
+    const unsigned p = (unsigned)order.pt[j];
+    mring[j % D] = (int)__builtin_amdgcn_raw_buffer_load_b32(mres, m_lane, p * mplane, 0);
+    dring[j % D] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(dres, d_lane, p * dplane, 0));
+  };
+#pragma unroll
+  for (int j = 0; j < D && j < P; ++j) load_point(j);
+  int j = 0;  // folds to a constant after unrolling
+  auto next = [&]() -> float {
+    float v = (float)mring[j % D] * dring[j % D];
+    asm volatile("" : "+v"(v));  // the slot is free from here on
+    if (j + D < P) load_point(j + D);
+    ++j;
+    return v;
+  };
+  float z[NC][Mo];
+  stream_vertical<ALG, float>(next, z);
+  store_pairs<ALG, OUT, VEC2>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, g.H, g.W);
+}
+
+template <int ALG, int OUT, bool VEC2>
+static hipError_t launch_sums_impl(const Geometry& g, const int32_t* M, const FilterViews& f,
+                                   float x_scale, float inv_y, void* y, hipStream_t s) {
+  // the 7x7 forms carry 10x7 partial outputs per pair: 8 waves with 256 registers each
+  constexpr int NW = AlgTraits<ALG>::M == 6 ? 16 : 8;
+  const dim3 grid((unsigned)(g.Tp / 16), (unsigned)((g.Cout + 4 * NW - 1) / (4 * NW)));
+  hipLaunchKernelGGL((output_sums_kernel<ALG, OUT, VEC2, NW>), grid, dim3(NW * 64), 0, s, M,
+                     f.dequant, x_scale, inv_y, y, g);
+  return hipGetLastError();
+}
+
+template <int ALG>
+static hipError_t launch_sums_alg(int out, const Geometry& g, const int32_t* M,
+                                  const FilterViews& f, float x_scale, float inv_y, void* y,
+                                  hipStream_t s) {
+  constexpr bool kPairs = AlgTraits<ALG>::M % 2 == 0;
+  if constexpr (kPairs) {
+    if (g.W % 2 == 0)
+      return out == 2 ? launch_sums_impl<ALG, 2, true>(g, M, f, x_scale, inv_y, y, s)
+                      : launch_sums_impl<ALG, 0, true>(g, M, f, x_scale, inv_y, y, s);
+  }
+  return out == 2 ? launch_sums_impl<ALG, 2, false>(g, M, f, x_scale, inv_y, y, s)
+                  : launch_sums_impl<ALG, 0, false>(g, M, f, x_scale, inv_y, y, s);
+}
+
+// out: 0 float32, 2 int8 with ReLU.  hipErrorNotSupported beyond the 32-bit offset limits.
+hipError_t launch_output_sums(int out, const Geometry& g, const int32_t* M, const FilterViews& f,
+                              float x_scale, float inv_y, void* y, hipStream_t s) {
+  const long long mbytes = 4ll * g.P * g.Tp * g.Kp, ybytes = 4ll * g.N * g.Cout * g.H * g.W;
+  if (mbytes >= (1ll << 31) || ybytes >= (1ll << 31) || out == 1) return hipErrorNotSupported;
+  switch (g.alg) {
+    case 0: return launch_sums_alg<0>(out, g, M, f, x_scale, inv_y, y, s);
+    case 1: return launch_sums_alg<1>(out, g, M, f, x_scale, inv_y, y, s);
+    case 2: return launch_sums_alg<2>(out, g, M, f, x_scale, inv_y, y, s);
+    case 3: return launch_sums_alg<3>(out, g, M, f, x_scale, inv_y, y, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace sfc

@@ -42,6 +42,12 @@ hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V
                                      const float* inv_sx, hipStream_t s);
 hipError_t launch_product(int mode, const Geometry& g, const void* V, const void* U, int32_t* M,
                           hipStream_t s);
+// requantized mode (sfc_gemm.hip): the products as P batched int8 GEMMs; the output
+// transform reading their sums (out: 0 float32, 2 int8 with ReLU)
+hipError_t launch_product_gemm_i8(const Geometry& g, const void* V, const void* U, int32_t* M,
+                                  hipStream_t s);
+hipError_t launch_output_sums(int out, const Geometry& g, const int32_t* M, const FilterViews& f,
+                              float x_scale, float inv_y, void* y, hipStream_t s);
 // out: 0 float32, 1 int32 sums (exact mode), 2 int8 with ReLU (inv_y = 1 / output scale)
 hipError_t launch_output_transform(int mode, int out, const Geometry& g, const int32_t* M,
                                    const FilterViews& f, float x_scale, float inv_y, void* y,

@@ -2,9 +2,9 @@
 //
 //   filter_transform_kernel   U = G f G^T               (once per layer)
 //   input_transform_kernel    V = B^T x B               (NCHW int8 -> [P][Tp][Cp])
-//   product_i8_kernel         M_p = V_p . U_p^T         (int8 MFMA, int32 sums)
-//   product_i16_kernel        the same for exact mode   (int16 operands, vector ALU)
-//   output_transform_kernel   y = A^T M A, corrections, dequantization, NCHW store
+//   product_i16_kernel        M_p = V_p . U_p^T, exact mode (int16 operands, vector ALU)
+//   output_transform_kernel   y = A^T M A, corrections, NCHW store, exact mode
+// (the requantized-mode products and output transform are in sfc_gemm.hip)
 //
 // Layouts (element strides): V[p][t][c] = (p*Tp + t)*Cp + c, U[p][k][c] =
 // (p*Kp + k)*Cp + c, M[p][t][k] = (p*Tp + t)*Kp + k.  Channels c >= Cin and
@@ -249,37 +249,6 @@ __global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
   if (i < n) p[i] = v;
 }
 
-// ---------------------------------------------------------------------------
-// transform-domain product, requantized mode: int8 MFMA 16x16x64.
-// One wave computes a 16-tile x 16-filter block of one point.  A-operand lane l
-// holds tile row l%16, channels 16*(l/16)..+15 of the 64-channel slice; the
-// B-operand holds filter row l%16 with the same channel slots; the result lane l
-// holds filter column l%16 of tile rows 4*(l/16)..+3.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void product_i8_kernel(const int8_t* __restrict__ V,
-                                                         const int8_t* __restrict__ U,
-                                                         int32_t* __restrict__ M, Geometry g) {
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  const int kblocks = g.Kp >> 4;
-  const int tblocks = g.Tp >> 4;
-  const int blk = blockIdx.x * 4 + wave;
-  if (blk >= kblocks * tblocks) return;
-  const int kb = blk % kblocks, tb = blk / kblocks;
-  const int p = blockIdx.y;
-  const int8_t* a_ptr = V + ((size_t)p * g.Tp + tb * 16 + (lane & 15)) * g.Cp + (lane >> 4) * 16;
-  const int8_t* b_ptr = U + ((size_t)p * g.Kp + kb * 16 + (lane & 15)) * g.Cp + (lane >> 4) * 16;
-  v4i acc = {0, 0, 0, 0};
-  for (int kc = 0; kc < g.Cp; kc += 64) {
-    const v4i a = *(const v4i*)(a_ptr + kc);
-    const v4i b = *(const v4i*)(b_ptr + kc);
-    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc, 0, 0, 0);
-  }
-  int32_t* out = M + ((size_t)p * g.Tp + tb * 16 + (lane >> 4) * 4) * g.Kp + kb * 16 + (lane & 15);
-#pragma unroll
-  for (int j = 0; j < 4; ++j) out[(size_t)j * g.Kp] = acc[j];
-}
-
 // exact mode: int16 operands, int32 sums on the vector ALU, 16x16 block per workgroup
 __global__ __launch_bounds__(256) void product_i16_kernel(const int16_t* __restrict__ V,
                                                           const int16_t* __restrict__ U,
@@ -306,15 +275,14 @@ __global__ __launch_bounds__(256) void product_i16_kernel(const int16_t* __restr
 }
 
 // ---------------------------------------------------------------------------
-// output transform, staged: one thread per (tile, filter), lanes along filters
+// output transform, exact mode: one thread per (tile, filter), lanes along filters;
+// the integer sums are divided by 36 exactly
 // ---------------------------------------------------------------------------
-template <int ALG, int MODE, int OUT>
+template <int ALG, int OUT>
 __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __restrict__ M,
-                                                               const float* __restrict__ dequant,
                                                                const float* __restrict__ wscale,
-                                                               float x_scale, float inv_y,
-                                                               void* __restrict__ y, Geometry g,
-                                                               int kx) {
+                                                               float x_scale, void* __restrict__ y,
+                                                               Geometry g, int kx) {
   const int k = blockIdx.y * kx + (threadIdx.x % kx);
   const int t = blockIdx.x * (256 / kx) + (threadIdx.x / kx);
   if (k >= g.Cout || t >= g.T) return;
@@ -327,32 +295,7 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __
   const size_t ybase = ((size_t)n * g.Cout + k) * g.H * g.W;
 
   constexpr int MT = AlgTraits<ALG>::M;
-  if constexpr (MODE == 1) {
-    float out[MT][MT];
-    output_transform<ALG, float>(
-        [&](int p) { return (float)m[p * pstride] * dequant[p * g.Kp + k]; }, out);
-#pragma unroll
-    for (int o1 = 0; o1 < MT; ++o1) {
-      const int h = MT * ti + o1;
-      if (h >= g.H) continue;
-#pragma unroll
-      for (int o2 = 0; o2 < MT; ++o2) {
-        const int w = MT * tj + o2;
-        if (w >= g.W) continue;
-        const float v = out[o1][o2] * x_scale;
-        if constexpr (OUT == 2) {
-          // next layer's activation: ReLU, one fused multiply-add that rounds to an
-          // integer (ties to even), clamp to [0, 127]
-          constexpr float kMagic = 12582912.0f;
-          float t = __fmaf_rn(v, inv_y, kMagic);
-          t = fminf(fmaxf(t, kMagic), kMagic + 127.0f);
-          ((int8_t*)y)[ybase + (size_t)h * g.W + w] = (int8_t)(__float_as_int(t) - 0x4B400000);
-        } else {
-          ((float*)y)[ybase + (size_t)h * g.W + w] = v;
-        }
-      }
-    }
-  } else {
+  {
     int out[MT][MT];
     output_transform<ALG, int>([&](int p) { return m[p * pstride]; }, out);
     const float scale = x_scale * wscale[k];
@@ -472,13 +415,9 @@ hipError_t launch_filter_transform(int mode, const Geometry& g, const int8_t* w,
 hipError_t launch_product(int mode, const Geometry& g, const void* V, const void* U, int32_t* M,
                           hipStream_t s) {
   const int blocks = (g.Tp / 16) * (g.Kp / 16);
-  if (mode == 1) {
-    hipLaunchKernelGGL(product_i8_kernel, dim3((blocks + 3) / 4, g.P), dim3(256), 0, s,
-                       (const int8_t*)V, (const int8_t*)U, M, g);
-  } else {
-    hipLaunchKernelGGL(product_i16_kernel, dim3(blocks, g.P), dim3(256), 0, s, (const int16_t*)V,
-                       (const int16_t*)U, M, g);
-  }
+  if (mode == 1) return launch_product_gemm_i8(g, V, U, M, s);
+  hipLaunchKernelGGL(product_i16_kernel, dim3(blocks, g.P), dim3(256), 0, s, (const int16_t*)V,
+                     (const int16_t*)U, M, g);
   return hipGetLastError();
 }
 
@@ -486,18 +425,17 @@ template <int ALG>
 static hipError_t launch_output_alg(int mode, int out, const Geometry& g, const int32_t* M,
                                     const FilterViews& f, float x_scale, float inv_y, void* y,
                                     hipStream_t s) {
+  if (mode == 1) return launch_output_sums(out, g, M, f, x_scale, inv_y, y, s);
   int kx = 64;
   while (kx > g.Kp) kx >>= 1;  // Kp is a multiple of 16
   dim3 grid((g.T + (256 / kx) - 1) / (256 / kx), (g.Cout + kx - 1) / kx);
   dim3 block(256);
-#define SFC_LAUNCH_OUT(MD, O)                                                                   \
-  hipLaunchKernelGGL((output_transform_kernel<ALG, MD, O>), grid, block, 0, s, M, f.dequant,     \
-                     f.wscale, x_scale, inv_y, y, g, kx)
-  if (mode == 1 && out == 2) SFC_LAUNCH_OUT(1, 2);
-  else if (mode == 1) SFC_LAUNCH_OUT(1, 0);
-  else if (out == 1) SFC_LAUNCH_OUT(0, 1);
-  else SFC_LAUNCH_OUT(0, 0);
-#undef SFC_LAUNCH_OUT
+  if (out == 1)
+    hipLaunchKernelGGL((output_transform_kernel<ALG, 1>), grid, block, 0, s, M, f.wscale, x_scale,
+                       y, g, kx);
+  else
+    hipLaunchKernelGGL((output_transform_kernel<ALG, 0>), grid, block, 0, s, M, f.wscale, x_scale,
+                       y, g, kx);
   return hipGetLastError();
 }
 

@@ -30,11 +30,12 @@ __device__ __forceinline__ void store_pairs(
     int W) {
   constexpr int M = AlgTraits<ALG>::M;
   constexpr unsigned esz = OUT == 2 ? 1u : 4u;
-  // Cache policy of the y stores.  7x7 tiles divide the ResNet image widths, a
-  // workgroup then writes whole image rows and the lines can stream past the L2 ("nt");
-  // 6x6 tiles leave row pieces that share cache lines with a neighbouring workgroup,
-  // which the L2 has to merge before they go to memory.
-  constexpr int kStore = M == 7 ? kStreamStore : 0;
+  // Cache policy of the y stores.  7x7 tiles divide the ResNet image widths; on wide
+  // images a workgroup then writes long whole rows and the lines can stream past the L2
+  // ("nt").  Everywhere else (6x6 tiles, or short rows of small feature maps, where a line
+  // is completed by several stores or several workgroups) the L2 has to merge the pieces
+  // before they go to memory: streaming those costs up to 2.5x the bytes in HBM writes.
+  const bool stream = M == 7 && W >= 48;
   constexpr int EV = VEC2 ? 2 : 1;        // elements per lane and store
   constexpr int NST = (M + EV - 1) / EV;  // stores per lane and output row (64*M elements)
   // store plan: the k-th store of this lane covers elements e = EV*(lane + 64*k) of the
@@ -84,16 +85,22 @@ __device__ __forceinline__ void store_pairs(
           t0 = __builtin_amdgcn_fmed3f(t0, kMagic, kMagic + 127.0f);
           t1 = __builtin_amdgcn_fmed3f(t1, kMagic, kMagic + 127.0f);
           const unsigned q0 = __float_as_uint(t0) & 0xffu, q1 = __float_as_uint(t1) & 0xffu;
-          if constexpr (VEC2)
-            __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(q0 | (q1 << 8)), yres, yoff[k],
-                                                  yrow, kStore);
-          else
-            __builtin_amdgcn_raw_buffer_store_b8((unsigned char)q0, yres, yoff[k], yrow, kStore);
+          if constexpr (VEC2) {
+            const unsigned short q = (unsigned short)(q0 | (q1 << 8));
+            if (stream) __builtin_amdgcn_raw_buffer_store_b16(q, yres, yoff[k], yrow, kStreamStore);
+            else __builtin_amdgcn_raw_buffer_store_b16(q, yres, yoff[k], yrow, 0);
+          } else {
+            if (stream) __builtin_amdgcn_raw_buffer_store_b8((unsigned char)q0, yres, yoff[k], yrow, kStreamStore);
+            else __builtin_amdgcn_raw_buffer_store_b8((unsigned char)q0, yres, yoff[k], yrow, 0);
+          }
         } else {
-          if constexpr (VEC2)
-            __builtin_amdgcn_raw_buffer_store_b64(v2f{v0, v1}, yres, yoff[k], yrow, kStore);
-          else
-            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v0), yres, yoff[k], yrow, kStore);
+          if constexpr (VEC2) {
+            if (stream) __builtin_amdgcn_raw_buffer_store_b64(v2f{v0, v1}, yres, yoff[k], yrow, kStreamStore);
+            else __builtin_amdgcn_raw_buffer_store_b64(v2f{v0, v1}, yres, yoff[k], yrow, 0);
+          } else {
+            if (stream) __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v0), yres, yoff[k], yrow, kStreamStore);
+            else __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v0), yres, yoff[k], yrow, 0);
+          }
         }
       }
     }
