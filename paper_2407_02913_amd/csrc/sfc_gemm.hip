@@ -148,7 +148,8 @@ hipError_t launch_product_gemm_i8(const Geometry& g, const void* V, const void* 
 // group and 16 consecutive tiles, lane l the pair (tile l%16, filter 4w + l/16) -- the
 // arrangement of the fused kernels, so the streaming output transform and the LDS-staged
 // NCHW store are theirs.  The int32 sums of the pair are read point by point in
-// processing order, kSumRing loads ahead; no barrier, no LDS besides the store staging.
+// processing order, a ring of loads ahead; no barrier, no LDS besides the store staging.
+// The kernel moves M and y once each and runs at the rate the memory system delivers them.
 // ---------------------------------------------------------------------------------------
 constexpr int kSumRing = 12;
 
