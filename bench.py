@@ -53,6 +53,25 @@ def stage_bytes(shape, P, tiles, path):
     return {"input_transform": x + v, "product": v + u + m, "output_transform": m + y}
 
 
+def pick_variant(shape, alg=None, path=None):
+    """Tile size and path per layer shape, from the per-layer timings on one MI355X: the
+    single-kernel path with 6x6 tiles where it exists (Cin <= 64); else 6x6 tiles while the
+    feature map is large (28x28: no ragged tiles to speak of, the cheaper transforms win);
+    7x7 tiles on 14x14 and 7x7 maps (no ragged tiles at all), with the products as batched
+    GEMMs through HBM once there are too few tiles for the fused kernel's operand stream
+    (7x7 maps, 512 channels)."""
+    if alg is None:
+        alg = "6x6_p88" if shape.H >= 28 else "7x7_p132"
+    if path is None:
+        if shape.Cin <= 64:
+            path = "single"
+        elif shape.H >= 14:
+            path = "fused"
+        else:
+            path = "staged"
+    return alg, path
+
+
 def run_stack(args):
     """The 13 stride-1 3x3 layers of the ResNet-18-shaped stack at batch 64, filter transforms
     done beforehand, int8 activations handed from layer to layer inside each resolution stage
@@ -66,15 +85,16 @@ def run_stack(args):
     binding.load()
     torch.cuda.set_device(0)
     layers = synth.stack_layers()
-    plans, bufs = [], []
+    plans, bufs, chosen = [], [], []
     for shape in layers:
         d = synth.make_layer(shape, batch=4)  # weights and calibration data; activations below
-        path = args.path or ("single" if shape.Cin <= 64 else "fused")
-        plan = binding.Plan(shape.N, shape.Cin, shape.Cout, shape.H, shape.W, alg=args.alg,
+        alg, path = pick_variant(shape, args.alg, args.path)
+        chosen.append(f"{alg}/{path}")
+        plan = binding.Plan(shape.N, shape.Cin, shape.Cout, shape.H, shape.W, alg=alg,
                             mode="requant", out="i8", path=path, per_channel_wscale=True)
         w_dev = torch.from_numpy(d["w"]).cuda()
         xc_dev = torch.from_numpy(d["x_calib"]).cuda()
-        calib = binding.Plan(4, shape.Cin, shape.Cout, shape.H, shape.W, alg=args.alg, mode="requant",
+        calib = binding.Plan(4, shape.Cin, shape.Cout, shape.H, shape.W, alg=alg, mode="requant",
                              path="staged", per_channel_wscale=True)
         scratch = binding.device_buffer(calib.workspace_bytes)
         sx = calib.calibrate_act_scales(xc_dev, scratch)
@@ -126,7 +146,7 @@ def run_stack(args):
         "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "resnet18 stack: 13 stride-1 3x3 layers, batch 64, int8 activations between layers",
-                   "algorithm": args.alg, "direct_gop": round(ops / 1e9, 1), "layer_us": per_layer}}))
+                   "variants": chosen, "direct_gop": round(ops / 1e9, 1), "layer_us": per_layer}}))
 
 
 def main():
@@ -136,7 +156,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet56")
     ap.add_argument("--path", default=None, choices=[None, "staged", "fused", "single"])
-    ap.add_argument("--alg", default="6x6_p88")
+    ap.add_argument("--alg", default=None,
+                    help="6x6_p88 | 6x6_p100 | 7x7_p132 | 7x7_p144 (default: 6x6_p88; per layer for the stack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=3,
                     help="HIP streams the steps are dealt to round-robin (independent batches overlap)")
@@ -150,6 +171,8 @@ def main():
 
     if args.workload == "stack":
         return run_stack(args)
+    if args.alg is None:
+        args.alg = "6x6_p88"
 
     import numpy as np
     import torch
