@@ -240,6 +240,40 @@ def main():
     torch.cuda.synchronize()
     single_stream_ms = e0.elapsed_time(e1) / args.steps
 
+    # The same steps replayed from one HIP graph (launch overhead taken out), and the warm
+    # figure: one buffer set, inputs and outputs staying in the memory-side cache.
+    graph_ms = warm_ms = None
+    try:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        nrep = min(nsets, 16)
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(nrep):
+                    step(i, stream=side)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        reps = max(2, args.steps // nrep)
+        e0.record()
+        for _ in range(reps):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        graph_ms = e0.elapsed_time(e1) / (reps * nrep)
+    except Exception as exc:  # the capture is a measurement aid, never the product path
+        print(f"graph replay skipped: {exc}", file=sys.stderr)
+    torch.cuda.synchronize()
+    for _ in range(10):
+        step(0)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        step(0)
+    e1.record()
+    torch.cuda.synchronize()
+    warm_ms = e0.elapsed_time(e1) / args.steps
+
     # per-kernel durations: each stage alone, back to back, over the rotating sets
     # (every set already holds valid V / M from the full passes above)
     if path == "single":
@@ -318,7 +352,9 @@ def main():
         "config": {"workload": f"{args.workload}: N={shape.N} Cin=Cout={shape.Cin} H=W={shape.H} 3x3 s1 p1",
                    "algorithm": f"SFC-6({args.alg[:3]},3x3) P={plan.P}", "mode": "requant-int8 transform domain",
                    "path": path, "buffer_sets": nsets, "streams": nstreams,
-                   "single_stream_ms_per_step": round(single_stream_ms, 5)},
+                   "single_stream_ms_per_step": round(single_stream_ms, 5),
+                   "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
+                   "warm_single_stream_ms_per_step": round(warm_ms, 5)},
         "roofline": roofline,
     }
 
