@@ -245,6 +245,41 @@ A7_1D = np.array(
     dtype=np.int64,
 )
 
+# SFC-4(4x4,3x3), Appendix A (first set of matrices): s = j, four-point symbolic DFT of the
+# inner samples x1..x4 plus one correction row per wrapped output.  Row order as printed:
+# X0, X2 (both real), then the complex point X1 = a0 + a1 j as (a0 + a1, a1, a0), then the
+# corrections (x0 - x4) f0 -> output 0 and (x5 - x1) f2 -> output 3.
+BT4_1D = np.array(
+    [
+        [0, 1, 1, 1, 1, 0],
+        [0, -1, 1, -1, 1, 0],
+        [0, 1, -1, -1, 1, 0],
+        [0, 0, -1, 0, 1, 0],
+        [0, 1, 0, -1, 0, 0],
+        [1, 0, 0, 0, -1, 0],
+        [0, -1, 0, 0, 0, 1],
+    ],
+    dtype=np.int64,
+)
+G4_1D = np.array(
+    [[1, 1, 1], [1, -1, 1], [1, -1, -1], [1, 0, -1], [0, -1, 0], [1, 0, 0], [0, 0, 1]],
+    dtype=np.int64,
+)
+A4_1D = np.array(  # numerators, A = A4_1D / 4
+    [
+        [1, 1, 1, 1],
+        [1, -1, 1, -1],
+        [0, 2, 0, -2],
+        [2, -2, -2, 2],
+        [-2, -2, 2, 2],
+        [4, 0, 0, 0],
+        [0, 0, 0, 4],
+    ],
+    dtype=np.int64,
+)
+A4_1D_DEN = 4
+SFC4_COMPLEX_GROUP = (4, 3, 2)  # (a0 row, a1 row, a0+a1 row) of the single complex point
+
 TILE_OUT = 6  # M of the primary variant SFC-6(6x6,3x3)
 TILE_IN = 8  # M + R - 1
 KERNEL = 3  # R
@@ -435,16 +470,92 @@ def hermitian_2d(m: int = 6):
     )
 
 
+def sfc4_1d():
+    """The three 1-D matrices of SFC-4(4,3) as printed in Appendix A: (B^T 7x6, G 7x3, A numerators 7x4, 4)."""
+    return BT4_1D.copy(), G4_1D.copy(), A4_1D.copy(), A4_1D_DEN
+
+
+def nested4_2d(m: int = 4):
+    """Nested 2-D form of SFC-4(4x4,3x3): 49 points, p = 7*p1 + p2 (Appendix A)."""
+    bt, g, a, den = sfc4_1d()
+    return np.kron(bt, bt), np.kron(g, g), np.kron(a, a), den * den
+
+
+def hermitian4_2d(m: int = 4):
+    """46-point 2-D form of SFC-4(4x4,3x3) ("when Hermitian symmetry is fully considered").
+
+    The paper states the count only.  Same construction as for SFC-6, with s = j: every
+    nested point in which at most one axis is the complex point is kept (40 of 49, nested
+    order).  The complex x complex block is the product of two elements of
+    Z[s]/(s^2+1) (x) Z[t]/(t^2+1), a = a00 + a10 s + a01 t + a11 s t; since
+    t^2 + 1 = (t - s)(t + s) that ring maps into Z[s] x Z[s] by t -> s and t -> -s, the 2-D
+    DFT values Z[1,1] and Z[1,-1]:
+        U = (a00 - a11) + (a10 + a01) s        (t -> s)
+        V = (a00 + a11) + (a10 - a01) s        (t -> -s)
+    each multiplied with the 3-multiplication rule of Eq. (DFT4M) (o0 = m0 - m1,
+    o1 = m2 - m0 - m1): points U0, U1, U0+U1, V0, V1, V0+V1, 6 multiplications instead of 9.
+    Inverse of the ring map: o00 = (Uo0 + Vo0)/2, o11 = (Vo0 - Uo0)/2, o10 = (Uo1 + Vo1)/2,
+    o01 = (Uo1 - Vo1)/2; the tile output is sum_ij (c_i (x) c_j) o_ij with c_1 = A[sum row]
+    and c_0 = A[a0 row] + c_1 (the inverse-DFT rows recovered from the folded A); the halves
+    cancel exactly.  Count: 40 + 6 = 46.
+    Returns (B2 [46,36], G2 [46,9], A2 numerators [46,16], 16).
+    """
+    bt, g, a, den = sfc4_1d()
+    r0, r1, rs = SFC4_COMPLEX_GROUP
+    complex_rows = {r0, r1, rs}
+    nrows = bt.shape[0]
+    b_rows, g_rows, a_rows = [], [], []
+    for p1 in range(nrows):
+        for p2 in range(nrows):
+            if p1 in complex_rows and p2 in complex_rows:
+                continue
+            b_rows.append(np.kron(bt[p1], bt[p2]))
+            g_rows.append(np.kron(g[p1], g[p2]))
+            a_rows.append(np.kron(a[p1], a[p2]))
+
+    def six_points(mat):
+        c = [[np.kron(mat[(r0, r1)[i]], mat[(r0, r1)[j]]) for j in range(2)] for i in range(2)]
+        u0 = c[0][0] - c[1][1]
+        u1 = c[1][0] + c[0][1]
+        v0 = c[0][0] + c[1][1]
+        v1 = c[1][0] - c[0][1]
+        return [u0, u1, u0 + u1, v0, v1, v0 + v1]
+
+    # 2 * o_ij as integer combinations of the six products (mU0,mU1,mU2,mV0,mV1,mV2)
+    uo0 = np.array([1, -1, 0, 0, 0, 0])
+    uo1 = np.array([-1, -1, 1, 0, 0, 0])
+    vo0 = np.array([0, 0, 0, 1, -1, 0])
+    vo1 = np.array([0, 0, 0, -1, -1, 1])
+    o_x2 = {(0, 0): uo0 + vo0, (1, 1): vo0 - uo0, (1, 0): uo1 + vo1, (0, 1): uo1 - vo1}
+    b_rows += six_points(bt)
+    g_rows += six_points(g)
+    c = (a[r0] + a[rs], a[rs])  # inverse-DFT coefficient rows of the real and imaginary part
+    block = np.zeros((6, m * m), dtype=np.int64)
+    for (i, j), comb in o_x2.items():
+        block += np.outer(comb, np.kron(c[i], c[j]))
+    assert np.all(block % 2 == 0), "halves must cancel"
+    a_rows += list(block // 2)
+    return (
+        np.array(b_rows, dtype=np.int64),
+        np.array(g_rows, dtype=np.int64),
+        np.array(a_rows, dtype=np.int64),
+        den * den,
+    )
+
+
 _ALGORITHMS = {
     "6x6_p88": (hermitian_2d, 6),
     "6x6_p100": (nested_2d, 6),
     "7x7_p132": (hermitian_2d, 7),
     "7x7_p144": (nested_2d, 7),
+    "4x4_p46": (hermitian4_2d, 4),
+    "4x4_p49": (nested4_2d, 4),
 }
 
 
 def algorithm(name: str):
-    """(B2, G2, A2 numerators, denominator) for "6x6_p88", "6x6_p100", "7x7_p132", "7x7_p144"."""
+    """(B2, G2, A2 numerators, denominator) for "6x6_p88", "6x6_p100", "7x7_p132", "7x7_p144",
+    "4x4_p46", "4x4_p49"."""
     build, m = _ALGORITHMS[name]
     return build(m)
 

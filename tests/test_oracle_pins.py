@@ -462,3 +462,95 @@ def test_7x7_requant_reduces_to_exact_and_tiles_imagenet_shapes_without_waste():
         assert np.allclose(y, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
     for hw in (56, 28, 14, 7):  # Sec. 4.2: feature maps of 224x224 models have the factor 7
         assert hw % 7 == 0 and sfc.tile_grid(hw, hw, 7) == (hw // 7, hw // 7)
+
+
+# ---- SFC-4(4x4,3x3), Appendix A ----------------------------------------------
+
+GOLDEN4 = os.path.join(os.path.dirname(__file__), "golden", "sfc4_4x4_3x3_printed.txt")
+
+
+def test_4x4_printed_matrices_and_1d_identity():
+    gold = load_golden(GOLDEN4)
+    bt, g, a, den = sfc.sfc4_1d()
+    assert den == 4
+    assert np.array_equal(gold["BT"], bt) and np.array_equal(gold["G"], g)
+    assert np.array_equal(gold["A_times_4"], a)
+    ref = np.zeros((4, 6, 3), dtype=np.int64)
+    for o in range(4):
+        for r in range(3):
+            ref[o, o + r, r] = den
+    assert np.array_equal(bilinear_1d(a, bt, g), ref)
+    # rows 0, 4, 3, 1 of B^T are the rows of F_4 (Eq. DFT4) on the inner samples, the last
+    # one negated; row 2 is the sum row of the 3-multiplication rule (Eq. DFT4M)
+    f4 = gold["F4"]
+    assert np.array_equal(bt[0, 1:5], f4[0]) and np.array_equal(bt[4, 1:5], f4[1])
+    assert np.array_equal(bt[3, 1:5], f4[2]) and np.array_equal(bt[1, 1:5], -f4[3])
+    r0, r1, rs = sfc.SFC4_COMPLEX_GROUP
+    assert np.array_equal(bt[rs], bt[r0] + bt[r1]) and np.array_equal(g[rs], g[r0] + g[r1])
+
+
+def test_4x4_three_multiplication_rule_is_complex_multiplication_at_j():
+    # Eq. (DFT4M): o0 = m0 - m1, o1 = m2 - m0 - m1 with m2 = (a0 + a1)(w0 + w1)
+    rng = np.random.default_rng(21)
+    for _ in range(50):
+        a0, a1, w0, w1 = (int(v) for v in rng.integers(-1000, 1000, size=4))
+        m0, m1, m2 = a0 * w0, a1 * w1, (a0 + a1) * (w0 + w1)
+        prod = complex(a0, a1) * complex(w0, w1)
+        assert (m0 - m1, m2 - m0 - m1) == (int(prod.real), int(prod.imag))
+
+
+def test_4x4_1d_brute_force():
+    bt, g, a, den = sfc.sfc4_1d()
+    rng = np.random.default_rng(22)
+    for _ in range(50):
+        x = rng.integers(-128, 128, size=6)
+        f = rng.integers(-128, 128, size=3)
+        y = a.T @ ((g @ f) * (bt @ x))
+        brute = [sum(int(x[o + r]) * int(f[r]) for r in range(3)) for o in range(4)]
+        assert np.array_equal(y, den * np.array(brute))
+
+
+@pytest.mark.parametrize("alg,points", [("4x4_p49", 49), ("4x4_p46", 46)])
+def test_4x4_2d_bilinear_identity_and_counts(alg, points):
+    c = load_golden(GOLDEN4)["counts"]
+    b2, g2, a2, den = sfc.algorithm(alg)
+    assert sfc.tile_out(alg) == 4 and den == 16
+    assert b2.shape == (points, 36) and g2.shape == (points, 9) and a2.shape == (points, 16)
+    t = np.einsum("po,pi,pr->oir", a2, b2, g2).reshape(4, 4, 6, 6, 3, 3)
+    ref = np.zeros_like(t)
+    for o1, o2, r1, r2 in itertools.product(range(4), range(4), range(3), range(3)):
+        ref[o1, o2, o1 + r1, o2 + r2, r1, r2] = den
+    assert np.array_equal(t, ref)
+    assert set(np.unique(b2)) <= {-1, 0, 1} and set(np.unique(g2)) <= {-1, 0, 1}
+    assert points == c["nested_multiplications" if points == 49 else "hermitian_multiplications"]
+    if points == 46:
+        direct = sfc.direct_multiplications_per_tile(4)
+        assert direct == c["direct_multiplications"]
+        assert round(10000 * points / direct) == c["complexity_percent_x100"]  # 31.94 %
+        # the first 40 points are the nested points that are not complex x complex
+        n2 = sfc.algorithm("4x4_p49")[0]
+        cr = set(sfc.SFC4_COMPLEX_GROUP)
+        keep = [7 * p1 + p2 for p1 in range(7) for p2 in range(7) if not (p1 in cr and p2 in cr)]
+        assert len(keep) == 40 and np.array_equal(b2[:40], n2[keep])
+
+
+@pytest.mark.parametrize("alg", ["4x4_p49", "4x4_p46"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_4x4_exact_sfc_equals_direct_conv(alg, shape):
+    n, c, k, h, w = shape
+    rng = np.random.default_rng(hash(shape) % 2**32 + 2)
+    x = rng.integers(-128, 128, size=(n, c, h, w)).astype(np.int8)
+    wt = rng.integers(-128, 128, size=(k, c, 3, 3)).astype(np.int8)
+    assert np.array_equal(sfc.conv_exact(x, wt, alg), sfc.direct_conv(x, wt))
+
+
+def test_4x4_requant_reduces_to_exact_when_nothing_rounds():
+    rng = np.random.default_rng(23)
+    x = rng.integers(-1, 2, size=(1, 3, 9, 6)).astype(np.int8)
+    w = rng.integers(-2, 3, size=(4, 3, 3, 3)).astype(np.int8)
+    for alg in ("4x4_p49", "4x4_p46"):
+        p = sfc.multiplications_per_tile(alg)
+        y = sfc.conv_requant(x, w, np.ones(p, np.float32), np.ones((p, 4), np.float32), 0.125,
+                             np.float32(0.5), alg)
+        ref = sfc.dequantize(sfc.direct_conv(x, w), 0.125, np.float32(0.5))
+        assert np.allclose(y, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
