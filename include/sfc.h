@@ -9,9 +9,10 @@
  *
  * with the addition-only symbolic DFT-6 transforms of Sec. 4.1, the correction
  * terms of Sec. 4.2 and the integrated matrices of Appendix A, on MxM output
- * tiles ((M+2)x(M+2) input tiles), M = 6 or 7.  Per tile and (Cin,Cout) pair it
- * spends P = 88 / 132 multiplications (Hermitian form, M = 6 / 7) or P = 100 / 144
- * (nested form), Appendix A.
+ * tiles ((M+2)x(M+2) input tiles), M = 6 or 7 -- or 4, with the four-point transforms
+ * of SFC-4(4x4,3x3).  Per tile and (Cin,Cout) pair it spends P = 88 / 132 / 46
+ * multiplications (Hermitian form, M = 6 / 7 / 4) or P = 100 / 144 / 49 (nested form),
+ * Appendix A.
  *
  * Conventions
  *  - "dev" pointers are device (HBM) addresses on the current HIP device, "host"
@@ -52,7 +53,11 @@ typedef enum {
   SFC_ALG_6X6_P88 = 0,  /* SFC-6(6x6,3x3), Hermitian symmetry fully used: 88 multiplications per tile */
   SFC_ALG_6X6_P100 = 1, /* SFC-6(6x6,3x3), nested (Kronecker) form: 100 multiplications */
   SFC_ALG_7X7_P132 = 2, /* SFC-6(7x7,3x3) (Sec. 4.2, Appendix A), Hermitian form: 132 multiplications */
-  SFC_ALG_7X7_P144 = 3  /* SFC-6(7x7,3x3), nested form: 144 multiplications */
+  SFC_ALG_7X7_P144 = 3, /* SFC-6(7x7,3x3), nested form: 144 multiplications */
+  /* SFC-4(4x4,3x3) (Appendix A, four-point symbolic DFT, s = j): 46 multiplications per
+   * 4x4 tile with Hermitian symmetry fully used, 49 in the nested form.  Staged path only. */
+  SFC_ALG_4X4_P46 = 4,
+  SFC_ALG_4X4_P49 = 5
 } sfc_alg;
 
 typedef enum {
@@ -114,11 +119,11 @@ sfc_status sfc_plan_sizes(const sfc_plan_t* plan, size_t* filter_bytes, size_t* 
 /* Requantized mode: the transform-domain scales of Sec. 5, copied into the plan.
  * sx_host[P]: one activation scale per point (s_Tx).  sw_host[P*Cout], laid out
  * [P][Cout]: one filter scale per point and output channel (s_Tf).  All > 0.
- * Point order, with R = 10 (M = 6) or 12 (M = 7) rows in the printed 1-D matrices:
- * nested form, p = R*p1 + p2 (p1 vertical); Hermitian form, first the R*R - 36
- * nested points that are not complex x complex, in that same order, then for
- * (k1,k2) = (1,1),(1,2),(2,1),(2,2) the six points U0,U1,U0+U1,V0,V1,V0+V1 of the
- * two independent 2-D frequencies.
+ * Point order, with R = 10 (M = 6), 12 (M = 7) or 7 (M = 4) rows in the printed 1-D
+ * matrices: nested form, p = R*p1 + p2 (p1 vertical); Hermitian form, first the nested
+ * points that are not complex x complex (R*R - 36 of them, R*R - 9 for M = 4), in that
+ * same order, then for (k1,k2) = (1,1),(1,2),(2,1),(2,2) (only (1,1) for M = 4) the six
+ * points U0,U1,U0+U1,V0,V1,V0+V1 of the two independent 2-D frequencies.
  * Must precede sfc_transform_filter. */
 sfc_status sfc_set_point_scales(sfc_plan_t* plan, const float* sx_host, const float* sw_host);
 

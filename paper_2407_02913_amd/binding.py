@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libsfc_hip.so")
 SFC_OK = 0
 STATUS_NAMES = {0: "SFC_OK", 1: "SFC_EINVAL", 2: "SFC_EUNSUPPORTED", 3: "SFC_ENOMEM",
                 4: "SFC_ENOTREADY", 5: "SFC_EHIP"}
-ALG = {"6x6_p88": 0, "6x6_p100": 1, "7x7_p132": 2, "7x7_p144": 3}
+ALG = {"6x6_p88": 0, "6x6_p100": 1, "7x7_p132": 2, "7x7_p144": 3, "4x4_p46": 4, "4x4_p49": 5}
 MODE = {"exact": 0, "requant": 1}
 OUT = {"f32": 0, "i32": 1, "i8": 2}
 PATH = {"staged": 0, "fused": 1, "single": 2}

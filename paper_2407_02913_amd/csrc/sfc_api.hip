@@ -70,7 +70,7 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   *out = nullptr;
   const sfc_conv_desc& d = *desc;
   if (d.N <= 0 || d.Cin <= 0 || d.Cout <= 0 || d.H <= 0 || d.W <= 0) return SFC_EINVAL;
-  if (d.alg < SFC_ALG_6X6_P88 || d.alg > SFC_ALG_7X7_P144) return SFC_EINVAL;
+  if (d.alg < SFC_ALG_6X6_P88 || d.alg > SFC_ALG_4X4_P49) return SFC_EINVAL;
   if (d.mode != SFC_MODE_EXACT && d.mode != SFC_MODE_REQUANT_I8) return SFC_EINVAL;
   if (d.out != SFC_OUT_F32 && d.out != SFC_OUT_I32 && d.out != SFC_OUT_I8_RELU) return SFC_EINVAL;
   if (d.path != SFC_PATH_STAGED && d.path != SFC_PATH_FUSED && d.path != SFC_PATH_SINGLE)
@@ -87,7 +87,8 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   Geometry g;
   g.N = d.N; g.Cin = d.Cin; g.Cout = d.Cout; g.H = d.H; g.W = d.W;
   g.alg = d.alg;
-  const int mt = (d.alg == SFC_ALG_7X7_P132 || d.alg == SFC_ALG_7X7_P144) ? 7 : 6;
+  const int mt = (d.alg == SFC_ALG_7X7_P132 || d.alg == SFC_ALG_7X7_P144) ? 7
+                 : (d.alg == SFC_ALG_4X4_P46 || d.alg == SFC_ALG_4X4_P49) ? 4 : 6;
   g.th = (d.H + mt - 1) / mt;
   g.tw = (d.W + mt - 1) / mt;
   const int64_t strips = (int64_t)d.N * g.th;
@@ -98,7 +99,7 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   g.Tp = (int)((T + 15) / 16 * 16);
   g.Cp = (d.Cin + 63) / 64 * 64;
   g.Kp = (d.Cout + 15) / 16 * 16;
-  static const int kPoints[4] = {88, 100, 132, 144};
+  static const int kPoints[6] = {88, 100, 132, 144, 46, 49};
   g.P = kPoints[d.alg];
   g.qmax = (float)((1 << ((d.transform_bits ? d.transform_bits : 8) - 1)) - 1);
 
@@ -217,6 +218,7 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
   float* wscale = table(plan->off_wscale);
   for (int k = 0; k < g.Kp; ++k)
     wscale[k] = k < g.Cout ? wscale_host[plan->d.per_channel_wscale ? k : 0] : 0.0f;
+  const double den = g.alg > 3 ? 16.0 : 36.0;  // the output transform yields den * y
   for (int p = 0; p < g.P; ++p) {
     inv_sx[p] = requant ? 1.0f / plan->sx[p] : 1.0f;
     for (int k = 0; k < g.Kp; ++k) {
@@ -224,7 +226,7 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
       if (requant && k < g.Cout) {
         const float sw = plan->sw[(size_t)p * g.Cout + k];
         inv = 1.0f / sw;
-        dq = (float)((double)plan->sx[p] * (double)sw * (double)wscale[k] / 36.0);
+        dq = (float)((double)plan->sx[p] * (double)sw * (double)wscale[k] / den);
       }
       dequant[(size_t)p * g.Kp + k] = dq;
       inv_sw[(size_t)p * g.Kp + k] = inv;

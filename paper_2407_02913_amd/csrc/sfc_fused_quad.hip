@@ -184,6 +184,7 @@ static unsigned quad_lds_bytes(int alg, int kc) {
 }
 
 bool fused_quad_supported(const Geometry& g) {
+  if (g.alg > 3) return false;  // SFC-6 forms only
   const int kc = g.Cp / 64;
   if (kc != 1 && kc != 2 && kc != 4 && kc != 8) return false;
   const int nw = quad_waves(g.alg, kc);

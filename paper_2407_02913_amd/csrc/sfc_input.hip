@@ -64,6 +64,7 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
 static int input_waves(int alg) { return alg_tile(alg) == 6 ? 16 : 8; }
 
 static bool make_input_plan(const Geometry& g, InputPlan* ip) {
+  if (g.alg > 3) return false;  // SFC-6 forms only
   const unsigned vbytes = (unsigned)g.P * 1024u;
   const unsigned lds_max = 160u * 1024u;
   if (vbytes + 16u + 64u > lds_max) return false;

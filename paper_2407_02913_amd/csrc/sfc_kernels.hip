@@ -276,7 +276,7 @@ __global__ __launch_bounds__(256) void product_i16_kernel(const int16_t* __restr
 
 // ---------------------------------------------------------------------------
 // output transform, exact mode: one thread per (tile, filter), lanes along filters;
-// the integer sums are divided by 36 exactly
+// the integer sums are divided by 36 (16 for SFC-4) exactly
 // ---------------------------------------------------------------------------
 template <int ALG, int OUT>
 __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __restrict__ M,
@@ -307,7 +307,7 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __
       for (int o2 = 0; o2 < MT; ++o2) {
         const int w = MT * tj + o2;
         if (w >= g.W) continue;
-        const int acc = out[o1][o2] / 36;  // exact: the sum is a multiple of 36
+        const int acc = out[o1][o2] / AlgTraits<ALG>::kDen;  // exact: the sum is a multiple of it
         if constexpr (OUT == 1)
           ((int32_t*)y)[ybase + (size_t)h * g.W + w] = acc;
         else
@@ -354,6 +354,8 @@ static hipError_t launch_input_alg(const Geometry& g, const int8_t* x, void* V, 
     case 1: return launch_input_impl<1, MODE>(g, x, V, inv_sx, maxima, s);
     case 2: return launch_input_impl<2, MODE>(g, x, V, inv_sx, maxima, s);
     case 3: return launch_input_impl<3, MODE>(g, x, V, inv_sx, maxima, s);
+    case 4: return launch_input_impl<4, MODE>(g, x, V, inv_sx, maxima, s);
+    case 5: return launch_input_impl<5, MODE>(g, x, V, inv_sx, maxima, s);
   }
   return hipErrorInvalidValue;
 }
@@ -384,6 +386,8 @@ hipError_t launch_filter_absmax(const Geometry& g, const int8_t* w, int32_t* max
     case 1: SFC_LAUNCH_FMAX(1); break;
     case 2: SFC_LAUNCH_FMAX(2); break;
     case 3: SFC_LAUNCH_FMAX(3); break;
+    case 4: SFC_LAUNCH_FMAX(4); break;
+    case 5: SFC_LAUNCH_FMAX(5); break;
     default: return hipErrorInvalidValue;
   }
 #undef SFC_LAUNCH_FMAX
@@ -406,6 +410,8 @@ hipError_t launch_filter_transform(int mode, const Geometry& g, const int8_t* w,
     case 1: SFC_LAUNCH_FT(1); break;
     case 2: SFC_LAUNCH_FT(2); break;
     case 3: SFC_LAUNCH_FT(3); break;
+    case 4: SFC_LAUNCH_FT(4); break;
+    case 5: SFC_LAUNCH_FT(5); break;
     default: return hipErrorInvalidValue;
   }
 #undef SFC_LAUNCH_FT
@@ -447,6 +453,8 @@ hipError_t launch_output_transform(int mode, int out, const Geometry& g, const i
     case 1: return launch_output_alg<1>(mode, out, g, M, f, x_scale, inv_y, y, s);
     case 2: return launch_output_alg<2>(mode, out, g, M, f, x_scale, inv_y, y, s);
     case 3: return launch_output_alg<3>(mode, out, g, M, f, x_scale, inv_y, y, s);
+    case 4: return launch_output_alg<4>(mode, out, g, M, f, x_scale, inv_y, y, s);
+    case 5: return launch_output_alg<5>(mode, out, g, M, f, x_scale, inv_y, y, s);
   }
   return hipErrorInvalidValue;
 }

@@ -29,24 +29,36 @@
 
 namespace sfc {
 
-// ALG: 0 = 6x6 Hermitian (88), 1 = 6x6 nested (100), 2 = 7x7 Hermitian (132), 3 = 7x7 nested (144)
+// SFC-4(4x4,3x3) (Appendix A, s = j): a signal of 6 samples becomes 6 components
+//   c0  X0    c1  -X2   (real, as printed)    c2  X1.a0   c3  X1.a1   (X1 = a0 + a1 j)
+//   c4  x0 - x4  (correction for output 0, with f0)     c5  x5 - x1  (for output 3, with f2)
+// and the 7 rows of the printed matrices are r0=c0 r1=c1 r2=c2+c3 r3=c3 r4=c2 r5=c4 r6=c5.
+// Product rule (Eq. DFT4M): o0 = m0 - m1, o1 = m2 - m0 - m1.  Hermitian form: the one
+// complex x complex block (9 points) becomes U = (a00 - a11) + (a10 + a01) s and
+// V = (a00 + a11) + (a10 - a01) s, each as (x0, x1, x0 + x1): 46 points instead of 49.
+//
+// ALG: 0 = 6x6 Hermitian (88), 1 = 6x6 nested (100), 2 = 7x7 Hermitian (132), 3 = 7x7 nested (144),
+//      4 = 4x4 Hermitian (46), 5 = 4x4 nested (49)
 template <int ALG>
 struct AlgTraits {
-  static_assert(ALG >= 0 && ALG < 4, "unknown algorithm");
-  static constexpr bool kHermitian = (ALG == 0 || ALG == 2);
-  static constexpr int M = ALG < 2 ? 6 : 7;   // outputs per tile edge
-  static constexpr int NI = M + 2;            // input samples per tile edge
-  static constexpr int NC = ALG < 2 ? 8 : 10; // components per axis
-  static constexpr int NR = NC + 2;           // rows of the printed 1-D matrices
-  static constexpr int NREAL = NR - 6;        // rows that are not part of a complex point
-  static constexpr int P = kHermitian ? NR * NR - 12 : NR * NR;
+  static_assert(ALG >= 0 && ALG < 6, "unknown algorithm");
+  static constexpr int kFamily = ALG < 4 ? 6 : 4;  // points of the symbolic DFT
+  static constexpr bool kHermitian = (ALG == 0 || ALG == 2 || ALG == 4);
+  static constexpr int M = ALG < 2 ? 6 : ALG < 4 ? 7 : 4;  // outputs per tile edge
+  static constexpr int NI = M + 2;                         // input samples per tile edge
+  static constexpr int NC = ALG < 2 ? 8 : ALG < 4 ? 10 : 6;  // components per axis
+  // rows of the printed 1-D matrices: one more than components per complex point
+  static constexpr int NR = kFamily == 6 ? NC + 2 : NC + 1;
+  static constexpr int NREAL = kFamily == 6 ? NR - 6 : NR - 3;  // rows outside a complex point
+  static constexpr int P = !kHermitian ? NR * NR : kFamily == 6 ? NR * NR - 12 : NR * NR - 3;
+  static constexpr int kDen = kFamily == 6 ? 36 : 16;  // the output transform yields kDen * y
 };
 
-constexpr int kNumAlgs = 4;
+constexpr int kNumAlgs = 6;
 __host__ __device__ constexpr int alg_points(int alg) {
-  return alg == 0 ? 88 : alg == 1 ? 100 : alg == 2 ? 132 : 144;
+  return alg == 0 ? 88 : alg == 1 ? 100 : alg == 2 ? 132 : alg == 3 ? 144 : alg == 4 ? 46 : 49;
 }
-__host__ __device__ constexpr int alg_tile(int alg) { return alg < 2 ? 6 : 7; }
+__host__ __device__ constexpr int alg_tile(int alg) { return alg < 2 ? 6 : alg < 4 ? 7 : 4; }
 
 // ---- row bookkeeping ----------------------------------------------------------
 
@@ -72,6 +84,11 @@ SFC_HD constexpr int kept_index(int r1, int r2) {
     }
   return -1;
 }
+
+// SFC-4: row -> component(s), in the printed row order
+SFC_HD constexpr int row4_c0(int r) { return r == 0 ? 0 : r == 1 ? 1 : r == 2 ? 2 : r == 3 ? 3 : r == 4 ? 2 : r - 1; }
+SFC_HD constexpr int row4_c1(int r) { return r == 2 ? 3 : -1; }
+SFC_HD constexpr bool row4_is_complex(int r) { return r >= 2 && r <= 4; }
 
 // Processing order of the fused kernels: canonical point indices grouped by
 // horizontal class (first the real columns with all their vertical rows, then the
@@ -111,6 +128,17 @@ struct Order {
 // six samples, one per correction input).
 template <int NI, int NC, typename T>
 SFC_HD void fwd_input(const T (&x)[NI], T (&c)[NC]) {
+  if constexpr (NI == 6) {
+    // SFC-4: 6 samples -> 6 components, 8 additions
+    const T s02 = x[1] + x[3], s13 = x[2] + x[4];
+    c[0] = s02 + s13;
+    c[1] = s13 - s02;
+    c[2] = x[1] - x[3];
+    c[3] = x[4] - x[2];
+    c[4] = x[0] - x[4];
+    c[5] = x[5] - x[1];
+    return;
+  } else {
   const T e0 = x[1] + x[4], e1 = x[2] + x[5], e2 = x[3] + x[6];
   const T d0 = x[1] - x[4], d1 = x[2] - x[5], d2 = x[3] - x[6];
   c[0] = e0 + e1 + e2;
@@ -125,11 +153,23 @@ SFC_HD void fwd_input(const T (&x)[NI], T (&c)[NC]) {
     c[8] = c[7];
     c[9] = x[8] - x[2];
   }
+  }
 }
 
 // Three filter taps -> NC components (rows of Appendix A's G without the sum rows).
 template <int NC, typename T>
 SFC_HD void fwd_filter(const T (&f)[3], T (&c)[NC]) {
+  if constexpr (NC == 6) {
+    // SFC-4 (rows of Appendix A's G without the sum row)
+    const T s = f[0] + f[2];
+    c[0] = s + f[1];
+    c[1] = s - f[1];
+    c[2] = -f[1];
+    c[3] = f[0] - f[2];
+    c[4] = f[0];
+    c[5] = f[2];
+    return;
+  } else {
   c[0] = f[0] + f[1] + f[2];
   c[1] = f[1] + f[2];
   c[2] = -f[0] - f[1];
@@ -142,13 +182,16 @@ SFC_HD void fwd_filter(const T (&f)[3], T (&c)[NC]) {
     c[8] = f[1];
     c[9] = f[2];
   }
+  }
 }
 
 // ---- forward, 2-D: components -> multiplication points ----------------------
 
 template <int NC, typename T>
 SFC_HD T nested_point(const T (&c)[NC][NC], int r1, int r2) {
-  const int a0 = row_c0(r1), a1 = row_c1(r1), b0 = row_c0(r2), b1 = row_c1(r2);
+  constexpr bool k4 = NC == 6;  // SFC-4
+  const int a0 = k4 ? row4_c0(r1) : row_c0(r1), a1 = k4 ? row4_c1(r1) : row_c1(r1);
+  const int b0 = k4 ? row4_c0(r2) : row_c0(r2), b1 = k4 ? row4_c1(r2) : row_c1(r2);
   T v = c[a0][b0];
   if (b1 >= 0) v += c[a0][b1];
   if (a1 >= 0) {
@@ -173,6 +216,20 @@ SFC_HD void hermitian_points(const T (&c)[NC][NC], int g1, int g2, T (&out)[6]) 
   out[5] = v0 + v1;
 }
 
+// SFC-4: the six Hermitian points of the single complex frequency pair (components 2, 3).
+template <typename T>
+SFC_HD void hermitian4_points(const T (&c)[6][6], T (&out)[6]) {
+  const T a00 = c[2][2], a10 = c[3][2], a01 = c[2][3], a11 = c[3][3];
+  const T u0 = a00 - a11, u1 = a10 + a01;
+  const T v0 = a00 + a11, v1 = a10 - a01;
+  out[0] = u0;
+  out[1] = u1;
+  out[2] = u0 + u1;
+  out[3] = v0;
+  out[4] = v1;
+  out[5] = v0 + v1;
+}
+
 // Calls f(p, value) for every point in canonical order.  Fully unrolled: p is a
 // compile-time constant at each call site after inlining.
 template <int ALG, typename T, typename F>
@@ -189,18 +246,29 @@ SFC_HD void for_each_point(const T (&c)[AlgTraits<ALG>::NC][AlgTraits<ALG>::NC],
     for (int r1 = 0; r1 < NR; ++r1)
 #pragma unroll
       for (int r2 = 0; r2 < NR; ++r2) {
-        if (row_is_complex(r1) && row_is_complex(r2)) continue;
+        if constexpr (AlgTraits<ALG>::kFamily == 4) {
+          if (row4_is_complex(r1) && row4_is_complex(r2)) continue;
+        } else {
+          if (row_is_complex(r1) && row_is_complex(r2)) continue;
+        }
         f(p++, nested_point(c, r1, r2));
       }
+    if constexpr (AlgTraits<ALG>::kFamily == 4) {
+      T h[6];
+      hermitian4_points(c, h);
 #pragma unroll
-    for (int g1 = 0; g1 < 2; ++g1)
+      for (int i = 0; i < 6; ++i) f(p++, h[i]);
+    } else {
 #pragma unroll
-      for (int g2 = 0; g2 < 2; ++g2) {
-        T h[6];
-        hermitian_points(c, g1, g2, h);
+      for (int g1 = 0; g1 < 2; ++g1)
 #pragma unroll
-        for (int i = 0; i < 6; ++i) f(p++, h[i]);
-      }
+        for (int g2 = 0; g2 < 2; ++g2) {
+          T h[6];
+          hermitian_points(c, g1, g2, h);
+#pragma unroll
+          for (int i = 0; i < 6; ++i) f(p++, h[i]);
+        }
+    }
   }
 }
 
@@ -267,11 +335,130 @@ SFC_HD void inv_outputs(const T (&c)[NC], T (&y)[NC - 2 - (NC == 10 ? 1 : 0)]) {
   if constexpr (NC == 10) y[6] = y0 + T(6) * (c[8] + c[9]);
 }
 
-// All P products of one (tile, Cout) pair -> M x M outputs times 36.
+template <typename T>
+struct Half;
+template <>
+struct Half<int> {
+  static SFC_HD int apply(int v) { return v >> 1; }  // exact: the argument is even
+};
+template <>
+struct Half<float> {
+  static SFC_HD float apply(float v) { return v * 0.5f; }
+};
+
+// SFC-4: 7 1-D products -> 6 components (Eq. DFT4M: o0 = m0 - m1, o1 = m2 - m0 - m1, with
+// the rows a0+a1, a1, a0 at positions 2, 3, 4).
+template <typename T>
+SFC_HD void collapse4_rows(const T (&r)[7], T (&c)[6]) {
+  c[0] = r[0];
+  c[1] = r[1];
+  c[2] = r[4] - r[3];
+  c[3] = r[2] - r[4] - r[3];
+  c[4] = r[5];
+  c[5] = r[6];
+}
+
+// SFC-4: 6 components -> 4 outputs, times 4 (inverse symbolic DFT-4 plus the corrections).
+template <typename T>
+SFC_HD void inv4_outputs(const T (&c)[6], T (&y)[4]) {
+  const T s = c[0] + c[1], d = c[0] - c[1];
+  const T re2 = c[2] + c[2], im2 = c[3] + c[3];
+  y[0] = s - re2 + T(4) * c[4];
+  y[1] = d + im2;
+  y[2] = s + re2;
+  y[3] = d - im2 + T(4) * c[5];
+}
+
+// SFC-4: all P products of one (tile, Cout) pair -> 4 x 4 outputs times 16.
+template <int ALG, typename T, typename G>
+SFC_HD void output_transform4(G&& get, T (&out)[4][4]) {
+  constexpr int NR = 7, NC = 6;
+  T comp[NC][NC];
+  if constexpr (!AlgTraits<ALG>::kHermitian) {
+    T half[NR][NC];
+#pragma unroll
+    for (int r1 = 0; r1 < NR; ++r1) {
+      T row[NR];
+#pragma unroll
+      for (int r2 = 0; r2 < NR; ++r2) row[r2] = get(NR * r1 + r2);
+      collapse4_rows(row, half[r1]);
+    }
+#pragma unroll
+    for (int b = 0; b < NC; ++b) {
+      T col[NR], cc[NC];
+#pragma unroll
+      for (int r1 = 0; r1 < NR; ++r1) col[r1] = half[r1][b];
+      collapse4_rows(col, cc);
+#pragma unroll
+      for (int a = 0; a < NC; ++a) comp[a][b] = cc[a];
+    }
+  } else {
+    T kept[NR][NR];
+    int p = 0;
+#pragma unroll
+    for (int r1 = 0; r1 < NR; ++r1)
+#pragma unroll
+      for (int r2 = 0; r2 < NR; ++r2) {
+        if (row4_is_complex(r1) && row4_is_complex(r2)) {
+          kept[r1][r2] = T(0);
+          continue;
+        }
+        kept[r1][r2] = get(p++);
+      }
+    // real r1 (rows 0, 1, 5, 6 -> components 0, 1, 4, 5): collapse along the horizontal axis
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r1 = i < 2 ? i : i + 3, a = i < 2 ? i : i + 2;
+      T cc[NC];
+      collapse4_rows(kept[r1], cc);
+#pragma unroll
+      for (int b = 0; b < NC; ++b) comp[a][b] = cc[b];
+    }
+    // complex r1, real r2: collapse along the vertical axis
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int r2 = j < 2 ? j : j + 3, b = j < 2 ? j : j + 2;
+      T col[NR], cc[NC];
+#pragma unroll
+      for (int r1 = 0; r1 < NR; ++r1) col[r1] = kept[r1][r2];
+      collapse4_rows(col, cc);
+      comp[2][b] = cc[2];
+      comp[3][b] = cc[3];
+    }
+    // complex x complex from the Hermitian block
+    T m[6];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) m[i] = get(p++);
+    const T uo0 = m[0] - m[1], uo1 = m[2] - m[0] - m[1];
+    const T vo0 = m[3] - m[4], vo1 = m[5] - m[3] - m[4];
+    comp[2][2] = Half<T>::apply(uo0 + vo0);  // o00
+    comp[3][3] = Half<T>::apply(vo0 - uo0);  // o11
+    comp[3][2] = Half<T>::apply(uo1 + vo1);  // o10
+    comp[2][3] = Half<T>::apply(uo1 - vo1);  // o01
+  }
+  T z[NC][4];
+#pragma unroll
+  for (int a = 0; a < NC; ++a) inv4_outputs(comp[a], z[a]);
+#pragma unroll
+  for (int o2 = 0; o2 < 4; ++o2) {
+    T col[NC], y[4];
+#pragma unroll
+    for (int a = 0; a < NC; ++a) col[a] = z[a][o2];
+    inv4_outputs(col, y);
+#pragma unroll
+    for (int o1 = 0; o1 < 4; ++o1) out[o1][o2] = y[o1];
+  }
+}
+
+// All P products of one (tile, Cout) pair -> M x M outputs times 36 (16 for SFC-4).
 // get(p) returns product p (already scaled in the dequantizing case).
 template <int ALG, typename T, typename G>
 SFC_HD void output_transform(G&& get, T (&out)[AlgTraits<ALG>::M][AlgTraits<ALG>::M]) {
   using Tr = AlgTraits<ALG>;
+  if constexpr (Tr::kFamily == 4) {
+    output_transform4<ALG, T>(get, out);
+    return;
+  } else {
   constexpr int NR = Tr::NR, NC = Tr::NC, M = Tr::M, NREAL = Tr::NREAL;
   T comp[NC][NC];
   if constexpr (!Tr::kHermitian) {
@@ -349,6 +536,7 @@ SFC_HD void output_transform(G&& get, T (&out)[AlgTraits<ALG>::M][AlgTraits<ALG>
     inv_outputs(col, y);
 #pragma unroll
     for (int o1 = 0; o1 < M; ++o1) out[o1][o2] = y[o1];
+  }
   }
 }
 

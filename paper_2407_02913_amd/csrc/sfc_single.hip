@@ -172,7 +172,7 @@ __global__ __launch_bounds__(64) void repack_filter_kernel(const int8_t* __restr
 static int single_waves(int alg) { return alg_tile(alg) == 6 ? kWaves6 : 8; }
 
 static bool make_single_plan(const Geometry& g, SinglePlan* sp) {
-  if (g.Cp != 64) return false;
+  if (g.Cp != 64 || g.alg > 3) return false;  // SFC-6 forms only
   const int M = alg_tile(g.alg);
   // LDS: the staged rows of the rectangle (later overwritten by V), the per-wave output
   // staging blocks, the per-tile store table

@@ -1,9 +1,10 @@
 // Host-side dump of the linear maps realized by the kernels' add networks
 // (sfc_points.hpp), so that a CPU test can compare them with the oracle's
-// matrices.  Prints, for every ALG (0: 6x6/88, 1: 6x6/100, 2: 7x7/132, 3: 7x7/144):
+// matrices.  Prints, for every ALG (0: 6x6/88, 1: 6x6/100, 2: 7x7/132, 3: 7x7/144,
+// 4: 4x4/46, 5: 4x4/49):
 //   B <alg> <p> <NI*NI ints>   input transform row p  (impulse responses)
 //   G <alg> <p> <9 ints>       filter transform row p
-//   A <alg> <p> <M*M ints>     output transform row p (times 36)
+//   A <alg> <p> <M*M ints>     output transform row p (times 36; times 16 for 4x4)
 #include <cmath>
 #include <cstdio>
 #include <vector>
@@ -66,5 +67,7 @@ int main() {
   dump<1>();
   dump<2>();
   dump<3>();
+  dump<4>();
+  dump<5>();
   return 0;
 }

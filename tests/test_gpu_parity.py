@@ -46,9 +46,10 @@ def rel_err(y, ref):
 
 
 ALGS = ["6x6_p88", "6x6_p100", "7x7_p132", "7x7_p144"]
+ALGS_STAGED = ALGS + ["4x4_p46", "4x4_p49"]  # SFC-4(4x4,3x3) runs on the staged path
 
 
-@pytest.mark.parametrize("alg", ALGS)
+@pytest.mark.parametrize("alg", ALGS_STAGED)
 @pytest.mark.parametrize("shape", SMALL_SHAPES)
 def test_exact_mode_taps_and_sums_bit_exact(binding, shape, alg):
     x, w, xs, ws = uniform_case(shape, 100 + len(alg) + sum(shape))
@@ -63,7 +64,7 @@ def test_exact_mode_taps_and_sums_bit_exact(binding, shape, alg):
     assert rel_err(y, oracle.dequantize(acc_ref, xs, ws)) <= F32_TOL
 
 
-@pytest.mark.parametrize("alg", ALGS)
+@pytest.mark.parametrize("alg", ALGS_STAGED)
 @pytest.mark.parametrize("shape", SMALL_SHAPES)
 def test_requant_mode_taps_bit_exact_and_output_close(binding, shape, alg):
     x, w, xs, ws = uniform_case(shape, 200 + len(alg) + sum(shape))
@@ -120,7 +121,7 @@ def test_single_filter_scale(binding):
     assert rel_err(y, oracle.dequantize(oracle.direct_conv(x, w), xs, ws)) <= F32_TOL
 
 
-@pytest.mark.parametrize("alg", ALGS)
+@pytest.mark.parametrize("alg", ALGS_STAGED)
 def test_gpu_calibration_matches_oracle(binding, alg):
     import torch
 
@@ -140,6 +141,32 @@ def test_gpu_calibration_matches_oracle(binding, alg):
 
 
 FULL = ["resnet56", "resnet28", "resnet14", "resnet7"]
+
+
+@pytest.mark.parametrize("alg", ["4x4_p46", "4x4_p49"])
+def test_sfc4_full_size_and_int8_output(binding, alg):
+    """SFC-4(4x4,3x3) on resnet28 (4x4 tiles divide 28): every tap and output element; then the
+    int8 + ReLU epilogue; the fused and single-kernel paths do not take the 4x4 forms."""
+    shape = synth.LAYERS["resnet28"]
+    print("case sfc4 full", alg, flush=True)
+    d = synth.make_layer(shape)
+    sx = oracle.calibrate_act_scales(d["x_calib"], alg)
+    sw = oracle.calibrate_filter_scales(d["w"], alg)
+    y_ref, taps_ref = oracle.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"], alg,
+                                          return_taps=True)
+    y, taps = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg,
+                             sx=sx, sw=sw, return_taps=True)
+    for tap in ("V", "U", "M"):
+        assert np.array_equal(taps[tap].astype(np.int64), taps_ref[tap]), tap
+    assert rel_err(y, y_ref) <= F32_TOL
+    y_scale = float(np.float32(max(y_ref.max(), 1e-6) / 127.0 * 0.8))
+    y8 = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg, out="i8",
+                        sx=sx, sw=sw, y_scale=y_scale)
+    assert check_i8_against_oracle(y8, y_ref, y_scale) < 1e-3
+    for path in ("fused", "single"):
+        with pytest.raises(binding.SfcError) as e:
+            binding.Plan(1, 16, 16, 8, 8, alg=alg, path=path)
+        assert e.value.code == 2
 
 
 @pytest.mark.parametrize("name", FULL)

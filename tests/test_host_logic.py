@@ -155,10 +155,11 @@ def kernel_maps(tmp_path_factory):
     return {k: np.array([v[i] for i in range(len(v))]) for k, v in maps.items()}
 
 
-@pytest.mark.parametrize("alg_id,alg", [(0, "6x6_p88"), (1, "6x6_p100"), (2, "7x7_p132"), (3, "7x7_p144")])
+@pytest.mark.parametrize("alg_id,alg", [(0, "6x6_p88"), (1, "6x6_p100"), (2, "7x7_p132"), (3, "7x7_p144"),
+                                        (4, "4x4_p46"), (5, "4x4_p49")])
 def test_kernel_add_networks_realize_the_oracle_matrices(kernel_maps, alg_id, alg):
     b2, g2, a2, den = oracle.algorithm(alg)
-    assert den == 36
+    assert den == (16 if alg.startswith("4x4") else 36)
     assert np.array_equal(kernel_maps[("B", alg_id)], b2)
     assert np.array_equal(kernel_maps[("G", alg_id)], g2)
     assert np.array_equal(kernel_maps[("A", alg_id)], a2)
