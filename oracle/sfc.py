@@ -1,4 +1,4 @@
-"""Plain numpy oracle for quantized 3x3 convolution by Symbolic Fourier Convolution.
+"""Plain numpy oracle for quantized 3x3 (and 5x5) convolution by Symbolic Fourier Convolution.
 
 TEST INFRASTRUCTURE ONLY.  This module is the slow, obviously-correct CPU
 statement of the method (arXiv 2407.02913).  It is imported by ``tests/``, by
@@ -11,10 +11,13 @@ floating-point stages are float64.
 What is the definition and what is the algorithm
 ------------------------------------------------
 * ``direct_conv``            -- the *definition* of the result (cross-correlation,
-                               stride 1, zero padding 1).  In exact-integer mode
-                               SFC reaches exactly this result.
+                               stride 1, zero padding (R-1)/2 for an RxR filter).  In
+                               exact-integer mode SFC reaches exactly this result.
 * ``sfc6_1d`` ...            -- the 1-D matrices of SFC-6(6,3) as printed in
                                Appendix A (one erratum, see ``BT_PRINTED_ROW7``).
+* ``sfc6_1d(6, 5)``          -- SFC-6(6x6,5x5): B^T and G as printed in Appendix A, A
+                               the one matrix that fits them (the print of A is
+                               unusable); re-derived by ``integrate_1d_5tap``.
 * ``nested_2d``              -- the 2-D form of Eq. (1): Kronecker products,
                                10*10 = 100 multiplications per 6x6 tile.
 * ``hermitian_2d``           -- the 88-multiplication form.  Appendix A only
@@ -245,6 +248,78 @@ A7_1D = np.array(
     dtype=np.int64,
 )
 
+# ---------------------------------------------------------------------------
+# Appendix A: SFC-6(6x6, 5x5).  B^T (14x10) and G (14x5) are used as printed: rows 0..7 are
+# the rows of SFC-6(6x6,3x3) acting on the inner samples x2..x7, with the filter's symbolic
+# DFT aligned as G_k = sum_r f_r s^{k (r - 4)}; six correction rows, each "wanted sample
+# minus the sample the cyclic convolution supplies" times one tap:
+#    8: (x0 - x6) f0 -> output 0      9: (x1 - x7) f0 -> output 1     10: (x1 - x7) f1 -> output 0
+#   11: (x8 - x2) f3 -> output 5     12: (x8 - x2) f4 -> output 4     13: (x9 - x3) f4 -> output 5
+# A is printed with seven columns for six outputs and cannot be right as it stands.  B^T and
+# G determine A uniquely (the 14 bilinear forms B^T[p,i] G[p,r] are linearly independent), and
+# that unique A is used: in rows 0..7 it equals the first six printed columns; the
+# correction rows send each product to the output named above.
+# ---------------------------------------------------------------------------
+BT65_1D = np.array(
+    [
+        [0, 0, 1, 1, 1, 1, 1, 1, 0, 0],
+        [0, 0, 1, 1, 0, -1, -1, 0, 0, 0],
+        [0, 0, 0, -1, -1, 0, 1, 1, 0, 0],
+        [0, 0, 1, 0, -1, -1, 0, 1, 0, 0],
+        [0, 0, 1, 0, -1, 1, 0, -1, 0, 0],
+        [0, 0, 0, -1, 1, 0, -1, 1, 0, 0],
+        [0, 0, 1, -1, 0, 1, -1, 0, 0, 0],
+        [0, 0, 1, -1, 1, -1, 1, -1, 0, 0],
+        [1, 0, 0, 0, 0, 0, -1, 0, 0, 0],
+        [0, 1, 0, 0, 0, 0, 0, -1, 0, 0],
+        [0, 1, 0, 0, 0, 0, 0, -1, 0, 0],
+        [0, 0, -1, 0, 0, 0, 0, 0, 1, 0],
+        [0, 0, -1, 0, 0, 0, 0, 0, 1, 0],
+        [0, 0, 0, -1, 0, 0, 0, 0, 0, 1],
+    ],
+    dtype=np.int64,
+)
+
+G65_1D = np.array(
+    [
+        [1, 1, 1, 1, 1],
+        [-1, -1, 0, 1, 1],
+        [1, 0, -1, -1, 0],
+        [0, -1, -1, 0, 1],
+        [0, 1, -1, 0, 1],
+        [-1, 0, 1, -1, 0],
+        [-1, 1, 0, -1, 1],
+        [1, -1, 1, -1, 1],
+        [1, 0, 0, 0, 0],
+        [1, 0, 0, 0, 0],
+        [0, 1, 0, 0, 0],
+        [0, 0, 0, 1, 0],
+        [0, 0, 0, 0, 1],
+        [0, 0, 0, 0, 1],
+    ],
+    dtype=np.int64,
+)
+
+A65_1D = np.array(  # numerators, A = A65_1D / 6
+    [
+        [1, 1, 1, 1, 1, 1],
+        [1, -1, -2, -1, 1, 2],
+        [1, 2, 1, -1, -2, -1],
+        [-2, -1, 1, 2, 1, -1],
+        [-2, 1, 1, -2, 1, 1],
+        [1, -2, 1, 1, -2, 1],
+        [1, 1, -2, 1, 1, -2],
+        [1, -1, 1, -1, 1, -1],
+        [6, 0, 0, 0, 0, 0],
+        [0, 6, 0, 0, 0, 0],
+        [6, 0, 0, 0, 0, 0],
+        [0, 0, 0, 0, 0, 6],
+        [0, 0, 0, 0, 6, 0],
+        [0, 0, 0, 0, 0, 6],
+    ],
+    dtype=np.int64,
+)
+
 # SFC-4(4x4,3x3), Appendix A (first set of matrices): s = j, four-point symbolic DFT of the
 # inner samples x1..x4 plus one correction row per wrapped output.  Row order as printed:
 # X0, X2 (both real), then the complex point X1 = a0 + a1 j as (a0 + a1, a1, a0), then the
@@ -286,11 +361,18 @@ KERNEL = 3  # R
 COMPLEX_GROUPS = ((1, 2, 3), (4, 5, 6))  # (a0 row, a1 row, a0+a1 row), both variants
 
 
-def sfc6_1d(m: int = 6):
-    """The three 1-D matrices of SFC-6(m,3), m = 6 or 7: (B^T, G, A numerators, 6).
+def sfc6_1d(m: int = 6, r: int = 3):
+    """The three 1-D matrices of SFC-6(m,r): (B^T, G, A numerators, 6).
 
-    m = 6: B^T 10x8, G 10x3, A 10x6.  m = 7: B^T 12x9, G 12x3, A 12x7.
+    r = 3, m = 6: B^T 10x8, G 10x3, A 10x6.  r = 3, m = 7: B^T 12x9, G 12x3, A 12x7.
+    r = 5, m = 6: B^T 14x10, G 14x5, A 14x6.
     """
+    if r == 5:
+        if m != 6:
+            raise ValueError(m)
+        return BT65_1D.copy(), G65_1D.copy(), A65_1D.copy(), A_1D_DEN
+    if r != 3:
+        raise ValueError(r)
     if m == 6:
         return BT_1D.copy(), G_1D.copy(), A_1D.copy(), A_1D_DEN
     if m == 7:
@@ -372,23 +454,78 @@ def integrate_1d(m: int = 6):
     return bt, g, a, 6
 
 
+def integrate_1d_5tap():
+    """Re-derive B^T, G, A of SFC-6(6x6,5x5) from Sec. 4.1-4.2 (same five steps as
+    ``integrate_1d``): the cyclic part works on the six inner samples x2..x7 of ten, the
+    filter's symbolic DFT is G_k = sum_r f_r s^{k (r - 4)}, and every (output o, tap r) whose
+    sample x_{o+r} lies outside x2..x7 gets one correction row (x_{o+r} minus the inner
+    sample six positions away, times f_r, added to output o); rows ordered by (r, o).
+    Returns (B^T 14x10, G 14x5, A numerators 14x6, 6).
+    """
+    bt = np.zeros((14, 10), dtype=np.int64)
+    g = np.zeros((14, 5), dtype=np.int64)
+    a = np.zeros((14, 6), dtype=np.int64)
+
+    def s_pow(n):
+        c = np.array([1, 0], dtype=np.int64)
+        for _ in range(n % 6):
+            c = np.array([-c[1], c[0] + c[1]])
+        return c
+
+    for brow, frow in {0: 0, 1: 1, 2: 2, 4: 3, 5: 4, 7: 5}.items():
+        bt[brow, 2:8] = F6[frow]
+    for k, (r0, r1) in ((1, (1, 2)), (2, (4, 5))):
+        for r in range(5):
+            c = s_pow(k * (r - 4))
+            g[r0, r], g[r1, r] = c[0], c[1]
+    g[0] = 1
+    for r in range(5):
+        g[7, r] = 1 if (r - 4) % 2 == 0 else -1
+    for r0, r1, rs in COMPLEX_GROUPS:
+        bt[rs] = bt[r0] + bt[r1]
+        g[rs] = g[r0] + g[r1]
+    # the inverse: with this alignment the cyclic result of iF_6 comes out rotated by one
+    # position (component products -> cyclic output (o + 1) mod 6 lands on output o)
+    rot = [(o + 1) % 6 for o in range(6)]
+    a[0] = IF6[0][rot]
+    a[7] = IF6[5][rot]
+    for (r0, r1, rs), (c0, c1) in zip(COMPLEX_GROUPS, ((1, 2), (3, 4))):
+        a[r0] = IF6[c0][rot] - IF6[c1][rot]
+        a[r1] = -IF6[c0][rot]
+        a[rs] = IF6[c1][rot]
+    row = 8
+    for r in range(5):
+        for o in range(6):
+            i = o + r
+            if 2 <= i <= 7:
+                continue
+            supplied = 2 + (i - 2) % 6
+            bt[row, i], bt[row, supplied] = 1, -1
+            g[row, r] = 1
+            a[row, o] = 6
+            row += 1
+    assert row == 14
+    return bt, g, a, 6
+
+
 # ---------------------------------------------------------------------------
 # 2-D forms (Eq. 1: y = A^T [ (G f G^T) . (B^T x B) ] A )
 # ---------------------------------------------------------------------------
 
 
-def nested_2d(m: int = 6):
-    """Nested (Kronecker) 2-D form: 100 points per 6x6 tile, 144 per 7x7 tile.
+def nested_2d(m: int = 6, r: int = 3):
+    """Nested (Kronecker) 2-D form: 100 points per 6x6 tile, 144 per 7x7 tile (3x3 filter),
+    196 per 6x6 tile with a 5x5 filter.
 
-    Returns (B2 [P,(m+2)^2], G2 [P,9], A2 numerators [P,m^2], 36); point
+    Returns (B2 [P,(m+r-1)^2], G2 [P,r^2], A2 numerators [P,m^2], 36); point
     p = rows*p1 + p2 with p1 along the vertical (row) axis of the tile.
     """
-    bt, g, a, den = sfc6_1d(m)
+    bt, g, a, den = sfc6_1d(m, r)
     return np.kron(bt, bt), np.kron(g, g), np.kron(a, a), den * den
 
 
-def hermitian_2d(m: int = 6):
-    """88-point (6x6) / 132-point (7x7) 2-D form ("when Hermitian symmetry is fully considered", Appendix A).
+def hermitian_2d(m: int = 6, r: int = 3):
+    """88-point (6x6) / 132-point (7x7) / 184-point (6x6 outputs, 5x5 filter) 2-D form ("when Hermitian symmetry is fully considered", Appendix A).
 
     The paper states the count only.  Construction used here:
 
@@ -412,14 +549,14 @@ def hermitian_2d(m: int = 6):
           o00 = Uo0 + o11,   o10 = Vo1 + o01
       and the tile output is sum_ij (c_i (x) c_j) o_ij with c_0 = -A[a1 row],
       c_1 = A[sum row] (the iF_6 rows recovered from the folded A).
-    Count: 64 + 4*6 = 88 for the 6x6 tile; 108 + 24 = 132 for the 7x7 tile (the
-    same construction: only the number of correction rows differs).  Order: the
+    Count: 64 + 4*6 = 88 for the 6x6 tile; 108 + 24 = 132 for the 7x7 tile; 160 + 24 = 184
+    for SFC-6(6x6,5x5) (the same construction: only the number of correction rows differs).  Order: the
     kept points in nested order, then the blocks (k1,k2) = (1,1), (1,2), (2,1),
     (2,2), six points each in the order U0, U1, U0+U1, V0, V1, V0+V1.
 
-    Returns (B2 [P,(m+2)^2], G2 [P,9], A2 numerators [P,m^2], 36).
+    Returns (B2 [P,(m+r-1)^2], G2 [P,r^2], A2 numerators [P,m^2], 36).
     """
-    bt, g, a, den = sfc6_1d(m)
+    bt, g, a, den = sfc6_1d(m, r)
     nrows = bt.shape[0]
     complex_rows = {r for grp in COMPLEX_GROUPS for r in grp}
     b_rows, g_rows, a_rows = [], [], []
@@ -543,26 +680,33 @@ def hermitian4_2d(m: int = 4):
     )
 
 
-_ALGORITHMS = {
-    "6x6_p88": (hermitian_2d, 6),
-    "6x6_p100": (nested_2d, 6),
-    "7x7_p132": (hermitian_2d, 7),
-    "7x7_p144": (nested_2d, 7),
-    "4x4_p46": (hermitian4_2d, 4),
-    "4x4_p49": (nested4_2d, 4),
+_ALGORITHMS = {  # name -> (2-D construction, outputs per tile edge M, filter size R)
+    "6x6_p88": (hermitian_2d, 6, 3),
+    "6x6_p100": (nested_2d, 6, 3),
+    "7x7_p132": (hermitian_2d, 7, 3),
+    "7x7_p144": (nested_2d, 7, 3),
+    "4x4_p46": (hermitian4_2d, 4, 3),
+    "4x4_p49": (nested4_2d, 4, 3),
+    "6x6_5x5_p184": (hermitian_2d, 6, 5),
+    "6x6_5x5_p196": (nested_2d, 6, 5),
 }
 
 
 def algorithm(name: str):
     """(B2, G2, A2 numerators, denominator) for "6x6_p88", "6x6_p100", "7x7_p132", "7x7_p144",
-    "4x4_p46", "4x4_p49"."""
-    build, m = _ALGORITHMS[name]
-    return build(m)
+    "4x4_p46", "4x4_p49" (3x3 filters) and "6x6_5x5_p184", "6x6_5x5_p196" (5x5 filters)."""
+    build, m, r = _ALGORITHMS[name]
+    return build(m) if r == 3 else build(m, r)
 
 
 def tile_out(name: str) -> int:
-    """Outputs per tile edge (M of SFC-6(MxM,3x3))."""
+    """Outputs per tile edge (M of SFC-N(MxM,RxR))."""
     return _ALGORITHMS[name][1]
+
+
+def kernel_size(name: str) -> int:
+    """Filter edge (R of SFC-N(MxM,RxR))."""
+    return _ALGORITHMS[name][2]
 
 
 def multiplications_per_tile(name: str) -> int:
@@ -570,12 +714,12 @@ def multiplications_per_tile(name: str) -> int:
     return algorithm(name)[0].shape[0]
 
 
-def direct_multiplications_per_tile(m: int = TILE_OUT) -> int:
-    return m * m * KERNEL * KERNEL
+def direct_multiplications_per_tile(m: int = TILE_OUT, r: int = KERNEL) -> int:
+    return m * m * r * r
 
 
 # ---------------------------------------------------------------------------
-# The definition: direct 3x3 cross-correlation, stride 1, zero padding 1.
+# The definition: direct RxR cross-correlation (R = 3 or 5), stride 1, zero padding (R-1)/2.
 # ---------------------------------------------------------------------------
 
 
@@ -588,7 +732,8 @@ def _exact_f64(*max_abs_and_len):
 
 
 def direct_conv(x: np.ndarray, w: np.ndarray) -> np.ndarray:
-    """acc[n,k,h,w] = sum_{c,r,s} x[n,c,h+r-1,w+s-1] * w[k,c,r,s], zeros outside.
+    """acc[n,k,h,w] = sum_{c,r,s} x[n,c,h+r-pad,w+s-pad] * w[k,c,r,s], zeros outside, for an
+    R x R filter (R odd) with pad = (R-1)/2.
 
     int8 inputs, exact int64 result.  (No kernel flip: the paper's matrices
     compute y_o = sum_r x_{o+r} f_r.)
@@ -596,15 +741,16 @@ def direct_conv(x: np.ndarray, w: np.ndarray) -> np.ndarray:
     x = np.asarray(x)
     w = np.asarray(w)
     n, c, h, wd = x.shape
-    k = w.shape[0]
-    assert w.shape == (k, c, 3, 3)
-    _exact_f64(np.abs(x).max(initial=1), np.abs(w).max(initial=1), 9 * c)
-    xp = np.zeros((n, c, h + 2, wd + 2), dtype=np.float64)
-    xp[:, :, 1 : 1 + h, 1 : 1 + wd] = x
+    k, rr = w.shape[0], w.shape[2]
+    assert w.shape == (k, c, rr, rr) and rr % 2 == 1
+    pad = (rr - 1) // 2
+    _exact_f64(np.abs(x).max(initial=1), np.abs(w).max(initial=1), rr * rr * c)
+    xp = np.zeros((n, c, h + 2 * pad, wd + 2 * pad), dtype=np.float64)
+    xp[:, :, pad : pad + h, pad : pad + wd] = x
     wf = w.astype(np.float64)
     acc = np.zeros((k, n, h, wd), dtype=np.float64)
-    for r in range(3):
-        for s in range(3):
+    for r in range(rr):
+        for s in range(rr):
             acc += np.tensordot(wf[:, :, r, s], xp[:, :, r : r + h, s : s + wd], axes=([1], [1]))
     return np.rint(acc).astype(np.int64).transpose(1, 0, 2, 3)
 
@@ -616,7 +762,7 @@ def dequantize(acc: np.ndarray, x_scale, w_scale) -> np.ndarray:
 
 
 # ---------------------------------------------------------------------------
-# Tiling (paper silent on padding; reading: zero pad 1, ragged tiles read zeros
+# Tiling (paper silent on padding; reading: zero pad (R-1)/2, ragged tiles read zeros
 # beyond the image and their surplus outputs are dropped -- exact by linearity)
 # ---------------------------------------------------------------------------
 
@@ -625,20 +771,22 @@ def tile_grid(h: int, w: int, m: int = TILE_OUT):
     return -(-h // m), -(-w // m)
 
 
-def gather_tiles(x: np.ndarray, m: int = TILE_OUT) -> np.ndarray:
-    """[N,C,H,W] -> tiles [T, C, m+2, m+2], T = N*th*tw, t = (n*th + ti)*tw + tj.
+def gather_tiles(x: np.ndarray, m: int = TILE_OUT, r: int = KERNEL) -> np.ndarray:
+    """[N,C,H,W] -> tiles [T, C, m+r-1, m+r-1], T = N*th*tw, t = (n*th + ti)*tw + tj.
 
-    Tile (ti,tj) covers input rows m*ti-1 .. m*ti+m and columns m*tj-1 .. m*tj+m.
+    Tile (ti,tj) covers input rows m*ti-pad .. m*ti+m-1+pad and the same columns of tj,
+    pad = (r-1)/2 (r = 3: rows m*ti-1 .. m*ti+m).
     """
     n, c, h, w = x.shape
     th, tw = tile_grid(h, w, m)
-    xp = np.zeros((n, c, m * th + 2, m * tw + 2), dtype=np.int64)
-    xp[:, :, 1 : 1 + h, 1 : 1 + w] = x
-    tiles = np.empty((n, th, tw, c, m + 2, m + 2), dtype=np.int64)
+    pad, ni = (r - 1) // 2, m + r - 1
+    xp = np.zeros((n, c, m * th + 2 * pad, m * tw + 2 * pad), dtype=np.int64)
+    xp[:, :, pad : pad + h, pad : pad + w] = x
+    tiles = np.empty((n, th, tw, c, ni, ni), dtype=np.int64)
     for ti in range(th):
         for tj in range(tw):
-            tiles[:, ti, tj] = xp[:, :, m * ti : m * ti + m + 2, m * tj : m * tj + m + 2]
-    return tiles.reshape(n * th * tw, c, m + 2, m + 2)
+            tiles[:, ti, tj] = xp[:, :, m * ti : m * ti + ni, m * tj : m * tj + ni]
+    return tiles.reshape(n * th * tw, c, ni, ni)
 
 
 def scatter_tiles(o: np.ndarray, n: int, h: int, w: int) -> np.ndarray:
@@ -665,10 +813,10 @@ def _isqrt(n: int) -> int:
 # ---------------------------------------------------------------------------
 
 
-def input_transform(x: np.ndarray, b2: np.ndarray) -> np.ndarray:
-    """V[p,t,c] = sum_ij B2[p,(i,j)] * tile[t,c,i,j]  (B^T x B, additions only)."""
+def input_transform(x: np.ndarray, b2: np.ndarray, r: int = KERNEL) -> np.ndarray:
+    """V[p,t,c] = sum_ij B2[p,(i,j)] * tile[t,c,i,j]  (B^T x B, additions only); r = filter edge."""
     n_in = _isqrt(b2.shape[1])
-    tiles = gather_tiles(x, n_in - 2)
+    tiles = gather_tiles(x, n_in - (r - 1), r)
     t, c = tiles.shape[:2]
     v = b2 @ tiles.reshape(t * c, n_in * n_in).T  # int64, exact
     return v.reshape(b2.shape[0], t, c)
@@ -677,7 +825,7 @@ def input_transform(x: np.ndarray, b2: np.ndarray) -> np.ndarray:
 def filter_transform(w: np.ndarray, g2: np.ndarray) -> np.ndarray:
     """U[p,k,c] = sum_rs G2[p,(r,s)] * w[k,c,r,s]  (G f G^T, additions only)."""
     k, c = w.shape[:2]
-    u = g2 @ np.asarray(w, dtype=np.int64).reshape(k * c, 9).T
+    u = g2 @ np.asarray(w, dtype=np.int64).reshape(k * c, g2.shape[1]).T
     return u.reshape(g2.shape[0], k, c)
 
 
@@ -703,7 +851,7 @@ def conv_exact(x, w, alg="6x6_p88", return_taps=False):
     """Eq. (1) over the integers, no transform-domain rounding: equals ``direct_conv``."""
     b2, g2, a2, den = algorithm(alg)
     n, _, h, wd = x.shape
-    v = input_transform(x, b2)
+    v = input_transform(x, b2, kernel_size(alg))
     u = filter_transform(w, g2)
     m = pointwise_product(v, u)
     acc = output_transform_exact(m, a2, den, n, h, wd)
@@ -742,7 +890,7 @@ def calibrate_act_scales(x_calib: np.ndarray, alg="6x6_p88", qmax: int = QMAX) -
     The paper learns its scales with AdaQuant on ImageNet images; abs-max
     calibration stands in for that.  One scale per multiplication point.
     """
-    v = input_transform(x_calib, algorithm(alg)[0])
+    v = input_transform(x_calib, algorithm(alg)[0], kernel_size(alg))
     mx = np.abs(v).max(axis=(1, 2)).astype(np.float32)
     s = mx / np.float32(qmax)
     return np.where(mx == 0, np.float32(1.0), s).astype(np.float32)
@@ -779,7 +927,7 @@ def conv_requant(x, w, sx_pt, sw_pt, x_scale, w_scale, alg="6x6_p88", qmax=QMAX,
     """
     b2, g2, a2, den = algorithm(alg)
     n, _, h, wd = x.shape
-    v = input_transform(x, b2)
+    v = input_transform(x, b2, kernel_size(alg))
     u = filter_transform(w, g2)
     vq = quantize(v, reciprocal_f32(sx_pt)[:, None, None], qmax)
     uq = quantize(u, reciprocal_f32(sw_pt)[:, :, None], qmax)

@@ -554,3 +554,148 @@ def test_4x4_requant_reduces_to_exact_when_nothing_rounds():
                              np.float32(0.5), alg)
         ref = sfc.dequantize(sfc.direct_conv(x, w), 0.125, np.float32(0.5))
         assert np.allclose(y, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
+
+
+# ---- SFC-6(6x6,5x5), Appendix A ----------------------------------------------
+
+GOLDEN65 = os.path.join(os.path.dirname(__file__), "golden", "sfc6_6x6_5x5_printed.txt")
+
+
+def expected_1d_5tap(den=6):
+    ref = np.zeros((6, 10, 5), dtype=np.int64)
+    for o in range(6):
+        for r in range(5):
+            ref[o, o + r, r] = den
+    return ref
+
+
+def test_5x5_printed_matrices_and_the_unusable_print_of_A():
+    gold = load_golden(GOLDEN65)
+    bt, g, a, den = sfc.sfc6_1d(6, 5)
+    assert den == 6
+    assert np.array_equal(gold["BT"], bt) and np.array_equal(gold["G"], g)
+    printed_a = gold["A_times_6_as_printed"]
+    assert printed_a.shape == (14, 7)  # seven columns for six outputs
+    # neither six-column window of the print satisfies the identity ...
+    for window in (printed_a[:, :6], printed_a[:, 1:]):
+        assert not np.array_equal(bilinear_1d(window, bt, g), expected_1d_5tap())
+    # ... the matrix used here does
+    assert np.array_equal(bilinear_1d(a, bt, g), expected_1d_5tap())
+    # and it keeps what the print gets right: the first six columns of the cyclic rows
+    assert np.array_equal(a[:8], printed_a[:8, :6])
+
+
+def test_5x5_A_is_the_only_matrix_that_fits_the_printed_BT_and_G():
+    # the 14 bilinear forms BT[p,i] G[p,r] are linearly independent, so A is determined
+    bt, g, a, den = sfc.sfc6_1d(6, 5)
+    forms = np.einsum("pi,pr->pir", bt, g).reshape(14, 50).T.astype(np.float64)
+    assert np.linalg.matrix_rank(forms) == 14
+    target = expected_1d_5tap().reshape(6, 50).T.astype(np.float64)
+    solved, *_ = np.linalg.lstsq(forms, target, rcond=None)
+    assert np.allclose(solved, a, atol=1e-9)
+    assert np.allclose(forms @ solved, target, atol=1e-9)
+
+
+def test_5x5_matrices_rederived_equal_the_print():
+    bt, g, a, den = sfc.integrate_1d_5tap()
+    pb, pg, pa, pden = sfc.sfc6_1d(6, 5)
+    assert den == pden
+    assert np.array_equal(bt, pb) and np.array_equal(g, pg) and np.array_equal(a, pa)
+    # rows 0..7 are the rows of SFC-6(6x6,3x3) moved one sample to the right
+    b3 = sfc.sfc6_1d(6)[0]
+    assert np.array_equal(pb[:8, 1:9], b3[:8]) and not pb[:8, [0, 9]].any()
+    for r0, r1, rs in sfc.COMPLEX_GROUPS:
+        assert np.array_equal(pb[rs], pb[r0] + pb[r1]) and np.array_equal(pg[rs], pg[r0] + pg[r1])
+
+
+def test_5x5_1d_brute_force():
+    bt, g, a, den = sfc.sfc6_1d(6, 5)
+    rng = np.random.default_rng(31)
+    for _ in range(50):
+        x = rng.integers(-128, 128, size=10)
+        f = rng.integers(-128, 128, size=5)
+        y = a.T @ ((g @ f) * (bt @ x))
+        brute = [sum(int(x[o + r]) * int(f[r]) for r in range(5)) for o in range(6)]
+        assert np.array_equal(y, den * np.array(brute))
+
+
+def test_5x5_filter_rows_are_the_symbolic_dft_at_s():
+    # G_k = sum_r f_r s^(k (r - 4)) evaluated numerically, against the printed rows
+    g = sfc.sfc6_1d(6, 5)[1]
+    rng = np.random.default_rng(32)
+    f = rng.integers(-128, 128, size=5)
+    u = g @ f
+    for k, (r0, r1, rs) in zip((1, 2), sfc.COMPLEX_GROUPS):
+        want = sum(int(f[r]) * sfc.S_ROOT ** (k * (r - 4)) for r in range(5))
+        assert abs(u[r0] + u[r1] * sfc.S_ROOT - want) < 1e-9
+        assert u[rs] == u[r0] + u[r1]
+    assert u[0] == f.sum() and u[7] == sum(int(f[r]) * (-1) ** r for r in range(5))
+
+
+@pytest.mark.parametrize("alg,points", [("6x6_5x5_p196", 196), ("6x6_5x5_p184", 184)])
+def test_5x5_2d_bilinear_identity_and_counts(alg, points):
+    c = load_golden(GOLDEN65)["counts"]
+    b2, g2, a2, den = sfc.algorithm(alg)
+    assert sfc.tile_out(alg) == 6 and sfc.kernel_size(alg) == 5 and den == 36
+    assert b2.shape == (points, 100) and g2.shape == (points, 25) and a2.shape == (points, 36)
+    t = np.einsum("po,pi,pr->oir", a2, b2, g2).reshape(6, 6, 10, 10, 5, 5)
+    ref = np.zeros_like(t)
+    for o1, o2, r1, r2 in itertools.product(range(6), range(6), range(5), range(5)):
+        ref[o1, o2, o1 + r1, o2 + r2, r1, r2] = den
+    assert np.array_equal(t, ref)
+    assert points == c["nested_multiplications" if points == 196 else "hermitian_multiplications"]
+    assert sfc.multiplications_per_tile(alg) == points
+    if points == 184:
+        direct = sfc.direct_multiplications_per_tile(6, 5)
+        assert direct == c["direct_multiplications"]
+        assert round(10000 * points / direct) == c["complexity_percent_x100"]  # 20.44 %
+        n2 = sfc.algorithm("6x6_5x5_p196")[0]
+        cr = {r for grp in sfc.COMPLEX_GROUPS for r in grp}
+        keep = [14 * p1 + p2 for p1 in range(14) for p2 in range(14) if not (p1 in cr and p2 in cr)]
+        assert len(keep) == 160 and np.array_equal(b2[:160], n2[keep])
+
+
+def test_direct_conv_5x5_brute_force_and_torch():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(33)
+    x = rng.integers(-128, 128, size=(2, 3, 7, 5)).astype(np.int8)
+    w = rng.integers(-128, 128, size=(2, 3, 5, 5)).astype(np.int8)
+    got = sfc.direct_conv(x, w)
+    brute = np.zeros_like(got)
+    for n, k, h, wd in itertools.product(range(2), range(2), range(7), range(5)):
+        acc = 0
+        for c, r, s in itertools.product(range(3), range(5), range(5)):
+            hh, ww = h + r - 2, wd + s - 2
+            if 0 <= hh < 7 and 0 <= ww < 5:
+                acc += int(x[n, c, hh, ww]) * int(w[k, c, r, s])
+        brute[n, k, h, wd] = acc
+    assert np.array_equal(got, brute)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(), padding=2)
+    assert np.array_equal(got, ref.numpy().astype(np.int64))
+
+
+@pytest.mark.parametrize("alg", ["6x6_5x5_p196", "6x6_5x5_p184"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_5x5_exact_sfc_equals_direct_conv(alg, shape):
+    n, c, k, h, w = shape
+    rng = np.random.default_rng(hash(shape) % 2**32 + 3)
+    x = rng.integers(-128, 128, size=(n, c, h, w)).astype(np.int8)
+    wt = rng.integers(-128, 128, size=(k, c, 5, 5)).astype(np.int8)
+    assert np.array_equal(sfc.conv_exact(x, wt, alg), sfc.direct_conv(x, wt))
+
+
+def test_5x5_extreme_values_and_requant_reduction():
+    x = np.full((1, 2, 8, 13), -128, dtype=np.int8)
+    w = np.full((3, 2, 5, 5), -128, dtype=np.int8)
+    w[:, :, ::2, 1::2] = 127
+    for alg in ("6x6_5x5_p196", "6x6_5x5_p184"):
+        assert np.array_equal(sfc.conv_exact(x, w, alg), sfc.direct_conv(x, w))
+    rng = np.random.default_rng(34)
+    x = rng.integers(-1, 2, size=(1, 3, 9, 7)).astype(np.int8)
+    w = rng.integers(-1, 2, size=(4, 3, 5, 5)).astype(np.int8)
+    for alg in ("6x6_5x5_p196", "6x6_5x5_p184"):
+        p = sfc.multiplications_per_tile(alg)
+        y = sfc.conv_requant(x, w, np.ones(p, np.float32), np.ones((p, 4), np.float32), 0.125,
+                             np.float32(0.5), alg)
+        ref = sfc.dequantize(sfc.direct_conv(x, w), 0.125, np.float32(0.5))
+        assert np.allclose(y, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
