@@ -1,9 +1,11 @@
 /*
  * sfc.h -- C ABI of the MI355X (gfx950) library for quantized 3x3 convolution by
- * Symbolic Fourier Convolution, SFC-6(6x6,3x3) and SFC-6(7x7,3x3) (arXiv 2407.02913).
+ * Symbolic Fourier Convolution, SFC-6(6x6,3x3) and SFC-6(7x7,3x3) (arXiv 2407.02913),
+ * with SFC-4(4x4,3x3) and the 5x5-filter algorithm SFC-6(6x6,5x5) beside them.
  *
  * The library computes, for int8 activations x[N,Cin,H,W] and int8 filters
- * w[Cout,Cin,3,3] (stride 1, zero padding 1, cross-correlation),
+ * w[Cout,Cin,R,R] (R = 3, or 5 for the SFC-6(6x6,5x5) algorithms; stride 1, zero padding
+ * (R-1)/2, cross-correlation),
  *
  *      y = A^T [ (G f G^T) . (B^T x B) ] A        summed over Cin      (Eq. 1)
  *
@@ -12,7 +14,8 @@
  * tiles ((M+2)x(M+2) input tiles), M = 6 or 7 -- or 4, with the four-point transforms
  * of SFC-4(4x4,3x3).  Per tile and (Cin,Cout) pair it spends P = 88 / 132 / 46
  * multiplications (Hermitian form, M = 6 / 7 / 4) or P = 100 / 144 / 49 (nested form),
- * Appendix A.
+ * Appendix A.  SFC-6(6x6,5x5) works on 6x6 output tiles (10x10 input tiles) with
+ * P = 184 (Hermitian) or 196 (nested) multiplications instead of 900.
  *
  * Conventions
  *  - "dev" pointers are device (HBM) addresses on the current HIP device, "host"
@@ -57,13 +60,20 @@ typedef enum {
   /* SFC-4(4x4,3x3) (Appendix A, four-point symbolic DFT, s = j): 46 multiplications per
    * 4x4 tile with Hermitian symmetry fully used, 49 in the nested form.  Staged path only. */
   SFC_ALG_4X4_P46 = 4,
-  SFC_ALG_4X4_P49 = 5
+  SFC_ALG_4X4_P49 = 5,
+  /* SFC-6(6x6,5x5) (Appendix A): 5x5 filters w[Cout,Cin,5,5], zero padding 2, 6x6 output
+   * tiles; 184 multiplications per tile in the Hermitian form, 196 in the nested form.
+   * B^T and G are the printed ones; the printed A (seven columns for six outputs) is
+   * replaced by the one matrix that fits them.  Staged path only, W <= 100. */
+  SFC_ALG_6X6_5X5_P184 = 6,
+  SFC_ALG_6X6_5X5_P196 = 7
 } sfc_alg;
 
 typedef enum {
   /* Transform domain kept in exact integers (int16 operands, int32 sums): the
    * result equals direct convolution bit for bit (Sec. 5.1 assumes the
-   * transforms accurate).  int32 sums are guaranteed for Cin <= 404. */
+   * transforms accurate).  int32 sums are guaranteed for Cin <= 404 (3x3 filters) and
+   * Cin <= 145 (5x5 filters). */
   SFC_MODE_EXACT = 0,
   /* Transform-domain operands rounded to int8 with one scale per point for the
    * activations and one per (point, Cout) for the filters (Sec. 5, the
@@ -90,7 +100,7 @@ typedef enum {
 } sfc_path;
 
 typedef struct {
-  int32_t N, Cin, Cout, H, W; /* 3x3 filter, stride 1, zero padding 1 are fixed */
+  int32_t N, Cin, Cout, H, W; /* stride 1; filter size and zero padding follow from alg */
   int32_t alg;                /* sfc_alg */
   int32_t mode;               /* sfc_mode */
   int32_t out;                /* sfc_out */
@@ -111,7 +121,8 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out);
 void sfc_plan_destroy(sfc_plan_t* plan);
 
 /* Sizes the caller must allocate (device bytes) and the derived counts:
- * P = multiplications per tile (88, 100, 132 or 144), tiles = N*ceil(H/M)*ceil(W/M).
+ * P = multiplications per tile (88, 100, 132, 144, 46, 49, 184 or 196),
+ * tiles = N*ceil(H/M)*ceil(W/M).
  * Any output pointer may be NULL. */
 sfc_status sfc_plan_sizes(const sfc_plan_t* plan, size_t* filter_bytes, size_t* workspace_bytes,
                           int32_t* P, int64_t* tiles);
@@ -119,8 +130,8 @@ sfc_status sfc_plan_sizes(const sfc_plan_t* plan, size_t* filter_bytes, size_t* 
 /* Requantized mode: the transform-domain scales of Sec. 5, copied into the plan.
  * sx_host[P]: one activation scale per point (s_Tx).  sw_host[P*Cout], laid out
  * [P][Cout]: one filter scale per point and output channel (s_Tf).  All > 0.
- * Point order, with R = 10 (M = 6), 12 (M = 7) or 7 (M = 4) rows in the printed 1-D
- * matrices: nested form, p = R*p1 + p2 (p1 vertical); Hermitian form, first the nested
+ * Point order, with R = 10 (M = 6), 12 (M = 7), 7 (M = 4) or 14 (5x5 filter) rows in the
+ * printed 1-D matrices: nested form, p = R*p1 + p2 (p1 vertical); Hermitian form, first the nested
  * points that are not complex x complex (R*R - 36 of them, R*R - 9 for M = 4), in that
  * same order, then for (k1,k2) = (1,1),(1,2),(2,1),(2,2) (only (1,1) for M = 4) the six
  * points U0,U1,U0+U1,V0,V1,V0+V1 of the two independent 2-D frequencies.

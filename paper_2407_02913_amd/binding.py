@@ -17,7 +17,9 @@ LIB_PATH = os.path.join(_HERE, "libsfc_hip.so")
 SFC_OK = 0
 STATUS_NAMES = {0: "SFC_OK", 1: "SFC_EINVAL", 2: "SFC_EUNSUPPORTED", 3: "SFC_ENOMEM",
                 4: "SFC_ENOTREADY", 5: "SFC_EHIP"}
-ALG = {"6x6_p88": 0, "6x6_p100": 1, "7x7_p132": 2, "7x7_p144": 3, "4x4_p46": 4, "4x4_p49": 5}
+ALG = {"6x6_p88": 0, "6x6_p100": 1, "7x7_p132": 2, "7x7_p144": 3, "4x4_p46": 4, "4x4_p49": 5,
+       "6x6_5x5_p184": 6, "6x6_5x5_p196": 7}
+KERNEL_SIZE = {name: 5 if "5x5" in name else 3 for name in ALG}  # filter edge R
 MODE = {"exact": 0, "requant": 1}
 OUT = {"f32": 0, "i32": 1, "i8": 2}
 PATH = {"staged": 0, "fused": 1, "single": 2}
@@ -123,6 +125,7 @@ class Plan:
                "sfc_plan_sizes")
         self.filter_bytes, self.workspace_bytes, self.P, self.tiles = fb.value, wb.value, p.value, t.value
         self.mode, self.out = mode, out
+        self.kernel_size = KERNEL_SIZE[alg]
         self._keep = []
 
     def close(self):
@@ -154,7 +157,13 @@ class Plan:
                "sfc_calibrate_act_scales")
         return out
 
+    def _check_weights(self, w_dev):
+        d, r = self.desc, self.kernel_size
+        assert w_dev.element_size() == 1 and w_dev.numel() == d.Cout * d.Cin * r * r, \
+            (tuple(w_dev.shape), (d.Cout, d.Cin, r, r))
+
     def calibrate_filter_scales(self, w_dev, workspace, stream=None) -> np.ndarray:
+        self._check_weights(w_dev)
         out = np.empty((self.P, self.desc.Cout), dtype=np.float32)
         _check(load().sfc_calibrate_filter_scales(self._h, C.c_void_p(w_dev.data_ptr()),
                                                   C.c_void_p(workspace.data_ptr()),
@@ -167,6 +176,7 @@ class Plan:
         need = self.desc.Cout if self.desc.per_channel_wscale else 1
         assert ws.size == need, (ws.size, need)
         assert filter_buf.numel() * filter_buf.element_size() >= self.filter_bytes
+        self._check_weights(w_dev)
         _check(load().sfc_transform_filter(self._h, C.c_void_p(w_dev.data_ptr()), _f32_ptr(ws),
                                            C.c_void_p(filter_buf.data_ptr()), _stream_ptr(stream)),
                "sfc_transform_filter")

@@ -70,7 +70,7 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   *out = nullptr;
   const sfc_conv_desc& d = *desc;
   if (d.N <= 0 || d.Cin <= 0 || d.Cout <= 0 || d.H <= 0 || d.W <= 0) return SFC_EINVAL;
-  if (d.alg < SFC_ALG_6X6_P88 || d.alg > SFC_ALG_4X4_P49) return SFC_EINVAL;
+  if (d.alg < SFC_ALG_6X6_P88 || d.alg > SFC_ALG_6X6_5X5_P196) return SFC_EINVAL;
   if (d.mode != SFC_MODE_EXACT && d.mode != SFC_MODE_REQUANT_I8) return SFC_EINVAL;
   if (d.out != SFC_OUT_F32 && d.out != SFC_OUT_I32 && d.out != SFC_OUT_I8_RELU) return SFC_EINVAL;
   if (d.path != SFC_PATH_STAGED && d.path != SFC_PATH_FUSED && d.path != SFC_PATH_SINGLE)
@@ -99,8 +99,10 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   g.Tp = (int)((T + 15) / 16 * 16);
   g.Cp = (d.Cin + 63) / 64 * 64;
   g.Kp = (d.Cout + 15) / 16 * 16;
-  static const int kPoints[6] = {88, 100, 132, 144, 46, 49};
+  static const int kPoints[8] = {88, 100, 132, 144, 46, 49, 184, 196};
   g.P = kPoints[d.alg];
+  // the 5x5 algorithms stage ten input rows of 64 channels in 64 KB of LDS
+  if (d.alg >= SFC_ALG_6X6_5X5_P184 && d.W > 100) return SFC_EUNSUPPORTED;
   g.qmax = (float)((1 << ((d.transform_bits ? d.transform_bits : 8) - 1)) - 1);
 
   if (d.path == SFC_PATH_FUSED && !sfc::fused_quad_supported(g)) return SFC_EUNSUPPORTED;
@@ -218,7 +220,8 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
   float* wscale = table(plan->off_wscale);
   for (int k = 0; k < g.Kp; ++k)
     wscale[k] = k < g.Cout ? wscale_host[plan->d.per_channel_wscale ? k : 0] : 0.0f;
-  const double den = g.alg > 3 ? 16.0 : 36.0;  // the output transform yields den * y
+  // the output transform yields den * y
+  const double den = (g.alg == SFC_ALG_4X4_P46 || g.alg == SFC_ALG_4X4_P49) ? 16.0 : 36.0;
   for (int p = 0; p < g.P; ++p) {
     inv_sx[p] = requant ? 1.0f / plan->sx[p] : 1.0f;
     for (int k = 0; k < g.Kp; ++k) {

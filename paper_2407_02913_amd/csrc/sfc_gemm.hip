@@ -225,7 +225,7 @@ __global__ __launch_bounds__(256) void output_sums_pairs_kernel(const int32_t* _
                                                                 float x_scale, float inv_y,
                                                                 void* __restrict__ y, Geometry g) {
   using Tr = AlgTraits<ALG>;
-  constexpr int P = Tr::P, Mo = Tr::M;
+  constexpr int Mo = Tr::M;
   const int kquads = g.Kp >> 2;
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;  // (tile block, quad, 64)
   const long long block = idx >> 6;
@@ -282,8 +282,9 @@ static hipError_t launch_sums_pairs(int out, const Geometry& g, const int32_t* M
 template <int ALG, int OUT, bool VEC2>
 static hipError_t launch_sums_impl(const Geometry& g, const int32_t* M, const FilterViews& f,
                                    float x_scale, float inv_y, void* y, hipStream_t s) {
-  // the 7x7 forms carry 10x7 partial outputs per pair: 8 waves with 256 registers each
-  constexpr int NW = AlgTraits<ALG>::M == 6 ? 16 : 8;
+  // the 7x7 forms carry 10x7 partial outputs per pair, the 5x5-filter forms 12x6: 8 waves
+  // with 256 registers each
+  constexpr int NW = AlgTraits<ALG>::NC == 8 ? 16 : 8;
   const dim3 grid((unsigned)(g.Tp / 16), (unsigned)((g.Cout + 4 * NW - 1) / (4 * NW)));
   hipLaunchKernelGGL((output_sums_kernel<ALG, OUT, VEC2, NW>), grid, dim3(NW * 64), 0, s, M,
                      f.dequant, x_scale, inv_y, y, g);
@@ -316,6 +317,8 @@ hipError_t launch_output_sums(int out, const Geometry& g, const int32_t* M, cons
     case 3: return launch_sums_alg<3>(out, g, M, f, x_scale, inv_y, y, s);
     case 4: return launch_sums_pairs<4>(out, g, M, f, x_scale, inv_y, y, s);
     case 5: return launch_sums_pairs<5>(out, g, M, f, x_scale, inv_y, y, s);
+    case 6: return launch_sums_alg<6>(out, g, M, f, x_scale, inv_y, y, s);
+    case 7: return launch_sums_alg<7>(out, g, M, f, x_scale, inv_y, y, s);
   }
   return hipErrorInvalidValue;
 }

@@ -9,8 +9,8 @@ namespace sfc {
 // Everything a kernel needs to know about one convolution, by value.
 struct Geometry {
   int N, Cin, Cout, H, W;
-  int alg;        // 0: 6x6 / 88 points, 1: 6x6 / 100, 2: 7x7 / 132, 3: 7x7 / 144
-  int th, tw;     // tile grid per image: ceil(H/M), ceil(W/M), M = 6 or 7 outputs per tile edge
+  int alg;        // sfc_alg: 0..3 SFC-6 with 6x6 / 7x7 tiles, 4..5 SFC-4, 6..7 SFC-6(6x6,5x5)
+  int th, tw;     // tile grid per image: ceil(H/M), ceil(W/M), M outputs per tile edge
   int strips;     // N * th: one strip = one row of tiles of one image
   int T;          // tiles = strips * tw
   int Tp;         // T rounded up to 16 (row padding of V and M)

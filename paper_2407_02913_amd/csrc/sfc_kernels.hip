@@ -1,4 +1,4 @@
-// HIP kernels for SFC-6(6x6,3x3) on gfx950 (wave64, int8 MFMA).
+// HIP kernels of the staged path on gfx950 (wave64), every algorithm of sfc_points.hpp.
 //
 //   filter_transform_kernel   U = G f G^T               (once per layer)
 //   input_transform_kernel    V = B^T x B               (NCHW int8 -> [P][Tp][Cp])
@@ -26,19 +26,22 @@ __device__ __forceinline__ int quantize_i8(int v, float inv, float qmax) {
   return __float_as_int(t) - 0x4B400000;
 }
 
-// 3x3 filter taps of one (k, c) -> NC x NC components (rows, then columns)
+// R x R filter taps of one (k, c) -> NC x NC components (rows, then columns)
 template <int ALG>
 __device__ __forceinline__ void filter_components(
-    const int (&f)[3][3], int (&comp)[AlgTraits<ALG>::NC][AlgTraits<ALG>::NC]) {
-  constexpr int NC = AlgTraits<ALG>::NC;
-  int half[3][NC];
+    const int (&f)[AlgTraits<ALG>::R][AlgTraits<ALG>::R],
+    int (&comp)[AlgTraits<ALG>::NC][AlgTraits<ALG>::NC]) {
+  constexpr int NC = AlgTraits<ALG>::NC, R = AlgTraits<ALG>::R;
+  int half[R][NC];
 #pragma unroll
-  for (int r = 0; r < 3; ++r) fwd_filter<NC>(f[r], half[r]);
+  for (int r = 0; r < R; ++r) fwd_filter<R, NC>(f[r], half[r]);
 #pragma unroll
   for (int b = 0; b < NC; ++b) {
-    const int col[3] = {half[0][b], half[1][b], half[2][b]};
+    int col[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) col[r] = half[r][b];
     int cc[NC];
-    fwd_filter<NC>(col, cc);
+    fwd_filter<R, NC>(col, cc);
 #pragma unroll
     for (int a = 0; a < NC; ++a) comp[a][b] = cc[a];
   }
@@ -55,13 +58,14 @@ __global__ __launch_bounds__(256) void filter_transform_kernel(const int8_t* __r
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   const int k = blockIdx.y;
   if (c >= g.Cp) return;
-  int f[3][3];
+  constexpr int R = AlgTraits<ALG>::R;
+  int f[R][R];
   const bool valid = (k < g.Cout) && (c < g.Cin);
 #pragma unroll
-  for (int r = 0; r < 3; ++r)
+  for (int r = 0; r < R; ++r)
 #pragma unroll
-    for (int s = 0; s < 3; ++s)
-      f[r][s] = valid ? (int)w[((size_t)k * g.Cin + c) * 9 + r * 3 + s] : 0;
+    for (int s = 0; s < R; ++s)
+      f[r][s] = valid ? (int)w[((size_t)k * g.Cin + c) * (R * R) + r * R + s] : 0;
   int comp[AlgTraits<ALG>::NC][AlgTraits<ALG>::NC];
   filter_components<ALG>(f, comp);
   for_each_point<ALG>(comp, [&](int p, int v) {
@@ -84,11 +88,12 @@ __global__ __launch_bounds__(256) void filter_absmax_kernel(const int8_t* __rest
   for (int i = threadIdx.x; i < AlgTraits<ALG>::P; i += blockDim.x) smax[i] = 0;
   __syncthreads();
   for (int c = threadIdx.x; c < g.Cin; c += blockDim.x) {
-    int f[3][3];
+    constexpr int R = AlgTraits<ALG>::R;
+    int f[R][R];
 #pragma unroll
-    for (int r = 0; r < 3; ++r)
+    for (int r = 0; r < R; ++r)
 #pragma unroll
-      for (int s = 0; s < 3; ++s) f[r][s] = (int)w[((size_t)k * g.Cin + c) * 9 + r * 3 + s];
+      for (int s = 0; s < R; ++s) f[r][s] = (int)w[((size_t)k * g.Cin + c) * (R * R) + r * R + s];
     int comp[AlgTraits<ALG>::NC][AlgTraits<ALG>::NC];
     filter_components<ALG>(f, comp);
     for_each_point<ALG>(comp, [&](int p, int v) { atomicMax(&smax[p], v < 0 ? -v : v); });
@@ -102,15 +107,15 @@ __global__ __launch_bounds__(256) void filter_absmax_kernel(const int8_t* __rest
 // input transform
 //
 // One workgroup owns S consecutive strips (a strip = one row of tiles of one
-// image, i.e. the M+2 input rows M*ti-1 .. M*ti+M) for 64 channels.  The input
-// rows of a (strip, channel) are one contiguous run of (M+2)*W bytes in NCHW, so the
+// image, i.e. the NI = M+R-1 input rows from M*ti-PAD on) for 64 channels.  The input
+// rows of a (strip, channel) are one contiguous run of NI*W bytes in NCHW, so the
 // workgroup copies them to LDS with coalesced loads, then each thread transforms
 // one (tile, channel) patch with lanes running along channels, which makes the
 // V stores contiguous.  MODE: 0 int16 out, 1 int8 requantized out, 2 abs-max.
 // ---------------------------------------------------------------------------
 struct StripParams {
   int S;         // strips per workgroup
-  int cs;        // LDS bytes per (strip, channel): (M+2)*W padded to 4*(odd)
+  int cs;        // LDS bytes per (strip, channel): NI*W padded to 4*(odd)
   int vec4;      // 1: W % 4 == 0, rows are dword aligned
 };
 
@@ -122,7 +127,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
                                                               Geometry g, StripParams sp) {
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int P = AlgTraits<ALG>::P, M = AlgTraits<ALG>::M, NI = AlgTraits<ALG>::NI,
-                NC = AlgTraits<ALG>::NC;
+                NC = AlgTraits<ALG>::NC, PAD = AlgTraits<ALG>::PAD;
   __shared__ int smax[MODE == 2 ? P : 1];
   if constexpr (MODE == 2) {
     for (int i = threadIdx.x; i < P; i += blockDim.x) smax[i] = 0;
@@ -145,7 +150,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
       if (strip < g.strips && c0 + c < g.Cin) {
         const int n = strip / g.th, ti = strip - n * g.th;
         const int row = (4 * e) / W;
-        const int h = M * ti - 1 + row;
+        const int h = M * ti - PAD + row;
         if (h >= 0 && h < H) {
           const size_t base = (((size_t)n * g.Cin + c0 + c) * H + h) * W + (4 * e - row * W);
           val = *(const unsigned*)(x + base);
@@ -164,7 +169,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
       if (strip < g.strips && c0 + c < g.Cin) {
         const int n = strip / g.th, ti = strip - n * g.th;
         const int row = e / W;
-        const int h = M * ti - 1 + row;
+        const int h = M * ti - PAD + row;
         if (h >= 0 && h < H) {
           const size_t base = (((size_t)n * g.Cin + c0 + c) * H + h) * W + (e - row * W);
           val = (unsigned char)x[base];
@@ -191,7 +196,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
       int row[NI];
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
-        const int col = M * tj - 1 + j;
+        const int col = M * tj - PAD + j;
         row[j] = (col >= 0 && col < W) ? (int)src[i * W + col] : 0;
       }
       fwd_input<NI, NC>(row, half[i]);  // horizontal axis: half[i][b]
@@ -323,7 +328,7 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __
 
 static StripParams strip_params(const Geometry& g) {
   StripParams sp;
-  int seg4 = ((alg_tile(g.alg) + 2) * g.W + 3) / 4;
+  int seg4 = ((alg_tile(g.alg) + alg_taps(g.alg) - 1) * g.W + 3) / 4;
   if ((seg4 & 1) == 0) seg4 += 1;  // odd dword stride: lanes along channels hit distinct banks
   sp.cs = 4 * seg4;
   sp.vec4 = (g.W % 4 == 0) ? 1 : 0;
@@ -356,6 +361,8 @@ static hipError_t launch_input_alg(const Geometry& g, const int8_t* x, void* V, 
     case 3: return launch_input_impl<3, MODE>(g, x, V, inv_sx, maxima, s);
     case 4: return launch_input_impl<4, MODE>(g, x, V, inv_sx, maxima, s);
     case 5: return launch_input_impl<5, MODE>(g, x, V, inv_sx, maxima, s);
+    case 6: return launch_input_impl<6, MODE>(g, x, V, inv_sx, maxima, s);
+    case 7: return launch_input_impl<7, MODE>(g, x, V, inv_sx, maxima, s);
   }
   return hipErrorInvalidValue;
 }
@@ -388,6 +395,8 @@ hipError_t launch_filter_absmax(const Geometry& g, const int8_t* w, int32_t* max
     case 3: SFC_LAUNCH_FMAX(3); break;
     case 4: SFC_LAUNCH_FMAX(4); break;
     case 5: SFC_LAUNCH_FMAX(5); break;
+    case 6: SFC_LAUNCH_FMAX(6); break;
+    case 7: SFC_LAUNCH_FMAX(7); break;
     default: return hipErrorInvalidValue;
   }
 #undef SFC_LAUNCH_FMAX
@@ -412,6 +421,8 @@ hipError_t launch_filter_transform(int mode, const Geometry& g, const int8_t* w,
     case 3: SFC_LAUNCH_FT(3); break;
     case 4: SFC_LAUNCH_FT(4); break;
     case 5: SFC_LAUNCH_FT(5); break;
+    case 6: SFC_LAUNCH_FT(6); break;
+    case 7: SFC_LAUNCH_FT(7); break;
     default: return hipErrorInvalidValue;
   }
 #undef SFC_LAUNCH_FT
@@ -455,6 +466,8 @@ hipError_t launch_output_transform(int mode, int out, const Geometry& g, const i
     case 3: return launch_output_alg<3>(mode, out, g, M, f, x_scale, inv_y, y, s);
     case 4: return launch_output_alg<4>(mode, out, g, M, f, x_scale, inv_y, y, s);
     case 5: return launch_output_alg<5>(mode, out, g, M, f, x_scale, inv_y, y, s);
+    case 6: return launch_output_alg<6>(mode, out, g, M, f, x_scale, inv_y, y, s);
+    case 7: return launch_output_alg<7>(mode, out, g, M, f, x_scale, inv_y, y, s);
   }
   return hipErrorInvalidValue;
 }

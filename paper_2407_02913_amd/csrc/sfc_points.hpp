@@ -1,7 +1,8 @@
-// Add networks of SFC-6(6x6,3x3) and SFC-6(7x7,3x3): forward transforms to the
-// multiplication points and the output transform back, as straight-line code.
+// Add networks of SFC-6(6x6,3x3), SFC-6(7x7,3x3), SFC-4(4x4,3x3) and SFC-6(6x6,5x5):
+// forward transforms to the multiplication points and the output transform back, as
+// straight-line code.
 //
-// A 1-D signal of M+2 samples (M = 6 or 7 outputs) becomes NC "components"
+// 3x3 filters: a 1-D signal of M+2 samples (M = 6 or 7 outputs) becomes NC "components"
 // (Sec. 4.1-4.2):
 //   c0  X0            (real, k = 0)
 //   c1  X1.a0   c2  X1.a1     X1 = a0 + a1 s,  s = exp(j pi/3), s^2 = s - 1
@@ -14,6 +15,13 @@
 // The 3-multiplication product rule (Eq. DFT6M) adds a row a0 + a1 per complex
 // point, giving the NR = NC + 2 rows of Appendix A's B^T and G:
 //   r0=c0 r1=c1 r2=c2 r3=c1+c2 r4=c3 r5=c4 r6=c3+c4 r7=c5 r8=c6 r9=c7 (r10=c8 r11=c9).
+// SFC-6(6x6,5x5) (Appendix A): ten samples, the symbolic DFT-6 works on x2..x7, the filter's
+// as G_k = sum_r f_r s^(k (r - 4)); six corrections (wanted sample minus the one the cyclic
+// convolution supplies, times one tap):
+//   c6  x0 - x6 with f0 -> output 0     c7  x1 - x7 with f0 -> output 1     c8  x1 - x7 with f1 -> output 0
+//   c9  x8 - x2 with f3 -> output 5     c10 x8 - x2 with f4 -> output 4     c11 x9 - x3 with f4 -> output 5
+// With this alignment the inverse symbolic DFT delivers the cyclic result rotated by one
+// position.  NC = 12 components, NR = 14 rows, 196 nested / 184 Hermitian points.
 // In 2-D the components form an NC x NC array C[a][b] (a: vertical axis).
 //   nested   : every (r_a, r_b) pair, NR^2 points (100 / 144).
 //   Hermitian: the pairs that are not complex x complex, then for each pair of
@@ -38,15 +46,18 @@ namespace sfc {
 // V = (a00 + a11) + (a10 - a01) s, each as (x0, x1, x0 + x1): 46 points instead of 49.
 //
 // ALG: 0 = 6x6 Hermitian (88), 1 = 6x6 nested (100), 2 = 7x7 Hermitian (132), 3 = 7x7 nested (144),
-//      4 = 4x4 Hermitian (46), 5 = 4x4 nested (49)
+//      4 = 4x4 Hermitian (46), 5 = 4x4 nested (49), all for 3x3 filters;
+//      6 = 6x6 outputs with a 5x5 filter, Hermitian (184), 7 = the same, nested (196)
 template <int ALG>
 struct AlgTraits {
-  static_assert(ALG >= 0 && ALG < 6, "unknown algorithm");
-  static constexpr int kFamily = ALG < 4 ? 6 : 4;  // points of the symbolic DFT
-  static constexpr bool kHermitian = (ALG == 0 || ALG == 2 || ALG == 4);
-  static constexpr int M = ALG < 2 ? 6 : ALG < 4 ? 7 : 4;  // outputs per tile edge
-  static constexpr int NI = M + 2;                         // input samples per tile edge
-  static constexpr int NC = ALG < 2 ? 8 : ALG < 4 ? 10 : 6;  // components per axis
+  static_assert(ALG >= 0 && ALG < 8, "unknown algorithm");
+  static constexpr int kFamily = (ALG < 4 || ALG >= 6) ? 6 : 4;  // points of the symbolic DFT
+  static constexpr bool kHermitian = ALG % 2 == 0;
+  static constexpr int M = ALG < 2 ? 6 : ALG < 4 ? 7 : ALG < 6 ? 4 : 6;  // outputs per tile edge
+  static constexpr int R = ALG < 6 ? 3 : 5;                              // filter taps per axis
+  static constexpr int PAD = (R - 1) / 2;                                // zero padding
+  static constexpr int NI = M + R - 1;                                   // input samples per tile edge
+  static constexpr int NC = ALG < 2 ? 8 : ALG < 4 ? 10 : ALG < 6 ? 6 : 12;  // components per axis
   // rows of the printed 1-D matrices: one more than components per complex point
   static constexpr int NR = kFamily == 6 ? NC + 2 : NC + 1;
   static constexpr int NREAL = kFamily == 6 ? NR - 6 : NR - 3;  // rows outside a complex point
@@ -54,11 +65,13 @@ struct AlgTraits {
   static constexpr int kDen = kFamily == 6 ? 36 : 16;  // the output transform yields kDen * y
 };
 
-constexpr int kNumAlgs = 6;
+constexpr int kNumAlgs = 8;
 __host__ __device__ constexpr int alg_points(int alg) {
-  return alg == 0 ? 88 : alg == 1 ? 100 : alg == 2 ? 132 : alg == 3 ? 144 : alg == 4 ? 46 : 49;
+  return alg == 0 ? 88 : alg == 1 ? 100 : alg == 2 ? 132 : alg == 3 ? 144 : alg == 4 ? 46
+       : alg == 5 ? 49 : alg == 6 ? 184 : 196;
 }
-__host__ __device__ constexpr int alg_tile(int alg) { return alg < 2 ? 6 : alg < 4 ? 7 : 4; }
+__host__ __device__ constexpr int alg_tile(int alg) { return alg < 2 ? 6 : alg < 4 ? 7 : alg < 6 ? 4 : 6; }
+__host__ __device__ constexpr int alg_taps(int alg) { return alg < 6 ? 3 : 5; }
 
 // ---- row bookkeeping ----------------------------------------------------------
 
@@ -124,11 +137,29 @@ struct Order {
 
 // ---- forward, 1-D ----------------------------------------------------------
 
-// M+2 samples -> NC components (14 additions for the symbolic DFT-6 of the inner
+// NI samples -> NC components (14 additions for the symbolic DFT-6 of the inner
 // six samples, one per correction input).
 template <int NI, int NC, typename T>
 SFC_HD void fwd_input(const T (&x)[NI], T (&c)[NC]) {
-  if constexpr (NI == 6) {
+  if constexpr (NC == 12) {
+    // 5-tap filter: ten samples, the inner six are x2..x7
+    static_assert(NI == 10, "SFC-6(6,5) takes ten samples");
+    const T e0 = x[2] + x[5], e1 = x[3] + x[6], e2 = x[4] + x[7];
+    const T d0 = x[2] - x[5], d1 = x[3] - x[6], d2 = x[4] - x[7];
+    c[0] = e0 + e1 + e2;
+    c[1] = d0 + d1;
+    c[2] = -d1 - d2;
+    c[3] = e0 - e2;
+    c[4] = e2 - e1;
+    c[5] = d0 - d1 + d2;
+    c[6] = x[0] - x[6];
+    c[7] = x[1] - x[7];
+    c[8] = c[7];
+    c[9] = x[8] - x[2];
+    c[10] = c[9];
+    c[11] = x[9] - x[3];
+    return;
+  } else if constexpr (NI == 6) {
     // SFC-4: 6 samples -> 6 components, 8 additions
     const T s02 = x[1] + x[3], s13 = x[2] + x[4];
     c[0] = s02 + s13;
@@ -156,10 +187,26 @@ SFC_HD void fwd_input(const T (&x)[NI], T (&c)[NC]) {
   }
 }
 
-// Three filter taps -> NC components (rows of Appendix A's G without the sum rows).
-template <int NC, typename T>
-SFC_HD void fwd_filter(const T (&f)[3], T (&c)[NC]) {
-  if constexpr (NC == 6) {
+// R filter taps -> NC components (rows of Appendix A's G without the sum rows).
+template <int R, int NC, typename T>
+SFC_HD void fwd_filter(const T (&f)[R], T (&c)[NC]) {
+  if constexpr (NC == 12) {
+    static_assert(R == 5, "SFC-6(6,5) takes five taps");
+    const T p = f[3] + f[4], q = f[0] + f[1];
+    c[0] = q + f[2] + p;
+    c[1] = p - q;
+    c[2] = f[0] - f[2] - f[3];
+    c[3] = f[1] - f[2] + f[4];
+    c[4] = f[2] - f[0] - f[3];
+    c[5] = f[0] - f[1] + f[2] - f[3] + f[4];
+    c[6] = f[0];
+    c[7] = f[0];
+    c[8] = f[1];
+    c[9] = f[3];
+    c[10] = f[4];
+    c[11] = f[4];
+    return;
+  } else if constexpr (NC == 6) {
     // SFC-4 (rows of Appendix A's G without the sum row)
     const T s = f[0] + f[2];
     c[0] = s + f[1];
@@ -315,8 +362,11 @@ SFC_HD void hermitian_collapse(const T (&m)[6], T& o00, T& o10, T& o01, T& o11) 
 // NC components -> M outputs, times 6 (the inverse symbolic DFT-6 through its
 // DFT-2 x DFT-3 structure, plus the correction products with weight 6).  For
 // M = 7 the seventh output is the cyclic output 0 with its own two corrections.
+// For the 5-tap form the cyclic result arrives rotated by one position and six
+// corrections are added.
+SFC_HD constexpr int inv_count(int nc) { return nc == 10 ? 7 : 6; }
 template <int NC, typename T>
-SFC_HD void inv_outputs(const T (&c)[NC], T (&y)[NC - 2 - (NC == 10 ? 1 : 0)]) {
+SFC_HD void inv_outputs(const T (&c)[NC], T (&y)[inv_count(NC)]) {
   // even harmonics k = 0, 2 repeat with period 3; odd harmonics k = 1, 3 flip sign
   const T t = c[0] - c[3];
   const T e0 = t - c[4] - c[4];
@@ -325,6 +375,15 @@ SFC_HD void inv_outputs(const T (&c)[NC], T (&y)[NC - 2 - (NC == 10 ? 1 : 0)]) {
   const T d0 = c[1] - c[2] - c[5];
   const T d1 = c[5] - c[1] - c[2] - c[2];
   const T d2 = -c[1] - c[1] - c[2] - c[5];
+  if constexpr (NC == 12) {
+    y[0] = e1 + d1 + T(6) * (c[6] + c[8]);
+    y[1] = e2 + d2 + T(6) * c[7];
+    y[2] = e0 - d0;
+    y[3] = e1 - d1;
+    y[4] = e2 - d2 + T(6) * c[10];
+    y[5] = e0 + d0 + T(6) * (c[9] + c[11]);
+    return;
+  }
   const T y0 = e0 + d0;
   y[0] = y0 + T(6) * c[6];
   y[1] = e1 + d1;

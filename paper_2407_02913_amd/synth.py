@@ -73,17 +73,17 @@ def weights(shape, dist: str, rng: np.random.Generator) -> np.ndarray:
     raise ValueError(dist)
 
 
-def make_layer(shape: LayerShape, batch: int | None = None, extra: int = 0):
+def make_layer(shape: LayerShape, batch: int | None = None, extra: int = 0, kernel: int = 3):
     """Draw one layer's inputs.
 
-    Returns a dict with ``x`` int8 [N,Cin,H,W], ``w`` int8 [Cout,Cin,3,3],
+    Returns a dict with ``x`` int8 [N,Cin,H,W], ``w`` int8 [Cout,Cin,kernel,kernel],
     ``x_scale`` (float), ``w_scale`` float32 [Cout] or [1], and ``x_calib``, a
     second activation tensor (4 images, different seed) for scale calibration.
     ``batch`` overrides N (for bounded CPU samples of the same workload).
     """
     n = shape.N if batch is None else batch
     x = activations((n, shape.Cin, shape.H, shape.W), shape.dist, _rng(shape.cfg, 0, extra))
-    w = weights((shape.Cout, shape.Cin, 3, 3), shape.dist, _rng(shape.cfg, 1, extra))
+    w = weights((shape.Cout, shape.Cin, kernel, kernel), shape.dist, _rng(shape.cfg, 1, extra))
     if shape.per_channel_wscale:
         ws = _rng(shape.cfg, 2, extra).uniform(0.005, 0.02, size=shape.Cout).astype(np.float32)
     else:

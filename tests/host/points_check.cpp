@@ -1,9 +1,9 @@
 // Host-side dump of the linear maps realized by the kernels' add networks
 // (sfc_points.hpp), so that a CPU test can compare them with the oracle's
 // matrices.  Prints, for every ALG (0: 6x6/88, 1: 6x6/100, 2: 7x7/132, 3: 7x7/144,
-// 4: 4x4/46, 5: 4x4/49):
+// 4: 4x4/46, 5: 4x4/49, 6: 6x6 with 5x5 filter/184, 7: the same/196):
 //   B <alg> <p> <NI*NI ints>   input transform row p  (impulse responses)
-//   G <alg> <p> <9 ints>       filter transform row p
+//   G <alg> <p> <R*R ints>     filter transform row p
 //   A <alg> <p> <M*M ints>     output transform row p (times 36; times 16 for 4x4)
 #include <cmath>
 #include <cstdio>
@@ -16,8 +16,8 @@ using namespace sfc;
 template <int ALG>
 void dump() {
   using Tr = AlgTraits<ALG>;
-  constexpr int P = Tr::P, NI = Tr::NI, NC = Tr::NC, M = Tr::M;
-  std::vector<std::vector<int>> B(P, std::vector<int>(NI * NI)), G(P, std::vector<int>(9)),
+  constexpr int P = Tr::P, NI = Tr::NI, NC = Tr::NC, M = Tr::M, R = Tr::R;
+  std::vector<std::vector<int>> B(P, std::vector<int>(NI * NI)), G(P, std::vector<int>(R * R)),
       A(P, std::vector<int>(M * M));
   for (int i = 0; i < NI; ++i)
     for (int j = 0; j < NI; ++j) {
@@ -33,18 +33,19 @@ void dump() {
       }
       for_each_point<ALG>(comp, [&](int p, int v) { B[p][i * NI + j] = v; });
     }
-  for (int i = 0; i < 3; ++i)
-    for (int j = 0; j < 3; ++j) {
-      int f[3][3] = {};
+  for (int i = 0; i < R; ++i)
+    for (int j = 0; j < R; ++j) {
+      int f[R][R] = {};
       f[i][j] = 1;
-      int half[3][NC], comp[NC][NC];
-      for (int r = 0; r < 3; ++r) fwd_filter<NC>(f[r], half[r]);
+      int half[R][NC], comp[NC][NC];
+      for (int r = 0; r < R; ++r) fwd_filter<R, NC>(f[r], half[r]);
       for (int b = 0; b < NC; ++b) {
-        int col[3] = {half[0][b], half[1][b], half[2][b]}, cc[NC];
-        fwd_filter<NC>(col, cc);
+        int col[R], cc[NC];
+        for (int r = 0; r < R; ++r) col[r] = half[r][b];
+        fwd_filter<R, NC>(col, cc);
         for (int a = 0; a < NC; ++a) comp[a][b] = cc[a];
       }
-      for_each_point<ALG>(comp, [&](int p, int v) { G[p][i * 3 + j] = v; });
+      for_each_point<ALG>(comp, [&](int p, int v) { G[p][i * R + j] = v; });
     }
   for (int q = 0; q < P; ++q) {
     float out[M][M];
@@ -69,5 +70,7 @@ int main() {
   dump<3>();
   dump<4>();
   dump<5>();
+  dump<6>();
+  dump<7>();
   return 0;
 }

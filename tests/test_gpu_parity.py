@@ -32,11 +32,11 @@ def binding():
     return b
 
 
-def uniform_case(shape, seed):
+def uniform_case(shape, seed, r=3):
     n, c, k, h, w = shape
     rng = np.random.default_rng(seed)
     x = rng.integers(-128, 128, size=(n, c, h, w)).astype(np.int8)
-    wt = rng.integers(-128, 128, size=(k, c, 3, 3)).astype(np.int8)
+    wt = rng.integers(-128, 128, size=(k, c, r, r)).astype(np.int8)
     ws = rng.uniform(0.005, 0.02, size=k).astype(np.float32)
     return x, wt, 0.02, ws
 
@@ -138,6 +138,95 @@ def test_gpu_calibration_matches_oracle(binding, alg):
     sx2 = plan.calibrate_act_scales(xd[:2].contiguous(), wbuf)
     assert np.array_equal(sx2, oracle.calibrate_act_scales(d["x"][:2], alg))
     plan.close()
+
+
+ALGS_5X5 = ["6x6_5x5_p184", "6x6_5x5_p196"]  # SFC-6(6x6,5x5), Appendix A: staged path
+
+
+@pytest.mark.parametrize("alg", ALGS_5X5)
+@pytest.mark.parametrize("shape", SMALL_SHAPES)
+def test_5x5_exact_mode_taps_and_sums_bit_exact(binding, shape, alg):
+    x, w, xs, ws = uniform_case(shape, 1300 + len(alg) + sum(shape), r=5)
+    print("case 5x5 exact", shape, alg, flush=True)
+    acc_ref, taps_ref = oracle.conv_exact(x, w, alg, return_taps=True)
+    assert np.array_equal(acc_ref, oracle.direct_conv(x, w))
+    acc, taps = binding.conv2d(x, w, xs, ws, mode="exact", alg=alg, out="i32", return_taps=True)
+    for name in ("V", "U", "M"):
+        assert np.array_equal(taps[name].astype(np.int64), taps_ref[name]), name
+    assert np.array_equal(acc.astype(np.int64), acc_ref)
+    y = binding.conv2d(x, w, xs, ws, mode="exact", alg=alg, out="f32")
+    assert rel_err(y, oracle.dequantize(acc_ref, xs, ws)) <= F32_TOL
+
+
+@pytest.mark.parametrize("alg", ALGS_5X5)
+@pytest.mark.parametrize("shape", SMALL_SHAPES)
+def test_5x5_requant_mode_taps_bit_exact_and_output_close(binding, shape, alg):
+    x, w, xs, ws = uniform_case(shape, 1400 + len(alg) + sum(shape), r=5)
+    print("case 5x5 requant", shape, alg, flush=True)
+    xc, _, _, _ = uniform_case(shape, 1500 + sum(shape), r=5)
+    sx = oracle.calibrate_act_scales(xc // 2, alg)
+    sw = oracle.calibrate_filter_scales(w, alg)
+    y_ref, taps_ref = oracle.conv_requant(x, w, sx, sw, xs, ws, alg, return_taps=True)
+    y, taps = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, sx=sx, sw=sw, return_taps=True)
+    for name in ("V", "U", "M"):
+        assert np.array_equal(taps[name].astype(np.int64), taps_ref[name]), name
+    if x.size > 1:
+        assert np.abs(taps["V"]).max() == 127  # the clamp was exercised
+    assert rel_err(y, y_ref) <= F32_TOL
+
+
+@pytest.mark.parametrize("alg", ALGS_5X5)
+def test_5x5_calibration_int8_output_and_limits(binding, alg):
+    """The library's abs-max calibration against the oracle's, the int8 + ReLU epilogue with
+    4-bit and 8-bit transform domains, and what the 5x5 forms do not take."""
+    import torch
+
+    shape = (4, 24, 20, 14, 10)
+    d = synth.make_layer(synth.LayerShape("cal5", *shape, "relu", True, 2), kernel=5)
+    print("case 5x5 calibration", alg, flush=True)
+    for bits in (8, 4):
+        qmax = 2 ** (bits - 1) - 1
+        plan = binding.Plan(*shape, alg=alg, mode="requant", transform_bits=bits)
+        wbuf = binding.device_buffer(plan.workspace_bytes)
+        sx = plan.calibrate_act_scales(torch.from_numpy(d["x_calib"]).cuda(), wbuf)
+        sw = plan.calibrate_filter_scales(torch.from_numpy(d["w"]).cuda(), wbuf)
+        plan.close()
+        assert np.array_equal(sx, oracle.calibrate_act_scales(d["x_calib"], alg, qmax=qmax))
+        assert np.array_equal(sw, oracle.calibrate_filter_scales(d["w"], alg, qmax=qmax))
+        y_ref = oracle.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"], alg, qmax=qmax)
+        y = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg,
+                           sx=sx, sw=sw, transform_bits=bits)
+        assert rel_err(y, y_ref) <= F32_TOL
+        y_scale = float(np.float32(max(y_ref.max(), 1e-6) / 127.0 * 0.8))
+        y8 = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg,
+                            out="i8", sx=sx, sw=sw, y_scale=y_scale, transform_bits=bits)
+        assert check_i8_against_oracle(y8, y_ref, y_scale) < 1e-3
+    for kw in (dict(path="fused"), dict(path="single"), dict(W=101)):
+        args = dict(N=1, Cin=16, Cout=16, H=8, W=8, alg=alg)
+        args.update(kw)
+        with pytest.raises(binding.SfcError) as e:
+            binding.Plan(**args)
+        assert e.value.code == 2
+
+
+def test_5x5_full_size_against_oracle(binding):
+    """A 5x5 layer on the resnet28 geometry (128 -> 128 channels, 28x28, 64 images): every tap
+    and every output element against the oracle, and the exact mode against direct convolution."""
+    shape = synth.LAYERS["resnet28"]
+    alg = "6x6_5x5_p184"
+    print("case 5x5 full", alg, flush=True)
+    d = synth.make_layer(shape, kernel=5)
+    sx = oracle.calibrate_act_scales(d["x_calib"], alg)
+    sw = oracle.calibrate_filter_scales(d["w"], alg)
+    y_ref, taps_ref = oracle.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"], alg,
+                                          return_taps=True)
+    y, taps = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg,
+                             sx=sx, sw=sw, return_taps=True)
+    for tap in ("V", "U", "M"):
+        assert np.array_equal(taps[tap].astype(np.int64), taps_ref[tap]), tap
+    assert rel_err(y, y_ref) <= F32_TOL
+    acc = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="exact", alg=alg, out="i32")
+    assert np.array_equal(acc.astype(np.int64), oracle.direct_conv(d["x"], d["w"]))
 
 
 FULL = ["resnet56", "resnet28", "resnet14", "resnet7"]

@@ -94,7 +94,7 @@ def test_plan_sizes_and_counts(lib):
 @pytest.mark.parametrize(
     "kw,code",
     [
-        (dict(N=0), 1), (dict(Cin=-1), 1), (dict(H=0), 1), (dict(alg=7), 1), (dict(mode=2), 1),
+        (dict(N=0), 1), (dict(Cin=-1), 1), (dict(H=0), 1), (dict(alg=8), 1), (dict(mode=2), 1),
         (dict(out=5), 1), (dict(path=3), 1), (dict(per_channel_wscale=2), 1),
         (dict(transform_bits=1), 1), (dict(transform_bits=9), 1),
         (dict(transform_bits=4, mode=0), 2),  # exact mode has no transform-domain rounding
@@ -156,7 +156,8 @@ def kernel_maps(tmp_path_factory):
 
 
 @pytest.mark.parametrize("alg_id,alg", [(0, "6x6_p88"), (1, "6x6_p100"), (2, "7x7_p132"), (3, "7x7_p144"),
-                                        (4, "4x4_p46"), (5, "4x4_p49")])
+                                        (4, "4x4_p46"), (5, "4x4_p49"),
+                                        (6, "6x6_5x5_p184"), (7, "6x6_5x5_p196")])
 def test_kernel_add_networks_realize_the_oracle_matrices(kernel_maps, alg_id, alg):
     b2, g2, a2, den = oracle.algorithm(alg)
     assert den == (16 if alg.startswith("4x4") else 36)
