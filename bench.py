@@ -157,7 +157,8 @@ def main():
     ap.add_argument("--workload", default="resnet56")
     ap.add_argument("--path", default=None, choices=[None, "staged", "fused", "single"])
     ap.add_argument("--alg", default=None,
-                    help="6x6_p88 | 6x6_p100 | 7x7_p132 | 7x7_p144 (default: 6x6_p88; per layer for the stack)")
+                    help="6x6_p88 | 6x6_p100 | 7x7_p132 | 7x7_p144 | 4x4_p46 | 4x4_p49, or with 5x5 filters "
+                         "6x6_5x5_p184 | 6x6_5x5_p196 (default: 6x6_p88; per layer for the stack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=3,
                     help="HIP streams the steps are dealt to round-robin (independent batches overlap)")
@@ -183,9 +184,13 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     shape = synth.LAYERS[args.workload]
-    data = synth.make_layer(shape)
-    # one kernel where the layer allows it (Cin <= 64), else input transform + fused product/output
-    path = args.path or ("single" if shape.Cin <= 64 else binding.DEFAULT_PATH)
+    ksize = binding.KERNEL_SIZE[args.alg]
+    data = synth.make_layer(shape, kernel=ksize)
+    # one kernel where the layer allows it (3x3 filters, Cin <= 64), else input transform + fused
+    # product/output; SFC-4 runs on the staged path
+    path = args.path or ("staged" if args.alg.startswith("4x4") else
+                         "single" if shape.Cin <= 64 and ksize == 3 else binding.DEFAULT_PATH)
+    direct_ops = shape.direct_ops * ksize * ksize // 9
 
     plan = binding.Plan(shape.N, shape.Cin, shape.Cout, shape.H, shape.W, alg=args.alg,
                         mode="requant", path=path, per_channel_wscale=shape.per_channel_wscale)
@@ -343,14 +348,16 @@ def main():
             roofline.update({"bound": "alu", "achieved": round(valu_tops, 2),
                              "peak": round(VALU_PEAK_TOPS, 2), "unit": "TOP/s",
                              "frac": round(valu_tops / VALU_PEAK_TOPS, 4)})
-    tops = shape.direct_ops / (ms_per_step * 1e-3) / 1e12
+    tops = direct_ops / (ms_per_step * 1e-3) / 1e12
     out = {
-        "metric": "direct-conv-equivalent int8 TOPS per 3x3 layer",
+        "metric": f"direct-conv-equivalent int8 TOPS per {ksize}x{ksize} layer",
         "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: N={shape.N} Cin=Cout={shape.Cin} H=W={shape.H} 3x3 s1 p1",
-                   "algorithm": f"SFC-6({args.alg[:3]},3x3) P={plan.P}", "mode": "requant-int8 transform domain",
+        "config": {"workload": f"{args.workload}: N={shape.N} Cin=Cout={shape.Cin} H=W={shape.H} "
+                               f"{ksize}x{ksize} s1 p{(ksize - 1) // 2}",
+                   "algorithm": f"SFC-{4 if args.alg.startswith('4x4') else 6}({args.alg[:3]},{ksize}x{ksize}) P={plan.P}",
+                   "mode": "requant-int8 transform domain",
                    "path": path, "buffer_sets": nsets, "streams": nstreams,
                    "single_stream_ms_per_step": round(single_stream_ms, 5),
                    "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
@@ -375,7 +382,7 @@ def main():
             dt = time.perf_counter() - t0
             if dt >= 10.0 or passes >= 50:
                 break
-        out["cpu_baseline"] = {"value": round(passes * shape.direct_ops / dt / 1e12, 5), "unit": "TOPS",
+        out["cpu_baseline"] = {"value": round(passes * direct_ops / dt / 1e12, 5), "unit": "TOPS",
                                "cores": int(cores), "kind": "oracle",
                                "sample": f"oracle.conv_requant on the full {args.workload} batch "
                                          f"(N={shape.N}), {passes} passes in {dt:.1f} s"}

@@ -205,6 +205,8 @@ hipError_t launch_repack_filter(const Geometry& g, int filters, const void* U, v
     case 1: hipLaunchKernelGGL(repack_filter_kernel<1>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
     case 2: hipLaunchKernelGGL(repack_filter_kernel<2>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
     case 3: hipLaunchKernelGGL(repack_filter_kernel<3>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
+    case 6: hipLaunchKernelGGL(repack_filter_kernel<6>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
+    case 7: hipLaunchKernelGGL(repack_filter_kernel<7>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -219,7 +221,10 @@ void single_point_order(int alg, int* pt /*[P]*/) {
     case 0: { constexpr Order<0> o{}; copy(o); break; }
     case 1: { constexpr Order<1> o{}; copy(o); break; }
     case 2: { constexpr Order<2> o{}; copy(o); break; }
-    default: { constexpr Order<3> o{}; copy(o); break; }
+    case 3: { constexpr Order<3> o{}; copy(o); break; }
+    case 6: { constexpr Order<6> o{}; copy(o); break; }
+    case 7: { constexpr Order<7> o{}; copy(o); break; }
+    default: break;  // no fused kernel for the other forms
   }
 }
 

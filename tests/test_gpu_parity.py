@@ -140,7 +140,7 @@ def test_gpu_calibration_matches_oracle(binding, alg):
     plan.close()
 
 
-ALGS_5X5 = ["6x6_5x5_p184", "6x6_5x5_p196"]  # SFC-6(6x6,5x5), Appendix A: staged path
+ALGS_5X5 = ["6x6_5x5_p184", "6x6_5x5_p196"]  # SFC-6(6x6,5x5), Appendix A: staged and fused paths
 
 
 @pytest.mark.parametrize("alg", ALGS_5X5)
@@ -178,7 +178,8 @@ def test_5x5_requant_mode_taps_bit_exact_and_output_close(binding, shape, alg):
 @pytest.mark.parametrize("alg", ALGS_5X5)
 def test_5x5_calibration_int8_output_and_limits(binding, alg):
     """The library's abs-max calibration against the oracle's, the int8 + ReLU epilogue with
-    4-bit and 8-bit transform domains, and what the 5x5 forms do not take."""
+    4-bit and 8-bit transform domains on the staged and the fused path, and what the 5x5 forms
+    do not take."""
     import torch
 
     shape = (4, 24, 20, 14, 10)
@@ -198,10 +199,11 @@ def test_5x5_calibration_int8_output_and_limits(binding, alg):
                            sx=sx, sw=sw, transform_bits=bits)
         assert rel_err(y, y_ref) <= F32_TOL
         y_scale = float(np.float32(max(y_ref.max(), 1e-6) / 127.0 * 0.8))
-        y8 = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg,
-                            out="i8", sx=sx, sw=sw, y_scale=y_scale, transform_bits=bits)
-        assert check_i8_against_oracle(y8, y_ref, y_scale) < 1e-3
-    for kw in (dict(path="fused"), dict(path="single"), dict(W=101)):
+        for path in ("staged", "fused"):
+            y8 = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg,
+                                out="i8", path=path, sx=sx, sw=sw, y_scale=y_scale, transform_bits=bits)
+            assert check_i8_against_oracle(y8, y_ref, y_scale) < 1e-3
+    for kw in (dict(path="single"), dict(W=101), dict(path="fused", Cin=330)):  # six 64-channel chunks
         args = dict(N=1, Cin=16, Cout=16, H=8, W=8, alg=alg)
         args.update(kw)
         with pytest.raises(binding.SfcError) as e:
@@ -225,6 +227,10 @@ def test_5x5_full_size_against_oracle(binding):
     for tap in ("V", "U", "M"):
         assert np.array_equal(taps[tap].astype(np.int64), taps_ref[tap]), tap
     assert rel_err(y, y_ref) <= F32_TOL
+    yf, taps = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg,
+                              path="fused", sx=sx, sw=sw, return_taps=True)
+    assert np.array_equal(taps["V"].astype(np.int64), taps_ref["V"])
+    assert rel_err(yf, y_ref) <= F32_TOL
     acc = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="exact", alg=alg, out="i32")
     assert np.array_equal(acc.astype(np.int64), oracle.direct_conv(d["x"], d["w"]))
 
@@ -327,6 +333,22 @@ def test_fused_path_matches_oracle(binding, shape, alg):
     # and it agrees with the staged path of the same library to float32 rounding
     y_staged = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path="staged", sx=sx, sw=sw)
     assert rel_err(y, y_staged.astype(np.float64)) <= F32_TOL
+
+
+@pytest.mark.parametrize("alg", ALGS_5X5)
+@pytest.mark.parametrize("shape", FUSED_SHAPES)
+def test_5x5_fused_path_matches_oracle(binding, shape, alg):
+    x, w, xs, ws = uniform_case(shape, 1600 + len(alg) + sum(shape), r=5)
+    print("case 5x5 fused", shape, alg, flush=True)
+    xc, _, _, _ = uniform_case(shape, 1700 + sum(shape), r=5)
+    sx = oracle.calibrate_act_scales(xc // 2, alg)
+    sw = oracle.calibrate_filter_scales(w, alg)
+    y_ref, taps_ref = oracle.conv_requant(x, w, sx, sw, xs, ws, alg, return_taps=True)
+    y, taps = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path="fused", sx=sx, sw=sw,
+                             return_taps=True)
+    for name in ("V", "U"):
+        assert np.array_equal(taps[name].astype(np.int64), taps_ref[name]), name
+    assert rel_err(y, y_ref) <= F32_TOL
 
 
 SINGLE_SHAPES = [
