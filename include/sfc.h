@@ -64,7 +64,7 @@ typedef enum {
   /* SFC-6(6x6,5x5) (Appendix A): 5x5 filters w[Cout,Cin,5,5], zero padding 2, 6x6 output
    * tiles; 184 multiplications per tile in the Hermitian form, 196 in the nested form.
    * B^T and G are the printed ones; the printed A (seven columns for six outputs) is
-   * replaced by the one matrix that fits them.  Staged path only, W <= 100. */
+   * replaced by the one matrix that fits them.  Staged and fused paths. */
   SFC_ALG_6X6_5X5_P184 = 6,
   SFC_ALG_6X6_5X5_P196 = 7
 } sfc_alg;

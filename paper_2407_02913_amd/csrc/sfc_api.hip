@@ -101,8 +101,6 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   g.Kp = (d.Cout + 15) / 16 * 16;
   static const int kPoints[8] = {88, 100, 132, 144, 46, 49, 184, 196};
   g.P = kPoints[d.alg];
-  // the 5x5 algorithms stage ten input rows of 64 channels in 64 KB of LDS
-  if (d.alg >= SFC_ALG_6X6_5X5_P184 && d.W > 100) return SFC_EUNSUPPORTED;
   g.qmax = (float)((1 << ((d.transform_bits ? d.transform_bits : 8) - 1)) - 1);
 
   if (d.path == SFC_PATH_FUSED && !sfc::fused_quad_supported(g)) return SFC_EUNSUPPORTED;

@@ -107,7 +107,9 @@ __global__ __launch_bounds__(256) void filter_absmax_kernel(const int8_t* __rest
 // input transform
 //
 // One workgroup owns S consecutive strips (a strip = one row of tiles of one
-// image, i.e. the NI = M+R-1 input rows from M*ti-PAD on) for 64 channels.  The input
+// image, i.e. the NI = M+R-1 input rows from M*ti-PAD on) for 64 channels -- whole
+// strips, or, when their rows do not fit in LDS (wide images), one chunk of tlw tile
+// columns of them, staged byte by byte with its halo columns.  The whole input
 // rows of a (strip, channel) are one contiguous run of NI*W bytes in NCHW, so the
 // workgroup copies them to LDS with coalesced loads, then each thread transforms
 // one (tile, channel) patch with lanes running along channels, which makes the
@@ -115,8 +117,11 @@ __global__ __launch_bounds__(256) void filter_absmax_kernel(const int8_t* __rest
 // ---------------------------------------------------------------------------
 struct StripParams {
   int S;         // strips per workgroup
-  int cs;        // LDS bytes per (strip, channel): NI*W padded to 4*(odd)
-  int vec4;      // 1: W % 4 == 0, rows are dword aligned
+  int cs;        // LDS bytes per (strip, channel): NI*pitch padded to 4*(odd)
+  int vec4;      // 1: whole rows with W % 4 == 0, staged as dwords
+  int chunks;    // tile-column chunks per strip (1: whole rows)
+  int tlw;       // tile columns per chunk
+  int pitch;     // staged bytes per row: W, or M*tlw + 2*PAD for a chunk
 };
 
 template <int ALG, int MODE>
@@ -135,7 +140,10 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
   const int strip0 = blockIdx.x * sp.S;
   const int c0 = blockIdx.y * 64;
   const int W = g.W, H = g.H;
-  const int seg = NI * W;  // bytes per (strip, channel)
+  const int pitch = sp.pitch;
+  const int seg = NI * pitch;  // bytes per (strip, channel)
+  const int tjc0 = blockIdx.z * sp.tlw;                       // first tile column of the chunk
+  const int colstart = sp.chunks > 1 ? M * tjc0 - PAD : 0;    // image column of staged byte 0
 
   // ---- stage the raw rows -------------------------------------------------
   if (sp.vec4) {
@@ -168,10 +176,11 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
       unsigned char val = 0;
       if (strip < g.strips && c0 + c < g.Cin) {
         const int n = strip / g.th, ti = strip - n * g.th;
-        const int row = e / W;
+        const int row = e / pitch;
         const int h = M * ti - PAD + row;
-        if (h >= 0 && h < H) {
-          const size_t base = (((size_t)n * g.Cin + c0 + c) * H + h) * W + (e - row * W);
+        const int col = colstart + (e - row * pitch);
+        if (h >= 0 && h < H && col >= 0 && col < W) {
+          const size_t base = (((size_t)n * g.Cin + c0 + c) * H + h) * W + col;
           val = (unsigned char)x[base];
         }
       }
@@ -181,14 +190,14 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
   __syncthreads();
 
   // ---- transform: item = (strip s, tile column tj, channel c), c fastest ----
-  const int items = sp.S * g.tw * 64;
+  const int items = sp.S * sp.tlw * 64;
   for (int item = threadIdx.x; item < items; item += blockDim.x) {
     const int c = item & 63;
     const int rest = item >> 6;
-    const int tj = rest % g.tw;
-    const int s = rest / g.tw;
+    const int tj = tjc0 + rest % sp.tlw;
+    const int s = rest / sp.tlw;
     const int strip = strip0 + s;
-    if (strip >= g.strips) continue;
+    if (strip >= g.strips || tj >= g.tw) continue;
     const signed char* src = (const signed char*)lds + (size_t)(s * 64 + c) * sp.cs;
     int half[NI][NC];
 #pragma unroll
@@ -197,7 +206,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const int8_t* __re
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
         const int col = M * tj - PAD + j;
-        row[j] = (col >= 0 && col < W) ? (int)src[i * W + col] : 0;
+        row[j] = (col >= 0 && col < W) ? (int)src[i * pitch + col - colstart] : 0;
       }
       fwd_input<NI, NC>(row, half[i]);  // horizontal axis: half[i][b]
     }
@@ -328,13 +337,31 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __
 
 static StripParams strip_params(const Geometry& g) {
   StripParams sp;
-  int seg4 = ((alg_tile(g.alg) + alg_taps(g.alg) - 1) * g.W + 3) / 4;
-  if ((seg4 & 1) == 0) seg4 += 1;  // odd dword stride: lanes along channels hit distinct banks
-  sp.cs = 4 * seg4;
+  const int M = alg_tile(g.alg), PAD = (alg_taps(g.alg) - 1) / 2, NI = M + 2 * PAD;
+  // odd dword stride between channels: lanes along channels hit distinct banks
+  auto channel_bytes = [&](int pitch) {
+    int seg4 = (NI * pitch + 3) / 4;
+    if ((seg4 & 1) == 0) seg4 += 1;
+    return 4 * seg4;
+  };
+  sp.chunks = 1;
+  sp.tlw = g.tw;
+  sp.pitch = g.W;
+  sp.cs = channel_bytes(g.W);
   sp.vec4 = (g.W % 4 == 0) ? 1 : 0;
+  if (64 * sp.cs > 64 * 1024) {
+    // wide rows: chunks of tile columns with their halo, at most 48 KB per strip
+    int tlw = g.tw;
+    while (tlw > 1 && 64 * channel_bytes(M * tlw + 2 * PAD) > 48 * 1024) --tlw;
+    sp.tlw = tlw;
+    sp.chunks = (g.tw + tlw - 1) / tlw;
+    sp.pitch = M * tlw + 2 * PAD;
+    sp.cs = channel_bytes(sp.pitch);
+    sp.vec4 = 0;
+  }
   // aim at >= 256 (tile, channel) items and <= 32 KB of LDS per workgroup
   int S = 1;
-  while (S < 16 && S * 2 * 64 * sp.cs <= 32 * 1024 && S * g.tw * 64 < 512) S *= 2;
+  while (S < 16 && S * 2 * 64 * sp.cs <= 32 * 1024 && S * sp.tlw * 64 < 512) S *= 2;
   sp.S = S;
   return sp;
 }
@@ -345,7 +372,7 @@ static hipError_t launch_input_impl(const Geometry& g, const int8_t* x, void* V,
   const StripParams sp = strip_params(g);
   const size_t lds = (size_t)sp.S * 64 * sp.cs;
   if (lds > 64 * 1024) return hipErrorInvalidValue;
-  dim3 grid((g.strips + sp.S - 1) / sp.S, g.Cp / 64);
+  dim3 grid((g.strips + sp.S - 1) / sp.S, g.Cp / 64, sp.chunks);
   hipLaunchKernelGGL((input_transform_kernel<ALG, MODE>), grid, dim3(256), lds, s, x, V, inv_sx,
                      maxima, g, sp);
   return hipGetLastError();

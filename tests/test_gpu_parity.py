@@ -203,7 +203,7 @@ def test_5x5_calibration_int8_output_and_limits(binding, alg):
             y8 = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg,
                                 out="i8", path=path, sx=sx, sw=sw, y_scale=y_scale, transform_bits=bits)
             assert check_i8_against_oracle(y8, y_ref, y_scale) < 1e-3
-    for kw in (dict(path="single"), dict(W=101), dict(path="fused", Cin=330)):  # six 64-channel chunks
+    for kw in (dict(path="single"), dict(path="fused", Cin=330)):  # six 64-channel chunks
         args = dict(N=1, Cin=16, Cout=16, H=8, W=8, alg=alg)
         args.update(kw)
         with pytest.raises(binding.SfcError) as e:
@@ -233,6 +233,38 @@ def test_5x5_full_size_against_oracle(binding):
     assert rel_err(yf, y_ref) <= F32_TOL
     acc = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="exact", alg=alg, out="i32")
     assert np.array_equal(acc.astype(np.int64), oracle.direct_conv(d["x"], d["w"]))
+
+
+WIDE_SHAPES = [  # rows too wide for whole-strip staging in the generic input kernel
+    (1, 3, 4, 9, 300),    # odd tile count per row, W a multiple of 4
+    (2, 5, 3, 13, 1024),  # the widest row the library takes
+    (1, 70, 8, 7, 203),   # two channel slices, W not a multiple of 4
+]
+
+
+@pytest.mark.parametrize("alg", ["6x6_p88", "7x7_p144", "4x4_p46", "6x6_5x5_p184"])
+@pytest.mark.parametrize("shape", WIDE_SHAPES)
+def test_wide_rows_exact_calibration_and_requant(binding, shape, alg):
+    import torch
+
+    r = binding.KERNEL_SIZE[alg]
+    x, w, xs, ws = uniform_case(shape, 1800 + len(alg) + sum(shape), r=r)
+    print("case wide", shape, alg, flush=True)
+    acc_ref, taps_ref = oracle.conv_exact(x, w, alg, return_taps=True)
+    acc, taps = binding.conv2d(x, w, xs, ws, mode="exact", alg=alg, out="i32", return_taps=True)
+    assert np.array_equal(taps["V"].astype(np.int64), taps_ref["V"])
+    assert np.array_equal(acc.astype(np.int64), acc_ref)
+    plan = binding.Plan(*shape, alg=alg, mode="requant")
+    wbuf = binding.device_buffer(plan.workspace_bytes)
+    sx = plan.calibrate_act_scales(torch.from_numpy(x // 2).cuda(), wbuf)
+    plan.close()
+    assert np.array_equal(sx, oracle.calibrate_act_scales(x // 2, alg))
+    sw = oracle.calibrate_filter_scales(w, alg)
+    y_ref, taps_ref = oracle.conv_requant(x, w, sx, sw, xs, ws, alg, return_taps=True)
+    y, taps = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, sx=sx, sw=sw, return_taps=True)
+    for name in ("V", "U", "M"):
+        assert np.array_equal(taps[name].astype(np.int64), taps_ref[name]), name
+    assert rel_err(y, y_ref) <= F32_TOL
 
 
 FULL = ["resnet56", "resnet28", "resnet14", "resnet7"]
