@@ -153,8 +153,29 @@ sfc_status sfc_calibrate_filter_scales(const sfc_plan_t* plan, const int8_t* w_d
                                        void* workspace_dev, void* stream,
                                        float* sw_host_out /*[P*Cout]*/);
 
+/* Scale granularities of the ablation study (Sec. 6, "Ablation Study on Quantization
+ * Granularity"): activations per tensor or per frequency (= per multiplication point),
+ * filters per output channel, per frequency, or per channel and frequency (Sec. 5's
+ * [T x T] and [OC x T x T] factors are the finest of each). */
+typedef enum { SFC_ACT_PER_TENSOR = 0, SFC_ACT_PER_POINT = 1 } sfc_act_granularity;
+typedef enum {
+  SFC_FILTER_PER_CHANNEL = 0,
+  SFC_FILTER_PER_POINT = 1,
+  SFC_FILTER_PER_CHANNEL_POINT = 2
+} sfc_filter_granularity;
+
+/* Host only, in place.  Coarsens the finest-granularity abs-max scales (as the calibration
+ * helpers return them) to the requested grouping: every scale becomes the maximum over its
+ * group, which is the abs-max scale of the group because all scales share the divisor qmax.
+ * sx_host [P]: per tensor -> all P entries equal.  sw_host [P*Cout] laid out [P][Cout]: per
+ * channel -> the maximum over points for each Cout; per point -> the maximum over Cout for
+ * each point.  The finest settings leave the arrays as they are.  The result is what
+ * sfc_set_point_scales takes, so every granularity runs on the same kernels. */
+sfc_status sfc_group_scales(const sfc_plan_t* plan, int32_t act_granularity,
+                            int32_t filter_granularity, float* sx_host, float* sw_host);
+
 /* Filter transform U = G f G^T (Appendix A's G, additions only), once per layer.
- * w_dev: int8 [Cout,Cin,3,3].  wscale_host: [1] or [Cout] spatial-domain filter
+ * w_dev: int8 [Cout,Cin,R,R].  wscale_host: [1] or [Cout] spatial-domain filter
  * scales.  filter_dev: >= filter_bytes, receives U (int16 in exact mode, rounded
  * to int8 in requantized mode) and the per-point dequantization table; the plan
  * remembers the pointer.  Asynchronous on `stream` apart from a small pageable

@@ -904,6 +904,31 @@ def calibrate_filter_scales(w: np.ndarray, alg="6x6_p88", qmax: int = QMAX) -> n
     return np.where(mx == 0, np.float32(1.0), s).astype(np.float32)
 
 
+def group_scales(sx_pt: np.ndarray, sw_pt: np.ndarray, act: str = "point", filt: str = "channel_point"):
+    """Scale granularities of the ablation study (Sec. 6, "Ablation Study on Quantization
+    Granularity"), from the finest abs-max scales ``sx_pt`` [P] and ``sw_pt`` [P, Cout].
+
+    ``act``: "tensor" (one activation scale) or "point" (one per frequency, Sec. 5's [T x T]).
+    ``filt``: "channel" (one per output channel), "point" (one per frequency) or
+    "channel_point" (Sec. 5's [OC x T x T]).  A group's abs-max scale is the largest scale
+    in the group, since all of them are maxima divided by the same qmax.  Returns float32
+    arrays of the full shapes [P] and [P, Cout], ready for ``conv_requant``.
+    """
+    sx = np.asarray(sx_pt, dtype=np.float32)
+    sw = np.asarray(sw_pt, dtype=np.float32)
+    if act == "tensor":
+        sx = np.full_like(sx, sx.max())
+    elif act != "point":
+        raise ValueError(act)
+    if filt == "channel":
+        sw = np.broadcast_to(sw.max(axis=0, keepdims=True), sw.shape).copy()
+    elif filt == "point":
+        sw = np.broadcast_to(sw.max(axis=1, keepdims=True), sw.shape).copy()
+    elif filt != "channel_point":
+        raise ValueError(filt)
+    return sx.copy(), sw
+
+
 def output_transform_dequant(m, a2, den, sx_pt, sw_pt, x_scale, w_scale, n, h, w):
     """y[o] = (s_x s_w[k] / den) * sum_p A2[p,o] * (M[p] * s_Tx[p] * s_Tf[p,k]), float64."""
     p, t, k = m.shape

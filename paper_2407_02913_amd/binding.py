@@ -19,6 +19,8 @@ STATUS_NAMES = {0: "SFC_OK", 1: "SFC_EINVAL", 2: "SFC_EUNSUPPORTED", 3: "SFC_ENO
                 4: "SFC_ENOTREADY", 5: "SFC_EHIP"}
 ALG = {"6x6_p88": 0, "6x6_p100": 1, "7x7_p132": 2, "7x7_p144": 3, "4x4_p46": 4, "4x4_p49": 5,
        "6x6_5x5_p184": 6, "6x6_5x5_p196": 7}
+ACT_GRANULARITY = {"tensor": 0, "point": 1}
+FILTER_GRANULARITY = {"channel": 0, "point": 1, "channel_point": 2}
 KERNEL_SIZE = {name: 5 if "5x5" in name else 3 for name in ALG}  # filter edge R
 MODE = {"exact": 0, "requant": 1}
 OUT = {"f32": 0, "i32": 1, "i8": 2}
@@ -30,6 +32,7 @@ DEFAULT_PATH = "fused"
 #: every symbol include/sfc.h declares
 EXPORTS = (
     "sfc_plan", "sfc_plan_destroy", "sfc_plan_sizes", "sfc_set_point_scales", "sfc_set_output_scale",
+    "sfc_group_scales",
     "sfc_calibrate_act_scales", "sfc_calibrate_filter_scales", "sfc_transform_filter",
     "sfc_conv2d_nchw", "sfc_conv2d_stages", "sfc_tap_info", "sfc_stream_copy", "sfc_status_string",
 )
@@ -71,6 +74,8 @@ def load(force: bool = False):
     lib.sfc_plan_sizes.restype = i32
     lib.sfc_set_point_scales.argtypes = [vp, C.POINTER(f32), C.POINTER(f32)]
     lib.sfc_set_point_scales.restype = i32
+    lib.sfc_group_scales.argtypes = [vp, i32, i32, C.POINTER(f32), C.POINTER(f32)]
+    lib.sfc_group_scales.restype = i32
     lib.sfc_set_output_scale.argtypes = [vp, f32]
     lib.sfc_set_output_scale.restype = i32
     lib.sfc_calibrate_act_scales.argtypes = [vp, vp, i32, vp, vp, C.POINTER(f32)]
@@ -145,6 +150,15 @@ class Plan:
         assert sx.shape == (self.P,) and sw.shape == (self.P, self.desc.Cout), (sx.shape, sw.shape)
         _check(load().sfc_set_point_scales(self._h, _f32_ptr(sx), _f32_ptr(sw)),
                "sfc_set_point_scales")
+
+    def group_scales(self, sx: np.ndarray, sw: np.ndarray, act="point", filt="channel_point"):
+        """Copies of the finest-granularity scales coarsened to the ablation's groupings."""
+        sx = np.array(sx, dtype=np.float32, order="C")
+        sw = np.array(sw, dtype=np.float32, order="C")
+        assert sx.shape == (self.P,) and sw.shape == (self.P, self.desc.Cout), (sx.shape, sw.shape)
+        _check(load().sfc_group_scales(self._h, ACT_GRANULARITY[act], FILTER_GRANULARITY[filt],
+                                       _f32_ptr(sx), _f32_ptr(sw)), "sfc_group_scales")
+        return sx, sw
 
     def set_output_scale(self, y_scale: float):
         _check(load().sfc_set_output_scale(self._h, C.c_float(y_scale)), "sfc_set_output_scale")

@@ -182,6 +182,36 @@ sfc_status sfc_set_point_scales(sfc_plan_t* plan, const float* sx_host, const fl
   return SFC_OK;
 }
 
+sfc_status sfc_group_scales(const sfc_plan_t* plan, int32_t act_granularity,
+                            int32_t filter_granularity, float* sx_host, float* sw_host) {
+  if (!plan || !sx_host || !sw_host) return SFC_EINVAL;
+  if (act_granularity != SFC_ACT_PER_TENSOR && act_granularity != SFC_ACT_PER_POINT)
+    return SFC_EINVAL;
+  if (filter_granularity < SFC_FILTER_PER_CHANNEL || filter_granularity > SFC_FILTER_PER_CHANNEL_POINT)
+    return SFC_EINVAL;
+  const int P = plan->g.P, K = plan->g.Cout;
+  if (act_granularity == SFC_ACT_PER_TENSOR) {
+    float m = sx_host[0];
+    for (int p = 1; p < P; ++p) m = sx_host[p] > m ? sx_host[p] : m;
+    for (int p = 0; p < P; ++p) sx_host[p] = m;
+  }
+  if (filter_granularity == SFC_FILTER_PER_CHANNEL) {
+    for (int k = 0; k < K; ++k) {
+      float m = sw_host[k];
+      for (int p = 1; p < P; ++p) m = sw_host[(size_t)p * K + k] > m ? sw_host[(size_t)p * K + k] : m;
+      for (int p = 0; p < P; ++p) sw_host[(size_t)p * K + k] = m;
+    }
+  } else if (filter_granularity == SFC_FILTER_PER_POINT) {
+    for (int p = 0; p < P; ++p) {
+      float* row = sw_host + (size_t)p * K;
+      float m = row[0];
+      for (int k = 1; k < K; ++k) m = row[k] > m ? row[k] : m;
+      for (int k = 0; k < K; ++k) row[k] = m;
+    }
+  }
+  return SFC_OK;
+}
+
 sfc_status sfc_set_output_scale(sfc_plan_t* plan, float y_scale) {
   if (!plan) return SFC_EINVAL;
   if (plan->d.out != SFC_OUT_I8_RELU) return SFC_EUNSUPPORTED;

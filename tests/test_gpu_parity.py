@@ -112,6 +112,45 @@ def test_sub_int8_transform_domain(binding, alg, path, bits):
     plan.close()
 
 
+@pytest.mark.parametrize("bits", [8, 6, 4])
+def test_scale_granularity_ablation(binding, bits):
+    """The granularity settings of Sec. 6's ablation (activations per tensor / per frequency,
+    filters per channel / per channel and frequency) at int8, int6 and int4 in the transform
+    domain, SFC-6(7x7,3x3): scales calibrated and grouped by the library, every setting bit-exact
+    in its taps and within tolerance of the oracle; the error against direct convolution falls as
+    the granularity gets finer (on synthetic data; accuracy itself needs ImageNet)."""
+    import torch
+
+    alg, shape = "7x7_p132", (4, 32, 24, 14, 14)
+    d = synth.make_layer(synth.LayerShape("abl", *shape, "relu", True, 5))
+    print("case ablation", bits, flush=True)
+    qmax = 2 ** (bits - 1) - 1
+    plan = binding.Plan(*shape, alg=alg, mode="requant", transform_bits=bits)
+    wbuf = binding.device_buffer(plan.workspace_bytes)
+    sx = plan.calibrate_act_scales(torch.from_numpy(d["x_calib"]).cuda(), wbuf)
+    sw = plan.calibrate_filter_scales(torch.from_numpy(d["w"]).cuda(), wbuf)
+    ref = oracle.dequantize(oracle.direct_conv(d["x"], d["w"]), d["x_scale"], d["w_scale"])
+    errs = []
+    for act, filt in (("tensor", "channel"), ("point", "channel"), ("point", "point"),
+                      ("point", "channel_point")):
+        gx, gw = plan.group_scales(sx, sw, act, filt)
+        ox, ow = oracle.group_scales(oracle.calibrate_act_scales(d["x_calib"], alg, qmax=qmax),
+                                     oracle.calibrate_filter_scales(d["w"], alg, qmax=qmax), act, filt)
+        assert np.array_equal(gx, ox) and np.array_equal(gw, ow)
+        y_ref, taps_ref = oracle.conv_requant(d["x"], d["w"], gx, gw, d["x_scale"], d["w_scale"], alg,
+                                              qmax=qmax, return_taps=True)
+        for path in ("staged", "fused"):
+            y, taps = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg,
+                                     path=path, sx=gx, sw=gw, return_taps=True, transform_bits=bits)
+            for name in taps:
+                assert np.array_equal(taps[name].astype(np.int64), taps_ref[name]), (name, act, filt)
+            assert rel_err(y, y_ref) <= F32_TOL
+        errs.append(float(np.sqrt(np.mean((y.astype(np.float64) - ref) ** 2))))
+    plan.close()
+    print("rms error vs direct convolution:", errs, flush=True)
+    assert errs[0] > errs[1] > errs[3] and errs[2] > errs[3], errs
+
+
 def test_single_filter_scale(binding):
     x, w, xs, _ = uniform_case((1, 16, 16, 32, 32), 7)
     ws = np.array([0.01], dtype=np.float32)

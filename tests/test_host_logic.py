@@ -183,3 +183,23 @@ def test_bench_operation_counts_match_the_add_networks(tmp_path):
     # the 6x6 input network is the paper's: 14 additions per symbolic DFT-6 plus the correction
     # inputs, 16 per 1-D pass over 8 + 8 lines, plus the sums of the product rule
     assert bench.ADD_NETWORK_OPS["6x6_p88"][0] == 16 * 16 + 48
+
+
+def test_group_scales_matches_the_oracle_for_every_granularity(lib):
+    """Host-only entry point: the ablation's scale groupings against the oracle's."""
+    from paper_2407_02913_amd import binding
+
+    rng = np.random.default_rng(5)
+    plan = binding.Plan(2, 16, 24, 14, 9, alg="6x6_p88", mode="requant")
+    sx = rng.uniform(0.1, 4.0, size=plan.P).astype(np.float32)
+    sw = rng.uniform(0.1, 4.0, size=(plan.P, 24)).astype(np.float32)
+    for act in ("tensor", "point"):
+        for filt in ("channel", "point", "channel_point"):
+            gx, gw = plan.group_scales(sx, sw, act, filt)
+            ox, ow = oracle.group_scales(sx, sw, act, filt)
+            assert np.array_equal(gx, ox) and np.array_equal(gw, ow), (act, filt)
+    h = plan._h
+    fx, fw = (C.c_float * plan.P)(), (C.c_float * (plan.P * 24))()
+    assert lib.sfc_group_scales(h, 2, 0, fx, fw) == 1 and lib.sfc_group_scales(h, 0, 3, fx, fw) == 1
+    assert lib.sfc_group_scales(h, 0, 0, None, fw) == 1
+    plan.close()

@@ -699,3 +699,51 @@ def test_5x5_extreme_values_and_requant_reduction():
                              np.float32(0.5), alg)
         ref = sfc.dequantize(sfc.direct_conv(x, w), 0.125, np.float32(0.5))
         assert np.allclose(y, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
+
+
+# ---- scale granularities of the ablation study (Sec. 6) -----------------------
+
+
+def test_grouped_scales_are_the_abs_max_scales_of_the_groups():
+    rng = np.random.default_rng(41)
+    x = rng.integers(-128, 128, size=(2, 5, 13, 9)).astype(np.int8)
+    w = rng.integers(-128, 128, size=(6, 5, 3, 3)).astype(np.int8)
+    alg = "6x6_p88"
+    b2, g2, _, _ = sfc.algorithm(alg)
+    v = np.abs(sfc.input_transform(x, b2))  # [P, T, C]
+    u = np.abs(sfc.filter_transform(w, g2))  # [P, K, C]
+    for qmax in (127, 7):
+        sx = sfc.calibrate_act_scales(x, alg, qmax=qmax)
+        sw = sfc.calibrate_filter_scales(w, alg, qmax=qmax)
+        q = np.float32(qmax)
+        # the definition, straight from the transformed tensors
+        sx_t, _ = sfc.group_scales(sx, sw, act="tensor")
+        assert np.all(sx_t == np.float32(v.max()) / q)
+        _, sw_c = sfc.group_scales(sx, sw, filt="channel")
+        assert np.array_equal(sw_c, np.broadcast_to(u.max(axis=(0, 2)).astype(np.float32) / q, sw.shape))
+        _, sw_p = sfc.group_scales(sx, sw, filt="point")
+        assert np.array_equal(sw_p, np.broadcast_to((u.max(axis=(1, 2)).astype(np.float32) / q)[:, None], sw.shape))
+        sx_f, sw_f = sfc.group_scales(sx, sw)
+        assert np.array_equal(sx_f, sx) and np.array_equal(sw_f, sw)
+    with pytest.raises(ValueError):
+        sfc.group_scales(sx, sw, act="channel")
+
+
+def test_finer_scale_granularity_lowers_the_error_at_low_bit_width():
+    # the ordering of Table "Ablation study ... with SFC(7x7, 3x3)", on synthetic data: the
+    # transform-domain gains of the points differ by up to 9x, which one scale per tensor wastes
+    rng = np.random.default_rng(42)
+    x = np.clip(np.rint(np.abs(rng.normal(0, 30, size=(2, 16, 14, 14)))), 0, 127).astype(np.int8)
+    w = np.clip(np.rint(rng.normal(0, 20, size=(8, 16, 3, 3))), -127, 127).astype(np.int8)
+    ref = sfc.dequantize(sfc.direct_conv(x, w), 0.02, 0.01)
+    alg = "7x7_p132"
+    for bits in (4, 6):
+        qmax = 2 ** (bits - 1) - 1
+        sx = sfc.calibrate_act_scales(x, alg, qmax=qmax)
+        sw = sfc.calibrate_filter_scales(w, alg, qmax=qmax)
+        errs = []
+        for act, filt in (("tensor", "channel"), ("point", "channel"), ("point", "channel_point")):
+            gx, gw = sfc.group_scales(sx, sw, act, filt)
+            y = sfc.conv_requant(x, w, gx, gw, 0.02, 0.01, alg, qmax=qmax)
+            errs.append(float(np.sqrt(np.mean((y - ref) ** 2))))
+        assert errs[0] > errs[1] > errs[2], errs
