@@ -194,10 +194,10 @@ def main():
     shape = synth.LAYERS[args.workload]
     ksize = binding.KERNEL_SIZE[args.alg]
     data = synth.make_layer(shape, kernel=ksize)
-    # one kernel where the layer allows it (3x3 filters, Cin <= 64), else input transform + fused
-    # product/output; SFC-4 runs on the staged path
-    path = args.path or ("staged" if args.alg.startswith("4x4") else
-                         "single" if shape.Cin <= 64 and ksize == 3 else binding.DEFAULT_PATH)
+    # one kernel where the layer allows it (SFC-6 with 3x3 filters, Cin <= 64), else input
+    # transform + fused product/output
+    one_kernel = shape.Cin <= 64 and ksize == 3 and not args.alg.startswith("4x4")
+    path = args.path or ("single" if one_kernel else binding.DEFAULT_PATH)
     direct_ops = shape.direct_ops * ksize * ksize // 9
 
     plan = binding.Plan(shape.N, shape.Cin, shape.Cout, shape.H, shape.W, alg=args.alg,

@@ -124,9 +124,11 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   if (d.path == SFC_PATH_SINGLE) p->quad_filters = (g.Cout + 63) / 64 * 64;
   if (d.path == SFC_PATH_FUSED) p->quad_filters = sfc::quad_filter_count(g);
   if (p->quad_filters > 0) {
-    off = align_up(off + (size_t)p->quad_filters * g.P * sizeof(float), 256);
+    // the fused kernels take the points in groups of four: positions up to a multiple of 4
+    const size_t pp = (size_t)(g.P + 3) / 4 * 4;
+    off = align_up(off + (size_t)p->quad_filters * pp * sizeof(float), 256);
     p->off_U_single = off;
-    off = align_up(off + (size_t)p->quad_filters * g.P * g.Cp, 256);
+    off = align_up(off + (size_t)p->quad_filters * pp * g.Cp, 256);
   }
   p->filter_bytes = off;
   off = 0;
@@ -265,11 +267,13 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
   }
   if (quad) {
     // [filter][processing position]; filters beyond Cout stay zero
-    std::vector<int> pt(g.P);
+    const int pp = (g.P + 3) / 4 * 4;
+    std::vector<int> pt(pp, -1);
     sfc::single_point_order(plan->d.alg, pt.data());
     float* dqs = table(plan->off_dq_single);
     for (int k = 0; k < g.Cout; ++k)
-      for (int j = 0; j < g.P; ++j) dqs[(size_t)k * g.P + j] = dequant[(size_t)pt[j] * g.Kp + k];
+      for (int j = 0; j < pp; ++j)
+        dqs[(size_t)k * pp + j] = pt[j] < 0 ? 0.0f : dequant[(size_t)pt[j] * g.Kp + k];
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (hipMemcpyAsync(static_cast<char*>(filter_dev) + plan->off_dequant, plan->staging.data(),

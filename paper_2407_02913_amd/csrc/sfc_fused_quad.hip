@@ -9,13 +9,12 @@ hipError_t launch_fused_quad_5tap(int out, const Geometry& g, const void* V, con
                                   float x_scale, float inv_y, void* y, hipStream_t s);
 
 bool fused_quad_supported(const Geometry& g) {
-  if (g.alg == 4 || g.alg == 5) return false;  // SFC-6 forms only
   const int kc = g.Cp / 64;
   if (kc != 1 && kc != 2 && kc != 4 && kc != 8) return false;
   const int nw = quad_waves(g.alg, kc);
   const long long kq = (long long)((g.Cout + 4 * nw - 1) / (4 * nw)) * nw;  // filter quads allocated
   const long long ybytes = 4ll * g.N * g.Cout * g.H * g.W;
-  const long long vbytes = (long long)g.P * g.Tp * g.Cp, ubytes = kq * 4 * g.P * g.Cp;
+  const long long vbytes = (long long)g.P * g.Tp * g.Cp, ubytes = kq * 4 * (g.P + 3) * g.Cp;
   const long long lim = 1ll << 31;
   return ybytes < lim && vbytes < lim && ubytes < lim && quad_lds_bytes(g.alg, kc) <= 160u * 1024u;
 }
@@ -31,6 +30,8 @@ hipError_t launch_fused_quad(int out, const Geometry& g, const void* V, const Fi
     case 1: return launch_quad_alg<1>(out, g, V, f, x_scale, inv_y, y, s);
     case 2: return launch_quad_alg<2>(out, g, V, f, x_scale, inv_y, y, s);
     case 3: return launch_quad_alg<3>(out, g, V, f, x_scale, inv_y, y, s);
+    case 4: return launch_quad_alg<4>(out, g, V, f, x_scale, inv_y, y, s);
+    case 5: return launch_quad_alg<5>(out, g, V, f, x_scale, inv_y, y, s);
     case 6:
     case 7: return launch_fused_quad_5tap(out, g, V, f, x_scale, inv_y, y, s);
   }

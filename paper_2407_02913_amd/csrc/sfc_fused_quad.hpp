@@ -26,7 +26,8 @@ __global__ __launch_bounds__(NW * 64, WGS) void fused_quad_kernel(
     const int8_t* __restrict__ V, const int8_t* __restrict__ Uf, const float* __restrict__ dqf,
     float x_scale, float inv_y, void* __restrict__ y, Geometry g, int kquads) {
   using Tr = AlgTraits<ALG>;
-  constexpr int P = Tr::P, M = Tr::M, NC = Tr::NC, PG = P / 4;
+  constexpr int P = Tr::P, M = Tr::M, NC = Tr::NC;
+  constexpr int PP = Order<ALG>::PP, PG = PP / 4;  // points padded to whole groups of four
   constexpr int CP = KC * 64;                 // padded input channels
   constexpr int GROUP_BYTES = 4 * 16 * CP;    // V of one group: 4 points x 16 tiles
   constexpr int CHUNKS = GROUP_BYTES / 16;    // 16-byte pieces of a group
@@ -64,9 +65,9 @@ __global__ __launch_bounds__(NW * 64, WGS) void fused_quad_kernel(
   const __amdgpu_buffer_rsrc_t vres =
       __builtin_amdgcn_make_buffer_rsrc((void*)V, 0, (int)(vplane * (unsigned)P), kBufferFlags);
   const __amdgpu_buffer_rsrc_t ures = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)Uf, 0, (int)((unsigned)kquads * (unsigned)(P * CP * 4)), kBufferFlags);
+      (void*)Uf, 0, (int)((unsigned)kquads * (unsigned)(PP * CP * 4)), kBufferFlags);
   const __amdgpu_buffer_rsrc_t dres = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)dqf, 0, (int)((unsigned)kquads * (unsigned)(P * 16)), kBufferFlags);
+      (void*)dqf, 0, (int)((unsigned)kquads * (unsigned)(PP * 16)), kBufferFlags);
   constexpr unsigned esz = OUT == 2 ? 1u : 4u;
   const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
       y, 0, (int)(esz * (unsigned)(g.N * g.Cout) * (unsigned)(g.H * g.W)), kBufferFlags);
@@ -88,8 +89,10 @@ __global__ __launch_bounds__(NW * 64, WGS) void fused_quad_kernel(
   }
   v4i lreg[NL];
   auto load_regs = [&](int pg) {
-    const int p0 = order.pt[4 * pg], p1 = order.pt[4 * pg + 1], p2 = order.pt[4 * pg + 2],
-              p3 = order.pt[4 * pg + 3];
+    // positions without a point (the tail of the last group of an SFC-4 form) re-read point
+    // 0; their filter operand is zero and their products are never taken
+    const int p0 = max(order.pt[4 * pg], 0), p1 = max(order.pt[4 * pg + 1], 0),
+              p2 = max(order.pt[4 * pg + 2], 0), p3 = max(order.pt[4 * pg + 3], 0);
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
       const int r = rsel[i];
@@ -107,7 +110,7 @@ __global__ __launch_bounds__(NW * 64, WGS) void fused_quad_kernel(
   // ---- filter operand and dequantization factors -----------------------------------
   const unsigned a_lane = (unsigned)lane * 16u;
   const unsigned a_wave = (unsigned)kq * (unsigned)(PG * KC * 1024);
-  const unsigned d_lane = (unsigned)kcol * (unsigned)(P * 4);
+  const unsigned d_lane = (unsigned)kcol * (unsigned)(PP * 4);
   v4i aring[RA];
   auto load_a = [&](int s) {  // step s = pg*KC + kc
     aring[s % RA] = __builtin_amdgcn_raw_buffer_load_b128(ures, a_lane, a_wave + (unsigned)s * 1024u, 0);
@@ -177,7 +180,7 @@ inline int quad_waves(int alg, int kc) {
   // the 7x7 forms carry 10x7 partial outputs per pair, the 5x5-filter forms 12x6: they need
   // the 256-register budget
   (void)kc;
-  return alg < 2 ? kQuadWaves6 : 8;
+  return (alg < 2 || alg == 4 || alg == 5) ? kQuadWaves6 : 8;
 }
 
 inline unsigned quad_lds_bytes(int alg, int kc) {
@@ -194,10 +197,11 @@ inline int quad_filter_count_for(const Geometry& g) {
 template <int ALG, int KC, int OUT, bool VEC2>
 inline hipError_t launch_quad_impl(const Geometry& g, const void* V, const FilterViews& f,
                                    float x_scale, float inv_y, void* y, hipStream_t s) {
-  constexpr int NW = ALG < 2 ? kQuadWaves6 : 8;
-  // 6x6 tiles with 3x3 filters: 128 registers per wave, as many workgroups per compute unit
-  // as make 16 waves
-  constexpr int WGS = ALG < 2 ? 16 / NW : 1;
+  // 6x6 tiles with 3x3 filters and the SFC-4 forms: 128 registers per wave, as many
+  // workgroups per compute unit as make 16 waves
+  constexpr bool kSmall = AlgTraits<ALG>::NC <= 8;
+  constexpr int NW = kSmall ? kQuadWaves6 : 8;
+  constexpr int WGS = kSmall ? 16 / NW : 1;
   auto kernel = fused_quad_kernel<ALG, KC, OUT, VEC2, NW, WGS>;
   static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once
   if (!attr_done) {

@@ -216,75 +216,12 @@ __global__ __launch_bounds__(NW * 64) void output_sums_kernel(const int32_t* __r
   store_pairs<ALG, OUT, VEC2>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, g.H, g.W);
 }
 
-// SFC-4(4x4,3x3): one thread per (tile, filter) pair, threads in the order of M's blocks
-// (64 consecutive threads read 256 contiguous bytes per point), the whole output transform
-// in registers, outputs stored straight to NCHW.
-template <int ALG, int OUT>
-__global__ __launch_bounds__(256) void output_sums_pairs_kernel(const int32_t* __restrict__ M,
-                                                                const float* __restrict__ dequant,
-                                                                float x_scale, float inv_y,
-                                                                void* __restrict__ y, Geometry g) {
-  using Tr = AlgTraits<ALG>;
-  constexpr int Mo = Tr::M;
-  const int kquads = g.Kp >> 2;
-  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;  // (tile block, quad, 64)
-  const long long block = idx >> 6;
-  if (block >= (long long)(g.Tp >> 4) * kquads) return;
-  const int l = (int)(idx & 63);
-  const int tb = (int)(block / kquads), kq = (int)(block - (long long)tb * kquads);
-  const int t = tb * 16 + (l >> 2), k = kq * 4 + (l & 3);
-  if (t >= g.T || k >= g.Cout) return;
-  const size_t mplane = (size_t)g.Tp * g.Kp;
-  const int32_t* m = M + (size_t)block * 64 + l;
-  float out[Mo][Mo];
-  output_transform<ALG, float>(
-      [&](int p) { return (float)m[p * mplane] * dequant[p * g.Kp + k]; }, out);
-  const int per = g.th * g.tw;
-  const int n = t / per, rem = t - n * per;
-  const int ti = rem / g.tw, tj = rem - ti * g.tw;
-  const size_t ybase = ((size_t)n * g.Cout + k) * g.H * g.W;
-#pragma unroll
-  for (int o1 = 0; o1 < Mo; ++o1) {
-    const int h = Mo * ti + o1;
-    if (h >= g.H) continue;
-#pragma unroll
-    for (int o2 = 0; o2 < Mo; ++o2) {
-      const int w = Mo * tj + o2;
-      if (w >= g.W) continue;
-      const float v = out[o1][o2] * x_scale;
-      if constexpr (OUT == 2) {
-        constexpr float kMagic = 12582912.0f;
-        float q = __fmaf_rn(v, inv_y, kMagic);
-        q = fminf(fmaxf(q, kMagic), kMagic + 127.0f);
-        ((int8_t*)y)[ybase + (size_t)h * g.W + w] = (int8_t)(__float_as_int(q) - 0x4B400000);
-      } else {
-        ((float*)y)[ybase + (size_t)h * g.W + w] = v;
-      }
-    }
-  }
-}
-
-template <int ALG>
-static hipError_t launch_sums_pairs(int out, const Geometry& g, const int32_t* M,
-                                    const FilterViews& f, float x_scale, float inv_y, void* y,
-                                    hipStream_t s) {
-  const long long threads = (long long)(g.Tp >> 4) * (g.Kp >> 2) * 64;
-  const dim3 grid((unsigned)((threads + 255) / 256));
-  if (out == 2)
-    hipLaunchKernelGGL((output_sums_pairs_kernel<ALG, 2>), grid, dim3(256), 0, s, M, f.dequant,
-                       x_scale, inv_y, y, g);
-  else
-    hipLaunchKernelGGL((output_sums_pairs_kernel<ALG, 0>), grid, dim3(256), 0, s, M, f.dequant,
-                       x_scale, inv_y, y, g);
-  return hipGetLastError();
-}
-
 template <int ALG, int OUT, bool VEC2>
 static hipError_t launch_sums_impl(const Geometry& g, const int32_t* M, const FilterViews& f,
                                    float x_scale, float inv_y, void* y, hipStream_t s) {
   // the 7x7 forms carry 10x7 partial outputs per pair, the 5x5-filter forms 12x6: 8 waves
   // with 256 registers each
-  constexpr int NW = AlgTraits<ALG>::NC == 8 ? 16 : 8;
+  constexpr int NW = AlgTraits<ALG>::NC <= 8 ? 16 : 8;
   const dim3 grid((unsigned)(g.Tp / 16), (unsigned)((g.Cout + 4 * NW - 1) / (4 * NW)));
   hipLaunchKernelGGL((output_sums_kernel<ALG, OUT, VEC2, NW>), grid, dim3(NW * 64), 0, s, M,
                      f.dequant, x_scale, inv_y, y, g);
@@ -315,8 +252,8 @@ hipError_t launch_output_sums(int out, const Geometry& g, const int32_t* M, cons
     case 1: return launch_sums_alg<1>(out, g, M, f, x_scale, inv_y, y, s);
     case 2: return launch_sums_alg<2>(out, g, M, f, x_scale, inv_y, y, s);
     case 3: return launch_sums_alg<3>(out, g, M, f, x_scale, inv_y, y, s);
-    case 4: return launch_sums_pairs<4>(out, g, M, f, x_scale, inv_y, y, s);
-    case 5: return launch_sums_pairs<5>(out, g, M, f, x_scale, inv_y, y, s);
+    case 4: return launch_sums_alg<4>(out, g, M, f, x_scale, inv_y, y, s);
+    case 5: return launch_sums_alg<5>(out, g, M, f, x_scale, inv_y, y, s);
     case 6: return launch_sums_alg<6>(out, g, M, f, x_scale, inv_y, y, s);
     case 7: return launch_sums_alg<7>(out, g, M, f, x_scale, inv_y, y, s);
   }

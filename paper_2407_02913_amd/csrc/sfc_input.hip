@@ -61,10 +61,10 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
 
 // waves per workgroup = tiles per workgroup: the 7x7 forms hold a 9x10 half-transformed
 // patch per tile and need the registers of an 8-wave workgroup
-static int input_waves(int alg) { return alg_tile(alg) == 6 ? 16 : 8; }
+static int input_waves(int alg) { return alg_tile(alg) == 7 ? 8 : 16; }
 
 static bool make_input_plan(const Geometry& g, InputPlan* ip) {
-  if (g.alg > 3) return false;  // SFC-6 forms only
+  if (g.alg > 5) return false;  // 3x3 filters only
   const unsigned vbytes = (unsigned)g.P * 1024u;
   const unsigned lds_max = 160u * 1024u;
   if (vbytes + 16u + 64u > lds_max) return false;
@@ -80,7 +80,7 @@ static bool make_input_plan(const Geometry& g, InputPlan* ip) {
 template <int ALG>
 static hipError_t launch_input_i8_alg(const Geometry& g, const InputPlan& ip, const int8_t* x,
                                       void* V, const float* inv_sx, hipStream_t s) {
-  constexpr int NW = AlgTraits<ALG>::M == 6 ? 16 : 8;
+  constexpr int NW = AlgTraits<ALG>::M == 7 ? 8 : 16;
   auto kernel = input_transform_i8_kernel<ALG, NW>;
   static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once
   if (!attr_done) {
@@ -105,6 +105,8 @@ hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V
     case 1: return launch_input_i8_alg<1>(g, ip, x, V, inv_sx, s);
     case 2: return launch_input_i8_alg<2>(g, ip, x, V, inv_sx, s);
     case 3: return launch_input_i8_alg<3>(g, ip, x, V, inv_sx, s);
+    case 4: return launch_input_i8_alg<4>(g, ip, x, V, inv_sx, s);
+    case 5: return launch_input_i8_alg<5>(g, ip, x, V, inv_sx, s);
   }
   return hipErrorInvalidValue;
 }

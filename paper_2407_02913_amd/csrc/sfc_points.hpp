@@ -103,35 +103,70 @@ SFC_HD constexpr int row4_c0(int r) { return r == 0 ? 0 : r == 1 ? 1 : r == 2 ? 
 SFC_HD constexpr int row4_c1(int r) { return r == 2 ? 3 : -1; }
 SFC_HD constexpr bool row4_is_complex(int r) { return r >= 2 && r <= 4; }
 
+// SFC-4: i-th real row (0, 1, 5, 6) and the component it carries (0, 1, 4, 5)
+SFC_HD constexpr int real_row4(int i) { return i < 2 ? i : i + 3; }
+SFC_HD constexpr int real_comp4(int i) { return i < 2 ? i : i + 2; }
+// SFC-4: canonical index of the kept nested point (r1, r2) of the Hermitian point set
+SFC_HD constexpr int kept_index4(int r1, int r2) {
+  int n = 0;
+  for (int a = 0; a < 7; ++a)
+    for (int b = 0; b < 7; ++b) {
+      if (row4_is_complex(a) && row4_is_complex(b)) continue;
+      if (a == r1 && b == r2) return n;
+      ++n;
+    }
+  return -1;
+}
+
 // Processing order of the fused kernels: canonical point indices grouped by
 // horizontal class (first the real columns with all their vertical rows, then the
-// two complex column groups), so that each group can be collapsed as soon as its
+// complex column groups), so that each group can be collapsed as soon as its
 // products exist.  pt[j] = canonical index of the j-th point, pos = its inverse.
+// The kernels take points in groups of four: PP is P rounded up to a multiple of four,
+// positions P .. PP-1 hold no point (pt = -1; only the SFC-4 forms have any).
 template <int ALG>
 struct Order {
   using Tr = AlgTraits<ALG>;
   static constexpr int P = Tr::P, NR = Tr::NR, NREAL = Tr::NREAL;
-  int pt[P];
+  static constexpr int PP = (P + 3) / 4 * 4;
+  int pt[PP];
   int pos[P];
   constexpr Order() : pt{}, pos{} {
     int n = 0;
-    // real columns: all vertical rows
-    for (int j = 0; j < NREAL; ++j)
-      for (int r1 = 0; r1 < NR; ++r1)
-        pt[n++] = Tr::kHermitian ? kept_index<NR>(r1, real_row(j)) : NR * r1 + real_row(j);
-    // complex column groups
-    for (int g2 = 0; g2 < 2; ++g2) {
+    if constexpr (Tr::kFamily == 4) {
+      // real columns 0, 1, 5, 6: all seven vertical rows
+      for (int j = 0; j < NREAL; ++j)
+        for (int r1 = 0; r1 < NR; ++r1)
+          pt[n++] = Tr::kHermitian ? kept_index4(r1, real_row4(j)) : NR * r1 + real_row4(j);
+      // the complex column group: rows 2, 3, 4 = (a0 + a1, a1, a0)
       if (!Tr::kHermitian) {
         for (int r1 = 0; r1 < NR; ++r1)
-          for (int i = 0; i < 3; ++i) pt[n++] = NR * r1 + 1 + 3 * g2 + i;
+          for (int i = 0; i < 3; ++i) pt[n++] = NR * r1 + 2 + i;
       } else {
         for (int j = 0; j < NREAL; ++j)
-          for (int i = 0; i < 3; ++i) pt[n++] = kept_index<NR>(real_row(j), 1 + 3 * g2 + i);
-        for (int g1 = 0; g1 < 2; ++g1)
-          for (int i = 0; i < 6; ++i) pt[n++] = (NR * NR - 36) + 6 * (2 * g1 + g2) + i;
+          for (int i = 0; i < 3; ++i) pt[n++] = kept_index4(real_row4(j), 2 + i);
+        for (int i = 0; i < 6; ++i) pt[n++] = (NR * NR - 9) + i;
+      }
+    } else {
+      // real columns: all vertical rows
+      for (int j = 0; j < NREAL; ++j)
+        for (int r1 = 0; r1 < NR; ++r1)
+          pt[n++] = Tr::kHermitian ? kept_index<NR>(r1, real_row(j)) : NR * r1 + real_row(j);
+      // complex column groups
+      for (int g2 = 0; g2 < 2; ++g2) {
+        if (!Tr::kHermitian) {
+          for (int r1 = 0; r1 < NR; ++r1)
+            for (int i = 0; i < 3; ++i) pt[n++] = NR * r1 + 1 + 3 * g2 + i;
+        } else {
+          for (int j = 0; j < NREAL; ++j)
+            for (int i = 0; i < 3; ++i) pt[n++] = kept_index<NR>(real_row(j), 1 + 3 * g2 + i);
+          for (int g1 = 0; g1 < 2; ++g1)
+            for (int i = 0; i < 6; ++i) pt[n++] = (NR * NR - 36) + 6 * (2 * g1 + g2) + i;
+        }
       }
     }
     for (int j = 0; j < P; ++j) pos[pt[j]] = j;
+    for (int j = P; j < PP; ++j) pt[j] = -1;
   }
 };
 
@@ -610,6 +645,48 @@ template <int ALG, typename T, typename F>
 SFC_HD void stream_vertical(F&& next, T (&z)[AlgTraits<ALG>::NC][AlgTraits<ALG>::M]) {
   using Tr = AlgTraits<ALG>;
   constexpr int NR = Tr::NR, NC = Tr::NC, NREAL = Tr::NREAL;
+  if constexpr (Tr::kFamily == 4) {
+    // SFC-4: four real columns, then the one complex column group (Eq. DFT4M)
+#pragma unroll
+    for (int j = 0; j < NREAL; ++j) {
+      T col[NR], cc[NC];
+#pragma unroll
+      for (int r1 = 0; r1 < NR; ++r1) col[r1] = next();
+      collapse4_rows(col, cc);
+      inv4_outputs(cc, z[real_comp4(j)]);
+    }
+    T c0[NC], c1[NC];
+    if constexpr (!Tr::kHermitian) {
+      T h0[NR], h1[NR];
+#pragma unroll
+      for (int r1 = 0; r1 < NR; ++r1) {
+        const T m2 = next(), m1 = next(), m0 = next();  // rows a0 + a1, a1, a0
+        h0[r1] = m0 - m1;
+        h1[r1] = m2 - m0 - m1;
+      }
+      collapse4_rows(h0, c0);
+      collapse4_rows(h1, c1);
+    } else {
+#pragma unroll
+      for (int j = 0; j < NREAL; ++j) {
+        const T m2 = next(), m1 = next(), m0 = next();
+        c0[real_comp4(j)] = m0 - m1;
+        c1[real_comp4(j)] = m2 - m0 - m1;
+      }
+      T m[6];
+#pragma unroll
+      for (int i = 0; i < 6; ++i) m[i] = next();
+      const T uo0 = m[0] - m[1], uo1 = m[2] - m[0] - m[1];
+      const T vo0 = m[3] - m[4], vo1 = m[5] - m[3] - m[4];
+      c0[2] = Half<T>::apply(uo0 + vo0);  // o00
+      c0[3] = Half<T>::apply(uo1 + vo1);  // o10
+      c1[2] = Half<T>::apply(uo1 - vo1);  // o01
+      c1[3] = Half<T>::apply(vo0 - uo0);  // o11
+    }
+    inv4_outputs(c0, z[2]);
+    inv4_outputs(c1, z[3]);
+    return;
+  } else {
 #pragma unroll
   for (int j = 0; j < NREAL; ++j) {
     T col[NR], cc[NC];
@@ -649,6 +726,7 @@ SFC_HD void stream_vertical(F&& next, T (&z)[AlgTraits<ALG>::NC][AlgTraits<ALG>:
     inv_outputs(c0, z[1 + 2 * g2]);
     inv_outputs(c1, z[2 + 2 * g2]);
   }
+  }
 }
 
 // Output row o1 of the pair: the inverse along the horizontal axis (times 36 overall).
@@ -659,7 +737,10 @@ SFC_HD void stream_row(const T (&z)[AlgTraits<ALG>::NC][AlgTraits<ALG>::M], int 
   T zc[NC];
 #pragma unroll
   for (int b = 0; b < NC; ++b) zc[b] = z[b][o1];
-  inv_outputs(zc, out);
+  if constexpr (AlgTraits<ALG>::kFamily == 4)
+    inv4_outputs(zc, out);
+  else
+    inv_outputs(zc, out);
 }
 
 }  // namespace sfc

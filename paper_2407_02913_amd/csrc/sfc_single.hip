@@ -153,7 +153,7 @@ __global__ __launch_bounds__(NW * 64) void single_conv_kernel(
 template <int ALG>
 __global__ __launch_bounds__(64) void repack_filter_kernel(const int8_t* __restrict__ U,
                                                            int8_t* __restrict__ Uf, Geometry g) {
-  constexpr int PG = AlgTraits<ALG>::P / 4;
+  constexpr int PG = Order<ALG>::PP / 4;
   constexpr Order<ALG> order{};
   const int KC = g.Cp >> 6;
   const int kq = blockIdx.x / (PG * KC), rem = blockIdx.x - kq * (PG * KC);
@@ -162,8 +162,8 @@ __global__ __launch_bounds__(64) void repack_filter_kernel(const int8_t* __restr
   const int i = l & 15, kseg = l >> 4;
   const int p = order.pt[4 * pg + (i & 3)];
   const int k = 4 * kq + (i >> 2);
-  v4i val = {0, 0, 0, 0};
-  if (k < g.Kp) val = *(const v4i*)(U + ((size_t)p * g.Kp + k) * g.Cp + 64 * kc + 16 * kseg);
+  v4i val = {0, 0, 0, 0};  // also for the positions of the last group that hold no point
+  if (k < g.Kp && p >= 0) val = *(const v4i*)(U + ((size_t)p * g.Kp + k) * g.Cp + 64 * kc + 16 * kseg);
   *(v4i*)(Uf + ((size_t)blockIdx.x * 64 + l) * 16) = val;
 }
 
@@ -199,12 +199,14 @@ bool single_supported(const Geometry& g) {
 
 hipError_t launch_repack_filter(const Geometry& g, int filters, const void* U, void* Uf,
                                 hipStream_t s) {
-  const dim3 grid((unsigned)((filters / 4) * (g.P / 4) * (g.Cp / 64)));
+  const dim3 grid((unsigned)((filters / 4) * ((g.P + 3) / 4) * (g.Cp / 64)));
   switch (g.alg) {
     case 0: hipLaunchKernelGGL(repack_filter_kernel<0>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
     case 1: hipLaunchKernelGGL(repack_filter_kernel<1>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
     case 2: hipLaunchKernelGGL(repack_filter_kernel<2>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
     case 3: hipLaunchKernelGGL(repack_filter_kernel<3>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
+    case 4: hipLaunchKernelGGL(repack_filter_kernel<4>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
+    case 5: hipLaunchKernelGGL(repack_filter_kernel<5>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
     case 6: hipLaunchKernelGGL(repack_filter_kernel<6>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
     case 7: hipLaunchKernelGGL(repack_filter_kernel<7>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
     default: return hipErrorInvalidValue;
@@ -212,8 +214,8 @@ hipError_t launch_repack_filter(const Geometry& g, int filters, const void* U, v
   return hipGetLastError();
 }
 
-// processing position -> canonical point index, for the host-built tables
-void single_point_order(int alg, int* pt /*[P]*/) {
+// processing position -> canonical point index (-1: no point), for the host-built tables
+void single_point_order(int alg, int* pt /*[P rounded up to a multiple of 4]*/) {
   auto copy = [&](const auto& o) {
     for (int j = 0; j < (int)(sizeof(o.pt) / sizeof(o.pt[0])); ++j) pt[j] = o.pt[j];
   };
@@ -222,9 +224,11 @@ void single_point_order(int alg, int* pt /*[P]*/) {
     case 1: { constexpr Order<1> o{}; copy(o); break; }
     case 2: { constexpr Order<2> o{}; copy(o); break; }
     case 3: { constexpr Order<3> o{}; copy(o); break; }
+    case 4: { constexpr Order<4> o{}; copy(o); break; }
+    case 5: { constexpr Order<5> o{}; copy(o); break; }
     case 6: { constexpr Order<6> o{}; copy(o); break; }
     case 7: { constexpr Order<7> o{}; copy(o); break; }
-    default: break;  // no fused kernel for the other forms
+    default: break;
   }
 }
 

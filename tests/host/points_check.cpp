@@ -5,6 +5,8 @@
 //   B <alg> <p> <NI*NI ints>   input transform row p  (impulse responses)
 //   G <alg> <p> <R*R ints>     filter transform row p
 //   A <alg> <p> <M*M ints>     output transform row p (times 36; times 16 for 4x4)
+//   S <alg> <p> <M*M ints>     the same row through the streaming form of the fused kernels
+//                              (products fed in processing order, stream_vertical + stream_row)
 #include <cmath>
 #include <cstdio>
 #include <vector>
@@ -52,6 +54,23 @@ void dump() {
     output_transform<ALG, float>([&](int p) { return p == q ? 3.0f : 0.0f; }, out);
     for (int o = 0; o < M * M; ++o) A[q][o] = (int)std::lround(out[o / M][o % M] / 3.0f);
   }
+  constexpr Order<ALG> order{};
+  for (int q = 0; q < P; ++q) {
+    int j = 0;
+    auto next = [&]() -> float { return order.pt[j++] == q ? 3.0f : 0.0f; };
+    float z[NC][M];
+    stream_vertical<ALG, float>(next, z);
+    std::printf("S %d %d", ALG, q);
+    for (int o1 = 0; o1 < M; ++o1) {
+      float out[M];
+      stream_row<ALG, float>(z, o1, out);
+      for (int o2 = 0; o2 < M; ++o2) std::printf(" %d", (int)std::lround(out[o2] / 3.0f));
+    }
+    std::printf("\n");
+    if (q == 0 && j != P) std::printf("S %d -1 %d\n", ALG, j);  // must consume exactly P products
+  }
+  for (int j = P; j < Order<ALG>::PP; ++j)
+    if (order.pt[j] != -1) std::printf("S %d -2 %d\n", ALG, j);
   for (int p = 0; p < P; ++p) {
     std::printf("B %d %d", ALG, p);
     for (int v : B[p]) std::printf(" %d", v);

@@ -46,7 +46,7 @@ def rel_err(y, ref):
 
 
 ALGS = ["6x6_p88", "6x6_p100", "7x7_p132", "7x7_p144"]
-ALGS_STAGED = ALGS + ["4x4_p46", "4x4_p49"]  # SFC-4(4x4,3x3) runs on the staged path
+ALGS_STAGED = ALGS + ["4x4_p46", "4x4_p49"]  # SFC-4(4x4,3x3): staged and fused paths
 
 
 @pytest.mark.parametrize("alg", ALGS_STAGED)
@@ -312,7 +312,8 @@ FULL = ["resnet56", "resnet28", "resnet14", "resnet7"]
 @pytest.mark.parametrize("alg", ["4x4_p46", "4x4_p49"])
 def test_sfc4_full_size_and_int8_output(binding, alg):
     """SFC-4(4x4,3x3) on resnet28 (4x4 tiles divide 28): every tap and output element; then the
-    int8 + ReLU epilogue; the fused and single-kernel paths do not take the 4x4 forms."""
+    int8 + ReLU epilogue on the staged and fused paths; the single-kernel path does not take the
+    4x4 forms."""
     shape = synth.LAYERS["resnet28"]
     print("case sfc4 full", alg, flush=True)
     d = synth.make_layer(shape)
@@ -326,13 +327,13 @@ def test_sfc4_full_size_and_int8_output(binding, alg):
         assert np.array_equal(taps[tap].astype(np.int64), taps_ref[tap]), tap
     assert rel_err(y, y_ref) <= F32_TOL
     y_scale = float(np.float32(max(y_ref.max(), 1e-6) / 127.0 * 0.8))
-    y8 = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg, out="i8",
-                        sx=sx, sw=sw, y_scale=y_scale)
-    assert check_i8_against_oracle(y8, y_ref, y_scale) < 1e-3
-    for path in ("fused", "single"):
-        with pytest.raises(binding.SfcError) as e:
-            binding.Plan(1, 16, 16, 8, 8, alg=alg, path=path)
-        assert e.value.code == 2
+    for path in ("staged", "fused"):
+        y8 = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg, out="i8",
+                            path=path, sx=sx, sw=sw, y_scale=y_scale)
+        assert check_i8_against_oracle(y8, y_ref, y_scale) < 1e-3
+    with pytest.raises(binding.SfcError) as e:
+        binding.Plan(1, 16, 16, 8, 8, alg=alg, path="single")
+    assert e.value.code == 2
 
 
 @pytest.mark.parametrize("name", FULL)
@@ -387,7 +388,7 @@ FUSED_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("alg", ALGS)
+@pytest.mark.parametrize("alg", ALGS_STAGED)
 @pytest.mark.parametrize("shape", FUSED_SHAPES)
 def test_fused_path_matches_oracle(binding, shape, alg):
     x, w, xs, ws = uniform_case(shape, 400 + len(alg) + sum(shape))
@@ -482,7 +483,7 @@ def test_fused_path_rejects_unsupported_channel_counts(binding):
     assert e.value.code == 2
 
 
-@pytest.mark.parametrize("alg", ["6x6_p88", "7x7_p132"])
+@pytest.mark.parametrize("alg", ["6x6_p88", "7x7_p132", "4x4_p46"])
 @pytest.mark.parametrize("name", FULL)
 def test_full_size_fused_against_oracle(binding, name, alg):
     """The launch configuration bench.py times, every output element (V as well)."""

@@ -164,6 +164,8 @@ def test_kernel_add_networks_realize_the_oracle_matrices(kernel_maps, alg_id, al
     assert np.array_equal(kernel_maps[("B", alg_id)], b2)
     assert np.array_equal(kernel_maps[("G", alg_id)], g2)
     assert np.array_equal(kernel_maps[("A", alg_id)], a2)
+    # the streaming form of the fused kernels (processing order + per-group collapse)
+    assert np.array_equal(kernel_maps[("S", alg_id)], a2)
 
 
 def test_bench_operation_counts_match_the_add_networks(tmp_path):
