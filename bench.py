@@ -26,7 +26,7 @@ VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 # Arithmetic of the add networks per item, counted by tests/host/op_count.cpp:
 # algorithm -> (additions per input (tile, channel), operations per output (tile, filter)).
 ADD_NETWORK_OPS = {"6x6_p88": (304, 438), "6x6_p100": (300, 422), "7x7_p132": (379, 580),
-                   "7x7_p144": (375, 564)}
+                   "7x7_p144": (375, 564), "4x4_p46": (110, 158), "4x4_p49": (111, 159)}
 
 
 def vector_ops(shape, alg, P, tiles):
@@ -194,10 +194,9 @@ def main():
     shape = synth.LAYERS[args.workload]
     ksize = binding.KERNEL_SIZE[args.alg]
     data = synth.make_layer(shape, kernel=ksize)
-    # one kernel where the layer allows it (SFC-6 with 3x3 filters, Cin <= 64), else input
-    # transform + fused product/output
-    one_kernel = shape.Cin <= 64 and ksize == 3 and not args.alg.startswith("4x4")
-    path = args.path or ("single" if one_kernel else binding.DEFAULT_PATH)
+    # one kernel where the layer allows it (3x3 filters, Cin <= 64), else input transform +
+    # fused product/output
+    path = args.path or ("single" if shape.Cin <= 64 and ksize == 3 else binding.DEFAULT_PATH)
     direct_ops = shape.direct_ops * ksize * ksize // 9
 
     plan = binding.Plan(shape.N, shape.Cin, shape.Cout, shape.H, shape.W, alg=args.alg,

@@ -46,16 +46,19 @@ struct SinglePlan {
 
 constexpr int kWaves6 = 16;  // waves per workgroup for the 6x6 forms
 
-template <int ALG, int OUT, bool VEC2, int NW>
-__global__ __launch_bounds__(NW * 64) void single_conv_kernel(
+// WGS: workgroups per compute unit the register budget is cut for (2 for the SFC-4 forms,
+// whose 48 KB of V and 24 partial outputs per pair leave room for a second workgroup, so
+// that one workgroup's loads and stores overlap the other's arithmetic).
+template <int ALG, int OUT, bool VEC2, int NW, int WGS>
+__global__ __launch_bounds__(NW * 64, WGS) void single_conv_kernel(
     const int8_t* __restrict__ x, const int8_t* __restrict__ Uf, const float* __restrict__ dqf,
     const float* __restrict__ inv_sx, float x_scale, float inv_y, void* __restrict__ y, Geometry g,
     SinglePlan sp) {
   using Tr = AlgTraits<ALG>;
-  constexpr int P = Tr::P, M = Tr::M, NC = Tr::NC, PG = P / 4;
+  constexpr int P = Tr::P, M = Tr::M, NC = Tr::NC;
+  constexpr int PP = Order<ALG>::PP, PG = PP / 4;  // points padded to whole groups of four
   constexpr int SPW = 16 / NW;  // passes per wave over tiles / filter quads
   static_assert(NW == 8 || NW == 16, "8 or 16 waves");
-  static_assert(P % 4 == 0, "points are processed in groups of four");
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -80,9 +83,9 @@ __global__ __launch_bounds__(NW * 64) void single_conv_kernel(
   // ---- 3. products + output transform: lane = (tile l%16, filter 4*kq + l/16) ------
   const int kfilters = sp.kgroups * 64;
   const __amdgpu_buffer_rsrc_t ures = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)Uf, 0, (int)((unsigned)kfilters * (unsigned)(P * 64)), kBufferFlags);
+      (void*)Uf, 0, (int)((unsigned)kfilters * (unsigned)(PP * 64)), kBufferFlags);
   const __amdgpu_buffer_rsrc_t dres = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)dqf, 0, (int)((unsigned)kfilters * (unsigned)(P * 4)), kBufferFlags);
+      (void*)dqf, 0, (int)((unsigned)kfilters * (unsigned)(PP * 4)), kBufferFlags);
   constexpr unsigned esz = OUT == 2 ? 1u : 4u;
   const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
       y, 0, (int)(esz * (unsigned)(g.N * g.Cout) * (unsigned)(H * W)), kBufferFlags);
@@ -96,7 +99,7 @@ __global__ __launch_bounds__(NW * 64) void single_conv_kernel(
     const int kcol = kq * 4 + (lane >> 4);            // this lane's filter
     const unsigned a_lane = (unsigned)lane * 16u;
     const unsigned a_wave = (unsigned)kq * (unsigned)(PG * 1024);
-    const unsigned d_lane = (unsigned)kcol * (unsigned)(P * 4);
+    const unsigned d_lane = (unsigned)kcol * (unsigned)(PP * 4);
     // Software pipeline over the points: call j of next() issues the LDS read of
     // point j+2's V operand and the MFMA of point j+1, then converts the accumulator
     // of point j.  The filter operand and the dequantization factors of group g
@@ -172,13 +175,14 @@ __global__ __launch_bounds__(64) void repack_filter_kernel(const int8_t* __restr
 static int single_waves(int alg) { return alg_tile(alg) == 6 ? kWaves6 : 8; }
 
 static bool make_single_plan(const Geometry& g, SinglePlan* sp) {
-  if (g.Cp != 64 || g.alg > 3) return false;  // SFC-6 forms only
+  if (g.Cp != 64 || g.alg > 5) return false;  // 3x3 filters only
   const int M = alg_tile(g.alg);
   // LDS: the staged rows of the rectangle (later overwritten by V), the per-wave output
   // staging blocks, the per-tile store table
   const unsigned vbytes = (unsigned)g.P * 1024u;
   const unsigned sbytes = (unsigned)single_waves(g.alg) * 64u * (unsigned)M * 4u + 256u;
-  const unsigned lds_max = 160u * 1024u;
+  // the SFC-4 forms leave half of the 160 KB to a second workgroup on the compute unit
+  const unsigned lds_max = (M == 4 ? 80u : 160u) * 1024u;
   if (vbytes + 16u + sbytes > lds_max) return false;
   if (!make_tile_rect(g, lds_max - 16u - sbytes, &sp->tr)) return false;
   sp->kgroups = (g.Cout + 63) / 64;
@@ -187,7 +191,7 @@ static bool make_single_plan(const Geometry& g, SinglePlan* sp) {
   sp->lds_bytes = sp->stage_off + sbytes;
   const long long xb = (long long)g.N * g.Cin * g.H * g.W;
   const long long yb = 4ll * g.N * g.Cout * g.H * g.W;
-  const long long ub = (long long)sp->kgroups * 64 * g.P * 64;
+  const long long ub = (long long)sp->kgroups * 64 * (g.P + 3) * 64;
   const long long lim = 1ll << 31;
   return sp->lds_bytes <= lds_max && xb < lim && yb < lim && ub < lim;
 }
@@ -236,7 +240,7 @@ template <int ALG, int OUT, bool VEC2, int NW>
 static hipError_t launch_single_impl(const Geometry& g, const SinglePlan& sp, const int8_t* x,
                                      const FilterViews& f, float x_scale, float inv_y, void* y,
                                      hipStream_t s) {
-  auto kernel = single_conv_kernel<ALG, OUT, VEC2, NW>;
+  auto kernel = single_conv_kernel<ALG, OUT, VEC2, NW, AlgTraits<ALG>::M == 4 ? 2 : 1>;
   static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once
   if (!attr_done) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -279,6 +283,8 @@ hipError_t launch_single_conv(int out, const Geometry& g, const int8_t* x, const
     case 1: return launch_single_alg<1>(out, g, sp, x, f, x_scale, inv_y, y, s);
     case 2: return launch_single_alg<2>(out, g, sp, x, f, x_scale, inv_y, y, s);
     case 3: return launch_single_alg<3>(out, g, sp, x, f, x_scale, inv_y, y, s);
+    case 4: return launch_single_alg<4>(out, g, sp, x, f, x_scale, inv_y, y, s);
+    case 5: return launch_single_alg<5>(out, g, sp, x, f, x_scale, inv_y, y, s);
   }
   return hipErrorInvalidValue;
 }

@@ -25,6 +25,10 @@ template <>
 struct Third<Op> {
   static Op apply(Op v) { ++g_ops; return Op(v.v / 3.0); }
 };
+template <>
+struct Half<Op> {
+  static Op apply(Op v) { ++g_ops; return Op(v.v / 2.0); }
+};
 }  // namespace sfc
 
 using namespace sfc;
@@ -62,5 +66,7 @@ int main() {
   count<1>();
   count<2>();
   count<3>();
+  count<4>();
+  count<5>();
   return 0;
 }

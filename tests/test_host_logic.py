@@ -177,7 +177,7 @@ def test_bench_operation_counts_match_the_add_networks(tmp_path):
     subprocess.run(["/opt/rocm/bin/hipcc", "--cuda-host-only", "-O1", "-std=c++17", src, "-o", str(exe)],
                    check=True, capture_output=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
-    names = ["6x6_p88", "6x6_p100", "7x7_p132", "7x7_p144"]
+    names = ["6x6_p88", "6x6_p100", "7x7_p132", "7x7_p144", "4x4_p46", "4x4_p49"]
     for line in out.splitlines():
         alg, pts, in_adds, out_ops = (int(v) for v in line.split())
         assert pts == oracle.multiplications_per_tile(names[alg])
