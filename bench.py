@@ -55,13 +55,17 @@ def stage_bytes(shape, P, tiles, path):
 
 def pick_variant(shape, alg=None, path=None):
     """Tile size and path per layer shape, from the per-layer timings on one MI355X: the
-    single-kernel path with 6x6 tiles where it exists (Cin <= 64); else 6x6 tiles while the
-    feature map is large (28x28: no ragged tiles to speak of, the cheaper transforms win);
+    single-kernel path where it exists (Cin <= 64), with SFC-4's 4x4 tiles when they divide
+    the feature map (no ragged tiles, two workgroups per compute unit); else 6x6 tiles while
+    the feature map is large (28x28: no ragged tiles to speak of, the cheaper transforms win);
     7x7 tiles on 14x14 and 7x7 maps (no ragged tiles at all), with the products as batched
     GEMMs through HBM once there are too few tiles for the fused kernel's operand stream
     (7x7 maps, 512 channels)."""
     if alg is None:
-        alg = "6x6_p88" if shape.H >= 28 else "7x7_p132"
+        if shape.Cin <= 64 and shape.H % 4 == 0 and shape.W % 4 == 0:
+            alg = "4x4_p46"
+        else:
+            alg = "6x6_p88" if shape.H >= 28 else "7x7_p132"
     if path is None:
         if shape.Cin <= 64:
             path = "single"
@@ -166,7 +170,8 @@ def main():
     ap.add_argument("--path", default=None, choices=[None, "staged", "fused", "single"])
     ap.add_argument("--alg", default=None,
                     help="6x6_p88 | 6x6_p100 | 7x7_p132 | 7x7_p144 | 4x4_p46 | 4x4_p49, or with 5x5 filters "
-                         "6x6_5x5_p184 | 6x6_5x5_p196 (default: 6x6_p88; per layer for the stack)")
+                         "6x6_5x5_p184 | 6x6_5x5_p196 (default: 4x4_p46 where Cin <= 64 and 4 divides the "
+                         "feature map, else 6x6_p88; per layer for the stack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--streams", type=int, default=3,
                     help="HIP streams the steps are dealt to round-robin (independent batches overlap)")
@@ -180,8 +185,11 @@ def main():
 
     if args.workload == "stack":
         return run_stack(args)
-    if args.alg is None:
-        args.alg = "6x6_p88"
+    if args.alg is None:  # the fastest form for the layer (one layer: the paths are chosen below)
+        from paper_2407_02913_amd import synth as _synth
+
+        _shape = _synth.LAYERS[args.workload]
+        args.alg = "4x4_p46" if _shape.Cin <= 64 and _shape.H % 4 == 0 and _shape.W % 4 == 0 else "6x6_p88"
 
     import numpy as np
     import torch
@@ -327,7 +335,7 @@ def main():
     dominant = max(stage_us, key=stage_us.get)
     achieved = bytes_per[dominant] / (stage_us[dominant] * 1e-6) / 1e9
     traffic = None
-    tfile = os.path.join(ROOT, "profiles", f"traffic_{dominant}_{args.workload}.txt")
+    tfile = os.path.join(ROOT, "profiles", f"traffic_{dominant}_{args.workload}_{args.alg}.txt")
     if os.path.exists(tfile):
         for line in open(tfile):
             if line.startswith("hbm_bytes_per_launch"):
