@@ -46,11 +46,12 @@ struct SinglePlan {
 
 constexpr int kWaves6 = 16;  // waves per workgroup for the 6x6 forms
 
-// WGS: workgroups per compute unit the register budget is cut for (2 for the SFC-4 forms,
-// whose 48 KB of V and 24 partial outputs per pair leave room for a second workgroup, so
-// that one workgroup's loads and stores overlap the other's arithmetic).
+// WGS: workgroups per compute unit the register budget is cut for (the second launch bound
+// counts waves per SIMD: NW * WGS / 4).  2 for the SFC-4 forms, whose 48 KB of V and 24
+// partial outputs per pair leave room for a second workgroup, so that one workgroup's
+// loads and stores overlap the other's arithmetic.
 template <int ALG, int OUT, bool VEC2, int NW, int WGS>
-__global__ __launch_bounds__(NW * 64, WGS) void single_conv_kernel(
+__global__ __launch_bounds__(NW * 64, NW * WGS / 4) void single_conv_kernel(
     const int8_t* __restrict__ x, const int8_t* __restrict__ Uf, const float* __restrict__ dqf,
     const float* __restrict__ inv_sx, float x_scale, float inv_y, void* __restrict__ y, Geometry g,
     SinglePlan sp) {
