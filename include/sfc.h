@@ -58,8 +58,7 @@ typedef enum {
   SFC_ALG_7X7_P132 = 2, /* SFC-6(7x7,3x3) (Sec. 4.2, Appendix A), Hermitian form: 132 multiplications */
   SFC_ALG_7X7_P144 = 3, /* SFC-6(7x7,3x3), nested form: 144 multiplications */
   /* SFC-4(4x4,3x3) (Appendix A, four-point symbolic DFT, s = j): 46 multiplications per
-   * 4x4 tile with Hermitian symmetry fully used, 49 in the nested form.  Staged and fused
-   * paths. */
+   * 4x4 tile with Hermitian symmetry fully used, 49 in the nested form.  Every path. */
   SFC_ALG_4X4_P46 = 4,
   SFC_ALG_4X4_P49 = 5,
   /* SFC-6(6x6,5x5) (Appendix A): 5x5 filters w[Cout,Cin,5,5], zero padding 2, 6x6 output
