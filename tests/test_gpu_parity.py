@@ -83,7 +83,7 @@ def test_requant_mode_taps_bit_exact_and_output_close(binding, shape, alg):
 
 @pytest.mark.parametrize("bits", [4, 6])
 @pytest.mark.parametrize("path", ["staged", "fused", "single"])
-@pytest.mark.parametrize("alg", ["6x6_p88", "7x7_p144"])
+@pytest.mark.parametrize("alg", ["6x6_p88", "7x7_p144", "4x4_p46"])
 def test_sub_int8_transform_domain(binding, alg, path, bits):
     """Transform-domain operands rounded to 4 or 6 bits (carried in int8 lanes), Sec. 6:
     taps bit-exact, output within tolerance, and the library's own abs-max calibration
@@ -513,18 +513,20 @@ def check_i8_against_oracle(y8, y_ref, y_scale):
     return float(np.count_nonzero(diff)) / diff.size
 
 
+@pytest.mark.parametrize("alg", ["6x6_p88", "4x4_p46"])
 @pytest.mark.parametrize("path", ["staged", "fused", "single"])
 @pytest.mark.parametrize("shape", [(1, 16, 16, 32, 32), (2, 3, 5, 14, 14), (1, 4, 4, 7, 7), (3, 70, 40, 9, 20)])
-def test_int8_relu_output(binding, shape, path):
+def test_int8_relu_output(binding, shape, path, alg):
     if path == "single" and shape[1] > 64:
         shape = (shape[0], 50, *shape[2:])
     x, w, xs, ws = uniform_case(shape, 600 + sum(shape))
-    print("case i8", shape, path, flush=True)
-    sx = oracle.calibrate_act_scales(x)
-    sw = oracle.calibrate_filter_scales(w)
-    y_ref = oracle.conv_requant(x, w, sx, sw, xs, ws)
+    print("case i8", shape, path, alg, flush=True)
+    sx = oracle.calibrate_act_scales(x, alg)
+    sw = oracle.calibrate_filter_scales(w, alg)
+    y_ref = oracle.conv_requant(x, w, sx, sw, xs, ws, alg)
     y_scale = float(np.float32(max(y_ref.max(), 1e-6) / 127.0 * 0.8))  # 0.8: some values clamp at 127
-    y8 = binding.conv2d(x, w, xs, ws, mode="requant", path=path, out="i8", sx=sx, sw=sw, y_scale=y_scale)
+    y8 = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path=path, out="i8", sx=sx, sw=sw,
+                        y_scale=y_scale)
     assert y8.dtype == np.int8 and y8.min() == 0 and y8.max() == 127
     frac = check_i8_against_oracle(y8, y_ref, y_scale)
     assert frac < 1e-3
