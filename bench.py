@@ -37,6 +37,7 @@ def vector_ops(shape, alg, P, tiles):
     in_adds, out_ops = ADD_NETWORK_OPS[alg]
     return tiles * (shape.Cin * (in_adds + 3 * P) + shape.Cout * (out_ops + 2 * P + m * m))
 ROTATE_BYTES = 640 << 20  # footprint of the rotating buffer sets (> 256 MB memory-side cache)
+RAMP_MS = 120.0  # untimed load before every timed region (see ramp() in main)
 
 
 def stage_bytes(shape, P, tiles, path):
@@ -133,6 +134,10 @@ def run_stack(args):
         for _ in range(args.warmup):
             step(streams)
         torch.cuda.synchronize()
+        t_end = time.perf_counter() + RAMP_MS * 1e-3  # untimed load: the clocks of an idle GPU ramp up
+        while time.perf_counter() < t_end:
+            step(streams)
+            torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
             step(streams)
@@ -224,6 +229,8 @@ def main():
     ybytes = 4 * shape.N * shape.Cout * shape.H * shape.W
     per_set = x_host.numel() + plan.workspace_bytes + ybytes
     nsets = args.buffer_sets if args.buffer_sets > 0 else max(2, min(24, -(-ROTATE_BYTES // per_set)))
+    # a whole number of sets per stream: a set is then always used on the same stream
+    nsets = -(-nsets // max(1, args.streams)) * max(1, args.streams)
     sets = []
     for _ in range(nsets):
         sets.append((x_host.cuda(), binding.device_buffer(plan.workspace_bytes),
@@ -237,22 +244,61 @@ def main():
 
     # Whole-job throughput: every step is an independent batch with its own buffers, so
     # consecutive steps are dealt to a few streams and the device overlaps one batch's
-    # input transform with another's product/output kernel.  Timed with the host clock
-    # between two device synchronizations.
+    # kernels with another's.  The K timed steps are launched from the host between two
+    # device synchronizations and timed with the host clock; beside that figure, the same K
+    # steps captured once into a HIP graph with one branch per stream (kernel launches only)
+    # and replayed.
     nstreams = max(1, min(args.streams, nsets))
     streams = [torch.cuda.Stream() for _ in range(nstreams)]
+
+    def ramp(mask=binding.STAGE_ALL, on_streams=True):
+        """Untimed steps until the device has been busy for RAMP_MS: the clocks of an idle GPU
+        take some tens of milliseconds of load to come up (the first 500 steps of this layer run
+        at 21 us, the steady state at 16 us), so every timed region starts from a busy device."""
+        t_end = time.perf_counter() + RAMP_MS * 1e-3
+        i = 0
+        while time.perf_counter() < t_end:
+            for _ in range(50):
+                step(i, mask, stream=streams[i % nstreams] if on_streams else None)
+                i += 1
+            torch.cuda.synchronize()
+
     for i in range(args.warmup):
         step(i, stream=streams[i % nstreams])
     torch.cuda.synchronize()
+    ramp()
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(i, stream=streams[i % nstreams])
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    job_graph_ms = None
+    try:
+        side = torch.cuda.Stream()
+        job = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(job, stream=side):
+                for b in streams:
+                    b.wait_stream(side)
+                for i in range(args.steps):
+                    step(i, stream=streams[i % nstreams])
+                for b in streams:
+                    side.wait_stream(b)
+        job.replay()  # untimed: the first replay uploads the graph
+        torch.cuda.synchronize()
+        ramp()  # the capture left the device idle
+        t0 = time.perf_counter()
+        job.replay()
+        torch.cuda.synchronize()
+        job_graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        del job
+    except Exception as exc:  # a measurement aid, never the product path
+        print(f"graph of the timed steps not captured: {exc}", file=sys.stderr)
 
     # latency of one step alone: same steps back to back on one stream, HIP events
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
+    ramp(on_streams=False)
     e0.record()
     for i in range(args.steps):
         step(i)
@@ -274,6 +320,7 @@ def main():
         for _ in range(3):
             graph.replay()
         torch.cuda.synchronize()
+        ramp(on_streams=False)
         reps = max(2, args.steps // nrep)
         e0.record()
         for _ in range(reps):
@@ -284,6 +331,7 @@ def main():
     except Exception as exc:  # the capture is a measurement aid, never the product path
         print(f"graph replay skipped: {exc}", file=sys.stderr)
     torch.cuda.synchronize()
+    ramp(on_streams=False)
     for _ in range(10):
         step(0)
     torch.cuda.synchronize()
@@ -307,9 +355,7 @@ def main():
     launches = max(50, min(args.steps, 400))
     stage_us = {}
     for name, mask in stages.items():
-        for i in range(10):
-            step(i, mask)
-        torch.cuda.synchronize()
+        ramp(mask, on_streams=False)
         e0.record()
         for i in range(launches):
             step(i, mask)
@@ -374,6 +420,8 @@ def main():
                    "algorithm": f"SFC-{4 if args.alg.startswith('4x4') else 6}({args.alg[:3]},{ksize}x{ksize}) P={plan.P}",
                    "mode": "requant-int8 transform domain",
                    "path": path, "buffer_sets": nsets, "streams": nstreams,
+                   "untimed_load_before_each_timed_region_ms": RAMP_MS,
+                   "same_steps_as_one_graph_ms_per_step": None if job_graph_ms is None else round(job_graph_ms, 5),
                    "single_stream_ms_per_step": round(single_stream_ms, 5),
                    "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
                    "warm_single_stream_ms_per_step": round(warm_ms, 5)},
