@@ -3,7 +3,8 @@
 //
 // A workgroup owns 16 consecutive tiles and 4*NW filters (wave w: filters 4w..4w+3,
 // lane l: the pair (tile l%16, filter 4w + l/16)).  Points are taken in groups of four
-// in the processing order of Order<ALG>.  For a group, the V rows of the 16 tiles
+// in the processing order of Order<ALG> (the SFC-4 forms pad their 46 / 49 points to
+// 48 / 52 positions whose filter operand is zero and whose products are never taken).  For a group, the V rows of the 16 tiles
 // (4 points x 16 tiles x Cin bytes) are copied by the whole workgroup from HBM into
 // one of two LDS buffers, already laid out as MFMA operands, while the previous
 // group is being multiplied; one barrier per group.  The filter operand of a group

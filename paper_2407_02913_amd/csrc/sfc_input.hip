@@ -1,5 +1,6 @@
 // Input-tile transform V = B^T x B with transform-domain requantization to int8,
-// the HBM-facing first stage of the two-kernel path (gfx950).
+// the HBM-facing first stage of the two-kernel path (gfx950), for the 3x3-filter
+// algorithms (the 5x5-filter forms use the generic kernel of sfc_kernels.hip).
 //
 // A workgroup owns up to NW tiles (a rectangle of S strips x tlw tile columns, or whole
 // images of a small feature map), one per wave, and 64 input channels:

@@ -2,9 +2,14 @@
 // transform, transform-domain products and output transform without V or M ever
 // leaving the compute unit.
 //
-// A workgroup of 16 waves (8 for the 7x7 forms, each wave then doing two passes)
-// owns a rectangle of up to 16 tiles (S strips x tlw tile columns; a strip = one
-// row of tiles of one image), all input channels and a group of 64 filters.
+// A workgroup of 16 waves (8 for the 7x7 and the SFC-4 forms, each wave then doing two
+// passes) owns a rectangle of up to 16 tiles (S strips x tlw tile columns; a strip = one
+// row of tiles of one image), all input channels and a group of 64 filters.  The SFC-4
+// forms need half the LDS and two thirds of the registers, so two of their workgroups
+// share a compute unit.
+//
+// Points are taken in groups of four (one filter-operand load per group); the SFC-4 forms
+// pad their 46 / 49 points to 48 / 52 positions with zero filter operands.
 //
 //  1. Stage: the M+2 input rows of every (strip, channel) go to LDS with dword
 //     loads, lanes running along the row, padding halo zero-filled.
