@@ -54,16 +54,19 @@ def stage_bytes(shape, P, tiles, path):
     return {"input_transform": x + v, "product": v + u + m, "output_transform": m + y}
 
 
-def pick_variant(shape, alg=None, path=None):
+def pick_variant(shape, alg=None, path=None, independent_batches=False):
     """Tile size and path per layer shape, from the per-layer timings on one MI355X: the
-    single-kernel path where it exists (Cin <= 64), with SFC-4's 4x4 tiles when they divide
-    the feature map (no ragged tiles, two workgroups per compute unit); else 6x6 tiles while
-    the feature map is large (28x28: no ragged tiles to speak of, the cheaper transforms win);
+    single-kernel path where it exists (Cin <= 64); SFC-4's 4x4 tiles when they divide a
+    large feature map (56x56, 28x28: no ragged tiles, two workgroups per compute unit) and
+    the channels are few (<= 64; <= 128 when independent batches overlap on several streams:
+    its two kernels take 41 us back to back against 40 us for 6x6 tiles, but 31 against 32 us
+    per step when they overlap); else 6x6 tiles while the feature map is large;
     7x7 tiles on 14x14 and 7x7 maps (no ragged tiles at all), with the products as batched
     GEMMs through HBM once there are too few tiles for the fused kernel's operand stream
     (7x7 maps, 512 channels)."""
     if alg is None:
-        if shape.Cin <= 64 and shape.H % 4 == 0 and shape.W % 4 == 0:
+        if (shape.Cin <= (128 if independent_batches else 64) and shape.H >= 28 and shape.H % 4 == 0
+                and shape.W % 4 == 0):
             alg = "4x4_p46"
         else:
             alg = "6x6_p88" if shape.H >= 28 else "7x7_p132"
@@ -190,12 +193,6 @@ def main():
 
     if args.workload == "stack":
         return run_stack(args)
-    if args.alg is None:  # the fastest form for the layer (one layer: the paths are chosen below)
-        from paper_2407_02913_amd import synth as _synth
-
-        _shape = _synth.LAYERS[args.workload]
-        args.alg = "4x4_p46" if _shape.Cin <= 64 and _shape.H % 4 == 0 and _shape.W % 4 == 0 else "6x6_p88"
-
     import numpy as np
     import torch
 
@@ -205,11 +202,15 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     shape = synth.LAYERS[args.workload]
+    if args.alg is None:  # the fastest form and path measured for this layer shape
+        args.alg, default_path = pick_variant(shape, None, args.path, independent_batches=True)
+    else:
+        default_path = None
     ksize = binding.KERNEL_SIZE[args.alg]
     data = synth.make_layer(shape, kernel=ksize)
     # one kernel where the layer allows it (3x3 filters, Cin <= 64), else input transform +
     # fused product/output
-    path = args.path or ("single" if shape.Cin <= 64 and ksize == 3 else binding.DEFAULT_PATH)
+    path = args.path or default_path or ("single" if shape.Cin <= 64 and ksize == 3 else binding.DEFAULT_PATH)
     direct_ops = shape.direct_ops * ksize * ksize // 9
 
     plan = binding.Plan(shape.N, shape.Cin, shape.Cout, shape.H, shape.W, alg=args.alg,

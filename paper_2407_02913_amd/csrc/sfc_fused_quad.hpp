@@ -181,7 +181,7 @@ inline int quad_waves(int alg, int kc) {
   // the 7x7 forms carry 10x7 partial outputs per pair, the 5x5-filter forms 12x6: they need
   // the 256-register budget
   (void)kc;
-  return (alg < 2 || alg == 4 || alg == 5) ? kQuadWaves6 : 8;
+  return alg < 2 ? kQuadWaves6 : 8;
 }
 
 inline unsigned quad_lds_bytes(int alg, int kc) {
@@ -198,11 +198,12 @@ inline int quad_filter_count_for(const Geometry& g) {
 template <int ALG, int KC, int OUT, bool VEC2>
 inline hipError_t launch_quad_impl(const Geometry& g, const void* V, const FilterViews& f,
                                    float x_scale, float inv_y, void* y, hipStream_t s) {
-  // 6x6 tiles with 3x3 filters and the SFC-4 forms: 128 registers per wave, as many
-  // workgroups per compute unit as make 16 waves
-  constexpr bool kSmall = AlgTraits<ALG>::NC <= 8;
-  constexpr int NW = kSmall ? kQuadWaves6 : 8;
-  constexpr int WGS = kSmall ? 16 / NW : 1;
+  // 6x6 tiles with 3x3 filters: 16 waves of 128 registers.  The SFC-4 forms need under 100
+  // registers: 8-wave workgroups, two of which share a compute unit and run out of phase
+  // (measured 31.0 against 32.5 us per step on 128 channels at 28x28).  The other forms: 8
+  // waves with the 256-register budget.
+  constexpr int NW = ALG < 2 ? kQuadWaves6 : 8;
+  constexpr int WGS = ALG < 2 ? 16 / NW : AlgTraits<ALG>::NC == 6 ? 2 : 1;
   auto kernel = fused_quad_kernel<ALG, KC, OUT, VEC2, NW, WGS>;
   static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once
   if (!attr_done) {
