@@ -30,12 +30,14 @@ __device__ __forceinline__ void store_pairs(
     int W) {
   constexpr int M = AlgTraits<ALG>::M;
   constexpr unsigned esz = OUT == 2 ? 1u : 4u;
-  // Cache policy of the y stores.  7x7 tiles divide the ResNet image widths; on wide
+  // Cache policy of the y stores.  7x7 and 4x4 tiles divide the ResNet image widths; on wide
   // images a workgroup then writes long whole rows and the lines can stream past the L2
-  // ("nt").  Everywhere else (6x6 tiles, or short rows of small feature maps, where a line
-  // is completed by several stores or several workgroups) the L2 has to merge the pieces
-  // before they go to memory: streaming those costs up to 2.5x the bytes in HBM writes.
-  const bool stream = M == 7 && W >= 48;
+  // ("nt"): nothing is left dirty in the L2 for the end of the kernel to write back, which
+  // shortens the 4x4 single kernel on 56x56 maps from 19.6 to 17.0 us.  Everywhere else (6x6
+  // tiles, or short rows of small feature maps, where a line is completed by several stores
+  // or several workgroups) the L2 has to merge the pieces before they go to memory:
+  // streaming those costs up to 2.5x the bytes in HBM writes.
+  const bool stream = (M == 7 || M == 4) && W >= 48;
   constexpr int EV = VEC2 ? 2 : 1;        // elements per lane and store
   constexpr int NST = (M + EV - 1) / EV;  // stores per lane and output row (64*M elements)
   // store plan: the k-th store of this lane covers elements e = EV*(lane + 64*k) of the
