@@ -22,7 +22,9 @@ struct InputPlan {
   unsigned lds_bytes;
 };
 
-template <int ALG, int NW>
+// VS: bytes of V per point in LDS, 64 per tile slot (512 for the 8-tile workgroups: half the
+// LDS, so that more workgroups share a compute unit and overlap their phases).
+template <int ALG, int NW, int VS>
 __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
     const int8_t* __restrict__ x, int8_t* __restrict__ V, const float* __restrict__ inv_sx,
     Geometry g, InputPlan ip) {
@@ -46,27 +48,28 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
 
   stage_input<ALG, NW>(x, lds, g, tr, bx, c0, wave, lane);
   __syncthreads();
-  transform_tiles<ALG, NW, 1>(lds, inv_sx, g.qmax, g, tr, bx, wave, lane);
+  transform_tiles<ALG, NW, 1, VS>(lds, inv_sx, g.qmax, g, tr, bx, wave, lane);
   __syncthreads();
 
   // ---- copy out: wave w takes positions w, w+NW, ...; lane = (tile, 16-byte quarter) ---
   const unsigned vplane = (unsigned)g.Tp * (unsigned)g.Cp;
   const __amdgpu_buffer_rsrc_t vres =
       __builtin_amdgcn_make_buffer_rsrc((void*)V, 0, (int)(vplane * (unsigned)P), kBufferFlags);
-  const int t = row_tab[lane >> 2];
+  const int t = row_tab[VS == 512 ? (lane >> 2) & 7 : lane >> 2];
   const unsigned lane_off = (unsigned)t * (unsigned)g.Cp + (unsigned)(c0 + 16 * (lane & 3));
   if (t >= 0) {
-    copy_out_points<ALG, NW>(lds, vres, lane_off, vplane, wave, lane);
+    copy_out_points<ALG, NW, VS>(lds, vres, lane_off, vplane, wave, lane);
   }
 }
 
-// waves per workgroup = tiles per workgroup: the 7x7 forms hold a 9x10 half-transformed
-// patch per tile and need the registers of an 8-wave workgroup
-static int input_waves(int alg) { return alg_tile(alg) == 7 ? 8 : 16; }
+// waves per workgroup = tiles per workgroup: 16 for the 6x6 forms (rectangles of 16 tiles
+// fit their feature maps best); 8 for the 7x7 forms (a 9x10 half-transformed patch per tile
+// needs the registers) and the 4x4 forms, with half the LDS per workgroup
+static int input_waves(int alg) { return alg_tile(alg) == 6 ? 16 : 8; }
 
 static bool make_input_plan(const Geometry& g, InputPlan* ip) {
   if (g.alg > 5) return false;  // 3x3 filters only
-  const unsigned vbytes = (unsigned)g.P * 1024u;
+  const unsigned vbytes = (unsigned)g.P * (input_waves(g.alg) == 8 ? 512u : 1024u);
   const unsigned lds_max = 160u * 1024u;
   if (vbytes + 16u + 64u > lds_max) return false;
   if (!make_tile_rect(g, lds_max - 16u - 64u, &ip->tr, input_waves(g.alg), true)) return false;
@@ -81,8 +84,8 @@ static bool make_input_plan(const Geometry& g, InputPlan* ip) {
 template <int ALG>
 static hipError_t launch_input_i8_alg(const Geometry& g, const InputPlan& ip, const int8_t* x,
                                       void* V, const float* inv_sx, hipStream_t s) {
-  constexpr int NW = AlgTraits<ALG>::M == 7 ? 8 : 16;
-  auto kernel = input_transform_i8_kernel<ALG, NW>;
+  constexpr int NW = AlgTraits<ALG>::M == 6 ? 16 : 8;
+  auto kernel = input_transform_i8_kernel<ALG, NW, NW == 8 ? 512 : 1024>;
   static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once
   if (!attr_done) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),

@@ -310,9 +310,10 @@ __device__ __forceinline__ void stage_input(const int8_t* __restrict__ x, unsign
 // of a whole image) hit 64 different banks.
 // Each thread applies the symbolic DFT-6 add network along rows and columns, forms
 // the multiplication points and rounds them to int8; the bytes go to
-// lds[order.pos[p]*1024 + tile*64 + channel], over the staging area (every patch is in
-// registers by then).  Call between two workgroup barriers; contains one itself.
-template <int ALG, int NW, int SPW = 16 / NW>
+// lds[order.pos[p]*VS + tile*64 + channel], over the staging area (every patch is in
+// registers by then); VS = 1024 (16 tile slots per point), or 512 for workgroups of
+// eight tiles.  Call between two workgroup barriers; contains one itself.
+template <int ALG, int NW, int SPW = 16 / NW, int VS = 1024>
 __device__ __forceinline__ void transform_tiles(unsigned char* lds, const float* __restrict__ inv_sx,
                                                 float qmax, const Geometry& g, const TileRect& tr,
                                                 int bx, int wave, int lane) {
@@ -383,7 +384,7 @@ __device__ __forceinline__ void transform_tiles(unsigned char* lds, const float*
       }
       unsigned char* outp = lds + tile * 64 + c;
       for_each_point<ALG>(comp, [&](int p, int v) {
-        outp[order.pos[p] * 1024] = (unsigned char)quantize_byte(v, inv_sx[p], qmax);
+        outp[order.pos[p] * VS] = (unsigned char)quantize_byte(v, inv_sx[p], qmax);
       });
     }
   }
@@ -392,12 +393,37 @@ __device__ __forceinline__ void transform_tiles(unsigned char* lds, const float*
 // Copies the rounded points of the rectangle from LDS ([position][tile][channel]) to
 // V: wave w takes positions w, w+NW, ...; lane = (tile, 16-byte quarter of its 64
 // channels); lane_off is the lane's byte offset inside a point's plane of V.
-template <int ALG, int NW>
+// VS = 512 (eight tiles per workgroup): a wave takes two positions at a time, lanes 0..31
+// the first, lanes 32..63 the second.
+template <int ALG, int NW, int VS = 1024>
 __device__ __forceinline__ void copy_out_points(const unsigned char* lds,
                                                 __amdgpu_buffer_rsrc_t vres, unsigned lane_off,
                                                 unsigned vplane, int wave, int lane) {
   constexpr int P = AlgTraits<ALG>::P;
   constexpr Order<ALG> order{};
+  if constexpr (VS == 512) {
+    const int hi = lane >> 5;  // which of the wave's two positions
+#pragma unroll
+    for (int jj = 0; jj < (P + 2 * NW - 1) / (2 * NW); ++jj) {
+      // positions 2*(jj*NW + wave) and the next one: compile-time candidates selected by
+      // the uniform wave index and the half of the wave
+      int p = -1;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const int j0 = 2 * (jj * NW + w);
+        if (w == wave) {
+          const int pa = j0 < P ? order.pt[j0 < P ? j0 : 0] : -1;
+          const int pb = j0 + 1 < P ? order.pt[j0 + 1 < P ? j0 + 1 : 0] : -1;
+          p = hi ? pb : pa;
+        }
+      }
+      if (p >= 0) {
+        const v4i d = *(const v4i*)(lds + (2 * (jj * NW + wave)) * 512 + lane * 16);
+        __builtin_amdgcn_raw_buffer_store_b128(d, vres, lane_off + (unsigned)p * vplane, 0, 0);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int jj = 0; jj < (P + NW - 1) / NW; ++jj) {
     // the position is one of NW compile-time values chosen by the uniform wave index,
