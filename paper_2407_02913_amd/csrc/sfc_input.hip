@@ -1,10 +1,9 @@
 // Input-tile transform V = B^T x B with transform-domain requantization to int8,
-// the HBM-facing first stage of the two-kernel path (gfx950), for the 3x3-filter
-// algorithms (the 5x5-filter forms use the generic kernel of sfc_kernels.hip).
+// the HBM-facing first stage of the two-kernel path (gfx950), every algorithm.
 //
 // A workgroup owns up to NW tiles (a rectangle of S strips x tlw tile columns, or whole
 // images of a small feature map), one per wave, and 64 input channels:
-//  1. stage the M+2 input rows of every (strip, channel) in LDS (coalesced dword loads),
+//  1. stage the input rows of every (strip, channel) in LDS (coalesced dword loads),
 //  2. transform: wave = tile, lane = channel; the rounded points land in LDS as
 //     [processing position][tile][channel], over the staging area,
 //  3. copy out: V[p][t][c0 .. c0+63] with 16-byte lanes, 64 contiguous bytes per
@@ -64,11 +63,11 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
 
 // waves per workgroup = tiles per workgroup: 16 for the 6x6 forms (rectangles of 16 tiles
 // fit their feature maps best); 8 for the 7x7 forms (a 9x10 half-transformed patch per tile
-// needs the registers) and the 4x4 forms, with half the LDS per workgroup
-static int input_waves(int alg) { return alg_tile(alg) == 6 ? 16 : 8; }
+// needs the registers, the 10x12 one of the 5x5-filter forms all the more) and the 4x4
+// forms, with half the LDS per workgroup
+static int input_waves(int alg) { return alg < 2 ? 16 : 8; }
 
 static bool make_input_plan(const Geometry& g, InputPlan* ip) {
-  if (g.alg > 5) return false;  // 3x3 filters only
   const unsigned vbytes = (unsigned)g.P * (input_waves(g.alg) == 8 ? 512u : 1024u);
   const unsigned lds_max = 160u * 1024u;
   if (vbytes + 16u + 64u > lds_max) return false;
@@ -84,7 +83,7 @@ static bool make_input_plan(const Geometry& g, InputPlan* ip) {
 template <int ALG>
 static hipError_t launch_input_i8_alg(const Geometry& g, const InputPlan& ip, const int8_t* x,
                                       void* V, const float* inv_sx, hipStream_t s) {
-  constexpr int NW = AlgTraits<ALG>::M == 6 ? 16 : 8;
+  constexpr int NW = ALG < 2 ? 16 : 8;
   auto kernel = input_transform_i8_kernel<ALG, NW, NW == 8 ? 512 : 1024>;
   static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once
   if (!attr_done) {
@@ -111,6 +110,8 @@ hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V
     case 3: return launch_input_i8_alg<3>(g, ip, x, V, inv_sx, s);
     case 4: return launch_input_i8_alg<4>(g, ip, x, V, inv_sx, s);
     case 5: return launch_input_i8_alg<5>(g, ip, x, V, inv_sx, s);
+    case 6: return launch_input_i8_alg<6>(g, ip, x, V, inv_sx, s);
+    case 7: return launch_input_i8_alg<7>(g, ip, x, V, inv_sx, s);
   }
   return hipErrorInvalidValue;
 }

@@ -26,11 +26,14 @@ struct TileRect {
 };
 
 // Staging layout: 64 bytes per image row (byte 4 holds image column colbase, a
-// multiple of 4 at or left of the rectangle's first column), M+2 rows per (strip,
+// multiple of 4 at or left of the rectangle's first column), NI = M+R-1 rows per (strip,
 // channel), plus one dword so that the channel stride is an odd number of dwords
 // and lanes running along channels hit distinct banks.
 constexpr int kStageRow = 64;
-__host__ __device__ constexpr int stage_channel_bytes(int tile) { return (tile + 2) * kStageRow + 4; }
+__host__ __device__ constexpr int stage_channel_bytes(int rows) { return rows * kStageRow + 4; }
+// input rows per tile and zero padding of an algorithm
+__host__ __device__ constexpr int alg_rows(int alg) { return alg_tile(alg) + alg_taps(alg) - 1; }
+__host__ __device__ constexpr int alg_pad(int alg) { return (alg_taps(alg) - 1) / 2; }
 
 // Chooses the rectangle that fills most of the 16 tile slots, given the LDS bytes
 // available for the staged rows.  False if no rectangle fits.
@@ -47,7 +50,7 @@ __host__ __device__ constexpr int plane_stride_bytes(int hw) {
 // alternative is a rectangle whose rows are not whole dwords (byte-wise staging).
 inline bool make_tile_rect(const Geometry& g, unsigned stage_budget, TileRect* tr,
                            int max_tiles = 16, bool partial_images = false) {
-  const int M = alg_tile(g.alg);
+  const int M = alg_tile(g.alg), PAD = alg_pad(g.alg);
   tr->whole = 0;
   tr->ipw = 0;
   tr->cs = 0;
@@ -70,10 +73,10 @@ inline bool make_tile_rect(const Geometry& g, unsigned stage_budget, TileRect* t
       return true;
     }
   }
-  const int tlw_max =
-      (kStageRow - 7) / M < max_tiles ? (kStageRow - 7) / M : max_tiles;  // 5 + M*tlw + 2 <= 64
+  // the first patch column lies at LDS byte 7-PAD at most, the last one M*tlw + 2*PAD - 1 further
+  const int tlw_max = (kStageRow - 7 - PAD) / M < max_tiles ? (kStageRow - 7 - PAD) / M : max_tiles;
   const int min_chunks = (g.tw + tlw_max - 1) / tlw_max;
-  const int s_fit = (int)(stage_budget / (64u * (unsigned)stage_channel_bytes(M)));
+  const int s_fit = (int)(stage_budget / (64u * (unsigned)stage_channel_bytes(alg_rows(g.alg))));
   if (s_fit < 1) return false;
   double best = -1.0;
   for (int chunks = min_chunks; chunks <= min_chunks + 4 && chunks <= g.tw; ++chunks) {
@@ -95,12 +98,12 @@ inline bool make_tile_rect(const Geometry& g, unsigned stage_budget, TileRect* t
   // the reciprocal is exact while strip * th < 2^32
   if ((long long)g.strips * g.th >= (1ll << 32) || g.th < 1) return false;
   tr->th_magic = ((1ull << 32) + (unsigned long long)g.th - 1) / (unsigned long long)g.th;
-  return tr->ntiles >= 1 && tr->ntiles <= max_tiles && 5 + M * tr->tlw + 2 <= kStageRow;
+  return tr->ntiles >= 1 && tr->ntiles <= max_tiles && M * tr->tlw <= kStageRow - 7 - PAD;
 }
 
 inline unsigned tile_rect_stage_bytes(const Geometry& g, const TileRect& tr) {
   if (tr.whole) return (unsigned)(tr.ipw * 64 * tr.cs);
-  return (unsigned)tr.S * 64u * (unsigned)stage_channel_bytes(alg_tile(g.alg));
+  return (unsigned)tr.S * 64u * (unsigned)stage_channel_bytes(alg_rows(g.alg));
 }
 inline unsigned tile_rect_groups(const Geometry& g, const TileRect& tr) {
   if (tr.whole) return (unsigned)((g.N + tr.ipw - 1) / tr.ipw);
@@ -215,9 +218,9 @@ template <int ALG, int NW>
 __device__ __forceinline__ void stage_tiles(const int8_t* __restrict__ x, unsigned char* lds,
                                             const Geometry& g, const TileRect& tr, int strip0,
                                             int tj0, int c0, int wave, int lane) {
-  constexpr int M = AlgTraits<ALG>::M, NI = AlgTraits<ALG>::NI;
+  constexpr int M = AlgTraits<ALG>::M, NI = AlgTraits<ALG>::NI, PAD = AlgTraits<ALG>::PAD;
   constexpr int ROWG = (NI + 3) / 4;  // groups of four staged rows
-  constexpr int WP = kStageRow, CS = stage_channel_bytes(M);
+  constexpr int WP = kStageRow, CS = stage_channel_bytes(NI);
   constexpr unsigned kOutOfRange = 0x80000000u;
   const int W = g.W, H = g.H;
   const unsigned xbytes = (unsigned)(g.N * g.Cin) * (unsigned)(H * W);
@@ -248,7 +251,7 @@ __device__ __forceinline__ void stage_tiles(const int8_t* __restrict__ x, unsign
         const bool live = k < ncombo && strip < g.strips;
         const int n = strip_image(tr, strip);
         const int ti = strip - n * g.th;
-        const int hlo = M * ti - 1 + 4 * rg;        // image row of rsub = 0
+        const int hlo = M * ti - PAD + 4 * rg;      // image row of rsub = 0
         const int base = (n * g.Cin * H + hlo) * W;  // its offset in channel 0 of image n
         const bool ok = live && nvalid > 0 && 4 * rg + rsub < NI &&
                         (unsigned)(hlo + rsub) < (unsigned)H;
@@ -318,12 +321,13 @@ __device__ __forceinline__ void transform_tiles(unsigned char* lds, const float*
                                                 float qmax, const Geometry& g, const TileRect& tr,
                                                 int bx, int wave, int lane) {
   using Tr = AlgTraits<ALG>;
-  constexpr int M = Tr::M, NI = Tr::NI, NC = Tr::NC;
-  constexpr int WP = kStageRow, CS = stage_channel_bytes(M);
+  constexpr int M = Tr::M, NI = Tr::NI, NC = Tr::NC, PAD = Tr::PAD;
+  constexpr int WP = kStageRow, CS = stage_channel_bytes(NI);
+  constexpr int ND = (NI + 6) / 4;  // aligned dwords that hold a patch row at any byte offset
   constexpr Order<ALG> order{};
   const int tj0 = tr.whole ? 0 : (bx % tr.chunks) * tr.tlw;
   const int colbase = (M * tj0) & ~3;
-  const int halo = M * tj0 - 1 - colbase + 4;  // LDS byte of the rectangle's first patch column
+  const int halo = M * tj0 - PAD - colbase + 4;  // LDS byte of the rectangle's first patch column
   int half[SPW][NI][NC];  // rows transformed: half[.][i][b]
 #pragma unroll
   for (int it = 0; it < SPW; ++it) {
@@ -336,7 +340,7 @@ __device__ __forceinline__ void transform_tiles(unsigned char* lds, const float*
         const int slot = tile / tpi, rem = tile - slot * tpi;
         const int ti = rem / g.tw, tj = rem - ti * g.tw;
         const signed char* plane = (const signed char*)lds + (slot * 64 + c) * tr.cs;
-        const int r0 = M * ti - 1, q0 = M * tj - 1;
+        const int r0 = M * ti - PAD, q0 = M * tj - PAD;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
           int row[NI];
@@ -350,15 +354,20 @@ __device__ __forceinline__ void transform_tiles(unsigned char* lds, const float*
         }
       } else {
         const int s = tile / tr.tlw, tjl = tile - s * tr.tlw;
-        // the patch row starts at an odd byte: three aligned dwords, shifted into place
+        // the patch row starts at any byte: ND aligned dwords, shifted into place (the last
+        // one may lie beyond the row's 64 bytes when the row does not need it: still inside
+        // the channel's staging block, never used)
         const int o = halo + M * tjl;
         const unsigned* src = (const unsigned*)(lds + (unsigned)(s * 64 + c) * CS + (o & ~3));
         const unsigned sh = (unsigned)(o & 3);
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-          const unsigned d0 = src[i * (WP / 4)], d1 = src[i * (WP / 4) + 1], d2 = src[i * (WP / 4) + 2];
-          const unsigned w[3] = {__builtin_amdgcn_alignbyte(d1, d0, sh),
-                                 __builtin_amdgcn_alignbyte(d2, d1, sh), d2 >> (8 * sh)};
+          unsigned d[ND], w[ND];
+#pragma unroll
+          for (int k = 0; k < ND; ++k) d[k] = src[i * (WP / 4) + k];
+#pragma unroll
+          for (int k = 0; k + 1 < ND; ++k) w[k] = __builtin_amdgcn_alignbyte(d[k + 1], d[k], sh);
+          w[ND - 1] = d[ND - 1] >> (8 * sh);
           int row[NI];
 #pragma unroll
           for (int j = 0; j < NI; ++j) row[j] = (int)(signed char)(w[j / 4] >> (8 * (j % 4)));
