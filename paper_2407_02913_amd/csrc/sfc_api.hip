@@ -28,6 +28,7 @@ struct sfc_plan_s {
   void* filter_dev;
   bool filter_ready;
   int quad_filters;  // filters covered by the regrouped filter operand (0: none)
+  int dq_filters;    // filters in the [filter][processing position] dequantization table (0: none)
   float inv_y;  // 1 / output scale (SFC_OUT_I8_RELU), 0: not set
 };
 
@@ -123,13 +124,16 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   p->quad_filters = 0;
   if (d.path == SFC_PATH_SINGLE) p->quad_filters = (g.Cout + 63) / 64 * 64;
   if (d.path == SFC_PATH_FUSED) p->quad_filters = sfc::quad_filter_count(g);
-  if (p->quad_filters > 0) {
-    // the fused kernels take the points in groups of four: positions up to a multiple of 4
-    const size_t pp = (size_t)(g.P + 3) / 4 * 4;
-    off = align_up(off + (size_t)p->quad_filters * pp * sizeof(float), 256);
+  // the staged output transform reads the same [filter][position] table as the fused kernels
+  p->dq_filters = p->quad_filters;
+  if (d.path == SFC_PATH_STAGED && d.mode == SFC_MODE_REQUANT_I8) p->dq_filters = g.Kp;
+  // the kernels take the points in groups of four: positions up to a multiple of 4
+  const size_t pp = (size_t)(g.P + 3) / 4 * 4;
+  if (p->dq_filters > 0) {
+    off = align_up(off + (size_t)p->dq_filters * pp * sizeof(float), 256);
     p->off_U_single = off;
-    off = align_up(off + (size_t)p->quad_filters * pp * g.Cp, 256);
   }
+  if (p->quad_filters > 0) off = align_up(off + (size_t)p->quad_filters * pp * g.Cp, 256);
   p->filter_bytes = off;
   off = 0;
   p->off_V = off;
@@ -237,7 +241,8 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
   // host image of the float tables: [dequant | inv_sw | inv_sx | wscale], contiguous
   // from off_dequant to filter_bytes
   const bool quad = plan->quad_filters > 0;
-  const size_t table_bytes = (quad ? plan->off_U_single : plan->filter_bytes) - plan->off_dequant;
+  const size_t table_bytes =
+      (plan->dq_filters > 0 ? plan->off_U_single : plan->filter_bytes) - plan->off_dequant;
   try {
     plan->staging.assign(table_bytes / sizeof(float), 0.0f);
   } catch (...) {
@@ -265,7 +270,7 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
       inv_sw[(size_t)p * g.Kp + k] = inv;
     }
   }
-  if (quad) {
+  if (plan->dq_filters > 0) {
     // [filter][processing position]; filters beyond Cout stay zero
     const int pp = (g.P + 3) / 4 * 4;
     std::vector<int> pt(pp, -1);

@@ -192,7 +192,7 @@ __global__ __launch_bounds__(NW * 64) void output_sums_kernel(const int32_t* __r
   const __amdgpu_buffer_rsrc_t mres =
       __builtin_amdgcn_make_buffer_rsrc((void*)M, 0, (int)(mplane * (unsigned)P), kBufferFlags);
   const __amdgpu_buffer_rsrc_t dres = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)dequant, 0, P * g.Kp * 4, kBufferFlags);
+      (void*)dequant, 0, Order<ALG>::PP * g.Kp * 4, kBufferFlags);
   constexpr unsigned esz = OUT == 2 ? 1u : 4u;
   const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
       y, 0, (int)(esz * (unsigned)(g.N * g.Cout) * (unsigned)(g.H * g.W)), kBufferFlags);
@@ -201,23 +201,31 @@ __global__ __launch_bounds__(NW * 64) void output_sums_kernel(const int32_t* __r
   const unsigned m_lane =
       kvalid ? (unsigned)(((blockIdx.x * (g.Kp >> 2) + kq) * 64 + (lane & 15) * 4 + (lane >> 4)) * 4)
              : 0x80000000u;
-  const unsigned d_lane = kvalid ? (unsigned)kcol * 4u : 0x80000000u;
-  const unsigned dplane = (unsigned)g.Kp * 4u;
+  // dequantization factors: [filter][processing position], one 16-byte load per four points
+  static_assert(D % 4 == 0, "the ring holds whole groups of four points");
+  const unsigned d_lane = kvalid ? (unsigned)kcol * (unsigned)(Order<ALG>::PP * 4) : 0x80000000u;
 
   int mring[D];
-  float dring[D];
+  v4f dring[D / 4];
   auto load_point = [&](int j) {
     const unsigned p = (unsigned)order.pt[j];
     mring[j % D] = (int)__builtin_amdgcn_raw_buffer_load_b32(mres, m_lane, p * mplane, 0);
-    dring[j % D] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(dres, d_lane, p * dplane, 0));
   };
+  auto load_factors = [&](int grp) {  // positions 4*grp .. 4*grp + 3
+    dring[grp % (D / 4)] = __builtin_bit_cast(
+        v4f, __builtin_amdgcn_raw_buffer_load_b128(dres, d_lane, (unsigned)grp * 16u, 0));
+  };
+#pragma unroll
+  for (int grp = 0; grp < D / 4 && 4 * grp < P; ++grp) load_factors(grp);
 #pragma unroll
   for (int j = 0; j < D && j < P; ++j) load_point(j);
   int j = 0;  // folds to a constant after unrolling
   auto next = [&]() -> float {
-    float v = (float)mring[j % D] * dring[j % D];
+    float v = (float)mring[j % D] * dring[(j >> 2) % (D / 4)][j & 3];
     asm volatile("" : "+v"(v));  // the slot is free from here on
     if (j + D < P) load_point(j + D);
+    // the factor slot of a group is free once its fourth product has been taken
+    if ((j & 3) == 3 && 4 * ((j >> 2) + D / 4) < P) load_factors((j >> 2) + D / 4);
     ++j;
     return v;
   };
@@ -234,7 +242,7 @@ static hipError_t launch_sums_impl(const Geometry& g, const int32_t* M, const Fi
   constexpr int NW = AlgTraits<ALG>::NC <= 8 ? 16 : 8;
   const dim3 grid((unsigned)(g.Tp / 16), (unsigned)((g.Cout + 4 * NW - 1) / (4 * NW)));
   hipLaunchKernelGGL((output_sums_kernel<ALG, OUT, VEC2, NW>), grid, dim3(NW * 64), 0, s, M,
-                     f.dequant, x_scale, inv_y, y, g);
+                     f.dequant_single, x_scale, inv_y, y, g);
   return hipGetLastError();
 }
 
