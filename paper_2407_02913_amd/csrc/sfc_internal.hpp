@@ -23,13 +23,16 @@ struct Geometry {
 // Device-side views of the filter buffer (all inside the caller's filter_dev).
 struct FilterViews {
   void* U;              // [P][Kp][Cp] int8 (requantized) or int16 (exact)
-  float* dequant;       // requantized: [P][Kp] s_Tx[p]*s_Tf[p,k]*s_w[k]/36; exact: unused
+  float* dequant;       // requantized: [P][Kp] s_Tx[p]*s_Tf[p,k]*s_w[k]/36 (kept for inspection;
+                        // the kernels read dequant_single); exact: unused
   float* inv_sw;        // [P][Kp] 1/s_Tf
   float* inv_sx;        // [P]     1/s_Tx
   float* wscale;        // [Kp]    s_w[k]
   // fused and single-kernel paths: U regrouped into MFMA operands of four points x four
-  // filters, and the dequantization factors as [filter][processing position]
+  // filters
   void* U_single;
+  // every requantized path: the dequantization factors as [filter][processing position],
+  // positions padded to a multiple of four, rows of filters beyond Cout zero
   float* dequant_single;
 };
 
