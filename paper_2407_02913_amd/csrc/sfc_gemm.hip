@@ -160,10 +160,17 @@ hipError_t launch_product_gemm_i8(const Geometry& g, const void* V, const void* 
 // NCHW store are theirs.  The int32 sums of the pair are read point by point in
 // processing order, a ring of loads ahead; no barrier, no LDS besides the store staging.
 // The kernel moves M and y once each and runs at the rate the memory system delivers them.
+// PLANES: the feature map is one tile and Cout a multiple of 4; y is then written plane by
+// plane (store_planes) from a staging block of M*M floats per pair.
 // ---------------------------------------------------------------------------------------
 constexpr int kSumRing = 12;
 
-template <int ALG, int OUT, bool VEC2, int NW>
+template <int ALG, bool PLANES, int NW>
+constexpr unsigned sums_stage_bytes() {
+  return (unsigned)(NW * 64 * AlgTraits<ALG>::M * (PLANES ? AlgTraits<ALG>::M : 1) * 4);
+}
+
+template <int ALG, int OUT, bool VEC2, int NW, bool PLANES>
 __global__ __launch_bounds__(NW * 64) void output_sums_kernel(const int32_t* __restrict__ M,
                                                               const float* __restrict__ dequant,
                                                               float x_scale, float inv_y,
@@ -171,11 +178,11 @@ __global__ __launch_bounds__(NW * 64) void output_sums_kernel(const int32_t* __r
   using Tr = AlgTraits<ALG>;
   constexpr int P = Tr::P, Mo = Tr::M, NC = Tr::NC, D = kSumRing;
   constexpr Order<ALG> order{};
-  __shared__ __align__(16) unsigned char lds[NW * 64 * Mo * 4 + 256];
+  extern __shared__ __align__(16) unsigned char lds[];  // staging blocks, then the tile table
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  float* stage = (float*)lds + wave * (64 * Mo);
-  int* tile_tab = (int*)(lds + NW * 64 * Mo * 4);
+  float* stage = (float*)lds + wave * (64 * Mo * (PLANES ? Mo : 1));
+  int* tile_tab = (int*)(lds + sums_stage_bytes<ALG, PLANES, NW>());
   const int t0 = blockIdx.x * 16;
   const int kq = blockIdx.y * NW + wave;
   const int kcol = kq * 4 + (lane >> 4);
@@ -231,18 +238,33 @@ __global__ __launch_bounds__(NW * 64) void output_sums_kernel(const int32_t* __r
   };
   float z[NC][Mo];
   stream_vertical<ALG, float>(next, z);
-  store_pairs<ALG, OUT, VEC2>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, g.H, g.W);
+  if constexpr (PLANES)
+    store_planes<ALG, OUT>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout);
+  else
+    store_pairs<ALG, OUT, VEC2>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, g.H, g.W);
 }
 
-template <int ALG, int OUT, bool VEC2>
+template <int ALG, int OUT, bool VEC2, bool PLANES = false>
 static hipError_t launch_sums_impl(const Geometry& g, const int32_t* M, const FilterViews& f,
                                    float x_scale, float inv_y, void* y, hipStream_t s) {
   // the 7x7 forms carry 10x7 partial outputs per pair, the 5x5-filter forms 12x6: 8 waves
   // with 256 registers each
   constexpr int NW = AlgTraits<ALG>::NC <= 8 ? 16 : 8;
+  constexpr unsigned lds_bytes = sums_stage_bytes<ALG, PLANES, NW>() + 256;
+  static_assert(lds_bytes <= 160u * 1024u, "staging blocks exceed the LDS of a compute unit");
+  auto kernel = output_sums_kernel<ALG, OUT, VEC2, NW, PLANES>;
+  if constexpr (lds_bytes > 64u * 1024u) {
+    static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once
+    if (!attr_done) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      (void)hipGetLastError();
+      attr_done = true;
+    }
+  }
   const dim3 grid((unsigned)(g.Tp / 16), (unsigned)((g.Cout + 4 * NW - 1) / (4 * NW)));
-  hipLaunchKernelGGL((output_sums_kernel<ALG, OUT, VEC2, NW>), grid, dim3(NW * 64), 0, s, M,
-                     f.dequant_single, x_scale, inv_y, y, g);
+  hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), lds_bytes, s, M, f.dequant_single, x_scale,
+                     inv_y, y, g);
   return hipGetLastError();
 }
 
@@ -251,6 +273,12 @@ static hipError_t launch_sums_alg(int out, const Geometry& g, const int32_t* M,
                                   const FilterViews& f, float x_scale, float inv_y, void* y,
                                   hipStream_t s) {
   constexpr bool kPairs = AlgTraits<ALG>::M % 2 == 0;
+  // 7x7 tiles on 7x7 maps: every (tile, filter) pair is a whole plane of y
+  if constexpr (AlgTraits<ALG>::M == 7) {
+    if (g.H == 7 && g.W == 7 && g.Cout % 4 == 0)
+      return out == 2 ? launch_sums_impl<ALG, 2, false, true>(g, M, f, x_scale, inv_y, y, s)
+                      : launch_sums_impl<ALG, 0, false, true>(g, M, f, x_scale, inv_y, y, s);
+  }
   if constexpr (kPairs) {
     if (g.W % 2 == 0)
       return out == 2 ? launch_sums_impl<ALG, 2, true>(g, M, f, x_scale, inv_y, y, s)

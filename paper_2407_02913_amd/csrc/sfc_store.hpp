@@ -110,4 +110,56 @@ __device__ __forceinline__ void store_pairs(
   }
 }
 
+// The same for feature maps that are one tile (H = W = M, so a (tile, filter) pair is a whole
+// plane of y and the four planes of a lane group are one run of 4*M*M elements): the wave
+// stages all M rows of its 64 pairs as [tile][filter][o1][o2], the order of y, and writes
+// them with four elements per lane, 1 KB of consecutive addresses per store instruction.
+// Row-by-row stores put a 128-byte line together from pieces of 4*M bytes issued M row
+// transforms apart, and the L2 wrote such lines to memory about twice (WRITE_SIZE 45.8 MB
+// for 25.7 MB of y on 7x7 maps).  Needs Cout % 4 == 0 (runs stay 16-byte aligned) and a
+// staging block of 64*M*M floats per wave.
+template <int ALG, int OUT>
+__device__ __forceinline__ void store_planes(
+    const float (&z)[AlgTraits<ALG>::NC][AlgTraits<ALG>::M], float* stage, const int* tile_tab,
+    int lane, int kq, float x_scale, float inv_y, __amdgpu_buffer_rsrc_t yres, int Cout) {
+  constexpr int M = AlgTraits<ALG>::M, MM = M * M;
+  constexpr unsigned esz = OUT == 2 ? 1u : 4u;
+  float* wr = stage + ((lane & 15) * 4 + (lane >> 4)) * MM;  // MM odd: conflict-free
+#pragma unroll
+  for (int o1 = 0; o1 < M; ++o1) {
+    float out[M];
+    stream_row<ALG, float>(z, o1, out);
+#pragma unroll
+    for (int o2 = 0; o2 < M; ++o2) wr[o1 * M + o2] = out[o2] * x_scale;
+  }
+  __builtin_amdgcn_wave_barrier();  // LDS accesses of one wave complete in order
+  constexpr int NQ = 16 * MM;       // groups of four elements in the wave's block
+  const bool kvalid = 4 * kq < Cout;
+#pragma unroll
+  for (int k = 0; k < (NQ + 63) / 64; ++k) {
+    const int q = lane + 64 * k;
+    if (q < NQ) {
+      const int tl = q / MM, r = q - tl * MM;  // tile, group within the tile's four planes
+      const v4f v = *(const v4f*)(stage + 4 * q);
+      if (kvalid && tile_tab[16 + tl] > 0) {
+        const unsigned off = esz * (unsigned)(tile_tab[tl] + 4 * kq * MM + 4 * r);
+        if constexpr (OUT == 2) {
+          // next layer's activation: ReLU, round half to even, clamp to [0, 127]
+          constexpr float kMagic = 12582912.0f;
+          unsigned word = 0;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float t = __fmaf_rn(v[i], inv_y, kMagic);
+            t = __builtin_amdgcn_fmed3f(t, kMagic, kMagic + 127.0f);
+            word |= (__float_as_uint(t) & 0xffu) << (8 * i);
+          }
+          __builtin_amdgcn_raw_buffer_store_b32(word, yres, off, 0, 0);
+        } else {
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, v), yres, off, 0, 0);
+        }
+      }
+    }
+  }
+}
+
 }  // namespace sfc
