@@ -22,7 +22,21 @@
 
 namespace sfc {
 
-template <int ALG, int KC, int OUT, bool VEC2, int NW, int WGS>
+// PLANES: whole tiles cover the feature map and the 16 tiles of a wave are whole images
+// (whole_image_tiles); y is then written image by image (store_planes) from staging blocks
+// of M*M floats per pair, which take the place of the V buffers once the last group of
+// points has been multiplied.
+template <int ALG, int KC, int NW, bool PLANES>
+constexpr unsigned quad_lds_layout(int what) {
+  constexpr unsigned M = AlgTraits<ALG>::M;
+  constexpr unsigned vbytes = 2u * 4u * 16u * 64u * KC;
+  constexpr unsigned stage = NW * 64u * M * (PLANES ? M : 1u) * 4u;
+  constexpr unsigned stage_off = PLANES ? 0u : vbytes;
+  constexpr unsigned tab_off = PLANES ? (vbytes > stage ? vbytes : stage) : vbytes + stage;
+  return what == 0 ? stage_off : what == 1 ? tab_off : tab_off + 256u;
+}
+
+template <int ALG, int KC, int OUT, bool VEC2, int NW, int WGS, bool PLANES = false>
 __global__ __launch_bounds__(NW * 64, WGS) void fused_quad_kernel(
     const int8_t* __restrict__ V, const int8_t* __restrict__ Uf, const float* __restrict__ dqf,
     float x_scale, float inv_y, void* __restrict__ y, Geometry g, int kquads) {
@@ -41,8 +55,9 @@ __global__ __launch_bounds__(NW * 64, WGS) void fused_quad_kernel(
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  float* stage = (float*)(lds + 2 * GROUP_BYTES) + wave * (64 * M);
-  int* tile_tab = (int*)(lds + 2 * GROUP_BYTES + NW * 64 * M * 4);
+  float* stage = (float*)(lds + quad_lds_layout<ALG, KC, NW, PLANES>(0)) +
+                 wave * (64 * M * (PLANES ? M : 1));
+  int* tile_tab = (int*)(lds + quad_lds_layout<ALG, KC, NW, PLANES>(1));
 
   // Workgroup -> (filter group, tile block).  Ids that share an XCD (an L2) cover a
   // contiguous range with the filter group varying slowest, so that the filter
@@ -171,7 +186,11 @@ __global__ __launch_bounds__(NW * 64, WGS) void fused_quad_kernel(
   float z[NC][M];
   stream_vertical<ALG, float>(next, z);
 
-  store_pairs<ALG, OUT, VEC2>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, g.H, g.W);
+  // (every wave has passed the barrier that ends the last group: the V buffers are free)
+  if constexpr (PLANES)
+    store_planes<ALG, OUT>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, g.th, g.tw);
+  else
+    store_pairs<ALG, OUT, VEC2>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, g.H, g.W);
 }
 
 // ---------------------------------------------------------------------------------
@@ -195,7 +214,7 @@ inline int quad_filter_count_for(const Geometry& g) {
   return (g.Cout + per_wg - 1) / per_wg * per_wg;
 }
 
-template <int ALG, int KC, int OUT, bool VEC2>
+template <int ALG, int KC, int OUT, bool VEC2, bool PLANES = false>
 inline hipError_t launch_quad_impl(const Geometry& g, const void* V, const FilterViews& f,
                                    float x_scale, float inv_y, void* y, hipStream_t s) {
   // 6x6 tiles with 3x3 filters: 16 waves of 128 registers.  The SFC-4 forms need under 100
@@ -204,7 +223,9 @@ inline hipError_t launch_quad_impl(const Geometry& g, const void* V, const Filte
   // waves with the 256-register budget.
   constexpr int NW = ALG < 2 ? kQuadWaves6 : 8;
   constexpr int WGS = ALG < 2 ? 16 / NW : AlgTraits<ALG>::NC == 6 ? 2 : 1;
-  auto kernel = fused_quad_kernel<ALG, KC, OUT, VEC2, NW, WGS>;
+  auto kernel = fused_quad_kernel<ALG, KC, OUT, VEC2, NW, WGS, PLANES>;
+  constexpr unsigned lds_bytes = quad_lds_layout<ALG, KC, NW, PLANES>(2);
+  static_assert(lds_bytes <= 160u * 1024u, "V buffers and staging exceed the LDS of a compute unit");
   static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once
   if (!attr_done) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -215,7 +236,7 @@ inline hipError_t launch_quad_impl(const Geometry& g, const void* V, const Filte
   const int kfilters = quad_filter_count_for(g);
   const int kgroups = kfilters / (4 * NW);
   const dim3 grid((unsigned)((g.Tp / 16) * kgroups));
-  hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), quad_lds_bytes(g.alg, KC), s, (const int8_t*)V,
+  hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), lds_bytes, s, (const int8_t*)V,
                      (const int8_t*)f.U_single, f.dequant_single, x_scale, inv_y, y, g,
                      kfilters / 4);
   return hipGetLastError();
@@ -225,6 +246,12 @@ template <int ALG, int KC>
 inline hipError_t launch_quad_kc(int out, const Geometry& g, const void* V, const FilterViews& f,
                                  float x_scale, float inv_y, void* y, hipStream_t s) {
   constexpr bool kPairs = AlgTraits<ALG>::M % 2 == 0;
+  // 7x7 tiles on 7x7, 14x14, 28x28 ... maps: a wave's pairs are whole planes of y
+  if constexpr (AlgTraits<ALG>::M == 7) {
+    if (whole_image_tiles(7, g.H, g.W, g.th, g.tw, g.Cout))
+      return out == 2 ? launch_quad_impl<ALG, KC, 2, false, true>(g, V, f, x_scale, inv_y, y, s)
+                      : launch_quad_impl<ALG, KC, 0, false, true>(g, V, f, x_scale, inv_y, y, s);
+  }
   if constexpr (kPairs) {
     if (g.W % 2 == 0)
       return out == 2 ? launch_quad_impl<ALG, KC, 2, true>(g, V, f, x_scale, inv_y, y, s)

@@ -160,8 +160,9 @@ hipError_t launch_product_gemm_i8(const Geometry& g, const void* V, const void* 
 // NCHW store are theirs.  The int32 sums of the pair are read point by point in
 // processing order, a ring of loads ahead; no barrier, no LDS besides the store staging.
 // The kernel moves M and y once each and runs at the rate the memory system delivers them.
-// PLANES: the feature map is one tile and Cout a multiple of 4; y is then written plane by
-// plane (store_planes) from a staging block of M*M floats per pair.
+// PLANES: whole tiles cover the feature map and the 16 tiles of a wave are whole images
+// (whole_image_tiles); y is then written image by image (store_planes) from a staging
+// block of M*M floats per pair.
 // ---------------------------------------------------------------------------------------
 constexpr int kSumRing = 12;
 
@@ -239,7 +240,7 @@ __global__ __launch_bounds__(NW * 64) void output_sums_kernel(const int32_t* __r
   float z[NC][Mo];
   stream_vertical<ALG, float>(next, z);
   if constexpr (PLANES)
-    store_planes<ALG, OUT>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout);
+    store_planes<ALG, OUT>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, g.th, g.tw);
   else
     store_pairs<ALG, OUT, VEC2>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, g.H, g.W);
 }
@@ -273,9 +274,9 @@ static hipError_t launch_sums_alg(int out, const Geometry& g, const int32_t* M,
                                   const FilterViews& f, float x_scale, float inv_y, void* y,
                                   hipStream_t s) {
   constexpr bool kPairs = AlgTraits<ALG>::M % 2 == 0;
-  // 7x7 tiles on 7x7 maps: every (tile, filter) pair is a whole plane of y
+  // 7x7 tiles on 7x7, 14x14, 28x28 ... maps: a wave's pairs are whole planes of y
   if constexpr (AlgTraits<ALG>::M == 7) {
-    if (g.H == 7 && g.W == 7 && g.Cout % 4 == 0)
+    if (whole_image_tiles(7, g.H, g.W, g.th, g.tw, g.Cout))
       return out == 2 ? launch_sums_impl<ALG, 2, false, true>(g, M, f, x_scale, inv_y, y, s)
                       : launch_sums_impl<ALG, 0, false, true>(g, M, f, x_scale, inv_y, y, s);
   }

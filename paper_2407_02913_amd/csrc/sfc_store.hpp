@@ -110,27 +110,40 @@ __device__ __forceinline__ void store_pairs(
   }
 }
 
-// The same for feature maps that are one tile (H = W = M, so a (tile, filter) pair is a whole
-// plane of y and the four planes of a lane group are one run of 4*M*M elements): the wave
-// stages all M rows of its 64 pairs as [tile][filter][o1][o2], the order of y, and writes
-// them with four elements per lane, 1 KB of consecutive addresses per store instruction.
-// Row-by-row stores put a 128-byte line together from pieces of 4*M bytes issued M row
-// transforms apart, and the L2 wrote such lines to memory about twice (WRITE_SIZE 45.8 MB
-// for 25.7 MB of y on 7x7 maps).  Needs Cout % 4 == 0 (runs stay 16-byte aligned) and a
-// staging block of 64*M*M floats per wave.
+// The same for feature maps that whole tiles cover exactly (H = M*th, W = M*tw) with th*tw
+// a divisor of 16: the 16 tiles of a wave are then 16/(th*tw) whole images, and the four
+// filter planes of an image are one run of 4*H*W elements of y.  The wave stages all M rows
+// of its 64 pairs as [image][filter][row][column], the order of y, and writes them with four
+// elements per lane, 1 KB of consecutive addresses per store instruction.  Row-by-row stores
+// put a 128-byte line together from pieces of 4*M bytes issued M row transforms apart, and
+// the L2 wrote such lines to memory about twice (WRITE_SIZE 45.8 MB for 25.7 MB of y on 7x7
+// maps).  Needs Cout % 4 == 0 (runs stay 16-byte aligned) and a staging block of 64*M*M
+// floats per wave.
+inline bool whole_image_tiles(int M, int H, int W, int th, int tw, int Cout) {
+  const int per = th * tw;
+  return H == M * th && W == M * tw && per <= 16 && 16 % per == 0 && Cout % 4 == 0;
+}
+
 template <int ALG, int OUT>
 __device__ __forceinline__ void store_planes(
     const float (&z)[AlgTraits<ALG>::NC][AlgTraits<ALG>::M], float* stage, const int* tile_tab,
-    int lane, int kq, float x_scale, float inv_y, __amdgpu_buffer_rsrc_t yres, int Cout) {
+    int lane, int kq, float x_scale, float inv_y, __amdgpu_buffer_rsrc_t yres, int Cout, int th,
+    int tw) {
   constexpr int M = AlgTraits<ALG>::M, MM = M * M;
   constexpr unsigned esz = OUT == 2 ? 1u : 4u;
-  float* wr = stage + ((lane & 15) * 4 + (lane >> 4)) * MM;  // MM odd: conflict-free
+  const int per = th * tw, W = M * tw, HW = per * MM;
+  {
+    const int tl = lane & 15, f = lane >> 4;
+    const int il = tl / per, rem = tl - il * per;  // image of the wave, tile of the image
+    const int ti = rem / tw, tj = rem - ti * tw;
+    float* wr = stage + (il * 4 + f) * HW + (M * ti) * W + M * tj;
 #pragma unroll
-  for (int o1 = 0; o1 < M; ++o1) {
-    float out[M];
-    stream_row<ALG, float>(z, o1, out);
+    for (int o1 = 0; o1 < M; ++o1) {
+      float out[M];
+      stream_row<ALG, float>(z, o1, out);
 #pragma unroll
-    for (int o2 = 0; o2 < M; ++o2) wr[o1 * M + o2] = out[o2] * x_scale;
+      for (int o2 = 0; o2 < M; ++o2) wr[o1 * W + o2] = out[o2] * x_scale;
+    }
   }
   __builtin_amdgcn_wave_barrier();  // LDS accesses of one wave complete in order
   constexpr int NQ = 16 * MM;       // groups of four elements in the wave's block
@@ -139,10 +152,10 @@ __device__ __forceinline__ void store_planes(
   for (int k = 0; k < (NQ + 63) / 64; ++k) {
     const int q = lane + 64 * k;
     if (q < NQ) {
-      const int tl = q / MM, r = q - tl * MM;  // tile, group within the tile's four planes
+      const int il = q / HW, r = q - il * HW;  // image, group within its four planes
       const v4f v = *(const v4f*)(stage + 4 * q);
-      if (kvalid && tile_tab[16 + tl] > 0) {
-        const unsigned off = esz * (unsigned)(tile_tab[tl] + 4 * kq * MM + 4 * r);
+      if (kvalid && tile_tab[16 + il * per] > 0) {
+        const unsigned off = esz * (unsigned)(tile_tab[il * per] + 4 * kq * HW + 4 * r);
         if constexpr (OUT == 2) {
           // next layer's activation: ReLU, round half to even, clamp to [0, 127]
           constexpr float kMagic = 12582912.0f;

@@ -533,25 +533,30 @@ def test_int8_relu_output(binding, shape, path, alg):
 
 
 @pytest.mark.parametrize("alg", ["7x7_p132", "7x7_p144"])
+@pytest.mark.parametrize("path", ["staged", "fused"])
 @pytest.mark.parametrize("shape", [
     (1, 4, 4, 7, 7),      # one tile, one filter quad
     (37, 20, 44, 7, 7),   # ragged last 16-tile block, filters end inside a 32-filter group
     (16, 64, 96, 7, 7),   # whole blocks and groups
     (5, 9, 6, 7, 7),      # Cout not a multiple of 4: row-by-row stores
+    (2, 5, 12, 7, 14),    # two tiles per image
+    (3, 100, 8, 14, 14),  # four tiles per image, two 64-channel slices
+    (3, 4, 8, 14, 28),    # eight tiles per image: 24 tiles, a ragged second block
+    (2, 16, 36, 28, 28),  # sixteen tiles per image: one image per wave
 ])
-def test_one_tile_feature_maps_on_the_staged_path(binding, shape, alg):
-    """7x7 tiles on 7x7 maps: the staged output transform writes whole planes of y.
-    float32 and int8 outputs against the oracle."""
+def test_feature_maps_of_whole_images_per_wave(binding, shape, path, alg):
+    """7x7 tiles that cover the map exactly, 1, 2, 4, 8 or 16 to an image: the output
+    transform writes whole planes of y.  float32 and int8 outputs against the oracle."""
     x, w, xs, ws = uniform_case(shape, 650 + sum(shape))
-    print("case planes", shape, alg, flush=True)
+    print("case planes", shape, path, alg, flush=True)
     sx = oracle.calibrate_act_scales(x, alg)
     sw = oracle.calibrate_filter_scales(w, alg)
     y_ref = oracle.conv_requant(x, w, sx, sw, xs, ws, alg)
-    y = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path="staged", sx=sx, sw=sw)
+    y = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path=path, sx=sx, sw=sw)
     assert y.shape == y_ref.shape
     assert rel_err(y, y_ref) <= F32_TOL
     y_scale = float(np.float32(max(y_ref.max(), 1e-6) / 127.0 * 0.8))
-    y8 = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path="staged", out="i8", sx=sx,
+    y8 = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path=path, out="i8", sx=sx,
                         sw=sw, y_scale=y_scale)
     assert y8.dtype == np.int8 and y8.min() == 0 and y8.max() == 127
     assert check_i8_against_oracle(y8, y_ref, y_scale) < 1e-3
