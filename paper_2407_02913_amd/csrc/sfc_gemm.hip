@@ -274,9 +274,10 @@ static hipError_t launch_sums_alg(int out, const Geometry& g, const int32_t* M,
                                   const FilterViews& f, float x_scale, float inv_y, void* y,
                                   hipStream_t s) {
   constexpr bool kPairs = AlgTraits<ALG>::M % 2 == 0;
-  // 7x7 tiles on 7x7, 14x14, 28x28 ... maps: a wave's pairs are whole planes of y
-  if constexpr (AlgTraits<ALG>::M == 7) {
-    if (whole_image_tiles(7, g.H, g.W, g.th, g.tw, g.Cout))
+  // 7x7 tiles on 7x7, 14x14, 28x28 ... maps, 4x4 tiles on 4x4, 8x8, 16x16 ...: a wave's
+  // pairs are whole planes of y
+  if constexpr (AlgTraits<ALG>::M == 7 || AlgTraits<ALG>::M == 4) {
+    if (whole_image_tiles(AlgTraits<ALG>::M, g.H, g.W, g.th, g.tw, g.Cout))
       return out == 2 ? launch_sums_impl<ALG, 2, false, true>(g, M, f, x_scale, inv_y, y, s)
                       : launch_sums_impl<ALG, 0, false, true>(g, M, f, x_scale, inv_y, y, s);
   }

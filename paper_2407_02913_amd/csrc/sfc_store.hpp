@@ -117,8 +117,8 @@ __device__ __forceinline__ void store_pairs(
 // elements per lane, 1 KB of consecutive addresses per store instruction.  Row-by-row stores
 // put a 128-byte line together from pieces of 4*M bytes issued M row transforms apart, and
 // the L2 wrote such lines to memory about twice (WRITE_SIZE 45.8 MB for 25.7 MB of y on 7x7
-// maps).  Needs Cout % 4 == 0 (runs stay 16-byte aligned) and a staging block of 64*M*M
-// floats per wave.  The float32 runs go out as streaming stores: nothing stays dirty in
+// maps).  Used by the 7x7 and the 4x4 forms.  Needs Cout % 4 == 0 (runs stay 16-byte aligned)
+// and a staging block of 64*M*M floats per wave.  The float32 runs go out as streaming stores: nothing stays dirty in
 // the L2 for the end of the kernel (output transform from M on 7x7 maps 25.3 instead of
 // 27.1 us, fused kernel on 14x14 maps 40.5 instead of 42.3 us).
 inline bool whole_image_tiles(int M, int H, int W, int th, int tw, int Cout) {
@@ -143,8 +143,15 @@ __device__ __forceinline__ void store_planes(
     for (int o1 = 0; o1 < M; ++o1) {
       float out[M];
       stream_row<ALG, float>(z, o1, out);
+      if constexpr (M % 4 == 0) {  // rows of whole 16-byte groups
 #pragma unroll
-      for (int o2 = 0; o2 < M; ++o2) wr[o1 * W + o2] = out[o2] * x_scale;
+        for (int o2 = 0; o2 < M; o2 += 4)
+          *(v4f*)(wr + o1 * W + o2) = v4f{out[o2] * x_scale, out[o2 + 1] * x_scale,
+                                          out[o2 + 2] * x_scale, out[o2 + 3] * x_scale};
+      } else {
+#pragma unroll
+        for (int o2 = 0; o2 < M; ++o2) wr[o1 * W + o2] = out[o2] * x_scale;
+      }
     }
   }
   __builtin_amdgcn_wave_barrier();  // LDS accesses of one wave complete in order

@@ -43,6 +43,9 @@ LAYERS = {
     "resnet28": LayerShape("resnet28", 64, 128, 128, 28, 28, "relu", True, 3),
     "resnet14": LayerShape("resnet14", 128, 256, 256, 14, 14, "relu", True, 4),
     "resnet7": LayerShape("resnet7", 256, 512, 512, 7, 7, "relu", True, 5),
+    # CIFAR-sized feature maps (powers of two): 4x4 tiles cover them exactly
+    "cifar16": LayerShape("cifar16", 256, 128, 128, 16, 16, "relu", True, 6),
+    "cifar8": LayerShape("cifar8", 512, 256, 256, 8, 8, "relu", True, 7),
 }
 
 #: ResNet-18-shaped stack of stride-1 3x3 layers at batch 64: (channels, spatial, count)

@@ -532,21 +532,23 @@ def test_int8_relu_output(binding, shape, path, alg):
     assert frac < 1e-3
 
 
-@pytest.mark.parametrize("alg", ["7x7_p132", "7x7_p144"])
+@pytest.mark.parametrize("alg", ["7x7_p132", "7x7_p144", "4x4_p46", "4x4_p49"])
 @pytest.mark.parametrize("path", ["staged", "fused"])
-@pytest.mark.parametrize("shape", [
-    (1, 4, 4, 7, 7),      # one tile, one filter quad
-    (37, 20, 44, 7, 7),   # ragged last 16-tile block, filters end inside a 32-filter group
-    (16, 64, 96, 7, 7),   # whole blocks and groups
-    (5, 9, 6, 7, 7),      # Cout not a multiple of 4: row-by-row stores
-    (2, 5, 12, 7, 14),    # two tiles per image
-    (3, 100, 8, 14, 14),  # four tiles per image, two 64-channel slices
-    (3, 4, 8, 14, 28),    # eight tiles per image: 24 tiles, a ragged second block
-    (2, 16, 36, 28, 28),  # sixteen tiles per image: one image per wave
+@pytest.mark.parametrize("case", [  # (N, Cin, Cout, tile rows, tile columns)
+    (1, 4, 4, 1, 1),      # one tile, one filter quad
+    (37, 20, 44, 1, 1),   # ragged last 16-tile block, filters end inside a filter group
+    (16, 64, 96, 1, 1),   # whole blocks and groups
+    (5, 9, 6, 1, 1),      # Cout not a multiple of 4: row-by-row stores
+    (2, 5, 12, 1, 2),     # two tiles per image
+    (3, 100, 8, 2, 2),    # four tiles per image, two 64-channel slices
+    (3, 4, 8, 2, 4),      # eight tiles per image: 24 tiles, a ragged second block
+    (2, 16, 36, 4, 4),    # sixteen tiles per image: one image per wave
 ])
-def test_feature_maps_of_whole_images_per_wave(binding, shape, path, alg):
-    """7x7 tiles that cover the map exactly, 1, 2, 4, 8 or 16 to an image: the output
+def test_feature_maps_of_whole_images_per_wave(binding, case, path, alg):
+    """7x7 or 4x4 tiles that cover the map exactly, 1, 2, 4, 8 or 16 to an image: the output
     transform writes whole planes of y.  float32 and int8 outputs against the oracle."""
+    m = oracle.tile_out(alg)
+    shape = (*case[:3], m * case[3], m * case[4])
     x, w, xs, ws = uniform_case(shape, 650 + sum(shape))
     print("case planes", shape, path, alg, flush=True)
     sx = oracle.calibrate_act_scales(x, alg)
