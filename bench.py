@@ -64,7 +64,9 @@ def pick_variant(shape, alg=None, path=None, independent_batches=False):
     7x7 tiles on 14x14 and 7x7 maps (no ragged tiles at all), with the products as batched
     GEMMs through HBM once there are too few tiles for the fused kernel's operand stream
     (7x7 maps, 512 channels; with 256 channels on 8x8 maps the fused kernel is still ahead,
-    53 against 67 us); 4x4 tiles on the 16x16 and smaller maps that they cover and 7x7 tiles do not."""
+    53 against 67 us) or too few (tile block, filter group) pairs to give every compute unit a
+    workgroup of the fused kernel (256 channels on 14x14 maps at batch 64: 128 of them, 47 us
+    per layer staged against 53 fused); 4x4 tiles on the 16x16 and smaller maps that they cover and 7x7 tiles do not."""
     if alg is None:
         if (shape.Cin <= (128 if independent_batches else 64) and shape.H >= 28 and shape.H % 4 == 0
                 and shape.W % 4 == 0):
@@ -76,10 +78,14 @@ def pick_variant(shape, alg=None, path=None, independent_batches=False):
     if path is None:
         if shape.Cin <= 64:
             path = "single"
-        elif shape.H >= 14 or shape.Cin < 512:
-            path = "fused"
         else:
-            path = "staged"
+            m = int(alg[0])
+            tiles = shape.N * -(-shape.H // m) * -(-shape.W // m)
+            fused_workgroups = -(-tiles // 16) * -(-shape.Cout // 32)
+            if fused_workgroups < 256 or (shape.H < 14 and shape.Cin >= 512):
+                path = "staged"
+            else:
+                path = "fused"
     return alg, path
 
 
