@@ -34,8 +34,13 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
   const TileRect& tr = ip.tr;
   // Workgroups are dealt to the 8 XCDs round-robin by id; remap so that each XCD (each
   // L2) gets a contiguous range of rectangles: neighbours share halo rows and columns.
-  const int bx = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int c0 = blockIdx.y * 64;
+  // Position = (tile group, 64-channel group), the channel group varying fastest: the
+  // workgroups that write the two 64-byte halves of a line of V (Cp = 128) run next to
+  // each other on one XCD.
+  const int cgn = g.Cp >> 6;
+  const int pos = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int bx = pos / cgn;
+  const int c0 = (pos - bx * cgn) * 64;
 
   // tile slot -> row of V (-1: no such tile)
   int* row_tab = (int*)(lds + ip.tab_off);
@@ -92,7 +97,7 @@ static hipError_t launch_input_i8_alg(const Geometry& g, const InputPlan& ip, co
     (void)hipGetLastError();
     attr_done = true;
   }
-  const dim3 grid(tile_rect_groups(g, ip.tr), (unsigned)(g.Cp / 64));
+  const dim3 grid(tile_rect_groups(g, ip.tr) * (unsigned)(g.Cp / 64));
   hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), ip.lds_bytes, s, x, (int8_t*)V, inv_sx, g, ip);
   return hipGetLastError();
 }
