@@ -47,6 +47,7 @@ struct SinglePlan {
   int kgroups;         // groups of 64 filters
   unsigned stage_off;  // LDS byte offset of the per-wave output staging blocks
   unsigned lds_bytes;
+  int strips;          // 1: the tiles of a strip are whole image rows, y is written strip by strip
 };
 
 constexpr int kWaves6 = 16;  // waves per workgroup for the 6x6 forms
@@ -55,7 +56,9 @@ constexpr int kWaves6 = 16;  // waves per workgroup for the 6x6 forms
 // counts waves per SIMD: NW * WGS / 4).  2 for the SFC-4 forms, whose 48 KB of V and 24
 // partial outputs per pair leave room for a second workgroup, so that one workgroup's
 // loads and stores overlap the other's arithmetic.
-template <int ALG, int OUT, bool VEC2, int NW, int WGS>
+// STRIPS: the rectangle's strips are whole image rows (SinglePlan::strips); step 4 stages all
+// M rows of a pair and writes y strip by strip (store_strips).
+template <int ALG, int OUT, bool VEC2, int NW, int WGS, bool STRIPS = false>
 __global__ __launch_bounds__(NW * 64, NW * WGS / 4) void single_conv_kernel(
     const int8_t* __restrict__ x, const int8_t* __restrict__ Uf, const float* __restrict__ dqf,
     const float* __restrict__ inv_sx, float x_scale, float inv_y, void* __restrict__ y, Geometry g,
@@ -73,7 +76,8 @@ __global__ __launch_bounds__(NW * 64, NW * WGS / 4) void single_conv_kernel(
   const int W = g.W, H = g.H;
 
   // per-tile store data for step 4, written by 16 lanes now and read after the barriers
-  int* tile_tab = (int*)(lds + sp.stage_off + NW * 64 * M * 4);
+  constexpr int STAGE_FLOATS = 64 * M * (STRIPS ? M : 1);  // per wave
+  int* tile_tab = (int*)(lds + sp.stage_off + NW * STAGE_FLOATS * 4);
   if (threadIdx.x < 16) {
     const int tl = threadIdx.x;
     const TileCoord tc = tile_coord(g, tr, bx, tl);
@@ -96,8 +100,9 @@ __global__ __launch_bounds__(NW * 64, NW * WGS / 4) void single_conv_kernel(
   const __amdgpu_buffer_rsrc_t yres = __builtin_amdgcn_make_buffer_rsrc(
       y, 0, (int)(esz * (unsigned)(g.N * g.Cout) * (unsigned)(H * W)), kBufferFlags);
   const unsigned char* vlane = lds + (lane & 15) * 64 + (lane >> 4) * 16;  // tile l%16, channels 16*(l/16)..
-  // this wave's private staging block for one output row: [filter 0..3][tile 0..15][o2]
-  float* stage = (float*)(lds + sp.stage_off) + wave * (64 * M);
+  // this wave's private staging block: one output row as [filter 0..3][tile 0..15][o2], or all
+  // M rows in the order of y
+  float* stage = (float*)(lds + sp.stage_off) + wave * STAGE_FLOATS;
 
 #pragma unroll 1
   for (int qi = 0; qi < SPW; ++qi) {
@@ -151,7 +156,13 @@ __global__ __launch_bounds__(NW * 64, NW * WGS / 4) void single_conv_kernel(
     stream_vertical<ALG, float>(next, z);
 
     // ---- 4. store ----------------------------------------------------------------
-    store_pairs<ALG, OUT, VEC2>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, H, W);
+    if constexpr (STRIPS) {
+      store_strips<ALG, OUT>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, H, W, tr.S,
+                             tr.tlw);
+      __builtin_amdgcn_wave_barrier();  // the next pass writes the block again
+    } else {
+      store_pairs<ALG, OUT, VEC2>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, H, W);
+    }
   }
 }
 
@@ -180,17 +191,25 @@ __global__ __launch_bounds__(64) void repack_filter_kernel(const int8_t* __restr
 // 256-register budget of 8 waves
 static int single_waves(int alg) { return alg_tile(alg) == 6 ? kWaves6 : 8; }
 
-static bool make_single_plan(const Geometry& g, SinglePlan* sp) {
+// strips: plan for store_strips (staging blocks of M rows per pair), which needs a rectangle
+// of whole image rows
+static bool make_single_plan_for(const Geometry& g, SinglePlan* sp, bool strips) {
   if (g.Cp != 64 || g.alg > 5) return false;  // 3x3 filters only
   const int M = alg_tile(g.alg);
+  if (strips && (M != 4 || g.W != M * g.tw || g.H != M * g.th || g.Cout % 4 != 0)) return false;
   // LDS: the staged rows of the rectangle (later overwritten by V), the per-wave output
   // staging blocks, the per-tile store table
   const unsigned vbytes = (unsigned)g.P * 1024u;
-  const unsigned sbytes = (unsigned)single_waves(g.alg) * 64u * (unsigned)M * 4u + 256u;
+  const unsigned sbytes =
+      (unsigned)single_waves(g.alg) * 64u * (unsigned)(M * (strips ? M : 1)) * 4u + 256u;
   // the SFC-4 forms leave half of the 160 KB to a second workgroup on the compute unit
   const unsigned lds_max = (M == 4 ? 80u : 160u) * 1024u;
   if (vbytes + 16u + sbytes > lds_max) return false;
   if (!make_tile_rect(g, lds_max - 16u - sbytes, &sp->tr)) return false;
+  if (strips && (sp->tr.whole || sp->tr.chunks != 1 || sp->tr.tlw != g.tw ||
+                 sp->tr.S * sp->tr.tlw > 16))
+    return false;
+  sp->strips = strips ? 1 : 0;
   sp->kgroups = (g.Cout + 63) / 64;
   const unsigned xbytes = tile_rect_stage_bytes(g, sp->tr);
   sp->stage_off = ((xbytes > vbytes ? xbytes : vbytes) + 15u) & ~15u;
@@ -200,6 +219,10 @@ static bool make_single_plan(const Geometry& g, SinglePlan* sp) {
   const long long ub = (long long)sp->kgroups * 64 * (g.P + 3) * 64;
   const long long lim = 1ll << 31;
   return sp->lds_bytes <= lds_max && xb < lim && yb < lim && ub < lim;
+}
+
+static bool make_single_plan(const Geometry& g, SinglePlan* sp) {
+  return make_single_plan_for(g, sp, true) || make_single_plan_for(g, sp, false);
 }
 
 bool single_supported(const Geometry& g) {
@@ -242,11 +265,11 @@ void single_point_order(int alg, int* pt /*[P rounded up to a multiple of 4]*/) 
   }
 }
 
-template <int ALG, int OUT, bool VEC2, int NW>
+template <int ALG, int OUT, bool VEC2, int NW, bool STRIPS = false>
 static hipError_t launch_single_impl(const Geometry& g, const SinglePlan& sp, const int8_t* x,
                                      const FilterViews& f, float x_scale, float inv_y, void* y,
                                      hipStream_t s) {
-  auto kernel = single_conv_kernel<ALG, OUT, VEC2, NW, AlgTraits<ALG>::M == 4 ? 2 : 1>;
+  auto kernel = single_conv_kernel<ALG, OUT, VEC2, NW, AlgTraits<ALG>::M == 4 ? 2 : 1, STRIPS>;
   static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once
   if (!attr_done) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -266,6 +289,10 @@ static hipError_t launch_single_out(const Geometry& g, const SinglePlan& sp, con
                                     hipStream_t s) {
   constexpr int NW = AlgTraits<ALG>::M == 6 ? kWaves6 : 8;
   constexpr bool kPairs = AlgTraits<ALG>::M % 2 == 0;  // pairs of an output row stay aligned
+  if constexpr (AlgTraits<ALG>::M == 4) {
+    if (sp.strips)
+      return launch_single_impl<ALG, OUT, true, NW, true>(g, sp, x, f, x_scale, inv_y, y, s);
+  }
   if constexpr (kPairs) {
     if (g.W % 2 == 0) return launch_single_impl<ALG, OUT, true, NW>(g, sp, x, f, x_scale, inv_y, y, s);
   }
