@@ -219,7 +219,8 @@ __device__ __forceinline__ void store_strips(
     }
   }
   __builtin_amdgcn_wave_barrier();  // LDS accesses of one wave complete in order
-  const bool stream = W >= 48 && (run * 4) % 128 == 0;
+  // int8 output: the row-by-row stores of wide maps stream as well (store_pairs), and so do these
+  const bool stream = W >= 48 && (OUT == 2 || (run * 4) % 128 == 0);
   const int rq = run >> 2;      // groups of four elements per (filter, strip)
   const int nq = 4 * S * rq;    // ... in the wave's block, at most 16*M*M
   const bool kvalid = 4 * kq < Cout;
@@ -242,7 +243,8 @@ __device__ __forceinline__ void store_strips(
             t = __builtin_amdgcn_fmed3f(t, kMagic, kMagic + 127.0f);
             word |= (__float_as_uint(t) & 0xffu) << (8 * i);
           }
-          __builtin_amdgcn_raw_buffer_store_b32(word, yres, off, 0, 0);
+          if (stream) __builtin_amdgcn_raw_buffer_store_b32(word, yres, off, 0, kStreamStore);
+          else __builtin_amdgcn_raw_buffer_store_b32(word, yres, off, 0, 0);
         } else {
           if (stream)
             __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, v), yres, off, 0, kStreamStore);
