@@ -54,13 +54,14 @@ def stage_bytes(shape, P, tiles, path):
     return {"input_transform": x + v, "product": v + u + m, "output_transform": m + y}
 
 
-def pick_variant(shape, alg=None, path=None, independent_batches=False):
+def pick_variant(shape, alg=None, path=None):
     """Tile size and path per layer shape, from the per-layer timings on one MI355X: the
     single-kernel path where it exists (Cin <= 64); SFC-4's 4x4 tiles when they divide a
     large feature map (56x56, 28x28: no ragged tiles, two workgroups per compute unit) and
-    the channels are few (<= 64; <= 128 when independent batches overlap on several streams:
-    its two kernels take 41 us back to back against 40 us for 6x6 tiles, but 31 against 32 us
-    per step when they overlap); else 6x6 tiles while the feature map is large;
+    the channels are few (<= 128: on 28x28 maps its two kernels take 38.0 us back to back
+    against 40.4 us for 6x6 and 38.7 us for 7x7 tiles, and 29.7 against 31.4 and 31.9 us per
+    step when independent batches overlap on several streams); else 6x6 tiles while the
+    feature map is large;
     7x7 tiles on 14x14 and 7x7 maps (no ragged tiles at all), with the products as batched
     GEMMs through HBM once there are too few tiles for the fused kernel's operand stream
     (7x7 maps, 512 channels; with 256 channels on 8x8 maps the fused kernel is still ahead,
@@ -68,8 +69,7 @@ def pick_variant(shape, alg=None, path=None, independent_batches=False):
     workgroup of the fused kernel (256 channels on 14x14 maps at batch 64: 128 of them, 47 us
     per layer staged against 53 fused); 4x4 tiles on the 16x16 and smaller maps that they cover and 7x7 tiles do not."""
     if alg is None:
-        if (shape.Cin <= (128 if independent_batches else 64) and shape.H >= 28 and shape.H % 4 == 0
-                and shape.W % 4 == 0):
+        if shape.Cin <= 128 and shape.H >= 28 and shape.H % 4 == 0 and shape.W % 4 == 0:
             alg = "4x4_p46"
         elif shape.H % 7 and shape.W % 7 and shape.H % 4 == 0 and shape.W % 4 == 0 and shape.H <= 16:
             alg = "4x4_p46"  # 16x16, 8x8, 4x4 maps: 4x4 tiles cover them, 7x7 tiles do not
@@ -212,7 +212,7 @@ def main():
     torch.cuda.set_device(0)
     shape = synth.LAYERS[args.workload]
     if args.alg is None:  # the fastest form and path measured for this layer shape
-        args.alg, default_path = pick_variant(shape, None, args.path, independent_batches=True)
+        args.alg, default_path = pick_variant(shape, None, args.path)
     else:
         default_path = None
     ksize = binding.KERNEL_SIZE[args.alg]
