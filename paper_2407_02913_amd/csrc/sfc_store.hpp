@@ -33,7 +33,9 @@ __device__ __forceinline__ void store_pairs(
   // Cache policy of the y stores.  7x7 and 4x4 tiles divide the ResNet image widths; on wide
   // images a workgroup then writes long whole rows and the lines can stream past the L2
   // ("nt"): nothing is left dirty in the L2 for the end of the kernel to write back, which
-  // shortens the 4x4 single kernel on 56x56 maps from 19.6 to 17.0 us.  Everywhere else (6x6
+  // shortened the 4x4 single kernel on 56x56 maps from 19.6 to 17.0 us (it now writes whole
+  // strips there, store_strips; the 49-point form and the fused kernels still come through
+  // here on wide maps).  Everywhere else (6x6
   // tiles, or short rows of small feature maps, where a line is completed by several stores
   // or several workgroups) the L2 has to merge the pieces before they go to memory:
   // streaming those costs up to 2.5x the bytes in HBM writes.
