@@ -187,6 +187,29 @@ def test_bench_operation_counts_match_the_add_networks(tmp_path):
     assert bench.ADD_NETWORK_OPS["6x6_p88"][0] == 16 * 16 + 48
 
 
+def test_bench_variant_per_layer_shape():
+    """bench.py's choice of tile size and path: the benchmark layer runs on the single-kernel
+    path with 4x4 tiles, and the choice follows what each path supports."""
+    import bench
+    from paper_2407_02913_amd import synth
+
+    want = {"tiny32": ("4x4_p46", "single"), "resnet56": ("4x4_p46", "single"),
+            "resnet28": ("4x4_p46", "fused"), "resnet14": ("7x7_p132", "fused"),
+            "resnet7": ("7x7_p132", "staged"), "cifar16": ("4x4_p46", "fused"),
+            "cifar8": ("4x4_p46", "fused")}
+    for name, shape in synth.LAYERS.items():
+        assert bench.pick_variant(shape) == want[name], name
+    # an explicit choice is kept
+    assert bench.pick_variant(synth.LAYERS["resnet56"], "6x6_p88", "staged") == ("6x6_p88", "staged")
+    for shape in synth.stack_layers():
+        alg, path = bench.pick_variant(shape)
+        assert path != "single" or shape.Cin <= 64  # the single kernel takes one 64-channel slice
+        m = int(alg[0])
+        if path == "fused":  # at least one workgroup per compute unit
+            tiles = shape.N * -(-shape.H // m) * -(-shape.W // m)
+            assert -(-tiles // 16) * -(-shape.Cout // 32) >= 256
+
+
 def test_group_scales_matches_the_oracle_for_every_granularity(lib):
     """Host-only entry point: the ablation's scale groupings against the oracle's."""
     from paper_2407_02913_amd import binding
