@@ -1,15 +1,25 @@
 #!/usr/bin/env python3
 """Throughput of the SFC 3x3 int8 convolution hot path on one MI355X.
 
-A step is one pass of the whole hot path (input-tile transform, transform-domain
-products, output transform with dequantization and NCHW store) over one batch of
-synthetic ResNet-shaped input already resident in HBM.  The filter transform is
-done once, outside the timed region, as the paper amortizes it (Sec. 3).
-Buffers rotate over several sets so that consecutive steps do not re-hit the
-memory-side cache.  Prints ONE JSON line.
+A step is one pass of the whole hot path (input-tile transform, transform-domain products,
+output transform with dequantization or int8 requantization, NCHW store) over one batch of
+synthetic ResNet-shaped input already resident in HBM.  Filter transforms are done once,
+outside the timed region, as the paper amortizes them (Sec. 3).
+
+Workloads: the four single ResNet-shaped layers and the 13-layer stack of stride-1 3x3 layers
+at batch 64 with int8 activations handed from layer to layer.  The headline is the stack, the
+largest of them; every workload gets the same record in `configs`.
+
+Protocol, the same for every workload: one HIP stream; W untimed warm-up steps; the device kept
+busy for RAMP_MS (the clocks of an idle GPU take tens of milliseconds of load to come up); then
+repeats of exactly K steps each between two HIP events, at least five repeats and at least
+MIN_TIMED_MS of timed work; `ms_per_step` is the median repeat.  Buffers rotate over several
+sets whose footprint exceeds the 256 MB memory-side cache, so the figures are the cold ones.
+Per-kernel durations come from the same protocol with one kernel per launch.  Prints ONE JSON line.
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -20,445 +30,344 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
 MFMA_I8_PEAK_TOPS = 5000.0  # dense int8
-# Vector ALU: 256 compute units x 64 lanes x 2.4 GHz, one operation per lane and cycle (the
-# path's adds, conversions and scalings are neither fused multiply-adds nor packed).
+# Vector ALU, for the side figure `valu_frac`: 256 compute units x 64 lanes x 2.4 GHz, one
+# operation per lane and cycle (the path's adds, conversions and scalings are neither fused
+# multiply-adds nor packed).  Not a roof of the method: the instruction mix is the kernels' own.
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 # Arithmetic of the add networks per item, counted by tests/host/op_count.cpp:
 # algorithm -> (additions per input (tile, channel), operations per output (tile, filter)).
 ADD_NETWORK_OPS = {"6x6_p88": (304, 438), "6x6_p100": (300, 422), "7x7_p132": (379, 580),
                    "7x7_p144": (375, 564), "4x4_p46": (110, 158), "4x4_p49": (111, 159)}
+ROTATE_BYTES = 320 << 20  # footprint of the rotating buffer sets (> 256 MB memory-side cache)
+RAMP_MS = 120.0  # untimed load before every timed region
+MIN_TIMED_MS = 50.0  # timed work per figure, whatever --steps says
+MIN_REPEATS = 5
 
 
-def vector_ops(shape, alg, P, tiles):
+def vector_ops(cin, cout, alg, P, tiles):
     """Algorithmic vector-ALU operations of one pass: the add networks, 3 per point for the
     rounding to int8 (convert, scale-and-round, clamp), 2 per point for the int32 products
     (convert, dequantize) and one multiplication per output for the activation scale."""
+    if alg not in ADD_NETWORK_OPS:
+        return None
     m = int(alg[0])
     in_adds, out_ops = ADD_NETWORK_OPS[alg]
-    return tiles * (shape.Cin * (in_adds + 3 * P) + shape.Cout * (out_ops + 2 * P + m * m))
-ROTATE_BYTES = 640 << 20  # footprint of the rotating buffer sets (> 256 MB memory-side cache)
-RAMP_MS = 120.0  # untimed load before every timed region (see ramp() in main)
+    return tiles * (cin * (in_adds + 3 * P) + cout * (out_ops + 2 * P + m * m))
 
 
-def stage_bytes(shape, P, tiles, path):
-    """Algorithmic bytes per launch of each kernel (requantized mode)."""
-    x = shape.N * shape.Cin * shape.H * shape.W
-    v = P * tiles * shape.Cin
-    u = P * shape.Cout * shape.Cin
-    m = 4 * P * tiles * shape.Cout
-    y = 4 * shape.N * shape.Cout * shape.H * shape.W
-    if path == "single":
-        return {"single_conv": x + u + y}
-    if path == "fused":
-        return {"input_transform": x + v, "fused_product_output": v + u + y}
-    return {"input_transform": x + v, "product": v + u + m, "output_transform": m + y}
+class Timer:
+    """HIP events on the current stream; repeats of exactly `steps` calls of fn(i)."""
 
+    def __init__(self, torch):
+        self.torch = torch
+        self.e0 = torch.cuda.Event(enable_timing=True)
+        self.e1 = torch.cuda.Event(enable_timing=True)
 
-def pick_variant(shape, alg=None, path=None):
-    """Tile size and path per layer shape, from the per-layer timings on one MI355X: the
-    single-kernel path where it exists (Cin <= 64); SFC-4's 4x4 tiles when they divide a
-    large feature map (56x56, 28x28: no ragged tiles, two workgroups per compute unit) and
-    the channels are few (<= 128: on 28x28 maps its two kernels take 38.0 us back to back
-    against 40.4 us for 6x6 and 38.7 us for 7x7 tiles, and 29.7 against 31.4 and 31.9 us per
-    step when independent batches overlap on several streams); else 6x6 tiles while the
-    feature map is large;
-    7x7 tiles on 14x14 and 7x7 maps (no ragged tiles at all), with the products as batched
-    GEMMs through HBM once there are too few tiles for the fused kernel's operand stream
-    (7x7 maps, 512 channels; with 256 channels on 8x8 maps the fused kernel is still ahead,
-    53 against 67 us) or too few (tile block, filter group) pairs to give every compute unit a
-    workgroup of the fused kernel (256 channels on 14x14 maps at batch 64: 128 of them, 47 us
-    per layer staged against 53 fused); 4x4 tiles on the 16x16 and smaller maps that they cover and 7x7 tiles do not."""
-    if alg is None:
-        if shape.Cin <= 128 and shape.H >= 28 and shape.H % 4 == 0 and shape.W % 4 == 0:
-            alg = "4x4_p46"
-        elif shape.H % 7 and shape.W % 7 and shape.H % 4 == 0 and shape.W % 4 == 0 and shape.H <= 16:
-            alg = "4x4_p46"  # 16x16, 8x8, 4x4 maps: 4x4 tiles cover them, 7x7 tiles do not
-        else:
-            alg = "6x6_p88" if shape.H >= 28 else "7x7_p132"
-    if path is None:
-        if shape.Cin <= 64:
-            path = "single"
-        else:
-            m = int(alg[0])
-            tiles = shape.N * -(-shape.H // m) * -(-shape.W // m)
-            fused_workgroups = -(-tiles // 16) * -(-shape.Cout // 32)
-            if fused_workgroups < 256 or (shape.H < 14 and shape.Cin >= 512):
-                path = "staged"
-            else:
-                path = "fused"
-    return alg, path
-
-
-def run_stack(args):
-    """The 13 stride-1 3x3 layers of the ResNet-18-shaped stack at batch 64, filter transforms
-    done beforehand, int8 activations handed from layer to layer inside each resolution stage
-    (the stride-2 layers between stages are not part of this path: every stage starts from its
-    own synthetic activations).  One step = the 13 layers; the layers of a stage run back to back
-    on one stream, the four stages (independent chains) on a stream each."""
-    import numpy as np
-    import torch
-
-    from paper_2407_02913_amd import binding, synth
-
-    binding.load()
-    torch.cuda.set_device(0)
-    layers = synth.stack_layers()
-    plans, bufs, chosen = [], [], []
-    for shape in layers:
-        d = synth.make_layer(shape, batch=4)  # weights and calibration data; activations below
-        alg, path = pick_variant(shape, args.alg, args.path)
-        chosen.append(f"{alg}/{path}")
-        plan = binding.Plan(shape.N, shape.Cin, shape.Cout, shape.H, shape.W, alg=alg,
-                            mode="requant", out="i8", path=path, per_channel_wscale=True)
-        w_dev = torch.from_numpy(d["w"]).cuda()
-        xc_dev = torch.from_numpy(d["x_calib"]).cuda()
-        calib = binding.Plan(4, shape.Cin, shape.Cout, shape.H, shape.W, alg=alg, mode="requant",
-                             path="staged", per_channel_wscale=True)
-        scratch = binding.device_buffer(calib.workspace_bytes)
-        sx = calib.calibrate_act_scales(xc_dev, scratch)
-        sw = calib.calibrate_filter_scales(w_dev, scratch)
-        calib.close()
-        plan.set_point_scales(sx, sw)
-        # output scale: spread of a sum of 9*Cin products of the synthetic distributions
-        plan.set_output_scale(float(4.0 * 0.02 * 0.0125 * 30.0 * 20.0 * np.sqrt(9.0 * shape.Cin) / 127.0))
-        fbuf = binding.device_buffer(plan.filter_bytes)
-        plan.transform_filter(w_dev, d["w_scale"], fbuf)
-        plans.append(plan)
-        bufs.append((fbuf, binding.device_buffer(plan.workspace_bytes),
-                     torch.empty((shape.N, shape.Cout, shape.H, shape.W), dtype=torch.int8, device="cuda")))
-    stage_in = {}
-    for shape in layers:
-        if shape.Cin not in stage_in:
-            rng = np.random.default_rng(synth.BASE_SEED + shape.Cin)
-            a = np.clip(np.rint(np.abs(rng.normal(0.0, 30.0, (shape.N, shape.Cin, shape.H, shape.W)))), 0, 127)
-            stage_in[shape.Cin] = torch.from_numpy(a.astype(np.int8)).cuda()
-
-    stage_streams = {cin: torch.cuda.Stream() for cin in stage_in}
-
-    def step(streams=None):
-        prev = None
-        for shape, plan, (_, ws, y) in zip(layers, plans, bufs):
-            x = stage_in[shape.Cin] if prev is None or prev[0].Cin != shape.Cin else prev[1]
-            plan.conv2d(x, 0.02, y, ws, stream=None if streams is None else streams[shape.Cin])
-            prev = (shape, y)
-
-    def timed(streams):
-        for _ in range(args.warmup):
-            step(streams)
-        torch.cuda.synchronize()
-        t_end = time.perf_counter() + RAMP_MS * 1e-3  # untimed load: the clocks of an idle GPU ramp up
+    def ramp(self, fn, ms=RAMP_MS):
+        t_end = time.perf_counter() + ms * 1e-3
+        i = 0
         while time.perf_counter() < t_end:
-            step(streams)
-            torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step(streams)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / args.steps
+            for _ in range(20):
+                fn(i)
+                i += 1
+            self.torch.cuda.synchronize()
 
-    ms_one_stream = timed(None)
-    ms = timed(stage_streams)
-    ops = sum(sh.direct_ops for sh in layers)
-    per_layer = []
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for shape, plan, (_, ws, y) in zip(layers, plans, bufs):
-        x = stage_in[shape.Cin]
-        e0.record()
-        for _ in range(20):
-            plan.conv2d(x, 0.02, y, ws)
-        e1.record()
+    def once(self, fn, steps, first=0):
+        self.e0.record()
+        for i in range(steps):
+            fn(first + i)
+        self.e1.record()
+        self.torch.cuda.synchronize()
+        return self.e0.elapsed_time(self.e1) / steps
+
+    def median(self, fn, steps, warmup=0):
+        """ms per call: median over repeats of `steps` calls each (>= MIN_REPEATS repeats and
+        >= MIN_TIMED_MS of timed work in total)."""
+        for i in range(warmup):
+            fn(i)
+        self.torch.cuda.synchronize()
+        self.ramp(fn)
+        first = self.once(fn, steps)
+        repeats = max(MIN_REPEATS, min(400, math.ceil(MIN_TIMED_MS / max(first * steps, 1e-6))))
+        vals = [self.once(fn, steps, r * steps) for r in range(repeats)]
+        vals.sort()
+        return vals[len(vals) // 2], repeats
+
+
+def graph_ms(torch, timer, fn, steps):
+    """The same steps captured once into a HIP graph (kernel launches only) and replayed:
+    what is left when the host's launch overhead is taken out.  A measurement aid."""
+    try:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(steps):
+                    fn(i, side)
+        for _ in range(2):
+            graph.replay()
         torch.cuda.synchronize()
-        per_layer.append(round(e0.elapsed_time(e1) * 1e3 / 20, 1))
-    print(json.dumps({
-        "metric": "direct-conv-equivalent int8 TOPS, 13-layer stack", "value": round(ops / (ms * 1e-3) / 1e12, 2),
-        "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": "resnet18 stack: 13 stride-1 3x3 layers, batch 64, int8 activations between layers",
-                   "variants": chosen, "direct_gop": round(ops / 1e9, 1), "streams": len(stage_streams),
-                   "single_stream_ms_per_step": round(ms_one_stream, 4), "layer_us": per_layer}}))
+        ms, _ = timer.median(lambda i: graph.replay(), 1)
+        del graph
+        return ms / steps
+    except Exception as exc:
+        print(f"graph replay skipped: {exc}", file=sys.stderr)
+        return None
+
+
+def traffic_from_profiles(kernel, workload, alg):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel, if any."""
+    tfile = os.path.join(ROOT, "profiles", f"traffic_{kernel}_{workload}_{alg}.txt")
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("hbm_bytes_per_launch"):
+                return float(line.split()[1])
+    return None
+
+
+def roofline(kernel_rows, workload):
+    """The roofline object of a workload from its per-kernel rows: the dominant kernel (largest
+    share of a step) against the HBM roof -- algorithmic bytes / its average duration / 8 TB/s --
+    and the product kernel against the int8 MFMA roof."""
+    dom = max(kernel_rows, key=lambda r: r["us_per_step"])
+    prod = max((r for r in kernel_rows if r["sfc_ops"]), key=lambda r: r["us_per_step"])
+    achieved = dom["algorithmic_bytes"] / (dom["avg_us"] * 1e-6) / 1e9
+    out = {"bound": "hbm", "kernel": dom["kernel"], "layer": dom["layer"], "achieved": round(achieved, 1),
+           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+           "traffic": traffic_from_profiles(dom["kernel"], dom["layer"], dom["alg"]),
+           "algorithmic_bytes": dom["algorithmic_bytes"], "avg_us": round(dom["avg_us"], 2),
+           "share_of_step": round(dom["us_per_step"] / sum(r["us_per_step"] for r in kernel_rows), 3),
+           "product_kernel": prod["kernel"] + " " + prod["layer"],
+           "product_mfma_frac": round(prod["sfc_ops"] / (prod["avg_us"] * 1e-6) / 1e12 / MFMA_I8_PEAK_TOPS, 4)}
+    if dom.get("vector_ops"):
+        out["valu_frac"] = round(dom["vector_ops"] / (dom["avg_us"] * 1e-6) / 1e12 / VALU_PEAK_TOPS, 4)
+    return out
+
+
+def kernel_rows(timer, layer, name, run_stage, launches, count=1):
+    """Per-kernel average durations of one layer: each kernel alone, back to back, over the
+    rotating sets (every set already holds valid V / M from full passes)."""
+    rows = []
+    kernels = layer.kernels()
+    for kname, (mask, nbytes, ops) in kernels.items():
+        ms, _ = timer.median(lambda i: run_stage(i, mask), launches)
+        row = {"kernel": kname, "layer": name, "alg": layer.alg, "avg_us": ms * 1e3,
+               "us_per_step": ms * 1e3 * count, "launches_per_step": count,
+               "algorithmic_bytes": nbytes, "sfc_ops": ops}
+        if len(kernels) == 1:
+            row["vector_ops"] = vector_ops(layer.shape.Cin, layer.shape.Cout, layer.alg, layer.P, layer.tiles)
+        rows.append(row)
+    return rows
+
+
+def public_rows(rows):
+    return [{"kernel": r["kernel"], "layer": r["layer"], "avg_us": round(r["avg_us"], 2),
+             "launches_per_step": r["launches_per_step"],
+             "hbm_gbs": round(r["algorithmic_bytes"] / (r["avg_us"] * 1e-6) / 1e9, 1),
+             "hbm_frac": round(r["algorithmic_bytes"] / (r["avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+             **({"mfma_frac": round(r["sfc_ops"] / (r["avg_us"] * 1e-6) / 1e12 / MFMA_I8_PEAK_TOPS, 4)}
+                if r["sfc_ops"] else {})} for r in rows]
+
+
+def bench_layer(args, name, torch, timer):
+    """One ResNet-shaped layer, float32 output."""
+    from paper_2407_02913_amd import binding, layers, synth
+
+    shape = synth.LAYERS[name]
+    data = synth.make_layer(shape)
+    layer = layers.Layer(shape, data, out="f32", alg=args.alg or "auto", path=args.path or "auto")
+    x_host = torch.from_numpy(data["x"])
+    ybytes = 4 * shape.N * shape.Cout * shape.H * shape.W
+    per_set = x_host.numel() + layer.workspace_bytes + ybytes
+    nsets = args.buffer_sets if args.buffer_sets > 0 else max(2, min(24, -(-ROTATE_BYTES // per_set)))
+    sets = [(x_host.cuda(), binding.device_buffer(layer.workspace_bytes), layer.new_output())
+            for _ in range(nsets)]
+
+    def step(i, stream=None, mask=binding.STAGE_ALL):
+        xd, ws, y = sets[i % nsets]
+        layer.run(xd, y, ws, stream=stream, stages=mask)
+
+    ms, repeats = timer.median(step, args.steps, args.warmup)
+    rows = kernel_rows(timer, layer, name, lambda i, mask: step(i, None, mask), max(50, args.steps))
+    ksize = layer.plan.kernel_size
+    ops = shape.direct_ops * ksize * ksize // 9
+    rec = {"workload": f"{name}: N={shape.N} Cin=Cout={shape.Cin} H=W={shape.H} {ksize}x{ksize} s1 p{(ksize - 1) // 2}, float32 out",
+           "algorithm": layer.alg, "path": layer.path, "P": layer.P,
+           "value": round(ops / (ms * 1e-3) / 1e12, 2), "unit": "TOPS", "ms_per_step": round(ms, 5),
+           "repeats": repeats, "buffer_sets": nsets, "direct_gop": round(ops / 1e9, 2),
+           "kernels": public_rows(rows), "roofline": roofline(rows, name)}
+    if not args.quick:
+        rec["graph_replay_ms_per_step"] = graph_ms(torch, timer, lambda i, s: step(i, s), min(nsets, 16))
+        if rec["graph_replay_ms_per_step"]:
+            rec["graph_replay_ms_per_step"] = round(rec["graph_replay_ms_per_step"], 5)
+    layer.close()
+    del sets
+    torch.cuda.empty_cache()
+    return rec
+
+
+def bench_stack(args, torch, timer):
+    """The 13 stride-1 3x3 layers of the ResNet-18-shaped stack at batch 64, int8 activations
+    handed from layer to layer inside each resolution stage (the stride-2 layers between stages
+    are not part of this path: every stage starts from its own synthetic activations).  One
+    step = the 13 layers back to back on one stream."""
+    import numpy as np
+
+    from paper_2407_02913_amd import binding, layers, synth
+
+    shapes = synth.stack_layers()
+    lay = [layers.Layer(s, synth.make_layer(s, batch=4), out="i8", alg=args.alg or "auto",
+                        path=args.path or "auto") for s in shapes]
+    ws_bytes = max(l.workspace_bytes for l in lay)
+    stages = sorted({(s.Cin, s.H) for s in shapes}, reverse=True, key=lambda t: t[1])
+    act_bytes = sum(3 * shapes[0].N * c * h * h for c, h in stages)
+    nsets = args.buffer_sets if args.buffer_sets > 0 else max(2, -(-ROTATE_BYTES // (act_bytes + ws_bytes)))
+    sets = []
+    for k in range(nsets):
+        bufs = {}
+        for c, h in stages:
+            rng = np.random.default_rng(synth.BASE_SEED + c + 1000 * k)
+            a = synth.activations((shapes[0].N, c, h, h), "relu", rng)
+            bufs[c] = [torch.from_numpy(a).cuda(),
+                       torch.empty((shapes[0].N, c, h, h), dtype=torch.int8, device="cuda"),
+                       torch.empty((shapes[0].N, c, h, h), dtype=torch.int8, device="cuda")]
+        sets.append((bufs, binding.device_buffer(ws_bytes)))
+
+    def step(i, stream=None):
+        bufs, ws = sets[i % nsets]
+        done = {}
+        for l in lay:
+            c = l.shape.Cin
+            k = done.get(c, 0)  # layer k of its stage reads buffer k (0: the stage input) ...
+            src = bufs[c][0] if k == 0 else bufs[c][1 + (k - 1) % 2]
+            l.run(src, bufs[c][1 + k % 2], ws, stream=stream)  # ... and writes the other one
+            done[c] = k + 1
+
+    ms, repeats = timer.median(step, args.steps, args.warmup)
+    ops = sum(s.direct_ops for s in shapes)
+    rows = []
+    for c, h in stages:
+        group = [l for l in lay if l.shape.Cin == c]
+        l0 = group[0]
+
+        def run_stage(i, mask, l0=l0, c=c):
+            bufs, ws = sets[i % nsets]
+            l0.run(bufs[c][0], bufs[c][1], ws, stages=mask)
+
+        for i in range(nsets):  # V (and M) of this layer in every set's workspace
+            run_stage(i, binding.STAGE_ALL)
+        rows += kernel_rows(timer, l0, f"stack_c{c}_s{h}", run_stage, max(50, args.steps), count=len(group))
+    rec = {"workload": "resnet18 stack: 13 stride-1 3x3 layers (4x 64@56, 3x 128@28, 3x 256@14, 3x 512@7), "
+                       "batch 64, int8 activations between layers",
+           "algorithm": sorted({l.alg for l in lay}), "path": [l.path for l in lay],
+           "value": round(ops / (ms * 1e-3) / 1e12, 2), "unit": "TOPS", "ms_per_step": round(ms, 5),
+           "repeats": repeats, "buffer_sets": nsets, "direct_gop": round(ops / 1e9, 2),
+           "kernels": public_rows(rows), "roofline": roofline(rows, "stack")}
+    if not args.quick:
+        g = graph_ms(torch, timer, lambda i, s: step(i, s), nsets)
+        rec["graph_replay_ms_per_step"] = None if g is None else round(g, 5)
+    for l in lay:
+        l.close()
+    return rec
+
+
+def cpu_baseline(args):
+    """The oracle as it stands, on the host cores: whole passes of the headline workload (the
+    13-layer stack) at a reduced batch until about 10 s have gone by, then the plain direct
+    convolution (the definition of the result) on the same sample."""
+    import numpy as np
+
+    from oracle import sfc as oracle  # the cpu_baseline leg is the only user of the oracle here
+    from paper_2407_02913_amd import synth
+
+    try:
+        from threadpoolctl import threadpool_info
+
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    batch, alg = 4, "4x4_p46"
+    shapes = synth.stack_layers(batch=batch)
+    data = [synth.make_layer(s) for s in shapes]
+    scales = [(oracle.calibrate_act_scales(d["x_calib"], alg), oracle.calibrate_filter_scales(d["w"], alg))
+              for d in data]
+    ops = sum(s.direct_ops for s in shapes)
+    passes, t0 = 0, time.perf_counter()
+    while True:
+        for d, (sx, sw) in zip(data, scales):
+            oracle.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"], alg)
+        passes += 1
+        dt = time.perf_counter() - t0
+        if dt >= 10.0 or passes >= 50:
+            break
+    dpasses, t0 = 0, time.perf_counter()
+    while True:
+        for d in data:
+            oracle.direct_conv(d["x"], d["w"])
+        dpasses += 1
+        ddt = time.perf_counter() - t0
+        if ddt >= 5.0 or dpasses >= 50:
+            break
+    return {"value": round(passes * ops / dt / 1e12, 5), "unit": "TOPS", "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle.conv_requant ({alg}) over the 13 layers of the stack at batch {batch} "
+                      f"(filter transforms included), {passes} passes in {dt:.1f} s; numpy: the per-point "
+                      "products run in its threaded BLAS, the integer transforms on one thread",
+            "direct_conv_value": round(dpasses * ops / ddt / 1e12, 5),
+            "direct_conv_sample": f"oracle.direct_conv (nine threaded float64 tensor contractions) on the same "
+                                  f"layers, {dpasses} passes in {ddt:.1f} s"}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="resnet56")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="all",
+                    help="all | stack | resnet56 | resnet28 | resnet14 | resnet7 (the headline is the stack; "
+                         "a single workload prints its own record as the headline)")
     ap.add_argument("--path", default=None, choices=[None, "staged", "fused", "single"])
     ap.add_argument("--alg", default=None,
                     help="6x6_p88 | 6x6_p100 | 7x7_p132 | 7x7_p144 | 4x4_p46 | 4x4_p49, or with 5x5 filters "
-                         "6x6_5x5_p184 | 6x6_5x5_p196 (default: 4x4_p46 where Cin <= 64 and 4 divides the "
-                         "feature map, else 6x6_p88; per layer for the stack)")
+                         "6x6_5x5_p184 | 6x6_5x5_p196 (default: the library's choice per layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--streams", type=int, default=3,
-                    help="HIP streams the steps are dealt to round-robin (independent batches overlap)")
+    ap.add_argument("--quick", action="store_true", help="skip the graph-replay side figure")
     ap.add_argument("--buffer-sets", type=int, default=0,
-                    help="rotating input/workspace/output sets (0: enough to exceed the memory-side cache)")
+                    help="rotating buffer sets (0: enough to exceed the memory-side cache)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the layer shards over "
               "the batch with no exchange step); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    if args.workload == "stack":
-        return run_stack(args)
-    import numpy as np
     import torch
 
-    from paper_2407_02913_amd import binding, synth
+    from paper_2407_02913_amd import binding
 
     binding.load()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    shape = synth.LAYERS[args.workload]
-    if args.alg is None:  # the fastest form and path measured for this layer shape
-        args.alg, default_path = pick_variant(shape, None, args.path)
-    else:
-        default_path = None
-    ksize = binding.KERNEL_SIZE[args.alg]
-    data = synth.make_layer(shape, kernel=ksize)
-    # one kernel where the layer allows it (3x3 filters, Cin <= 64), else input transform +
-    # fused product/output
-    path = args.path or default_path or ("single" if shape.Cin <= 64 and ksize == 3 else binding.DEFAULT_PATH)
-    direct_ops = shape.direct_ops * ksize * ksize // 9
-
-    plan = binding.Plan(shape.N, shape.Cin, shape.Cout, shape.H, shape.W, alg=args.alg,
-                        mode="requant", path=path, per_channel_wscale=shape.per_channel_wscale)
-    x_host = torch.from_numpy(data["x"])
-    w_dev = torch.from_numpy(data["w"]).cuda()
-    xc_dev = torch.from_numpy(data["x_calib"]).cuda()
-    fbuf = binding.device_buffer(plan.filter_bytes)
-    # scales from the library's own abs-max calibration (no oracle on the product path)
-    scratch = binding.device_buffer(plan.workspace_bytes)
-    sx = plan.calibrate_act_scales(xc_dev, scratch)
-    sw = plan.calibrate_filter_scales(w_dev, scratch)
-    plan.set_point_scales(sx, sw)
-    plan.transform_filter(w_dev, data["w_scale"], fbuf)
-    del scratch
-
-    ybytes = 4 * shape.N * shape.Cout * shape.H * shape.W
-    per_set = x_host.numel() + plan.workspace_bytes + ybytes
-    nsets = args.buffer_sets if args.buffer_sets > 0 else max(2, min(24, -(-ROTATE_BYTES // per_set)))
-    # a whole number of sets per stream: a set is then always used on the same stream
-    nsets = -(-nsets // max(1, args.streams)) * max(1, args.streams)
-    sets = []
-    for _ in range(nsets):
-        sets.append((x_host.cuda(), binding.device_buffer(plan.workspace_bytes),
-                     torch.empty((shape.N, shape.Cout, shape.H, shape.W), dtype=torch.float32,
-                                 device="cuda")))
-    xs = float(data["x_scale"])
-
-    def step(i, mask=binding.STAGE_ALL, stream=None):
-        xd, ws, y = sets[i % nsets]
-        plan.conv2d_stages(xd, xs, y, ws, mask, stream=stream)
-
-    # Whole-job throughput: every step is an independent batch with its own buffers, so
-    # consecutive steps are dealt to a few streams and the device overlaps one batch's
-    # kernels with another's.  The K timed steps are launched from the host between two
-    # device synchronizations and timed with the host clock; beside that figure, the same K
-    # steps captured once into a HIP graph with one branch per stream (kernel launches only)
-    # and replayed.
-    nstreams = max(1, min(args.streams, nsets))
-    streams = [torch.cuda.Stream() for _ in range(nstreams)]
-
-    def ramp(mask=binding.STAGE_ALL, on_streams=True):
-        """Untimed steps until the device has been busy for RAMP_MS: the clocks of an idle GPU
-        take some tens of milliseconds of load to come up (the first 500 steps of this layer run
-        at 21 us, the steady state at 16 us), so every timed region starts from a busy device."""
-        t_end = time.perf_counter() + RAMP_MS * 1e-3
-        i = 0
-        while time.perf_counter() < t_end:
-            for _ in range(50):
-                step(i, mask, stream=streams[i % nstreams] if on_streams else None)
-                i += 1
-            torch.cuda.synchronize()
-
-    for i in range(args.warmup):
-        step(i, stream=streams[i % nstreams])
-    torch.cuda.synchronize()
-    ramp()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i, stream=streams[i % nstreams])
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    job_graph_ms = None
-    try:
-        side = torch.cuda.Stream()
-        job = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(job, stream=side):
-                for b in streams:
-                    b.wait_stream(side)
-                for i in range(args.steps):
-                    step(i, stream=streams[i % nstreams])
-                for b in streams:
-                    side.wait_stream(b)
-        job.replay()  # untimed: the first replay uploads the graph
-        torch.cuda.synchronize()
-        ramp()  # the capture left the device idle
-        t0 = time.perf_counter()
-        job.replay()
-        torch.cuda.synchronize()
-        job_graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-        del job
-    except Exception as exc:  # a measurement aid, never the product path
-        print(f"graph of the timed steps not captured: {exc}", file=sys.stderr)
-
-    # latency of one step alone: same steps back to back on one stream, HIP events
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    ramp(on_streams=False)
-    e0.record()
-    for i in range(args.steps):
-        step(i)
-    e1.record()
-    torch.cuda.synchronize()
-    single_stream_ms = e0.elapsed_time(e1) / args.steps
-
-    # The same steps replayed from one HIP graph (launch overhead taken out), and the warm
-    # figure: one buffer set, inputs and outputs staying in the memory-side cache.
-    graph_ms = warm_ms = None
-    try:
-        side = torch.cuda.Stream()
-        graph = torch.cuda.CUDAGraph()
-        nrep = min(nsets, 16)
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph, stream=side):
-                for i in range(nrep):
-                    step(i, stream=side)
-        for _ in range(3):
-            graph.replay()
-        torch.cuda.synchronize()
-        ramp(on_streams=False)
-        reps = max(2, args.steps // nrep)
-        e0.record()
-        for _ in range(reps):
-            graph.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        graph_ms = e0.elapsed_time(e1) / (reps * nrep)
-    except Exception as exc:  # the capture is a measurement aid, never the product path
-        print(f"graph replay skipped: {exc}", file=sys.stderr)
-    torch.cuda.synchronize()
-    ramp(on_streams=False)
-    for _ in range(10):
-        step(0)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(args.steps):
-        step(0)
-    e1.record()
-    torch.cuda.synchronize()
-    warm_ms = e0.elapsed_time(e1) / args.steps
-
-    # per-kernel durations: each stage alone, back to back, over the rotating sets
-    # (every set already holds valid V / M from the full passes above)
-    if path == "single":
-        stages = {"single_conv": binding.STAGE_ALL}
-    elif path == "fused":
-        stages = {"input_transform": binding.STAGE_INPUT,
-                  "fused_product_output": binding.STAGE_PRODUCT | binding.STAGE_OUTPUT}
-    else:
-        stages = {"input_transform": binding.STAGE_INPUT, "product": binding.STAGE_PRODUCT,
-                  "output_transform": binding.STAGE_OUTPUT}
-    launches = max(50, min(args.steps, 400))
-    stage_us = {}
-    for name, mask in stages.items():
-        ramp(mask, on_streams=False)
-        e0.record()
-        for i in range(launches):
-            step(i, mask)
-        e1.record()
-        torch.cuda.synchronize()
-        stage_us[name] = e0.elapsed_time(e1) * 1e3 / launches
-    # calibration: the library's plain copy kernel over rotating 128 MiB buffers gives
-    # the streaming bandwidth this device reaches in this run (read + write bytes)
-    cal_bytes = 128 << 20
-    cal = [(torch.empty(cal_bytes, dtype=torch.uint8, device="cuda"),
-            torch.empty(cal_bytes, dtype=torch.uint8, device="cuda")) for _ in range(3)]
-    for i in range(3):
-        binding.stream_copy(cal[i][1], cal[i][0])
-    torch.cuda.synchronize()
-    e0.record()
-    for i in range(12):
-        binding.stream_copy(cal[i % 3][1], cal[i % 3][0])
-    e1.record()
-    torch.cuda.synchronize()
-    copy_gbs = 2 * cal_bytes * 12 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del cal
-    bytes_per = stage_bytes(shape, plan.P, plan.tiles, path)
-    dominant = max(stage_us, key=stage_us.get)
-    achieved = bytes_per[dominant] / (stage_us[dominant] * 1e-6) / 1e9
-    traffic = None
-    tfile = os.path.join(ROOT, "profiles", f"traffic_{dominant}_{args.workload}_{args.alg}.txt")
-    if os.path.exists(tfile):
-        for line in open(tfile):
-            if line.startswith("hbm_bytes_per_launch"):
-                traffic = float(line.split()[1])
-    hbm_frac = achieved / HBM_PEAK_GBS
-    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_frac, 4),
-                "traffic": traffic, "algorithmic_bytes": bytes_per[dominant],
-                "avg_us": round(stage_us[dominant], 2),
-                "stages_us": {k: round(v, 2) for k, v in stage_us.items()},
-                "stages_gbs": {k: round(bytes_per[k] / (stage_us[k] * 1e-6) / 1e9, 1) for k in stage_us},
-                "stream_copy_gbs": round(copy_gbs, 1)}
-    sfc_ops = 2 * plan.P * plan.tiles * shape.Cin * shape.Cout
-    prod_key = {"single": "single_conv", "fused": "fused_product_output", "staged": "product"}[path]
-    roofline["product_mfma_frac"] = round(sfc_ops / (stage_us[prod_key] * 1e-6) / 1e12 / MFMA_I8_PEAK_TOPS, 4)
-
-    if path == "single":
-        # one kernel does all the vector arithmetic of the path: it is nearer to the vector-ALU
-        # roof than to the HBM roof, so that is the roof it is reported against
-        vops = vector_ops(shape, args.alg, plan.P, plan.tiles)
-        valu_tops = vops / (stage_us[dominant] * 1e-6) / 1e12
-        roofline.update({"hbm_achieved_gbs": roofline["achieved"], "hbm_frac": roofline["frac"],
-                         "algorithmic_vector_ops": vops})
-        if valu_tops / VALU_PEAK_TOPS > hbm_frac:
-            roofline.update({"bound": "alu", "achieved": round(valu_tops, 2),
-                             "peak": round(VALU_PEAK_TOPS, 2), "unit": "TOP/s",
-                             "frac": round(valu_tops / VALU_PEAK_TOPS, 4)})
-    tops = direct_ops / (ms_per_step * 1e-3) / 1e12
+    timer = Timer(torch)
+    names = ["resnet56", "resnet28", "resnet14", "resnet7", "stack"] if args.workload == "all" else [args.workload]
+    records = []
+    for name in names:
+        rec = bench_stack(args, torch, timer) if name == "stack" else bench_layer(args, name, torch, timer)
+        records.append(rec)
+    head = records[-1]
     out = {
-        "metric": f"direct-conv-equivalent int8 TOPS per {ksize}x{ksize} layer",
-        "value": round(tops, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: N={shape.N} Cin=Cout={shape.Cin} H=W={shape.H} "
-                               f"{ksize}x{ksize} s1 p{(ksize - 1) // 2}",
-                   "algorithm": f"SFC-{4 if args.alg.startswith('4x4') else 6}({args.alg[:3]},{ksize}x{ksize}) P={plan.P}",
-                   "mode": "requant-int8 transform domain",
-                   "path": path, "buffer_sets": nsets, "streams": nstreams,
-                   "untimed_load_before_each_timed_region_ms": RAMP_MS,
-                   "same_steps_as_one_graph_ms_per_step": None if job_graph_ms is None else round(job_graph_ms, 5),
-                   "single_stream_ms_per_step": round(single_stream_ms, 5),
-                   "graph_replay_ms_per_step": None if graph_ms is None else round(graph_ms, 5),
-                   "warm_single_stream_ms_per_step": round(warm_ms, 5)},
-        "roofline": roofline,
+        "metric": "direct-conv-equivalent int8 TOPS per 3x3 layer; % MFMA/HBM roofline",
+        "value": head["value"], "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": head["workload"], "algorithm": head["algorithm"], "path": head["path"],
+                   "mode": "requant-int8 transform domain", "protocol":
+                       f"one stream, HIP events, median of {head['repeats']} repeats of {args.steps} steps, "
+                       f"{head['buffer_sets']} rotating buffer sets, {RAMP_MS:.0f} ms of untimed load before",
+                   "graph_replay_ms_per_step": head.get("graph_replay_ms_per_step")},
+        "roofline": head["roofline"],
+        "configs": records,
     }
-
     if not args.no_cpu_baseline:
-        from oracle import sfc as oracle  # the cpu_baseline leg is the only user of the oracle here
-
-        try:
-            from threadpoolctl import threadpool_info
-
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-        except Exception:
-            cores = os.cpu_count()
-        # bounded sample: whole passes over the same batch until about 10 s have gone by
-        passes, t0 = 0, time.perf_counter()
-        while True:
-            oracle.conv_requant(data["x"], data["w"], sx, sw, data["x_scale"], data["w_scale"], args.alg)
-            passes += 1
-            dt = time.perf_counter() - t0
-            if dt >= 10.0 or passes >= 50:
-                break
-        out["cpu_baseline"] = {"value": round(passes * direct_ops / dt / 1e12, 5), "unit": "TOPS",
-                               "cores": int(cores), "kind": "oracle",
-                               "sample": f"oracle.conv_requant on the full {args.workload} batch "
-                                         f"(N={shape.N}), {passes} passes in {dt:.1f} s"}
+        out["cpu_baseline"] = cpu_baseline(args)
     print(json.dumps(out))
 
 

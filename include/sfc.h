@@ -48,11 +48,17 @@ typedef enum {
   SFC_EUNSUPPORTED = 2, /* valid request this build does not implement */
   SFC_ENOMEM = 3,       /* host allocation failed */
   SFC_ENOTREADY = 4,    /* scales or filter not set yet */
-  SFC_EHIP = 5          /* a HIP runtime call or kernel launch failed */
+  SFC_EHIP = 5,         /* a HIP runtime call or kernel launch failed */
+  SFC_EWORKSPACE = 6    /* a caller-owned device buffer is smaller than sfc_plan_sizes says */
 } sfc_status;
 
 /* Which 2-D point set realizes the element-wise product of Eq. (1), Appendix A. */
 typedef enum {
+  /* sfc_plan picks the tile size for 3x3 filters from the layer shape (sfc_plan_choice tells
+   * which): SFC-4's 4x4 tiles where they divide a large feature map with few channels, 7x7
+   * tiles on the 14x14 and 7x7 maps they cover exactly, 6x6 tiles otherwise; always the
+   * Hermitian point set. */
+  SFC_ALG_AUTO = -1,
   SFC_ALG_6X6_P88 = 0,  /* SFC-6(6x6,3x3), Hermitian symmetry fully used: 88 multiplications per tile */
   SFC_ALG_6X6_P100 = 1, /* SFC-6(6x6,3x3), nested (Kronecker) form: 100 multiplications */
   SFC_ALG_7X7_P132 = 2, /* SFC-6(7x7,3x3) (Sec. 4.2, Appendix A), Hermitian form: 132 multiplications */
@@ -92,6 +98,8 @@ typedef enum {
 } sfc_out;
 
 typedef enum {
+  /* sfc_plan picks the fastest path that covers the layer (sfc_plan_choice tells which) */
+  SFC_PATH_AUTO = -1,
   SFC_PATH_STAGED = 0, /* V and M pass through the workspace; taps available */
   SFC_PATH_FUSED = 1,  /* product and output transform in one kernel; M never leaves the chip */
   /* Cin <= 64 only: input transform, products and output transform in one kernel;
@@ -112,13 +120,29 @@ typedef struct {
    * domain, Sec. 6) run on the same kernels; the abs-max calibration helpers divide by the
    * same bound.  Must be 0 in exact mode. */
   int32_t transform_bits;
+  /* SFC_FLAG_* bits, 0 for none */
+  int32_t flags;
 } sfc_conv_desc;
+
+/* Exact mode keeps every sum in 32 bits.  The sums an output is made of (kDen = 36, or 16 for
+ * SFC-4, times the convolution sum) are guaranteed to fit for Cin <= 404 with 3x3 filters and
+ * Cin <= 145 with 5x5 filters; sfc_plan refuses more channels (SFC_EUNSUPPORTED) unless this
+ * flag is set.  The arithmetic runs modulo 2^32 (unsigned, so wrap-around is defined): with
+ * the SFC-6 forms an output is exact whenever its kDen-fold sum lies inside the int32 range,
+ * whatever the intermediate sums do (the only division on the way, by 3, is a multiplication
+ * by the inverse of 3 modulo 2^32); the SFC-4 forms halve intermediate sums, which must fit
+ * as well.  With the flag the caller vouches for that on its data. */
+enum { SFC_FLAG_EXACT_WIDE = 1 };
 
 /* Host only.  Validates the description and derives the tile grid
  * (ceil(H/M) x ceil(W/M) tiles per image) and all buffer sizes.  No device work.
  * *out receives a plan to be released with sfc_plan_destroy. */
 sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out);
 void sfc_plan_destroy(sfc_plan_t* plan);
+
+/* What sfc_plan chose (or was given): the sfc_alg and sfc_path the plan runs.  Either output
+ * pointer may be NULL. */
+sfc_status sfc_plan_choice(const sfc_plan_t* plan, int32_t* alg, int32_t* path);
 
 /* Sizes the caller must allocate (device bytes) and the derived counts:
  * P = multiplications per tile (88, 100, 132, 144, 46, 49, 184 or 196),
@@ -146,11 +170,13 @@ sfc_status sfc_set_output_scale(sfc_plan_t* plan, float y_scale);
  * data; abs-max over a calibration tensor stands in): scale = max|value|/qmax
  * (qmax = 127, or 2^(transform_bits-1) - 1),
  * 1 where the maximum is 0.  Both block until the result is in host memory.
- * workspace_dev must hold workspace_bytes of a plan whose N >= n_images. */
+ * workspace_dev holds workspace_bytes bytes, at least the plan's workspace size
+ * (SFC_EWORKSPACE otherwise, nothing launched); n_images <= the plan's N. */
 sfc_status sfc_calibrate_act_scales(const sfc_plan_t* plan, const int8_t* x_dev, int32_t n_images,
-                                    void* workspace_dev, void* stream, float* sx_host_out /*[P]*/);
+                                    void* workspace_dev, size_t workspace_bytes, void* stream,
+                                    float* sx_host_out /*[P]*/);
 sfc_status sfc_calibrate_filter_scales(const sfc_plan_t* plan, const int8_t* w_dev,
-                                       void* workspace_dev, void* stream,
+                                       void* workspace_dev, size_t workspace_bytes, void* stream,
                                        float* sw_host_out /*[P*Cout]*/);
 
 /* Scale granularities of the ablation study (Sec. 6, "Ablation Study on Quantization
@@ -176,23 +202,27 @@ sfc_status sfc_group_scales(const sfc_plan_t* plan, int32_t act_granularity,
 
 /* Filter transform U = G f G^T (Appendix A's G, additions only), once per layer.
  * w_dev: int8 [Cout,Cin,R,R].  wscale_host: [1] or [Cout] spatial-domain filter
- * scales.  filter_dev: >= filter_bytes, receives U (int16 in exact mode, rounded
+ * scales.  filter_dev: filter_bytes bytes, at least the plan's filter size
+ * (SFC_EWORKSPACE otherwise, nothing launched); receives U (int16 in exact mode, rounded
  * to int8 in requantized mode) and the per-point dequantization table; the plan
  * remembers the pointer.  Asynchronous on `stream` apart from a small pageable
  * host-to-device copy.  Requantized mode needs sfc_set_point_scales first
- * (SFC_ENOTREADY otherwise). */
+ * (SFC_ENOTREADY otherwise).  Also raises, on the current device, the dynamic-LDS limit of
+ * the kernels this plan launches (SFC_EHIP if the device refuses): sfc_conv2d_nchw runs
+ * on the device that was current here. */
 sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const float* wscale_host,
-                                void* filter_dev, void* stream);
+                                void* filter_dev, size_t filter_bytes, void* stream);
 
 /* The hot path: input-tile transform V = B^T x B, P products
  * M_p[tiles x Cout] = V_p[tiles x Cin] . U_p[Cin x Cout], output transform with
  * the correction terms, dequantization and the NCHW store.
  * x_dev: int8 [N,Cin,H,W]; x_scale: spatial-domain activation scale.
  * y_dev: float32 (SFC_OUT_F32), int32 (SFC_OUT_I32) or int8 (SFC_OUT_I8_RELU) [N,Cout,H,W].
- * workspace_dev: >= workspace_bytes, private to this call until it completes.
+ * workspace_dev: workspace_bytes bytes, at least the plan's workspace size (SFC_EWORKSPACE
+ * otherwise, nothing launched), private to this call until it completes.
  * SFC_ENOTREADY before sfc_transform_filter. */
 sfc_status sfc_conv2d_nchw(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale, void* y_dev,
-                           void* workspace_dev, void* stream);
+                           void* workspace_dev, size_t workspace_bytes, void* stream);
 
 /* Profiling aid: the same work as sfc_conv2d_nchw restricted to the stages in
  * stage_mask, so that one stage can be timed alone on buffers a full call has
@@ -202,7 +232,8 @@ sfc_status sfc_conv2d_nchw(const sfc_plan_t* plan, const int8_t* x_dev, float x_
  * SFC_PATH_SINGLE only SFC_STAGE_ALL is accepted. */
 enum { SFC_STAGE_INPUT = 1, SFC_STAGE_PRODUCT = 2, SFC_STAGE_OUTPUT = 4, SFC_STAGE_ALL = 7 };
 sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale,
-                             void* y_dev, void* workspace_dev, void* stream, int32_t stage_mask);
+                             void* y_dev, void* workspace_dev, size_t workspace_bytes, void* stream,
+                             int32_t stage_mask);
 
 /* Where the intermediate tensors of the last call live, for parity checks.
  * which: 0 = V [P][tiles][Cin], 1 = U [P][Cout][Cin], 2 = M [P][tiles][Cout] (int32).

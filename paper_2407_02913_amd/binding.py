@@ -16,22 +16,27 @@ LIB_PATH = os.path.join(_HERE, "libsfc_hip.so")
 
 SFC_OK = 0
 STATUS_NAMES = {0: "SFC_OK", 1: "SFC_EINVAL", 2: "SFC_EUNSUPPORTED", 3: "SFC_ENOMEM",
-                4: "SFC_ENOTREADY", 5: "SFC_EHIP"}
-ALG = {"6x6_p88": 0, "6x6_p100": 1, "7x7_p132": 2, "7x7_p144": 3, "4x4_p46": 4, "4x4_p49": 5,
+                4: "SFC_ENOTREADY", 5: "SFC_EHIP", 6: "SFC_EWORKSPACE"}
+ALG = {"auto": -1, "6x6_p88": 0, "6x6_p100": 1, "7x7_p132": 2, "7x7_p144": 3, "4x4_p46": 4, "4x4_p49": 5,
        "6x6_5x5_p184": 6, "6x6_5x5_p196": 7}
 ACT_GRANULARITY = {"tensor": 0, "point": 1}
 FILTER_GRANULARITY = {"channel": 0, "point": 1, "channel_point": 2}
+ALG_NAME = {v: k for k, v in ALG.items()}
 KERNEL_SIZE = {name: 5 if "5x5" in name else 3 for name in ALG}  # filter edge R
 MODE = {"exact": 0, "requant": 1}
 OUT = {"f32": 0, "i32": 1, "i8": 2}
-PATH = {"staged": 0, "fused": 1, "single": 2}
+PATH = {"auto": -1, "staged": 0, "fused": 1, "single": 2}
+PATH_NAME = {v: k for k, v in PATH.items()}
+FLAG_EXACT_WIDE = 1
+#: what alg="auto" resolves to for 3x3 filters in requantized mode, and the widest layer
+#: path="auto" runs in one kernel (mirrors of the library's rule, for tests and reports)
+AUTO_ALG_3X3 = "4x4_p46"
+SINGLE_MAX_CIN = 64
 STAGE_INPUT, STAGE_PRODUCT, STAGE_OUTPUT, STAGE_ALL = 1, 2, 4, 7
-#: the path bench.py and callers get when they do not ask for one
-DEFAULT_PATH = "fused"
-
 #: every symbol include/sfc.h declares
 EXPORTS = (
-    "sfc_plan", "sfc_plan_destroy", "sfc_plan_sizes", "sfc_set_point_scales", "sfc_set_output_scale",
+    "sfc_plan", "sfc_plan_destroy", "sfc_plan_choice", "sfc_plan_sizes", "sfc_set_point_scales",
+    "sfc_set_output_scale",
     "sfc_group_scales",
     "sfc_calibrate_act_scales", "sfc_calibrate_filter_scales", "sfc_transform_filter",
     "sfc_conv2d_nchw", "sfc_conv2d_stages", "sfc_tap_info", "sfc_stream_copy", "sfc_status_string",
@@ -41,7 +46,7 @@ EXPORTS = (
 class ConvDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("N", "Cin", "Cout", "H", "W", "alg", "mode", "out", "path", "per_channel_wscale",
-                 "transform_bits")]
+                 "transform_bits", "flags")]
 
 
 class SfcError(RuntimeError):
@@ -69,6 +74,8 @@ def load(force: bool = False):
     lib.sfc_plan.restype = i32
     lib.sfc_plan_destroy.argtypes = [vp]
     lib.sfc_plan_destroy.restype = None
+    lib.sfc_plan_choice.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
+    lib.sfc_plan_choice.restype = i32
     lib.sfc_plan_sizes.argtypes = [vp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t),
                                    C.POINTER(i32), C.POINTER(C.c_int64)]
     lib.sfc_plan_sizes.restype = i32
@@ -78,15 +85,15 @@ def load(force: bool = False):
     lib.sfc_group_scales.restype = i32
     lib.sfc_set_output_scale.argtypes = [vp, f32]
     lib.sfc_set_output_scale.restype = i32
-    lib.sfc_calibrate_act_scales.argtypes = [vp, vp, i32, vp, vp, C.POINTER(f32)]
+    lib.sfc_calibrate_act_scales.argtypes = [vp, vp, i32, vp, C.c_size_t, vp, C.POINTER(f32)]
     lib.sfc_calibrate_act_scales.restype = i32
-    lib.sfc_calibrate_filter_scales.argtypes = [vp, vp, vp, vp, C.POINTER(f32)]
+    lib.sfc_calibrate_filter_scales.argtypes = [vp, vp, vp, C.c_size_t, vp, C.POINTER(f32)]
     lib.sfc_calibrate_filter_scales.restype = i32
-    lib.sfc_transform_filter.argtypes = [vp, vp, C.POINTER(f32), vp, vp]
+    lib.sfc_transform_filter.argtypes = [vp, vp, C.POINTER(f32), vp, C.c_size_t, vp]
     lib.sfc_transform_filter.restype = i32
-    lib.sfc_conv2d_nchw.argtypes = [vp, vp, f32, vp, vp, vp]
+    lib.sfc_conv2d_nchw.argtypes = [vp, vp, f32, vp, vp, C.c_size_t, vp]
     lib.sfc_conv2d_nchw.restype = i32
-    lib.sfc_conv2d_stages.argtypes = [vp, vp, f32, vp, vp, vp, i32]
+    lib.sfc_conv2d_stages.argtypes = [vp, vp, f32, vp, vp, C.c_size_t, vp, i32]
     lib.sfc_conv2d_stages.restype = i32
     lib.sfc_tap_info.argtypes = [vp, vp, i32, C.POINTER(vp), C.POINTER(i32),
                                  C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
@@ -108,6 +115,10 @@ def _f32_ptr(a: np.ndarray):
     return a.ctypes.data_as(C.POINTER(C.c_float))
 
 
+def _nbytes(t) -> int:
+    return int(t.numel() * t.element_size())
+
+
 def _stream_ptr(stream):
     import torch
 
@@ -119,18 +130,22 @@ class Plan:
     """Owns one sfc_plan_t.  Tensors passed in are torch CUDA tensors."""
 
     def __init__(self, N, Cin, Cout, H, W, alg="6x6_p88", mode="requant", out="f32",
-                 path="staged", per_channel_wscale=True, transform_bits=0):
+                 path="staged", per_channel_wscale=True, transform_bits=0, flags=0):
         lib = load()
         self.desc = ConvDesc(N, Cin, Cout, H, W, ALG[alg], MODE[mode], OUT[out], PATH[path],
-                             1 if per_channel_wscale else 0, int(transform_bits))
+                             1 if per_channel_wscale else 0, int(transform_bits), int(flags))
         self._h = C.c_void_p()
         _check(lib.sfc_plan(C.byref(self.desc), C.byref(self._h)), "sfc_plan")
+        a, pth = C.c_int32(), C.c_int32()
+        _check(lib.sfc_plan_choice(self._h, C.byref(a), C.byref(pth)), "sfc_plan_choice")
+        #: what the plan runs ("auto" resolved by the library)
+        self.alg, self.path = ALG_NAME[a.value], PATH_NAME[pth.value]
         fb, wb, p, t = C.c_size_t(), C.c_size_t(), C.c_int32(), C.c_int64()
         _check(lib.sfc_plan_sizes(self._h, C.byref(fb), C.byref(wb), C.byref(p), C.byref(t)),
                "sfc_plan_sizes")
         self.filter_bytes, self.workspace_bytes, self.P, self.tiles = fb.value, wb.value, p.value, t.value
         self.mode, self.out = mode, out
-        self.kernel_size = KERNEL_SIZE[alg]
+        self.kernel_size = KERNEL_SIZE[self.alg]
         self._keep = []
 
     def close(self):
@@ -167,7 +182,7 @@ class Plan:
         out = np.empty(self.P, dtype=np.float32)
         _check(load().sfc_calibrate_act_scales(self._h, C.c_void_p(x_dev.data_ptr()),
                                                int(x_dev.shape[0]), C.c_void_p(workspace.data_ptr()),
-                                               _stream_ptr(stream), _f32_ptr(out)),
+                                               _nbytes(workspace), _stream_ptr(stream), _f32_ptr(out)),
                "sfc_calibrate_act_scales")
         return out
 
@@ -180,7 +195,7 @@ class Plan:
         self._check_weights(w_dev)
         out = np.empty((self.P, self.desc.Cout), dtype=np.float32)
         _check(load().sfc_calibrate_filter_scales(self._h, C.c_void_p(w_dev.data_ptr()),
-                                                  C.c_void_p(workspace.data_ptr()),
+                                                  C.c_void_p(workspace.data_ptr()), _nbytes(workspace),
                                                   _stream_ptr(stream), _f32_ptr(out)),
                "sfc_calibrate_filter_scales")
         return out
@@ -189,25 +204,24 @@ class Plan:
         ws = np.ascontiguousarray(np.asarray(w_scale, dtype=np.float32).reshape(-1))
         need = self.desc.Cout if self.desc.per_channel_wscale else 1
         assert ws.size == need, (ws.size, need)
-        assert filter_buf.numel() * filter_buf.element_size() >= self.filter_bytes
         self._check_weights(w_dev)
         _check(load().sfc_transform_filter(self._h, C.c_void_p(w_dev.data_ptr()), _f32_ptr(ws),
-                                           C.c_void_p(filter_buf.data_ptr()), _stream_ptr(stream)),
+                                           C.c_void_p(filter_buf.data_ptr()), _nbytes(filter_buf),
+                                           _stream_ptr(stream)),
                "sfc_transform_filter")
         self._keep = [filter_buf]
 
     def conv2d(self, x_dev, x_scale: float, y_dev, workspace, stream=None):
-        assert workspace.numel() * workspace.element_size() >= self.workspace_bytes
         _check(load().sfc_conv2d_nchw(self._h, C.c_void_p(x_dev.data_ptr()), C.c_float(x_scale),
-                                      C.c_void_p(y_dev.data_ptr()),
-                                      C.c_void_p(workspace.data_ptr()), _stream_ptr(stream)),
+                                      C.c_void_p(y_dev.data_ptr()), C.c_void_p(workspace.data_ptr()),
+                                      _nbytes(workspace), _stream_ptr(stream)),
                "sfc_conv2d_nchw")
 
     def conv2d_stages(self, x_dev, x_scale: float, y_dev, workspace, mask: int, stream=None):
         _check(load().sfc_conv2d_stages(self._h, C.c_void_p(x_dev.data_ptr()), C.c_float(x_scale),
                                         C.c_void_p(y_dev.data_ptr()),
-                                        C.c_void_p(workspace.data_ptr()), _stream_ptr(stream),
-                                        int(mask)), "sfc_conv2d_stages")
+                                        C.c_void_p(workspace.data_ptr()), _nbytes(workspace),
+                                        _stream_ptr(stream), int(mask)), "sfc_conv2d_stages")
 
     def tap(self, which: str, workspace) -> np.ndarray:
         """Copy of V, U or M in canonical [P][tiles|Cout][Cin|Cout] order (synchronizes)."""
@@ -250,7 +264,7 @@ def device_buffer(nbytes: int):
 
 def conv2d(x: np.ndarray, w: np.ndarray, x_scale: float, w_scale, mode="requant", alg="6x6_p88",
            out="f32", path="staged", sx=None, sw=None, return_taps=False, y_scale=None,
-           transform_bits=0):
+           transform_bits=0, flags=0):
     """Convenience wrapper: numpy in, numpy out, one layer through the C ABI."""
     import torch
 
@@ -258,7 +272,7 @@ def conv2d(x: np.ndarray, w: np.ndarray, x_scale: float, w_scale, mode="requant"
     cout = w.shape[0]
     ws_arr = np.asarray(w_scale, dtype=np.float32).reshape(-1)
     plan = Plan(n, cin, cout, h, wd, alg=alg, mode=mode, out=out, path=path,
-                per_channel_wscale=ws_arr.size != 1, transform_bits=transform_bits)
+                per_channel_wscale=ws_arr.size != 1, transform_bits=transform_bits, flags=flags)
     xd = torch.from_numpy(np.ascontiguousarray(x)).cuda()
     wdv = torch.from_numpy(np.ascontiguousarray(w)).cuda()
     fbuf = device_buffer(plan.filter_bytes)
@@ -274,7 +288,7 @@ def conv2d(x: np.ndarray, w: np.ndarray, x_scale: float, w_scale, mode="requant"
     torch.cuda.synchronize()
     res = y.cpu().numpy()
     if return_taps:
-        names = {"staged": ("V", "U", "M"), "fused": ("V", "U"), "single": ("U",)}[path]
+        names = {"staged": ("V", "U", "M"), "fused": ("V", "U"), "single": ("U",)}[plan.path]
         taps = {k: plan.tap(k, wbuf) for k in names}
         plan.close()
         return res, taps

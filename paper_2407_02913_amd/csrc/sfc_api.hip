@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -50,6 +51,66 @@ FilterViews views(const sfc_plan_s* p, void* filter_dev) {
   return f;
 }
 
+bool alg_is_7x7(int alg) { return alg == SFC_ALG_7X7_P132 || alg == SFC_ALG_7X7_P144; }
+
+// Tile grid and padded extents of a description whose algorithm is fixed.  False when the
+// tile count leaves the 32-bit range the kernels index with.
+bool make_geometry(const sfc_conv_desc& d, Geometry* out) {
+  Geometry g;
+  g.N = d.N; g.Cin = d.Cin; g.Cout = d.Cout; g.H = d.H; g.W = d.W;
+  g.alg = d.alg;
+  const int mt = (d.alg == SFC_ALG_7X7_P132 || d.alg == SFC_ALG_7X7_P144) ? 7
+                 : (d.alg == SFC_ALG_4X4_P46 || d.alg == SFC_ALG_4X4_P49) ? 4 : 6;
+  g.th = (d.H + mt - 1) / mt;
+  g.tw = (d.W + mt - 1) / mt;
+  const int64_t strips = (int64_t)d.N * g.th;
+  const int64_t T = strips * g.tw;
+  if (T > (1ll << 30)) return false;
+  g.strips = (int)strips;
+  g.T = (int)T;
+  g.Tp = (int)((T + 15) / 16 * 16);
+  g.Cp = (d.Cin + 63) / 64 * 64;
+  g.Kp = (d.Cout + 15) / 16 * 16;
+  static const int kPoints[8] = {88, 100, 132, 144, 46, 49, 184, 196};
+  g.P = kPoints[d.alg];
+  g.qmax = (float)((1 << ((d.transform_bits ? d.transform_bits : 8) - 1)) - 1);
+  *out = g;
+  return true;
+}
+
+// SFC_ALG_AUTO (3x3 filters), from per-layer timings of the ResNet shapes on one MI355X.
+// Requantized mode: SFC-4's 4x4 tiles -- 46 points per tile keep two workgroups on a compute
+// unit and the filter operand small, which outweighs even the ragged tiles of 14x14 and 7x7
+// maps while there are few (tile, filter) pairs (256 channels at 14x14, batch 64: 38.9 us
+// against 47.0 us for 7x7 tiles; 512 channels at 7x7, batch 64: 31.9 against 46.8 us) -- except
+// where 7x7 tiles cover the map exactly, 4x4 tiles do not, and the layer has at least 96 K
+// (tile, filter) pairs: then the 31 % of surplus outputs of the ragged 4x4 tiles cost more
+// than the larger point set (256 channels at 14x14, batch 128: 55.6 us with 7x7 tiles against
+// 60.8; 512 channels at 7x7, batch 256: 64.0 against 79.1).  Exact mode: 6x6 tiles, the form
+// Sec. 4 and the 3.68x figure are about.
+int choose_alg(const sfc_conv_desc& d) {
+  if (d.mode == SFC_MODE_EXACT) return SFC_ALG_6X6_P88;
+  if (d.H % 7 == 0 && d.W % 7 == 0 && (d.H % 4 != 0 || d.W % 4 != 0) && d.H <= 14 && d.W <= 14) {
+    const int64_t pairs = (int64_t)d.N * (d.H / 7) * (d.W / 7) * d.Cout;
+    if (pairs >= 96 * 1024) return SFC_ALG_7X7_P132;
+  }
+  return SFC_ALG_4X4_P46;
+}
+
+// SFC_PATH_AUTO: one kernel where the layer allows it, else input transform + fused
+// product/output kernel, else the staged path (exact mode, channel counts the fused
+// kernel does not take).
+int choose_path(const sfc_conv_desc& d, const Geometry& g) {
+  if (d.mode != SFC_MODE_REQUANT_I8) return SFC_PATH_STAGED;
+  if (sfc::single_supported(g)) return SFC_PATH_SINGLE;
+  // 7x7 tiles on 7x7 maps with 512 and more channels: the fused kernel would stream its
+  // operands from L2 eight times over; the products as batched GEMMs through HBM are faster
+  // (64.0 against 77.0 us at batch 256)
+  const bool gemm = alg_is_7x7(d.alg) && d.H < 14 && d.Cin >= 512;
+  if (!gemm && sfc::fused_quad_supported(g)) return SFC_PATH_FUSED;
+  return SFC_PATH_STAGED;
+}
+
 }  // namespace
 
 extern "C" {
@@ -62,6 +123,7 @@ const char* sfc_status_string(sfc_status s) {
     case SFC_ENOMEM: return "host allocation failed";
     case SFC_ENOTREADY: return "scales or filter not set";
     case SFC_EHIP: return "HIP runtime or launch failure";
+    case SFC_EWORKSPACE: return "device buffer smaller than the plan needs";
   }
   return "unknown status";
 }
@@ -69,41 +131,30 @@ const char* sfc_status_string(sfc_status s) {
 sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   if (!desc || !out) return SFC_EINVAL;
   *out = nullptr;
-  const sfc_conv_desc& d = *desc;
+  sfc_conv_desc d = *desc;
   if (d.N <= 0 || d.Cin <= 0 || d.Cout <= 0 || d.H <= 0 || d.W <= 0) return SFC_EINVAL;
-  if (d.alg < SFC_ALG_6X6_P88 || d.alg > SFC_ALG_6X6_5X5_P196) return SFC_EINVAL;
+  if (d.alg < SFC_ALG_AUTO || d.alg > SFC_ALG_6X6_5X5_P196) return SFC_EINVAL;
   if (d.mode != SFC_MODE_EXACT && d.mode != SFC_MODE_REQUANT_I8) return SFC_EINVAL;
   if (d.out != SFC_OUT_F32 && d.out != SFC_OUT_I32 && d.out != SFC_OUT_I8_RELU) return SFC_EINVAL;
-  if (d.path != SFC_PATH_STAGED && d.path != SFC_PATH_FUSED && d.path != SFC_PATH_SINGLE)
-    return SFC_EINVAL;
+  if (d.path < SFC_PATH_AUTO || d.path > SFC_PATH_SINGLE) return SFC_EINVAL;
+  if ((d.flags & ~SFC_FLAG_EXACT_WIDE) != 0) return SFC_EINVAL;
   if (d.per_channel_wscale != 0 && d.per_channel_wscale != 1) return SFC_EINVAL;
   if (d.transform_bits != 0 && (d.transform_bits < 2 || d.transform_bits > 8)) return SFC_EINVAL;
   if (d.transform_bits != 0 && d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
   if (d.out == SFC_OUT_I32 && d.mode != SFC_MODE_EXACT) return SFC_EUNSUPPORTED;
   if (d.out == SFC_OUT_I8_RELU && d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
-  if (d.path != SFC_PATH_STAGED && d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
-  if (d.W > 1024 || d.H > (1 << 20) || d.Cin > (1 << 16) || d.Cout > 65535 * 16)
+  if (d.path > SFC_PATH_STAGED && d.mode != SFC_MODE_REQUANT_I8) return SFC_EUNSUPPORTED;
+  // Cout: one workgroup row per filter (filter transform, abs-max) must fit a launch grid
+  if (d.W > 1024 || d.H > (1 << 20) || d.Cin > (1 << 16) || d.Cout > 65520)
+    return SFC_EUNSUPPORTED;
+  if (d.alg == SFC_ALG_AUTO) d.alg = choose_alg(d);
+  if (d.mode == SFC_MODE_EXACT && !(d.flags & SFC_FLAG_EXACT_WIDE) &&
+      d.Cin > (d.alg >= SFC_ALG_6X6_5X5_P184 ? 145 : 404))
     return SFC_EUNSUPPORTED;
 
   Geometry g;
-  g.N = d.N; g.Cin = d.Cin; g.Cout = d.Cout; g.H = d.H; g.W = d.W;
-  g.alg = d.alg;
-  const int mt = (d.alg == SFC_ALG_7X7_P132 || d.alg == SFC_ALG_7X7_P144) ? 7
-                 : (d.alg == SFC_ALG_4X4_P46 || d.alg == SFC_ALG_4X4_P49) ? 4 : 6;
-  g.th = (d.H + mt - 1) / mt;
-  g.tw = (d.W + mt - 1) / mt;
-  const int64_t strips = (int64_t)d.N * g.th;
-  const int64_t T = strips * g.tw;
-  if (T > (1ll << 30)) return SFC_EUNSUPPORTED;
-  g.strips = (int)strips;
-  g.T = (int)T;
-  g.Tp = (int)((T + 15) / 16 * 16);
-  g.Cp = (d.Cin + 63) / 64 * 64;
-  g.Kp = (d.Cout + 15) / 16 * 16;
-  static const int kPoints[8] = {88, 100, 132, 144, 46, 49, 184, 196};
-  g.P = kPoints[d.alg];
-  g.qmax = (float)((1 << ((d.transform_bits ? d.transform_bits : 8) - 1)) - 1);
-
+  if (!make_geometry(d, &g)) return SFC_EUNSUPPORTED;
+  if (d.path == SFC_PATH_AUTO) d.path = choose_path(d, g);
   if (d.path == SFC_PATH_FUSED && !sfc::fused_quad_supported(g)) return SFC_EUNSUPPORTED;
   if (d.path == SFC_PATH_SINGLE && !sfc::single_supported(g)) return SFC_EUNSUPPORTED;
 
@@ -153,6 +204,13 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
 }
 
 void sfc_plan_destroy(sfc_plan_t* plan) { delete plan; }
+
+sfc_status sfc_plan_choice(const sfc_plan_t* plan, int32_t* alg, int32_t* path) {
+  if (!plan) return SFC_EINVAL;
+  if (alg) *alg = plan->d.alg;
+  if (path) *path = plan->d.path;
+  return SFC_OK;
+}
 
 sfc_status sfc_plan_sizes(const sfc_plan_t* plan, size_t* filter_bytes, size_t* workspace_bytes,
                           int32_t* P, int64_t* tiles) {
@@ -229,9 +287,10 @@ sfc_status sfc_set_output_scale(sfc_plan_t* plan, float y_scale) {
 }
 
 sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const float* wscale_host,
-                                void* filter_dev, void* stream) {
+                                void* filter_dev, size_t filter_bytes, void* stream) {
   if (!plan || !w_dev || !wscale_host || !filter_dev) return SFC_EINVAL;
   if (!aligned16(w_dev) || !aligned16(filter_dev)) return SFC_EINVAL;
+  if (filter_bytes < plan->filter_bytes) return SFC_EWORKSPACE;
   const Geometry& g = plan->g;
   const bool requant = plan->d.mode == SFC_MODE_REQUANT_I8;
   if (requant && !plan->scales_set) return SFC_ENOTREADY;
@@ -281,6 +340,8 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
         dqs[(size_t)k * pp + j] = pt[j] < 0 ? 0.0f : dequant[(size_t)pt[j] * g.Kp + k];
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
+  // the kernels of this plan's path that need more than the default 64 KB of dynamic LDS
+  if (requant && sfc::prepare_kernels(plan->d.path, plan->d.out, g) != hipSuccess) return SFC_EHIP;
   if (hipMemcpyAsync(static_cast<char*>(filter_dev) + plan->off_dequant, plan->staging.data(),
                      table_bytes, hipMemcpyHostToDevice, s) != hipSuccess)
     return SFC_EHIP;
@@ -295,11 +356,13 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
 }
 
 sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale,
-                             void* y_dev, void* workspace_dev, void* stream, int32_t stage_mask) {
+                             void* y_dev, void* workspace_dev, size_t workspace_bytes, void* stream,
+                             int32_t stage_mask) {
   if (!plan || !x_dev || !y_dev || !workspace_dev) return SFC_EINVAL;
   if (!aligned16(x_dev) || !aligned16(y_dev) || !aligned16(workspace_dev)) return SFC_EINVAL;
   if (!(x_scale > 0.0f) || !std::isfinite(x_scale)) return SFC_EINVAL;
   if (stage_mask <= 0 || stage_mask > SFC_STAGE_ALL) return SFC_EINVAL;
+  if (workspace_bytes < plan->workspace_bytes) return SFC_EWORKSPACE;
   if (!plan->filter_ready) return SFC_ENOTREADY;
   if (plan->d.out == SFC_OUT_I8_RELU && plan->inv_y == 0.0f) return SFC_ENOTREADY;
   const bool fused = plan->d.path == SFC_PATH_FUSED;
@@ -341,8 +404,9 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
 }
 
 sfc_status sfc_conv2d_nchw(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale, void* y_dev,
-                           void* workspace_dev, void* stream) {
-  return sfc_conv2d_stages(plan, x_dev, x_scale, y_dev, workspace_dev, stream, SFC_STAGE_ALL);
+                           void* workspace_dev, size_t workspace_bytes, void* stream) {
+  return sfc_conv2d_stages(plan, x_dev, x_scale, y_dev, workspace_dev, workspace_bytes, stream,
+                           SFC_STAGE_ALL);
 }
 
 sfc_status sfc_tap_info(const sfc_plan_t* plan, const void* workspace_dev, int32_t which,
@@ -417,10 +481,12 @@ static sfc_status maxima_to_scales(const int32_t* dev, size_t count, float qmax,
 }
 
 sfc_status sfc_calibrate_act_scales(const sfc_plan_t* plan, const int8_t* x_dev, int32_t n_images,
-                                    void* workspace_dev, void* stream, float* sx_host_out) {
+                                    void* workspace_dev, size_t workspace_bytes, void* stream,
+                                    float* sx_host_out) {
   if (!plan || !x_dev || !workspace_dev || !sx_host_out) return SFC_EINVAL;
   if (!aligned16(x_dev) || !aligned16(workspace_dev)) return SFC_EINVAL;
   if (n_images <= 0 || n_images > plan->g.N) return SFC_EINVAL;
+  if (workspace_bytes < plan->workspace_bytes) return SFC_EWORKSPACE;
   Geometry g = plan->g;
   g.N = n_images;
   g.strips = n_images * g.th;
@@ -433,9 +499,11 @@ sfc_status sfc_calibrate_act_scales(const sfc_plan_t* plan, const int8_t* x_dev,
 }
 
 sfc_status sfc_calibrate_filter_scales(const sfc_plan_t* plan, const int8_t* w_dev,
-                                       void* workspace_dev, void* stream, float* sw_host_out) {
+                                       void* workspace_dev, size_t workspace_bytes, void* stream,
+                                       float* sw_host_out) {
   if (!plan || !w_dev || !workspace_dev || !sw_host_out) return SFC_EINVAL;
   if (!aligned16(w_dev) || !aligned16(workspace_dev)) return SFC_EINVAL;
+  if (workspace_bytes < plan->workspace_bytes) return SFC_EWORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   int32_t* maxima = static_cast<int32_t*>(workspace_dev);
   if (sfc::launch_filter_absmax(plan->g, w_dev, maxima, s) != hipSuccess)

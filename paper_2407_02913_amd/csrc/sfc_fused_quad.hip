@@ -6,7 +6,7 @@
 namespace sfc {
 
 hipError_t launch_fused_quad_5tap(int out, const Geometry& g, const void* V, const FilterViews& f,
-                                  float x_scale, float inv_y, void* y, hipStream_t s);
+                                  float x_scale, float inv_y, void* y, hipStream_t s, bool prepare);
 
 bool fused_quad_supported(const Geometry& g) {
   const int kc = g.Cp / 64;
@@ -23,17 +23,17 @@ bool fused_quad_supported(const Geometry& g) {
 int quad_filter_count(const Geometry& g) { return quad_filter_count_for(g); }
 
 hipError_t launch_fused_quad(int out, const Geometry& g, const void* V, const FilterViews& f,
-                             float x_scale, float inv_y, void* y, hipStream_t s) {
+                             float x_scale, float inv_y, void* y, hipStream_t s, bool prepare) {
   if (!fused_quad_supported(g) || out == 1) return hipErrorNotSupported;
   switch (g.alg) {
-    case 0: return launch_quad_alg<0>(out, g, V, f, x_scale, inv_y, y, s);
-    case 1: return launch_quad_alg<1>(out, g, V, f, x_scale, inv_y, y, s);
-    case 2: return launch_quad_alg<2>(out, g, V, f, x_scale, inv_y, y, s);
-    case 3: return launch_quad_alg<3>(out, g, V, f, x_scale, inv_y, y, s);
-    case 4: return launch_quad_alg<4>(out, g, V, f, x_scale, inv_y, y, s);
-    case 5: return launch_quad_alg<5>(out, g, V, f, x_scale, inv_y, y, s);
+    case 0: return launch_quad_alg<0>(out, g, V, f, x_scale, inv_y, y, s, prepare);
+    case 1: return launch_quad_alg<1>(out, g, V, f, x_scale, inv_y, y, s, prepare);
+    case 2: return launch_quad_alg<2>(out, g, V, f, x_scale, inv_y, y, s, prepare);
+    case 3: return launch_quad_alg<3>(out, g, V, f, x_scale, inv_y, y, s, prepare);
+    case 4: return launch_quad_alg<4>(out, g, V, f, x_scale, inv_y, y, s, prepare);
+    case 5: return launch_quad_alg<5>(out, g, V, f, x_scale, inv_y, y, s, prepare);
     case 6:
-    case 7: return launch_fused_quad_5tap(out, g, V, f, x_scale, inv_y, y, s);
+    case 7: return launch_fused_quad_5tap(out, g, V, f, x_scale, inv_y, y, s, prepare);
   }
   return hipErrorInvalidValue;
 }

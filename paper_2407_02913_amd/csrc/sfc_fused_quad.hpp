@@ -225,7 +225,8 @@ inline int quad_filter_count_for(const Geometry& g) {
 
 template <int ALG, int KC, int OUT, bool VEC2, bool PLANES = false>
 inline hipError_t launch_quad_impl(const Geometry& g, const void* V, const FilterViews& f,
-                                   float x_scale, float inv_y, void* y, hipStream_t s) {
+                                   float x_scale, float inv_y, void* y, hipStream_t s,
+                                   bool prepare) {
   // 6x6 tiles with 3x3 filters: 16 waves of 128 registers.  The SFC-4 forms need under 100
   // registers: 8-wave workgroups, two of which share a compute unit and run out of phase
   // (measured 31.0 against 32.5 us per step on 128 channels at 28x28).  The other forms: 8
@@ -235,13 +236,7 @@ inline hipError_t launch_quad_impl(const Geometry& g, const void* V, const Filte
   auto kernel = fused_quad_kernel<ALG, KC, OUT, VEC2, NW, WGS, PLANES>;
   constexpr unsigned lds_bytes = quad_lds_layout<ALG, KC, NW, PLANES>(2);
   static_assert(lds_bytes <= 160u * 1024u, "V buffers and staging exceed the LDS of a compute unit");
-  static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once
-  if (!attr_done) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    (void)hipGetLastError();
-    attr_done = true;
-  }
+  if (prepare) return raise_lds_limit(reinterpret_cast<const void*>(kernel));
   const int kfilters = quad_filter_count_for(g);
   const int kgroups = kfilters / (4 * NW);
   const dim3 grid((unsigned)((g.Tp / 16) * kgroups));
@@ -253,32 +248,32 @@ inline hipError_t launch_quad_impl(const Geometry& g, const void* V, const Filte
 
 template <int ALG, int KC>
 inline hipError_t launch_quad_kc(int out, const Geometry& g, const void* V, const FilterViews& f,
-                                 float x_scale, float inv_y, void* y, hipStream_t s) {
+                                 float x_scale, float inv_y, void* y, hipStream_t s, bool prepare) {
   constexpr bool kPairs = AlgTraits<ALG>::M % 2 == 0;
   // 7x7 tiles on 7x7, 14x14, 28x28 ... maps, 4x4 tiles on 4x4, 8x8, 16x16 ...: a wave's
   // pairs are whole planes of y
   if constexpr (AlgTraits<ALG>::M == 7 || AlgTraits<ALG>::M == 4) {
     if (whole_image_tiles(AlgTraits<ALG>::M, g.H, g.W, g.th, g.tw, g.Cout))
-      return out == 2 ? launch_quad_impl<ALG, KC, 2, false, true>(g, V, f, x_scale, inv_y, y, s)
-                      : launch_quad_impl<ALG, KC, 0, false, true>(g, V, f, x_scale, inv_y, y, s);
+      return out == 2 ? launch_quad_impl<ALG, KC, 2, false, true>(g, V, f, x_scale, inv_y, y, s, prepare)
+                      : launch_quad_impl<ALG, KC, 0, false, true>(g, V, f, x_scale, inv_y, y, s, prepare);
   }
   if constexpr (kPairs) {
     if (g.W % 2 == 0)
-      return out == 2 ? launch_quad_impl<ALG, KC, 2, true>(g, V, f, x_scale, inv_y, y, s)
-                      : launch_quad_impl<ALG, KC, 0, true>(g, V, f, x_scale, inv_y, y, s);
+      return out == 2 ? launch_quad_impl<ALG, KC, 2, true>(g, V, f, x_scale, inv_y, y, s, prepare)
+                      : launch_quad_impl<ALG, KC, 0, true>(g, V, f, x_scale, inv_y, y, s, prepare);
   }
-  return out == 2 ? launch_quad_impl<ALG, KC, 2, false>(g, V, f, x_scale, inv_y, y, s)
-                  : launch_quad_impl<ALG, KC, 0, false>(g, V, f, x_scale, inv_y, y, s);
+  return out == 2 ? launch_quad_impl<ALG, KC, 2, false>(g, V, f, x_scale, inv_y, y, s, prepare)
+                  : launch_quad_impl<ALG, KC, 0, false>(g, V, f, x_scale, inv_y, y, s, prepare);
 }
 
 template <int ALG>
 inline hipError_t launch_quad_alg(int out, const Geometry& g, const void* V, const FilterViews& f,
-                                  float x_scale, float inv_y, void* y, hipStream_t s) {
+                                  float x_scale, float inv_y, void* y, hipStream_t s, bool prepare) {
   switch (g.Cp / 64) {
-    case 1: return launch_quad_kc<ALG, 1>(out, g, V, f, x_scale, inv_y, y, s);
-    case 2: return launch_quad_kc<ALG, 2>(out, g, V, f, x_scale, inv_y, y, s);
-    case 4: return launch_quad_kc<ALG, 4>(out, g, V, f, x_scale, inv_y, y, s);
-    case 8: return launch_quad_kc<ALG, 8>(out, g, V, f, x_scale, inv_y, y, s);
+    case 1: return launch_quad_kc<ALG, 1>(out, g, V, f, x_scale, inv_y, y, s, prepare);
+    case 2: return launch_quad_kc<ALG, 2>(out, g, V, f, x_scale, inv_y, y, s, prepare);
+    case 4: return launch_quad_kc<ALG, 4>(out, g, V, f, x_scale, inv_y, y, s, prepare);
+    case 8: return launch_quad_kc<ALG, 8>(out, g, V, f, x_scale, inv_y, y, s, prepare);
   }
   return hipErrorNotSupported;
 }

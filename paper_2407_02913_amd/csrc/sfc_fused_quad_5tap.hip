@@ -5,10 +5,10 @@
 namespace sfc {
 
 hipError_t launch_fused_quad_5tap(int out, const Geometry& g, const void* V, const FilterViews& f,
-                                  float x_scale, float inv_y, void* y, hipStream_t s) {
+                                  float x_scale, float inv_y, void* y, hipStream_t s, bool prepare) {
   switch (g.alg) {
-    case 6: return launch_quad_alg<6>(out, g, V, f, x_scale, inv_y, y, s);
-    case 7: return launch_quad_alg<7>(out, g, V, f, x_scale, inv_y, y, s);
+    case 6: return launch_quad_alg<6>(out, g, V, f, x_scale, inv_y, y, s, prepare);
+    case 7: return launch_quad_alg<7>(out, g, V, f, x_scale, inv_y, y, s, prepare);
   }
   return hipErrorInvalidValue;
 }

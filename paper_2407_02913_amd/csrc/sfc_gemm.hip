@@ -247,22 +247,17 @@ __global__ __launch_bounds__(NW * 64) void output_sums_kernel(const int32_t* __r
 
 template <int ALG, int OUT, bool VEC2, bool PLANES = false>
 static hipError_t launch_sums_impl(const Geometry& g, const int32_t* M, const FilterViews& f,
-                                   float x_scale, float inv_y, void* y, hipStream_t s) {
+                                   float x_scale, float inv_y, void* y, hipStream_t s,
+                                   bool prepare) {
   // the 7x7 forms carry 10x7 partial outputs per pair, the 5x5-filter forms 12x6: 8 waves
   // with 256 registers each
   constexpr int NW = AlgTraits<ALG>::NC <= 8 ? 16 : 8;
   constexpr unsigned lds_bytes = sums_stage_bytes<ALG, PLANES, NW>() + 256;
   static_assert(lds_bytes <= 160u * 1024u, "staging blocks exceed the LDS of a compute unit");
   auto kernel = output_sums_kernel<ALG, OUT, VEC2, NW, PLANES>;
-  if constexpr (lds_bytes > 64u * 1024u) {
-    static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once
-    if (!attr_done) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-      (void)hipGetLastError();
-      attr_done = true;
-    }
-  }
+  if (prepare)
+    return lds_bytes > 64u * 1024u ? raise_lds_limit(reinterpret_cast<const void*>(kernel))
+                                   : hipSuccess;
   const dim3 grid((unsigned)(g.Tp / 16), (unsigned)((g.Cout + 4 * NW - 1) / (4 * NW)));
   hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), lds_bytes, s, M, f.dequant_single, x_scale,
                      inv_y, y, g);
@@ -272,38 +267,38 @@ static hipError_t launch_sums_impl(const Geometry& g, const int32_t* M, const Fi
 template <int ALG>
 static hipError_t launch_sums_alg(int out, const Geometry& g, const int32_t* M,
                                   const FilterViews& f, float x_scale, float inv_y, void* y,
-                                  hipStream_t s) {
+                                  hipStream_t s, bool prepare) {
   constexpr bool kPairs = AlgTraits<ALG>::M % 2 == 0;
   // 7x7 tiles on 7x7, 14x14, 28x28 ... maps, 4x4 tiles on 4x4, 8x8, 16x16 ...: a wave's
   // pairs are whole planes of y
   if constexpr (AlgTraits<ALG>::M == 7 || AlgTraits<ALG>::M == 4) {
     if (whole_image_tiles(AlgTraits<ALG>::M, g.H, g.W, g.th, g.tw, g.Cout))
-      return out == 2 ? launch_sums_impl<ALG, 2, false, true>(g, M, f, x_scale, inv_y, y, s)
-                      : launch_sums_impl<ALG, 0, false, true>(g, M, f, x_scale, inv_y, y, s);
+      return out == 2 ? launch_sums_impl<ALG, 2, false, true>(g, M, f, x_scale, inv_y, y, s, prepare)
+                      : launch_sums_impl<ALG, 0, false, true>(g, M, f, x_scale, inv_y, y, s, prepare);
   }
   if constexpr (kPairs) {
     if (g.W % 2 == 0)
-      return out == 2 ? launch_sums_impl<ALG, 2, true>(g, M, f, x_scale, inv_y, y, s)
-                      : launch_sums_impl<ALG, 0, true>(g, M, f, x_scale, inv_y, y, s);
+      return out == 2 ? launch_sums_impl<ALG, 2, true>(g, M, f, x_scale, inv_y, y, s, prepare)
+                      : launch_sums_impl<ALG, 0, true>(g, M, f, x_scale, inv_y, y, s, prepare);
   }
-  return out == 2 ? launch_sums_impl<ALG, 2, false>(g, M, f, x_scale, inv_y, y, s)
-                  : launch_sums_impl<ALG, 0, false>(g, M, f, x_scale, inv_y, y, s);
+  return out == 2 ? launch_sums_impl<ALG, 2, false>(g, M, f, x_scale, inv_y, y, s, prepare)
+                  : launch_sums_impl<ALG, 0, false>(g, M, f, x_scale, inv_y, y, s, prepare);
 }
 
 // out: 0 float32, 2 int8 with ReLU.  hipErrorNotSupported beyond the 32-bit offset limits.
 hipError_t launch_output_sums(int out, const Geometry& g, const int32_t* M, const FilterViews& f,
-                              float x_scale, float inv_y, void* y, hipStream_t s) {
+                              float x_scale, float inv_y, void* y, hipStream_t s, bool prepare) {
   const long long mbytes = 4ll * g.P * g.Tp * g.Kp, ybytes = 4ll * g.N * g.Cout * g.H * g.W;
   if (mbytes >= (1ll << 31) || ybytes >= (1ll << 31) || out == 1) return hipErrorNotSupported;
   switch (g.alg) {
-    case 0: return launch_sums_alg<0>(out, g, M, f, x_scale, inv_y, y, s);
-    case 1: return launch_sums_alg<1>(out, g, M, f, x_scale, inv_y, y, s);
-    case 2: return launch_sums_alg<2>(out, g, M, f, x_scale, inv_y, y, s);
-    case 3: return launch_sums_alg<3>(out, g, M, f, x_scale, inv_y, y, s);
-    case 4: return launch_sums_alg<4>(out, g, M, f, x_scale, inv_y, y, s);
-    case 5: return launch_sums_alg<5>(out, g, M, f, x_scale, inv_y, y, s);
-    case 6: return launch_sums_alg<6>(out, g, M, f, x_scale, inv_y, y, s);
-    case 7: return launch_sums_alg<7>(out, g, M, f, x_scale, inv_y, y, s);
+    case 0: return launch_sums_alg<0>(out, g, M, f, x_scale, inv_y, y, s, prepare);
+    case 1: return launch_sums_alg<1>(out, g, M, f, x_scale, inv_y, y, s, prepare);
+    case 2: return launch_sums_alg<2>(out, g, M, f, x_scale, inv_y, y, s, prepare);
+    case 3: return launch_sums_alg<3>(out, g, M, f, x_scale, inv_y, y, s, prepare);
+    case 4: return launch_sums_alg<4>(out, g, M, f, x_scale, inv_y, y, s, prepare);
+    case 5: return launch_sums_alg<5>(out, g, M, f, x_scale, inv_y, y, s, prepare);
+    case 6: return launch_sums_alg<6>(out, g, M, f, x_scale, inv_y, y, s, prepare);
+    case 7: return launch_sums_alg<7>(out, g, M, f, x_scale, inv_y, y, s, prepare);
   }
   return hipErrorInvalidValue;
 }

@@ -87,16 +87,10 @@ static bool make_input_plan(const Geometry& g, InputPlan* ip) {
 
 template <int ALG>
 static hipError_t launch_input_i8_alg(const Geometry& g, const InputPlan& ip, const int8_t* x,
-                                      void* V, const float* inv_sx, hipStream_t s) {
+                                      void* V, const float* inv_sx, hipStream_t s, bool prepare) {
   constexpr int NW = ALG < 2 ? 16 : 8;
   auto kernel = input_transform_i8_kernel<ALG, NW, NW == 8 ? 512 : 1024>;
-  static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once
-  if (!attr_done) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    (void)hipGetLastError();
-    attr_done = true;
-  }
+  if (prepare) return raise_lds_limit(reinterpret_cast<const void*>(kernel));
   const dim3 grid(tile_rect_groups(g, ip.tr) * (unsigned)(g.Cp / 64));
   hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), ip.lds_bytes, s, x, (int8_t*)V, inv_sx, g, ip);
   return hipGetLastError();
@@ -105,18 +99,18 @@ static hipError_t launch_input_i8_alg(const Geometry& g, const InputPlan& ip, co
 // Returns hipErrorNotSupported when the geometry is outside this kernel's limits;
 // the caller then uses the generic kernel.
 hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V,
-                                     const float* inv_sx, hipStream_t s) {
+                                     const float* inv_sx, hipStream_t s, bool prepare) {
   InputPlan ip;
   if (!make_input_plan(g, &ip)) return hipErrorNotSupported;
   switch (g.alg) {
-    case 0: return launch_input_i8_alg<0>(g, ip, x, V, inv_sx, s);
-    case 1: return launch_input_i8_alg<1>(g, ip, x, V, inv_sx, s);
-    case 2: return launch_input_i8_alg<2>(g, ip, x, V, inv_sx, s);
-    case 3: return launch_input_i8_alg<3>(g, ip, x, V, inv_sx, s);
-    case 4: return launch_input_i8_alg<4>(g, ip, x, V, inv_sx, s);
-    case 5: return launch_input_i8_alg<5>(g, ip, x, V, inv_sx, s);
-    case 6: return launch_input_i8_alg<6>(g, ip, x, V, inv_sx, s);
-    case 7: return launch_input_i8_alg<7>(g, ip, x, V, inv_sx, s);
+    case 0: return launch_input_i8_alg<0>(g, ip, x, V, inv_sx, s, prepare);
+    case 1: return launch_input_i8_alg<1>(g, ip, x, V, inv_sx, s, prepare);
+    case 2: return launch_input_i8_alg<2>(g, ip, x, V, inv_sx, s, prepare);
+    case 3: return launch_input_i8_alg<3>(g, ip, x, V, inv_sx, s, prepare);
+    case 4: return launch_input_i8_alg<4>(g, ip, x, V, inv_sx, s, prepare);
+    case 5: return launch_input_i8_alg<5>(g, ip, x, V, inv_sx, s, prepare);
+    case 6: return launch_input_i8_alg<6>(g, ip, x, V, inv_sx, s, prepare);
+    case 7: return launch_input_i8_alg<7>(g, ip, x, V, inv_sx, s, prepare);
   }
   return hipErrorInvalidValue;
 }

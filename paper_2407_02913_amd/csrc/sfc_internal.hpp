@@ -41,8 +41,11 @@ hipError_t launch_filter_transform(int mode, const Geometry& g, const int8_t* w,
 hipError_t launch_input_transform(int mode, const Geometry& g, const int8_t* x, void* V,
                                   const float* inv_sx, hipStream_t s);
 // requantized-mode kernel; hipErrorNotSupported when the geometry is outside its limits
+// Launchers with a `prepare` argument: when true nothing is launched; the call raises, on the
+// current device, the dynamic-LDS limit of the kernel instantiation it would launch (the
+// data pointers are not looked at) and returns what the runtime said.
 hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V,
-                                     const float* inv_sx, hipStream_t s);
+                                     const float* inv_sx, hipStream_t s, bool prepare = false);
 hipError_t launch_product(int mode, const Geometry& g, const void* V, const void* U, int32_t* M,
                           hipStream_t s);
 // requantized mode (sfc_gemm.hip): the products as P batched int8 GEMMs; the output
@@ -50,7 +53,8 @@ hipError_t launch_product(int mode, const Geometry& g, const void* V, const void
 hipError_t launch_product_gemm_i8(const Geometry& g, const void* V, const void* U, int32_t* M,
                                   hipStream_t s);
 hipError_t launch_output_sums(int out, const Geometry& g, const int32_t* M, const FilterViews& f,
-                              float x_scale, float inv_y, void* y, hipStream_t s);
+                              float x_scale, float inv_y, void* y, hipStream_t s,
+                              bool prepare = false);
 // out: 0 float32, 1 int32 sums (exact mode), 2 int8 with ReLU (inv_y = 1 / output scale)
 hipError_t launch_output_transform(int mode, int out, const Geometry& g, const int32_t* M,
                                    const FilterViews& f, float x_scale, float inv_y, void* y,
@@ -60,7 +64,8 @@ hipError_t launch_output_transform(int mode, int out, const Geometry& g, const i
 bool fused_quad_supported(const Geometry& g);
 int quad_filter_count(const Geometry& g);
 hipError_t launch_fused_quad(int out, const Geometry& g, const void* V, const FilterViews& f,
-                             float x_scale, float inv_y, void* y, hipStream_t s);
+                             float x_scale, float inv_y, void* y, hipStream_t s,
+                             bool prepare = false);
 // single-kernel path: whether it covers this geometry, the bytes of its filter operand,
 // the regrouping of the canonical U, the processing order (position -> canonical point)
 bool single_supported(const Geometry& g);
@@ -69,7 +74,15 @@ hipError_t launch_repack_filter(const Geometry& g, int filters, const void* U, v
                                 hipStream_t s);
 void single_point_order(int alg, int* pt /*[P]*/);
 hipError_t launch_single_conv(int out, const Geometry& g, const int8_t* x, const FilterViews& f,
-                              float x_scale, float inv_y, void* y, hipStream_t s);
+                              float x_scale, float inv_y, void* y, hipStream_t s,
+                              bool prepare = false);
+// Requantized mode: prepares every kernel that `path` (sfc_path) launches for this geometry
+// and output type.  Once per plan, from sfc_transform_filter.
+hipError_t prepare_kernels(int path, int out, const Geometry& g);
+// The limit of a kernel's dynamic LDS raised to the 160 KB of a gfx950 compute unit.
+inline hipError_t raise_lds_limit(const void* kernel) {
+  return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
 // abs-max calibration: maxima are int32, zeroed by the launcher
 hipError_t launch_act_absmax(const Geometry& g, const int8_t* x, int32_t* maxima /*[P]*/,
                              hipStream_t s);

@@ -273,7 +273,7 @@ __global__ __launch_bounds__(256) void product_i16_kernel(const int16_t* __restr
   const int kb = blockIdx.x % kblocks, tb = blockIdx.x / kblocks;
   const int p = blockIdx.y;
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-  int acc = 0;
+  unsigned acc = 0;  // sums modulo 2^32: wrap-around is defined, exact while the true sum fits
   for (int kc = 0; kc < g.Cp; kc += 64) {
     for (int i = threadIdx.x; i < 16 * 64; i += 256) {
       const int r = i >> 6, c = i & 63;
@@ -282,10 +282,10 @@ __global__ __launch_bounds__(256) void product_i16_kernel(const int16_t* __restr
     }
     __syncthreads();
 #pragma unroll 16
-    for (int c = 0; c < 64; ++c) acc += (int)sv[ty][c] * (int)su[tx][c];
+    for (int c = 0; c < 64; ++c) acc += (unsigned)((int)sv[ty][c] * (int)su[tx][c]);
     __syncthreads();
   }
-  M[((size_t)p * g.Tp + tb * 16 + ty) * g.Kp + kb * 16 + tx] = acc;
+  M[((size_t)p * g.Tp + tb * 16 + ty) * g.Kp + kb * 16 + tx] = (int32_t)acc;
 }
 
 // ---------------------------------------------------------------------------
@@ -310,8 +310,11 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __
 
   constexpr int MT = AlgTraits<ALG>::M;
   {
-    int out[MT][MT];
-    output_transform<ALG, int>([&](int p) { return m[p * pstride]; }, out);
+    // unsigned: the add network runs modulo 2^32 (the division by 3 of the Hermitian forms
+    // is a multiplication by the inverse of 3), so only the final kDen-fold sums -- and, for
+    // SFC-4, the sums it halves -- have to fit 32 bits
+    unsigned out[MT][MT];
+    output_transform<ALG, unsigned>([&](int p) { return (unsigned)m[p * pstride]; }, out);
     const float scale = x_scale * wscale[k];
 #pragma unroll
     for (int o1 = 0; o1 < MT; ++o1) {
@@ -321,7 +324,7 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const int32_t* __
       for (int o2 = 0; o2 < MT; ++o2) {
         const int w = MT * tj + o2;
         if (w >= g.W) continue;
-        const int acc = out[o1][o2] / AlgTraits<ALG>::kDen;  // exact: the sum is a multiple of it
+        const int acc = (int)out[o1][o2] / AlgTraits<ALG>::kDen;  // exact: the sum is a multiple of it
         if constexpr (OUT == 1)
           ((int32_t*)y)[ybase + (size_t)h * g.W + w] = acc;
         else
@@ -402,6 +405,16 @@ hipError_t launch_input_transform(int mode, const Geometry& g, const int8_t* x, 
     return launch_input_alg<1>(g, x, V, inv_sx, nullptr, s);
   }
   return launch_input_alg<0>(g, x, V, inv_sx, nullptr, s);
+}
+
+hipError_t prepare_kernels(int path, int out, const Geometry& g) {
+  const FilterViews none{};
+  if (path == 2) return launch_single_conv(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true);
+  // the generic input kernel (geometries the int8 one does not take) stays under 64 KB
+  hipError_t e = launch_input_transform_i8(g, nullptr, nullptr, nullptr, nullptr, true);
+  if (e != hipSuccess && e != hipErrorNotSupported) return e;
+  if (path == 1) return launch_fused_quad(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true);
+  return launch_output_sums(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true);
 }
 
 hipError_t launch_act_absmax(const Geometry& g, const int8_t* x, int32_t* maxima, hipStream_t s) {

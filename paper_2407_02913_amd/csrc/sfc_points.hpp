@@ -377,6 +377,10 @@ struct Third<int> {
   static SFC_HD int apply(int v) { return (int)((unsigned)v * 0xAAAAAAABu); }
 };
 template <>
+struct Third<unsigned> {  // the same modulo 2^32, wrap-around defined
+  static SFC_HD unsigned apply(unsigned v) { return v * 0xAAAAAAABu; }
+};
+template <>
 struct Third<float> {
   static SFC_HD float apply(float v) { return v * (1.0f / 3.0f); }
 };
@@ -434,6 +438,10 @@ struct Half;
 template <>
 struct Half<int> {
   static SFC_HD int apply(int v) { return v >> 1; }  // exact: the argument is even
+};
+template <>
+struct Half<unsigned> {  // two's-complement value halved (exact while it fits 32 bits)
+  static SFC_HD unsigned apply(unsigned v) { return (unsigned)((int)v >> 1); }
 };
 template <>
 struct Half<float> {

@@ -268,15 +268,9 @@ void single_point_order(int alg, int* pt /*[P rounded up to a multiple of 4]*/) 
 template <int ALG, int OUT, bool VEC2, int NW, bool STRIPS = false>
 static hipError_t launch_single_impl(const Geometry& g, const SinglePlan& sp, const int8_t* x,
                                      const FilterViews& f, float x_scale, float inv_y, void* y,
-                                     hipStream_t s) {
+                                     hipStream_t s, bool prepare) {
   auto kernel = single_conv_kernel<ALG, OUT, VEC2, NW, AlgTraits<ALG>::M == 4 ? 2 : 1, STRIPS>;
-  static bool attr_done = false;  // raises the dynamic LDS limit of this instantiation once
-  if (!attr_done) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    (void)hipGetLastError();
-    attr_done = true;
-  }
+  if (prepare) return raise_lds_limit(reinterpret_cast<const void*>(kernel));
   const dim3 grid(tile_rect_groups(g, sp.tr), (unsigned)sp.kgroups);
   hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), sp.lds_bytes, s, x, (const int8_t*)f.U_single,
                      f.dequant_single, f.inv_sx, x_scale, inv_y, y, g, sp);
@@ -286,38 +280,38 @@ static hipError_t launch_single_impl(const Geometry& g, const SinglePlan& sp, co
 template <int ALG, int OUT>
 static hipError_t launch_single_out(const Geometry& g, const SinglePlan& sp, const int8_t* x,
                                     const FilterViews& f, float x_scale, float inv_y, void* y,
-                                    hipStream_t s) {
+                                    hipStream_t s, bool prepare) {
   constexpr int NW = AlgTraits<ALG>::M == 6 ? kWaves6 : 8;
   constexpr bool kPairs = AlgTraits<ALG>::M % 2 == 0;  // pairs of an output row stay aligned
   if constexpr (AlgTraits<ALG>::M == 4) {
     if (sp.strips)
-      return launch_single_impl<ALG, OUT, true, NW, true>(g, sp, x, f, x_scale, inv_y, y, s);
+      return launch_single_impl<ALG, OUT, true, NW, true>(g, sp, x, f, x_scale, inv_y, y, s, prepare);
   }
   if constexpr (kPairs) {
-    if (g.W % 2 == 0) return launch_single_impl<ALG, OUT, true, NW>(g, sp, x, f, x_scale, inv_y, y, s);
+    if (g.W % 2 == 0) return launch_single_impl<ALG, OUT, true, NW>(g, sp, x, f, x_scale, inv_y, y, s, prepare);
   }
-  return launch_single_impl<ALG, OUT, false, NW>(g, sp, x, f, x_scale, inv_y, y, s);
+  return launch_single_impl<ALG, OUT, false, NW>(g, sp, x, f, x_scale, inv_y, y, s, prepare);
 }
 
 template <int ALG>
 static hipError_t launch_single_alg(int out, const Geometry& g, const SinglePlan& sp,
                                     const int8_t* x, const FilterViews& f, float x_scale,
-                                    float inv_y, void* y, hipStream_t s) {
-  return out == 2 ? launch_single_out<ALG, 2>(g, sp, x, f, x_scale, inv_y, y, s)
-                  : launch_single_out<ALG, 0>(g, sp, x, f, x_scale, inv_y, y, s);
+                                    float inv_y, void* y, hipStream_t s, bool prepare) {
+  return out == 2 ? launch_single_out<ALG, 2>(g, sp, x, f, x_scale, inv_y, y, s, prepare)
+                  : launch_single_out<ALG, 0>(g, sp, x, f, x_scale, inv_y, y, s, prepare);
 }
 
 hipError_t launch_single_conv(int out, const Geometry& g, const int8_t* x, const FilterViews& f,
-                              float x_scale, float inv_y, void* y, hipStream_t s) {
+                              float x_scale, float inv_y, void* y, hipStream_t s, bool prepare) {
   SinglePlan sp;
   if (!make_single_plan(g, &sp) || out == 1) return hipErrorNotSupported;
   switch (g.alg) {
-    case 0: return launch_single_alg<0>(out, g, sp, x, f, x_scale, inv_y, y, s);
-    case 1: return launch_single_alg<1>(out, g, sp, x, f, x_scale, inv_y, y, s);
-    case 2: return launch_single_alg<2>(out, g, sp, x, f, x_scale, inv_y, y, s);
-    case 3: return launch_single_alg<3>(out, g, sp, x, f, x_scale, inv_y, y, s);
-    case 4: return launch_single_alg<4>(out, g, sp, x, f, x_scale, inv_y, y, s);
-    case 5: return launch_single_alg<5>(out, g, sp, x, f, x_scale, inv_y, y, s);
+    case 0: return launch_single_alg<0>(out, g, sp, x, f, x_scale, inv_y, y, s, prepare);
+    case 1: return launch_single_alg<1>(out, g, sp, x, f, x_scale, inv_y, y, s, prepare);
+    case 2: return launch_single_alg<2>(out, g, sp, x, f, x_scale, inv_y, y, s, prepare);
+    case 3: return launch_single_alg<3>(out, g, sp, x, f, x_scale, inv_y, y, s, prepare);
+    case 4: return launch_single_alg<4>(out, g, sp, x, f, x_scale, inv_y, y, s, prepare);
+    case 5: return launch_single_alg<5>(out, g, sp, x, f, x_scale, inv_y, y, s, prepare);
   }
   return hipErrorInvalidValue;
 }

@@ -332,17 +332,20 @@ def test_sfc4_full_size_and_int8_output(binding, alg):
         assert check_i8_against_oracle(y8, y_ref, y_scale) < 1e-3
 
 
-@pytest.mark.parametrize("name", FULL)
-def test_full_size_requant_against_oracle(binding, name):
-    """The ResNet-shaped workloads at full size, staged path, every element."""
+@pytest.mark.parametrize("name,alg", [(n, "6x6_p88") for n in FULL] +
+                         [("resnet14", "7x7_p132"), ("resnet7", "7x7_p132"),  # the 7x7 stretch of Sec. 4.2
+                          ("resnet14", "4x4_p46"), ("resnet7", "4x4_p46")])   # ragged 4x4 tiles
+def test_full_size_requant_against_oracle(binding, name, alg):
+    """The ResNet-shaped workloads at full size, staged path: every element of V, U, M and y."""
     shape = synth.LAYERS[name]
-    print("case full", name, flush=True)
+    print("case full", name, alg, flush=True)
     d = synth.make_layer(shape)
-    sx = oracle.calibrate_act_scales(d["x_calib"])
-    sw = oracle.calibrate_filter_scales(d["w"])
-    y_ref, taps_ref = oracle.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"], return_taps=True)
-    y, taps = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", sx=sx, sw=sw,
-                             return_taps=True)
+    sx = oracle.calibrate_act_scales(d["x_calib"], alg)
+    sw = oracle.calibrate_filter_scales(d["w"], alg)
+    y_ref, taps_ref = oracle.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"], alg,
+                                          return_taps=True)
+    y, taps = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="requant", alg=alg, sx=sx,
+                             sw=sw, return_taps=True)
     for tap in ("V", "U", "M"):
         assert np.array_equal(taps[tap].astype(np.int64), taps_ref[tap]), tap
     assert rel_err(y, y_ref) <= F32_TOL
@@ -359,7 +362,9 @@ def test_full_size_exact_against_direct_conv(binding, name):
     d = synth.make_layer(shape)
     ref = oracle.direct_conv(d["x"], d["w"])
     assert np.abs(ref).max() * 36 < 2**31  # int32 sums hold for this data (Cin = 512 included)
-    acc = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="exact", out="i32")
+    # beyond 404 channels the caller vouches for the 32-bit sums (checked on this data above)
+    flags = binding.FLAG_EXACT_WIDE if shape.Cin > 404 else 0
+    acc = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="exact", out="i32", flags=flags)
     assert np.array_equal(acc.astype(np.int64), ref)
 
 
@@ -589,28 +594,56 @@ def test_int8_output_needs_its_scale(binding):
 
 
 def test_resnet18_shaped_stack_chained_with_int8_activations(binding):
-    """The 13 stride-1 3x3 layers, chained inside each resolution stage (reduced batch).
+    """The 13 stride-1 3x3 layers at batch 64 exactly as bench.py runs them: layers built by
+    ``layers.Layer`` (algorithm and path chosen by the library, the library's own abs-max
+    calibration, int8 + ReLU output with the same output scale), chained inside each resolution
+    stage.
 
-    Every layer is checked against the oracle on the oracle's own input of that layer;
-    the library's self-chained run must then stay close to the oracle's chain."""
-    layers = synth.stack_layers(batch=8)
+    Every layer is checked against the oracle on the oracle's own input of that layer, with the
+    scales the library calibrated (the scales are inputs of both sides; that the library's
+    calibration equals the oracle's is test_gpu_calibration_matches_oracle); the library's
+    self-chained run must then stay close to the oracle's chain."""
+    from paper_2407_02913_amd import layers
+
     x_ref = x_gpu = None
     prev = None
-    for idx, shape in enumerate(layers):
-        print("case stack layer", idx, shape.name, flush=True)
-        d = synth.make_layer(shape)
+    for idx, shape in enumerate(synth.stack_layers()):
+        assert shape.N == synth.STACK_BATCH == 64
+        d = synth.make_layer(shape, batch=4)  # weights, filter scales, calibration activations
+        layer = layers.Layer(shape, d, out="i8", alg="auto", path="auto")
+        print("case stack layer", idx, shape.name, layer.alg, layer.path, flush=True)
         if prev is None or (shape.Cin, shape.H) != (prev.Cin, prev.H):
-            x_ref = x_gpu = d["x"]  # a new stage starts from fresh synthetic activations
-        sx = oracle.calibrate_act_scales(x_ref)
-        sw = oracle.calibrate_filter_scales(d["w"])
-        y_ref = oracle.conv_requant(x_ref, d["w"], sx, sw, d["x_scale"], d["w_scale"])
-        y_scale = float(np.float32(max(y_ref.max(), 1e-6) / 127.0))
-        kw = dict(mode="requant", path="fused", out="i8", sx=sx, sw=sw, y_scale=y_scale)
-        y8 = binding.conv2d(x_ref, d["w"], d["x_scale"], d["w_scale"], **kw)
-        check_i8_against_oracle(y8, y_ref, y_scale)
+            rng = np.random.default_rng(synth.BASE_SEED + shape.Cin)
+            x_ref = x_gpu = synth.activations((shape.N, shape.Cin, shape.H, shape.W), "relu", rng)
+        y_ref = oracle.conv_requant(x_ref, d["w"], layer.sx, layer.sw, d["x_scale"], d["w_scale"], layer.alg)
+        y8 = layers.np_conv(layer, x_ref)
+        frac = check_i8_against_oracle(y8, y_ref, layer.y_scale)
+        assert frac < 1e-3
+        assert y8.max() >= 32  # the output scale puts the activations into the int8 range
         # self-chained: the library's own previous output is this layer's input
-        y8_chain = binding.conv2d(x_gpu, d["w"], d["x_scale"], d["w_scale"], **kw)
-        x_next_ref = oracle.requantize_activation(y_ref, y_scale)
+        y8_chain = layers.np_conv(layer, x_gpu)
+        x_next_ref = oracle.requantize_activation(y_ref, layer.y_scale)
+        # (a sanity check of the chain, not the parity bar: single steps of difference at
+        # rounding boundaries of one layer spread through the next ones of the stage)
         delta = np.abs(y8_chain.astype(np.int64) - x_next_ref.astype(np.int64))
-        assert delta.max() <= 2 and np.mean(delta != 0) < 0.01
+        assert delta.max() <= 4 and np.mean(delta != 0) < 0.01
         x_ref, x_gpu, prev = x_next_ref, y8_chain, shape
+        layer.close()
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_single_layers_as_benchmarked(binding, name):
+    """The four ResNet-shaped layers exactly as bench.py runs them (``layers.Layer``: algorithm
+    and path chosen by the library, its own calibration, float32 output), every element."""
+    from paper_2407_02913_amd import layers
+
+    shape = synth.LAYERS[name]
+    d = synth.make_layer(shape)
+    layer = layers.Layer(shape, d, out="f32", alg="auto", path="auto")
+    print("case layer as benchmarked", name, layer.alg, layer.path, flush=True)
+    assert np.array_equal(layer.sx, oracle.calibrate_act_scales(d["x_calib"], layer.alg))
+    assert np.array_equal(layer.sw, oracle.calibrate_filter_scales(d["w"], layer.alg))
+    y_ref = oracle.conv_requant(d["x"], d["w"], layer.sx, layer.sw, d["x_scale"], d["w_scale"], layer.alg)
+    y = layers.np_conv(layer, d["x"])
+    assert rel_err(y, y_ref) <= F32_TOL
+    layer.close()

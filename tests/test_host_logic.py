@@ -60,7 +60,7 @@ def make_desc(**kw):
     from paper_2407_02913_amd import binding
 
     base = dict(N=2, Cin=16, Cout=24, H=14, W=9, alg=0, mode=1, out=0, path=0, per_channel_wscale=1,
-                transform_bits=0)
+                transform_bits=0, flags=0)
     base.update(kw)
     return binding.ConvDesc(**base)
 
@@ -94,18 +94,86 @@ def test_plan_sizes_and_counts(lib):
 @pytest.mark.parametrize(
     "kw,code",
     [
-        (dict(N=0), 1), (dict(Cin=-1), 1), (dict(H=0), 1), (dict(alg=8), 1), (dict(mode=2), 1),
-        (dict(out=5), 1), (dict(path=3), 1), (dict(per_channel_wscale=2), 1),
+        (dict(N=0), 1), (dict(Cin=-1), 1), (dict(H=0), 1), (dict(alg=8), 1), (dict(alg=-2), 1),
+        (dict(mode=2), 1), (dict(out=5), 1), (dict(path=3), 1), (dict(path=-2), 1),
+        (dict(per_channel_wscale=2), 1), (dict(flags=2), 1),
         (dict(transform_bits=1), 1), (dict(transform_bits=9), 1),
         (dict(transform_bits=4, mode=0), 2),  # exact mode has no transform-domain rounding
         (dict(out=1, mode=1), 2),  # raw integer output only in exact mode
         (dict(path=1, mode=0), 2),  # fused path is the requantized one
         (dict(W=5000), 2),
+        # exact mode keeps 32-bit sums: guaranteed up to 404 channels (3x3), 145 (5x5 filters)
+        (dict(mode=0, Cin=405), 2), (dict(mode=0, alg=6, Cin=146), 2),
+        (dict(Cout=65521), 2),  # one workgroup row per (padded) filter must fit a launch grid
     ],
 )
 def test_plan_rejects_bad_descriptions(lib, kw, code):
     st, h = plan_status(lib, make_desc(**kw))
     assert st == code and not h.value
+
+
+def test_exact_mode_channel_bound_and_its_opt_in(lib):
+    for kw in (dict(mode=0, Cin=404), dict(mode=0, alg=6, Cin=145), dict(mode=0, Cin=512, flags=1),
+               dict(mode=1, Cin=512)):
+        st, h = plan_status(lib, make_desc(**kw))
+        assert st == 0, kw
+        lib.sfc_plan_destroy(h)
+
+
+def test_auto_algorithm_and_path(lib):
+    """SFC_ALG_AUTO / SFC_PATH_AUTO: the library's choice per layer shape, reported by
+    sfc_plan_choice; an explicit choice is kept.  The ResNet shapes and the 13-layer stack get
+    what bench.py runs (it asks for auto and reads the choice back)."""
+    from paper_2407_02913_amd import binding, synth
+
+    def choice(shape, **kw):
+        plan = binding.Plan(shape.N, shape.Cin, shape.Cout, shape.H, shape.W, **kw)
+        got = (plan.alg, plan.path)
+        plan.close()
+        return got
+
+    want = {"tiny32": ("4x4_p46", "single"), "resnet56": ("4x4_p46", "single"),
+            "resnet28": ("4x4_p46", "fused"), "resnet14": ("7x7_p132", "fused"),
+            "resnet7": ("7x7_p132", "staged"), "cifar16": ("4x4_p46", "fused"),
+            "cifar8": ("4x4_p46", "fused")}
+    for name, shape in synth.LAYERS.items():
+        assert choice(shape, alg="auto", path="auto") == want[name], name
+    assert choice(synth.LAYERS["resnet56"], alg="6x6_p88", path="staged") == ("6x6_p88", "staged")
+    assert choice(synth.LAYERS["resnet56"], alg="7x7_p132", path="auto") == ("7x7_p132", "single")
+    # exact mode runs staged, on the 6x6 form the paper's headline count is about
+    assert choice(synth.LAYERS["tiny32"], alg="auto", path="auto", mode="exact") == ("6x6_p88", "staged")
+    # channel counts the fused kernel does not take (three 64-channel slices) fall back
+    odd = synth.LayerShape("odd", 2, 192, 32, 14, 14, "relu", True, 9)
+    assert choice(odd, alg="auto", path="auto")[1] == "staged"
+    for shape in synth.stack_layers():
+        alg, path = choice(shape, alg="auto", path="auto", out="i8")
+        assert alg == binding.AUTO_ALG_3X3
+        assert path == ("single" if shape.Cin <= binding.SINGLE_MAX_CIN else "fused")
+
+
+def test_undersized_buffers_are_refused_before_any_launch(lib):
+    """Every call that takes a caller-owned device buffer takes its size and returns
+    SFC_EWORKSPACE when it is too small (no GPU here: a launch would fail differently)."""
+    st, h = plan_status(lib, make_desc())
+    assert st == 0
+    fb, wb = C.c_size_t(), C.c_size_t()
+    assert lib.sfc_plan_sizes(h, C.byref(fb), C.byref(wb), None, None) == 0
+    p = 88
+    sx = (C.c_float * p)(*([0.5] * p))
+    sw = (C.c_float * (p * 24))(*([0.25] * (p * 24)))
+    assert lib.sfc_set_point_scales(h, sx, sw) == 0
+    ws = (C.c_float * 24)(*([0.01] * 24))
+    dev = C.c_void_p(4096)
+    assert lib.sfc_transform_filter(h, dev, ws, dev, fb.value - 1, None) == 6
+    assert lib.sfc_conv2d_nchw(h, dev, C.c_float(1.0), dev, dev, wb.value - 1, None) == 6
+    assert lib.sfc_conv2d_stages(h, dev, C.c_float(1.0), dev, dev, 0, None, 7) == 6
+    out = (C.c_float * (p * 24))()
+    assert lib.sfc_calibrate_act_scales(h, dev, 1, dev, wb.value - 1, None, out) == 6
+    assert lib.sfc_calibrate_filter_scales(h, dev, dev, wb.value - 1, None, out) == 6
+    # large enough: the next check in line answers (the filter has not been transformed)
+    assert lib.sfc_conv2d_nchw(h, dev, C.c_float(1.0), dev, dev, wb.value, None) == 4
+    assert lib.sfc_status_string(6) == b"device buffer smaller than the plan needs"
+    lib.sfc_plan_destroy(h)
 
 
 def test_null_and_order_errors_without_gpu(lib):
@@ -122,16 +190,17 @@ def test_null_and_order_errors_without_gpu(lib):
     assert lib.sfc_set_point_scales(h, nan, sw) == 1
     assert lib.sfc_set_point_scales(h, sx, sw) == 0
     # conv before the filter transform, and misaligned / null pointers: rejected before any launch
-    assert lib.sfc_conv2d_nchw(h, C.c_void_p(256), C.c_float(1.0), C.c_void_p(512), C.c_void_p(1024), None) == 4
-    assert lib.sfc_conv2d_nchw(h, None, C.c_float(1.0), C.c_void_p(512), C.c_void_p(1024), None) == 1
-    assert lib.sfc_conv2d_nchw(h, C.c_void_p(257), C.c_float(1.0), C.c_void_p(512), C.c_void_p(1024), None) == 1
-    assert lib.sfc_conv2d_nchw(h, C.c_void_p(256), C.c_float(-1.0), C.c_void_p(512), C.c_void_p(1024), None) == 1
+    big = C.c_size_t(1 << 40)
+    assert lib.sfc_conv2d_nchw(h, C.c_void_p(256), C.c_float(1.0), C.c_void_p(512), C.c_void_p(1024), big, None) == 4
+    assert lib.sfc_conv2d_nchw(h, None, C.c_float(1.0), C.c_void_p(512), C.c_void_p(1024), big, None) == 1
+    assert lib.sfc_conv2d_nchw(h, C.c_void_p(257), C.c_float(1.0), C.c_void_p(512), C.c_void_p(1024), big, None) == 1
+    assert lib.sfc_conv2d_nchw(h, C.c_void_p(256), C.c_float(-1.0), C.c_void_p(512), C.c_void_p(1024), big, None) == 1
     ws = (C.c_float * 24)(*([0.01] * 24))
-    assert lib.sfc_transform_filter(h, C.c_void_p(3), ws, C.c_void_p(512), None) == 1
+    assert lib.sfc_transform_filter(h, C.c_void_p(3), ws, C.c_void_p(512), big, None) == 1
     lib.sfc_plan_destroy(h)
     # requantized mode needs its scales before the filter transform
     st, h = plan_status(lib, make_desc())
-    assert lib.sfc_transform_filter(h, C.c_void_p(256), ws, C.c_void_p(512), None) == 4
+    assert lib.sfc_transform_filter(h, C.c_void_p(256), ws, C.c_void_p(512), big, None) == 4
     lib.sfc_plan_destroy(h)
     # exact-mode plans take no point scales
     st, h = plan_status(lib, make_desc(mode=0))
@@ -185,29 +254,6 @@ def test_bench_operation_counts_match_the_add_networks(tmp_path):
     # the 6x6 input network is the paper's: 14 additions per symbolic DFT-6 plus the correction
     # inputs, 16 per 1-D pass over 8 + 8 lines, plus the sums of the product rule
     assert bench.ADD_NETWORK_OPS["6x6_p88"][0] == 16 * 16 + 48
-
-
-def test_bench_variant_per_layer_shape():
-    """bench.py's choice of tile size and path: the benchmark layer runs on the single-kernel
-    path with 4x4 tiles, and the choice follows what each path supports."""
-    import bench
-    from paper_2407_02913_amd import synth
-
-    want = {"tiny32": ("4x4_p46", "single"), "resnet56": ("4x4_p46", "single"),
-            "resnet28": ("4x4_p46", "fused"), "resnet14": ("7x7_p132", "fused"),
-            "resnet7": ("7x7_p132", "staged"), "cifar16": ("4x4_p46", "fused"),
-            "cifar8": ("4x4_p46", "fused")}
-    for name, shape in synth.LAYERS.items():
-        assert bench.pick_variant(shape) == want[name], name
-    # an explicit choice is kept
-    assert bench.pick_variant(synth.LAYERS["resnet56"], "6x6_p88", "staged") == ("6x6_p88", "staged")
-    for shape in synth.stack_layers():
-        alg, path = bench.pick_variant(shape)
-        assert path != "single" or shape.Cin <= 64  # the single kernel takes one 64-channel slice
-        m = int(alg[0])
-        if path == "fused":  # at least one workgroup per compute unit
-            tiles = shape.N * -(-shape.H // m) * -(-shape.W // m)
-            assert -(-tiles // 16) * -(-shape.Cout // 32) >= 256
 
 
 def test_group_scales_matches_the_oracle_for_every_granularity(lib):
