@@ -224,6 +224,18 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
 sfc_status sfc_conv2d_nchw(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale, void* y_dev,
                            void* workspace_dev, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or pass a workspace along (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same work as
+ * sfc_conv2d_nchw with the workspace taken from a buffer of SFC_STATIC_WORKSPACE_BYTES that
+ * is part of the library's code object, one copy per GPU, held until the process ends.  The
+ * call allocates and frees nothing.  Plans whose workspace is larger are refused with
+ * SFC_EWORKSPACE before any launch.  Every call on a GPU shares that GPU's buffer: calls that
+ * overlap on one GPU (different streams, or threads) race; calls queued on one stream do
+ * not.  V (and M) of the previous call are overwritten, nothing needs clearing. */
+#define SFC_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)
+sfc_status sfc_conv2d_nchw_static(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale,
+                                  void* y_dev, void* stream);
+
 /* Profiling aid: the same work as sfc_conv2d_nchw restricted to the stages in
  * stage_mask, so that one stage can be timed alone on buffers a full call has
  * filled.  SFC_STAGE_INPUT: V = B^T x B.  SFC_STAGE_PRODUCT: M = V.U (staged path).

@@ -32,6 +32,7 @@ FLAG_EXACT_WIDE = 1
 #: path="auto" runs in one kernel (mirrors of the library's rule, for tests and reports)
 AUTO_ALG_3X3 = "4x4_p46"
 SINGLE_MAX_CIN = 64
+STATIC_WORKSPACE_BYTES = 32 << 20  # SFC_STATIC_WORKSPACE_BYTES
 STAGE_INPUT, STAGE_PRODUCT, STAGE_OUTPUT, STAGE_ALL = 1, 2, 4, 7
 #: every symbol include/sfc.h declares
 EXPORTS = (
@@ -39,7 +40,7 @@ EXPORTS = (
     "sfc_set_output_scale",
     "sfc_group_scales",
     "sfc_calibrate_act_scales", "sfc_calibrate_filter_scales", "sfc_transform_filter",
-    "sfc_conv2d_nchw", "sfc_conv2d_stages", "sfc_tap_info", "sfc_stream_copy", "sfc_status_string",
+    "sfc_conv2d_nchw", "sfc_conv2d_nchw_static", "sfc_conv2d_stages", "sfc_tap_info", "sfc_stream_copy", "sfc_status_string",
 )
 
 
@@ -93,6 +94,8 @@ def load(force: bool = False):
     lib.sfc_transform_filter.restype = i32
     lib.sfc_conv2d_nchw.argtypes = [vp, vp, f32, vp, vp, C.c_size_t, vp]
     lib.sfc_conv2d_nchw.restype = i32
+    lib.sfc_conv2d_nchw_static.argtypes = [vp, vp, f32, vp, vp]
+    lib.sfc_conv2d_nchw_static.restype = i32
     lib.sfc_conv2d_stages.argtypes = [vp, vp, f32, vp, vp, C.c_size_t, vp, i32]
     lib.sfc_conv2d_stages.restype = i32
     lib.sfc_tap_info.argtypes = [vp, vp, i32, C.POINTER(vp), C.POINTER(i32),
@@ -216,6 +219,12 @@ class Plan:
                                       C.c_void_p(y_dev.data_ptr()), C.c_void_p(workspace.data_ptr()),
                                       _nbytes(workspace), _stream_ptr(stream)),
                "sfc_conv2d_nchw")
+
+    def conv2d_static(self, x_dev, x_scale: float, y_dev, stream=None):
+        """sfc_conv2d_nchw with the library's built-in workspace (nothing is allocated)."""
+        _check(load().sfc_conv2d_nchw_static(self._h, C.c_void_p(x_dev.data_ptr()), C.c_float(x_scale),
+                                             C.c_void_p(y_dev.data_ptr()), _stream_ptr(stream)),
+               "sfc_conv2d_nchw_static")
 
     def conv2d_stages(self, x_dev, x_scale: float, y_dev, workspace, mask: int, stream=None):
         _check(load().sfc_conv2d_stages(self._h, C.c_void_p(x_dev.data_ptr()), C.c_float(x_scale),

@@ -33,7 +33,32 @@ struct sfc_plan_s {
   float inv_y;  // 1 / output scale (SFC_OUT_I8_RELU), 0: not set
 };
 
+// Workspace of sfc_conv2d_nchw_static: part of the code object, one copy per GPU.  In host
+// code this name is only a handle for hipGetSymbolAddress; the device address it yields is
+// what kernels and copies get.
+static __device__ __align__(256) unsigned char scratch[SFC_STATIC_WORKSPACE_BYTES];
+
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device; nullptr if
+// the runtime refuses.
+void* static_workspace() {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* addr[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    addr[dev] = p;
+  }
+  return addr[dev];
+}
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -406,6 +431,16 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
 sfc_status sfc_conv2d_nchw(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale, void* y_dev,
                            void* workspace_dev, size_t workspace_bytes, void* stream) {
   return sfc_conv2d_stages(plan, x_dev, x_scale, y_dev, workspace_dev, workspace_bytes, stream,
+                           SFC_STAGE_ALL);
+}
+
+sfc_status sfc_conv2d_nchw_static(const sfc_plan_t* plan, const int8_t* x_dev, float x_scale,
+                                  void* y_dev, void* stream) {
+  if (!plan) return SFC_EINVAL;
+  if (plan->workspace_bytes > SFC_STATIC_WORKSPACE_BYTES) return SFC_EWORKSPACE;
+  void* ws = static_workspace();
+  if (!ws) return SFC_EHIP;
+  return sfc_conv2d_stages(plan, x_dev, x_scale, y_dev, ws, SFC_STATIC_WORKSPACE_BYTES, stream,
                            SFC_STAGE_ALL);
 }
 
