@@ -30,6 +30,7 @@ struct sfc_plan_s {
   bool filter_ready;
   int quad_filters;  // filters covered by the regrouped filter operand (0: none)
   int dq_filters;    // filters in the [filter][processing position] dequantization table (0: none)
+  bool quad16;       // fused path of the SFC-4 forms: 16 filters per wave, four pairs per lane
   float inv_y;  // 1 / output scale (SFC_OUT_I8_RELU), 0: not set
 };
 
@@ -199,7 +200,9 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   p->off_U_single = off;
   p->quad_filters = 0;
   if (d.path == SFC_PATH_SINGLE) p->quad_filters = (g.Cout + 63) / 64 * 64;
-  if (d.path == SFC_PATH_FUSED) p->quad_filters = sfc::quad_filter_count(g);
+  p->quad16 = d.path == SFC_PATH_FUSED && sfc::quad16_supported(g);
+  if (d.path == SFC_PATH_FUSED)
+    p->quad_filters = p->quad16 ? sfc::quad16_filter_count(g) : sfc::quad_filter_count(g);
   // the staged output transform reads the same [filter][position] table as the fused kernels
   p->dq_filters = p->quad_filters;
   if (d.path == SFC_PATH_STAGED && d.mode == SFC_MODE_REQUANT_I8) p->dq_filters = g.Kp;
@@ -355,14 +358,24 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
     }
   }
   if (plan->dq_filters > 0) {
-    // [filter][processing position]; filters beyond Cout stay zero
     const int pp = (g.P + 3) / 4 * 4;
     std::vector<int> pt(pp, -1);
     sfc::single_point_order(plan->d.alg, pt.data());
     float* dqs = table(plan->off_dq_single);
-    for (int k = 0; k < g.Cout; ++k)
-      for (int j = 0; j < pp; ++j)
-        dqs[(size_t)k * pp + j] = pt[j] < 0 ? 0.0f : dequant[(size_t)pt[j] * g.Kp + k];
+    if (plan->quad16) {
+      // [group of 16 filters][processing position][lane quarter q][i]: filter 16*fg + 4*i + q
+      for (int k = 0; k < g.Cout; ++k) {
+        const int fg = k >> 4, i = (k & 15) >> 2, q = k & 3;
+        for (int j = 0; j < pp; ++j)
+          dqs[((size_t)fg * pp + j) * 16 + 4 * q + i] =
+              pt[j] < 0 ? 0.0f : dequant[(size_t)pt[j] * g.Kp + k];
+      }
+    } else {
+      // [filter][processing position]; filters beyond Cout stay zero
+      for (int k = 0; k < g.Cout; ++k)
+        for (int j = 0; j < pp; ++j)
+          dqs[(size_t)k * pp + j] = pt[j] < 0 ? 0.0f : dequant[(size_t)pt[j] * g.Kp + k];
+    }
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   // the kernels of this plan's path that need more than the default 64 KB of dynamic LDS
@@ -373,7 +386,9 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
   const FilterViews f = views(plan, filter_dev);
   if (sfc::launch_filter_transform(plan->d.mode, g, w_dev, f, s) != hipSuccess)
     return SFC_EHIP;
-  if (quad && sfc::launch_repack_filter(g, plan->quad_filters, f.U, f.U_single, s) != hipSuccess)
+  if (quad && (plan->quad16 ? sfc::launch_repack_filter16(g, plan->quad_filters, f.U, f.U_single, s)
+                            : sfc::launch_repack_filter(g, plan->quad_filters, f.U, f.U_single, s)) !=
+                  hipSuccess)
     return SFC_EHIP;
   plan->filter_dev = filter_dev;
   plan->filter_ready = true;
@@ -412,7 +427,9 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
   }
   if (fused) {
     if (tail &&
-        sfc::launch_fused_quad(plan->d.out, g, V, f, x_scale, plan->inv_y, y_dev, s) != hipSuccess)
+        (plan->quad16 ? sfc::launch_quad16(plan->d.out, g, V, f, x_scale, plan->inv_y, y_dev, s)
+                      : sfc::launch_fused_quad(plan->d.out, g, V, f, x_scale, plan->inv_y, y_dev, s)) !=
+            hipSuccess)
       return SFC_EHIP;
     return SFC_OK;
   }

@@ -66,6 +66,15 @@ int quad_filter_count(const Geometry& g);
 hipError_t launch_fused_quad(int out, const Geometry& g, const void* V, const FilterViews& f,
                              float x_scale, float inv_y, void* y, hipStream_t s,
                              bool prepare = false);
+// the same for the SFC-4 forms with 16 filters per wave and four pairs per lane
+// (sfc_quad16.hip): U_single holds its filter operand, dequant_single its factors as
+// [group of 16 filters][position][lane quarter][4]
+bool quad16_supported(const Geometry& g);
+int quad16_filter_count(const Geometry& g);
+hipError_t launch_repack_filter16(const Geometry& g, int filters, const void* U, void* U16,
+                                  hipStream_t s);
+hipError_t launch_quad16(int out, const Geometry& g, const void* V, const FilterViews& f,
+                         float x_scale, float inv_y, void* y, hipStream_t s, bool prepare = false);
 // single-kernel path: whether it covers this geometry, the bytes of its filter operand,
 // the regrouping of the canonical U, the processing order (position -> canonical point)
 bool single_supported(const Geometry& g);
