@@ -31,7 +31,7 @@ FLAG_EXACT_WIDE = 1
 #: what alg="auto" resolves to for 3x3 filters in requantized mode, and the widest layer
 #: path="auto" runs in one kernel (mirrors of the library's rule, for tests and reports)
 AUTO_ALG_3X3 = "4x4_p46"
-SINGLE_MAX_CIN = 64
+SINGLE_MAX_CIN = 128
 STATIC_WORKSPACE_BYTES = 32 << 20  # SFC_STATIC_WORKSPACE_BYTES
 STAGE_INPUT, STAGE_PRODUCT, STAGE_OUTPUT, STAGE_ALL = 1, 2, 4, 7
 #: every symbol include/sfc.h declares

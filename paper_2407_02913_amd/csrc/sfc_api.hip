@@ -30,7 +30,7 @@ struct sfc_plan_s {
   bool filter_ready;
   int quad_filters;  // filters covered by the regrouped filter operand (0: none)
   int dq_filters;    // filters in the [filter][processing position] dequantization table (0: none)
-  bool quad16;       // fused path of the SFC-4 forms: 16 filters per wave, four pairs per lane
+  bool quad16;       // SFC-4 forms: 16 filters per wave, four pairs per lane (fused and single paths)
   float inv_y;  // 1 / output scale (SFC_OUT_I8_RELU), 0: not set
 };
 
@@ -199,8 +199,9 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   p->off_dq_single = off;
   p->off_U_single = off;
   p->quad_filters = 0;
-  if (d.path == SFC_PATH_SINGLE) p->quad_filters = (g.Cout + 63) / 64 * 64;
-  p->quad16 = d.path == SFC_PATH_FUSED && sfc::quad16_supported(g);
+  p->quad16 = (d.path == SFC_PATH_FUSED && sfc::quad16_supported(g)) ||
+              (d.path == SFC_PATH_SINGLE && sfc::single16_supported(g));
+  if (d.path == SFC_PATH_SINGLE) p->quad_filters = p->quad16 ? g.Kp : (g.Cout + 63) / 64 * 64;
   if (d.path == SFC_PATH_FUSED)
     p->quad_filters = p->quad16 ? sfc::quad16_filter_count(g) : sfc::quad_filter_count(g);
   // the staged output transform reads the same [filter][position] table as the fused kernels
@@ -408,8 +409,11 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
   const bool fused = plan->d.path == SFC_PATH_FUSED;
   if (plan->d.path == SFC_PATH_SINGLE) {
     if (stage_mask != SFC_STAGE_ALL) return SFC_EINVAL;  // one kernel: no stage runs alone
-    if (sfc::launch_single_conv(plan->d.out, plan->g, x_dev, views(plan, plan->filter_dev), x_scale,
-                                plan->inv_y, y_dev, static_cast<hipStream_t>(stream)) != hipSuccess)
+    const FilterViews f = views(plan, plan->filter_dev);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if ((plan->quad16 ? sfc::launch_single16(plan->d.out, plan->g, x_dev, f, x_scale, plan->inv_y, y_dev, s)
+                      : sfc::launch_single_conv(plan->d.out, plan->g, x_dev, f, x_scale, plan->inv_y,
+                                                y_dev, s)) != hipSuccess)
       return SFC_EHIP;
     return SFC_OK;
   }

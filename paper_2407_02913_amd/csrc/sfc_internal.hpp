@@ -75,6 +75,11 @@ hipError_t launch_repack_filter16(const Geometry& g, int filters, const void* U,
                                   hipStream_t s);
 hipError_t launch_quad16(int out, const Geometry& g, const void* V, const FilterViews& f,
                          float x_scale, float inv_y, void* y, hipStream_t s, bool prepare = false);
+// single-kernel path of the SFC-4 forms, up to 128 input channels (sfc_single16.hip), on the
+// same filter operand and factor table as launch_quad16
+bool single16_supported(const Geometry& g);
+hipError_t launch_single16(int out, const Geometry& g, const int8_t* x, const FilterViews& f,
+                           float x_scale, float inv_y, void* y, hipStream_t s, bool prepare = false);
 // single-kernel path: whether it covers this geometry, the bytes of its filter operand,
 // the regrouping of the canonical U, the processing order (position -> canonical point)
 bool single_supported(const Geometry& g);

@@ -458,17 +458,51 @@ def test_single_kernel_path_matches_oracle(binding, shape, alg):
     assert rel_err(y, y_ref) <= F32_TOL
 
 
-def test_single_kernel_path_needs_at_most_64_input_channels(binding):
+SINGLE_WIDE_SHAPES = [  # two 64-channel chunks in one kernel (the SFC-4 forms)
+    (3, 70, 40, 9, 20),
+    (2, 128, 136, 11, 7),   # nine groups of 16 filters: two workgroups along Cout, odd W
+    (1, 100, 24, 28, 28),   # rectangles of two strips
+    (2, 128, 16, 14, 14),   # whole-image staging
+    (5, 65, 8, 7, 7),
+    (1, 96, 130, 56, 56),   # one strip per workgroup
+    (2, 127, 5, 6, 61),
+]
+
+
+@pytest.mark.parametrize("alg", ["4x4_p46", "4x4_p49"])
+@pytest.mark.parametrize("shape", SINGLE_WIDE_SHAPES)
+def test_single_kernel_path_with_two_channel_chunks(binding, shape, alg):
+    x, w, xs, ws = uniform_case(shape, 750 + len(alg) + sum(shape))
+    print("case single wide", shape, alg, flush=True)
+    xc, _, _, _ = uniform_case(shape, 850 + sum(shape))
+    sx = oracle.calibrate_act_scales(xc // 2, alg)
+    sw = oracle.calibrate_filter_scales(w, alg)
+    y_ref, taps_ref = oracle.conv_requant(x, w, sx, sw, xs, ws, alg, return_taps=True)
+    y, taps = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path="single", sx=sx, sw=sw,
+                             return_taps=True)
+    assert np.array_equal(taps["U"].astype(np.int64), taps_ref["U"])
+    assert rel_err(y, y_ref) <= F32_TOL
+    y_scale = float(np.float32(max(y_ref.max(), 1e-6) / 127.0 * 0.8))
+    y8 = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path="single", out="i8", sx=sx, sw=sw,
+                        y_scale=y_scale)
+    assert check_i8_against_oracle(y8, y_ref, y_scale) < 1e-3
+
+
+def test_single_kernel_path_channel_limits(binding):
     with pytest.raises(binding.SfcError) as e:
-        binding.Plan(1, 65, 16, 8, 8, path="single")
+        binding.Plan(1, 65, 16, 8, 8, path="single")  # 6x6 tiles: one chunk of 64 channels
+    assert e.value.code == 2
+    with pytest.raises(binding.SfcError) as e:
+        binding.Plan(1, 129, 16, 8, 8, alg="4x4_p46", path="single")  # SFC-4: two chunks
     assert e.value.code == 2
 
 
-@pytest.mark.parametrize("alg", ["6x6_p88", "7x7_p132", "4x4_p46", "4x4_p49"])
-def test_full_size_single_kernel_against_oracle(binding, alg):
-    """resnet56 in the launch configuration bench.py times, every output element."""
-    shape = synth.LAYERS["resnet56"]
-    print("case full single", alg, flush=True)
+@pytest.mark.parametrize("name,alg", [("resnet56", a) for a in ("6x6_p88", "7x7_p132", "4x4_p46", "4x4_p49")] +
+                         [("resnet28", "4x4_p46"), ("resnet28", "4x4_p49")])
+def test_full_size_single_kernel_against_oracle(binding, name, alg):
+    """resnet56 and resnet28 in the launch configuration bench.py times, every output element."""
+    shape = synth.LAYERS[name]
+    print("case full single", name, alg, flush=True)
     d = synth.make_layer(shape)
     sx = oracle.calibrate_act_scales(d["x_calib"], alg)
     sw = oracle.calibrate_filter_scales(d["w"], alg)
