@@ -183,9 +183,11 @@ def bench_layer(args, name, torch, timer):
     sets = [(x_host.cuda(), binding.device_buffer(layer.workspace_bytes), layer.new_output())
             for _ in range(nsets)]
 
+    cur = torch.cuda.current_stream()  # looked up once: the call is slow next to a launch
+
     def step(i, stream=None, mask=binding.STAGE_ALL):
         xd, ws, y = sets[i % nsets]
-        layer.run(xd, y, ws, stream=stream, stages=mask)
+        layer.run(xd, y, ws, stream=stream or cur, stages=mask)
 
     ms, repeats = timer.median(step, args.steps, args.warmup)
     rows = kernel_rows(timer, layer, name, lambda i, mask: step(i, None, mask), max(50, args.steps))
@@ -233,7 +235,10 @@ def bench_stack(args, torch, timer):
                        torch.empty((shapes[0].N, c, h, h), dtype=torch.int8, device="cuda")]
         sets.append((bufs, binding.device_buffer(ws_bytes)))
 
+    cur = torch.cuda.current_stream()  # looked up once: the call is slow next to a launch
+
     def step(i, stream=None):
+        stream = stream or cur
         bufs, ws = sets[i % nsets]
         done = {}
         for l in lay:
@@ -252,7 +257,7 @@ def bench_stack(args, torch, timer):
 
         def run_stage(i, mask, l0=l0, c=c):
             bufs, ws = sets[i % nsets]
-            l0.run(bufs[c][0], bufs[c][1], ws, stages=mask)
+            l0.run(bufs[c][0], bufs[c][1], ws, stream=cur, stages=mask)
 
         for i in range(nsets):  # V (and M) of this layer in every set's workspace
             run_stage(i, binding.STAGE_ALL)

@@ -10,6 +10,7 @@
 
 #include "../../include/sfc.h"
 #include "sfc_internal.hpp"
+#include "sfc_mfma_input.hpp"
 
 using sfc::FilterViews;
 using sfc::Geometry;
@@ -19,7 +20,7 @@ struct sfc_plan_s {
   Geometry g;
   int esz;  // bytes per transform-domain operand: 2 exact, 1 requantized
   // filter buffer layout (byte offsets)
-  size_t off_U, off_dequant, off_inv_sw, off_inv_sx, off_wscale, off_dq_single, off_U_single,
+  size_t off_U, off_dequant, off_inv_sw, off_inv_sx, off_wscale, off_input_tab, off_dq_single, off_U_single,
       filter_bytes;
   // workspace layout
   size_t off_V, off_M, workspace_bytes;
@@ -72,6 +73,7 @@ FilterViews views(const sfc_plan_s* p, void* filter_dev) {
   f.inv_sw = reinterpret_cast<float*>(b + p->off_inv_sw);
   f.inv_sx = reinterpret_cast<float*>(b + p->off_inv_sx);
   f.wscale = reinterpret_cast<float*>(b + p->off_wscale);
+  f.input_tab = reinterpret_cast<unsigned char*>(b + p->off_input_tab);
   f.dequant_single = reinterpret_cast<float*>(b + p->off_dq_single);
   f.U_single = b + p->off_U_single;
   return f;
@@ -196,6 +198,9 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   p->off_inv_sw = off;   off = align_up(off + PK * sizeof(float), 256);
   p->off_inv_sx = off;   off = align_up(off + g.P * sizeof(float), 256);
   p->off_wscale = off;   off = align_up(off + g.Kp * sizeof(float), 256);
+  p->off_input_tab = off;
+  if (d.mode == SFC_MODE_REQUANT_I8 && (d.alg == SFC_ALG_4X4_P46 || d.alg == SFC_ALG_4X4_P49))
+    off = align_up(off + sfc::kInputTabBytes, 256);
   p->off_dq_single = off;
   p->off_U_single = off;
   p->quad_filters = 0;
@@ -358,6 +363,8 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
       inv_sw[(size_t)p * g.Kp + k] = inv;
     }
   }
+  if (plan->off_dq_single > plan->off_input_tab)
+    sfc::build_input_table(plan->d.alg, inv_sx, reinterpret_cast<unsigned char*>(table(plan->off_input_tab)));
   if (plan->dq_filters > 0) {
     const int pp = (g.P + 3) / 4 * 4;
     std::vector<int> pt(pp, -1);
@@ -425,7 +432,7 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
   char* ws = static_cast<char*>(workspace_dev);
   void* V = ws + plan->off_V;
   if (stage_mask & SFC_STAGE_INPUT) {
-    if (sfc::launch_input_transform(plan->d.mode, g, x_dev, V, f.inv_sx, s) !=
+    if (sfc::launch_input_transform(plan->d.mode, g, x_dev, V, f.inv_sx, f.input_tab, s) !=
         hipSuccess)
       return SFC_EHIP;
   }

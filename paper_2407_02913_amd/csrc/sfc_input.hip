@@ -10,6 +10,7 @@
 //     (point, tile).
 #include "sfc_device.hpp"
 #include "sfc_internal.hpp"
+#include "sfc_mfma_input.hpp"
 #include "sfc_points.hpp"
 #include "sfc_tile_input.hpp"
 
@@ -26,9 +27,12 @@ struct InputPlan {
 template <int ALG, int NW, int VS>
 __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
     const int8_t* __restrict__ x, int8_t* __restrict__ V, const float* __restrict__ inv_sx,
-    Geometry g, InputPlan ip) {
+    const unsigned char* __restrict__ intab, Geometry g, InputPlan ip) {
   extern __shared__ __align__(16) unsigned char lds[];
   constexpr int P = AlgTraits<ALG>::P;
+  // LDS bytes from one position's V to the next: the SFC-4 forms write 16 positions per
+  // instruction (sfc_mfma_input.hpp) and need them in different banks
+  constexpr int VSP = AlgTraits<ALG>::kFamily == 4 ? VS + 16 : VS;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const TileRect& tr = ip.tr;
@@ -52,7 +56,50 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
 
   stage_input<ALG, NW>(x, lds, g, tr, bx, c0, wave, lane);
   __syncthreads();
-  transform_tiles<ALG, NW, 1, VS>(lds, inv_sx, g.qmax, g, tr, bx, wave, lane);
+  if constexpr (AlgTraits<ALG>::kFamily == 4) {
+    // on the matrix cores: wave = tile, four groups of 16 channels; rounded and packed in
+    // registers before V is written over the staged rows
+    using Tr = AlgTraits<ALG>;
+    constexpr int NPB = MfmaInput<ALG>::NPB, PP = Order<ALG>::PP;
+    MfmaInput<ALG> mi;
+    mi.load(intab, lane);
+    unsigned packed[4][NPB];
+    const int tile = wave;
+    if (tile < tr.ntiles) {
+      if (tr.whole) {
+        const int tpi = g.th * g.tw;
+        const int slot = tile / tpi, rem = tile - slot * tpi;
+        const int ti = rem / g.tw, tj = rem - ti * g.tw;
+#pragma unroll
+        for (int cg = 0; cg < 4; ++cg)
+          mi.transform(MfmaInput<ALG>::operand_plane(lds + slot * 64 * tr.cs, tr.cs, 16 * cg,
+                                                     Tr::M * ti - Tr::PAD, Tr::M * tj - Tr::PAD, g.H,
+                                                     g.W, lane),
+                       g.qmax, packed[cg]);
+      } else {
+        const int tj0 = (bx % tr.chunks) * tr.tlw;
+        const int halo = Tr::M * tj0 - Tr::PAD - ((Tr::M * tj0) & ~3) + 4;
+        const int s = tile / tr.tlw, tjl = tile - s * tr.tlw;
+#pragma unroll
+        for (int cg = 0; cg < 4; ++cg)
+          mi.transform(MfmaInput<ALG>::template operand_rect<stage_channel_bytes(Tr::NI)>(
+                           lds, s, 16 * cg, halo + Tr::M * tjl, lane),
+                       g.qmax, packed[cg]);
+      }
+    }
+    __syncthreads();
+    if (tile < tr.ntiles) {
+#pragma unroll
+      for (int cg = 0; cg < 4; ++cg)
+#pragma unroll
+        for (int m = 0; m < NPB; ++m) {
+          const int pos = 16 * m + (lane & 15);
+          if (pos < PP) *(unsigned*)(lds + pos * VSP + tile * 64 + 16 * cg + 4 * (lane >> 4)) = packed[cg][m];
+        }
+    }
+  } else {
+    transform_tiles<ALG, NW, 1, VS>(lds, inv_sx, g.qmax, g, tr, bx, wave, lane);
+  }
   __syncthreads();
 
   // ---- copy out: wave w takes positions w, w+NW, ...; lane = (tile, 16-byte quarter) ---
@@ -62,7 +109,7 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
   const int t = row_tab[VS == 512 ? (lane >> 2) & 7 : lane >> 2];
   const unsigned lane_off = (unsigned)t * (unsigned)g.Cp + (unsigned)(c0 + 16 * (lane & 3));
   if (t >= 0) {
-    copy_out_points<ALG, NW, VS>(lds, vres, lane_off, vplane, wave, lane);
+    copy_out_points<ALG, NW, VS, VSP>(lds, vres, lane_off, vplane, wave, lane);
   }
 }
 
@@ -73,7 +120,8 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
 static int input_waves(int alg) { return alg < 2 ? 16 : 8; }
 
 static bool make_input_plan(const Geometry& g, InputPlan* ip) {
-  const unsigned vbytes = (unsigned)g.P * (input_waves(g.alg) == 8 ? 512u : 1024u);
+  // (16 more bytes per position for the SFC-4 forms, whose points are padded to 48 / 52)
+  const unsigned vbytes = (unsigned)((g.P + 3) / 4 * 4) * ((input_waves(g.alg) == 8 ? 512u : 1024u) + 16u);
   const unsigned lds_max = 160u * 1024u;
   if (vbytes + 16u + 64u > lds_max) return false;
   if (!make_tile_rect(g, lds_max - 16u - 64u, &ip->tr, input_waves(g.alg), true)) return false;
@@ -87,30 +135,32 @@ static bool make_input_plan(const Geometry& g, InputPlan* ip) {
 
 template <int ALG>
 static hipError_t launch_input_i8_alg(const Geometry& g, const InputPlan& ip, const int8_t* x,
-                                      void* V, const float* inv_sx, hipStream_t s, bool prepare) {
+                                      void* V, const float* inv_sx, const unsigned char* intab,
+                                      hipStream_t s, bool prepare) {
   constexpr int NW = ALG < 2 ? 16 : 8;
   auto kernel = input_transform_i8_kernel<ALG, NW, NW == 8 ? 512 : 1024>;
   if (prepare) return raise_lds_limit(reinterpret_cast<const void*>(kernel));
   const dim3 grid(tile_rect_groups(g, ip.tr) * (unsigned)(g.Cp / 64));
-  hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), ip.lds_bytes, s, x, (int8_t*)V, inv_sx, g, ip);
+  hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), ip.lds_bytes, s, x, (int8_t*)V, inv_sx, intab, g, ip);
   return hipGetLastError();
 }
 
 // Returns hipErrorNotSupported when the geometry is outside this kernel's limits;
 // the caller then uses the generic kernel.
 hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V,
-                                     const float* inv_sx, hipStream_t s, bool prepare) {
+                                     const float* inv_sx, const unsigned char* intab,
+                                     hipStream_t s, bool prepare) {
   InputPlan ip;
   if (!make_input_plan(g, &ip)) return hipErrorNotSupported;
   switch (g.alg) {
-    case 0: return launch_input_i8_alg<0>(g, ip, x, V, inv_sx, s, prepare);
-    case 1: return launch_input_i8_alg<1>(g, ip, x, V, inv_sx, s, prepare);
-    case 2: return launch_input_i8_alg<2>(g, ip, x, V, inv_sx, s, prepare);
-    case 3: return launch_input_i8_alg<3>(g, ip, x, V, inv_sx, s, prepare);
-    case 4: return launch_input_i8_alg<4>(g, ip, x, V, inv_sx, s, prepare);
-    case 5: return launch_input_i8_alg<5>(g, ip, x, V, inv_sx, s, prepare);
-    case 6: return launch_input_i8_alg<6>(g, ip, x, V, inv_sx, s, prepare);
-    case 7: return launch_input_i8_alg<7>(g, ip, x, V, inv_sx, s, prepare);
+    case 0: return launch_input_i8_alg<0>(g, ip, x, V, inv_sx, intab, s, prepare);
+    case 1: return launch_input_i8_alg<1>(g, ip, x, V, inv_sx, intab, s, prepare);
+    case 2: return launch_input_i8_alg<2>(g, ip, x, V, inv_sx, intab, s, prepare);
+    case 3: return launch_input_i8_alg<3>(g, ip, x, V, inv_sx, intab, s, prepare);
+    case 4: return launch_input_i8_alg<4>(g, ip, x, V, inv_sx, intab, s, prepare);
+    case 5: return launch_input_i8_alg<5>(g, ip, x, V, inv_sx, intab, s, prepare);
+    case 6: return launch_input_i8_alg<6>(g, ip, x, V, inv_sx, intab, s, prepare);
+    case 7: return launch_input_i8_alg<7>(g, ip, x, V, inv_sx, intab, s, prepare);
   }
   return hipErrorInvalidValue;
 }

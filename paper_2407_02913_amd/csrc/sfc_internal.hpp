@@ -34,18 +34,24 @@ struct FilterViews {
   // every requantized path: the dequantization factors as [filter][processing position],
   // positions padded to a multiple of four, rows of filters beyond Cout zero
   float* dequant_single;
+  // SFC-4 forms on the fused and single paths: the table of the input transform on the
+  // matrix cores (sfc_mfma_input.hpp)
+  unsigned char* input_tab;
 };
 
 hipError_t launch_filter_transform(int mode, const Geometry& g, const int8_t* w,
                                    const FilterViews& f, hipStream_t s);
+// input_tab: FilterViews::input_tab (read by the SFC-4 forms in requantized mode)
 hipError_t launch_input_transform(int mode, const Geometry& g, const int8_t* x, void* V,
-                                  const float* inv_sx, hipStream_t s);
+                                  const float* inv_sx, const unsigned char* input_tab,
+                                  hipStream_t s);
 // requantized-mode kernel; hipErrorNotSupported when the geometry is outside its limits
 // Launchers with a `prepare` argument: when true nothing is launched; the call raises, on the
 // current device, the dynamic-LDS limit of the kernel instantiation it would launch (the
 // data pointers are not looked at) and returns what the runtime said.
 hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V,
-                                     const float* inv_sx, hipStream_t s, bool prepare = false);
+                                     const float* inv_sx, const unsigned char* input_tab,
+                                     hipStream_t s, bool prepare = false);
 hipError_t launch_product(int mode, const Geometry& g, const void* V, const void* U, int32_t* M,
                           hipStream_t s);
 // requantized mode (sfc_gemm.hip): the products as P batched int8 GEMMs; the output

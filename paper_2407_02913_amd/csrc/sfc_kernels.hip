@@ -398,9 +398,10 @@ static hipError_t launch_input_alg(const Geometry& g, const int8_t* x, void* V, 
 }
 
 hipError_t launch_input_transform(int mode, const Geometry& g, const int8_t* x, void* V,
-                                  const float* inv_sx, hipStream_t s) {
+                                  const float* inv_sx, const unsigned char* input_tab,
+                                  hipStream_t s) {
   if (mode == 1) {
-    const hipError_t e = launch_input_transform_i8(g, x, V, inv_sx, s);
+    const hipError_t e = launch_input_transform_i8(g, x, V, inv_sx, input_tab, s);
     if (e != hipErrorNotSupported) return e;
     return launch_input_alg<1>(g, x, V, inv_sx, nullptr, s);
   }
@@ -414,7 +415,7 @@ hipError_t prepare_kernels(int path, int out, const Geometry& g) {
                ? launch_single16(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true)
                : launch_single_conv(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true);
   // the generic input kernel (geometries the int8 one does not take) stays under 64 KB
-  hipError_t e = launch_input_transform_i8(g, nullptr, nullptr, nullptr, nullptr, true);
+  hipError_t e = launch_input_transform_i8(g, nullptr, nullptr, nullptr, nullptr, nullptr, true);
   if (e != hipSuccess && e != hipErrorNotSupported) return e;
   if (path == 1)
     return quad16_supported(g)

@@ -1,0 +1,117 @@
+// Input-tile transform of the SFC-4(4x4,3x3) forms on the matrix cores (gfx950).
+//
+// V = B^T x B of a 6 x 6 patch is 46 / 49 sums of patch samples with coefficients 0, +1, -1
+// (the four-point symbolic DFT with its correction rows, Appendix A).  On the vector ALU that
+// is 110 additions per (tile, channel) plus a conversion per point; here the same sums are
+// taken by int8 MFMA 16x16x64 instructions: operand A holds the patches of 16 channels (row =
+// channel; the 64 k-bytes are the patch rows of 8 bytes each, k = 8 i + j, of which j < 6 and
+// i < 6 carry samples), operand B the coefficients of 16 multiplication points (column = point
+// in processing order).  The coefficient table is produced on the host by running the add
+// networks of sfc_points.hpp on unit patches, so both forms compute the same integers.  Lane l
+// ends with the sums of channels 4(l/16) .. 4(l/16)+3 for point l%16 of the block: after
+// rounding, four bytes that go to V as one dword.
+#pragma once
+#include "sfc_device.hpp"
+#include "sfc_points.hpp"
+
+namespace sfc {
+
+constexpr int kInputTabRows = 64;  // positions padded to whole blocks of 16
+// the table behind the filter operand: float inv_pos[64] (1 / s_Tx by processing position, 0
+// for positions without a point), then int8 coeff[64][64] ([position][k])
+constexpr unsigned kInputTabBytes = kInputTabRows * 4 + kInputTabRows * 64;
+
+// Host: fills the table for one algorithm from the add networks (inv_sx by canonical point).
+void build_input_table(int alg, const float* inv_sx, unsigned char* tab);
+
+#ifdef __HIPCC__
+
+template <int ALG>
+struct MfmaInput {
+  static constexpr int PP = Order<ALG>::PP;
+  static constexpr int NPB = (PP + 15) / 16;  // blocks of 16 points
+  v4i coeff[NPB];
+  float inv[NPB];
+
+  __device__ __forceinline__ void load(const unsigned char* __restrict__ tab, int lane) {
+    const float* inv_pos = (const float*)tab;
+    const unsigned char* c = tab + kInputTabRows * 4;
+#pragma unroll
+    for (int m = 0; m < NPB; ++m) {
+      const int pos = 16 * m + (lane & 15);
+      inv[m] = inv_pos[pos];
+      coeff[m] = *(const v4i*)(c + pos * 64 + 16 * (lane >> 4));
+    }
+  }
+
+  // Operand A from the staged rows of a tile rectangle (sfc_tile_input.hpp: 64 bytes per
+  // image row, six rows per channel, CS bytes per channel): lane = (channel l%16 of the group
+  // of 16 starting at ch0, patch rows 2(l/16), 2(l/16)+1); o = LDS byte of the tile's first
+  // patch column.  Lanes 48..63 (k >= 48, coefficients zero) repeat rows 4, 5.
+  template <int CS>
+  static __device__ __forceinline__ v4i operand_rect(const unsigned char* in, int s, int ch0, int o,
+                                                     int lane) {
+    const int ch = ch0 + (lane & 15), rp = min(lane >> 4, 2);
+    const unsigned* src =
+        (const unsigned*)(in + (unsigned)(s * 64 + ch) * CS + (2 * rp) * 64 + (o & ~3));
+    const unsigned sh = (unsigned)(o & 3);
+    v4i a;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const unsigned d0 = src[r * 16], d1 = src[r * 16 + 1], d2 = src[r * 16 + 2];
+      a[2 * r] = (int)__builtin_amdgcn_alignbyte(d1, d0, sh);
+      a[2 * r + 1] = (int)__builtin_amdgcn_alignbyte(d2, d1, sh);
+    }
+    return a;
+  }
+
+  // Operand A from whole channel planes (small feature maps): sample (r0 + i, q0 + j) of the
+  // plane of channel ch0 + l%16, zero outside the image.
+  static __device__ __forceinline__ v4i operand_plane(const unsigned char* planes, int cs, int ch0,
+                                                      int r0, int q0, int H, int W, int lane) {
+    const unsigned char* plane = planes + (ch0 + (lane & 15)) * cs;
+    const int rp = min(lane >> 4, 2);
+    v4i a;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int h = r0 + 2 * rp + r;
+      const bool rok = (unsigned)h < (unsigned)H;
+      unsigned w[2] = {0u, 0u};
+#pragma unroll
+      for (int j = 0; j < 6; ++j) {
+        const int q = q0 + j;
+        const bool ok = rok && (unsigned)q < (unsigned)W;
+        const unsigned v = ok ? (unsigned)plane[h * W + q] : 0u;
+        w[j >> 2] |= v << (8 * (j & 3));
+      }
+      a[2 * r] = (int)w[0];
+      a[2 * r + 1] = (int)w[1];
+    }
+    return a;
+  }
+
+  // The sums of the lane's four channels for its point of every block, rounded to int8
+  // (clamp(round-half-even(v / s_Tx), +-qmax)) and packed: byte i = channel 4(l/16) + i.
+  __device__ __forceinline__ void transform(v4i a, float qmax, unsigned (&packed)[NPB]) const {
+    constexpr float kMagic = 12582912.0f;
+#pragma unroll
+    for (int m = 0; m < NPB; ++m) {
+      const v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, coeff[m], v4i{0, 0, 0, 0}, 0, 0, 0);
+      unsigned q[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float t = __fmaf_rn((float)d[i], inv[m], kMagic);
+        t = __builtin_amdgcn_fmed3f(t, kMagic - qmax, kMagic + qmax);
+        q[i] = __float_as_uint(t);
+      }
+      // low bytes of q[0..3] -> one dword
+      const unsigned lo = __builtin_amdgcn_perm(q[1], q[0], 0x0c0c0400u);
+      const unsigned hi = __builtin_amdgcn_perm(q[3], q[2], 0x04000c0cu);
+      packed[m] = lo | hi;
+    }
+  }
+};
+
+#endif  // __HIPCC__
+
+}  // namespace sfc

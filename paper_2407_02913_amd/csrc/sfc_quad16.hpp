@@ -87,14 +87,14 @@ constexpr unsigned quad16_lds_layout(int what) {
 // Software pipeline: call j issues the matrix instructions of position j + 1 and then converts
 // the sums of position j, so the matrix pipe works under the vector arithmetic of the output
 // transform.  Leaves z[b][o1] of the lane's four pairs (f4 element i: filter quad i).
-template <int ALG, int KC, int VB, typename Sync>
+template <int ALG, int KC, int VB, int PS = KC * 1024, typename Sync>
 __device__ __forceinline__ void quad16_products(const unsigned char* vbuf, int lane,
                                                 __amdgpu_buffer_rsrc_t ures, unsigned a_wave,
                                                 __amdgpu_buffer_rsrc_t dres, unsigned d_wave,
                                                 Sync&& sync,
                                                 f4 (&z)[AlgTraits<ALG>::NC][AlgTraits<ALG>::M]) {
   constexpr int PP = Order<ALG>::PP;
-  constexpr int GROUP_BYTES = 4 * 16 * 64 * KC;
+  constexpr int GROUP_BYTES = 4 * PS;      // PS: bytes from one position's V to the next
   constexpr int STEPS = PP * KC;           // filter-operand blocks of the wave
   constexpr int RA = 8;                    // ... in flight
   constexpr int RD = 4;                    // factor loads in flight (positions)
@@ -121,14 +121,14 @@ __device__ __forceinline__ void quad16_products(const unsigned char* vbuf, int l
   constexpr int NB = PREB ? KC : 1;
   v4i breg[NB];
   auto read_b = [&](int jj) {
-    const unsigned char* bsrc = blane + ((jj >> 2) % VB) * GROUP_BYTES + (jj & 3) * KC * 1024;
+    const unsigned char* bsrc = blane + ((jj >> 2) % VB) * GROUP_BYTES + (jj & 3) * PS;
 #pragma unroll
     for (int kc = 0; kc < NB; ++kc) breg[kc] = *(const v4i*)(bsrc + kc * 1024);
   };
   // the sums of position jj: KC chained matrix instructions
   auto products = [&](int jj) -> v4i {
     v4i acc = {0, 0, 0, 0};
-    const unsigned char* bsrc = blane + ((jj >> 2) % VB) * GROUP_BYTES + (jj & 3) * KC * 1024;
+    const unsigned char* bsrc = blane + ((jj >> 2) % VB) * GROUP_BYTES + (jj & 3) * PS;
 #pragma unroll
     for (int kc = 0; kc < KC; ++kc) {
       const int s = jj * KC + kc;

@@ -18,8 +18,11 @@
 //  4. Store: the wave's 16 x 16 x 16 outputs go through its LDS block (over V, once every
 //     wave is done with it) and out as whole tile rows, four image rows of 16 tiles per filter
 //     and instruction.
+#include <cstring>
+
 #include "sfc_device.hpp"
 #include "sfc_internal.hpp"
+#include "sfc_mfma_input.hpp"
 #include "sfc_points.hpp"
 #include "sfc_quad16.hpp"
 #include "sfc_tile_input.hpp"
@@ -37,16 +40,16 @@ struct Single16Plan {
 template <int ALG, int KC, int OUT, int EV, int NW>
 __global__ __launch_bounds__(NW * 64, 2) void single16_kernel(
     const int8_t* __restrict__ x, const int8_t* __restrict__ U16, const float* __restrict__ dq16,
-    const float* __restrict__ inv_sx, float x_scale, float inv_y, void* __restrict__ y, Geometry g,
-    Single16Plan sp) {
+    const unsigned char* __restrict__ intab, float x_scale, float inv_y, void* __restrict__ y,
+    Geometry g, Single16Plan sp) {
   using Tr = AlgTraits<ALG>;
   constexpr int M = Tr::M, NI = Tr::NI, NC = Tr::NC, PAD = Tr::PAD;
   constexpr int PP = Order<ALG>::PP, PG = PP / 4;
   constexpr int SPW = 16 / NW, NITEM = SPW * KC;
-  constexpr int WP = kStageRow, CS = stage_channel_bytes(NI);
-  constexpr int ND = (NI + 6) / 4;
-  constexpr int VS = KC * 1024;  // bytes of V per position
-  constexpr Order<ALG> order{};
+  constexpr int CS = stage_channel_bytes(NI);
+  // bytes of V per position: KC operand blocks of 1 KiB and 16 bytes that put the 16 positions
+  // a wave writes at once into different LDS banks
+  constexpr int VS = KC * 1024 + 16;
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -65,78 +68,60 @@ __global__ __launch_bounds__(NW * 64, 2) void single16_kernel(
     stage_input<ALG, NW>(x, lds + kc * sp.chunk_in, g, tr, bx, 64 * kc, wave, lane);
   __syncthreads();
 
-  // ---- 2. input transform --------------------------------------------------------------
+  // ---- 2. input transform (sfc_mfma_input.hpp) --------------------------------------------
+  // An item is (tile, 64-channel chunk, group of 16 channels): the wave of tile t takes the
+  // items of tiles t, t + NW, ...  All items are transformed, rounded and packed in registers
+  // before the first byte of V is written, because V lies over the staged rows.
   {
+    MfmaInput<ALG> mi;
+    mi.load(intab, lane);
+    constexpr int NPB = MfmaInput<ALG>::NPB;
     const int tj0 = tr.whole ? 0 : (bx % tr.chunks) * tr.tlw;
     const int colbase = (M * tj0) & ~3;
     const int halo = M * tj0 - PAD - colbase + 4;  // LDS byte of the rectangle's first patch column
-    int half[NITEM][NI][NC];  // rows transformed: half[.][i][b]
+    unsigned packed[NITEM * 4][NPB];
 #pragma unroll
     for (int it = 0; it < NITEM; ++it) {
-      const int tile = wave + NW * (it / KC), kc = it % KC, c = lane;
+      const int tile = wave + NW * (it / KC), kc = it % KC;
       const unsigned char* in = lds + kc * sp.chunk_in;
       if (tile < tr.ntiles) {
         if (tr.whole) {
-          // whole images: sign-extending byte reads of the plane, zeros outside the image
           const int tpi = g.th * g.tw;
           const int slot = tile / tpi, rem = tile - slot * tpi;
           const int ti = rem / g.tw, tj = rem - ti * g.tw;
-          const signed char* plane = (const signed char*)in + (slot * 64 + c) * tr.cs;
-          const int r0 = M * ti - PAD, q0 = M * tj - PAD;
 #pragma unroll
-          for (int i = 0; i < NI; ++i) {
-            int row[NI];
-            const bool rok = (unsigned)(r0 + i) < (unsigned)g.H;
-#pragma unroll
-            for (int j = 0; j < NI; ++j) {
-              row[j] = 0;
-              if (rok && (unsigned)(q0 + j) < (unsigned)g.W) row[j] = plane[(r0 + i) * g.W + q0 + j];
-            }
-            fwd_input<NI, NC>(row, half[it][i]);
+          for (int cg = 0; cg < 4; ++cg) {
+            const v4i a = MfmaInput<ALG>::operand_plane(in + slot * 64 * tr.cs, tr.cs, 16 * cg, M * ti - PAD,
+                                                        M * tj - PAD, g.H, g.W, lane);
+            mi.transform(a, g.qmax, packed[4 * it + cg]);
           }
         } else {
           const int s = tile / tr.tlw, tjl = tile - s * tr.tlw;
-          const int o = halo + M * tjl;
-          const unsigned* src = (const unsigned*)(in + (unsigned)(s * 64 + c) * CS + (o & ~3));
-          const unsigned sh = (unsigned)(o & 3);
 #pragma unroll
-          for (int i = 0; i < NI; ++i) {
-            unsigned d[ND], w[ND];
-#pragma unroll
-            for (int k = 0; k < ND; ++k) d[k] = src[i * (WP / 4) + k];
-#pragma unroll
-            for (int k = 0; k + 1 < ND; ++k) w[k] = __builtin_amdgcn_alignbyte(d[k + 1], d[k], sh);
-            w[ND - 1] = d[ND - 1] >> (8 * sh);
-            int row[NI];
-#pragma unroll
-            for (int j = 0; j < NI; ++j) row[j] = (int)(signed char)(w[j / 4] >> (8 * (j % 4)));
-            fwd_input<NI, NC>(row, half[it][i]);
+          for (int cg = 0; cg < 4; ++cg) {
+            const v4i a = MfmaInput<ALG>::template operand_rect<CS>(in, s, 16 * cg, halo + M * tjl, lane);
+            mi.transform(a, g.qmax, packed[4 * it + cg]);
           }
         }
       }
     }
-    __syncthreads();  // every patch is in registers: the staging area becomes V
+    __syncthreads();  // every patch has been read: the staging area becomes V
 #pragma unroll
     for (int it = 0; it < NITEM; ++it) {
-      const int tile = wave + NW * (it / KC), kc = it % KC, c = lane;
-      unsigned char* outp = lds + kc * 1024 + tile * 64 + c;
-      if (tile < tr.ntiles) {
-        int comp[NC][NC];
-#pragma unroll
-        for (int b = 0; b < NC; ++b) {
-          int colv[NI], cc[NC];
-#pragma unroll
-          for (int i = 0; i < NI; ++i) colv[i] = half[it][i][b];
-          fwd_input<NI, NC>(colv, cc);
-#pragma unroll
-          for (int a = 0; a < NC; ++a) comp[a][b] = cc[a];
-        }
-        for_each_point<ALG>(comp, [&](int p, int v) {
-          outp[order.pos[p] * VS] = (unsigned char)quantize_byte(v, inv_sx[p], g.qmax);
-        });
-      }
+      const int tile = wave + NW * (it / KC), kc = it % KC;
       // (an empty tile slot keeps stale bytes: they only reach products of that slot, which
       // are never stored)
+      if (tile < tr.ntiles) {
+#pragma unroll
+        for (int cg = 0; cg < 4; ++cg)
+#pragma unroll
+          for (int m = 0; m < NPB; ++m) {
+            const int pos = 16 * m + (lane & 15);
+            if (pos < PP)
+              *(unsigned*)(lds + pos * VS + kc * 1024 + tile * 64 + 16 * cg + 4 * (lane >> 4)) =
+                  packed[4 * it + cg][m];
+          }
+      }
     }
   }
   __syncthreads();
@@ -153,10 +138,45 @@ __global__ __launch_bounds__(NW * 64, 2) void single16_kernel(
   // groups beyond the last one read zeros (offsets outside the operand) and store nothing
   const int fg = blockIdx.y * NW + wave;
   f4 z[NC][M];
-  quad16_products<ALG, KC, PG>(lds, lane, ures, (unsigned)fg * (unsigned)(PP * KC * 1024), dres,
+  quad16_products<ALG, KC, PG, VS>(lds, lane, ures, (unsigned)fg * (unsigned)(PP * KC * 1024), dres,
                                (unsigned)fg * (unsigned)(PP * 64), [](int) {}, z);
   __syncthreads();  // the staging blocks take the place of V
   quad16_store<ALG, OUT, EV>(z, stage, tile_tab, lane, fg * 4, x_scale, inv_y, yres, g);
+}
+
+// Coefficients of the input transform by processing position, from the add networks: the
+// image of every unit patch under fwd_input (rows, then columns) and for_each_point.
+template <int ALG>
+static void fill_input_table(const float* inv_sx, unsigned char* tab) {
+  using Tr = AlgTraits<ALG>;
+  constexpr int NI = Tr::NI, NC = Tr::NC;
+  constexpr Order<ALG> order{};
+  float* inv_pos = reinterpret_cast<float*>(tab);
+  signed char* coeff = reinterpret_cast<signed char*>(tab) + kInputTabRows * 4;
+  std::memset(tab, 0, kInputTabBytes);
+  for (int p = 0; p < Tr::P; ++p) inv_pos[order.pos[p]] = inv_sx[p];
+  for (int i = 0; i < NI; ++i)
+    for (int j = 0; j < NI; ++j) {
+      int half[NI][NC], comp[NC][NC];
+      for (int r = 0; r < NI; ++r) {
+        int row[NI] = {};
+        if (r == i) row[j] = 1;
+        fwd_input<NI, NC>(row, half[r]);
+      }
+      for (int b = 0; b < NC; ++b) {
+        int colv[NI], cc[NC];
+        for (int r = 0; r < NI; ++r) colv[r] = half[r][b];
+        fwd_input<NI, NC>(colv, cc);
+        for (int a = 0; a < NC; ++a) comp[a][b] = cc[a];
+      }
+      for_each_point<ALG>(comp, [&](int p, int v) { coeff[order.pos[p] * 64 + 8 * i + j] = (signed char)v; });
+    }
+}
+
+void build_input_table(int alg, const float* inv_sx, unsigned char* tab) {
+  if (alg == 4) fill_input_table<4>(inv_sx, tab);
+  else if (alg == 5) fill_input_table<5>(inv_sx, tab);
+  else std::memset(tab, 0, kInputTabBytes);
 }
 
 // waves per workgroup: one group of 16 filters each; with two channel chunks eight waves share
@@ -168,7 +188,7 @@ static bool make_single16_plan(const Geometry& g, int out, Single16Plan* sp) {
   if ((g.alg != 4 && g.alg != 5) || (g.Cp != 64 && g.Cp != 128)) return false;
   const int kc = g.Cp / 64, nw = single16_waves(g);
   const unsigned pp = (unsigned)((g.P + 3) / 4 * 4);
-  const unsigned vbytes = pp * (unsigned)kc * 1024u;
+  const unsigned vbytes = pp * ((unsigned)kc * 1024u + 16u);
   const unsigned sbytes = (unsigned)nw * (out == 2 ? 4096u : 16384u);
   const unsigned lds_max = 160u * 1024u - 256u;
   if (vbytes > lds_max || sbytes > lds_max) return false;
@@ -201,7 +221,7 @@ static hipError_t launch_single16_impl(const Geometry& g, const Single16Plan& sp
   if (prepare) return raise_lds_limit(reinterpret_cast<const void*>(kernel));
   const dim3 grid(tile_rect_groups(g, sp.tr), (unsigned)((sp.fgroups + NW - 1) / NW));
   hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), sp.lds_bytes, s, x, (const int8_t*)f.U_single,
-                     f.dequant_single, f.inv_sx, x_scale, inv_y, y, g, sp);
+                     f.dequant_single, f.input_tab, x_scale, inv_y, y, g, sp);
   return hipGetLastError();
 }
 

@@ -404,7 +404,8 @@ __device__ __forceinline__ void transform_tiles(unsigned char* lds, const float*
 // channels); lane_off is the lane's byte offset inside a point's plane of V.
 // VS = 512 (eight tiles per workgroup): a wave takes two positions at a time, lanes 0..31
 // the first, lanes 32..63 the second.
-template <int ALG, int NW, int VS = 1024>
+// VSP: LDS bytes from one position to the next (VS, or more when the points are padded).
+template <int ALG, int NW, int VS = 1024, int VSP = VS>
 __device__ __forceinline__ void copy_out_points(const unsigned char* lds,
                                                 __amdgpu_buffer_rsrc_t vres, unsigned lane_off,
                                                 unsigned vplane, int wave, int lane) {
@@ -427,7 +428,7 @@ __device__ __forceinline__ void copy_out_points(const unsigned char* lds,
         }
       }
       if (p >= 0) {
-        const v4i d = *(const v4i*)(lds + (2 * (jj * NW + wave)) * 512 + lane * 16);
+        const v4i d = *(const v4i*)(lds + (2 * (jj * NW + wave) + hi) * VSP + (lane & 31) * 16);
         __builtin_amdgcn_raw_buffer_store_b128(d, vres, lane_off + (unsigned)p * vplane, 0, 0);
       }
     }
@@ -442,7 +443,7 @@ __device__ __forceinline__ void copy_out_points(const unsigned char* lds,
     for (int w = 0; w < NW; ++w)
       if (w == wave && jj * NW + w < P) p = order.pt[jj * NW + w];
     if (p >= 0) {
-      const v4i d = *(const v4i*)(lds + (jj * NW + wave) * 1024 + lane * 16);
+      const v4i d = *(const v4i*)(lds + (jj * NW + wave) * VSP + lane * 16);
       __builtin_amdgcn_raw_buffer_store_b128(d, vres, lane_off, (unsigned)p * vplane, 0);
     }
   }
