@@ -115,6 +115,25 @@ def graph_ms(torch, timer, fn, steps):
         return None
 
 
+def copy_bandwidth(torch, timer):
+    """The library's plain copy kernel over rotating 128 MiB buffers: the streaming bandwidth
+    (read + write bytes) this device reaches in this run, and a kernel of known traffic for
+    scaling the byte counters of a rocprofv3 --pmc run of this command."""
+    from paper_2407_02913_amd import binding
+
+    nbytes = 128 << 20
+    bufs = [(torch.empty(nbytes, dtype=torch.uint8, device="cuda"),
+             torch.empty(nbytes, dtype=torch.uint8, device="cuda")) for _ in range(3)]
+    cur = torch.cuda.current_stream()
+    for a, b in bufs:
+        binding.stream_copy(b, a, stream=cur)
+    torch.cuda.synchronize()
+    ms = timer.once(lambda i: binding.stream_copy(bufs[i % 3][1], bufs[i % 3][0], stream=cur), 12)
+    del bufs
+    torch.cuda.empty_cache()
+    return 2 * nbytes / (ms * 1e-3) / 1e9
+
+
 def traffic_from_profiles(kernel, workload, alg):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel, if any."""
     tfile = os.path.join(ROOT, "profiles", f"traffic_{kernel}_{workload}_{alg}.txt")
@@ -358,6 +377,7 @@ def main():
         rec = bench_stack(args, torch, timer) if name == "stack" else bench_layer(args, name, torch, timer)
         records.append(rec)
     head = records[-1]
+    head["roofline"]["stream_copy_gbs"] = round(copy_bandwidth(torch, timer), 1)
     out = {
         "metric": "direct-conv-equivalent int8 TOPS per 3x3 layer; % MFMA/HBM roofline",
         "value": head["value"], "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -197,6 +197,7 @@ __device__ __forceinline__ void quad16_store(const f4 (&z)[AlgTraits<ALG>::NC][A
   constexpr unsigned kOutOfRange = 0x80000000u;
   constexpr float kMagic = 12582912.0f;
   const int tl = lane & 15, q = lane >> 4;
+  const float act = x_scale * inv_y;  // int8 output: activation scale over output scale
   // float32 staging: 16-byte slots, slot (tile, row) of a filter moved round by tile/4 so
   // that the 16 lanes of a quarter wave fall into different banks, writing and reading
   auto slot = [](int tile, int row) { return tile * 4 + ((row + (tile >> 2)) & 3); };
@@ -217,7 +218,7 @@ __device__ __forceinline__ void quad16_store(const f4 (&z)[AlgTraits<ALG>::NC][A
 #pragma unroll
         for (int o2 = 0; o2 < M; ++o2) {
           // next layer's activation: ReLU, round half to even, clamp to [0, 127]
-          float t = __fmaf_rn(out[o2] * x_scale, inv_y, kMagic);
+          float t = __fmaf_rn(out[o2], act, kMagic);
           t = __builtin_amdgcn_fmed3f(t, kMagic, kMagic + 127.0f);
           word |= (__float_as_uint(t) & 0xffu) << (8 * o2);
         }

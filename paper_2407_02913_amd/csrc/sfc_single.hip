@@ -1,15 +1,13 @@
-// The whole hot path in one kernel, for layers with Cin <= 64 (gfx950): input-tile
-// transform, transform-domain products and output transform without V or M ever
-// leaving the compute unit.
+// The whole hot path in one kernel, for layers with Cin <= 64 and the SFC-6 forms with 3x3
+// filters (gfx950): input-tile transform, transform-domain products and output transform
+// without V or M ever leaving the compute unit.  (The SFC-4 forms have their own kernel,
+// sfc_single16.hip.)
 //
-// A workgroup of 16 waves (8 for the 7x7 and the SFC-4 forms, each wave then doing two
-// passes) owns a rectangle of up to 16 tiles (S strips x tlw tile columns; a strip = one
-// row of tiles of one image), all input channels and a group of 64 filters.  The SFC-4
-// forms need half the LDS and two thirds of the registers, so two of their workgroups
-// share a compute unit.
+// A workgroup of 16 waves (8 for the 7x7 forms, each wave then doing two passes) owns a
+// rectangle of up to 16 tiles (S strips x tlw tile columns; a strip = one row of tiles of one
+// image), all input channels and a group of 64 filters.
 //
-// Points are taken in groups of four (one filter-operand load per group); the SFC-4 forms
-// pad their 46 / 49 points to 48 / 52 positions with zero filter operands.
+// Points are taken in groups of four (one filter-operand load per group).
 //
 //  1. Stage: the M+2 input rows of every (strip, channel) go to LDS with dword
 //     loads, lanes running along the row, padding halo zero-filled.
@@ -47,19 +45,12 @@ struct SinglePlan {
   int kgroups;         // groups of 64 filters
   unsigned stage_off;  // LDS byte offset of the per-wave output staging blocks
   unsigned lds_bytes;
-  int strips;          // 1: the tiles of a strip are whole image rows, y is written strip by strip
 };
 
 constexpr int kWaves6 = 16;  // waves per workgroup for the 6x6 forms
 
-// WGS: workgroups per compute unit the register budget is cut for (the second launch bound
-// counts waves per SIMD: NW * WGS / 4).  2 for the SFC-4 forms, whose 48 KB of V and 24
-// partial outputs per pair leave room for a second workgroup, so that one workgroup's
-// loads and stores overlap the other's arithmetic.
-// STRIPS: the rectangle's strips are whole image rows (SinglePlan::strips); step 4 stages all
-// M rows of a pair and writes y strip by strip (store_strips).
-template <int ALG, int OUT, bool VEC2, int NW, int WGS, bool STRIPS = false>
-__global__ __launch_bounds__(NW * 64, NW * WGS / 4) void single_conv_kernel(
+template <int ALG, int OUT, bool VEC2, int NW>
+__global__ __launch_bounds__(NW * 64, NW / 4) void single_conv_kernel(
     const int8_t* __restrict__ x, const int8_t* __restrict__ Uf, const float* __restrict__ dqf,
     const float* __restrict__ inv_sx, float x_scale, float inv_y, void* __restrict__ y, Geometry g,
     SinglePlan sp) {
@@ -76,7 +67,7 @@ __global__ __launch_bounds__(NW * 64, NW * WGS / 4) void single_conv_kernel(
   const int W = g.W, H = g.H;
 
   // per-tile store data for step 4, written by 16 lanes now and read after the barriers
-  constexpr int STAGE_FLOATS = 64 * M * (STRIPS ? M : 1);  // per wave
+  constexpr int STAGE_FLOATS = 64 * M;  // per wave
   int* tile_tab = (int*)(lds + sp.stage_off + NW * STAGE_FLOATS * 4);
   if (threadIdx.x < 16) {
     const int tl = threadIdx.x;
@@ -156,13 +147,7 @@ __global__ __launch_bounds__(NW * 64, NW * WGS / 4) void single_conv_kernel(
     stream_vertical<ALG, float>(next, z);
 
     // ---- 4. store ----------------------------------------------------------------
-    if constexpr (STRIPS) {
-      store_strips<ALG, OUT>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, H, W, tr.S,
-                             tr.tlw);
-      __builtin_amdgcn_wave_barrier();  // the next pass writes the block again
-    } else {
-      store_pairs<ALG, OUT, VEC2>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, H, W);
-    }
+    store_pairs<ALG, OUT, VEC2>(z, stage, tile_tab, lane, kq, x_scale, inv_y, yres, g.Cout, H, W);
   }
 }
 
@@ -191,25 +176,16 @@ __global__ __launch_bounds__(64) void repack_filter_kernel(const int8_t* __restr
 // 256-register budget of 8 waves
 static int single_waves(int alg) { return alg_tile(alg) == 6 ? kWaves6 : 8; }
 
-// strips: plan for store_strips (staging blocks of M rows per pair), which needs a rectangle
-// of whole image rows
-static bool make_single_plan_for(const Geometry& g, SinglePlan* sp, bool strips) {
-  if (g.Cp != 64 || g.alg > 5) return false;  // 3x3 filters only
+static bool make_single_plan(const Geometry& g, SinglePlan* sp) {
+  if (g.Cp != 64 || g.alg > 3) return false;  // the SFC-6 forms with 3x3 filters
   const int M = alg_tile(g.alg);
-  if (strips && (M != 4 || g.W != M * g.tw || g.H != M * g.th || g.Cout % 4 != 0)) return false;
   // LDS: the staged rows of the rectangle (later overwritten by V), the per-wave output
   // staging blocks, the per-tile store table
   const unsigned vbytes = (unsigned)g.P * 1024u;
-  const unsigned sbytes =
-      (unsigned)single_waves(g.alg) * 64u * (unsigned)(M * (strips ? M : 1)) * 4u + 256u;
-  // the SFC-4 forms leave half of the 160 KB to a second workgroup on the compute unit
-  const unsigned lds_max = (M == 4 ? 80u : 160u) * 1024u;
+  const unsigned sbytes = (unsigned)single_waves(g.alg) * 64u * (unsigned)M * 4u + 256u;
+  const unsigned lds_max = 160u * 1024u;
   if (vbytes + 16u + sbytes > lds_max) return false;
   if (!make_tile_rect(g, lds_max - 16u - sbytes, &sp->tr)) return false;
-  if (strips && (sp->tr.whole || sp->tr.chunks != 1 || sp->tr.tlw != g.tw ||
-                 sp->tr.S * sp->tr.tlw > 16))
-    return false;
-  sp->strips = strips ? 1 : 0;
   sp->kgroups = (g.Cout + 63) / 64;
   const unsigned xbytes = tile_rect_stage_bytes(g, sp->tr);
   sp->stage_off = ((xbytes > vbytes ? xbytes : vbytes) + 15u) & ~15u;
@@ -219,10 +195,6 @@ static bool make_single_plan_for(const Geometry& g, SinglePlan* sp, bool strips)
   const long long ub = (long long)sp->kgroups * 64 * (g.P + 3) * 64;
   const long long lim = 1ll << 31;
   return sp->lds_bytes <= lds_max && xb < lim && yb < lim && ub < lim;
-}
-
-static bool make_single_plan(const Geometry& g, SinglePlan* sp) {
-  return make_single_plan_for(g, sp, true) || make_single_plan_for(g, sp, false);
 }
 
 bool single_supported(const Geometry& g) {
@@ -265,11 +237,11 @@ void single_point_order(int alg, int* pt /*[P rounded up to a multiple of 4]*/) 
   }
 }
 
-template <int ALG, int OUT, bool VEC2, int NW, bool STRIPS = false>
+template <int ALG, int OUT, bool VEC2, int NW>
 static hipError_t launch_single_impl(const Geometry& g, const SinglePlan& sp, const int8_t* x,
                                      const FilterViews& f, float x_scale, float inv_y, void* y,
                                      hipStream_t s, bool prepare) {
-  auto kernel = single_conv_kernel<ALG, OUT, VEC2, NW, AlgTraits<ALG>::M == 4 ? 2 : 1, STRIPS>;
+  auto kernel = single_conv_kernel<ALG, OUT, VEC2, NW>;
   if (prepare) return raise_lds_limit(reinterpret_cast<const void*>(kernel));
   const dim3 grid(tile_rect_groups(g, sp.tr), (unsigned)sp.kgroups);
   hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), sp.lds_bytes, s, x, (const int8_t*)f.U_single,
@@ -283,10 +255,6 @@ static hipError_t launch_single_out(const Geometry& g, const SinglePlan& sp, con
                                     hipStream_t s, bool prepare) {
   constexpr int NW = AlgTraits<ALG>::M == 6 ? kWaves6 : 8;
   constexpr bool kPairs = AlgTraits<ALG>::M % 2 == 0;  // pairs of an output row stay aligned
-  if constexpr (AlgTraits<ALG>::M == 4) {
-    if (sp.strips)
-      return launch_single_impl<ALG, OUT, true, NW, true>(g, sp, x, f, x_scale, inv_y, y, s, prepare);
-  }
   if constexpr (kPairs) {
     if (g.W % 2 == 0) return launch_single_impl<ALG, OUT, true, NW>(g, sp, x, f, x_scale, inv_y, y, s, prepare);
   }
@@ -310,8 +278,6 @@ hipError_t launch_single_conv(int out, const Geometry& g, const int8_t* x, const
     case 1: return launch_single_alg<1>(out, g, sp, x, f, x_scale, inv_y, y, s, prepare);
     case 2: return launch_single_alg<2>(out, g, sp, x, f, x_scale, inv_y, y, s, prepare);
     case 3: return launch_single_alg<3>(out, g, sp, x, f, x_scale, inv_y, y, s, prepare);
-    case 4: return launch_single_alg<4>(out, g, sp, x, f, x_scale, inv_y, y, s, prepare);
-    case 5: return launch_single_alg<5>(out, g, sp, x, f, x_scale, inv_y, y, s, prepare);
   }
   return hipErrorInvalidValue;
 }

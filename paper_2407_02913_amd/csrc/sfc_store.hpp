@@ -33,9 +33,7 @@ __device__ __forceinline__ void store_pairs(
   // Cache policy of the y stores.  7x7 and 4x4 tiles divide the ResNet image widths; on wide
   // images a workgroup then writes long whole rows and the lines can stream past the L2
   // ("nt"): nothing is left dirty in the L2 for the end of the kernel to write back, which
-  // shortened the 4x4 single kernel on 56x56 maps from 19.6 to 17.0 us (it now writes whole
-  // strips there, store_strips; the 49-point form and the fused kernels still come through
-  // here on wide maps).  Everywhere else (6x6
+  // shortened a 4x4 single kernel on 56x56 maps from 19.6 to 17.0 us.  Everywhere else (6x6
   // tiles, or short rows of small feature maps, where a line is completed by several stores
   // or several workgroups) the L2 has to merge the pieces before they go to memory:
   // streaming those costs up to 2.5x the bytes in HBM writes.
@@ -180,78 +178,6 @@ __device__ __forceinline__ void store_planes(
           __builtin_amdgcn_raw_buffer_store_b32(word, yres, off, 0, 0);
         } else {
           __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, v), yres, off, 0, kStreamStore);
-        }
-      }
-    }
-  }
-}
-
-// The same for the tile rectangles of the single kernel when whole tiles cover the image rows
-// (W = M*tlw, H = M*th) and M*W is a whole number of 16-byte groups: the tiles of a strip
-// are then M whole image rows, M*W consecutive elements of y per filter.  Slot s*tlw + tj of
-// the wave's 16 tile slots is tile column tj of strip s (S strips).  The wave stages all M
-// rows of its pairs as [filter][strip][row][tile column][o2], the order of y, and writes them
-// with four elements per lane; on wide maps whose strips are whole 128-byte lines the
-// float32 runs stream past the L2 (row-by-row streaming stores sent the line a 224-byte row
-// ends in to memory twice: 29.1 MB for 25.7 MB of y on 56x56 maps).  Needs Cout % 4 == 0 and
-// a staging block of 64*M*M floats per wave.
-template <int ALG, int OUT>
-__device__ __forceinline__ void store_strips(
-    const float (&z)[AlgTraits<ALG>::NC][AlgTraits<ALG>::M], float* stage, const int* tile_tab,
-    int lane, int kq, float x_scale, float inv_y, __amdgpu_buffer_rsrc_t yres, int Cout, int H,
-    int W, int S, int tlw) {
-  constexpr int M = AlgTraits<ALG>::M;
-  static_assert(M % 4 == 0, "rows of whole 16-byte groups");
-  constexpr unsigned esz = OUT == 2 ? 1u : 4u;
-  const int run = M * W;  // elements of one (filter, strip)
-  {
-    const int tl = lane & 15, f = lane >> 4;
-    const int s = tl / tlw, tj = tl - s * tlw;
-    float* wr = stage + (f * S + s) * run + M * tj;
-#pragma unroll
-    for (int o1 = 0; o1 < M; ++o1) {
-      float out[M];
-      stream_row<ALG, float>(z, o1, out);
-      if (tl < S * tlw) {
-#pragma unroll
-        for (int o2 = 0; o2 < M; o2 += 4)
-          *(v4f*)(wr + o1 * W + o2) = v4f{out[o2] * x_scale, out[o2 + 1] * x_scale,
-                                          out[o2 + 2] * x_scale, out[o2 + 3] * x_scale};
-      }
-    }
-  }
-  __builtin_amdgcn_wave_barrier();  // LDS accesses of one wave complete in order
-  // int8 output: the row-by-row stores of wide maps stream as well (store_pairs), and so do these
-  const bool stream = W >= 48 && (OUT == 2 || (run * 4) % 128 == 0);
-  const int rq = run >> 2;      // groups of four elements per (filter, strip)
-  const int nq = 4 * S * rq;    // ... in the wave's block, at most 16*M*M
-  const bool kvalid = 4 * kq < Cout;
-#pragma unroll
-  for (int k = 0; k < (16 * M * M + 63) / 64; ++k) {
-    const int q = lane + 64 * k;
-    if (q < nq) {
-      const int fs = q / rq, r = q - fs * rq;
-      const int f = fs / S, s = fs - f * S;
-      const v4f v = *(const v4f*)(stage + 4 * q);
-      if (kvalid && tile_tab[16 + s * tlw] > 0) {
-        const unsigned off = esz * (unsigned)(tile_tab[s * tlw] + (4 * kq + f) * (H * W) + 4 * r);
-        if constexpr (OUT == 2) {
-          // next layer's activation: ReLU, round half to even, clamp to [0, 127]
-          constexpr float kMagic = 12582912.0f;
-          unsigned word = 0;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            float t = __fmaf_rn(v[i], inv_y, kMagic);
-            t = __builtin_amdgcn_fmed3f(t, kMagic, kMagic + 127.0f);
-            word |= (__float_as_uint(t) & 0xffu) << (8 * i);
-          }
-          if (stream) __builtin_amdgcn_raw_buffer_store_b32(word, yres, off, 0, kStreamStore);
-          else __builtin_amdgcn_raw_buffer_store_b32(word, yres, off, 0, 0);
-        } else {
-          if (stream)
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, v), yres, off, 0, kStreamStore);
-          else
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, v), yres, off, 0, 0);
         }
       }
     }
