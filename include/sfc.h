@@ -102,9 +102,9 @@ typedef enum {
   SFC_PATH_AUTO = -1,
   SFC_PATH_STAGED = 0, /* V and M pass through the workspace; taps available */
   SFC_PATH_FUSED = 1,  /* product and output transform in one kernel; M never leaves the chip */
-  /* Cin <= 64, or Cin <= 128 with the SFC-4 forms: input transform, products and output
-   * transform in one kernel; neither V nor M leaves the chip, the workspace is used by
-   * calibration only. */
+  /* Input transform, products and output transform in one kernel; neither V nor M leaves the
+   * chip, the workspace is used by calibration only.  Cin <= 64; with the SFC-4 forms also
+   * Cin <= 128, and Cin <= 512 on feature maps of at most 16 tiles (16x16 and smaller). */
   SFC_PATH_SINGLE = 2
 } sfc_path;
 

@@ -130,7 +130,10 @@ int choose_alg(const sfc_conv_desc& d) {
 // kernel does not take).
 int choose_path(const sfc_conv_desc& d, const Geometry& g) {
   if (d.mode != SFC_MODE_REQUANT_I8) return SFC_PATH_STAGED;
-  if (sfc::single_supported(g)) return SFC_PATH_SINGLE;
+  // (with more than 128 channels the single-kernel path repeats the input transform for
+  // every 64 filters and is slower than two kernels: 51 against 30 us for 256 channels on
+  // 14x14 maps at batch 64; it stays available on request)
+  if (g.Cp <= 128 && sfc::single_supported(g)) return SFC_PATH_SINGLE;
   // 7x7 tiles on 7x7 maps with 512 and more channels: the fused kernel would stream its
   // operands from L2 eight times over; the products as batched GEMMs through HBM are faster
   // (64.0 against 77.0 us at batch 256)
@@ -205,7 +208,7 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   p->off_U_single = off;
   p->quad_filters = 0;
   p->quad16 = (d.path == SFC_PATH_FUSED && sfc::quad16_supported(g)) ||
-              (d.path == SFC_PATH_SINGLE && sfc::single16_supported(g));
+              (d.path == SFC_PATH_SINGLE && (sfc::single16_supported(g) || sfc::single16k_supported(g)));
   if (d.path == SFC_PATH_SINGLE) p->quad_filters = p->quad16 ? g.Kp : (g.Cout + 63) / 64 * 64;
   if (d.path == SFC_PATH_FUSED)
     p->quad_filters = p->quad16 ? sfc::quad16_filter_count(g) : sfc::quad_filter_count(g);
@@ -418,10 +421,14 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
     if (stage_mask != SFC_STAGE_ALL) return SFC_EINVAL;  // one kernel: no stage runs alone
     const FilterViews f = views(plan, plan->filter_dev);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if ((plan->quad16 ? sfc::launch_single16(plan->d.out, plan->g, x_dev, f, x_scale, plan->inv_y, y_dev, s)
-                      : sfc::launch_single_conv(plan->d.out, plan->g, x_dev, f, x_scale, plan->inv_y,
-                                                y_dev, s)) != hipSuccess)
-      return SFC_EHIP;
+    hipError_t e;
+    if (!plan->quad16)
+      e = sfc::launch_single_conv(plan->d.out, plan->g, x_dev, f, x_scale, plan->inv_y, y_dev, s);
+    else if (plan->g.Cp <= 128)
+      e = sfc::launch_single16(plan->d.out, plan->g, x_dev, f, x_scale, plan->inv_y, y_dev, s);
+    else
+      e = sfc::launch_single16k(plan->d.out, plan->g, x_dev, f, x_scale, plan->inv_y, y_dev, s);
+    if (e != hipSuccess) return SFC_EHIP;
     return SFC_OK;
   }
   const int tail = stage_mask & (SFC_STAGE_PRODUCT | SFC_STAGE_OUTPUT);

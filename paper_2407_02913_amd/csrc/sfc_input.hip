@@ -54,7 +54,9 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
     row_tab[tl] = tc.live ? (tc.n * g.th + tc.ti) * g.tw + tc.tj : -1;
   }
 
-  stage_input<ALG, NW>(x, lds, g, tr, bx, c0, wave, lane);
+  // (the SFC-4 forms stage 16 bytes into the LDS: plane patches are read from up to 4 bytes early)
+  unsigned char* in = lds + (AlgTraits<ALG>::kFamily == 4 ? 16 : 0);
+  stage_input<ALG, NW>(x, in, g, tr, bx, c0, wave, lane);
   __syncthreads();
   if constexpr (AlgTraits<ALG>::kFamily == 4) {
     // on the matrix cores: wave = tile, four groups of 16 channels; rounded and packed in
@@ -72,7 +74,7 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
         const int ti = rem / g.tw, tj = rem - ti * g.tw;
 #pragma unroll
         for (int cg = 0; cg < 4; ++cg)
-          mi.transform(MfmaInput<ALG>::operand_plane(lds + slot * 64 * tr.cs, tr.cs, 16 * cg,
+          mi.transform(MfmaInput<ALG>::operand_plane(in + slot * 64 * tr.cs, tr.cs, 16 * cg,
                                                      Tr::M * ti - Tr::PAD, Tr::M * tj - Tr::PAD, g.H,
                                                      g.W, lane),
                        g.qmax, packed[cg]);
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
 #pragma unroll
         for (int cg = 0; cg < 4; ++cg)
           mi.transform(MfmaInput<ALG>::template operand_rect<stage_channel_bytes(Tr::NI)>(
-                           lds, s, 16 * cg, halo + Tr::M * tjl, lane),
+                           in, s, 16 * cg, halo + Tr::M * tjl, lane),
                        g.qmax, packed[cg]);
       }
     }
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
         }
     }
   } else {
-    transform_tiles<ALG, NW, 1, VS>(lds, inv_sx, g.qmax, g, tr, bx, wave, lane);
+    transform_tiles<ALG, NW, 1, VS>(in, inv_sx, g.qmax, g, tr, bx, wave, lane);
   }
   __syncthreads();
 
@@ -124,8 +126,8 @@ static bool make_input_plan(const Geometry& g, InputPlan* ip) {
   const unsigned vbytes = (unsigned)((g.P + 3) / 4 * 4) * ((input_waves(g.alg) == 8 ? 512u : 1024u) + 16u);
   const unsigned lds_max = 160u * 1024u;
   if (vbytes + 16u + 64u > lds_max) return false;
-  if (!make_tile_rect(g, lds_max - 16u - 64u, &ip->tr, input_waves(g.alg), true)) return false;
-  const unsigned xbytes = tile_rect_stage_bytes(g, ip->tr);
+  if (!make_tile_rect(g, lds_max - 32u - 64u, &ip->tr, input_waves(g.alg), true)) return false;
+  const unsigned xbytes = tile_rect_stage_bytes(g, ip->tr) + 16u;
   ip->tab_off = ((xbytes > vbytes ? xbytes : vbytes) + 15u) & ~15u;
   ip->lds_bytes = ip->tab_off + 64u;
   const long long xb = (long long)g.N * g.Cin * g.H * g.W;

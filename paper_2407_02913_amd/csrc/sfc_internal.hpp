@@ -86,6 +86,11 @@ hipError_t launch_quad16(int out, const Geometry& g, const void* V, const Filter
 bool single16_supported(const Geometry& g);
 hipError_t launch_single16(int out, const Geometry& g, const int8_t* x, const FilterViews& f,
                            float x_scale, float inv_y, void* y, hipStream_t s, bool prepare = false);
+// the same for 129 to 512 input channels on feature maps of at most 16 tiles, the products
+// accumulated in registers chunk by chunk (sfc_single16k.hip)
+bool single16k_supported(const Geometry& g);
+hipError_t launch_single16k(int out, const Geometry& g, const int8_t* x, const FilterViews& f,
+                            float x_scale, float inv_y, void* y, hipStream_t s, bool prepare = false);
 // single-kernel path: whether it covers this geometry, the bytes of its filter operand,
 // the regrouping of the canonical U, the processing order (position -> canonical point)
 bool single_supported(const Geometry& g);

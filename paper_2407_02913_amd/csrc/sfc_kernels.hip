@@ -410,10 +410,11 @@ hipError_t launch_input_transform(int mode, const Geometry& g, const int8_t* x, 
 
 hipError_t prepare_kernels(int path, int out, const Geometry& g) {
   const FilterViews none{};
-  if (path == 2)
-    return single16_supported(g)
-               ? launch_single16(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true)
-               : launch_single_conv(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true);
+  if (path == 2) {
+    if (single16_supported(g)) return launch_single16(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true);
+    if (single16k_supported(g)) return launch_single16k(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true);
+    return launch_single_conv(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true);
+  }
   // the generic input kernel (geometries the int8 one does not take) stays under 64 KB
   hipError_t e = launch_input_transform_i8(g, nullptr, nullptr, nullptr, nullptr, nullptr, true);
   if (e != hipSuccess && e != hipErrorNotSupported) return e;

@@ -66,28 +66,51 @@ struct MfmaInput {
   }
 
   // Operand A from whole channel planes (small feature maps): sample (r0 + i, q0 + j) of the
-  // plane of channel ch0 + l%16, zero outside the image.
-  static __device__ __forceinline__ v4i operand_plane(const unsigned char* planes, int cs, int ch0,
-                                                      int r0, int q0, int H, int W, int lane) {
-    const unsigned char* plane = planes + (ch0 + (lane & 15)) * cs;
+  // plane of channel ch0 + l%16, zero outside the image.  The tile position (r0, q0) is the
+  // same for the whole wave.  A patch row is cut out of three aligned dwords; its columns
+  // outside the image are masked (the same mask for every lane), a row outside the image is
+  // replaced by zeros.  The dwords may reach up to 4 bytes before the first plane and 8 bytes
+  // past the last one: the caller keeps that much LDS around the planes.
+  // (the per-tile part of that, the same for every lane, channel group and chunk)
+  struct PlaneTile {
+    int boff[2];        // byte offset of the lane's two patch rows from plane - 4 (rows clamped)
+    bool rok[2];        // whether they lie inside the image
+    unsigned cmask[2];  // bytes of a row's two dwords that are image columns
+  };
+  static __device__ __forceinline__ PlaneTile plane_tile(int r0, int q0, int H, int W, int lane) {
+    PlaneTile t;
     const int rp = min(lane >> 4, 2);
-    v4i a;
+    t.cmask[0] = t.cmask[1] = 0u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if ((unsigned)(q0 + j) < (unsigned)W) t.cmask[j >> 2] |= 0xffu << (8 * (j & 3));
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
       const int h = r0 + 2 * rp + r;
-      const bool rok = (unsigned)h < (unsigned)H;
-      unsigned w[2] = {0u, 0u};
+      t.rok[r] = (unsigned)h < (unsigned)H;
+      t.boff[r] = min(max(h, 0), H - 1) * W + q0 + 4;  // >= 3
+    }
+    return t;
+  }
+  static __device__ __forceinline__ v4i operand_plane(const unsigned char* planes, int cs, int ch0,
+                                                      const PlaneTile& t, int lane) {
+    const unsigned char* plane = planes + (ch0 + (lane & 15)) * cs;
+    v4i a;
 #pragma unroll
-      for (int j = 0; j < 6; ++j) {
-        const int q = q0 + j;
-        const bool ok = rok && (unsigned)q < (unsigned)W;
-        const unsigned v = ok ? (unsigned)plane[h * W + q] : 0u;
-        w[j >> 2] |= v << (8 * (j & 3));
-      }
-      a[2 * r] = (int)w[0];
-      a[2 * r + 1] = (int)w[1];
+    for (int r = 0; r < 2; ++r) {
+      const unsigned* src = (const unsigned*)(plane - 4 + (t.boff[r] & ~3));
+      const unsigned sh = (unsigned)(t.boff[r] & 3);
+      const unsigned d0 = src[0], d1 = src[1], d2 = src[2];
+      const unsigned w0 = __builtin_amdgcn_alignbyte(d1, d0, sh) & t.cmask[0];
+      const unsigned w1 = __builtin_amdgcn_alignbyte(d2, d1, sh) & t.cmask[1];
+      a[2 * r] = t.rok[r] ? (int)w0 : 0;
+      a[2 * r + 1] = t.rok[r] ? (int)w1 : 0;
     }
     return a;
+  }
+  static __device__ __forceinline__ v4i operand_plane(const unsigned char* planes, int cs, int ch0,
+                                                      int r0, int q0, int H, int W, int lane) {
+    return operand_plane(planes, cs, ch0, plane_tile(r0, q0, H, W, lane), lane);
   }
 
   // The sums of the lane's four channels for its point of every block, rounded to int8

@@ -649,50 +649,66 @@ SFC_HD void output_transform(G&& get, T (&out)[AlgTraits<ALG>::M][AlgTraits<ALG>
 // z[b][o1]: horizontal component b, vertical output o1, times 6.  Each group
 // collapses at once: product-rule post-additions, Hermitian recombination, inverse
 // symbolic DFT-6 with the corrections along the vertical axis.
+// SFC-4, first part: the products of the four real columns (7 each, processing positions
+// 0 .. 27) give z[0], z[1], z[4], z[5].
+template <int ALG, typename T, typename F>
+SFC_HD void stream_vertical4_real(F&& next, T (&z)[6][4]) {
+  constexpr int NR = 7, NC = 6;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    T col[NR], cc[NC];
+#pragma unroll
+    for (int r1 = 0; r1 < NR; ++r1) col[r1] = next();
+    collapse4_rows(col, cc);
+    inv4_outputs(cc, z[real_comp4(j)]);
+  }
+}
+
+// SFC-4, second part: the products of the complex column group (positions 28 on; Eq. DFT4M)
+// give z[2], z[3].
+template <int ALG, typename T, typename F>
+SFC_HD void stream_vertical4_complex(F&& next, T (&z)[6][4]) {
+  constexpr int NR = 7, NC = 6, NREAL = 4;
+  T c0[NC], c1[NC];
+  if constexpr (!AlgTraits<ALG>::kHermitian) {
+    T h0[NR], h1[NR];
+#pragma unroll
+    for (int r1 = 0; r1 < NR; ++r1) {
+      const T m2 = next(), m1 = next(), m0 = next();  // rows a0 + a1, a1, a0
+      h0[r1] = m0 - m1;
+      h1[r1] = m2 - m0 - m1;
+    }
+    collapse4_rows(h0, c0);
+    collapse4_rows(h1, c1);
+  } else {
+#pragma unroll
+    for (int j = 0; j < NREAL; ++j) {
+      const T m2 = next(), m1 = next(), m0 = next();
+      c0[real_comp4(j)] = m0 - m1;
+      c1[real_comp4(j)] = m2 - m0 - m1;
+    }
+    T m[6];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) m[i] = next();
+    const T uo0 = m[0] - m[1], uo1 = m[2] - m[0] - m[1];
+    const T vo0 = m[3] - m[4], vo1 = m[5] - m[3] - m[4];
+    c0[2] = Half<T>::apply(uo0 + vo0);  // o00
+    c0[3] = Half<T>::apply(uo1 + vo1);  // o10
+    c1[2] = Half<T>::apply(uo1 - vo1);  // o01
+    c1[3] = Half<T>::apply(vo0 - uo0);  // o11
+  }
+  inv4_outputs(c0, z[2]);
+  inv4_outputs(c1, z[3]);
+}
+
 template <int ALG, typename T, typename F>
 SFC_HD void stream_vertical(F&& next, T (&z)[AlgTraits<ALG>::NC][AlgTraits<ALG>::M]) {
   using Tr = AlgTraits<ALG>;
   constexpr int NR = Tr::NR, NC = Tr::NC, NREAL = Tr::NREAL;
   if constexpr (Tr::kFamily == 4) {
-    // SFC-4: four real columns, then the one complex column group (Eq. DFT4M)
-#pragma unroll
-    for (int j = 0; j < NREAL; ++j) {
-      T col[NR], cc[NC];
-#pragma unroll
-      for (int r1 = 0; r1 < NR; ++r1) col[r1] = next();
-      collapse4_rows(col, cc);
-      inv4_outputs(cc, z[real_comp4(j)]);
-    }
-    T c0[NC], c1[NC];
-    if constexpr (!Tr::kHermitian) {
-      T h0[NR], h1[NR];
-#pragma unroll
-      for (int r1 = 0; r1 < NR; ++r1) {
-        const T m2 = next(), m1 = next(), m0 = next();  // rows a0 + a1, a1, a0
-        h0[r1] = m0 - m1;
-        h1[r1] = m2 - m0 - m1;
-      }
-      collapse4_rows(h0, c0);
-      collapse4_rows(h1, c1);
-    } else {
-#pragma unroll
-      for (int j = 0; j < NREAL; ++j) {
-        const T m2 = next(), m1 = next(), m0 = next();
-        c0[real_comp4(j)] = m0 - m1;
-        c1[real_comp4(j)] = m2 - m0 - m1;
-      }
-      T m[6];
-#pragma unroll
-      for (int i = 0; i < 6; ++i) m[i] = next();
-      const T uo0 = m[0] - m[1], uo1 = m[2] - m[0] - m[1];
-      const T vo0 = m[3] - m[4], vo1 = m[5] - m[3] - m[4];
-      c0[2] = Half<T>::apply(uo0 + vo0);  // o00
-      c0[3] = Half<T>::apply(uo1 + vo1);  // o10
-      c1[2] = Half<T>::apply(uo1 - vo1);  // o01
-      c1[3] = Half<T>::apply(vo0 - uo0);  // o11
-    }
-    inv4_outputs(c0, z[2]);
-    inv4_outputs(c1, z[3]);
+    // SFC-4: four real columns, then the one complex column group
+    stream_vertical4_real<ALG, T>(next, z);
+    stream_vertical4_complex<ALG, T>(next, z);
     return;
   } else {
 #pragma unroll

@@ -199,7 +199,7 @@ static bool make_single_plan(const Geometry& g, SinglePlan* sp) {
 
 bool single_supported(const Geometry& g) {
   SinglePlan sp;
-  return single16_supported(g) || make_single_plan(g, &sp);
+  return single16_supported(g) || single16k_supported(g) || make_single_plan(g, &sp);
 }
 
 hipError_t launch_repack_filter(const Geometry& g, int filters, const void* U, void* Uf,

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(NW * 64, 2) void single16_kernel(
   // ---- 1. stage ----------------------------------------------------------------------
 #pragma unroll
   for (int kc = 0; kc < KC; ++kc)
-    stage_input<ALG, NW>(x, lds + kc * sp.chunk_in, g, tr, bx, 64 * kc, wave, lane);
+    stage_input<ALG, NW>(x, lds + 16 + kc * sp.chunk_in, g, tr, bx, 64 * kc, wave, lane);
   __syncthreads();
 
   // ---- 2. input transform (sfc_mfma_input.hpp) --------------------------------------------
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(NW * 64, 2) void single16_kernel(
 #pragma unroll
     for (int it = 0; it < NITEM; ++it) {
       const int tile = wave + NW * (it / KC), kc = it % KC;
-      const unsigned char* in = lds + kc * sp.chunk_in;
+      const unsigned char* in = lds + 16 + kc * sp.chunk_in;  // (16: plane patches are read from up to 4 bytes early)
       if (tile < tr.ntiles) {
         if (tr.whole) {
           const int tpi = g.th * g.tw;
@@ -192,9 +192,9 @@ static bool make_single16_plan(const Geometry& g, int out, Single16Plan* sp) {
   const unsigned sbytes = (unsigned)nw * (out == 2 ? 4096u : 16384u);
   const unsigned lds_max = 160u * 1024u - 256u;
   if (vbytes > lds_max || sbytes > lds_max) return false;
-  if (!make_tile_rect(g, lds_max / (unsigned)kc, &sp->tr)) return false;
+  if (!make_tile_rect(g, (lds_max - 16u) / (unsigned)kc, &sp->tr)) return false;
   sp->chunk_in = tile_rect_stage_bytes(g, sp->tr);
-  unsigned top = sp->chunk_in * (unsigned)kc;
+  unsigned top = 16u + sp->chunk_in * (unsigned)kc;
   if (vbytes > top) top = vbytes;
   if (sbytes > top) top = sbytes;
   sp->tab_off = (top + 15u) & ~15u;

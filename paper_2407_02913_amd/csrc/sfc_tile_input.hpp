@@ -154,7 +154,7 @@ __device__ __forceinline__ TileCoord tile_coord(const Geometry& g, const TileRec
 // would it reach past the buffer, so there the bytes are fetched one by one.  Images
 // beyond N read nothing (zeros).  Channels beyond Cin re-read the last one (their filter
 // operand is zero).
-template <int NW>
+template <int NW, int BATCH = 8>
 __device__ __forceinline__ void stage_images(const int8_t* __restrict__ x, unsigned char* lds,
                                              const Geometry& g, const TileRect& tr, int bx, int c0,
                                              int wave, int lane) {
@@ -170,7 +170,7 @@ __device__ __forceinline__ void stage_images(const int8_t* __restrict__ x, unsig
   const int per_image = (64 / cpi) * ipp; // instructions per image
   const int total = tr.ipw * per_image;
   const int sub = lane / lpc, dw_lane = lane - sub * lpc;
-  constexpr int BATCH = 8;  // loads in flight per wave before the first LDS write
+  // BATCH: loads in flight per wave before the first LDS write
   for (int k0 = wave; k0 < total; k0 += NW * BATCH) {
     unsigned vals[BATCH];
     int dst[BATCH];

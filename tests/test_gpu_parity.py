@@ -492,9 +492,11 @@ def test_single_kernel_path_channel_limits(binding):
     with pytest.raises(binding.SfcError) as e:
         binding.Plan(1, 65, 16, 8, 8, path="single")  # 6x6 tiles: one chunk of 64 channels
     assert e.value.code == 2
-    with pytest.raises(binding.SfcError) as e:
-        binding.Plan(1, 129, 16, 8, 8, alg="4x4_p46", path="single")  # SFC-4: two chunks
-    assert e.value.code == 2
+    for shape in ((1, 129, 16, 28, 28),   # SFC-4: two chunks on maps of more than 16 tiles ...
+                  (1, 513, 16, 8, 8)):    # ... eight chunks on smaller ones
+        with pytest.raises(binding.SfcError) as e:
+            binding.Plan(*shape, alg="4x4_p46", path="single")
+        assert e.value.code == 2
 
 
 @pytest.mark.parametrize("name,alg", [("resnet56", a) for a in ("6x6_p88", "7x7_p132", "4x4_p46", "4x4_p49")] +
@@ -681,3 +683,36 @@ def test_single_layers_as_benchmarked(binding, name):
     y = layers.np_conv(layer, d["x"])
     assert rel_err(y, y_ref) <= F32_TOL
     layer.close()
+
+
+SINGLE_DEEP_SHAPES = [  # 256 / 512 input channels on small maps: products accumulated chunk by chunk
+    (3, 256, 72, 14, 14),   # one image (16 tiles) per workgroup, two workgroups along Cout
+    (5, 200, 64, 7, 7),     # four images per workgroup, ragged last group; four chunks, the last part empty
+    (2, 512, 40, 8, 8),     # eight chunks
+    (9, 300, 130, 4, 4),    # one tile per image: 16 images per workgroup; five chunks
+    (1, 256, 16, 13, 9),    # odd W: single-element stores
+    (2, 512, 512, 7, 7),
+]
+
+
+@pytest.mark.parametrize("alg", ["4x4_p46", "4x4_p49"])
+@pytest.mark.parametrize("shape", SINGLE_DEEP_SHAPES)
+def test_single_kernel_path_with_many_channel_chunks(binding, shape, alg):
+    x, w, xs, ws = uniform_case(shape, 770 + len(alg) + sum(shape))
+    print("case single deep", shape, alg, flush=True)
+    xc, _, _, _ = uniform_case(shape, 870 + sum(shape))
+    sx = oracle.calibrate_act_scales(xc // 2, alg)
+    sw = oracle.calibrate_filter_scales(w, alg)
+    y_ref, taps_ref = oracle.conv_requant(x, w, sx, sw, xs, ws, alg, return_taps=True)
+    y, taps = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path="single", sx=sx, sw=sw,
+                             return_taps=True)
+    assert np.array_equal(taps["U"].astype(np.int64), taps_ref["U"])
+    assert rel_err(y, y_ref) <= F32_TOL
+    y_scale = float(np.float32(max(y_ref.max(), 1e-6) / 127.0 * 0.8))
+    y8 = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path="single", out="i8", sx=sx, sw=sw,
+                        y_scale=y_scale)
+    assert check_i8_against_oracle(y8, y_ref, y_scale) < 1e-3
+    # larger maps do not fit: the path is refused
+    with pytest.raises(binding.SfcError) as e:
+        binding.Plan(1, shape[1], 16, 28, 28, alg=alg, path="single")
+    assert e.value.code == 2
