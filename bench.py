@@ -193,7 +193,7 @@ def bench_layer(args, name, torch, timer):
     from paper_2407_02913_amd import binding, layers, synth
 
     shape = synth.LAYERS[name]
-    data = synth.make_layer(shape)
+    data = synth.make_layer(shape, kernel=binding.KERNEL_SIZE[args.alg or "auto"])
     layer = layers.Layer(shape, data, out="f32", alg=args.alg or "auto", path=args.path or "auto")
     x_host = torch.from_numpy(data["x"])
     ybytes = 4 * shape.N * shape.Cout * shape.H * shape.W
