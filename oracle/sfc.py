@@ -1,4 +1,4 @@
-"""Plain numpy oracle for quantized 3x3 (and 5x5) convolution by Symbolic Fourier Convolution.
+"""Plain numpy oracle for quantized 3x3 (and 5x5, 7x7) convolution by Symbolic Fourier Convolution.
 
 TEST INFRASTRUCTURE ONLY.  This module is the slow, obviously-correct CPU
 statement of the method (arXiv 2407.02913).  It is imported by ``tests/``, by
@@ -18,6 +18,13 @@ What is the definition and what is the algorithm
 * ``sfc6_1d(6, 5)``          -- SFC-6(6x6,5x5): B^T and G as printed in Appendix A, A
                                the one matrix that fits them (the print of A is
                                unusable); re-derived by ``integrate_1d_5tap``.
+* ``sfc6_1d(4, 7)``          -- SFC-6(4x4,7x7) of Table 1: no matrices are printed; they are
+                               derived by ``integrate_1d_ten`` (the same five steps, which
+                               for 6 outputs and 5 taps reproduce Appendix A's print).
+                               Its multiplication count (184 / 196) is PARITY UNPINNED
+                               against Table 1, whose 21.99 % is no whole number of
+                               multiplications; the results are pinned by the bilinear
+                               identity, brute force and ``direct_conv``.
 * ``nested_2d``              -- the 2-D form of Eq. (1): Kronecker products,
                                10*10 = 100 multiplications per 6x6 tile.
 * ``hermitian_2d``           -- the 88-multiplication form.  Appendix A only
@@ -366,7 +373,12 @@ def sfc6_1d(m: int = 6, r: int = 3):
 
     r = 3, m = 6: B^T 10x8, G 10x3, A 10x6.  r = 3, m = 7: B^T 12x9, G 12x3, A 12x7.
     r = 5, m = 6: B^T 14x10, G 14x5, A 14x6.
+    r = 7, m = 4: B^T 14x10, G 14x7, A 14x4 (derived, not printed: ``integrate_1d_ten``).
     """
+    if r == 7:
+        if m != 4:
+            raise ValueError(m)
+        return integrate_1d_ten(4, 7)
     if r == 5:
         if m != 6:
             raise ValueError(m)
@@ -505,6 +517,66 @@ def integrate_1d_5tap():
             a[row, o] = 6
             row += 1
     assert row == 14
+    return bt, g, a, 6
+
+
+def integrate_1d_ten(m: int, r: int):
+    """B^T, G, A of an SFC-6 algorithm on ten samples, m + r - 1 = 10, from Sec. 4.1-4.2:
+    SFC-6(6,5) (Appendix A) and SFC-6(4,7) (Table 1, no matrices printed).
+
+    The five steps of ``integrate_1d``, with the window and the alignment of the printed
+    SFC-6(6,5) matrices:
+      1. forward SFT-6 (F_6) of the six inner samples x2..x7                       (Eq. DFT6)
+      2. the filter's symbolic DFT aligned on its last tap, G_k = sum_t f_t s^{k(t-(r-1))}
+      3. one a0+a1 row per complex point                                           (Eq. DFT6M)
+      4. iF_6 with the product rule's post-additions folded in; with that alignment the
+         cyclic result for output o is the one iF_6 as printed delivers at position
+         (o + r - 4) mod 6
+      5. one correction row for every (tap t, output o) whose sample x_{o+t} lies outside
+         x2..x7: (x_{o+t} minus the inner sample a multiple of six positions away) times
+         f_t, added to output o; rows ordered by (t, o)                             (Sec. 4.2)
+    For m = 4, r = 7 there are six such pairs -- (0,0) (0,1) (1,0) (5,3) (6,2) (6,3) -- so
+    B^T is the printed B^T of SFC-6(6,5) and the algorithm has 8 + 6 = 14 rows.
+    Returns (B^T, G, A numerators, 6).
+    """
+    if m + r - 1 != 10:
+        raise ValueError((m, r))
+    outside = [(t, o) for t in range(r) for o in range(m) if not 2 <= o + t <= 7]
+    rows = 8 + len(outside)
+    bt = np.zeros((rows, 10), dtype=np.int64)
+    g = np.zeros((rows, r), dtype=np.int64)
+    a = np.zeros((rows, m), dtype=np.int64)
+
+    def s_pow(n):
+        c = np.array([1, 0], dtype=np.int64)
+        for _ in range(n % 6):
+            c = np.array([-c[1], c[0] + c[1]])
+        return c
+
+    for brow, frow in {0: 0, 1: 1, 2: 2, 4: 3, 5: 4, 7: 5}.items():
+        bt[brow, 2:8] = F6[frow]
+    for k, (r0, r1) in ((1, (1, 2)), (2, (4, 5))):
+        for t in range(r):
+            c = s_pow(k * (t - (r - 1)))
+            g[r0, t], g[r1, t] = c[0], c[1]
+    g[0] = 1
+    for t in range(r):
+        g[7, t] = 1 if (t - (r - 1)) % 2 == 0 else -1
+    for r0, r1, rs in COMPLEX_GROUPS:
+        bt[rs] = bt[r0] + bt[r1]
+        g[rs] = g[r0] + g[r1]
+    rot = [(o + r - 4) % 6 for o in range(m)]
+    a[0] = IF6[0][rot]
+    a[7] = IF6[5][rot]
+    for (r0, r1, rs), (c0, c1) in zip(COMPLEX_GROUPS, ((1, 2), (3, 4))):
+        a[r0] = IF6[c0][rot] - IF6[c1][rot]
+        a[r1] = -IF6[c0][rot]
+        a[rs] = IF6[c1][rot]
+    for row, (t, o) in enumerate(outside, start=8):
+        i = o + t
+        bt[row, i], bt[row, 2 + (i - 2) % 6] = 1, -1
+        g[row, t] = 1
+        a[row, o] = 6
     return bt, g, a, 6
 
 
@@ -689,12 +761,15 @@ _ALGORITHMS = {  # name -> (2-D construction, outputs per tile edge M, filter si
     "4x4_p49": (nested4_2d, 4, 3),
     "6x6_5x5_p184": (hermitian_2d, 6, 5),
     "6x6_5x5_p196": (nested_2d, 6, 5),
+    "4x4_7x7_p184": (hermitian_2d, 4, 7),
+    "4x4_7x7_p196": (nested_2d, 4, 7),
 }
 
 
 def algorithm(name: str):
     """(B2, G2, A2 numerators, denominator) for "6x6_p88", "6x6_p100", "7x7_p132", "7x7_p144",
-    "4x4_p46", "4x4_p49" (3x3 filters) and "6x6_5x5_p184", "6x6_5x5_p196" (5x5 filters)."""
+    "4x4_p46", "4x4_p49" (3x3 filters), "6x6_5x5_p184", "6x6_5x5_p196" (5x5 filters) and
+    "4x4_7x7_p184", "4x4_7x7_p196" (7x7 filters)."""
     build, m, r = _ALGORITHMS[name]
     return build(m) if r == 3 else build(m, r)
 
