@@ -1,11 +1,12 @@
 /*
  * sfc.h -- C ABI of the MI355X (gfx950) library for quantized 3x3 convolution by
  * Symbolic Fourier Convolution, SFC-6(6x6,3x3) and SFC-6(7x7,3x3) (arXiv 2407.02913),
- * with SFC-4(4x4,3x3) and the 5x5-filter algorithm SFC-6(6x6,5x5) beside them.
+ * with SFC-4(4x4,3x3), the 5x5-filter algorithm SFC-6(6x6,5x5) and the 7x7-filter algorithm
+ * SFC-6(4x4,7x7) beside them.
  *
  * The library computes, for int8 activations x[N,Cin,H,W] and int8 filters
- * w[Cout,Cin,R,R] (R = 3, or 5 for the SFC-6(6x6,5x5) algorithms; stride 1, zero padding
- * (R-1)/2, cross-correlation),
+ * w[Cout,Cin,R,R] (R = 3, or 5 for the SFC-6(6x6,5x5) and 7 for the SFC-6(4x4,7x7)
+ * algorithms; stride 1, zero padding (R-1)/2, cross-correlation),
  *
  *      y = A^T [ (G f G^T) . (B^T x B) ] A        summed over Cin      (Eq. 1)
  *
@@ -15,7 +16,8 @@
  * of SFC-4(4x4,3x3).  Per tile and (Cin,Cout) pair it spends P = 88 / 132 / 46
  * multiplications (Hermitian form, M = 6 / 7 / 4) or P = 100 / 144 / 49 (nested form),
  * Appendix A.  SFC-6(6x6,5x5) works on 6x6 output tiles (10x10 input tiles) with
- * P = 184 (Hermitian) or 196 (nested) multiplications instead of 900.
+ * P = 184 (Hermitian) or 196 (nested) multiplications instead of 900; SFC-6(4x4,7x7) on
+ * 4x4 output tiles (the same 10x10 input tiles) with as many instead of 784.
  *
  * Conventions
  *  - "dev" pointers are device (HBM) addresses on the current HIP device, "host"
@@ -55,9 +57,8 @@ typedef enum {
 /* Which 2-D point set realizes the element-wise product of Eq. (1), Appendix A. */
 typedef enum {
   /* sfc_plan picks the tile size for 3x3 filters from the layer shape (sfc_plan_choice tells
-   * which): SFC-4's 4x4 tiles where they divide a large feature map with few channels, 7x7
-   * tiles on the 14x14 and 7x7 maps they cover exactly, 6x6 tiles otherwise; always the
-   * Hermitian point set. */
+   * which).  Requantized mode: SFC-4's 4x4 tiles, except 7x7 tiles on 14x14 and 7x7 maps
+   * with many (tile, filter) pairs; exact mode: 6x6 tiles; always the Hermitian point set. */
   SFC_ALG_AUTO = -1,
   SFC_ALG_6X6_P88 = 0,  /* SFC-6(6x6,3x3), Hermitian symmetry fully used: 88 multiplications per tile */
   SFC_ALG_6X6_P100 = 1, /* SFC-6(6x6,3x3), nested (Kronecker) form: 100 multiplications */
@@ -72,14 +73,23 @@ typedef enum {
    * B^T and G are the printed ones; the printed A (seven columns for six outputs) is
    * replaced by the one matrix that fits them.  Staged and fused paths. */
   SFC_ALG_6X6_5X5_P184 = 6,
-  SFC_ALG_6X6_5X5_P196 = 7
+  SFC_ALG_6X6_5X5_P196 = 7,
+  /* SFC-6(4x4,7x7) (Table 1, last row): 7x7 filters w[Cout,Cin,7,7], zero padding 3, 4x4
+   * output tiles from the same 10x10 input tiles and the same input transform as
+   * SFC-6(6x6,5x5).  The paper prints no matrices for it; G and A follow from the steps of
+   * Sec. 4.1-4.2 that reproduce the printed SFC-6(6x6,5x5) ones (filter DFT
+   * G_k = sum_r f_r s^(k r), six correction terms).  184 multiplications per tile in the
+   * Hermitian form, 196 nested, of 784 (Table 1's 21.99 % is no whole number of
+   * multiplications and is not reproduced).  Staged and fused paths. */
+  SFC_ALG_4X4_7X7_P184 = 8,
+  SFC_ALG_4X4_7X7_P196 = 9
 } sfc_alg;
 
 typedef enum {
   /* Transform domain kept in exact integers (int16 operands, int32 sums): the
    * result equals direct convolution bit for bit (Sec. 5.1 assumes the
-   * transforms accurate).  int32 sums are guaranteed for Cin <= 404 (3x3 filters) and
-   * Cin <= 145 (5x5 filters). */
+   * transforms accurate).  int32 sums are guaranteed for Cin <= 404 (3x3 filters),
+   * Cin <= 145 (5x5 filters) and Cin <= 74 (7x7 filters). */
   SFC_MODE_EXACT = 0,
   /* Transform-domain operands rounded to int8 with one scale per point for the
    * activations and one per (point, Cout) for the filters (Sec. 5, the
@@ -127,7 +137,7 @@ typedef struct {
 
 /* Exact mode keeps every sum in 32 bits.  The sums an output is made of (kDen = 36, or 16 for
  * SFC-4, times the convolution sum) are guaranteed to fit for Cin <= 404 with 3x3 filters and
- * Cin <= 145 with 5x5 filters; sfc_plan refuses more channels (SFC_EUNSUPPORTED) unless this
+ * Cin <= 145 with 5x5 and Cin <= 74 with 7x7 filters; sfc_plan refuses more channels (SFC_EUNSUPPORTED) unless this
  * flag is set.  The arithmetic runs modulo 2^32 (unsigned, so wrap-around is defined): with
  * the SFC-6 forms an output is exact whenever its kDen-fold sum lies inside the int32 range,
  * whatever the intermediate sums do (the only division on the way, by 3, is a multiplication
@@ -155,7 +165,7 @@ sfc_status sfc_plan_sizes(const sfc_plan_t* plan, size_t* filter_bytes, size_t* 
 /* Requantized mode: the transform-domain scales of Sec. 5, copied into the plan.
  * sx_host[P]: one activation scale per point (s_Tx).  sw_host[P*Cout], laid out
  * [P][Cout]: one filter scale per point and output channel (s_Tf).  All > 0.
- * Point order, with R = 10 (M = 6), 12 (M = 7), 7 (M = 4) or 14 (5x5 filter) rows in the
+ * Point order, with R = 10 (M = 6), 12 (M = 7), 7 (M = 4) or 14 (5x5 and 7x7 filters) rows in the
  * printed 1-D matrices: nested form, p = R*p1 + p2 (p1 vertical); Hermitian form, first the nested
  * points that are not complex x complex (R*R - 36 of them, R*R - 9 for M = 4), in that
  * same order, then for (k1,k2) = (1,1),(1,2),(2,1),(2,2) (only (1,1) for M = 4) the six

@@ -18,11 +18,12 @@ SFC_OK = 0
 STATUS_NAMES = {0: "SFC_OK", 1: "SFC_EINVAL", 2: "SFC_EUNSUPPORTED", 3: "SFC_ENOMEM",
                 4: "SFC_ENOTREADY", 5: "SFC_EHIP", 6: "SFC_EWORKSPACE"}
 ALG = {"auto": -1, "6x6_p88": 0, "6x6_p100": 1, "7x7_p132": 2, "7x7_p144": 3, "4x4_p46": 4, "4x4_p49": 5,
-       "6x6_5x5_p184": 6, "6x6_5x5_p196": 7}
+       "6x6_5x5_p184": 6, "6x6_5x5_p196": 7, "4x4_7x7_p184": 8, "4x4_7x7_p196": 9}
 ACT_GRANULARITY = {"tensor": 0, "point": 1}
 FILTER_GRANULARITY = {"channel": 0, "point": 1, "channel_point": 2}
 ALG_NAME = {v: k for k, v in ALG.items()}
-KERNEL_SIZE = {name: 5 if "5x5" in name else 3 for name in ALG}  # filter edge R
+KERNEL_SIZE = {name: 7 if name.startswith("4x4_7x7") else 5 if "5x5" in name else 3
+               for name in ALG}  # filter edge R
 MODE = {"exact": 0, "requant": 1}
 OUT = {"f32": 0, "i32": 1, "i8": 2}
 PATH = {"auto": -1, "staged": 0, "fused": 1, "single": 2}

@@ -87,8 +87,7 @@ bool make_geometry(const sfc_conv_desc& d, Geometry* out) {
   Geometry g;
   g.N = d.N; g.Cin = d.Cin; g.Cout = d.Cout; g.H = d.H; g.W = d.W;
   g.alg = d.alg;
-  const int mt = (d.alg == SFC_ALG_7X7_P132 || d.alg == SFC_ALG_7X7_P144) ? 7
-                 : (d.alg == SFC_ALG_4X4_P46 || d.alg == SFC_ALG_4X4_P49) ? 4 : 6;
+  const int mt = sfc::alg_tile(d.alg);
   g.th = (d.H + mt - 1) / mt;
   g.tw = (d.W + mt - 1) / mt;
   const int64_t strips = (int64_t)d.N * g.th;
@@ -99,8 +98,7 @@ bool make_geometry(const sfc_conv_desc& d, Geometry* out) {
   g.Tp = (int)((T + 15) / 16 * 16);
   g.Cp = (d.Cin + 63) / 64 * 64;
   g.Kp = (d.Cout + 15) / 16 * 16;
-  static const int kPoints[8] = {88, 100, 132, 144, 46, 49, 184, 196};
-  g.P = kPoints[d.alg];
+  g.P = sfc::alg_points(d.alg);
   g.qmax = (float)((1 << ((d.transform_bits ? d.transform_bits : 8) - 1)) - 1);
   *out = g;
   return true;
@@ -164,7 +162,7 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   *out = nullptr;
   sfc_conv_desc d = *desc;
   if (d.N <= 0 || d.Cin <= 0 || d.Cout <= 0 || d.H <= 0 || d.W <= 0) return SFC_EINVAL;
-  if (d.alg < SFC_ALG_AUTO || d.alg > SFC_ALG_6X6_5X5_P196) return SFC_EINVAL;
+  if (d.alg < SFC_ALG_AUTO || d.alg > SFC_ALG_4X4_7X7_P196) return SFC_EINVAL;
   if (d.mode != SFC_MODE_EXACT && d.mode != SFC_MODE_REQUANT_I8) return SFC_EINVAL;
   if (d.out != SFC_OUT_F32 && d.out != SFC_OUT_I32 && d.out != SFC_OUT_I8_RELU) return SFC_EINVAL;
   if (d.path < SFC_PATH_AUTO || d.path > SFC_PATH_SINGLE) return SFC_EINVAL;
@@ -180,7 +178,7 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
     return SFC_EUNSUPPORTED;
   if (d.alg == SFC_ALG_AUTO) d.alg = choose_alg(d);
   if (d.mode == SFC_MODE_EXACT && !(d.flags & SFC_FLAG_EXACT_WIDE) &&
-      d.Cin > (d.alg >= SFC_ALG_6X6_5X5_P184 ? 145 : 404))
+      d.Cin > (d.alg >= SFC_ALG_4X4_7X7_P184 ? 74 : d.alg >= SFC_ALG_6X6_5X5_P184 ? 145 : 404))
     return SFC_EUNSUPPORTED;
 
   Geometry g;

@@ -1,11 +1,14 @@
 // Launch side of the fused product + output-transform kernel (sfc_fused_quad.hpp): limits,
 // filter-operand size and the dispatch over algorithm, channel chunks and output type.  The
-// 5x5-filter algorithms are instantiated in sfc_fused_quad_5tap.hip.
+// 5x5- and 7x7-filter algorithms are instantiated in sfc_fused_quad_5tap.hip and
+// sfc_fused_quad_7tap.hip.
 #include "sfc_fused_quad.hpp"
 
 namespace sfc {
 
 hipError_t launch_fused_quad_5tap(int out, const Geometry& g, const void* V, const FilterViews& f,
+                                  float x_scale, float inv_y, void* y, hipStream_t s, bool prepare);
+hipError_t launch_fused_quad_7tap(int out, const Geometry& g, const void* V, const FilterViews& f,
                                   float x_scale, float inv_y, void* y, hipStream_t s, bool prepare);
 
 bool fused_quad_supported(const Geometry& g) {
@@ -34,6 +37,8 @@ hipError_t launch_fused_quad(int out, const Geometry& g, const void* V, const Fi
     case 5: return launch_quad_alg<5>(out, g, V, f, x_scale, inv_y, y, s, prepare);
     case 6:
     case 7: return launch_fused_quad_5tap(out, g, V, f, x_scale, inv_y, y, s, prepare);
+    case 8:
+    case 9: return launch_fused_quad_7tap(out, g, V, f, x_scale, inv_y, y, s, prepare);
   }
   return hipErrorInvalidValue;
 }

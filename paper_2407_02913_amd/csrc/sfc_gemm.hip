@@ -299,6 +299,8 @@ hipError_t launch_output_sums(int out, const Geometry& g, const int32_t* M, cons
     case 5: return launch_sums_alg<5>(out, g, M, f, x_scale, inv_y, y, s, prepare);
     case 6: return launch_sums_alg<6>(out, g, M, f, x_scale, inv_y, y, s, prepare);
     case 7: return launch_sums_alg<7>(out, g, M, f, x_scale, inv_y, y, s, prepare);
+    case 8: return launch_sums_alg<8>(out, g, M, f, x_scale, inv_y, y, s, prepare);
+    case 9: return launch_sums_alg<9>(out, g, M, f, x_scale, inv_y, y, s, prepare);
   }
   return hipErrorInvalidValue;
 }

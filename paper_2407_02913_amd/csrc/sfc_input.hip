@@ -163,6 +163,8 @@ hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V
     case 5: return launch_input_i8_alg<5>(g, ip, x, V, inv_sx, intab, s, prepare);
     case 6: return launch_input_i8_alg<6>(g, ip, x, V, inv_sx, intab, s, prepare);
     case 7: return launch_input_i8_alg<7>(g, ip, x, V, inv_sx, intab, s, prepare);
+    case 8: return launch_input_i8_alg<8>(g, ip, x, V, inv_sx, intab, s, prepare);
+    case 9: return launch_input_i8_alg<9>(g, ip, x, V, inv_sx, intab, s, prepare);
   }
   return hipErrorInvalidValue;
 }

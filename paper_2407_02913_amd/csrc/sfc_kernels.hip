@@ -393,6 +393,8 @@ static hipError_t launch_input_alg(const Geometry& g, const int8_t* x, void* V, 
     case 5: return launch_input_impl<5, MODE>(g, x, V, inv_sx, maxima, s);
     case 6: return launch_input_impl<6, MODE>(g, x, V, inv_sx, maxima, s);
     case 7: return launch_input_impl<7, MODE>(g, x, V, inv_sx, maxima, s);
+    case 8: return launch_input_impl<8, MODE>(g, x, V, inv_sx, maxima, s);
+    case 9: return launch_input_impl<9, MODE>(g, x, V, inv_sx, maxima, s);
   }
   return hipErrorInvalidValue;
 }
@@ -445,6 +447,8 @@ hipError_t launch_filter_absmax(const Geometry& g, const int8_t* w, int32_t* max
     case 5: SFC_LAUNCH_FMAX(5); break;
     case 6: SFC_LAUNCH_FMAX(6); break;
     case 7: SFC_LAUNCH_FMAX(7); break;
+    case 8: SFC_LAUNCH_FMAX(8); break;
+    case 9: SFC_LAUNCH_FMAX(9); break;
     default: return hipErrorInvalidValue;
   }
 #undef SFC_LAUNCH_FMAX
@@ -471,6 +475,8 @@ hipError_t launch_filter_transform(int mode, const Geometry& g, const int8_t* w,
     case 5: SFC_LAUNCH_FT(5); break;
     case 6: SFC_LAUNCH_FT(6); break;
     case 7: SFC_LAUNCH_FT(7); break;
+    case 8: SFC_LAUNCH_FT(8); break;
+    case 9: SFC_LAUNCH_FT(9); break;
     default: return hipErrorInvalidValue;
   }
 #undef SFC_LAUNCH_FT
@@ -516,6 +522,8 @@ hipError_t launch_output_transform(int mode, int out, const Geometry& g, const i
     case 5: return launch_output_alg<5>(mode, out, g, M, f, x_scale, inv_y, y, s);
     case 6: return launch_output_alg<6>(mode, out, g, M, f, x_scale, inv_y, y, s);
     case 7: return launch_output_alg<7>(mode, out, g, M, f, x_scale, inv_y, y, s);
+    case 8: return launch_output_alg<8>(mode, out, g, M, f, x_scale, inv_y, y, s);
+    case 9: return launch_output_alg<9>(mode, out, g, M, f, x_scale, inv_y, y, s);
   }
   return hipErrorInvalidValue;
 }

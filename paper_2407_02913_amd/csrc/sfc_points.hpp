@@ -1,4 +1,4 @@
-// Add networks of SFC-6(6x6,3x3), SFC-6(7x7,3x3), SFC-4(4x4,3x3) and SFC-6(6x6,5x5):
+// Add networks of SFC-6(6x6,3x3), SFC-6(7x7,3x3), SFC-4(4x4,3x3), SFC-6(6x6,5x5) and SFC-6(4x4,7x7):
 // forward transforms to the multiplication points and the output transform back, as
 // straight-line code.
 //
@@ -22,6 +22,13 @@
 //   c9  x8 - x2 with f3 -> output 5     c10 x8 - x2 with f4 -> output 4     c11 x9 - x3 with f4 -> output 5
 // With this alignment the inverse symbolic DFT delivers the cyclic result rotated by one
 // position.  NC = 12 components, NR = 14 rows, 196 nested / 184 Hermitian points.
+// SFC-6(4x4,7x7) (Table 1; derived with the same steps): the same ten samples, window and
+// differences on the input side, so the same input transform; the filter's symbolic DFT is
+// G_k = sum_r f_r s^(k r) (aligned on the seventh tap, s^6 = 1); six corrections:
+//   c6  x0 - x6 with f0 -> output 0     c7  x1 - x7 with f0 -> output 1     c8  x1 - x7 with f1 -> output 0
+//   c9  x8 - x2 with f5 -> output 3     c10 x8 - x2 with f6 -> output 2     c11 x9 - x3 with f6 -> output 3
+// and the inverse delivers the cyclic result rotated by three positions.  Also NC = 12,
+// NR = 14, 196 / 184 points.
 // In 2-D the components form an NC x NC array C[a][b] (a: vertical axis).
 //   nested   : every (r_a, r_b) pair, NR^2 points (100 / 144).
 //   Hermitian: the pairs that are not complex x complex, then for each pair of
@@ -47,14 +54,15 @@ namespace sfc {
 //
 // ALG: 0 = 6x6 Hermitian (88), 1 = 6x6 nested (100), 2 = 7x7 Hermitian (132), 3 = 7x7 nested (144),
 //      4 = 4x4 Hermitian (46), 5 = 4x4 nested (49), all for 3x3 filters;
-//      6 = 6x6 outputs with a 5x5 filter, Hermitian (184), 7 = the same, nested (196)
+//      6 = 6x6 outputs with a 5x5 filter, Hermitian (184), 7 = the same, nested (196);
+//      8 = 4x4 outputs with a 7x7 filter, Hermitian (184), 9 = the same, nested (196)
 template <int ALG>
 struct AlgTraits {
-  static_assert(ALG >= 0 && ALG < 8, "unknown algorithm");
+  static_assert(ALG >= 0 && ALG < 10, "unknown algorithm");
   static constexpr int kFamily = (ALG < 4 || ALG >= 6) ? 6 : 4;  // points of the symbolic DFT
   static constexpr bool kHermitian = ALG % 2 == 0;
-  static constexpr int M = ALG < 2 ? 6 : ALG < 4 ? 7 : ALG < 6 ? 4 : 6;  // outputs per tile edge
-  static constexpr int R = ALG < 6 ? 3 : 5;                              // filter taps per axis
+  static constexpr int M = ALG < 2 ? 6 : ALG < 4 ? 7 : ALG < 6 ? 4 : ALG < 8 ? 6 : 4;  // outputs per tile edge
+  static constexpr int R = ALG < 6 ? 3 : ALG < 8 ? 5 : 7;                // filter taps per axis
   static constexpr int PAD = (R - 1) / 2;                                // zero padding
   static constexpr int NI = M + R - 1;                                   // input samples per tile edge
   static constexpr int NC = ALG < 2 ? 8 : ALG < 4 ? 10 : ALG < 6 ? 6 : 12;  // components per axis
@@ -65,13 +73,15 @@ struct AlgTraits {
   static constexpr int kDen = kFamily == 6 ? 36 : 16;  // the output transform yields kDen * y
 };
 
-constexpr int kNumAlgs = 8;
+constexpr int kNumAlgs = 10;
 __host__ __device__ constexpr int alg_points(int alg) {
   return alg == 0 ? 88 : alg == 1 ? 100 : alg == 2 ? 132 : alg == 3 ? 144 : alg == 4 ? 46
-       : alg == 5 ? 49 : alg == 6 ? 184 : 196;
+       : alg == 5 ? 49 : (alg == 6 || alg == 8) ? 184 : 196;
 }
-__host__ __device__ constexpr int alg_tile(int alg) { return alg < 2 ? 6 : alg < 4 ? 7 : alg < 6 ? 4 : 6; }
-__host__ __device__ constexpr int alg_taps(int alg) { return alg < 6 ? 3 : 5; }
+__host__ __device__ constexpr int alg_tile(int alg) {
+  return alg < 2 ? 6 : alg < 4 ? 7 : alg < 6 ? 4 : alg < 8 ? 6 : 4;
+}
+__host__ __device__ constexpr int alg_taps(int alg) { return alg < 6 ? 3 : alg < 8 ? 5 : 7; }
 
 // ---- row bookkeeping ----------------------------------------------------------
 
@@ -177,8 +187,8 @@ struct Order {
 template <int NI, int NC, typename T>
 SFC_HD void fwd_input(const T (&x)[NI], T (&c)[NC]) {
   if constexpr (NC == 12) {
-    // 5-tap filter: ten samples, the inner six are x2..x7
-    static_assert(NI == 10, "SFC-6(6,5) takes ten samples");
+    // 5-tap and 7-tap filters: ten samples, the inner six are x2..x7
+    static_assert(NI == 10, "SFC-6(6,5) and SFC-6(4,7) take ten samples");
     const T e0 = x[2] + x[5], e1 = x[3] + x[6], e2 = x[4] + x[7];
     const T d0 = x[2] - x[5], d1 = x[3] - x[6], d2 = x[4] - x[7];
     c[0] = e0 + e1 + e2;
@@ -225,7 +235,24 @@ SFC_HD void fwd_input(const T (&x)[NI], T (&c)[NC]) {
 // R filter taps -> NC components (rows of Appendix A's G without the sum rows).
 template <int R, int NC, typename T>
 SFC_HD void fwd_filter(const T (&f)[R], T (&c)[NC]) {
-  if constexpr (NC == 12) {
+  if constexpr (NC == 12 && R == 7) {
+    // G_k = sum_r f_r s^(k r): s^0..s^6 = 1, s, s - 1, -1, -s, 1 - s, 1
+    const T a = f[0] + f[6], b = f[2] + f[5], d = f[1] + f[4];
+    const T e = f[2] - f[5], h = f[1] - f[4];
+    c[0] = a + b + d + f[3];
+    c[1] = a - f[3] - e;
+    c[2] = h + e;
+    c[3] = a + f[3] - d;
+    c[4] = d - b;
+    c[5] = a - f[3] + e - h;
+    c[6] = f[0];
+    c[7] = f[0];
+    c[8] = f[1];
+    c[9] = f[5];
+    c[10] = f[6];
+    c[11] = f[6];
+    return;
+  } else if constexpr (NC == 12) {
     static_assert(R == 5, "SFC-6(6,5) takes five taps");
     const T p = f[3] + f[4], q = f[0] + f[1];
     c[0] = q + f[2] + p;
@@ -402,10 +429,11 @@ SFC_HD void hermitian_collapse(const T (&m)[6], T& o00, T& o10, T& o01, T& o11) 
 // DFT-2 x DFT-3 structure, plus the correction products with weight 6).  For
 // M = 7 the seventh output is the cyclic output 0 with its own two corrections.
 // For the 5-tap form the cyclic result arrives rotated by one position and six
-// corrections are added.
-SFC_HD constexpr int inv_count(int nc) { return nc == 10 ? 7 : 6; }
-template <int NC, typename T>
-SFC_HD void inv_outputs(const T (&c)[NC], T (&y)[inv_count(NC)]) {
+// corrections are added; for the 7-tap form (four outputs) rotated by three positions.
+template <int NC, int MO, typename T>
+SFC_HD void inv_outputs(const T (&c)[NC], T (&y)[MO]) {
+  static_assert((NC == 8 && MO == 6) || (NC == 10 && MO == 7) || (NC == 12 && (MO == 6 || MO == 4)),
+                "components and outputs of one of the SFC-6 algorithms");
   // even harmonics k = 0, 2 repeat with period 3; odd harmonics k = 1, 3 flip sign
   const T t = c[0] - c[3];
   const T e0 = t - c[4] - c[4];
@@ -414,23 +442,28 @@ SFC_HD void inv_outputs(const T (&c)[NC], T (&y)[inv_count(NC)]) {
   const T d0 = c[1] - c[2] - c[5];
   const T d1 = c[5] - c[1] - c[2] - c[2];
   const T d2 = -c[1] - c[1] - c[2] - c[5];
-  if constexpr (NC == 12) {
+  if constexpr (NC == 12 && MO == 4) {
+    y[0] = e0 - d0 + T(6) * (c[6] + c[8]);
+    y[1] = e1 - d1 + T(6) * c[7];
+    y[2] = e2 - d2 + T(6) * c[10];
+    y[3] = e0 + d0 + T(6) * (c[9] + c[11]);
+  } else if constexpr (NC == 12) {
     y[0] = e1 + d1 + T(6) * (c[6] + c[8]);
     y[1] = e2 + d2 + T(6) * c[7];
     y[2] = e0 - d0;
     y[3] = e1 - d1;
     y[4] = e2 - d2 + T(6) * c[10];
     y[5] = e0 + d0 + T(6) * (c[9] + c[11]);
-    return;
+  } else {
+    const T y0 = e0 + d0;
+    y[0] = y0 + T(6) * c[6];
+    y[1] = e1 + d1;
+    y[2] = e2 + d2;
+    y[3] = e0 - d0;
+    y[4] = e1 - d1;
+    y[5] = e2 - d2 + T(6) * c[7];
+    if constexpr (NC == 10) y[6] = y0 + T(6) * (c[8] + c[9]);
   }
-  const T y0 = e0 + d0;
-  y[0] = y0 + T(6) * c[6];
-  y[1] = e1 + d1;
-  y[2] = e2 + d2;
-  y[3] = e0 - d0;
-  y[4] = e1 - d1;
-  y[5] = e2 - d2 + T(6) * c[7];
-  if constexpr (NC == 10) y[6] = y0 + T(6) * (c[8] + c[9]);
 }
 
 template <typename T>

@@ -214,6 +214,8 @@ hipError_t launch_repack_filter(const Geometry& g, int filters, const void* U, v
     case 5: hipLaunchKernelGGL(repack_filter_kernel<5>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
     case 6: hipLaunchKernelGGL(repack_filter_kernel<6>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
     case 7: hipLaunchKernelGGL(repack_filter_kernel<7>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
+    case 8: hipLaunchKernelGGL(repack_filter_kernel<8>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
+    case 9: hipLaunchKernelGGL(repack_filter_kernel<9>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)Uf, g); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -233,6 +235,8 @@ void single_point_order(int alg, int* pt /*[P rounded up to a multiple of 4]*/) 
     case 5: { constexpr Order<5> o{}; copy(o); break; }
     case 6: { constexpr Order<6> o{}; copy(o); break; }
     case 7: { constexpr Order<7> o{}; copy(o); break; }
+    case 8: { constexpr Order<8> o{}; copy(o); break; }
+    case 9: { constexpr Order<9> o{}; copy(o); break; }
     default: break;
   }
 }

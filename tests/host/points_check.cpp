@@ -1,7 +1,8 @@
 // Host-side dump of the linear maps realized by the kernels' add networks
 // (sfc_points.hpp), so that a CPU test can compare them with the oracle's
 // matrices.  Prints, for every ALG (0: 6x6/88, 1: 6x6/100, 2: 7x7/132, 3: 7x7/144,
-// 4: 4x4/46, 5: 4x4/49, 6: 6x6 with 5x5 filter/184, 7: the same/196):
+// 4: 4x4/46, 5: 4x4/49, 6: 6x6 with 5x5 filter/184, 7: the same/196, 8: 4x4 with 7x7
+// filter/184, 9: the same/196):
 //   B <alg> <p> <NI*NI ints>   input transform row p  (impulse responses)
 //   G <alg> <p> <R*R ints>     filter transform row p
 //   A <alg> <p> <M*M ints>     output transform row p (times 36; times 16 for 4x4)
@@ -91,5 +92,7 @@ int main() {
   dump<5>();
   dump<6>();
   dump<7>();
+  dump<8>();
+  dump<9>();
   return 0;
 }

@@ -179,13 +179,14 @@ def test_gpu_calibration_matches_oracle(binding, alg):
     plan.close()
 
 
-ALGS_5X5 = ["6x6_5x5_p184", "6x6_5x5_p196"]  # SFC-6(6x6,5x5), Appendix A: staged and fused paths
+# SFC-6(6x6,5x5) (Appendix A) and SFC-6(4x4,7x7) (Table 1): staged and fused paths
+ALGS_5X5 = ["6x6_5x5_p184", "6x6_5x5_p196", "4x4_7x7_p184", "4x4_7x7_p196"]
 
 
 @pytest.mark.parametrize("alg", ALGS_5X5)
 @pytest.mark.parametrize("shape", SMALL_SHAPES)
 def test_5x5_exact_mode_taps_and_sums_bit_exact(binding, shape, alg):
-    x, w, xs, ws = uniform_case(shape, 1300 + len(alg) + sum(shape), r=5)
+    x, w, xs, ws = uniform_case(shape, 1300 + len(alg) + sum(shape), r=binding.KERNEL_SIZE[alg])
     print("case 5x5 exact", shape, alg, flush=True)
     acc_ref, taps_ref = oracle.conv_exact(x, w, alg, return_taps=True)
     assert np.array_equal(acc_ref, oracle.direct_conv(x, w))
@@ -200,9 +201,9 @@ def test_5x5_exact_mode_taps_and_sums_bit_exact(binding, shape, alg):
 @pytest.mark.parametrize("alg", ALGS_5X5)
 @pytest.mark.parametrize("shape", SMALL_SHAPES)
 def test_5x5_requant_mode_taps_bit_exact_and_output_close(binding, shape, alg):
-    x, w, xs, ws = uniform_case(shape, 1400 + len(alg) + sum(shape), r=5)
+    x, w, xs, ws = uniform_case(shape, 1400 + len(alg) + sum(shape), r=binding.KERNEL_SIZE[alg])
     print("case 5x5 requant", shape, alg, flush=True)
-    xc, _, _, _ = uniform_case(shape, 1500 + sum(shape), r=5)
+    xc, _, _, _ = uniform_case(shape, 1500 + sum(shape))
     sx = oracle.calibrate_act_scales(xc // 2, alg)
     sw = oracle.calibrate_filter_scales(w, alg)
     y_ref, taps_ref = oracle.conv_requant(x, w, sx, sw, xs, ws, alg, return_taps=True)
@@ -222,7 +223,7 @@ def test_5x5_calibration_int8_output_and_limits(binding, alg):
     import torch
 
     shape = (4, 24, 20, 14, 10)
-    d = synth.make_layer(synth.LayerShape("cal5", *shape, "relu", True, 2), kernel=5)
+    d = synth.make_layer(synth.LayerShape("cal5", *shape, "relu", True, 2), kernel=binding.KERNEL_SIZE[alg])
     print("case 5x5 calibration", alg, flush=True)
     for bits in (8, 4):
         qmax = 2 ** (bits - 1) - 1
@@ -250,13 +251,14 @@ def test_5x5_calibration_int8_output_and_limits(binding, alg):
         assert e.value.code == 2
 
 
-def test_5x5_full_size_against_oracle(binding):
-    """A 5x5 layer on the resnet28 geometry (128 -> 128 channels, 28x28, 64 images): every tap
-    and every output element against the oracle, and the exact mode against direct convolution."""
+@pytest.mark.parametrize("alg", ["6x6_5x5_p184", "4x4_7x7_p184"])
+def test_5x5_full_size_against_oracle(binding, alg):
+    """A 5x5 (7x7) layer on the resnet28 geometry (128 -> 128 channels, 28x28, 64 images): every
+    tap and every output element against the oracle, and the exact mode against direct
+    convolution (7x7 filters: on the first 64 input channels, the range exact mode guarantees)."""
     shape = synth.LAYERS["resnet28"]
-    alg = "6x6_5x5_p184"
     print("case 5x5 full", alg, flush=True)
-    d = synth.make_layer(shape, kernel=5)
+    d = synth.make_layer(shape, kernel=binding.KERNEL_SIZE[alg])
     sx = oracle.calibrate_act_scales(d["x_calib"], alg)
     sw = oracle.calibrate_filter_scales(d["w"], alg)
     y_ref, taps_ref = oracle.conv_requant(d["x"], d["w"], sx, sw, d["x_scale"], d["w_scale"], alg,
@@ -270,8 +272,11 @@ def test_5x5_full_size_against_oracle(binding):
                               path="fused", sx=sx, sw=sw, return_taps=True)
     assert np.array_equal(taps["V"].astype(np.int64), taps_ref["V"])
     assert rel_err(yf, y_ref) <= F32_TOL
-    acc = binding.conv2d(d["x"], d["w"], d["x_scale"], d["w_scale"], mode="exact", alg=alg, out="i32")
-    assert np.array_equal(acc.astype(np.int64), oracle.direct_conv(d["x"], d["w"]))
+    xe, we = d["x"], d["w"]
+    if binding.KERNEL_SIZE[alg] == 7:
+        xe, we = np.ascontiguousarray(xe[:16, :64]), np.ascontiguousarray(we[:, :64])
+    acc = binding.conv2d(xe, we, d["x_scale"], d["w_scale"], mode="exact", alg=alg, out="i32")
+    assert np.array_equal(acc.astype(np.int64), oracle.direct_conv(xe, we))
 
 
 WIDE_SHAPES = [  # rows too wide for whole-strip staging in the generic input kernel
@@ -281,7 +286,7 @@ WIDE_SHAPES = [  # rows too wide for whole-strip staging in the generic input ke
 ]
 
 
-@pytest.mark.parametrize("alg", ["6x6_p88", "7x7_p144", "4x4_p46", "6x6_5x5_p184"])
+@pytest.mark.parametrize("alg", ["6x6_p88", "7x7_p144", "4x4_p46", "6x6_5x5_p184", "4x4_7x7_p196"])
 @pytest.mark.parametrize("shape", WIDE_SHAPES)
 def test_wide_rows_exact_calibration_and_requant(binding, shape, alg):
     import torch
@@ -411,9 +416,9 @@ def test_fused_path_matches_oracle(binding, shape, alg):
 @pytest.mark.parametrize("alg", ALGS_5X5)
 @pytest.mark.parametrize("shape", FUSED_SHAPES)
 def test_5x5_fused_path_matches_oracle(binding, shape, alg):
-    x, w, xs, ws = uniform_case(shape, 1600 + len(alg) + sum(shape), r=5)
+    x, w, xs, ws = uniform_case(shape, 1600 + len(alg) + sum(shape), r=binding.KERNEL_SIZE[alg])
     print("case 5x5 fused", shape, alg, flush=True)
-    xc, _, _, _ = uniform_case(shape, 1700 + sum(shape), r=5)
+    xc, _, _, _ = uniform_case(shape, 1700 + sum(shape))
     sx = oracle.calibrate_act_scales(xc // 2, alg)
     sw = oracle.calibrate_filter_scales(w, alg)
     y_ref, taps_ref = oracle.conv_requant(x, w, sx, sw, xs, ws, alg, return_taps=True)

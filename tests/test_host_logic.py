@@ -94,7 +94,7 @@ def test_plan_sizes_and_counts(lib):
 @pytest.mark.parametrize(
     "kw,code",
     [
-        (dict(N=0), 1), (dict(Cin=-1), 1), (dict(H=0), 1), (dict(alg=8), 1), (dict(alg=-2), 1),
+        (dict(N=0), 1), (dict(Cin=-1), 1), (dict(H=0), 1), (dict(alg=10), 1), (dict(alg=-2), 1),
         (dict(mode=2), 1), (dict(out=5), 1), (dict(path=3), 1), (dict(path=-2), 1),
         (dict(per_channel_wscale=2), 1), (dict(flags=2), 1),
         (dict(transform_bits=1), 1), (dict(transform_bits=9), 1),
@@ -102,8 +102,9 @@ def test_plan_sizes_and_counts(lib):
         (dict(out=1, mode=1), 2),  # raw integer output only in exact mode
         (dict(path=1, mode=0), 2),  # fused path is the requantized one
         (dict(W=5000), 2),
-        # exact mode keeps 32-bit sums: guaranteed up to 404 channels (3x3), 145 (5x5 filters)
-        (dict(mode=0, Cin=405), 2), (dict(mode=0, alg=6, Cin=146), 2),
+        # exact mode keeps 32-bit sums: guaranteed up to 404 channels (3x3), 145 (5x5 filters),
+        # 74 (7x7 filters)
+        (dict(mode=0, Cin=405), 2), (dict(mode=0, alg=6, Cin=146), 2), (dict(mode=0, alg=8, Cin=75), 2),
         (dict(Cout=65521), 2),  # one workgroup row per (padded) filter must fit a launch grid
     ],
 )
@@ -113,7 +114,8 @@ def test_plan_rejects_bad_descriptions(lib, kw, code):
 
 
 def test_exact_mode_channel_bound_and_its_opt_in(lib):
-    for kw in (dict(mode=0, Cin=404), dict(mode=0, alg=6, Cin=145), dict(mode=0, Cin=512, flags=1),
+    for kw in (dict(mode=0, Cin=404), dict(mode=0, alg=6, Cin=145), dict(mode=0, alg=9, Cin=74),
+               dict(mode=0, Cin=512, flags=1),
                dict(mode=1, Cin=512)):
         st, h = plan_status(lib, make_desc(**kw))
         assert st == 0, kw
@@ -226,10 +228,11 @@ def kernel_maps(tmp_path_factory):
 
 @pytest.mark.parametrize("alg_id,alg", [(0, "6x6_p88"), (1, "6x6_p100"), (2, "7x7_p132"), (3, "7x7_p144"),
                                         (4, "4x4_p46"), (5, "4x4_p49"),
-                                        (6, "6x6_5x5_p184"), (7, "6x6_5x5_p196")])
+                                        (6, "6x6_5x5_p184"), (7, "6x6_5x5_p196"),
+                                        (8, "4x4_7x7_p184"), (9, "4x4_7x7_p196")])
 def test_kernel_add_networks_realize_the_oracle_matrices(kernel_maps, alg_id, alg):
     b2, g2, a2, den = oracle.algorithm(alg)
-    assert den == (16 if alg.startswith("4x4") else 36)
+    assert den == (16 if alg in ("4x4_p46", "4x4_p49") else 36)
     assert np.array_equal(kernel_maps[("B", alg_id)], b2)
     assert np.array_equal(kernel_maps[("G", alg_id)], g2)
     assert np.array_equal(kernel_maps[("A", alg_id)], a2)
