@@ -39,6 +39,9 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+#include <utility>
+
 // host + device so that the add networks can also be checked on the CPU
 #define SFC_HD __host__ __device__ __forceinline__
 
@@ -677,6 +680,26 @@ SFC_HD void output_transform(G&& get, T (&out)[AlgTraits<ALG>::M][AlgTraits<ALG>
 
 // ---- output transform, streaming form ------------------------------------------
 
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N-1>): a loop whose index is a
+// compile-time constant inside the body
+template <typename F, int... I>
+SFC_HD void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+SFC_HD void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+// The product at processing position J: next(integral_constant<int, J>) if the source takes
+// its position as a compile-time constant, else next() (sources that count for themselves).
+template <int J, typename F>
+SFC_HD auto take_product(F&& next) {
+  if constexpr (std::is_invocable_v<F, std::integral_constant<int, J>>)
+    return next(std::integral_constant<int, J>{});
+  else
+    return next();
+}
+
 // Consumes the P products of one (tile, filter) pair in the processing order of
 // Order<ALG> (next() returns the following product, already scaled) and leaves
 // z[b][o1]: horizontal component b, vertical output o1, times 6.  Each group
@@ -687,14 +710,16 @@ SFC_HD void output_transform(G&& get, T (&out)[AlgTraits<ALG>::M][AlgTraits<ALG>
 template <int ALG, typename T, typename F>
 SFC_HD void stream_vertical4_real(F&& next, T (&z)[6][4]) {
   constexpr int NR = 7, NC = 6;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  static_for<4>([&](auto jc) {
+    constexpr int j = decltype(jc)::value;
     T col[NR], cc[NC];
-#pragma unroll
-    for (int r1 = 0; r1 < NR; ++r1) col[r1] = next();
+    static_for<NR>([&](auto rc) {
+      constexpr int r1 = decltype(rc)::value;
+      col[r1] = take_product<NR * j + r1>(next);
+    });
     collapse4_rows(col, cc);
     inv4_outputs(cc, z[real_comp4(j)]);
-  }
+  });
 }
 
 // SFC-4, second part: the products of the complex column group (positions 28 on; Eq. DFT4M)
@@ -702,27 +727,32 @@ SFC_HD void stream_vertical4_real(F&& next, T (&z)[6][4]) {
 template <int ALG, typename T, typename F>
 SFC_HD void stream_vertical4_complex(F&& next, T (&z)[6][4]) {
   constexpr int NR = 7, NC = 6, NREAL = 4;
+  constexpr int J0 = NR * NREAL;  // positions of the real columns come first
   T c0[NC], c1[NC];
   if constexpr (!AlgTraits<ALG>::kHermitian) {
     T h0[NR], h1[NR];
-#pragma unroll
-    for (int r1 = 0; r1 < NR; ++r1) {
-      const T m2 = next(), m1 = next(), m0 = next();  // rows a0 + a1, a1, a0
+    static_for<NR>([&](auto rc) {
+      constexpr int r1 = decltype(rc)::value;
+      const T m2 = take_product<J0 + 3 * r1>(next), m1 = take_product<J0 + 3 * r1 + 1>(next),
+              m0 = take_product<J0 + 3 * r1 + 2>(next);  // rows a0 + a1, a1, a0
       h0[r1] = m0 - m1;
       h1[r1] = m2 - m0 - m1;
-    }
+    });
     collapse4_rows(h0, c0);
     collapse4_rows(h1, c1);
   } else {
-#pragma unroll
-    for (int j = 0; j < NREAL; ++j) {
-      const T m2 = next(), m1 = next(), m0 = next();
+    static_for<NREAL>([&](auto jc) {
+      constexpr int j = decltype(jc)::value;
+      const T m2 = take_product<J0 + 3 * j>(next), m1 = take_product<J0 + 3 * j + 1>(next),
+              m0 = take_product<J0 + 3 * j + 2>(next);
       c0[real_comp4(j)] = m0 - m1;
       c1[real_comp4(j)] = m2 - m0 - m1;
-    }
+    });
     T m[6];
-#pragma unroll
-    for (int i = 0; i < 6; ++i) m[i] = next();
+    static_for<6>([&](auto ic) {
+      constexpr int i = decltype(ic)::value;
+      m[i] = take_product<J0 + 3 * NREAL + i>(next);
+    });
     const T uo0 = m[0] - m[1], uo1 = m[2] - m[0] - m[1];
     const T vo0 = m[3] - m[4], vo1 = m[5] - m[3] - m[4];
     c0[2] = Half<T>::apply(uo0 + vo0);  // o00

@@ -55,6 +55,13 @@ struct Half<f4> {
   static __device__ __forceinline__ f4 apply(const f4& a) { return a * f4(0.5f); }
 };
 
+// Lane n of the reader's row of 16 lanes (its quarter of the wave), as a DPP row broadcast:
+// folds into the instruction that takes the value.
+template <int N>
+__device__ __forceinline__ float row_lane(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x150 + N, 0xf, 0xf, false));
+}
+
 // V buffers of the fused kernel (groups of four points in LDS) and groups in flight in
 // registers behind them, by channel chunks: the load of a group is issued kVRegs groups
 // before its products
@@ -80,7 +87,11 @@ constexpr unsigned quad16_lds_layout(int what) {
 //   ures, a_wave  filter operand: block (position j, chunk kc) at a_wave + (j*KC + kc) KiB,
 //                 16 bytes per lane
 //   dres, d_wave  dequantization factors: 16 floats per position at d_wave + 64 j, lane
-//                 quarter l/16 takes four
+//                 quarter l/16 takes four.  They are loaded once, 16 positions per
+//                 instruction (lane (quarter, n) fetches those of position 16 m + n), and a
+//                 product takes its factors from lane n of its quarter by a row broadcast: a
+//                 load per position and wave instead kept the compute unit's vector-memory
+//                 path busy with 64-byte pieces.
 //   sync(pg)      called when the wave has read the last V of group pg (or issued its last
 //                 products): returns once group pg + 1 is in place; it may overwrite the
 //                 buffers of the groups before pg
@@ -97,22 +108,20 @@ __device__ __forceinline__ void quad16_products(const unsigned char* vbuf, int l
   constexpr int GROUP_BYTES = 4 * PS;      // PS: bytes from one position's V to the next
   constexpr int STEPS = PP * KC;           // filter-operand blocks of the wave
   constexpr int RA = 8;                    // ... in flight
-  constexpr int RD = 4;                    // factor loads in flight (positions)
+  constexpr int NDB = (PP + 15) / 16;      // blocks of 16 positions' factors
   const unsigned a_lane = (unsigned)lane * 16u;
-  const unsigned d_lane = (unsigned)(lane >> 4) * 16u;
+  const unsigned d_lane = (unsigned)(lane & 15) * 64u + (unsigned)(lane >> 4) * 16u;
   v4i aring[RA];
-  v4f dring[RD];
+  v4f dblk[NDB];
   auto load_a = [&](int s) {
     aring[s % RA] = __builtin_amdgcn_raw_buffer_load_b128(ures, a_lane, a_wave + (unsigned)s * 1024u, 0);
   };
-  auto load_d = [&](int j) {
-    dring[j % RD] = __builtin_bit_cast(
-        v4f, __builtin_amdgcn_raw_buffer_load_b128(dres, d_lane, d_wave + (unsigned)j * 64u, 0));
-  };
+#pragma unroll
+  for (int m = 0; m < NDB; ++m)  // (a last block may reach past the wave's table: never used)
+    dblk[m] = __builtin_bit_cast(
+        v4f, __builtin_amdgcn_raw_buffer_load_b128(dres, d_lane, d_wave + (unsigned)m * 1024u, 0));
 #pragma unroll
   for (int s = 0; s < RA && s < STEPS; ++s) load_a(s);
-#pragma unroll
-  for (int j = 0; j < RD && j < PP; ++j) load_d(j);
   const unsigned char* blane = vbuf + (lane & 15) * 64 + (lane >> 4) * 16;
   // V of position jj for the lane's tile: KC reads of 16 bytes.  Up to two chunks they are
   // issued a call ahead of the matrix instructions that take them (PREB); with more the
@@ -143,8 +152,9 @@ __device__ __forceinline__ void quad16_products(const unsigned char* vbuf, int l
   if constexpr (PREB) read_b(0);
   v4i acc_cur = products(0);
   if constexpr (PREB) read_b(1);
-  int j = 0;  // folds to a constant after unrolling
-  auto next = [&]() -> f4 {
+  // (the streaming output transform asks for the products in order and names the position)
+  auto next = [&](auto position) __attribute__((always_inline)) -> f4 {
+    constexpr int j = decltype(position)::value;
     v4i acc_new = acc_cur;
     if constexpr (PREB) {
       if (j + 1 < PP) acc_new = products(j + 1);
@@ -158,18 +168,15 @@ __device__ __forceinline__ void quad16_products(const unsigned char* vbuf, int l
     }
     __builtin_amdgcn_sched_barrier(0);  // the matrix instructions go first
     f4 v;
-    const v4f d = dring[j % RD];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      float t = (float)acc_cur[i] * d[i];
+      float t = (float)acc_cur[i] * row_lane<j & 15>(dblk[j >> 4][i]);
       // the scaled products are materialized here, the accumulator is not kept alive
       asm volatile("" : "+v"(t));
       v.v[i] = t;
     }
-    if (j + RD < PP) load_d(j + RD);
     acc_cur = acc_new;
     __builtin_amdgcn_sched_barrier(0);
-    ++j;
     return v;
   };
   // positions P .. PP-1 hold no point: their filter operand is zero, their products unused
@@ -222,7 +229,8 @@ __device__ __forceinline__ void quad16_store(const f4 (&z)[AlgTraits<ALG>::NC][A
           t = __builtin_amdgcn_fmed3f(t, kMagic, kMagic + 127.0f);
           word |= (__float_as_uint(t) & 0xffu) << (8 * o2);
         }
-        *(unsigned*)(stage + ((f * 16 + tl) * 4 + o1) * 4) = word;
+        // (rows moved round by the quarter: the four quarters of the wave write different banks)
+        *(unsigned*)(stage + ((f * 16 + tl) * 4 + ((o1 + q) & 3)) * 4) = word;
       } else {
         *(v4f*)(stage + (f * 64 + slot(tl, o1)) * 16) =
             v4f{out[0] * x_scale, out[1] * x_scale, out[2] * x_scale, out[3] * x_scale};
@@ -244,7 +252,7 @@ __device__ __forceinline__ void quad16_store(const f4 (&z)[AlgTraits<ALG>::NC][A
     const unsigned off = esz * (base + (unsigned)kc * (unsigned)HW);
     const int ncol = kc < g.Cout ? cols : 0;
     if constexpr (OUT == 2) {
-      const unsigned word = *(const unsigned*)(stage + ((k * 16 + tl) * 4 + q) * 4);
+      const unsigned word = *(const unsigned*)(stage + ((k * 16 + tl) * 4 + ((q + k) & 3)) * 4);
       if constexpr (EV == 4) {
         const unsigned o = ncol > 0 ? off : kOutOfRange;
         if constexpr (kStream) __builtin_amdgcn_raw_buffer_store_b32(word, yres, o, 0, kStreamStore);

@@ -234,13 +234,14 @@ __device__ __forceinline__ void stage_tiles(const int8_t* __restrict__ x, unsign
   const int lane_off = rsub * W + col;  // lane part of the byte offset
   const unsigned plane_stride = (unsigned)(H * W);
   constexpr int CPW = 64 / NW;  // channels per wave
-  constexpr int CB = 6;         // combinations per batch
   const int ncombo = tr.S * ROWG;
   // A dword can reach past the end of the tensor only if rows are not whole dwords; the
   // buffer load then returns zero for all of it, so those bytes are fetched one by one.
   // Rows of whole dwords take the loop without that check.
-  auto run = [&](auto tail_check) {
+  // CB: combinations per batch (every load of a batch is issued, live or not)
+  auto run = [&](auto tail_check, auto batch) {
     constexpr bool kTail = decltype(tail_check)::value;
+    constexpr int CB = decltype(batch)::value;
     for (int k0 = 0; k0 < ncombo; k0 += CB) {
       unsigned vals[CB][CPW];
 #pragma unroll
@@ -288,10 +289,13 @@ __device__ __forceinline__ void stage_tiles(const int8_t* __restrict__ x, unsign
       }
     }
   };
-  if ((W & 3) == 0)
-    run(std::false_type{});  // every dword lies wholly inside or outside its row
-  else
-    run(std::true_type{});
+  if ((W & 3) == 0) {  // every dword lies wholly inside or outside its row
+    if (ncombo <= ROWG) run(std::false_type{}, std::integral_constant<int, ROWG>{});
+    else if (ncombo <= 2 * ROWG) run(std::false_type{}, std::integral_constant<int, 2 * ROWG>{});
+    else run(std::false_type{}, std::integral_constant<int, 6>{});
+  } else {
+    run(std::true_type{}, std::integral_constant<int, 6>{});
+  }
 }
 
 // Stage the input of workgroup bx in the shape its TileRect says.
