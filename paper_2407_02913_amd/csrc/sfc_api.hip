@@ -105,18 +105,17 @@ bool make_geometry(const sfc_conv_desc& d, Geometry* out) {
 }
 
 // SFC_ALG_AUTO (3x3 filters), from per-layer timings of the ResNet shapes on one MI355X.
-// Requantized mode: SFC-4's 4x4 tiles -- 46 points per tile keep two workgroups on a compute
-// unit and the filter operand small, which outweighs even the ragged tiles of 14x14 and 7x7
-// maps while there are few (tile, filter) pairs (256 channels at 14x14, batch 64: 38.9 us
-// against 47.0 us for 7x7 tiles; 512 channels at 7x7, batch 64: 31.9 against 46.8 us) -- except
-// where 7x7 tiles cover the map exactly, 4x4 tiles do not, and the layer has at least 96 K
-// (tile, filter) pairs: then the 31 % of surplus outputs of the ragged 4x4 tiles cost more
-// than the larger point set (256 channels at 14x14, batch 128: 55.6 us with 7x7 tiles against
-// 60.8; 512 channels at 7x7, batch 256: 64.0 against 79.1).  Exact mode: 6x6 tiles, the form
-// Sec. 4 and the 3.68x figure are about.
+// Requantized mode: SFC-4's 4x4 tiles -- 46 points per tile keep two or three workgroups on a
+// compute unit and the filter operand small, which outweighs even the ragged tiles of 14x14
+// and 7x7 maps (256 channels at 14x14: 28.9 us against 47.5 us for 7x7 tiles at batch 64,
+// 49.1 against 55.8 at batch 128; 512 channels at 7x7, batch 64: 31.2 against 38.9) -- except
+// on 7x7 maps, which one 7x7 tile covers exactly, once the layer has at least 96 K (tile,
+// filter) pairs: then the 31 % of surplus outputs of the ragged 4x4 tiles cost more than the
+// larger point set (512 channels at 7x7, batch 256: 64.5 us with 7x7 tiles against 78.8).
+// Exact mode: 6x6 tiles, the form Sec. 4 and the 3.68x figure are about.
 int choose_alg(const sfc_conv_desc& d) {
   if (d.mode == SFC_MODE_EXACT) return SFC_ALG_6X6_P88;
-  if (d.H % 7 == 0 && d.W % 7 == 0 && (d.H % 4 != 0 || d.W % 4 != 0) && d.H <= 14 && d.W <= 14) {
+  if (d.H == 7 && d.W == 7) {
     const int64_t pairs = (int64_t)d.N * (d.H / 7) * (d.W / 7) * d.Cout;
     if (pairs >= 96 * 1024) return SFC_ALG_7X7_P132;
   }

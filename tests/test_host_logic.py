@@ -135,7 +135,7 @@ def test_auto_algorithm_and_path(lib):
         return got
 
     want = {"tiny32": ("4x4_p46", "single"), "resnet56": ("4x4_p46", "single"),
-            "resnet28": ("4x4_p46", "single"), "resnet14": ("7x7_p132", "fused"),
+            "resnet28": ("4x4_p46", "single"), "resnet14": ("4x4_p46", "fused"),
             "resnet7": ("7x7_p132", "staged"), "cifar16": ("4x4_p46", "single"),
             "cifar8": ("4x4_p46", "fused")}
     for name, shape in synth.LAYERS.items():
