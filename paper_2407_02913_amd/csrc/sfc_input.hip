@@ -24,7 +24,9 @@ struct InputPlan {
 
 // VS: bytes of V per point in LDS, 64 per tile slot (512 for the 8-tile workgroups: half the
 // LDS, so that more workgroups share a compute unit and overlap their phases).
-template <int ALG, int NW, int VS>
+// TPW: tiles per wave (SFC-4 forms: 2 when the workgroup takes whole images of 9 to 16 tiles,
+// whose planes it copies as they lie in memory instead of staging sparse 64-byte row windows).
+template <int ALG, int NW, int VS, int TPW = 1>
 __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
     const int8_t* __restrict__ x, int8_t* __restrict__ V, const float* __restrict__ inv_sx,
     const unsigned char* __restrict__ intab, Geometry g, InputPlan ip) {
@@ -65,41 +67,50 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
     constexpr int NPB = MfmaInput<ALG>::NPB, PP = Order<ALG>::PP;
     MfmaInput<ALG> mi;
     mi.load(intab, lane);
-    unsigned packed[4][NPB];
-    const int tile = wave;
-    if (tile < tr.ntiles) {
-      if (tr.whole) {
-        const int tpi = g.th * g.tw;
-        const int slot = tile / tpi, rem = tile - slot * tpi;
-        const int ti = rem / g.tw, tj = rem - ti * g.tw;
+    unsigned packed[TPW][4][NPB];
 #pragma unroll
-        for (int cg = 0; cg < 4; ++cg)
-          mi.transform(MfmaInput<ALG>::operand_plane(in + slot * 64 * tr.cs, tr.cs, 16 * cg,
-                                                     Tr::M * ti - Tr::PAD, Tr::M * tj - Tr::PAD, g.H,
-                                                     g.W, lane),
-                       g.qmax, packed[cg]);
-      } else {
-        const int tj0 = (bx % tr.chunks) * tr.tlw;
-        const int halo = Tr::M * tj0 - Tr::PAD - ((Tr::M * tj0) & ~3) + 4;
-        const int s = tile / tr.tlw, tjl = tile - s * tr.tlw;
+    for (int it = 0; it < TPW; ++it) {
+      const int tile = wave + NW * it;
+      if (tile < tr.ntiles) {
+        if (tr.whole) {
+          const int tpi = g.th * g.tw;
+          const int slot = tile / tpi, rem = tile - slot * tpi;
+          const int ti = rem / g.tw, tj = rem - ti * g.tw;
 #pragma unroll
-        for (int cg = 0; cg < 4; ++cg)
-          mi.transform(MfmaInput<ALG>::template operand_rect<stage_channel_bytes(Tr::NI)>(
-                           in, s, 16 * cg, halo + Tr::M * tjl, lane),
-                       g.qmax, packed[cg]);
+          for (int cg = 0; cg < 4; ++cg)
+            mi.transform(MfmaInput<ALG>::operand_plane(in + slot * 64 * tr.cs, tr.cs, 16 * cg,
+                                                       Tr::M * ti - Tr::PAD, Tr::M * tj - Tr::PAD, g.H,
+                                                       g.W, lane),
+                         g.qmax, packed[it][cg]);
+        } else {
+          const int tj0 = (bx % tr.chunks) * tr.tlw;
+          const int halo = Tr::M * tj0 - Tr::PAD - ((Tr::M * tj0) & ~3) + 4;
+          const int s = tile / tr.tlw, tjl = tile - s * tr.tlw;
+#pragma unroll
+          for (int cg = 0; cg < 4; ++cg)
+            mi.transform(MfmaInput<ALG>::template operand_rect<stage_channel_bytes(Tr::NI)>(
+                             in, s, 16 * cg, halo + Tr::M * tjl, lane),
+                         g.qmax, packed[it][cg]);
+        }
       }
     }
     __syncthreads();
-    if (tile < tr.ntiles) {
 #pragma unroll
-      for (int cg = 0; cg < 4; ++cg)
+    for (int it = 0; it < TPW; ++it) {
+      const int tile = wave + NW * it;
+      if (tile < tr.ntiles) {
 #pragma unroll
-        for (int m = 0; m < NPB; ++m) {
-          const int pos = 16 * m + (lane & 15);
-          if (pos < PP) *(unsigned*)(lds + pos * VSP + tile * 64 + 16 * cg + 4 * (lane >> 4)) = packed[cg][m];
-        }
+        for (int cg = 0; cg < 4; ++cg)
+#pragma unroll
+          for (int m = 0; m < NPB; ++m) {
+            const int pos = 16 * m + (lane & 15);
+            if (pos < PP)
+              *(unsigned*)(lds + pos * VSP + tile * 64 + 16 * cg + 4 * (lane >> 4)) = packed[it][cg][m];
+          }
+      }
     }
   } else {
+    static_assert(AlgTraits<ALG>::kFamily == 4 || TPW == 1, "one tile per wave on the vector-ALU path");
     transform_tiles<ALG, NW, 1, VS>(in, inv_sx, g.qmax, g, tr, bx, wave, lane);
   }
   __syncthreads();
@@ -120,13 +131,26 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
 // needs the registers, the 10x12 one of the 5x5-filter forms all the more) and the 4x4
 // forms, with half the LDS per workgroup
 static int input_waves(int alg) { return alg < 2 ? 16 : 8; }
+// tile slots of a workgroup: one per wave, or two per wave for the SFC-4 forms on feature
+// maps of 9 to 16 tiles when these then go through whole-image staging: the 64 channel planes
+// of an image are one contiguous run, against sparse 64-byte row windows for the 8-tile
+// rectangles of two strips (256 channels on 14x14 maps, 128 images: 23.0 -> 14.1 us)
+static int input_tile_slots(const Geometry& g) {
+  const int tpi = g.th * g.tw;
+  if ((g.alg == 4 || g.alg == 5) && tpi > 8 && tpi <= 16) {
+    TileRect tr;
+    if (make_tile_rect(g, 160u * 1024u - 32u - 64u, &tr, 16, true) && tr.whole) return 16;
+  }
+  return input_waves(g.alg);
+}
 
 static bool make_input_plan(const Geometry& g, InputPlan* ip) {
   // (16 more bytes per position for the SFC-4 forms, whose points are padded to 48 / 52)
-  const unsigned vbytes = (unsigned)((g.P + 3) / 4 * 4) * ((input_waves(g.alg) == 8 ? 512u : 1024u) + 16u);
+  const int slots = input_tile_slots(g);
+  const unsigned vbytes = (unsigned)((g.P + 3) / 4 * 4) * ((slots == 8 ? 512u : 1024u) + 16u);
   const unsigned lds_max = 160u * 1024u;
   if (vbytes + 16u + 64u > lds_max) return false;
-  if (!make_tile_rect(g, lds_max - 32u - 64u, &ip->tr, input_waves(g.alg), true)) return false;
+  if (!make_tile_rect(g, lds_max - 32u - 64u, &ip->tr, slots, true)) return false;
   const unsigned xbytes = tile_rect_stage_bytes(g, ip->tr) + 16u;
   ip->tab_off = ((xbytes > vbytes ? xbytes : vbytes) + 15u) & ~15u;
   ip->lds_bytes = ip->tab_off + 64u;
@@ -140,9 +164,17 @@ static hipError_t launch_input_i8_alg(const Geometry& g, const InputPlan& ip, co
                                       void* V, const float* inv_sx, const unsigned char* intab,
                                       hipStream_t s, bool prepare) {
   constexpr int NW = ALG < 2 ? 16 : 8;
+  const dim3 grid(tile_rect_groups(g, ip.tr) * (unsigned)(g.Cp / 64));
+  if constexpr (AlgTraits<ALG>::kFamily == 4) {
+    if (input_tile_slots(g) == 16) {  // two tiles per wave
+      auto kernel2 = input_transform_i8_kernel<ALG, NW, 1024, 2>;
+      if (prepare) return raise_lds_limit(reinterpret_cast<const void*>(kernel2));
+      hipLaunchKernelGGL(kernel2, grid, dim3(NW * 64), ip.lds_bytes, s, x, (int8_t*)V, inv_sx, intab, g, ip);
+      return hipGetLastError();
+    }
+  }
   auto kernel = input_transform_i8_kernel<ALG, NW, NW == 8 ? 512 : 1024>;
   if (prepare) return raise_lds_limit(reinterpret_cast<const void*>(kernel));
-  const dim3 grid(tile_rect_groups(g, ip.tr) * (unsigned)(g.Cp / 64));
   hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), ip.lds_bytes, s, x, (int8_t*)V, inv_sx, intab, g, ip);
   return hipGetLastError();
 }
