@@ -51,9 +51,14 @@ struct MfmaInput {
   template <int CS>
   static __device__ __forceinline__ v4i operand_rect(const unsigned char* in, int s, int ch0, int o,
                                                      int lane) {
+    return operand_rect<CS>(in, ch0, s * 64 * CS + o, lane);
+  }
+  // (the same with the strip folded into the offset: o = strip * 64 * CS + LDS byte of the
+  // tile's first patch column, which lies in the first 64 bytes)
+  template <int CS>
+  static __device__ __forceinline__ v4i operand_rect(const unsigned char* in, int ch0, int o, int lane) {
     const int ch = ch0 + (lane & 15), rp = min(lane >> 4, 2);
-    const unsigned* src =
-        (const unsigned*)(in + (unsigned)(s * 64 + ch) * CS + (2 * rp) * 64 + (o & ~3));
+    const unsigned* src = (const unsigned*)(in + (unsigned)ch * CS + (2 * rp) * 64 + (o & ~3));
     const unsigned sh = (unsigned)(o & 3);
     v4i a;
 #pragma unroll
@@ -113,17 +118,23 @@ struct MfmaInput {
     return operand_plane(planes, cs, ch0, plane_tile(r0, q0, H, W, lane), lane);
   }
 
-  // The sums of the lane's four channels for its point of every block, rounded to int8
-  // (clamp(round-half-even(v / s_Tx), +-qmax)) and packed: byte i = channel 4(l/16) + i.
-  __device__ __forceinline__ void transform(v4i a, float qmax, unsigned (&packed)[NPB]) const {
+  // The sums of the lane's four channels for its point of every block (matrix instructions
+  // only: a caller can issue those of the next patch before it rounds the current one) ...
+  __device__ __forceinline__ void sums(v4i a, v4i (&d)[NPB]) const {
+#pragma unroll
+    for (int m = 0; m < NPB; ++m)
+      d[m] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, coeff[m], v4i{0, 0, 0, 0}, 0, 0, 0);
+  }
+  // ... and their rounding to int8 (clamp(round-half-even(v / s_Tx), +-qmax)), packed: byte i =
+  // channel 4(l/16) + i.
+  __device__ __forceinline__ void round(const v4i (&d)[NPB], float qmax, unsigned (&packed)[NPB]) const {
     constexpr float kMagic = 12582912.0f;
 #pragma unroll
     for (int m = 0; m < NPB; ++m) {
-      const v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, coeff[m], v4i{0, 0, 0, 0}, 0, 0, 0);
       unsigned q[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        float t = __fmaf_rn((float)d[i], inv[m], kMagic);
+        float t = __fmaf_rn((float)d[m][i], inv[m], kMagic);
         t = __builtin_amdgcn_fmed3f(t, kMagic - qmax, kMagic + qmax);
         q[i] = __float_as_uint(t);
       }
@@ -132,6 +143,11 @@ struct MfmaInput {
       const unsigned hi = __builtin_amdgcn_perm(q[3], q[2], 0x04000c0cu);
       packed[m] = lo | hi;
     }
+  }
+  __device__ __forceinline__ void transform(v4i a, float qmax, unsigned (&packed)[NPB]) const {
+    v4i d[NPB];
+    sums(a, d);
+    round(d, qmax, packed);
   }
 };
 

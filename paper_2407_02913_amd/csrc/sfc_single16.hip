@@ -45,7 +45,7 @@ __global__ __launch_bounds__(NW * 64, 2) void single16_kernel(
   using Tr = AlgTraits<ALG>;
   constexpr int M = Tr::M, NI = Tr::NI, NC = Tr::NC, PAD = Tr::PAD;
   constexpr int PP = Order<ALG>::PP, PG = PP / 4;
-  constexpr int SPW = 16 / NW, NITEM = SPW * KC;
+  static_assert(NW == 4 * KC, "one wave per (channel chunk, group of 16 channels)");
   constexpr int CS = stage_channel_bytes(NI);
   // bytes of V per position: KC operand blocks of 1 KiB and 16 bytes that put the 16 positions
   // a wave writes at once into different LDS banks
@@ -60,6 +60,13 @@ __global__ __launch_bounds__(NW * 64, 2) void single16_kernel(
     const int tl = threadIdx.x;
     const TileCoord tc = tile_coord(g, tr, bx, tl);
     write_tile_entry<M>(tile_tab, tl, tc.live, tc.n, tc.ti, tc.tj, g.Cout, g.H, g.W);
+    if (!tr.whole) {
+      // rectangle: where the patch of tile slot tl starts in the staged rows of a chunk
+      // (slots beyond the rectangle repeat its last tile)
+      const int t = min(tl, tr.ntiles - 1), s = t / tr.tlw, tj0 = (bx % tr.chunks) * tr.tlw;
+      const int halo = M * tj0 - PAD - ((M * tj0) & ~3) + 4;  // LDS byte of the rectangle's first patch column
+      tile_tab[48 + tl] = s * 64 * CS + halo + M * (t - s * tr.tlw);
+    }
   }
 
   // ---- 1. stage ----------------------------------------------------------------------
@@ -69,58 +76,67 @@ __global__ __launch_bounds__(NW * 64, 2) void single16_kernel(
   __syncthreads();
 
   // ---- 2. input transform (sfc_mfma_input.hpp) --------------------------------------------
-  // An item is (tile, 64-channel chunk, group of 16 channels): the wave of tile t takes the
-  // items of tiles t, t + NW, ...  All items are transformed, rounded and packed in registers
-  // before the first byte of V is written, because V lies over the staged rows.
+  // A patch is (tile, 64-channel chunk, group of 16 channels).  Wave w takes the patches of
+  // chunk w / 4, channel group w % 4 of every tile, so all waves have the same number of them.
+  // All patches are transformed, rounded and packed in registers before the first byte of V
+  // is written, because V lies over the staged rows.
   {
     MfmaInput<ALG> mi;
     mi.load(intab, lane);
     constexpr int NPB = MfmaInput<ALG>::NPB;
-    const int tj0 = tr.whole ? 0 : (bx % tr.chunks) * tr.tlw;
-    const int colbase = (M * tj0) & ~3;
-    const int halo = M * tj0 - PAD - colbase + 4;  // LDS byte of the rectangle's first patch column
-    unsigned packed[NITEM * 4][NPB];
-#pragma unroll
-    for (int it = 0; it < NITEM; ++it) {
-      const int tile = wave + NW * (it / KC), kc = it % KC;
-      const unsigned char* in = lds + 16 + kc * sp.chunk_in;  // (16: plane patches are read from up to 4 bytes early)
-      if (tile < tr.ntiles) {
-        if (tr.whole) {
+    constexpr int NQ = 16;  // tile slots
+    const int kc = wave >> 2, cg = wave & 3;
+    const unsigned char* in = lds + 16 + kc * sp.chunk_in;  // (16: plane patches are read from up to 4 bytes early)
+    unsigned packed[NQ][NPB];
+    // Software pipeline: the LDS reads of patch q + 2 and the matrix instructions of patch
+    // q + 1 are issued before patch q is rounded, so neither latency is waited for.  (An empty
+    // tile slot repeats the last tile: its bytes are not written.)
+    auto run = [&](auto whole_images) __attribute__((always_inline)) {
+      constexpr bool kWhole = decltype(whole_images)::value;
+      auto fetch = [&](int q) __attribute__((always_inline)) -> v4i {  // q folds to a constant
+        if constexpr (kWhole) {
+          const int tile = min(q, tr.ntiles - 1);
           const int tpi = g.th * g.tw;
           const int slot = tile / tpi, rem = tile - slot * tpi;
           const int ti = rem / g.tw, tj = rem - ti * g.tw;
-#pragma unroll
-          for (int cg = 0; cg < 4; ++cg) {
-            const v4i a = MfmaInput<ALG>::operand_plane(in + slot * 64 * tr.cs, tr.cs, 16 * cg, M * ti - PAD,
-                                                        M * tj - PAD, g.H, g.W, lane);
-            mi.transform(a, g.qmax, packed[4 * it + cg]);
-          }
+          return MfmaInput<ALG>::operand_plane(in + slot * 64 * tr.cs, tr.cs, 16 * cg, M * ti - PAD,
+                                               M * tj - PAD, g.H, g.W, lane);
         } else {
-          const int s = tile / tr.tlw, tjl = tile - s * tr.tlw;
+          const int off = __builtin_amdgcn_readfirstlane(tile_tab[48 + q]);
+          return MfmaInput<ALG>::template operand_rect<CS>(in, 16 * cg, off, lane);
+        }
+      };
+      v4i d_cur[NPB], d_nxt[NPB];
+      v4i a_nxt = fetch(0);
+      mi.sums(a_nxt, d_cur);
+      a_nxt = fetch(1);
 #pragma unroll
-          for (int cg = 0; cg < 4; ++cg) {
-            const v4i a = MfmaInput<ALG>::template operand_rect<CS>(in, s, 16 * cg, halo + M * tjl, lane);
-            mi.transform(a, g.qmax, packed[4 * it + cg]);
-          }
+      for (int q = 0; q < NQ; ++q) {
+        if (q < tr.ntiles) {  // (the same for every wave)
+          if (q + 1 < NQ) mi.sums(a_nxt, d_nxt);
+          if (q + 2 < NQ) a_nxt = fetch(q + 2);
+          __builtin_amdgcn_sched_barrier(0);  // reads and matrix instructions go first
+          mi.round(d_cur, g.qmax, packed[q]);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int m = 0; m < NPB; ++m) d_cur[m] = d_nxt[m];
         }
       }
-    }
+    };
+    if (tr.whole) run(std::true_type{});
+    else run(std::false_type{});
     __syncthreads();  // every patch has been read: the staging area becomes V
 #pragma unroll
-    for (int it = 0; it < NITEM; ++it) {
-      const int tile = wave + NW * (it / KC), kc = it % KC;
+    for (int q = 0; q < NQ; ++q) {
       // (an empty tile slot keeps stale bytes: they only reach products of that slot, which
       // are never stored)
-      if (tile < tr.ntiles) {
+      if (q < tr.ntiles) {
 #pragma unroll
-        for (int cg = 0; cg < 4; ++cg)
-#pragma unroll
-          for (int m = 0; m < NPB; ++m) {
-            const int pos = 16 * m + (lane & 15);
-            if (pos < PP)
-              *(unsigned*)(lds + pos * VS + kc * 1024 + tile * 64 + 16 * cg + 4 * (lane >> 4)) =
-                  packed[4 * it + cg][m];
-          }
+        for (int m = 0; m < NPB; ++m) {
+          const int pos = 16 * m + (lane & 15);
+          if (pos < PP)
+            *(unsigned*)(lds + pos * VS + kc * 1024 + q * 64 + 16 * cg + 4 * (lane >> 4)) = packed[q][m];
+        }
       }
     }
   }
