@@ -126,6 +126,150 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
   }
 }
 
+// SFC-4 forms on small feature maps (whole images staged as they lie in memory): after the
+// one barrier that follows the staging every wave works on its own.  It transforms its tiles on
+// the matrix cores (sfc_mfma_input.hpp: lane = (position, four channels)), turns the rounded
+// bytes of a tile round in a block of LDS that only it uses -- [position][64 channels], 80 bytes
+// from row to row -- and writes them to V with 16-byte lanes, 64 contiguous bytes per
+// (position, tile).  No further barrier and no separate copy-out phase: a wave's stores are
+// under way while it, and the other waves, transform the next tile.
+constexpr int kWaveRowBytes = 80;  // LDS bytes per position in a wave's block (conflict-free dword writes)
+
+struct WaveInputPlan {
+  TileRect tr;
+  unsigned blk_off;  // LDS byte offset of the waves' blocks
+  unsigned tab_off;  // ... of the tile -> V row table
+  unsigned lds_bytes;
+};
+
+template <int ALG, int NW, int TPW>
+__global__ __launch_bounds__(NW * 64) void input_transform_waves_kernel(
+    const int8_t* __restrict__ x, int8_t* __restrict__ V, const unsigned char* __restrict__ intab,
+    Geometry g, WaveInputPlan ip) {
+  using Tr = AlgTraits<ALG>;
+  static_assert(Tr::kFamily == 4, "the SFC-4 forms");
+  extern __shared__ __align__(16) unsigned char lds[];
+  constexpr int P = Tr::P, PP = Order<ALG>::PP, NPB = MfmaInput<ALG>::NPB;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const TileRect& tr = ip.tr;
+  const int cgn = g.Cp >> 6;
+  const int pos = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int bx = pos / cgn;
+  const int c0 = (pos - bx * cgn) * 64;
+  int* row_tab = (int*)(lds + ip.tab_off);
+  if (threadIdx.x < 16) {
+    const int tl = threadIdx.x;
+    const TileCoord tc = tile_coord(g, tr, bx, tl);
+    row_tab[tl] = tc.live ? (tc.n * g.th + tc.ti) * g.tw + tc.tj : -1;
+  }
+  unsigned char* in = lds + 16;  // (plane patches are read from up to 4 bytes early)
+  stage_images<NW>(x, in, g, tr, bx, c0, wave, lane);
+
+  MfmaInput<ALG> mi;
+  mi.load(intab, lane);
+  // this lane's part of a store: position 16 m + lane / 4, channels 16 (lane % 4) ..
+  const unsigned vplane = (unsigned)g.Tp * (unsigned)g.Cp;
+  const __amdgpu_buffer_rsrc_t vres =
+      __builtin_amdgcn_make_buffer_rsrc((void*)V, 0, (int)(vplane * (unsigned)P), kBufferFlags);
+  const int* point = (const int*)(intab + kInputTabPoints);
+  unsigned pofs[NPB];
+#pragma unroll
+  for (int m = 0; m < NPB; ++m) {
+    const int p = point[16 * m + (lane >> 2)];
+    pofs[m] = p >= 0 ? (unsigned)p * vplane + (unsigned)(c0 + 16 * (lane & 3)) : 0x80000000u;
+  }
+  unsigned char* blk = lds + ip.blk_off + wave * (PP * kWaveRowBytes);
+  __syncthreads();
+
+  // patch q = 4 * (tile of the wave) + channel group, software-pipelined as in the
+  // single-kernel path: reads of patch q + 2 and matrix instructions of patch q + 1 go before
+  // the rounding of patch q
+  constexpr int NQ = 4 * TPW;
+  const int tpi = g.th * g.tw;
+  typename MfmaInput<ALG>::PlaneTile ptile = {};
+  const unsigned char* planes = in;
+  auto fetch = [&](int q) __attribute__((always_inline)) -> v4i {  // q folds to a constant
+    if ((q & 3) == 0) {
+      const int tile = min(wave + NW * (q >> 2), tr.ntiles - 1);
+      const int slot = tile / tpi, rem = tile - slot * tpi;
+      const int ti = rem / g.tw, tj = rem - ti * g.tw;
+      ptile = MfmaInput<ALG>::plane_tile(Tr::M * ti - Tr::PAD, Tr::M * tj - Tr::PAD, g.H, g.W, lane);
+      planes = in + slot * 64 * tr.cs;
+    }
+    return MfmaInput<ALG>::operand_plane(planes, tr.cs, 16 * (q & 3), ptile, lane);
+  };
+  unsigned packed[NQ][NPB];
+  v4i d_cur[NPB], d_nxt[NPB];
+  v4i a_nxt = fetch(0);
+  mi.sums(a_nxt, d_cur);
+  a_nxt = fetch(1);
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    if (q + 1 < NQ) mi.sums(a_nxt, d_nxt);
+    if (q + 2 < NQ) a_nxt = fetch(q + 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mi.round(d_cur, g.qmax, packed[q]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int m = 0; m < NPB; ++m) d_cur[m] = d_nxt[m];
+  }
+#pragma unroll
+  for (int it = 0; it < TPW; ++it) {
+    const int tile = wave + NW * it;
+    const int t = tile < tr.ntiles ? row_tab[tile] : -1;  // the same for the whole wave
+    if (t >= 0) {
+#pragma unroll
+      for (int cg = 0; cg < 4; ++cg)
+#pragma unroll
+        for (int m = 0; m < NPB; ++m) {
+          const int j = 16 * m + (lane & 15);
+          if (j < PP) *(unsigned*)(blk + j * kWaveRowBytes + 16 * cg + 4 * (lane >> 4)) = packed[4 * it + cg][m];
+        }
+      __builtin_amdgcn_wave_barrier();  // LDS accesses of one wave complete in order
+#pragma unroll
+      for (int m = 0; m < NPB; ++m) {
+        const int j = 16 * m + (lane >> 2);
+        if (j < PP) {
+          const v4i d = *(const v4i*)(blk + j * kWaveRowBytes + 16 * (lane & 3));
+          __builtin_amdgcn_raw_buffer_store_b128(d, vres, pofs[m], (unsigned)t * (unsigned)g.Cp, 0);
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
+static bool make_wave_input_plan(const Geometry& g, WaveInputPlan* ip) {
+  if (g.alg != 4 && g.alg != 5) return false;
+  const int tpi = g.th * g.tw;
+  if (tpi > 16) return false;
+  const int slots = tpi > 8 ? 16 : 8;
+  const unsigned lds_max = 160u * 1024u;
+  if (!make_tile_rect(g, lds_max / 2, &ip->tr, slots, true) || !ip->tr.whole) return false;
+  const unsigned pp = (unsigned)((g.P + 3) / 4 * 4);
+  ip->blk_off = (16u + tile_rect_stage_bytes(g, ip->tr) + 16u + 15u) & ~15u;
+  ip->tab_off = ip->blk_off + 8u * pp * (unsigned)kWaveRowBytes;
+  ip->lds_bytes = ip->tab_off + 64u;
+  const long long xb = (long long)g.N * g.Cin * g.H * g.W;
+  const long long vb = (long long)g.P * g.Tp * g.Cp;
+  return ip->lds_bytes <= lds_max && xb < (1ll << 31) && vb < (1ll << 31);
+}
+
+template <int ALG>
+static hipError_t launch_input_waves_alg(const Geometry& g, const WaveInputPlan& ip, const int8_t* x,
+                                         void* V, const unsigned char* intab, hipStream_t s,
+                                         bool prepare) {
+  const dim3 grid(tile_rect_groups(g, ip.tr) * (unsigned)(g.Cp / 64));
+  auto launch = [&](auto kernel) {
+    if (prepare) return raise_lds_limit(reinterpret_cast<const void*>(kernel));
+    hipLaunchKernelGGL(kernel, grid, dim3(8 * 64), ip.lds_bytes, s, x, (int8_t*)V, intab, g, ip);
+    return hipGetLastError();
+  };
+  return g.th * g.tw > 8 ? launch(input_transform_waves_kernel<ALG, 8, 2>)
+                         : launch(input_transform_waves_kernel<ALG, 8, 1>);
+}
+
 // waves per workgroup = tiles per workgroup: 16 for the 6x6 forms (rectangles of 16 tiles
 // fit their feature maps best); 8 for the 7x7 forms (a 9x10 half-transformed patch per tile
 // needs the registers, the 10x12 one of the 5x5-filter forms all the more) and the 4x4
@@ -184,6 +328,10 @@ static hipError_t launch_input_i8_alg(const Geometry& g, const InputPlan& ip, co
 hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V,
                                      const float* inv_sx, const unsigned char* intab,
                                      hipStream_t s, bool prepare) {
+  WaveInputPlan wp;
+  if (make_wave_input_plan(g, &wp))
+    return g.alg == 4 ? launch_input_waves_alg<4>(g, wp, x, V, intab, s, prepare)
+                      : launch_input_waves_alg<5>(g, wp, x, V, intab, s, prepare);
   InputPlan ip;
   if (!make_input_plan(g, &ip)) return hipErrorNotSupported;
   switch (g.alg) {

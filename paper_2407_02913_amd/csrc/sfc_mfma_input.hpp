@@ -18,8 +18,10 @@ namespace sfc {
 
 constexpr int kInputTabRows = 64;  // positions padded to whole blocks of 16
 // the table behind the filter operand: float inv_pos[64] (1 / s_Tx by processing position, 0
-// for positions without a point), then int8 coeff[64][64] ([position][k])
-constexpr unsigned kInputTabBytes = kInputTabRows * 4 + kInputTabRows * 64;
+// for positions without a point), then int8 coeff[64][64] ([position][k]), then int
+// point[64] (canonical point of a processing position, -1: none)
+constexpr unsigned kInputTabPoints = kInputTabRows * 4 + kInputTabRows * 64;  // offset of point[]
+constexpr unsigned kInputTabBytes = kInputTabPoints + kInputTabRows * 4;
 
 // Host: fills the table for one algorithm from the add networks (inv_sx by canonical point).
 void build_input_table(int alg, const float* inv_sx, unsigned char* tab);

@@ -171,6 +171,8 @@ static void fill_input_table(const float* inv_sx, unsigned char* tab) {
   signed char* coeff = reinterpret_cast<signed char*>(tab) + kInputTabRows * 4;
   std::memset(tab, 0, kInputTabBytes);
   for (int p = 0; p < Tr::P; ++p) inv_pos[order.pos[p]] = inv_sx[p];
+  int* point = reinterpret_cast<int*>(tab + kInputTabPoints);
+  for (int j = 0; j < kInputTabRows; ++j) point[j] = j < Order<ALG>::PP ? order.pt[j] : -1;
   for (int i = 0; i < NI; ++i)
     for (int j = 0; j < NI; ++j) {
       int half[NI][NC], comp[NC][NC];
