@@ -351,8 +351,9 @@ def main():
                          "a single workload prints its own record as the headline)")
     ap.add_argument("--path", default=None, choices=[None, "staged", "fused", "single"])
     ap.add_argument("--alg", default=None,
-                    help="6x6_p88 | 6x6_p100 | 7x7_p132 | 7x7_p144 | 4x4_p46 | 4x4_p49, or with 5x5 filters "
-                         "6x6_5x5_p184 | 6x6_5x5_p196 (default: the library's choice per layer)")
+                    help="6x6_p88 | 6x6_p100 | 7x7_p132 | 7x7_p144 | 4x4_p46 | 4x4_p49, with 5x5 filters "
+                         "6x6_5x5_p184 | 6x6_5x5_p196, with 7x7 filters 4x4_7x7_p184 | 4x4_7x7_p196 "
+                         "(default: the library's choice per layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quick", action="store_true", help="skip the graph-replay side figure")
     ap.add_argument("--buffer-sets", type=int, default=0,
