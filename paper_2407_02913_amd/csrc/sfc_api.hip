@@ -31,7 +31,8 @@ struct sfc_plan_s {
   bool filter_ready;
   int quad_filters;  // filters covered by the regrouped filter operand (0: none)
   int dq_filters;    // filters in the [filter][processing position] dequantization table (0: none)
-  bool quad16;       // SFC-4 forms: 16 filters per wave, four pairs per lane (fused and single paths)
+  bool quad16;       // filter operand in groups of 16 filters (sfc_quad16.hpp, sfc_splitk.hip)
+  bool splitk;       // fused path: input channels split over the waves of a workgroup
   float inv_y;  // 1 / output scale (SFC_OUT_I8_RELU), 0: not set
 };
 
@@ -204,11 +205,14 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   p->off_dq_single = off;
   p->off_U_single = off;
   p->quad_filters = 0;
-  p->quad16 = (d.path == SFC_PATH_FUSED && sfc::quad16_supported(g)) ||
+  p->splitk = d.path == SFC_PATH_FUSED && !sfc::quad16_supported(g) && sfc::splitk_supported(g);
+  p->quad16 = p->splitk || (d.path == SFC_PATH_FUSED && sfc::quad16_supported(g)) ||
               (d.path == SFC_PATH_SINGLE && (sfc::single16_supported(g) || sfc::single16k_supported(g)));
   if (d.path == SFC_PATH_SINGLE) p->quad_filters = p->quad16 ? g.Kp : (g.Cout + 63) / 64 * 64;
   if (d.path == SFC_PATH_FUSED)
-    p->quad_filters = p->quad16 ? sfc::quad16_filter_count(g) : sfc::quad_filter_count(g);
+    p->quad_filters = p->splitk   ? sfc::splitk_filter_count(g)
+                      : p->quad16 ? sfc::quad16_filter_count(g)
+                                  : sfc::quad_filter_count(g);
   // the staged output transform reads the same [filter][position] table as the fused kernels
   p->dq_filters = p->quad_filters;
   if (d.path == SFC_PATH_STAGED && d.mode == SFC_MODE_REQUANT_I8) p->dq_filters = g.Kp;
@@ -442,8 +446,9 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
   }
   if (fused) {
     if (tail &&
-        (plan->quad16 ? sfc::launch_quad16(plan->d.out, g, V, f, x_scale, plan->inv_y, y_dev, s)
-                      : sfc::launch_fused_quad(plan->d.out, g, V, f, x_scale, plan->inv_y, y_dev, s)) !=
+        (plan->splitk   ? sfc::launch_splitk(plan->d.out, g, V, f, x_scale, plan->inv_y, y_dev, s)
+         : plan->quad16 ? sfc::launch_quad16(plan->d.out, g, V, f, x_scale, plan->inv_y, y_dev, s)
+                        : sfc::launch_fused_quad(plan->d.out, g, V, f, x_scale, plan->inv_y, y_dev, s)) !=
             hipSuccess)
       return SFC_EHIP;
     return SFC_OK;

@@ -81,6 +81,13 @@ hipError_t launch_repack_filter16(const Geometry& g, int filters, const void* U,
                                   hipStream_t s);
 hipError_t launch_quad16(int out, const Geometry& g, const void* V, const FilterViews& f,
                          float x_scale, float inv_y, void* y, hipStream_t s, bool prepare = false);
+// products + output transform with the input channels split over the waves of a workgroup
+// (sfc_splitk.hip: 512 channels, 7x7 and 4x4 tiles), on the filter operand and factor table
+// of launch_quad16
+bool splitk_supported(const Geometry& g);
+int splitk_filter_count(const Geometry& g);
+hipError_t launch_splitk(int out, const Geometry& g, const void* V, const FilterViews& f,
+                         float x_scale, float inv_y, void* y, hipStream_t s, bool prepare = false);
 // single-kernel path of the SFC-4 forms, up to 128 input channels (sfc_single16.hip), on the
 // same filter operand and factor table as launch_quad16
 bool single16_supported(const Geometry& g);

@@ -421,9 +421,9 @@ hipError_t prepare_kernels(int path, int out, const Geometry& g) {
   hipError_t e = launch_input_transform_i8(g, nullptr, nullptr, nullptr, nullptr, nullptr, true);
   if (e != hipSuccess && e != hipErrorNotSupported) return e;
   if (path == 1)
-    return quad16_supported(g)
-               ? launch_quad16(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true)
-               : launch_fused_quad(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true);
+    return quad16_supported(g)   ? launch_quad16(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true)
+           : splitk_supported(g) ? launch_splitk(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true)
+                                 : launch_fused_quad(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true);
   return launch_output_sums(out, g, nullptr, none, 1.0f, 1.0f, nullptr, nullptr, true);
 }
 

@@ -774,45 +774,54 @@ SFC_HD void stream_vertical(F&& next, T (&z)[AlgTraits<ALG>::NC][AlgTraits<ALG>:
     stream_vertical4_complex<ALG, T>(next, z);
     return;
   } else {
-#pragma unroll
-  for (int j = 0; j < NREAL; ++j) {
+  static_for<NREAL>([&](auto jc) {
+    constexpr int j = decltype(jc)::value;
     T col[NR], cc[NC];
-#pragma unroll
-    for (int r1 = 0; r1 < NR; ++r1) col[r1] = next();
+    static_for<NR>([&](auto rc) {
+      constexpr int r1 = decltype(rc)::value;
+      col[r1] = take_product<NR * j + r1>(next);
+    });
     collapse_rows(col, cc);
     inv_outputs(cc, z[real_comp(j)]);
-  }
-#pragma unroll
-  for (int g2 = 0; g2 < 2; ++g2) {
+  });
+  // the two complex column groups: 3 NR positions each (nested), or 3 NREAL + 12 (Hermitian)
+  constexpr int GSZ = Tr::kHermitian ? 3 * NREAL + 12 : 3 * NR;
+  static_for<2>([&](auto gc) {
+    constexpr int g2 = decltype(gc)::value;
+    constexpr int J0 = NREAL * NR + g2 * GSZ;
     T c0[NC], c1[NC];
     if constexpr (!Tr::kHermitian) {
       T h0[NR], h1[NR];
-#pragma unroll
-      for (int r1 = 0; r1 < NR; ++r1) {
-        const T m0 = next(), m1 = next(), m2 = next();
+      static_for<NR>([&](auto rc) {
+        constexpr int r1 = decltype(rc)::value;
+        const T m0 = take_product<J0 + 3 * r1>(next), m1 = take_product<J0 + 3 * r1 + 1>(next),
+                m2 = take_product<J0 + 3 * r1 + 2>(next);
         h0[r1] = m0 - m1;
         h1[r1] = m2 - m0;
-      }
+      });
       collapse_rows(h0, c0);
       collapse_rows(h1, c1);
     } else {
-#pragma unroll
-      for (int j = 0; j < NREAL; ++j) {
-        const T m0 = next(), m1 = next(), m2 = next();
+      static_for<NREAL>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        const T m0 = take_product<J0 + 3 * j>(next), m1 = take_product<J0 + 3 * j + 1>(next),
+                m2 = take_product<J0 + 3 * j + 2>(next);
         c0[real_comp(j)] = m0 - m1;
         c1[real_comp(j)] = m2 - m0;
-      }
-#pragma unroll
-      for (int g1 = 0; g1 < 2; ++g1) {
+      });
+      static_for<2>([&](auto g1c) {
+        constexpr int g1 = decltype(g1c)::value;
         T m[6];
-#pragma unroll
-        for (int i = 0; i < 6; ++i) m[i] = next();
+        static_for<6>([&](auto ic) {
+          constexpr int i = decltype(ic)::value;
+          m[i] = take_product<J0 + 3 * NREAL + 6 * g1 + i>(next);
+        });
         hermitian_collapse(m, c0[1 + 2 * g1], c0[2 + 2 * g1], c1[1 + 2 * g1], c1[2 + 2 * g1]);
-      }
+      });
     }
     inv_outputs(c0, z[1 + 2 * g2]);
     inv_outputs(c1, z[2 + 2 * g2]);
-  }
+  });
   }
 }
 

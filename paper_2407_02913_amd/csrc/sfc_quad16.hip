@@ -54,12 +54,13 @@ __global__ __launch_bounds__(64) void repack_filter16_kernel(const int8_t* __res
 hipError_t launch_repack_filter16(const Geometry& g, int filters, const void* U, void* U16,
                                   hipStream_t s) {
   const dim3 grid((unsigned)((filters / 16) * ((g.P + 3) / 4 * 4) * (g.Cp / 64)));
-  if (g.alg == 4)
-    hipLaunchKernelGGL(repack_filter16_kernel<4>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)U16, g);
-  else if (g.alg == 5)
-    hipLaunchKernelGGL(repack_filter16_kernel<5>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)U16, g);
-  else
-    return hipErrorInvalidValue;
+  switch (g.alg) {
+    case 2: hipLaunchKernelGGL(repack_filter16_kernel<2>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)U16, g); break;
+    case 3: hipLaunchKernelGGL(repack_filter16_kernel<3>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)U16, g); break;
+    case 4: hipLaunchKernelGGL(repack_filter16_kernel<4>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)U16, g); break;
+    case 5: hipLaunchKernelGGL(repack_filter16_kernel<5>, grid, dim3(64), 0, s, (const int8_t*)U, (int8_t*)U16, g); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

@@ -385,6 +385,8 @@ FUSED_SHAPES = [
     (5, 64, 64, 12, 18),  # 30 tiles: padding rows in the last block
     (2, 200, 72, 11, 7),  # four chunks (Cin padded to 256), two workgroups along Cout
     (1, 500, 24, 8, 8),  # eight chunks
+    (3, 460, 72, 14, 14),  # eight chunks, three filter pairs of 32, whole-image stores with 7x7 tiles
+    (2, 512, 40, 9, 13),  # eight chunks, odd W
     # small feature maps, staged as whole images: batch not a multiple of the images per
     # workgroup, plane sizes that are / are not whole dwords, planes above 64 dwords
     (5, 20, 8, 7, 7),
