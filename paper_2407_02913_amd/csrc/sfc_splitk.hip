@@ -158,15 +158,23 @@ __global__ __launch_bounds__(kSplitWaves * 64, 1) void splitk_kernel(
   const unsigned char* blane = vbuf + (CPW * ks) * 1024 + (lane & 15) * 64 + (lane >> 4) * 16;
   unsigned char* xw = xbuf + (fgl * 16 + ks) * 256 + lane * 4;        // + point*8 KiB + i*1 KiB
   const unsigned char* xr = xbuf + (fgl * 16 + ks * 4) * 256 + lane * 4;  // + point*8 KiB + ks'*256
-  auto partials = [&](int pg) {
+  // (every LDS read of a step is issued before the first result is waited for: the operand
+  // reads of four points, and the partial sums of the group that is being finished)
+  auto read_b = [&](int pg, v4i (&b)[4][CPW]) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int c = 0; c < CPW; ++c)
+        b[r][c] = *(const v4i*)(blane + (pg & 1) * GROUP_BYTES + (r * KC + c) * 1024);
+  };
+  auto partials = [&](int pg, const v4i (&b)[4][CPW]) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       v4i acc = {0, 0, 0, 0};
 #pragma unroll
       for (int c = 0; c < CPW; ++c) {
         const int s = (4 * pg + r) * CPW + c;
-        const v4i b = *(const v4i*)(blane + (pg & 1) * GROUP_BYTES + (r * KC + c) * 1024);
-        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(aring[s % RA], b, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(aring[s % RA], b[r][c], acc, 0, 0, 0);
         if (s + RA < STEPS) load_a(s + RA);
       }
 #pragma unroll
@@ -180,7 +188,11 @@ __global__ __launch_bounds__(kSplitWaves * 64, 1) void splitk_kernel(
   store_lds(0);
   if (PG > 1) load_regs(1);
   __syncthreads();
-  partials(0);
+  {
+    v4i b[4][CPW];
+    read_b(0, b);
+    partials(0, b);
+  }
   if (PG > 1) store_lds(1);
   if (PG > 2) load_regs(2);
   __syncthreads();
@@ -190,26 +202,34 @@ __global__ __launch_bounds__(kSplitWaves * 64, 1) void splitk_kernel(
     constexpr int j = decltype(position)::value;
     constexpr int r = j & 3, pg = j >> 2;
     if constexpr (r == 0) {
-      // group pg + 1: its V is in LDS; its partial sums go to the other exchange buffer
-      if (pg + 1 < PG) partials(pg + 1);
-      // the sums of group pg over all channels, scaled
+      // the partial sums of group pg (all four waves of the filter group wrote them before the
+      // last barrier) and the operands of group pg + 1: every read goes out first
+      int part[4][4];
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
         const unsigned char* src = xr + (pg & 1) * XGROUP + rr * (NW * 1024);
-        const int s0 = *(const int*)(src), s1 = *(const int*)(src + 256), s2 = *(const int*)(src + 512),
-                  s3 = *(const int*)(src + 768);
-        constexpr int jj = 4 * pg;  // position of rr = 0; the lane index of a row broadcast is a constant
-        float d;
-        if (rr == 0) d = row_lane<(jj + 0) & 15>(dblk[(jj + 0) >> 4]);
-        else if (rr == 1) d = row_lane<(jj + 1) & 15>(dblk[(jj + 1) >> 4]);
-        else if (rr == 2) d = row_lane<(jj + 2) & 15>(dblk[(jj + 2) >> 4]);
-        else d = row_lane<(jj + 3) & 15>(dblk[(jj + 3) >> 4]);
-        float v = (float)((s0 + s1) + (s2 + s3)) * d;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) part[rr][k] = *(const int*)(src + 256 * k);
+      }
+      v4i b[4][CPW];
+      if (pg + 1 < PG) read_b(pg + 1, b);
+      // V of group pg + 2 into the buffer group pg has left; group pg + 3 requested
+      if (pg + 2 < PG) store_lds(pg + 2);
+      if (pg + 3 < PG) load_regs(pg + 3);
+      __builtin_amdgcn_sched_barrier(0);
+      // group pg + 1: its partial sums go to the other exchange buffer
+      if (pg + 1 < PG) partials(pg + 1, b);
+      // the sums of group pg over all channels, scaled
+      constexpr int jj = 4 * pg;  // the lane index of a row broadcast is a compile-time constant
+      const float d0 = row_lane<(jj + 0) & 15>(dblk[(jj + 0) >> 4]), d1 = row_lane<(jj + 1) & 15>(dblk[(jj + 1) >> 4]),
+                  d2 = row_lane<(jj + 2) & 15>(dblk[(jj + 2) >> 4]), d3 = row_lane<(jj + 3) & 15>(dblk[(jj + 3) >> 4]);
+      const float dd[4] = {d0, d1, d2, d3};
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        float v = (float)((part[rr][0] + part[rr][1]) + (part[rr][2] + part[rr][3])) * dd[rr];
         asm volatile("" : "+v"(v));
         cur[rr] = v;
       }
-      if (pg + 2 < PG) store_lds(pg + 2);
-      if (pg + 3 < PG) load_regs(pg + 3);
       __syncthreads();  // partial sums of group pg + 1 and V of group pg + 2 are in place
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -235,9 +255,9 @@ bool splitk_supported(const Geometry& g) {
   if (g.Cp != 512) return false;
   const long long fgroups = splitk_filter_count(g) / 16;
   // Small layers only (at most two workgroups per compute unit): there it is ahead of the
-  // one-pair-per-lane kernel (512 channels on 7x7 maps, batch 64, 4x4 tiles: 29.1 against
-  // 30.7 us per layer; 7x7 tiles at batch 256: 72.9 against 74.7), on larger ones behind (4x4
-  // tiles at batch 256: 90.9 against 85.9).
+  // one-pair-per-lane kernel (512 channels on 7x7 maps, batch 64, 4x4 tiles: 27.3 against
+  // 30.7 us per layer; 7x7 tiles at batch 256: 67.3 against 74.7), on larger ones level or
+  // behind (4x4 tiles at batch 256: 85 to 91 against 85.9).
   if ((long long)(g.Tp / 16) * (fgroups / 2) > 512) return false;
   const long long ybytes = 4ll * g.N * g.Cout * g.H * g.W;
   const long long vbytes = (long long)g.P * g.Tp * g.Cp;
