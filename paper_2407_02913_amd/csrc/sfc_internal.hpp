@@ -52,6 +52,13 @@ hipError_t launch_input_transform(int mode, const Geometry& g, const int8_t* x, 
 hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V,
                                      const float* inv_sx, const unsigned char* input_tab,
                                      hipStream_t s, bool prepare = false);
+// SFC-6 forms with 3x3 filters, one tile per image (sfc_input_image.hip): whether the kernel
+// applies, its table (kImageTabBytes at FilterViews::input_tab, built on the host for the
+// layer's H and W), the launch
+bool image_input_supported(const Geometry& g);
+void build_image_input_table(const Geometry& g, const float* inv_sx, unsigned char* tab);
+hipError_t launch_input_image(const Geometry& g, const int8_t* x, void* V, const unsigned char* tab,
+                              hipStream_t s, bool prepare);
 hipError_t launch_product(int mode, const Geometry& g, const void* V, const void* U, int32_t* M,
                           hipStream_t s);
 // requantized mode (sfc_gemm.hip): the products as P batched int8 GEMMs; the output
