@@ -261,7 +261,10 @@ sfc_status sfc_conv2d_stages(const sfc_plan_t* plan, const int8_t* x_dev, float 
 /* Where the intermediate tensors of the last call live, for parity checks.
  * which: 0 = V [P][tiles][Cin], 1 = U [P][Cout][Cin], 2 = M [P][tiles][Cout] (int32).
  * ptr receives a device address inside workspace_dev (V, M) or the filter buffer
- * (U); elem_bytes is 1 or 2 for V and U (int8 / int16) and 4 for M.  The tensor is
+ * (U); elem_bytes is 1 or 2 for V and U (int8 / int16) and 4 or 3 for M: in requantized
+ * mode, when Cin rounded up to 64, times the square of the transform-domain bound
+ * 2^(bits-1) - 1, is below 2^23 (int8: up to 512 channels), no sum can reach 2^23 in
+ * magnitude and each is kept as a little-endian 24-bit two's complement integer.  The tensor is
  * described as a five-axis strided view (strides in elements): element (p, a, b) of
  * the logical tensor [P][A][B] sits at
  *   p*strides[0] + (a / dims[2])*strides[1] + (a % dims[2])*strides[2]

@@ -247,11 +247,18 @@ class Plan:
         off = ptr.value - base.data_ptr()
         nbytes = base.numel() * base.element_size()
         assert 0 <= off < nbytes
-        dtype = {1: torch.int8, 2: torch.int16, 4: torch.int32}[esz.value]
         torch.cuda.synchronize()
-        flat = base.view(torch.uint8)[off:].view(dtype)
-        view = torch.as_strided(flat, tuple(dims), tuple(strides))
-        full = view.cpu().numpy().reshape(dims[0], dims[1] * dims[2], dims[3] * dims[4])
+        if esz.value == 3:  # 24-bit sums: three bytes per element, little-endian, two's complement
+            flat = base.view(torch.uint8)[off:]
+            view = torch.as_strided(flat, tuple(dims) + (3,), tuple(3 * s for s in strides) + (1,))
+            b = view.cpu().numpy().astype(np.int32)
+            full = (b[..., 0] | (b[..., 1] << 8) | (b[..., 2] << 16))
+            full = (full ^ 0x800000) - 0x800000
+        else:
+            dtype = {1: torch.int8, 2: torch.int16, 4: torch.int32}[esz.value]
+            flat = base.view(torch.uint8)[off:].view(dtype)
+            full = torch.as_strided(flat, tuple(dims), tuple(strides)).cpu().numpy()
+        full = full.reshape(dims[0], dims[1] * dims[2], dims[3] * dims[4])
         d = self.desc
         rows, cols = {"V": (self.tiles, d.Cin), "U": (d.Cout, d.Cin), "M": (self.tiles, d.Cout)}[which]
         return full[:, :rows, :cols].copy()

@@ -514,7 +514,7 @@ sfc_status sfc_tap_info(const sfc_plan_t* plan, const void* workspace_dev, int32
       if (!workspace_dev) return SFC_EINVAL;
       if (plan->d.path != SFC_PATH_STAGED) return SFC_EUNSUPPORTED;
       *ptr = ws + plan->off_M;
-      *elem_bytes = 4;
+      *elem_bytes = plan->d.mode == SFC_MODE_REQUANT_I8 ? sfc::m_sum_bytes(g) : 4;
       dims[0] = g.P;
       strides[0] = (int64_t)g.Tp * g.Kp;
       if (plan->d.mode == SFC_MODE_REQUANT_I8) {

@@ -32,7 +32,8 @@ constexpr int kGemmPitch = 80;   // LDS bytes per operand row (64 + padding)
 __global__ __launch_bounds__(256) void product_gemm_i8_kernel(const int8_t* __restrict__ V,
                                                               const int8_t* __restrict__ U,
                                                               int32_t* __restrict__ M, Geometry g,
-                                                              int nbt, int nbf, int stream_m) {
+                                                              int nbt, int nbf, int stream_m,
+                                                              int m_bytes) {
   constexpr int BL = kGemmBlock, PITCH = kGemmPitch;
   constexpr int TILE_BYTES = BL * PITCH;  // one staged operand
   __shared__ __align__(16) unsigned char lds[4 * TILE_BYTES];  // [buffer][U, V]
@@ -112,9 +113,11 @@ __global__ __launch_bounds__(256) void product_gemm_i8_kernel(const int8_t* __re
   }
 
   // lane: filter quad (k0 + 16*i)/4 + lane/16, tile block (t0 + 16*j)/16, tile lane%16 of it:
-  // the four sums of an accumulator are 16 contiguous bytes of M, a wave writes 1 KiB
+  // the four sums of an accumulator are 16 contiguous bytes of M (12 when the sums are kept
+  // in three bytes each, m_sum_bytes), a wave writes 1 KiB (768 bytes)
+  const size_t plane = (size_t)g.Tp * g.Kp * (size_t)m_bytes;
   const __amdgpu_buffer_rsrc_t mres = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)(M + (size_t)p * g.Tp * g.Kp), 0, g.Tp * g.Kp * 4, kBufferFlags);
+      (void*)((unsigned char*)M + (size_t)p * plane), 0, (int)plane, kBufferFlags);
   const int k0 = bf * BL + wm * 64, t0 = bt * BL + wn * 64;
   const int kquads = g.Kp >> 2;
 #pragma unroll
@@ -124,15 +127,34 @@ __global__ __launch_bounds__(256) void product_gemm_i8_kernel(const int8_t* __re
     for (int i = 0; i < 4; ++i) {
       const int kq = ((k0 + 16 * i) >> 2) + (lane >> 4);
       if (tb * 16 < g.Tp && kq < kquads) {
-        // a wave writes 1 KiB of whole cache lines; stream_m: past the L2 ("nt")
-        const unsigned off = (unsigned)(((tb * kquads + kq) * 64 + (lane & 15) * 4) * 4);
-        if (stream_m)
-          __builtin_amdgcn_raw_buffer_store_b128(acc[i][j], mres, off, 0, kStreamStore);
-        else
-          __builtin_amdgcn_raw_buffer_store_b128(acc[i][j], mres, off, 0, 0);
+        // a wave writes whole cache lines; stream_m: past the L2 ("nt")
+        const unsigned elem = (unsigned)((tb * kquads + kq) * 64 + (lane & 15) * 4);
+        const v4i a = acc[i][j];
+        if (m_bytes == 3) {
+          v3i d;
+          d[0] = (int)__builtin_amdgcn_perm((unsigned)a[1], (unsigned)a[0], 0x04020100u);
+          d[1] = (int)__builtin_amdgcn_perm((unsigned)a[2], (unsigned)a[1], 0x05040201u);
+          d[2] = (int)__builtin_amdgcn_perm((unsigned)a[3], (unsigned)a[2], 0x06050402u);
+          if (stream_m)
+            __builtin_amdgcn_raw_buffer_store_b96(d, mres, elem * 3u, 0, kStreamStore);
+          else
+            __builtin_amdgcn_raw_buffer_store_b96(d, mres, elem * 3u, 0, 0);
+        } else if (stream_m) {
+          __builtin_amdgcn_raw_buffer_store_b128(a, mres, elem * 4u, 0, kStreamStore);
+        } else {
+          __builtin_amdgcn_raw_buffer_store_b128(a, mres, elem * 4u, 0, 0);
+        }
       }
     }
   }
+}
+
+// Bytes per sum of M.  A sum of Cp products of operands within +-qmax is below 2^23 in
+// magnitude when Cp qmax^2 < 2^23 (int8 operands: up to 512 channels); it is then stored as a
+// little-endian 24-bit two's complement integer, which takes a quarter off the largest tensor
+// of the staged path (512 channels on 7x7 maps, 256 images: M 69 -> 52 MB).
+int m_sum_bytes(const Geometry& g) {
+  return (double)g.Cp * (double)g.qmax * (double)g.qmax < 8388608.0 ? 3 : 4;
 }
 
 hipError_t launch_product_gemm_i8(const Geometry& g, const void* V, const void* U, int32_t* M,
@@ -147,9 +169,10 @@ hipError_t launch_product_gemm_i8(const Geometry& g, const void* V, const void* 
   // stores: the L2 then holds no dirty lines for the end of the kernel to write back (512
   // channels on 7x7 maps, 256 images, M = 69 MB: 23.4 instead of 27.6 us; the output
   // transform that follows reads M from memory either way once several batches are in flight).
-  const int stream_m = (long long)g.P * g.Tp * g.Kp * 4 > (48ll << 20) ? 1 : 0;
+  const int m_bytes = m_sum_bytes(g);
+  const int stream_m = (long long)g.P * g.Tp * g.Kp * m_bytes > (48ll << 20) ? 1 : 0;
   hipLaunchKernelGGL(product_gemm_i8_kernel, dim3((unsigned)total), dim3(256), 0, s,
-                     (const int8_t*)V, (const int8_t*)U, M, g, nbt, nbf, stream_m);
+                     (const int8_t*)V, (const int8_t*)U, M, g, nbt, nbf, stream_m, m_bytes);
   return hipGetLastError();
 }
 
@@ -164,7 +187,12 @@ hipError_t launch_product_gemm_i8(const Geometry& g, const void* V, const void* 
 // (whole_image_tiles); y is then written image by image (store_planes) from a staging
 // block of M*M floats per pair.
 // ---------------------------------------------------------------------------------------
-constexpr int kSumRing = 12;
+// Points in flight per lane: 12 where a compute unit holds many waves; 32 for the forms
+// whose partial outputs allow few (7x7 tiles, 5x5 and 7x7 filters: four-wave workgroups), so
+// that the eight waves a compute unit has on a small layer still keep some 64 KB of M on
+// the way (512 channels on 7x7 maps, 256 images: 22.8 us with 12).
+template <int ALG>
+constexpr int sum_ring() { return AlgTraits<ALG>::NC <= 8 ? 12 : 32; }
 
 template <int ALG, bool PLANES, int NW>
 constexpr unsigned sums_stage_bytes() {
@@ -175,9 +203,10 @@ template <int ALG, int OUT, bool VEC2, int NW, bool PLANES>
 __global__ __launch_bounds__(NW * 64) void output_sums_kernel(const int32_t* __restrict__ M,
                                                               const float* __restrict__ dequant,
                                                               float x_scale, float inv_y,
-                                                              void* __restrict__ y, Geometry g) {
+                                                              void* __restrict__ y, Geometry g,
+                                                              int m_bytes) {
   using Tr = AlgTraits<ALG>;
-  constexpr int P = Tr::P, Mo = Tr::M, NC = Tr::NC, D = kSumRing;
+  constexpr int P = Tr::P, Mo = Tr::M, NC = Tr::NC, D = sum_ring<ALG>();
   constexpr Order<ALG> order{};
   extern __shared__ __align__(16) unsigned char lds[];  // staging blocks, then the tile table
   const int lane = threadIdx.x & 63;
@@ -196,9 +225,12 @@ __global__ __launch_bounds__(NW * 64) void output_sums_kernel(const int32_t* __r
   }
   __syncthreads();
 
-  const unsigned mplane = (unsigned)g.Tp * (unsigned)g.Kp * 4u;  // bytes of one point of M
-  const __amdgpu_buffer_rsrc_t mres =
-      __builtin_amdgcn_make_buffer_rsrc((void*)M, 0, (int)(mplane * (unsigned)P), kBufferFlags);
+  // bytes of one point of M; three-byte sums are read as the low bytes of a dword (the last
+  // one reaches a byte past the tensor, inside the 256-byte rounding of its buffer)
+  const unsigned mplane = (unsigned)g.Tp * (unsigned)g.Kp * (unsigned)m_bytes;
+  const unsigned msh = m_bytes == 3 ? 8u : 0u;
+  const __amdgpu_buffer_rsrc_t mres = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)M, 0, (int)(mplane * (unsigned)P + (4u - (unsigned)m_bytes)), kBufferFlags);
   const __amdgpu_buffer_rsrc_t dres = __builtin_amdgcn_make_buffer_rsrc(
       (void*)dequant, 0, Order<ALG>::PP * g.Kp * 4, kBufferFlags);
   constexpr unsigned esz = OUT == 2 ? 1u : 4u;
@@ -207,7 +239,8 @@ __global__ __launch_bounds__(NW * 64) void output_sums_kernel(const int32_t* __r
   // filters beyond the padded count read nothing (zeros) and store nothing
   const bool kvalid = kcol < g.Kp;
   const unsigned m_lane =
-      kvalid ? (unsigned)(((blockIdx.x * (g.Kp >> 2) + kq) * 64 + (lane & 15) * 4 + (lane >> 4)) * 4)
+      kvalid ? (unsigned)((blockIdx.x * (g.Kp >> 2) + kq) * 64 + (lane & 15) * 4 + (lane >> 4)) *
+                   (unsigned)m_bytes
              : 0x80000000u;
   // dequantization factors: [filter][processing position], one 16-byte load per four points
   static_assert(D % 4 == 0, "the ring holds whole groups of four points");
@@ -229,7 +262,7 @@ __global__ __launch_bounds__(NW * 64) void output_sums_kernel(const int32_t* __r
   for (int j = 0; j < D && j < P; ++j) load_point(j);
   int j = 0;  // folds to a constant after unrolling
   auto next = [&]() -> float {
-    float v = (float)mring[j % D] * dring[(j >> 2) % (D / 4)][j & 3];
+    float v = (float)((mring[j % D] << msh) >> msh) * dring[(j >> 2) % (D / 4)][j & 3];
     asm volatile("" : "+v"(v));  // the slot is free from here on
     if (j + D < P) load_point(j + D);
     // the factor slot of a group is free once its fourth product has been taken
@@ -262,7 +295,7 @@ static hipError_t launch_sums_impl(const Geometry& g, const int32_t* M, const Fi
                                    : hipSuccess;
   const dim3 grid((unsigned)(g.Tp / 16), (unsigned)((g.Cout + 4 * NW - 1) / (4 * NW)));
   hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), lds_bytes, s, M, f.dequant_single, x_scale,
-                     inv_y, y, g);
+                     inv_y, y, g, m_sum_bytes(g));
   return hipGetLastError();
 }
 

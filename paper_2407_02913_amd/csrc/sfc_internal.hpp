@@ -63,6 +63,8 @@ hipError_t launch_product(int mode, const Geometry& g, const void* V, const void
                           hipStream_t s);
 // requantized mode (sfc_gemm.hip): the products as P batched int8 GEMMs; the output
 // transform reading their sums (out: 0 float32, 2 int8 with ReLU)
+// bytes per int32 sum of M as the GEMM stores it (3: 24-bit, when no sum can exceed that; 4)
+int m_sum_bytes(const Geometry& g);
 hipError_t launch_product_gemm_i8(const Geometry& g, const void* V, const void* U, int32_t* M,
                                   hipStream_t s);
 hipError_t launch_output_sums(int out, const Geometry& g, const int32_t* M, const FilterViews& f,

@@ -70,11 +70,14 @@ class Layer:
     def kernels(self):
         """The kernels one call launches: name -> (stage mask, algorithmic bytes, int8 MFMA
         operations or 0).  Algorithmic bytes: every tensor a kernel must read or write, once --
-        x = N Cin H W, V = P T Cin, U = P Cout Cin, M = 4 P T Cout, y = N Cout H W times the
-        output element size; operations of the products: 2 P T Cin Cout."""
+        x = N Cin H W, V = P T Cin, U = P Cout Cin, M = P T Cout times the bytes of a sum (three
+        while Cin, rounded up to 64, times 127^2 stays below 2^23, as the library stores them; else
+        four), y = N Cout H W times the output element size; operations of the products:
+        2 P T Cin Cout."""
         s, p, t = self.shape, self.P, self.tiles
         x = self.N * s.Cin * s.H * s.W
-        v, u, m = p * t * s.Cin, p * s.Cout * s.Cin, 4 * p * t * s.Cout
+        mb = 3 if -(-s.Cin // 64) * 64 * 127 * 127 < 2 ** 23 else 4
+        v, u, m = p * t * s.Cin, p * s.Cout * s.Cin, mb * p * t * s.Cout
         y = self.N * s.Cout * s.H * s.W * (1 if self.out == "i8" else 4)
         ops = 2 * p * t * s.Cin * s.Cout
         if self.path == "single":

@@ -87,6 +87,7 @@ IMAGE_SHAPES = [  # feature maps of one tile per image (H, W <= tile edge): the 
     (3, 200, 16, 5, 6),   # four ranges of 64 channels, planes of 30 bytes
     (9, 130, 8, 6, 6),    # one full 6x6 tile
     (520, 130, 8, 3, 2),  # ranges of 128 channels, the last half empty (Cin padded to 192)
+    (2, 600, 8, 6, 6),    # more than 512 channels: the sums of M take four bytes, not three
 ]
 
 
@@ -106,6 +107,27 @@ def test_single_tile_images_taps_bit_exact(binding, shape, alg):
     if alg.startswith("7x7") and -(-shape[1] // 64) in (1, 2, 4, 8):  # what the fused path takes
         y = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path="fused", sx=sx, sw=sw)
         assert rel_err(y, y_ref) <= F32_TOL
+
+
+@pytest.mark.parametrize("alg", ["7x7_p132", "4x4_p46"])
+def test_staged_sums_at_the_three_byte_bound(binding, alg):
+    """512 channels with every transform-domain operand at the clamp: sums of +-512 * 127^2 =
+    +-8258048, the largest a three-byte sum of M has to hold, bit-exact."""
+    shape = (2, 512, 20, 7, 7)
+    rng = np.random.default_rng(77)
+    x = rng.choice(np.array([-127, 127], dtype=np.int8), size=(shape[0], shape[1], shape[3], shape[4]))
+    x[0] = 127  # a constant image: its zero-frequency point is at the clamp in every channel
+    w = np.full((shape[2], shape[1], 3, 3), 127, dtype=np.int8)
+    w[1::2] = -127
+    print("case bound", alg, flush=True)
+    sx = np.full_like(oracle.calibrate_act_scales(x, alg), 1e-3)
+    sw = np.full_like(oracle.calibrate_filter_scales(w, alg), 1e-3)
+    y_ref, taps_ref = oracle.conv_requant(x, w, sx, sw, 0.02, 0.01, alg, return_taps=True)
+    assert np.abs(taps_ref["M"]).max() == 512 * 127 * 127
+    y, taps = binding.conv2d(x, w, 0.02, 0.01, mode="requant", alg=alg, sx=sx, sw=sw, return_taps=True)
+    for name in ("V", "U", "M"):
+        assert np.array_equal(taps[name].astype(np.int64), taps_ref[name]), name
+    assert rel_err(y, y_ref) <= F32_TOL
 
 
 @pytest.mark.parametrize("bits", [4, 6])
