@@ -202,8 +202,8 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
   p->off_input_tab = off;
   if (d.mode == SFC_MODE_REQUANT_I8 && (d.alg == SFC_ALG_4X4_P46 || d.alg == SFC_ALG_4X4_P49))
     off = align_up(off + sfc::kInputTabBytes, 256);
-  else if (d.mode == SFC_MODE_REQUANT_I8 && sfc::image_input_supported(g))
-    off = align_up(off + sfc::kImageTabBytes, 256);
+  if (d.mode == SFC_MODE_REQUANT_I8 && sfc::image_input_supported(g))
+    off = align_up(off + sfc::image_table_bytes(g), 256);
   p->off_dq_single = off;
   p->off_U_single = off;
   p->quad_filters = 0;
@@ -371,8 +371,9 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
   }
   if (plan->off_dq_single > plan->off_input_tab) {
     unsigned char* tab = reinterpret_cast<unsigned char*>(table(plan->off_input_tab));
-    if (sfc::image_input_supported(g)) sfc::build_image_input_table(g, inv_sx, tab);
-    else sfc::build_input_table(plan->d.alg, inv_sx, tab);
+    if (g.alg == SFC_ALG_4X4_P46 || g.alg == SFC_ALG_4X4_P49) sfc::build_input_table(g.alg, inv_sx, tab);
+    if (sfc::image_input_supported(g))
+      sfc::build_image_input_table(g, inv_sx, tab + sfc::image_table_offset(g));
   }
   if (plan->dq_filters > 0) {
     const int pp = (g.P + 3) / 4 * 4;

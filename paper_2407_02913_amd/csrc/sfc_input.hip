@@ -328,7 +328,8 @@ static hipError_t launch_input_i8_alg(const Geometry& g, const InputPlan& ip, co
 hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V,
                                      const float* inv_sx, const unsigned char* intab,
                                      hipStream_t s, bool prepare) {
-  if (image_input_supported(g)) return launch_input_image(g, x, V, intab, s, prepare);
+  if (image_input_supported(g))
+    return launch_input_image(g, x, V, intab ? intab + image_table_offset(g) : nullptr, s, prepare);
   WaveInputPlan wp;
   if (make_wave_input_plan(g, &wp))
     return g.alg == 4 ? launch_input_waves_alg<4>(g, wp, x, V, intab, s, prepare)

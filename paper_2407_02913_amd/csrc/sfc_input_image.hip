@@ -1,15 +1,16 @@
-// Input-tile transform of the SFC-6 forms with 3x3 filters when an image is a single tile
-// (H, W <= the tile edge: the 7x7 feature maps of the last stage under the 7x7 tiles of
-// Sec. 4.2), requantized mode, on the matrix cores (gfx950).
+// Input-tile transform of the forms with 3x3 filters on feature maps of at most 64 samples
+// and at most four tiles (the 7x7 maps of the last stage: one 7x7 tile of Sec. 4.2, or four
+// 4x4 tiles), requantized mode, on the matrix cores (gfx950).
 //
-// With one tile per image every patch sample outside the image is padding, so V = B^T x B
-// (Eq. 7 with the matrices of Sec. 4.1 / Appendix A) is a sum over the H W <= 49 image samples
-// alone: k = h W + w indexes them as they lie in memory, and one int8 MFMA 16x16x64 takes the
-// sums of 16 channels (operand A: row = channel, 64 k-bytes = the start of the channel plane)
-// for 16 multiplication points (operand B: coefficients 0, +-1, +-2 by processing position,
-// produced on the host from the add networks of sfc_points.hpp for the layer's H and W).
+// Every sample of a patch lies in the image or is padding, so V = B^T x B (Eq. 7 with the
+// matrices of Sec. 4.1 / Appendix A) of any tile is a sum over the H W <= 64 image samples:
+// k = h W + w indexes them as they lie in memory, and one int8 MFMA 16x16x64 takes the sums
+// of 16 channels (operand A: row = channel, 64 k-bytes = the start of the channel plane, the
+// same for every tile of the image) for 16 multiplication points (operand B: coefficients
+// 0, +-1, +-2 by tile of the image and processing position, produced on the host from the
+// add networks of sfc_points.hpp for the layer's H and W).
 //
-// A wave owns one image and CG groups of 16 channels.  It reads its planes from global memory
+// A wave owns one tile and CG groups of 16 channels.  It reads its planes from global memory
 // straight into operands (four dword loads per lane and group of channels; no staging, no
 // workgroup barrier), takes the sums block by block of 16 points, rounds them (four channels
 // of a point per lane: one dword), turns each block round in a small piece of LDS that only it
@@ -26,10 +27,11 @@ namespace sfc {
 
 // the table behind operand B: float inv_pos[144] (1 / s_Tx by processing position, 0 for
 // positions without a point), int point[144] (canonical point of a position, -1: none), int8
-// coeff[144][64] ([position][k])
+// coeff[tiles per image][144][64] ([tile][position][k])
 constexpr unsigned kImageTabPoint = kImageTabRows * 4;
 constexpr unsigned kImageTabCoeff = kImageTabRows * 8;
-static_assert(kImageTabBytes == kImageTabCoeff + kImageTabRows * 64, "table layout");
+constexpr unsigned kImageTabTile = kImageTabRows * 64;
+constexpr int kImageMaxTiles = 4;
 
 
 template <int ALG, int CG>
@@ -37,7 +39,7 @@ __global__ __launch_bounds__(256, 2) void input_transform_image_kernel(
     const int8_t* __restrict__ x, int8_t* __restrict__ V, const unsigned char* __restrict__ tab,
     Geometry g) {
   using Tr = AlgTraits<ALG>;
-  static_assert(Tr::kFamily == 6 && Tr::R == 3, "SFC-6 with 3x3 filters");
+  static_assert(Tr::R == 3, "3x3 filters");
   constexpr int P = Tr::P, PP = Order<ALG>::PP, NPB = (PP + 15) / 16;
   static_assert(16 * NPB <= kImageTabRows, "table rows");
   // LDS bytes per position of a block: the dword writes of a block fall into 64 different banks
@@ -45,13 +47,15 @@ __global__ __launch_bounds__(256, 2) void input_transform_image_kernel(
   __shared__ __align__(16) unsigned char lds[4 * 16 * kImageBlockRow];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  // unit = (image, channel range), the channel range varying fastest: the waves that write the
+  // unit = (tile, channel range), the channel range varying fastest: the waves that write the
   // parts of one row of V run next to each other, on one XCD
   const int ranges = (g.Cp + 16 * CG - 1) / (16 * CG);
   const int unit = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + wave;
-  const int n = unit / ranges;
-  const int c0 = (unit - n * ranges) * (16 * CG);
-  if (n >= g.N) return;  // (whole waves; the kernel has no workgroup barrier)
+  const int t = unit / ranges;  // tiles are numbered image by image
+  const int c0 = (unit - t * ranges) * (16 * CG);
+  if (t >= g.T) return;  // (whole waves; the kernel has no workgroup barrier)
+  const int tpi = g.th * g.tw;
+  const int n = t / tpi, tile = t - n * tpi;
 
   // ---- operands A: 16 bytes from byte 16 (lane / 16) of the plane of channel c0 + 16 q + lane % 16
   const int hw = g.H * g.W;
@@ -84,7 +88,7 @@ __global__ __launch_bounds__(256, 2) void input_transform_image_kernel(
   // ---- operands B and the per-position constants
   const float* inv_pos = (const float*)tab;
   const int* point = (const int*)(tab + kImageTabPoint);
-  const unsigned char* ctab = tab + kImageTabCoeff;
+  const unsigned char* ctab = tab + kImageTabCoeff + (unsigned)tile * kImageTabTile;
   v4i coeff[NPB];
   float inv[NPB];
 #pragma unroll
@@ -110,7 +114,7 @@ __global__ __launch_bounds__(256, 2) void input_transform_image_kernel(
       const int p = point[16 * m + RPS * h + prow];
       pofs[m][h] = p >= 0 && cok ? (unsigned)p * vplane + (unsigned)(c0 + 16 * piece) : 0x80000000u;
     }
-  const unsigned trow = (unsigned)n * (unsigned)g.Cp;  // one tile per image: tile index = image
+  const unsigned trow = (unsigned)t * (unsigned)g.Cp;
   unsigned char* blk = lds + wave * (16 * kImageBlockRow);
 
   // ---- block by block of 16 positions; the matrix instructions of block m + 1 are issued
@@ -154,8 +158,8 @@ __global__ __launch_bounds__(256, 2) void input_transform_image_kernel(
 }
 
 bool image_input_supported(const Geometry& g) {
-  if (g.alg < 0 || g.alg > 3) return false;
-  if (g.th != 1 || g.tw != 1 || g.H * g.W > 64) return false;
+  if (g.alg < 0 || g.alg > 5) return false;
+  if (g.th * g.tw > kImageMaxTiles || g.H * g.W > 64) return false;
   const long long xb = (long long)g.N * g.Cin * g.H * g.W;
   const long long vb = (long long)g.P * g.Tp * g.Cp;
   return xb < (1ll << 31) && vb < (1ll << 31);
@@ -169,29 +173,43 @@ static void fill_image_table(const Geometry& g, const float* inv_sx, unsigned ch
   using Tr = AlgTraits<ALG>;
   constexpr int NI = Tr::NI, NC = Tr::NC;
   constexpr Order<ALG> order{};
-  std::memset(tab, 0, kImageTabBytes);
+  std::memset(tab, 0, image_table_bytes(g));
   float* inv_pos = reinterpret_cast<float*>(tab);
   int* point = reinterpret_cast<int*>(tab + kImageTabPoint);
   signed char* coeff = reinterpret_cast<signed char*>(tab) + kImageTabCoeff;
   for (int p = 0; p < Tr::P; ++p) inv_pos[order.pos[p]] = inv_sx[p];
   for (int j = 0; j < kImageTabRows; ++j) point[j] = j < Order<ALG>::PP ? order.pt[j] : -1;
-  for (int h = 0; h < g.H; ++h)
-    for (int w = 0; w < g.W; ++w) {
-      const int i = h + Tr::PAD, j = w + Tr::PAD;
-      int half[NI][NC], comp[NC][NC];
-      for (int r = 0; r < NI; ++r) {
-        int row[NI] = {};
-        if (r == i) row[j] = 1;
-        fwd_input<NI, NC>(row, half[r]);
+  for (int tile = 0; tile < g.th * g.tw; ++tile) {
+    const int r0 = Tr::M * (tile / g.tw) - Tr::PAD, q0 = Tr::M * (tile % g.tw) - Tr::PAD;
+    for (int i = 0; i < NI; ++i)
+      for (int j = 0; j < NI; ++j) {
+        const int h = r0 + i, w = q0 + j;
+        if (h < 0 || h >= g.H || w < 0 || w >= g.W) continue;
+        int half[NI][NC], comp[NC][NC];
+        for (int r = 0; r < NI; ++r) {
+          int row[NI] = {};
+          if (r == i) row[j] = 1;
+          fwd_input<NI, NC>(row, half[r]);
+        }
+        for (int b = 0; b < NC; ++b) {
+          int colv[NI], cc[NC];
+          for (int r = 0; r < NI; ++r) colv[r] = half[r][b];
+          fwd_input<NI, NC>(colv, cc);
+          for (int a = 0; a < NC; ++a) comp[a][b] = cc[a];
+        }
+        for_each_point<ALG>(comp, [&](int p, int v) {
+          coeff[(unsigned)tile * kImageTabTile + order.pos[p] * 64 + h * g.W + w] = (signed char)v;
+        });
       }
-      for (int b = 0; b < NC; ++b) {
-        int colv[NI], cc[NC];
-        for (int r = 0; r < NI; ++r) colv[r] = half[r][b];
-        fwd_input<NI, NC>(colv, cc);
-        for (int a = 0; a < NC; ++a) comp[a][b] = cc[a];
-      }
-      for_each_point<ALG>(comp, [&](int p, int v) { coeff[order.pos[p] * 64 + h * g.W + w] = (signed char)v; });
-    }
+  }
+}
+
+unsigned image_table_offset(const Geometry& g) {
+  return g.alg == 4 || g.alg == 5 ? (kInputTabBytes + 255u) & ~255u : 0u;
+}
+
+unsigned image_table_bytes(const Geometry& g) {
+  return image_input_supported(g) ? kImageTabCoeff + (unsigned)(g.th * g.tw) * kImageTabTile : 0u;
 }
 
 void build_image_input_table(const Geometry& g, const float* inv_sx, unsigned char* tab) {
@@ -200,17 +218,19 @@ void build_image_input_table(const Geometry& g, const float* inv_sx, unsigned ch
     case 1: fill_image_table<1>(g, inv_sx, tab); break;
     case 2: fill_image_table<2>(g, inv_sx, tab); break;
     case 3: fill_image_table<3>(g, inv_sx, tab); break;
-    default: std::memset(tab, 0, kImageTabBytes);
+    case 4: fill_image_table<4>(g, inv_sx, tab); break;
+    case 5: fill_image_table<5>(g, inv_sx, tab); break;
+    default: break;
   }
 }
 
 template <int ALG>
 static hipError_t launch_image_alg(const Geometry& g, const int8_t* x, void* V,
                                    const unsigned char* tab, hipStream_t s) {
-  // 128 channels per wave where that leaves at least four waves per compute unit, else 64
-  const bool wide = (long long)g.N * ((g.Cp + 127) / 128) >= 2048;
+  // 128 channels per wave where that leaves at least eight waves per compute unit, else 64
+  const bool wide = (long long)g.T * ((g.Cp + 127) / 128) >= 2048;
   const int ranges = wide ? (g.Cp + 127) / 128 : g.Cp / 64;
-  const unsigned grid = (unsigned)(((long long)g.N * ranges + 3) / 4);
+  const unsigned grid = (unsigned)(((long long)g.T * ranges + 3) / 4);
   if (wide)
     hipLaunchKernelGGL((input_transform_image_kernel<ALG, 8>), dim3(grid), dim3(256), 0, s, x, (int8_t*)V, tab, g);
   else
@@ -227,6 +247,8 @@ hipError_t launch_input_image(const Geometry& g, const int8_t* x, void* V, const
     case 1: return launch_image_alg<1>(g, x, V, tab, s);
     case 2: return launch_image_alg<2>(g, x, V, tab, s);
     case 3: return launch_image_alg<3>(g, x, V, tab, s);
+    case 4: return launch_image_alg<4>(g, x, V, tab, s);
+    case 5: return launch_image_alg<5>(g, x, V, tab, s);
   }
   return hipErrorInvalidValue;
 }

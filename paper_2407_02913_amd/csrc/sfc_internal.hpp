@@ -52,10 +52,13 @@ hipError_t launch_input_transform(int mode, const Geometry& g, const int8_t* x, 
 hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V,
                                      const float* inv_sx, const unsigned char* input_tab,
                                      hipStream_t s, bool prepare = false);
-// SFC-6 forms with 3x3 filters, one tile per image (sfc_input_image.hip): whether the kernel
-// applies, its table (kImageTabBytes at FilterViews::input_tab, built on the host for the
-// layer's H and W), the launch
+// 3x3 filters on feature maps of at most 64 samples and four tiles (sfc_input_image.hip):
+// whether the kernel applies, its table (image_table_bytes; in the filter buffer after the
+// table of the SFC-4 forms, image_table_offset bytes from FilterViews::input_tab; built on the
+// host for the layer's H and W), the launch
 bool image_input_supported(const Geometry& g);
+unsigned image_table_bytes(const Geometry& g);
+unsigned image_table_offset(const Geometry& g);
 void build_image_input_table(const Geometry& g, const float* inv_sx, unsigned char* tab);
 hipError_t launch_input_image(const Geometry& g, const int8_t* x, void* V, const unsigned char* tab,
                               hipStream_t s, bool prepare);

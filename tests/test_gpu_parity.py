@@ -81,19 +81,21 @@ def test_requant_mode_taps_bit_exact_and_output_close(binding, shape, alg):
     assert rel_err(y, y_ref) <= F32_TOL
 
 
-IMAGE_SHAPES = [  # feature maps of one tile per image (H, W <= tile edge): the input transform reads planes as they lie
+IMAGE_SHAPES = [  # feature maps of at most 64 samples and four tiles: the input transform reads planes as they lie
     (1, 3, 4, 7, 7),      # 147 bytes: the last dwords of the tensor are fetched byte by byte
     (5, 70, 24, 7, 7),    # channels padded to 128, the last 58 zero
     (3, 200, 16, 5, 6),   # four ranges of 64 channels, planes of 30 bytes
     (9, 130, 8, 6, 6),    # one full 6x6 tile
     (520, 130, 8, 3, 2),  # ranges of 128 channels, the last half empty (Cin padded to 192)
     (2, 600, 8, 6, 6),    # more than 512 channels: the sums of M take four bytes, not three
+    (3, 96, 8, 8, 8),     # 64 samples, four tiles per image in every form
+    (2, 40, 8, 2, 16),    # one row of four 4x4 tiles (three 6x6 or 7x7 tiles)
 ]
 
 
-@pytest.mark.parametrize("alg", ALGS)
+@pytest.mark.parametrize("alg", ALGS_STAGED)
 @pytest.mark.parametrize("shape", IMAGE_SHAPES)
-def test_single_tile_images_taps_bit_exact(binding, shape, alg):
+def test_small_images_taps_bit_exact(binding, shape, alg):
     x, w, xs, ws = uniform_case(shape, 250 + len(alg) + sum(shape))
     print("case image", shape, alg, flush=True)
     xc, _, _, _ = uniform_case(shape, 350 + sum(shape))
@@ -104,7 +106,7 @@ def test_single_tile_images_taps_bit_exact(binding, shape, alg):
     for name in ("V", "U", "M"):
         assert np.array_equal(taps[name].astype(np.int64), taps_ref[name]), name
     assert rel_err(y, y_ref) <= F32_TOL
-    if alg.startswith("7x7") and -(-shape[1] // 64) in (1, 2, 4, 8):  # what the fused path takes
+    if not alg.startswith("6x6") and -(-shape[1] // 64) in (1, 2, 4, 8):  # what the fused path takes
         y = binding.conv2d(x, w, xs, ws, mode="requant", alg=alg, path="fused", sx=sx, sw=sw)
         assert rel_err(y, y_ref) <= F32_TOL
 
