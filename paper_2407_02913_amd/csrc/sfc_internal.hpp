@@ -52,7 +52,8 @@ hipError_t launch_input_transform(int mode, const Geometry& g, const int8_t* x, 
 hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V,
                                      const float* inv_sx, const unsigned char* input_tab,
                                      hipStream_t s, bool prepare = false);
-// 3x3 filters on feature maps of at most 64 samples and four tiles (sfc_input_image.hip):
+// 3x3 filters on small feature maps (a patch within 128 bytes of a plane, at most 16 tiles per
+// image; sfc_input_image.hip):
 // whether the kernel applies, its table (image_table_bytes; in the filter buffer after the
 // table of the SFC-4 forms, image_table_offset bytes from FilterViews::input_tab; built on the
 // host for the layer's H and W), the launch

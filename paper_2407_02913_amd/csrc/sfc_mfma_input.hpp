@@ -26,9 +26,6 @@ constexpr unsigned kInputTabBytes = kInputTabPoints + kInputTabRows * 4;
 // Host: fills the table for one algorithm from the add networks (inv_sx by canonical point).
 void build_input_table(int alg, const float* inv_sx, unsigned char* tab);
 
-// The table of the small-image kernel (sfc_input_image.hip): 144 rows of float inv_pos and of
-// int point, then 144 rows of int8 coeff[64] per tile of an image.
-constexpr int kImageTabRows = 144;
 
 #ifdef __HIPCC__
 

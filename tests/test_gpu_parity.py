@@ -81,7 +81,7 @@ def test_requant_mode_taps_bit_exact_and_output_close(binding, shape, alg):
     assert rel_err(y, y_ref) <= F32_TOL
 
 
-IMAGE_SHAPES = [  # feature maps of at most 64 samples and four tiles: the input transform reads planes as they lie
+IMAGE_SHAPES = [  # small feature maps (a patch within 128 bytes of a plane): the input transform reads planes as they lie
     (1, 3, 4, 7, 7),      # 147 bytes: the last dwords of the tensor are fetched byte by byte
     (5, 70, 24, 7, 7),    # channels padded to 128, the last 58 zero
     (3, 200, 16, 5, 6),   # four ranges of 64 channels, planes of 30 bytes
@@ -90,6 +90,9 @@ IMAGE_SHAPES = [  # feature maps of at most 64 samples and four tiles: the input
     (2, 600, 8, 6, 6),    # more than 512 channels: the sums of M take four bytes, not three
     (3, 96, 8, 8, 8),     # 64 samples, four tiles per image in every form
     (2, 40, 8, 2, 16),    # one row of four 4x4 tiles (three 6x6 or 7x7 tiles)
+    (3, 70, 8, 14, 14),   # 16, 9 or 4 tiles per image, patches of up to 121 bytes: two steps of 64
+    (2, 64, 8, 9, 13),    # odd width
+    (1, 20, 8, 16, 15),   # 16 tiles of 4x4; too wide for the 7x7 forms (generic kernel)
 ]
 
 
