@@ -189,8 +189,9 @@ hipError_t launch_product_gemm_i8(const Geometry& g, const void* V, const void* 
 // ---------------------------------------------------------------------------------------
 // Points in flight per lane: 12 where a compute unit holds many waves; 32 for the forms
 // whose partial outputs allow few (7x7 tiles, 5x5 and 7x7 filters: four-wave workgroups), so
-// that the eight waves a compute unit has on a small layer still keep some 64 KB of M on
-// the way (512 channels on 7x7 maps, 256 images: 22.8 us with 12).
+// that the eight waves a compute unit has on a small layer keep some 64 KB of M on the way
+// (512 channels on 7x7 maps, 256 images: the same 23 us either way when measured alone; the
+// kernel there is bound by the bytes of M, see m_sum_bytes).
 template <int ALG>
 constexpr int sum_ring() { return AlgTraits<ALG>::NC <= 8 ? 12 : 32; }
 
