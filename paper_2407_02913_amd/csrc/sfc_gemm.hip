@@ -286,8 +286,9 @@ static hipError_t launch_sums_impl(const Geometry& g, const int32_t* M, const Fi
   // the 7x7 forms carry 10x7 partial outputs per pair, the 5x5- and 7x7-filter forms 12x6 or
   // 12x4: they need the 256-register budget; four waves per workgroup, so that a small layer
   // still has several workgroups per compute unit, reading M and writing y out of phase (512
-  // channels on 7x7 maps at batch 64, 7x7 tiles: staged path 38.9 us against 47.3 with eight)
-  constexpr int NW = AlgTraits<ALG>::NC <= 8 ? 16 : 4;
+  // channels on 7x7 maps at batch 64, 7x7 tiles: staged path 38.9 us against 47.3 with eight).
+  // The 6x6 forms (8x6 partial outputs) take eight waves: with sixteen, 128 registers, they spill.
+  constexpr int NW = AlgTraits<ALG>::NC <= 6 ? 16 : AlgTraits<ALG>::NC <= 8 ? 8 : 4;
   constexpr unsigned lds_bytes = sums_stage_bytes<ALG, PLANES, NW>() + 256;
   static_assert(lds_bytes <= 160u * 1024u, "staging blocks exceed the LDS of a compute unit");
   auto kernel = output_sums_kernel<ALG, OUT, VEC2, NW, PLANES>;
