@@ -206,7 +206,7 @@ __global__ __launch_bounds__(NW * 64, WGS) void fused_quad_kernel(
 
 // ---------------------------------------------------------------------------------
 
-constexpr int kQuadWaves6 = 16;  // waves per workgroup for the 6x6 forms
+constexpr int kQuadWaves6 = 8;  // waves per workgroup for the 6x6 forms
 inline int quad_waves(int alg, int kc) {
   // the 7x7 forms carry 10x7 partial outputs per pair, the 5x5-filter forms 12x6: they need
   // the 256-register budget
@@ -229,12 +229,12 @@ template <int ALG, int KC, int OUT, bool VEC2, bool PLANES = false>
 inline hipError_t launch_quad_impl(const Geometry& g, const void* V, const FilterViews& f,
                                    float x_scale, float inv_y, void* y, hipStream_t s,
                                    bool prepare) {
-  // 6x6 tiles with 3x3 filters: 16 waves of 128 registers.  The SFC-4 forms need under 100
-  // registers: 8-wave workgroups, two of which share a compute unit and run out of phase
-  // (measured 31.0 against 32.5 us per step on 128 channels at 28x28).  The other forms: 8
-  // waves with the 256-register budget.
+  // The SFC-4 forms need under 100 registers: 8-wave workgroups, two of which share a compute
+  // unit and run out of phase (measured 31.0 against 32.5 us per step on 128 channels at
+  // 28x28).  The other forms: 8 waves with the 256-register budget (the 6x6 forms spilled with
+  // 16 waves of 128 registers).
   constexpr int NW = ALG < 2 ? kQuadWaves6 : 8;
-  constexpr int WGS = ALG < 2 ? 16 / NW : AlgTraits<ALG>::NC == 6 ? 2 : 1;
+  constexpr int WGS = AlgTraits<ALG>::NC == 6 ? 2 : 1;
   auto kernel = fused_quad_kernel<ALG, KC, OUT, VEC2, NW, WGS, PLANES>;
   constexpr unsigned lds_bytes = quad_lds_layout<ALG, KC, NW, PLANES>(2);
   static_assert(lds_bytes <= 160u * 1024u, "V buffers and staging exceed the LDS of a compute unit");
