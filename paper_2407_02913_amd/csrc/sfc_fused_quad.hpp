@@ -49,8 +49,9 @@ __global__ __launch_bounds__(NW * 64, WGS) void fused_quad_kernel(
   constexpr int NT = NW * 64;
   constexpr int NL = (CHUNKS + NT - 1) / NT;  // pieces per thread and group
   // filter operand blocks in flight (four with eight chunks, where the 8-wave forms have the
-  // registers: 512 channels on 7x7 maps, 7x7 tiles, batch 256: 74.7 against 76.9 us)
-  constexpr int RA = KC < 2 ? 1 : (KC >= 8 && NW <= 8) ? 4 : 2;
+  // registers: 512 channels on 7x7 maps, 7x7 tiles, batch 256: 74.7 against 76.9 us; the 5x5-
+  // and 7x7-filter forms, with 12 classes of partial outputs, do not)
+  constexpr int RA = KC < 2 ? 1 : (KC >= 8 && NW <= 8 && AlgTraits<ALG>::NC <= 10) ? 4 : 2;
   constexpr Order<ALG> order{};
   extern __shared__ __align__(16) unsigned char lds[];
   unsigned char* vbuf = lds;  // [2][GROUP_BYTES], block (r*KC + kc) = 16 tiles x 64 bytes
