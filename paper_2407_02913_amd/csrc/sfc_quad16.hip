@@ -10,12 +10,13 @@ constexpr int kQuad16Waves = 4;
 bool quad16_supported(const Geometry& g) {
   if (g.alg != 4 && g.alg != 5) return false;
   const int kc = g.Cp / 64;
-  if (kc != 1 && kc != 2 && kc != 4 && kc != 8) return false;
+  // Up to four channel chunks: with eight a wave's filter operand stream (8 KiB per point) is
+  // not hidden behind its own arithmetic (sfc_splitk.hip and the one-pair-per-lane kernel take
+  // those layers).
+  if (kc != 1 && kc != 2 && kc != 4) return false;
   // A wave takes 256 (tile, filter) pairs: with fewer than one wave per SIMD of the chip the
-  // one-pair-per-lane kernel, whose waves take 64, fills it better (512 channels on 7x7 maps
-  // at batch 64: 22 against 37 us); the same with eight channel chunks, where a wave's filter
-  // operand stream (8 KiB per point) is not hidden behind its own arithmetic.
-  if (kc == 8 || (long long)(g.Tp / 16) * ((g.Cout + 15) / 16) < 1024) return false;
+  // one-pair-per-lane kernel, whose waves take 64, fills it better.
+  if ((long long)(g.Tp / 16) * ((g.Cout + 15) / 16) < 1024) return false;
   const long long fgroups = quad16_filter_count(g) / 16;
   const long long ybytes = 4ll * g.N * g.Cout * g.H * g.W;
   const long long vbytes = (long long)g.P * g.Tp * g.Cp;
@@ -102,7 +103,6 @@ static hipError_t launch_quad16_alg(int out, const Geometry& g, const void* V, c
     case 1: return launch_quad16_kc<ALG, 1>(out, g, V, f, x_scale, inv_y, y, s, prepare);
     case 2: return launch_quad16_kc<ALG, 2>(out, g, V, f, x_scale, inv_y, y, s, prepare);
     case 4: return launch_quad16_kc<ALG, 4>(out, g, V, f, x_scale, inv_y, y, s, prepare);
-    case 8: return launch_quad16_kc<ALG, 8>(out, g, V, f, x_scale, inv_y, y, s, prepare);
   }
   return hipErrorNotSupported;
 }
