@@ -16,6 +16,8 @@
 
 namespace sfc {
 
+constexpr int kWaveRowBytes = 80;  // LDS bytes per position in a wave's block (conflict-free dword writes)
+
 struct InputPlan {
   TileRect tr;
   unsigned tab_off;  // LDS byte offset of the tile -> V row table
@@ -34,6 +36,7 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
   constexpr int P = AlgTraits<ALG>::P;
   // LDS bytes from one position's V to the next: the SFC-4 forms write 16 positions per
   // instruction (sfc_mfma_input.hpp) and need them in different banks
+  constexpr bool kRows16 = AlgTraits<ALG>::R > 3;  // 10 x 10 patches on the matrix cores, below
   constexpr int VSP = AlgTraits<ALG>::kFamily == 4 ? VS + 16 : VS;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -109,6 +112,83 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
           }
       }
     }
+  } else if constexpr (kRows16) {
+    // 5x5 and 7x7 filters: the 184 / 196 sums of a 10 x 10 patch as int8 matrix instructions,
+    // wave = tile, four groups of 16 channels; per block of 16 positions three steps of 64
+    // k-bytes (sfc_mfma_input.hpp).  The coefficients of a block (three 16-byte loads per lane
+    // from the table, the next block's under way) serve the four channel groups.  The rounded
+    // bytes of a block are turned round in a piece of LDS that only this wave uses and written
+    // to V with 16-byte lanes, 64 contiguous bytes per (position, tile): V never lies in LDS
+    // as a whole, so three workgroups share a compute unit and overlap their phases (5x5
+    // filters, 128 channels on 28x28 maps, batch 64: 29.1 us with V collected in LDS).
+    using Tr = AlgTraits<ALG>;
+    static_assert(TPW == 1, "one tile per wave");
+    constexpr int PP = Order<ALG>::PP, NPB = (PP + 15) / 16, CS = stage_channel_bytes(Tr::NI);
+    static_assert(16 * NPB <= kRowsTabRows && Tr::NI <= 12, "table rows, three steps of four patch rows");
+    const float* inv_pos = (const float*)intab;
+    const int* point = (const int*)(intab + kRowsTabPoint);
+    const unsigned char* ctab = intab + kRowsTabCoeff;
+    const int t = wave < tr.ntiles ? row_tab[wave] : -1;  // the same for the whole wave
+    if (t >= 0) {
+      const int tj0 = (bx % tr.chunks) * tr.tlw;
+      const int halo = Tr::M * tj0 - Tr::PAD - ((Tr::M * tj0) & ~3) + 4;
+      const int s = wave / tr.tlw, tjl = wave - s * tr.tlw;
+      const int o = s * 64 * CS + halo + Tr::M * tjl;
+      v4i a[4][3];
+#pragma unroll
+      for (int cg = 0; cg < 4; ++cg)
+#pragma unroll
+        for (int st = 0; st < 3; ++st) a[cg][st] = operand_rows16<CS, Tr::NI>(in, 16 * cg, o, lane, st);
+      // this lane's part of a store: position 16 m + lane / 4, channels c0 + 16 (lane % 4) ..
+      const unsigned vplane = (unsigned)g.Tp * (unsigned)g.Cp;
+      const __amdgpu_buffer_rsrc_t vres =
+          __builtin_amdgcn_make_buffer_rsrc((void*)V, 0, (int)(vplane * (unsigned)P), kBufferFlags);
+      const unsigned trow = (unsigned)t * (unsigned)g.Cp;
+      unsigned char* blk = lds + ip.tab_off - (NW - wave) * (16 * kWaveRowBytes);
+      constexpr float kMagic = 12582912.0f;
+      const float lo = kMagic - g.qmax, hi = kMagic + g.qmax;
+      v4i c_cur[3], c_nxt[3];
+      float inv_cur, inv_nxt = 0.0f;
+      int pt_cur, pt_nxt = -1;
+      auto load_block = [&](int m, v4i (&c)[3], float& inv, int& pt) __attribute__((always_inline)) {
+        const int pos = 16 * m + (lane & 15);
+        inv = inv_pos[pos];
+        pt = point[16 * m + (lane >> 2)];
+#pragma unroll
+        for (int st = 0; st < 3; ++st) c[st] = *(const v4i*)(ctab + pos * 192 + 64 * st + 16 * (lane >> 4));
+      };
+      load_block(0, c_cur, inv_cur, pt_cur);
+#pragma unroll
+      for (int m = 0; m < NPB; ++m) {
+        if (m + 1 < NPB) load_block(m + 1, c_nxt, inv_nxt, pt_nxt);
+#pragma unroll
+        for (int cg = 0; cg < 4; ++cg) {
+          v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[cg][0], c_cur[0], v4i{0, 0, 0, 0}, 0, 0, 0);
+          d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[cg][1], c_cur[1], d, 0, 0, 0);
+          d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[cg][2], c_cur[2], d, 0, 0, 0);
+          unsigned b[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float v = __fmaf_rn((float)d[i], inv_cur, kMagic);
+            v = __builtin_amdgcn_fmed3f(v, lo, hi);
+            b[i] = __float_as_uint(v);
+          }
+          const unsigned w = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u) | __builtin_amdgcn_perm(b[3], b[2], 0x04000c0cu);
+          *(unsigned*)(blk + (lane & 15) * kWaveRowBytes + 16 * cg + 4 * (lane >> 4)) = w;
+        }
+        __builtin_amdgcn_wave_barrier();  // LDS accesses of one wave complete in order
+        const v4i d = *(const v4i*)(blk + (lane >> 2) * kWaveRowBytes + 16 * (lane & 3));
+        const unsigned pofs =
+            pt_cur >= 0 ? (unsigned)pt_cur * vplane + (unsigned)(c0 + 16 * (lane & 3)) : 0x80000000u;
+        __builtin_amdgcn_raw_buffer_store_b128(d, vres, pofs, trow, 0);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int st = 0; st < 3; ++st) c_cur[st] = c_nxt[st];
+        inv_cur = inv_nxt;
+        pt_cur = pt_nxt;
+      }
+    }
+    return;  // (no workgroup barrier after this point on this path)
   } else {
     static_assert(AlgTraits<ALG>::kFamily == 4 || TPW == 1, "one tile per wave on the vector-ALU path");
     transform_tiles<ALG, NW, 1, VS>(in, inv_sx, g.qmax, g, tr, bx, wave, lane);
@@ -133,7 +213,6 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
 // from row to row -- and writes them to V with 16-byte lanes, 64 contiguous bytes per
 // (position, tile).  No further barrier and no separate copy-out phase: a wave's stores are
 // under way while it, and the other waves, transform the next tile.
-constexpr int kWaveRowBytes = 80;  // LDS bytes per position in a wave's block (conflict-free dword writes)
 
 struct WaveInputPlan {
   TileRect tr;
@@ -289,18 +368,28 @@ static int input_tile_slots(const Geometry& g) {
 }
 
 static bool make_input_plan(const Geometry& g, InputPlan* ip) {
+  const unsigned lds_max = 160u * 1024u;
+  const long long xb = (long long)g.N * g.Cin * g.H * g.W;
+  const long long vb = (long long)g.P * g.Tp * g.Cp;
+  if (xb >= (1ll << 31) || vb >= (1ll << 31)) return false;
+  if (g.alg >= 6) {
+    // 5x5 and 7x7 filters: staged rows of one strip (rectangles only), then a block of 16
+    // positions per wave; a third of the LDS, so that three workgroups share a compute unit
+    if (!make_tile_rect(g, 48u * 1024u, &ip->tr, 8, true, false)) return false;
+    const unsigned xbytes = tile_rect_stage_bytes(g, ip->tr) + 32u;  // (patch reads reach 8 bytes past a row)
+    ip->tab_off = ((xbytes + 15u) & ~15u) + 8u * 16u * (unsigned)kWaveRowBytes;
+    ip->lds_bytes = ip->tab_off + 64u;
+    return ip->lds_bytes <= lds_max;
+  }
   // (16 more bytes per position for the SFC-4 forms, whose points are padded to 48 / 52)
   const int slots = input_tile_slots(g);
   const unsigned vbytes = (unsigned)((g.P + 3) / 4 * 4) * ((slots == 8 ? 512u : 1024u) + 16u);
-  const unsigned lds_max = 160u * 1024u;
   if (vbytes + 16u + 64u > lds_max) return false;
   if (!make_tile_rect(g, lds_max - 32u - 64u, &ip->tr, slots, true)) return false;
   const unsigned xbytes = tile_rect_stage_bytes(g, ip->tr) + 16u;
   ip->tab_off = ((xbytes > vbytes ? xbytes : vbytes) + 15u) & ~15u;
   ip->lds_bytes = ip->tab_off + 64u;
-  const long long xb = (long long)g.N * g.Cin * g.H * g.W;
-  const long long vb = (long long)g.P * g.Tp * g.Cp;
-  return ip->lds_bytes <= lds_max && xb < (1ll << 31) && vb < (1ll << 31);
+  return ip->lds_bytes <= lds_max;
 }
 
 template <int ALG>

@@ -27,7 +27,35 @@ constexpr unsigned kInputTabBytes = kInputTabPoints + kInputTabRows * 4;
 void build_input_table(int alg, const float* inv_sx, unsigned char* tab);
 
 
+// The forms with 5x5 and 7x7 filters (10 x 10 patches): k = 16 i + j over three matrix steps
+// of 64 (patch rows 4 s .. 4 s + 3 in step s; j >= 10 and i >= 10 carry no coefficient).  Table:
+// float inv_pos[208], int point[208], int8 coeff[208][192] ([position][k]).
+constexpr int kRowsTabRows = 208;
+constexpr unsigned kRowsTabPoint = kRowsTabRows * 4;
+constexpr unsigned kRowsTabCoeff = kRowsTabRows * 8;
+constexpr unsigned kRowsTabBytes = kRowsTabCoeff + kRowsTabRows * 192;
+void build_rows_table(int alg, const float* inv_sx, unsigned char* tab);
+
 #ifdef __HIPCC__
+
+// Operand A of step s from the staged rows of a tile rectangle (sfc_tile_input.hpp): lane =
+// (channel l%16 of the group of 16 starting at ch0, patch row 4 s + l/16), 16 bytes from LDS
+// byte o of the row (o = strip * 64 * CS + byte of the tile's first patch column).  Rows past
+// the patch repeat its last row, bytes past it belong to the next row: both meet zero
+// coefficients.
+template <int CS, int NI>
+__device__ __forceinline__ v4i operand_rows16(const unsigned char* in, int ch0, int o, int lane, int s) {
+  const int ch = ch0 + (lane & 15), row = min(4 * s + (lane >> 4), NI - 1);
+  const unsigned* src = (const unsigned*)(in + (unsigned)ch * CS + row * 64 + (o & ~3));
+  const unsigned sh = (unsigned)(o & 3);
+  unsigned d[5];
+#pragma unroll
+  for (int i = 0; i < 5; ++i) d[i] = src[i];
+  v4i a;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a[i] = (int)__builtin_amdgcn_alignbyte(d[i + 1], d[i], sh);
+  return a;
+}
 
 template <int ALG>
 struct MfmaInput {

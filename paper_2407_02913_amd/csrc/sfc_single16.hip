@@ -191,6 +191,47 @@ static void fill_input_table(const float* inv_sx, unsigned char* tab) {
     }
 }
 
+// The same for the 10 x 10 patches of the 5x5- and 7x7-filter forms: k = 16 i + j.
+template <int ALG>
+static void fill_rows_table(const float* inv_sx, unsigned char* tab) {
+  using Tr = AlgTraits<ALG>;
+  constexpr int NI = Tr::NI, NC = Tr::NC;
+  constexpr Order<ALG> order{};
+  static_assert(NI <= 12 && Order<ALG>::PP <= kRowsTabRows, "three steps of four rows, table rows");
+  std::memset(tab, 0, kRowsTabBytes);
+  float* inv_pos = reinterpret_cast<float*>(tab);
+  int* point = reinterpret_cast<int*>(tab + kRowsTabPoint);
+  signed char* coeff = reinterpret_cast<signed char*>(tab) + kRowsTabCoeff;
+  for (int p = 0; p < Tr::P; ++p) inv_pos[order.pos[p]] = inv_sx[p];
+  for (int j = 0; j < kRowsTabRows; ++j) point[j] = j < Order<ALG>::PP ? order.pt[j] : -1;
+  for (int i = 0; i < NI; ++i)
+    for (int j = 0; j < NI; ++j) {
+      int half[NI][NC], comp[NC][NC];
+      for (int r = 0; r < NI; ++r) {
+        int row[NI] = {};
+        if (r == i) row[j] = 1;
+        fwd_input<NI, NC>(row, half[r]);
+      }
+      for (int b = 0; b < NC; ++b) {
+        int colv[NI], cc[NC];
+        for (int r = 0; r < NI; ++r) colv[r] = half[r][b];
+        fwd_input<NI, NC>(colv, cc);
+        for (int a = 0; a < NC; ++a) comp[a][b] = cc[a];
+      }
+      for_each_point<ALG>(comp, [&](int p, int v) { coeff[order.pos[p] * 192 + 16 * i + j] = (signed char)v; });
+    }
+}
+
+void build_rows_table(int alg, const float* inv_sx, unsigned char* tab) {
+  switch (alg) {
+    case 6: fill_rows_table<6>(inv_sx, tab); break;
+    case 7: fill_rows_table<7>(inv_sx, tab); break;
+    case 8: fill_rows_table<8>(inv_sx, tab); break;
+    case 9: fill_rows_table<9>(inv_sx, tab); break;
+    default: std::memset(tab, 0, kRowsTabBytes);
+  }
+}
+
 void build_input_table(int alg, const float* inv_sx, unsigned char* tab) {
   if (alg == 4) fill_input_table<4>(inv_sx, tab);
   else if (alg == 5) fill_input_table<5>(inv_sx, tab);

@@ -48,8 +48,9 @@ __host__ __device__ constexpr int plane_stride_bytes(int hw) {
 // max_tiles: tile slots of a workgroup (16, or 8 for workgroups of eight one-tile waves).
 // partial_images: take whole images even if they leave tile slots empty, when the
 // alternative is a rectangle whose rows are not whole dwords (byte-wise staging).
+// whole_images: false keeps to rectangles whatever the size of the feature map.
 inline bool make_tile_rect(const Geometry& g, unsigned stage_budget, TileRect* tr,
-                           int max_tiles = 16, bool partial_images = false) {
+                           int max_tiles = 16, bool partial_images = false, bool whole_images = true) {
   const int M = alg_tile(g.alg), PAD = alg_pad(g.alg);
   tr->whole = 0;
   tr->ipw = 0;
@@ -57,7 +58,7 @@ inline bool make_tile_rect(const Geometry& g, unsigned stage_budget, TileRect* t
   // Small feature maps: whole images, if the tile slots are used at least as well as a
   // rectangle would (always the case when the tiles of an image divide 16).
   const int tpi = g.th * g.tw;
-  if (tpi <= max_tiles && g.H * g.W <= 1024) {
+  if (whole_images && tpi <= max_tiles && g.H * g.W <= 1024) {
     const int cs = plane_stride_bytes(g.H * g.W);
     int ipw = max_tiles / tpi;
     if (ipw > g.N) ipw = g.N;
