@@ -204,7 +204,7 @@ sfc_status sfc_plan(const sfc_conv_desc* desc, sfc_plan_t** out) {
     off = align_up(off + sfc::kInputTabBytes, 256);
   if (d.mode == SFC_MODE_REQUANT_I8 && sfc::image_input_supported(g))
     off = align_up(off + sfc::image_table_bytes(g), 256);
-  if (d.mode == SFC_MODE_REQUANT_I8 && d.alg >= SFC_ALG_6X6_5X5_P184)
+  if (d.mode == SFC_MODE_REQUANT_I8 && sfc::rows_table_offset(g) != ~0u)
     off = align_up(off + sfc::kRowsTabBytes, 256);
   p->off_dq_single = off;
   p->off_U_single = off;
@@ -376,7 +376,7 @@ sfc_status sfc_transform_filter(sfc_plan_t* plan, const int8_t* w_dev, const flo
     if (g.alg == SFC_ALG_4X4_P46 || g.alg == SFC_ALG_4X4_P49) sfc::build_input_table(g.alg, inv_sx, tab);
     if (sfc::image_input_supported(g))
       sfc::build_image_input_table(g, inv_sx, tab + sfc::image_table_offset(g));
-    if (g.alg >= SFC_ALG_6X6_5X5_P184) sfc::build_rows_table(g.alg, inv_sx, tab);
+    if (sfc::rows_table_offset(g) != ~0u) sfc::build_rows_table(g.alg, inv_sx, tab + sfc::rows_table_offset(g));
   }
   if (plan->dq_filters > 0) {
     const int pp = (g.P + 3) / 4 * 4;

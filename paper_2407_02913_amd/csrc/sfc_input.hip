@@ -36,7 +36,7 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
   constexpr int P = AlgTraits<ALG>::P;
   // LDS bytes from one position's V to the next: the SFC-4 forms write 16 positions per
   // instruction (sfc_mfma_input.hpp) and need them in different banks
-  constexpr bool kRows16 = AlgTraits<ALG>::R > 3;  // 10 x 10 patches on the matrix cores, below
+  constexpr bool kRows16 = AlgTraits<ALG>::kFamily == 6;  // 8x8 to 10x10 patches on the matrix cores, below
   constexpr int VSP = AlgTraits<ALG>::kFamily == 4 ? VS + 16 : VS;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -113,9 +113,9 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
       }
     }
   } else if constexpr (kRows16) {
-    // 5x5 and 7x7 filters: the 184 / 196 sums of a 10 x 10 patch as int8 matrix instructions,
-    // wave = tile, four groups of 16 channels; per block of 16 positions three steps of 64
-    // k-bytes (sfc_mfma_input.hpp).  The coefficients of a block (three 16-byte loads per lane
+    // SFC-6 forms: the sums of an 8x8, 9x9 or 10x10 patch as int8 matrix instructions, wave =
+    // tile, four groups of 16 channels; per block of 16 positions two or three steps of 64
+    // k-bytes (sfc_mfma_input.hpp).  The coefficients of a block (16-byte loads per lane
     // from the table, the next block's under way) serve the four channel groups.  The rounded
     // bytes of a block are turned round in a piece of LDS that only this wave uses and written
     // to V with 16-byte lanes, 64 contiguous bytes per (position, tile): V never lies in LDS
@@ -125,6 +125,7 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
     static_assert(TPW == 1, "one tile per wave");
     constexpr int PP = Order<ALG>::PP, NPB = (PP + 15) / 16, CS = stage_channel_bytes(Tr::NI);
     static_assert(16 * NPB <= kRowsTabRows && Tr::NI <= 12, "table rows, three steps of four patch rows");
+    constexpr int KST = (Tr::NI + 3) / 4;  // steps that carry patch rows
     const float* inv_pos = (const float*)intab;
     const int* point = (const int*)(intab + kRowsTabPoint);
     const unsigned char* ctab = intab + kRowsTabCoeff;
@@ -134,11 +135,11 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
       const int halo = Tr::M * tj0 - Tr::PAD - ((Tr::M * tj0) & ~3) + 4;
       const int s = wave / tr.tlw, tjl = wave - s * tr.tlw;
       const int o = s * 64 * CS + halo + Tr::M * tjl;
-      v4i a[4][3];
+      v4i a[4][KST];
 #pragma unroll
       for (int cg = 0; cg < 4; ++cg)
 #pragma unroll
-        for (int st = 0; st < 3; ++st) a[cg][st] = operand_rows16<CS, Tr::NI>(in, 16 * cg, o, lane, st);
+        for (int st = 0; st < KST; ++st) a[cg][st] = operand_rows16<CS, Tr::NI>(in, 16 * cg, o, lane, st);
       // this lane's part of a store: position 16 m + lane / 4, channels c0 + 16 (lane % 4) ..
       const unsigned vplane = (unsigned)g.Tp * (unsigned)g.Cp;
       const __amdgpu_buffer_rsrc_t vres =
@@ -147,15 +148,15 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
       unsigned char* blk = lds + ip.tab_off - (NW - wave) * (16 * kWaveRowBytes);
       constexpr float kMagic = 12582912.0f;
       const float lo = kMagic - g.qmax, hi = kMagic + g.qmax;
-      v4i c_cur[3], c_nxt[3];
+      v4i c_cur[KST], c_nxt[KST];
       float inv_cur, inv_nxt = 0.0f;
       int pt_cur, pt_nxt = -1;
-      auto load_block = [&](int m, v4i (&c)[3], float& inv, int& pt) __attribute__((always_inline)) {
+      auto load_block = [&](int m, v4i (&c)[KST], float& inv, int& pt) __attribute__((always_inline)) {
         const int pos = 16 * m + (lane & 15);
         inv = inv_pos[pos];
         pt = point[16 * m + (lane >> 2)];
 #pragma unroll
-        for (int st = 0; st < 3; ++st) c[st] = *(const v4i*)(ctab + pos * 192 + 64 * st + 16 * (lane >> 4));
+        for (int st = 0; st < KST; ++st) c[st] = *(const v4i*)(ctab + pos * 192 + 64 * st + 16 * (lane >> 4));
       };
       load_block(0, c_cur, inv_cur, pt_cur);
 #pragma unroll
@@ -164,8 +165,8 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
 #pragma unroll
         for (int cg = 0; cg < 4; ++cg) {
           v4i d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[cg][0], c_cur[0], v4i{0, 0, 0, 0}, 0, 0, 0);
-          d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[cg][1], c_cur[1], d, 0, 0, 0);
-          d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[cg][2], c_cur[2], d, 0, 0, 0);
+#pragma unroll
+          for (int st = 1; st < KST; ++st) d = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[cg][st], c_cur[st], d, 0, 0, 0);
           unsigned b[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
         __builtin_amdgcn_raw_buffer_store_b128(d, vres, pofs, trow, 0);
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int st = 0; st < 3; ++st) c_cur[st] = c_nxt[st];
+        for (int st = 0; st < KST; ++st) c_cur[st] = c_nxt[st];
         inv_cur = inv_nxt;
         pt_cur = pt_nxt;
       }
@@ -372,12 +373,13 @@ static bool make_input_plan(const Geometry& g, InputPlan* ip) {
   const long long xb = (long long)g.N * g.Cin * g.H * g.W;
   const long long vb = (long long)g.P * g.Tp * g.Cp;
   if (xb >= (1ll << 31) || vb >= (1ll << 31)) return false;
-  if (g.alg >= 6) {
-    // 5x5 and 7x7 filters: staged rows of one strip (rectangles only), then a block of 16
+  if (g.alg < 4 || g.alg >= 6) {
+    // SFC-6 forms: staged rows of one strip (rectangles only), then a block of 16
     // positions per wave; a third of the LDS, so that three workgroups share a compute unit
-    if (!make_tile_rect(g, 48u * 1024u, &ip->tr, 8, true, false)) return false;
+    const int waves = input_waves(g.alg);  // one tile slot each
+    if (!make_tile_rect(g, 48u * 1024u, &ip->tr, waves, true, false)) return false;
     const unsigned xbytes = tile_rect_stage_bytes(g, ip->tr) + 32u;  // (patch reads reach 8 bytes past a row)
-    ip->tab_off = ((xbytes + 15u) & ~15u) + 8u * 16u * (unsigned)kWaveRowBytes;
+    ip->tab_off = ((xbytes + 15u) & ~15u) + (unsigned)waves * 16u * (unsigned)kWaveRowBytes;
     ip->lds_bytes = ip->tab_off + 64u;
     return ip->lds_bytes <= lds_max;
   }
@@ -390,6 +392,11 @@ static bool make_input_plan(const Geometry& g, InputPlan* ip) {
   ip->tab_off = ((xbytes > vbytes ? xbytes : vbytes) + 15u) & ~15u;
   ip->lds_bytes = ip->tab_off + 64u;
   return ip->lds_bytes <= lds_max;
+}
+
+unsigned rows_table_offset(const Geometry& g) {
+  if (g.alg == 4 || g.alg == 5) return ~0u;
+  return (image_table_bytes(g) + 255u) & ~255u;
 }
 
 template <int ALG>
@@ -408,7 +415,10 @@ static hipError_t launch_input_i8_alg(const Geometry& g, const InputPlan& ip, co
   }
   auto kernel = input_transform_i8_kernel<ALG, NW, NW == 8 ? 512 : 1024>;
   if (prepare) return raise_lds_limit(reinterpret_cast<const void*>(kernel));
-  hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), ip.lds_bytes, s, x, (int8_t*)V, inv_sx, intab, g, ip);
+  // (the SFC-6 forms read the table of the row-form transform)
+  const unsigned toff = rows_table_offset(g);
+  const unsigned char* tab = intab && toff != ~0u ? intab + toff : intab;
+  hipLaunchKernelGGL(kernel, grid, dim3(NW * 64), ip.lds_bytes, s, x, (int8_t*)V, inv_sx, tab, g, ip);
   return hipGetLastError();
 }
 

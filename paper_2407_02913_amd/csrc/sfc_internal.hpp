@@ -60,6 +60,9 @@ hipError_t launch_input_transform_i8(const Geometry& g, const int8_t* x, void* V
 bool image_input_supported(const Geometry& g);
 unsigned image_table_bytes(const Geometry& g);
 unsigned image_table_offset(const Geometry& g);
+// SFC-6 forms: bytes from FilterViews::input_tab to the table of the row-form input transform
+// (kRowsTabBytes, after the small-image table if the geometry has one); ~0u: no such table
+unsigned rows_table_offset(const Geometry& g);
 void build_image_input_table(const Geometry& g, const float* inv_sx, unsigned char* tab);
 hipError_t launch_input_image(const Geometry& g, const int8_t* x, void* V, const unsigned char* tab,
                               hipStream_t s, bool prepare);

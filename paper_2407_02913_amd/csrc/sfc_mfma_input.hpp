@@ -27,8 +27,9 @@ constexpr unsigned kInputTabBytes = kInputTabPoints + kInputTabRows * 4;
 void build_input_table(int alg, const float* inv_sx, unsigned char* tab);
 
 
-// The forms with 5x5 and 7x7 filters (10 x 10 patches): k = 16 i + j over three matrix steps
-// of 64 (patch rows 4 s .. 4 s + 3 in step s; j >= 10 and i >= 10 carry no coefficient).  Table:
+// The SFC-6 forms (8x8, 9x9 and 10x10 patches) outside small feature maps: k = 16 i + j over
+// two or three matrix steps of 64 (patch rows 4 s .. 4 s + 3 in step s; columns and rows past
+// the patch carry no coefficient).  Table, at the start of FilterViews::input_tab:
 // float inv_pos[208], int point[208], int8 coeff[208][192] ([position][k]).
 constexpr int kRowsTabRows = 208;
 constexpr unsigned kRowsTabPoint = kRowsTabRows * 4;

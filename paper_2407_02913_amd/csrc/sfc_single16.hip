@@ -191,7 +191,7 @@ static void fill_input_table(const float* inv_sx, unsigned char* tab) {
     }
 }
 
-// The same for the 10 x 10 patches of the 5x5- and 7x7-filter forms: k = 16 i + j.
+// The same for the 8x8 to 10x10 patches of the SFC-6 forms: k = 16 i + j.
 template <int ALG>
 static void fill_rows_table(const float* inv_sx, unsigned char* tab) {
   using Tr = AlgTraits<ALG>;
@@ -224,6 +224,10 @@ static void fill_rows_table(const float* inv_sx, unsigned char* tab) {
 
 void build_rows_table(int alg, const float* inv_sx, unsigned char* tab) {
   switch (alg) {
+    case 0: fill_rows_table<0>(inv_sx, tab); break;
+    case 1: fill_rows_table<1>(inv_sx, tab); break;
+    case 2: fill_rows_table<2>(inv_sx, tab); break;
+    case 3: fill_rows_table<3>(inv_sx, tab); break;
     case 6: fill_rows_table<6>(inv_sx, tab); break;
     case 7: fill_rows_table<7>(inv_sx, tab); break;
     case 8: fill_rows_table<8>(inv_sx, tab); break;
