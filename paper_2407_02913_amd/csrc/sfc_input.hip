@@ -1,13 +1,15 @@
 // Input-tile transform V = B^T x B with transform-domain requantization to int8,
-// the HBM-facing first stage of the two-kernel path (gfx950), every algorithm.
+// the HBM-facing first stage of the two-kernel paths (gfx950), every algorithm, on the
+// matrix cores (sfc_mfma_input.hpp; small feature maps: sfc_input_image.hip).
 //
 // A workgroup owns up to NW tiles (a rectangle of S strips x tlw tile columns, or whole
 // images of a small feature map), one per wave, and 64 input channels:
 //  1. stage the input rows of every (strip, channel) in LDS (coalesced dword loads),
-//  2. transform: wave = tile, lane = channel; the rounded points land in LDS as
-//     [processing position][tile][channel], over the staging area,
-//  3. copy out: V[p][t][c0 .. c0+63] with 16-byte lanes, 64 contiguous bytes per
-//     (point, tile).
+//  2. transform: wave = tile, four groups of 16 channels, lane = (position, four channels);
+//  3. SFC-4 forms: the rounded points land in LDS as [processing position][tile][channel],
+//     over the staging area, and are copied out with 16-byte lanes, 64 contiguous bytes per
+//     (point, tile) and NW tiles in a row; SFC-6 forms: every wave turns blocks of 16
+//     positions round in LDS of its own and stores them directly.
 #include "sfc_device.hpp"
 #include "sfc_internal.hpp"
 #include "sfc_mfma_input.hpp"
@@ -191,8 +193,7 @@ __global__ __launch_bounds__(NW * 64) void input_transform_i8_kernel(
     }
     return;  // (no workgroup barrier after this point on this path)
   } else {
-    static_assert(AlgTraits<ALG>::kFamily == 4 || TPW == 1, "one tile per wave on the vector-ALU path");
-    transform_tiles<ALG, NW, 1, VS>(in, inv_sx, g.qmax, g, tr, bx, wave, lane);
+    static_assert(AlgTraits<ALG>::kFamily == 4 || kRows16, "every form has its matrix-core transform");
   }
   __syncthreads();
 
