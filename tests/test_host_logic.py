@@ -142,6 +142,12 @@ def test_auto_algorithm_and_path(lib):
         assert choice(shape, alg="auto", path="auto") == want[name], name
     assert choice(synth.LAYERS["resnet56"], alg="6x6_p88", path="staged") == ("6x6_p88", "staged")
     assert choice(synth.LAYERS["resnet56"], alg="7x7_p132", path="auto") == ("7x7_p132", "single")
+    # 512 channels on 7x7 maps: one 7x7 tile per image through the batched GEMMs from batch 128 on
+    r7 = synth.LAYERS["resnet7"]
+    assert choice(synth.LayerShape("b128", 128, r7.Cin, r7.Cout, 7, 7, "relu", True, 9), alg="auto",
+                  path="auto") == ("7x7_p132", "staged")
+    assert choice(synth.LayerShape("b64", 64, r7.Cin, r7.Cout, 7, 7, "relu", True, 9), alg="auto",
+                  path="auto") == ("4x4_p46", "fused")
     # exact mode runs staged, on the 6x6 form the paper's headline count is about
     assert choice(synth.LAYERS["tiny32"], alg="auto", path="auto", mode="exact") == ("6x6_p88", "staged")
     # channel counts the fused kernel does not take (three 64-channel slices) fall back
