@@ -223,14 +223,16 @@ __device__ __forceinline__ void quad16_store(const f4 (&z)[AlgTraits<ALG>::NC][A
       float out[M];
       stream_row<ALG, float>(zi, o1, out);
       if constexpr (OUT == 2) {
-        unsigned word = 0;
+        unsigned b[M];
 #pragma unroll
         for (int o2 = 0; o2 < M; ++o2) {
           // next layer's activation: ReLU, round half to even, clamp to [0, 127]
           float t = __fmaf_rn(out[o2], act, kMagic);
           t = __builtin_amdgcn_fmed3f(t, kMagic, kMagic + 127.0f);
-          word |= (__float_as_uint(t) & 0xffu) << (8 * o2);
+          b[o2] = __float_as_uint(t);
         }
+        // the low bytes of the four outputs -> one dword
+        const unsigned word = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u) | __builtin_amdgcn_perm(b[3], b[2], 0x04000c0cu);
         // (rows moved round by the quarter: the four quarters of the wave write different banks)
         *(unsigned*)(stage + ((f * 16 + tl) * 4 + ((o1 + q) & 3)) * 4) = word;
       } else {
